@@ -1,0 +1,283 @@
+"""Layer-by-layer forward / backward definitions used by the CDP oracle.
+
+TEST INFRASTRUCTURE ONLY (see package docstring).  Everything is plain numpy in
+float64, NHWC for images, one function pair per layer kind, no fusion and no
+blocking: each formula is the textbook definition of the layer and of its
+vector-Jacobian product.  The paper treats a stage as an opaque differentiable
+module (Sec. 3.1, "forward and backward pass over the micro-batch"); the layer
+set here is what the benchmark configurations need.
+
+Pins (tests/test_oracle_layers.py): finite differences in fp64 for every
+layer kind and for whole stages, brute-force 7-loop convolution, 1x1 conv on
+1x1 images == linear, CE closed forms.
+"""
+from __future__ import annotations
+
+from typing import Callable, List, Optional, Sequence
+
+import numpy as np
+
+import cdp_workloads as wl
+
+Array = np.ndarray
+
+
+# ---------------------------------------------------------------------------
+# bf16 rounding (round-to-nearest-even on the upper 16 bits of a float32)
+# ---------------------------------------------------------------------------
+def round_bf16(a: Array) -> Array:
+    f = np.ascontiguousarray(a, dtype=np.float32)
+    u = f.view(np.uint32).astype(np.uint64)
+    lsb = (u >> np.uint64(16)) & np.uint64(1)
+    u = (u + np.uint64(0x7FFF) + lsb) & np.uint64(0xFFFF0000)
+    return u.astype(np.uint32).view(np.float32).reshape(f.shape).astype(np.float64)
+
+
+def identity(a: Array) -> Array:
+    return a
+
+
+# ---------------------------------------------------------------------------
+# individual layers
+# ---------------------------------------------------------------------------
+def linear_fwd(x: Array, W: Array, b: Array) -> Array:
+    return x.reshape(x.shape[0], -1) @ W.T + b
+
+
+def linear_bwd(x: Array, W: Array, dy: Array):
+    x2 = x.reshape(x.shape[0], -1)
+    dx = (dy @ W).reshape(x.shape)
+    return dx, dy.T @ x2, dy.sum(axis=0)
+
+
+def conv2d_fwd(x: Array, W: Array, stride: int, pad: int) -> Array:
+    """y[b,ho,wo,o] = sum_{kh,kw,c} x[b, ho*s+kh-p, wo*s+kw-p, c] * W[o,kh,kw,c]."""
+    Bn, H, Wd, C = x.shape
+    O, KH, KW, _ = W.shape
+    Ho = (H + 2 * pad - KH) // stride + 1
+    Wo = (Wd + 2 * pad - KW) // stride + 1
+    xp = np.pad(x, ((0, 0), (pad, pad), (pad, pad), (0, 0)))
+    y = np.zeros((Bn, Ho, Wo, O), dtype=x.dtype)
+    for kh in range(KH):
+        for kw in range(KW):
+            xs = xp[:, kh:kh + stride * (Ho - 1) + 1:stride, kw:kw + stride * (Wo - 1) + 1:stride, :]
+            y += xs @ W[:, kh, kw, :].T
+    return y
+
+
+def conv2d_bwd(x: Array, W: Array, stride: int, pad: int, dy: Array):
+    Bn, H, Wd, C = x.shape
+    O, KH, KW, _ = W.shape
+    _, Ho, Wo, _ = dy.shape
+    xp = np.pad(x, ((0, 0), (pad, pad), (pad, pad), (0, 0)))
+    dxp = np.zeros_like(xp)
+    dW = np.zeros_like(W)
+    dy2 = dy.reshape(-1, O)
+    for kh in range(KH):
+        for kw in range(KW):
+            sl = (slice(None), slice(kh, kh + stride * (Ho - 1) + 1, stride),
+                  slice(kw, kw + stride * (Wo - 1) + 1, stride), slice(None))
+            dW[:, kh, kw, :] = dy2.T @ xp[sl].reshape(-1, C)
+            dxp[sl] += dy @ W[:, kh, kw, :]
+    dx = dxp[:, pad:pad + H, pad:pad + Wd, :]
+    return dx, dW
+
+
+def affine_fwd(x: Array, gamma: Array, beta: Array) -> Array:
+    return x * gamma + beta
+
+
+def affine_bwd(x: Array, gamma: Array, dy: Array):
+    red = tuple(range(x.ndim - 1))
+    return dy * gamma, (dy * x).sum(axis=red), dy.sum(axis=red)
+
+
+def maxpool_fwd(x: Array, ks: int, stride: int, pad: int):
+    """Max over each window; also returns the flat window index of the first maximum."""
+    Bn, H, Wd, C = x.shape
+    Ho = (H + 2 * pad - ks) // stride + 1
+    Wo = (Wd + 2 * pad - ks) // stride + 1
+    xp = np.pad(x, ((0, 0), (pad, pad), (pad, pad), (0, 0)), constant_values=-np.inf)
+    best = np.full((Bn, Ho, Wo, C), -np.inf, dtype=x.dtype)
+    arg = np.zeros((Bn, Ho, Wo, C), dtype=np.int64)
+    for kh in range(ks):
+        for kw in range(ks):
+            xs = xp[:, kh:kh + stride * (Ho - 1) + 1:stride, kw:kw + stride * (Wo - 1) + 1:stride, :]
+            better = xs > best
+            best = np.where(better, xs, best)
+            arg = np.where(better, kh * ks + kw, arg)
+    return best, arg
+
+
+def maxpool_bwd(x_shape, arg: Array, ks: int, stride: int, pad: int, dy: Array) -> Array:
+    Bn, H, Wd, C = x_shape
+    _, Ho, Wo, _ = dy.shape
+    dxp = np.zeros((Bn, H + 2 * pad, Wd + 2 * pad, C), dtype=dy.dtype)
+    for kh in range(ks):
+        for kw in range(ks):
+            sl = (slice(None), slice(kh, kh + stride * (Ho - 1) + 1, stride),
+                  slice(kw, kw + stride * (Wo - 1) + 1, stride), slice(None))
+            dxp[sl] += np.where(arg == kh * ks + kw, dy, 0.0)
+    return dxp[:, pad:pad + H, pad:pad + Wd, :]
+
+
+def gap_fwd(x: Array) -> Array:
+    return x.mean(axis=(1, 2))
+
+
+def gap_bwd(x_shape, dy: Array) -> Array:
+    Bn, H, Wd, C = x_shape
+    return np.broadcast_to(dy[:, None, None, :] / (H * Wd), x_shape).copy()
+
+
+def ce_fwd(logits: Array, labels: Array):
+    """loss = mean_b [ logsumexp(z_b) - z_b[y_b] ];  dz = (softmax(z) - onehot(y)) / B."""
+    Bn = logits.shape[0]
+    m = logits.max(axis=1, keepdims=True)
+    e = np.exp(logits - m)
+    s = e.sum(axis=1, keepdims=True)
+    lse = (m + np.log(s))[:, 0]
+    loss = float((lse - logits[np.arange(Bn), labels]).mean())
+    dz = e / s
+    dz[np.arange(Bn), labels] -= 1.0
+    return loss, dz / Bn
+
+
+# ---------------------------------------------------------------------------
+# stages: a list of layers over numbered tensors (tensor 0 = stage input)
+# ---------------------------------------------------------------------------
+def split_params(stage: Sequence[wl.Layer], params: Sequence[Array]) -> List[List[Array]]:
+    out, k = [], 0
+    for layer in stage:
+        n = len(wl.layer_param_shapes(layer))
+        out.append(list(params[k:k + n]))
+        k += n
+    assert k == len(params)
+    return out
+
+
+def materialized(stage: Sequence[wl.Layer]) -> List[bool]:
+    """materialized[k+1]: tensor k+1 is written to memory by a fused kernel of the
+    bf16 device path (the next layer is not an elementwise follower of it).  Only
+    used by the optional rounding emulation."""
+    m = [True] * (len(stage) + 1)
+    for k, layer in enumerate(stage):
+        nxt = stage[k + 1] if k + 1 < len(stage) else None
+        if nxt is not None and nxt.src < 0 and nxt.kind in (wl.RELU, wl.AFFINE, wl.ADD, wl.CE_HEAD):
+            m[k + 1] = False
+    return m
+
+
+def stage_forward(stage: Sequence[wl.Layer], params: Sequence[Array], x: Array,
+                  labels: Optional[Array] = None, rnd: Callable[[Array], Array] = identity):
+    """Run every layer in order.  Returns (output, saved) where output is the last
+    tensor, or the scalar loss if the stage ends in a CE head; ``saved`` holds what
+    the backward pass needs."""
+    lp = split_params(stage, params)
+    mat = materialized(stage)
+    tensors: List[Array] = [x]
+    aux: List[object] = []
+    loss = None
+    for k, layer in enumerate(stage):
+        src = tensors[k if layer.src < 0 else layer.src]
+        kind, p = layer.kind, layer.p
+        a = None
+        if kind == wl.LINEAR:
+            y = linear_fwd(src, rnd(lp[k][0]), rnd(lp[k][1]))
+        elif kind == wl.RELU:
+            y = np.maximum(src, 0.0)
+        elif kind == wl.CONV2D:
+            y = conv2d_fwd(src, rnd(lp[k][0]), p[3], p[4])
+        elif kind == wl.AFFINE:
+            y = affine_fwd(src, rnd(lp[k][0]), rnd(lp[k][1]))
+        elif kind == wl.ADD:
+            y = src + tensors[p[0]]
+        elif kind == wl.MAXPOOL:
+            y, a = maxpool_fwd(src, p[0], p[1], p[2])
+        elif kind == wl.GAP:
+            y = gap_fwd(src)
+        elif kind == wl.CE_HEAD:
+            assert labels is not None and k == len(stage) - 1
+            loss, a = ce_fwd(src, labels)
+            a = rnd(a)
+            y = np.zeros(())
+        else:
+            raise ValueError(kind)
+        if mat[k + 1] and kind != wl.CE_HEAD:
+            y = rnd(y)
+        tensors.append(y)
+        aux.append(a)
+    saved = {"tensors": tensors, "aux": aux}
+    return (loss if loss is not None else tensors[-1]), saved
+
+
+def stage_backward(stage: Sequence[wl.Layer], params: Sequence[Array], saved, dy: Optional[Array],
+                   rnd: Callable[[Array], Array] = identity, need_dx: bool = True):
+    """Vector-Jacobian product of the whole stage.  ``dy`` is the gradient of the
+    micro-batch objective with respect to the stage output (None for a stage that
+    ends in the CE head).  Returns (dx, grads) with grads ordered like params."""
+    lp = split_params(stage, params)
+    mat = materialized(stage)
+    tensors, aux = saved["tensors"], saved["aux"]
+    dt: List[Optional[Array]] = [None] * len(tensors)
+
+    def acc(idx: int, g: Array) -> None:
+        dt[idx] = g if dt[idx] is None else dt[idx] + g
+
+    if dy is not None:
+        acc(len(stage), dy)
+    grads: List[List[Array]] = [[] for _ in stage]
+    for k in range(len(stage) - 1, -1, -1):
+        layer = stage[k]
+        kind, p = layer.kind, layer.p
+        si = k if layer.src < 0 else layer.src
+        src = tensors[si]
+        if kind == wl.CE_HEAD:
+            acc(si, aux[k])
+            continue
+        g = dt[k + 1]
+        assert g is not None, "tensor %d has no consumer" % (k + 1)
+        if mat[k + 1]:
+            g = rnd(g)
+        if kind == wl.LINEAR:
+            dx, dW, db = linear_bwd(src, rnd(lp[k][0]), g)
+            grads[k] = [dW, db]
+        elif kind == wl.RELU:
+            dx = g * (src > 0)
+        elif kind == wl.CONV2D:
+            dx, dW = conv2d_bwd(src, rnd(lp[k][0]), p[3], p[4], g)
+            grads[k] = [dW]
+        elif kind == wl.AFFINE:
+            dx, dg, dbeta = affine_bwd(src, rnd(lp[k][0]), g)
+            grads[k] = [dg, dbeta]
+        elif kind == wl.ADD:
+            dx = g
+            acc(p[0], g)
+        elif kind == wl.MAXPOOL:
+            dx = maxpool_bwd(src.shape, aux[k], p[0], p[1], p[2], g)
+        elif kind == wl.GAP:
+            dx = gap_bwd(src.shape, g)
+        else:
+            raise ValueError(kind)
+        acc(si, dx)
+    flat = [g for gl in grads for g in gl]
+    dx0 = dt[0]
+    if dx0 is not None:
+        dx0 = rnd(dx0)
+    return dx0, flat
+
+
+def model_forward_backward(stages, params_per_stage, x, labels, rnd=identity):
+    """Ordinary whole-network forward and backward on one micro-batch, each stage
+    j evaluated at params_per_stage[j].  Returns (loss, grads per stage)."""
+    saved = []
+    h = x
+    for j, st in enumerate(stages):
+        h, sv = stage_forward(st, params_per_stage[j], h, labels if j == len(stages) - 1 else None, rnd)
+        saved.append(sv)
+    loss = h
+    grads = [None] * len(stages)
+    dy = None
+    for j in range(len(stages) - 1, -1, -1):
+        dy, grads[j] = stage_backward(stages[j], params_per_stage[j], saved[j], dy, rnd)
+    return loss, grads
