@@ -284,7 +284,7 @@ def get_config(name: str) -> Config:
         return Config("cfg2_mini", _mlp(200, 136, 4, 10, stem=True), (200,), 10, N=4, B=24,
                       dtype=BF16, lr=0.05, steps=8)
     if name == "cfg5_mini":      # bf16, d=3, N=16
-        return Config("cfg5_mini", _mlp(192, 192, 24, 100, stem=False), (192,), 100, N=16, B=16,
+        return Config("cfg5_mini", _mlp(320, 320, 24, 100, stem=False), (320,), 100, N=16, B=40,
                       dtype=BF16, lr=0.05, steps=5)
     if name == "resnet18_mini":  # 8 BasicBlock stages at 1/8 width, 8x8 images
         return Config("resnet18_mini", _resnet18_cifar(10, widths=(8, 16, 32, 64)), (8, 8, 3), 10,

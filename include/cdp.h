@@ -1,0 +1,168 @@
+/* libcdp -- single-GPU hot path of Cyclic Data Parallelism (CDP) training on MI355X.
+ *
+ * The library executes the paper's execution timeline (Sec. 3.2 "Algorithmic
+ * description", Fig. 1b/1c): N micro-batches run one uniform delay apart; in every
+ * tick ("time step") each active micro-batch runs the forward or the backward of one
+ * stage with the per-stage weight version chosen by the update rule (Eq. (CDP),
+ * Eq. (CDP-v1), Eq. (CDP-v2), Eq. (DP)); backward passes add into a per-stage
+ * gradient accumulator and a stage is updated by SGD as soon as it holds N gradients.
+ * Placement is the single-GPU one of Sec. 4.1 "Cyclic implementation" (Fig. 2.a.ii).
+ *
+ * Conventions
+ *   - every function returns CDP_OK (0) or a negative cdp_status; nothing throws;
+ *     a failed call leaves the context as it was (CDP_EINVAL) or unusable (CDP_EHIP);
+ *   - "dev" pointers are HIP device pointers, "host" pointers are ordinary host memory;
+ *   - the caller owns every pointer it passes (inputs, labels, output buffers, the
+ *     arena, the stream); the library owns only cdp_ctx and sub-allocates the arena;
+ *   - all device work is enqueued on opts->hip_stream; calls return without waiting
+ *     unless stated otherwise;
+ *   - indices are 0-based: stage j in [0,S), micro-batch i in [0,N), step t >= 0,
+ *     tick >= 0.  Micro-batch i of step t starts at tick 2*S*t + d*i, d = 2S/N.
+ */
+#ifndef CDP_H
+#define CDP_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct cdp_ctx cdp_ctx;
+
+typedef enum {
+  CDP_OK = 0,
+  CDP_EINVAL = -1, /* bad argument, unsupported layer pattern, N does not divide 2S */
+  CDP_ENOMEM = -2, /* arena too small (cdp_arena_bytes tells the need)               */
+  CDP_ESTATE = -3, /* call not valid now (e.g. weight version no longer in the ring) */
+  CDP_EHIP = -4    /* a HIP runtime call failed; see cdp_last_error                  */
+} cdp_status;
+
+/* Update rule u_{i,j} of Eq. (CDP).  DP runs the lock-step timeline of Fig. 1a. */
+typedef enum {
+  CDP_RULE_DP = 0, /* Eq. (DP):     every gradient of step t at theta_t               */
+  CDP_RULE_V1 = 1, /* Eq. (CDP-v1): every gradient of step t at theta_{t-1}           */
+  CDP_RULE_V2 = 2  /* Eq. (CDP-v2): freshest version in memory when the stage is read */
+} cdp_rule;
+
+/* Arithmetic of the contractions.  Accumulation, master weights, gradient
+ * accumulators and the loss head are always fp32. */
+typedef enum { CDP_F32 = 0, CDP_BF16 = 1 } cdp_dtype;
+
+typedef enum {
+  CDP_LINEAR = 1,  /* p = {in, out}                  params W[out][in], b[out]          */
+  CDP_RELU = 2,    /* p = {}                                                           */
+  CDP_CONV2D = 3,  /* p = {cin, cout, k, stride, pad} params W[cout][k][k][cin], NHWC   */
+  CDP_AFFINE = 4,  /* p = {channels}                 params gamma[c], beta[c]           */
+  CDP_ADD = 5,     /* p = {src2}  y = tensor[src] + tensor[src2]                       */
+  CDP_MAXPOOL = 6, /* p = {k, stride, pad}                                             */
+  CDP_GAP = 7,     /* p = {}      global average pool [B,H,W,C] -> [B,C]               */
+  CDP_CE_HEAD = 8  /* p = {classes} mean softmax cross-entropy of the micro-batch      */
+} cdp_layer_kind;
+
+/* One layer of a stage.  Tensors of a stage are numbered: 0 = stage input, k+1 =
+ * output of layer k.  src = tensor read by the layer, -1 = output of the previous
+ * layer.  Supported sequences (fused into one kernel each):
+ *   LINEAR [RELU] | CONV2D [AFFINE] [ADD] [RELU] | MAXPOOL | GAP | LINEAR CE_HEAD.
+ * CE_HEAD must be the last layer of the last stage and only there. */
+typedef struct {
+  int32_t kind;
+  int32_t src;
+  int32_t p[6];
+} cdp_layer_desc;
+
+typedef struct {
+  const cdp_layer_desc* layers; /* host */
+  int32_t n_layers;
+} cdp_stage_desc;
+
+typedef struct {
+  int32_t dtype;       /* cdp_dtype                                                     */
+  int32_t dry_run;     /* 1: host bookkeeping only (schedule, versions, pool); no HIP
+                          call is made, arena and stream are ignored                    */
+  int32_t in_rank;     /* 1: in_dims = {features}; 3: in_dims = {H, W, C}               */
+  int32_t in_dims[3];  /* per-sample input shape                                        */
+  void* hip_stream;    /* hipStream_t, may be NULL (default stream)                     */
+  void* arena;         /* dev, 256-byte aligned, at least cdp_arena_bytes() long        */
+  size_t arena_bytes;
+} cdp_opts;
+
+/* One executed (micro-batch, stage) pass. */
+typedef struct {
+  int32_t tick, mb, step, stage, dir /* 0 fwd, 1 bwd */, version;
+} cdp_trace_rec;
+
+typedef struct {
+  int64_t ticks_run;
+  int64_t steps_enqueued;
+  int64_t peak_live_stage_inputs;   /* max over ticks of retained stage inputs (in-tick)  */
+  int64_t last_live_stage_inputs;   /* value in the most recent tick                      */
+  int64_t peak_activation_bytes;    /* high-water mark of bytes in use in the pool        */
+  int64_t cur_activation_bytes;
+  int64_t pool_span_bytes;          /* arena bytes the pool ever touched                  */
+  int64_t dp_activation_bytes;      /* same stages under lock-step DP: N * sum_j bytes_j  */
+  int64_t weight_bytes;             /* ring (2 versions) + fp32 master + fp32 accumulator */
+  int64_t kernel_launches;
+} cdp_stats;
+
+/* Bytes of device arena the configuration needs (weights ring, master, accumulators,
+ * activation pool found by a dry simulation of the schedule).  Host-only. */
+int cdp_arena_bytes(const cdp_stage_desc* stages, int n_stages, int n_microbatches,
+                    int micro_batch, int rule, const cdp_opts* opts, size_t* bytes_out);
+
+/* Create a context.  stages/N/micro_batch/lr/rule are the quantities of Sec. 3
+ * (theta = {theta^j}, N micro-batches of size B, learning rate gamma, rule u_{i,j}).
+ * Requires N | 2S for the cyclic rules.  Weights start at zero until cdp_set_weights. */
+int cdp_init(cdp_ctx** out, const cdp_stage_desc* stages, int n_stages, int n_microbatches,
+             int micro_batch, float lr, int rule, const cdp_opts* opts);
+
+/* theta_0^j: host fp32, the stage's parameter tensors concatenated in layer order.
+ * Both ring slots receive it (theta_{-1} := theta_0).  Only valid before the first tick. */
+int cdp_set_weights(cdp_ctx* ctx, int stage, const float* host_f32, size_t n);
+
+/* Number of fp32 parameters of a stage. */
+int cdp_param_count(const cdp_ctx* ctx, int stage, size_t* n_out);
+
+/* Advance one tick.  x_dev: fp32 [N*B, in_dims...] and y_dev: int32 [N*B] of the
+ * mini-batch whose micro-batches may start in this tick (the step tick/(2S)); they are
+ * read only in ticks where a micro-batch starts (x) -- labels are copied at that time.
+ * May be NULL in ticks where no micro-batch starts (the drain). */
+int cdp_tick(cdp_ctx* ctx, const float* x_dev, const int32_t* y_dev);
+
+/* Enqueue mini-batch t (the next one) and run its 2S ticks.  x_dev/y_dev as above;
+ * they must stay valid until the enqueued work has run. */
+int cdp_step(cdp_ctx* ctx, const float* x_dev, const int32_t* y_dev);
+
+/* Run the remaining d*(N-1) ticks so that every stage reaches theta_T. */
+int cdp_drain(cdp_ctx* ctx);
+
+/* Copy a stage's parameters to host fp32 (synchronises the stream).  version = -1:
+ * freshest (fp32 master values); version = freshest-1: the compute-precision copy
+ * still held in the ring (its folded/rounded form is not inverted: CDP_ESTATE for
+ * stages with AFFINE layers).  Any other version: CDP_ESTATE. */
+int cdp_get_weights(cdp_ctx* ctx, int stage, int version, float* host_f32, size_t cap,
+                    size_t* n_out);
+
+/* Micro-batch objectives f_i of step t: host fp32 [N] (synchronises).  CDP_ESTATE if
+ * the step's head passes have not all run yet or the step left the log (last 1024). */
+int cdp_get_losses(cdp_ctx* ctx, int64_t step, float* host_f32, size_t cap);
+
+/* Executed passes in order (tick, then micro-batch ascending). Host-only. */
+int cdp_get_trace(const cdp_ctx* ctx, cdp_trace_rec* out, size_t cap, size_t* n_out);
+
+/* In-tick count of retained stage inputs for every tick run so far. Host-only. */
+int cdp_get_live_counts(const cdp_ctx* ctx, int32_t* out, size_t cap, size_t* n_out);
+
+int cdp_get_stats(const cdp_ctx* ctx, cdp_stats* out);
+
+/* Text of the last error on this context (or of the last failed cdp_init /
+ * cdp_arena_bytes when ctx is NULL).  Never NULL. */
+const char* cdp_last_error(const cdp_ctx* ctx);
+
+void cdp_destroy(cdp_ctx* ctx);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* CDP_H */

@@ -1,0 +1,37 @@
+/* libcdp kernel-level entry points: the contractions a CDP tick is made of, callable on
+ * their own (unit parity tests against the CPU oracle, roofline micro-benchmarks).
+ * All pointers are HIP device pointers owned by the caller; work is enqueued on
+ * `stream` (hipStream_t, may be NULL) and the call returns without waiting.
+ * Return value: 0 or a negative status code of cdp.h. */
+#ifndef CDP_KERNELS_H
+#define CDP_KERNELS_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* C[M][N] (fp32, row-major, ldc = N) = A * B^T with fp32 accumulation, the tile
+ * contraction used by every stage forward / backward of a tick (Sec. 3.1: "forward and
+ * backward pass over the micro-batch").
+ *   dtype      0 fp32, 1 bf16 (operand element type)
+ *   tile_shape 0: 128x128, 1: 64x128, 2: 64x64 workgroup tile
+ *   a_kmajor   1: A[m][k] at A[m*lda + k]   0: A[m][k] at A[k*lda + m]
+ *   b_kmajor   1: B[n][k] at B[n*ldb + k]   0: B[n][k] at B[k*ldb + n] */
+int cdp_k_gemm(int dtype, int tile_shape, int a_kmajor, int b_kmajor, const void* A, const void* B,
+               float* C, int M, int N, int K, int lda, int ldb, void* stream);
+
+/* One NHWC convolution contraction as implicit GEMM (no affine, no activation).
+ *   which 0: forward        y[B][Ho][Wo][Cout] (elem type) = conv(x, w),  w[Cout][k][k][Cin]
+ *         1: data gradient  dx[B][H][W][Cin]   (elem type) from dy and wt[Cin][k][k][Cout]
+ *         2: weight gradient dw[Cout][k][k][Cin] (fp32, overwritten) from dy and x
+ * in0/in1: (x, w) | (dy, wt) | (dy, x).  `out` must not alias the inputs. */
+int cdp_k_conv(int dtype, int which, const void* in0, const void* in1, void* out, int B, int H, int W,
+               int Cin, int Cout, int ksize, int stride, int pad, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* CDP_KERNELS_H */

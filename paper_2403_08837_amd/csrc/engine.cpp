@@ -1,0 +1,836 @@
+// Host engine of libcdp: tick scheduler, weight-version ring, gradient-accumulator
+// bookkeeping, activation pool, per-tick launch lists, and the C ABI of include/cdp.h.
+//
+// Timeline (Sec. 3.2 "Algorithmic description", Fig. 1): micro-batch i of step t starts at
+// tick 2S*t + d*i and runs forward of stages 0..S-1 then backward of stages S-1..0, one
+// stage per tick.  Version rule (Sec. 3.2 "Update rules"): the forward of stage j reads
+//   DP: theta_t      v1: theta_{t-1}      v2: the freshest version in memory,
+// and the backward reads the version its own forward used, so that the applied gradient
+// is the gradient at one consistent point theta_hat_{i,t} as Eq. (CDP) states.  A stage
+// is updated at the end of the tick in which it received its N-th gradient; the new
+// version is written into the other ring slot and is visible from the next tick.
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cstdio>
+#include <cstring>
+#include <map>
+#include <string>
+#include <vector>
+
+#include "../../include/cdp.h"
+#include "kernels.h"
+#include "plan.h"
+
+using namespace cdp;
+
+namespace {
+
+constexpr int LOSS_LOG_STEPS = 1024;
+constexpr size_t TRACE_CAP = 1u << 20;
+
+thread_local std::string g_last_error;
+
+struct Block {
+  int64_t off = -1;
+  int64_t bytes = 0;
+  bool valid() const { return off >= 0; }
+};
+
+// Size-class slab pool over [base, base+cap) of the arena: one free list per block
+// size, new slots carved from a bump pointer.  Every size class is bounded by its own
+// peak live count, so the footprint stops growing after the first steady-state period.
+struct Pool {
+  int64_t base = 0, cap = 0, bump = 0, in_use = 0, peak = 0;
+  std::map<int64_t, std::vector<int64_t>> free_lists;
+  bool alloc(int64_t bytes, Block* out) {
+    bytes = align_up(std::max<int64_t>(bytes, 1), 256);
+    auto& fl = free_lists[bytes];
+    int64_t off;
+    if (!fl.empty()) {
+      off = fl.back();
+      fl.pop_back();
+    } else {
+      if (cap >= 0 && bump + bytes > cap) return false;
+      off = bump;
+      bump += bytes;
+    }
+    in_use += bytes;
+    peak = std::max(peak, in_use);
+    out->off = base + off;
+    out->bytes = bytes;
+    return true;
+  }
+  void release(const Block& b) {
+    if (!b.valid()) return;
+    free_lists[b.bytes].push_back(b.off - base);
+    in_use -= b.bytes;
+  }
+};
+
+struct VisitRecord {
+  bool live = false;
+  int version = 0;
+  int64_t step = 0;
+  std::vector<Block> t;  // per tensor of the stage
+};
+
+struct StageState {
+  int64_t master = 0, G = 0, slot[2] = {0, 0};
+  int ver = 0, cnt = 0;
+  int ring_ver[2] = {0, 0};
+};
+
+enum ItemKind { IT_GEMM, IT_COLSUM, IT_STAGE_IN, IT_CE, IT_MAXPOOL_F, IT_MAXPOOL_B, IT_GAP_F, IT_GAP_B };
+struct Item {
+  int kind;
+  GemmProb g;
+  ColsumProb c;
+  const void* p0 = nullptr; const void* p1 = nullptr; void* p2 = nullptr; void* p3 = nullptr;
+  int64_t n0 = 0;
+  int i[10] = {0};
+};
+typedef std::vector<std::vector<Item>> Program;
+
+}  // namespace
+
+struct cdp_ctx {
+  ModelPlan plan;
+  int S = 0, N = 0, B = 0, d = 0, rule = 0;
+  float lr = 0.f;
+  bool dry = false;
+  hipStream_t stream = nullptr;
+  char* arena = nullptr;
+  int64_t arena_bytes = 0;
+  std::vector<StageState> st;
+  int64_t labels_off = 0, loss_off = 0;
+  Pool pool;
+  std::vector<std::vector<VisitRecord>> rec;  // [mb][stage]
+  std::vector<Block> carry;                   // per micro-batch: activation / gradient between stages
+  std::vector<Block> deferred;                // released when the tick's launches are enqueued
+  int64_t tick = 0, origin_tick = 0, origin_step = 0, steps_enqueued = 0;
+  bool weights_locked = false;
+  std::vector<int> heads_done;                // per logged step: head passes run
+  std::vector<cdp_trace_rec> trace;
+  std::vector<int32_t> live_counts;
+  cdp_stats stats;
+  int64_t in_features = 0;                    // per-sample input elements
+  std::string err;
+
+  void* ptr(int64_t off) const { return reinterpret_cast<void*>(reinterpret_cast<uintptr_t>(arena) + (uintptr_t)off); }
+  float* fptr(int64_t off) const { return static_cast<float*>(ptr(off)); }
+};
+
+namespace {
+
+int fail(cdp_ctx* c, int code, const std::string& msg) {
+  if (c) c->err = msg;
+  g_last_error = msg;
+  return code;
+}
+
+#define HIP_TRY(ctx, expr)                                                                     \
+  do {                                                                                         \
+    hipError_t e_ = (expr);                                                                    \
+    if (e_ != hipSuccess) return fail(ctx, CDP_EHIP, std::string(#expr) + ": " + hipGetErrorString(e_)); \
+  } while (0)
+
+int64_t tensor_bytes(const cdp_ctx* c, const TensorInfo& t) {
+  return (int64_t)c->B * t.per_sample() * (t.f32 ? 4 : c->plan.elem_bytes);
+}
+
+bool pool_alloc(cdp_ctx* c, int64_t bytes, Block* b) {
+  if (!c->pool.alloc(bytes, b)) return false;
+  c->stats.peak_activation_bytes = std::max<int64_t>(c->stats.peak_activation_bytes, c->pool.in_use);
+  c->stats.pool_span_bytes = std::max<int64_t>(c->stats.pool_span_bytes, c->pool.bump);
+  return true;
+}
+
+// --------------------------------------------------------------------------- layouts
+struct StaticLayout {
+  std::vector<StageState> st;
+  int64_t labels_off, loss_off, pool_base, weight_bytes;
+};
+
+StaticLayout static_layout(const ModelPlan& plan, int N, int B) {
+  StaticLayout L;
+  int64_t off = 0;
+  L.weight_bytes = 0;
+  for (const StagePlan& sp : plan.stages) {
+    StageState s;
+    s.master = off; off = align_up(off + sp.n_params * 4, 256);
+    s.G = off; off = align_up(off + sp.n_params * 4, 256);
+    s.slot[0] = off; off = align_up(off + sp.slot_bytes, 256);
+    s.slot[1] = off; off = align_up(off + sp.slot_bytes, 256);
+    L.st.push_back(s);
+  }
+  L.weight_bytes = off;
+  L.labels_off = off; off = align_up(off + (int64_t)N * B * 4, 256);
+  L.loss_off = off; off = align_up(off + (int64_t)LOSS_LOG_STEPS * N * 4, 256);
+  L.pool_base = off;
+  return L;
+}
+
+// --------------------------------------------------------------------------- GEMM problems
+void conv_geom(const Op& o, int mode, ConvGeom* g) {
+  if (mode == OP_CONV_DGRAD) {
+    g->H = o.Hout; g->W = o.Wout; g->C = o.Cout; g->OH = o.Hin; g->OW = o.Win;
+  } else {
+    g->H = o.Hin; g->W = o.Win; g->C = o.Cin; g->OH = o.Hout; g->OW = o.Wout;
+  }
+  g->KH = o.KH; g->KW = o.KW; g->stride = o.stride; g->pad = o.pad;
+}
+
+bool pointwise(const Op& o) { return !o.is_conv || (o.KH == 1 && o.KW == 1 && o.stride == 1 && o.pad == 0); }
+
+GemmProb zero_prob() {
+  GemmProb p;
+  memset(&p, 0, sizeof(p));
+  p.splits = 1;
+  return p;
+}
+
+GemmProb fwd_prob(const cdp_ctx* c, const Op& o, const void* x, void* y, const char* slot, const void* res) {
+  GemmProb p = zero_prob();
+  const int rows = c->B * o.Hout * o.Wout;
+  p.A = x; p.B = slot + o.wf; p.out = y;
+  p.aux0 = o.bias_c >= 0 ? slot + o.bias_c : nullptr;
+  p.aux1 = res;
+  p.M = rows; p.N = o.Cout; p.K = (int)o.K();
+  p.ldb = (int)o.K(); p.ldo = o.Cout;
+  p.b_mode = OP_PLAIN_K;
+  if (pointwise(o)) { p.a_mode = OP_PLAIN_K; p.lda = o.Cin; }
+  else { p.a_mode = OP_CONV_FWD; conv_geom(o, OP_CONV_FWD, &p.g); }
+  p.epi = EPI_FWD;
+  p.flags = (o.relu ? GF_RELU : 0) | (o.out_f32 ? GF_OUT_F32 : 0);
+  return p;
+}
+
+GemmProb dgrad_prob(const cdp_ctx* c, const Op& o, const void* dz, void* dx, const char* slot, const void* add,
+                    const void* mask, bool accumulate) {
+  GemmProb p = zero_prob();
+  p.A = dz; p.B = slot + o.wt; p.out = dx; p.aux0 = add; p.aux1 = mask;
+  p.M = c->B * o.Hin * o.Win; p.N = o.Cin; p.K = o.KH * o.KW * o.Cout;
+  p.ldb = p.K; p.ldo = o.Cin;
+  p.b_mode = OP_PLAIN_K;
+  if (pointwise(o)) { p.a_mode = OP_PLAIN_K; p.lda = o.Cout; }
+  else { p.a_mode = OP_CONV_DGRAD; conv_geom(o, OP_CONV_DGRAD, &p.g); }
+  p.epi = EPI_DGRAD;
+  p.flags = accumulate ? GF_ACCUM : 0;
+  return p;
+}
+
+GemmProb wgrad_prob(const cdp_ctx* c, const Op& o, const void* dz, const void* x, const char* slot, float* G, bool first) {
+  GemmProb p = zero_prob();
+  const int rows = c->B * o.Hout * o.Wout;
+  p.A = dz; p.a_mode = OP_PLAIN_R; p.lda = o.Cout;
+  p.B = x;
+  if (pointwise(o)) { p.b_mode = OP_PLAIN_R; p.ldb = o.Cin; }
+  else { p.b_mode = OP_CONV_WGRAD; conv_geom(o, OP_CONV_WGRAD, &p.g); }
+  p.M = o.Cout; p.N = (int)o.K(); p.K = rows;
+  p.out = G + o.w_off; p.ldo = (int)o.K();
+  p.epi = EPI_WGRAD;
+  if (o.is_conv) {
+    // accumulators of conv weights are kept zeroed by the update kernel; split the long
+    // reduction over output positions and add atomically
+    p.flags = GF_ATOMIC;
+    const int tiles = ((p.M + 127) / 128) * ((p.N + 127) / 128);
+    const int ktiles = (p.K + 31) / 32;
+    int splits = std::max(1, std::min((1024 + tiles - 1) / tiles, ktiles / 8));
+    p.splits = std::min(splits, 256);
+    if (o.has_gamma) { p.aux0 = slot + o.gamma_c; p.aux1 = slot + o.wp; p.aux2 = G + o.g_off; }
+  } else {
+    p.flags = first ? 0 : GF_ACCUM;
+  }
+  return p;
+}
+
+int pick_tile(const GemmProb& p) {
+  if (p.M <= 64) return p.N >= 128 ? TILE_64x128 : TILE_64x64;
+  if (p.N <= 64) return TILE_64x64;
+  return TILE_128x128;
+}
+
+// --------------------------------------------------------------------------- programs
+int build_forward(cdp_ctx* c, int i, int64_t t, int j, int version, const float* x_dev, const int32_t* y_dev, Program* prog) {
+  const StagePlan& sp = c->plan.stages[j];
+  VisitRecord& r = c->rec[i][j];
+  r.live = true; r.version = version; r.step = t;
+  r.t.assign(sp.tensors.size(), Block());
+  const char* slot = static_cast<const char*>(c->ptr(c->st[j].slot[version & 1]));
+  size_t level = 0;
+  auto at = [&](size_t l) -> std::vector<Item>& { if (prog->size() <= l) prog->resize(l + 1); return (*prog)[l]; };
+  if (j == 0) {
+    if (!pool_alloc(c, tensor_bytes(c, sp.tensors[0]), &r.t[0])) return fail(c, CDP_ENOMEM, "activation pool exhausted");
+    Item it; it.kind = IT_STAGE_IN;
+    it.p0 = x_dev + (int64_t)i * c->B * c->in_features;
+    it.p1 = y_dev + (int64_t)i * c->B;
+    it.p2 = c->ptr(r.t[0].off);
+    it.p3 = static_cast<int32_t*>(c->ptr(c->labels_off)) + (int64_t)i * c->B;
+    it.i[0] = c->B; it.n0 = c->in_features;
+    at(level++).push_back(it);
+  } else {
+    r.t[0] = c->carry[i];
+    c->carry[i] = Block();
+  }
+  for (const Op& o : sp.ops) {
+    if (!pool_alloc(c, tensor_bytes(c, sp.tensors[o.out]), &r.t[o.out])) return fail(c, CDP_ENOMEM, "activation pool exhausted");
+    Item it;
+    if (o.kind == OPK_GEMM) {
+      it.kind = IT_GEMM;
+      it.g = fwd_prob(c, o, c->ptr(r.t[o.in].off), c->ptr(r.t[o.out].off), slot, o.res >= 0 ? c->ptr(r.t[o.res].off) : nullptr);
+    } else if (o.kind == OPK_MAXPOOL) {
+      it.kind = IT_MAXPOOL_F;
+      it.p0 = c->ptr(r.t[o.in].off); it.p2 = c->ptr(r.t[o.out].off);
+      it.i[0] = c->B; it.i[1] = o.Hin; it.i[2] = o.Win; it.i[3] = o.Cin; it.i[4] = o.pk; it.i[5] = o.ps; it.i[6] = o.pp;
+    } else if (o.kind == OPK_GAP) {
+      it.kind = IT_GAP_F;
+      it.p0 = c->ptr(r.t[o.in].off); it.p2 = c->ptr(r.t[o.out].off);
+      it.i[0] = c->B; it.i[1] = o.Hin * o.Win; it.i[2] = o.Cin;
+    } else {  // OPK_CE
+      it.kind = IT_CE;
+      it.p0 = c->ptr(r.t[o.in].off);
+      it.p1 = static_cast<int32_t*>(c->ptr(c->labels_off)) + (int64_t)i * c->B;
+      it.p2 = c->ptr(r.t[o.out].off);
+      it.p3 = c->fptr(c->loss_off) + (t % LOSS_LOG_STEPS) * c->N + i;
+      it.i[0] = c->B; it.i[1] = o.classes;
+    }
+    at(level++).push_back(it);
+  }
+  // keep what the backward pass reads; hand the stage output to the next stage
+  const int last = (int)sp.tensors.size() - 1;
+  for (int k = 0; k <= last; ++k) {
+    const TensorInfo& ti = sp.tensors[k];
+    bool keep = ti.consumed && !ti.f32;            // logits feed only the loss head
+    if (k == last) keep = sp.has_head;             // dlogits stay; other outputs travel on
+    if (k == last && !sp.has_head) { c->carry[i] = r.t[k]; r.t[k] = Block(); continue; }
+    if (!keep) { c->deferred.push_back(r.t[k]); r.t[k] = Block(); }
+  }
+  if (sp.has_head) c->heads_done[t % LOSS_LOG_STEPS]++;
+  return CDP_OK;
+}
+
+int build_backward(cdp_ctx* c, int i, int j, Program* prog, bool first_grad) {
+  const StagePlan& sp = c->plan.stages[j];
+  VisitRecord& r = c->rec[i][j];
+  if (!r.live) return fail(c, CDP_ESTATE, "backward without a matching forward");
+  const StageState& ss = c->st[j];
+  const char* slot = static_cast<const char*>(c->ptr(ss.slot[r.version & 1]));
+  float* G = c->fptr(ss.G);
+  const int nt = (int)sp.tensors.size(), last = nt - 1;
+  std::vector<const void*> g(nt, nullptr), addend(nt, nullptr);
+  std::vector<Block> owned(nt);
+  Block incoming;
+  if (sp.has_head) {
+    g[last] = c->ptr(r.t[last].off);
+  } else {
+    incoming = c->carry[i];
+    c->carry[i] = Block();
+    if (!incoming.valid()) return fail(c, CDP_ESTATE, "missing upstream gradient");
+    g[last] = c->ptr(incoming.off);
+  }
+  size_t level = 0;
+  auto at = [&](size_t l) -> std::vector<Item>& { if (prog->size() <= l) prog->resize(l + 1); return (*prog)[l]; };
+  for (int oi = (int)sp.ops.size() - 1; oi >= 0; --oi) {
+    const Op& o = sp.ops[oi];
+    const void* dz = g[o.out];
+    if (!dz && addend[o.out] && !sp.tensors[o.out].relu) dz = addend[o.out];  // tensor used only as a residual operand
+    if (!dz) return fail(c, CDP_ESTATE, "internal: gradient of a tensor was never produced");
+    if (o.kind == OPK_CE) { g[o.in] = dz; continue; }
+    const bool need_dx = !(j == 0 && o.in == 0);
+    const TensorInfo& tin = sp.tensors[o.in];
+    void* dx = nullptr;
+    bool accumulate = false;
+    if (need_dx) {
+      if (g[o.in]) {
+        dx = const_cast<void*>(g[o.in]);
+        accumulate = true;
+      } else {
+        if (!pool_alloc(c, tensor_bytes(c, tin), &owned[o.in])) return fail(c, CDP_ENOMEM, "activation pool exhausted");
+        dx = c->ptr(owned[o.in].off);
+        g[o.in] = dx;
+      }
+    }
+    const void* xin = c->ptr(r.t[o.in].off);
+    const void* mask = tin.relu ? xin : nullptr;
+    if (o.kind == OPK_GEMM) {
+      if (o.res >= 0) {
+        if (g[o.res] || addend[o.res]) return fail(c, CDP_EINVAL, "residual operand with an earlier gradient is not supported");
+        addend[o.res] = dz;
+      }
+      if (need_dx) {
+        Item it; it.kind = IT_GEMM;
+        it.g = dgrad_prob(c, o, dz, dx, slot, accumulate ? nullptr : addend[o.in], mask, accumulate);
+        at(level).push_back(it);
+      }
+      Item w; w.kind = IT_GEMM;
+      w.g = wgrad_prob(c, o, dz, xin, slot, G, first_grad);
+      at(level).push_back(w);
+      if (o.b_off >= 0) {
+        Item b; b.kind = IT_COLSUM;
+        b.c.src = dz; b.c.out = G + o.b_off; b.c.rows = c->B * o.Hout * o.Wout; b.c.cols = o.Cout; b.c.ld = o.Cout;
+        at(level).push_back(b);
+      }
+    } else if (need_dx) {
+      if (accumulate) return fail(c, CDP_EINVAL, "pooling input with several consumers is not supported");
+      Item it;
+      it.kind = (o.kind == OPK_MAXPOOL) ? IT_MAXPOOL_B : IT_GAP_B;
+      it.p0 = xin; it.p1 = dz; it.p2 = dx;
+      if (o.kind == OPK_MAXPOOL) {
+        it.i[0] = c->B; it.i[1] = o.Hin; it.i[2] = o.Win; it.i[3] = o.Cin; it.i[4] = o.pk; it.i[5] = o.ps; it.i[6] = o.pp;
+        it.i[7] = tin.relu ? 1 : 0;
+      } else {
+        it.i[0] = c->B; it.i[1] = o.Hin * o.Win; it.i[2] = o.Cin; it.i[3] = tin.relu ? 1 : 0;
+      }
+      at(level).push_back(it);
+    }
+    ++level;
+  }
+  // release everything the pass held; the gradient of the stage input travels on
+  for (int k = 0; k < nt; ++k) {
+    if (r.t[k].valid()) c->deferred.push_back(r.t[k]);
+    if (owned[k].valid()) {
+      if (k == 0 && j > 0) c->carry[i] = owned[k];
+      else c->deferred.push_back(owned[k]);
+    }
+  }
+  if (incoming.valid()) c->deferred.push_back(incoming);
+  r.live = false;
+  r.t.clear();
+  return CDP_OK;
+}
+
+// --------------------------------------------------------------------------- launching
+int launch_level(cdp_ctx* c, std::vector<Item>& items) {
+  // grouped contractions, one launch per tile shape (and per GEMM_MAX_PROBS problems)
+  for (int shape = 0; shape < TILE_COUNT; ++shape) {
+    std::vector<const GemmProb*> sel;
+    for (const Item& it : items)
+      if (it.kind == IT_GEMM && pick_tile(it.g) == shape) sel.push_back(&it.g);
+    // longest reductions first so the tail of the launch is made of short tiles
+    std::stable_sort(sel.begin(), sel.end(), [](const GemmProb* a, const GemmProb* b) { return a->K / a->splits > b->K / b->splits; });
+    for (size_t k = 0; k < sel.size(); k += GEMM_MAX_PROBS) {
+      GemmBatch batch;
+      batch.n = (int)std::min<size_t>(GEMM_MAX_PROBS, sel.size() - k);
+      for (int q = 0; q < batch.n; ++q) batch.p[q] = *sel[k + q];
+      HIP_TRY(c, launch_gemm_batch(batch, c->plan.dtype, shape, c->stream));
+      c->stats.kernel_launches++;
+    }
+  }
+  ColsumBatch cb;
+  cb.n = 0;
+  for (const Item& it : items) {
+    if (it.kind != IT_COLSUM) continue;
+    cb.p[cb.n++] = it.c;
+    if (cb.n == COLSUM_MAX_PROBS) {
+      HIP_TRY(c, launch_colsum_batch(cb, c->plan.dtype, c->stream));
+      c->stats.kernel_launches++;
+      cb.n = 0;
+    }
+  }
+  if (cb.n) {
+    HIP_TRY(c, launch_colsum_batch(cb, c->plan.dtype, c->stream));
+    c->stats.kernel_launches++;
+  }
+  const int dt = c->plan.dtype;
+  for (const Item& it : items) {
+    switch (it.kind) {
+      case IT_STAGE_IN:
+        HIP_TRY(c, launch_stage_input(static_cast<const float*>(it.p0), static_cast<const int32_t*>(it.p1), it.p2,
+                                      static_cast<int32_t*>(it.p3), it.i[0], it.n0, dt, c->stream));
+        break;
+      case IT_CE:
+        HIP_TRY(c, launch_ce_head(static_cast<const float*>(it.p0), static_cast<const int32_t*>(it.p1), it.p2,
+                                  static_cast<float*>(it.p3), it.i[0], it.i[1], dt, c->stream));
+        break;
+      case IT_MAXPOOL_F:
+        HIP_TRY(c, launch_maxpool_fwd(it.p0, it.p2, it.i[0], it.i[1], it.i[2], it.i[3], it.i[4], it.i[5], it.i[6], dt, c->stream));
+        break;
+      case IT_MAXPOOL_B:
+        HIP_TRY(c, launch_maxpool_bwd(it.p0, it.p1, it.p2, it.i[0], it.i[1], it.i[2], it.i[3], it.i[4], it.i[5], it.i[6],
+                                      it.i[7], dt, c->stream));
+        break;
+      case IT_GAP_F:
+        HIP_TRY(c, launch_gap_fwd(it.p0, it.p2, it.i[0], it.i[1], it.i[2], dt, c->stream));
+        break;
+      case IT_GAP_B:
+        HIP_TRY(c, launch_gap_bwd(it.p0, it.p1, it.p2, it.i[0], it.i[1], it.i[2], it.i[3], dt, c->stream));
+        break;
+      default:
+        continue;
+    }
+    c->stats.kernel_launches++;
+  }
+  return CDP_OK;
+}
+
+int launch_program(cdp_ctx* c, Program& prog) {
+  for (auto& level : prog) {
+    int rc = launch_level(c, level);
+    if (rc) return rc;
+  }
+  return CDP_OK;
+}
+
+// Writes the compute copies of stage j's current master weights into ring slot `slot`;
+// with scale != 0 first applies master -= scale * G (the SGD step of Eq. (CDP)).
+int refresh_slot(cdp_ctx* c, int j, int slot, float scale) {
+  const StagePlan& sp = c->plan.stages[j];
+  const StageState& ss = c->st[j];
+  char* sl = static_cast<char*>(c->ptr(ss.slot[slot]));
+  float* master = c->fptr(ss.master);
+  float* G = c->fptr(ss.G);
+  for (const Op& o : sp.ops) {
+    if (o.kind != OPK_GEMM) continue;
+    // vector parameters first: the folded weights use the updated gamma
+    if (o.g_off >= 0) {
+      HIP_TRY(c, launch_update_vec(master + o.g_off, G + o.g_off, reinterpret_cast<float*>(sl + o.gamma_c), o.Cout, scale, c->stream));
+      c->stats.kernel_launches++;
+    }
+    if (o.b_off >= 0) {
+      HIP_TRY(c, launch_update_vec(master + o.b_off, G + o.b_off, reinterpret_cast<float*>(sl + o.bias_c), o.Cout, scale, c->stream));
+      c->stats.kernel_launches++;
+    }
+    RepackArgs a;
+    a.master = master + o.w_off; a.G = G + o.w_off;
+    a.gamma = o.has_gamma ? reinterpret_cast<const float*>(sl + o.gamma_c) : nullptr;
+    a.wf = sl + o.wf; a.wt = sl + o.wt; a.wp = o.has_gamma ? sl + o.wp : nullptr;
+    a.O = o.Cout; a.T = o.KH * o.KW; a.C = o.Cin; a.scale = scale;
+    a.zero_g = o.is_conv ? 1 : 0;  // conv accumulators take atomic adds and must start at zero
+    HIP_TRY(c, launch_repack(a, c->plan.dtype, c->stream));
+    c->stats.kernel_launches++;
+  }
+  return CDP_OK;
+}
+
+int inflight(const cdp_ctx* c) {
+  int n = 0;
+  for (int i = 0; i < c->N; ++i) {
+    const int64_t rel = c->tick - c->origin_tick - (int64_t)c->d * i;
+    if (rel < 0) continue;
+    const int64_t t = c->origin_step + rel / (2 * c->S);
+    if (t < c->steps_enqueued) ++n;
+  }
+  return n;
+}
+
+int run_tick(cdp_ctx* c, const float* x_dev, const int32_t* y_dev) {
+  const int S = c->S, N = c->N, d = c->d;
+  const int64_t rel_tick = c->tick - c->origin_tick;
+  if (rel_tick % (2 * S) == 0) {
+    const int64_t t_new = c->origin_step + rel_tick / (2 * S);
+    if (t_new == c->steps_enqueued && x_dev != nullptr) {
+      if (!y_dev) return fail(c, CDP_EINVAL, "labels missing");
+      c->steps_enqueued++;
+      c->heads_done[t_new % LOSS_LOG_STEPS] = 0;
+    }
+  }
+  struct Visit { int i; int64_t t; int j; int dir; int version; };
+  std::vector<Visit> act;
+  int n_fwd = 0;
+  for (int i = 0; i < N; ++i) {
+    const int64_t rel = rel_tick - (int64_t)d * i;
+    if (rel < 0) continue;
+    const int64_t t = c->origin_step + rel / (2 * S);
+    const int p = (int)(rel % (2 * S));
+    if (t >= c->steps_enqueued) continue;
+    Visit v{i, t, p < S ? p : 2 * S - 1 - p, p < S ? 0 : 1, 0};
+    if (v.dir == 0 && v.j == 0 && x_dev == nullptr) return fail(c, CDP_EINVAL, "a micro-batch starts in this tick but x_dev is NULL");
+    n_fwd += (v.dir == 0);
+    act.push_back(v);
+  }
+  int live = n_fwd;
+  for (int i = 0; i < N; ++i)
+    for (int j = 0; j < S; ++j) live += c->rec[i][j].live ? 1 : 0;
+  c->stats.last_live_stage_inputs = live;
+  c->stats.peak_live_stage_inputs = std::max<int64_t>(c->stats.peak_live_stage_inputs, live);
+  if (c->live_counts.size() < TRACE_CAP) c->live_counts.push_back(live);
+  c->weights_locked = c->weights_locked || !act.empty();
+
+  std::vector<Program> progs(act.size());
+  for (size_t a = 0; a < act.size(); ++a) {
+    Visit& v = act[a];
+    StageState& ss = c->st[v.j];
+    int rc;
+    if (v.dir == 0) {
+      if (c->rule == CDP_RULE_V2) v.version = ss.ver;
+      else if (c->rule == CDP_RULE_V1) v.version = (int)std::max<int64_t>(v.t - 1, 0);
+      else v.version = (int)v.t;
+      if (ss.ring_ver[v.version & 1] != v.version) return fail(c, CDP_ESTATE, "internal: weight version left the ring before its forward");
+      rc = build_forward(c, v.i, v.t, v.j, v.version, x_dev, y_dev, &progs[a]);
+    } else {
+      v.version = c->rec[v.i][v.j].version;
+      if (ss.ring_ver[v.version & 1] != v.version) return fail(c, CDP_ESTATE, "internal: weight version left the ring before its backward");
+      rc = build_backward(c, v.i, v.j, &progs[a], ss.cnt == 0);
+      ss.cnt++;
+    }
+    if (rc) return rc;
+    if (c->trace.size() < TRACE_CAP) c->trace.push_back(cdp_trace_rec{(int32_t)c->tick, v.i, (int32_t)v.t, v.j, v.dir, v.version});
+  }
+  if (!c->dry) {
+    if (c->rule == CDP_RULE_DP) {
+      // lock-step: all micro-batches hit the same stage, so passes run one after another
+      // (their weight gradients share one accumulator)
+      for (auto& p : progs) {
+        int rc = launch_program(c, p);
+        if (rc) return rc;
+      }
+    } else {
+      // cyclic: the passes of a tick touch distinct micro-batches and never two backwards of
+      // one stage, so their launch lists merge level by level into grouped launches
+      Program merged;
+      for (auto& p : progs) {
+        if (merged.size() < p.size()) merged.resize(p.size());
+        for (size_t l = 0; l < p.size(); ++l) merged[l].insert(merged[l].end(), p[l].begin(), p[l].end());
+      }
+      int rc = launch_program(c, merged);
+      if (rc) return rc;
+    }
+  }
+  for (const Block& b : c->deferred) c->pool.release(b);
+  c->deferred.clear();
+  c->stats.cur_activation_bytes = c->pool.in_use;
+  // SGD update of every stage that now holds N gradients (end of tick)
+  for (int j = 0; j < S; ++j) {
+    StageState& ss = c->st[j];
+    if (ss.cnt != N) continue;
+    const int nv = ss.ver + 1;
+    if (!c->dry) {
+      int rc = refresh_slot(c, j, nv & 1, c->lr / (float)N);
+      if (rc) return rc;
+    }
+    ss.ring_ver[nv & 1] = nv;
+    ss.ver = nv;
+    ss.cnt = 0;
+  }
+  c->tick++;
+  c->stats.ticks_run = c->tick;
+  c->stats.steps_enqueued = c->steps_enqueued;
+  // a fully drained timeline restarts its cycle at the next tick
+  if (inflight(c) == 0) {
+    bool any = false;
+    for (int i = 0; i < N && !any; ++i)
+      for (int j = 0; j < S && !any; ++j) any = c->rec[i][j].live;
+    if (!any) { c->origin_tick = c->tick; c->origin_step = c->steps_enqueued; }
+  }
+  return CDP_OK;
+}
+
+int check_args(const cdp_stage_desc* stages, int n_stages, int N, int B, int rule, const cdp_opts* opts, ModelPlan* plan) {
+  if (!stages || !opts) return fail(nullptr, CDP_EINVAL, "stages/opts is NULL");
+  if (N <= 0 || B <= 0) return fail(nullptr, CDP_EINVAL, "N and micro_batch must be positive");
+  if (rule != CDP_RULE_DP && rule != CDP_RULE_V1 && rule != CDP_RULE_V2) return fail(nullptr, CDP_EINVAL, "unknown update rule");
+  if (rule != CDP_RULE_DP && (2 * n_stages) % N != 0)
+    return fail(nullptr, CDP_EINVAL, "the cyclic schedule needs N to divide 2S (uniform delay d = 2S/N)");
+  std::string e = build_plan(stages, n_stages, opts, plan);
+  if (!e.empty()) return fail(nullptr, CDP_EINVAL, e);
+  if (B > 1024 && plan->stages.back().has_head) return fail(nullptr, CDP_EINVAL, "micro_batch above 1024 is not supported by the loss head");
+  return CDP_OK;
+}
+
+int make_ctx(cdp_ctx** out, const cdp_stage_desc* stages, int n_stages, int N, int B, float lr, int rule, const cdp_opts* opts,
+             bool force_dry) {
+  cdp_ctx* c = new cdp_ctx();
+  int rc = check_args(stages, n_stages, N, B, rule, opts, &c->plan);
+  if (rc) { delete c; return rc; }
+  c->S = n_stages; c->N = N; c->B = B; c->rule = rule; c->lr = lr;
+  c->d = rule == CDP_RULE_DP ? 0 : 2 * n_stages / N;
+  c->dry = force_dry || opts->dry_run != 0;
+  c->stream = static_cast<hipStream_t>(opts->hip_stream);
+  c->arena = c->dry ? nullptr : static_cast<char*>(opts->arena);
+  c->arena_bytes = (int64_t)opts->arena_bytes;
+  StaticLayout L = static_layout(c->plan, N, B);
+  c->st = L.st;
+  c->labels_off = L.labels_off; c->loss_off = L.loss_off;
+  c->pool.base = L.pool_base;
+  c->pool.cap = c->dry ? -1 : c->arena_bytes - L.pool_base;
+  c->rec.assign(N, std::vector<VisitRecord>(n_stages));
+  c->carry.assign(N, Block());
+  c->heads_done.assign(LOSS_LOG_STEPS, 0);
+  memset(&c->stats, 0, sizeof(c->stats));
+  c->stats.weight_bytes = L.weight_bytes;
+  const TensorInfo& t0 = c->plan.stages[0].tensors[0];
+  c->in_features = t0.per_sample();
+  // lock-step DP keeps every stage input of every micro-batch at the end of the forward pass
+  int64_t dp = 0;
+  for (const StagePlan& sp : c->plan.stages)
+    for (size_t k = 0; k + 1 < sp.tensors.size(); ++k)
+      if (sp.tensors[k].consumed && !sp.tensors[k].f32) dp += align_up(tensor_bytes(c, sp.tensors[k]), 256);
+  c->stats.dp_activation_bytes = dp * N;
+  *out = c;
+  return CDP_OK;
+}
+
+}  // namespace
+
+// =============================================================================== C ABI
+extern "C" {
+
+int cdp_arena_bytes(const cdp_stage_desc* stages, int n_stages, int N, int B, int rule, const cdp_opts* opts, size_t* bytes_out) {
+  if (!bytes_out) return fail(nullptr, CDP_EINVAL, "bytes_out is NULL");
+  cdp_ctx* c = nullptr;
+  int rc = make_ctx(&c, stages, n_stages, N, B, 0.f, rule, opts, true);
+  if (rc) return rc;
+  // dry simulation of the timeline: the pool is deterministic, so the span found here is
+  // the span of the real run
+  const float* fake_x = reinterpret_cast<const float*>(uintptr_t(256));
+  const int32_t* fake_y = reinterpret_cast<const int32_t*>(uintptr_t(256));
+  const int steps = 4;
+  for (int t = 0; t < steps && rc == CDP_OK; ++t)
+    for (int k = 0; k < 2 * n_stages && rc == CDP_OK; ++k) rc = run_tick(c, fake_x, fake_y);
+  while (rc == CDP_OK && inflight(c) > 0) rc = run_tick(c, nullptr, nullptr);
+  if (rc == CDP_OK) *bytes_out = (size_t)(c->pool.base + align_up(c->pool.bump, 256) + 256);
+  else g_last_error = c->err;
+  delete c;
+  return rc;
+}
+
+int cdp_init(cdp_ctx** out, const cdp_stage_desc* stages, int n_stages, int N, int B, float lr, int rule, const cdp_opts* opts) {
+  if (!out) return fail(nullptr, CDP_EINVAL, "out is NULL");
+  *out = nullptr;
+  cdp_ctx* c = nullptr;
+  int rc = make_ctx(&c, stages, n_stages, N, B, lr, rule, opts, false);
+  if (rc) return rc;
+  if (!c->dry) {
+    size_t need = 0;
+    rc = cdp_arena_bytes(stages, n_stages, N, B, rule, opts, &need);
+    if (rc) { delete c; return rc; }
+    if (!opts->arena || (reinterpret_cast<uintptr_t>(opts->arena) & 255) != 0) {
+      delete c;
+      return fail(nullptr, CDP_EINVAL, "arena must be a 256-byte aligned device pointer");
+    }
+    if (opts->arena_bytes < need) {
+      delete c;
+      return fail(nullptr, CDP_ENOMEM, "arena too small: need " + std::to_string(need) + " bytes");
+    }
+    // accumulators and the loss log start at zero; weights are zero until cdp_set_weights
+    hipError_t e = hipMemsetAsync(c->arena, 0, (size_t)c->pool.base, c->stream);
+    if (e != hipSuccess) {
+      std::string m = std::string("hipMemsetAsync: ") + hipGetErrorString(e);
+      delete c;
+      return fail(nullptr, CDP_EHIP, m);
+    }
+  }
+  *out = c;
+  return CDP_OK;
+}
+
+int cdp_param_count(const cdp_ctx* c, int stage, size_t* n_out) {
+  if (!c || !n_out || stage < 0 || stage >= c->S) return fail(nullptr, CDP_EINVAL, "bad argument");
+  *n_out = (size_t)c->plan.stages[stage].n_params;
+  return CDP_OK;
+}
+
+int cdp_set_weights(cdp_ctx* c, int stage, const float* host, size_t n) {
+  if (!c) return fail(nullptr, CDP_EINVAL, "ctx is NULL");
+  if (stage < 0 || stage >= c->S || !host) return fail(c, CDP_EINVAL, "bad stage or NULL weights");
+  if (n != (size_t)c->plan.stages[stage].n_params) return fail(c, CDP_EINVAL, "weight count does not match the stage");
+  if (c->weights_locked) return fail(c, CDP_ESTATE, "weights can only be set before the first tick");
+  if (c->dry) return CDP_OK;
+  HIP_TRY(c, hipMemcpyAsync(c->fptr(c->st[stage].master), host, n * 4, hipMemcpyHostToDevice, c->stream));
+  HIP_TRY(c, hipStreamSynchronize(c->stream));
+  for (int s = 0; s < 2; ++s) {
+    int rc = refresh_slot(c, stage, s, 0.f);
+    if (rc) return rc;
+  }
+  return CDP_OK;
+}
+
+int cdp_tick(cdp_ctx* c, const float* x_dev, const int32_t* y_dev) {
+  if (!c) return fail(nullptr, CDP_EINVAL, "ctx is NULL");
+  return run_tick(c, x_dev, y_dev);
+}
+
+int cdp_step(cdp_ctx* c, const float* x_dev, const int32_t* y_dev) {
+  if (!c) return fail(nullptr, CDP_EINVAL, "ctx is NULL");
+  if (!x_dev || !y_dev) return fail(c, CDP_EINVAL, "x_dev / y_dev is NULL");
+  if ((c->tick - c->origin_tick) % (2 * c->S) != 0) return fail(c, CDP_ESTATE, "cdp_step must start on a step boundary");
+  for (int k = 0; k < 2 * c->S; ++k) {
+    int rc = run_tick(c, x_dev, y_dev);
+    if (rc) return rc;
+  }
+  return CDP_OK;
+}
+
+int cdp_drain(cdp_ctx* c) {
+  if (!c) return fail(nullptr, CDP_EINVAL, "ctx is NULL");
+  // finish the started step boundary bookkeeping: no new mini-batch is enqueued, so the
+  // remaining passes are exactly those of micro-batches already in flight
+  int guard = 4 * c->S + c->d * c->N + 4;
+  while (inflight(c) > 0 && guard-- > 0) {
+    int rc = run_tick(c, nullptr, nullptr);
+    if (rc) return rc;
+  }
+  return CDP_OK;
+}
+
+int cdp_get_weights(cdp_ctx* c, int stage, int version, float* host, size_t cap, size_t* n_out) {
+  if (!c) return fail(nullptr, CDP_EINVAL, "ctx is NULL");
+  if (stage < 0 || stage >= c->S || !host) return fail(c, CDP_EINVAL, "bad stage or NULL buffer");
+  const StagePlan& sp = c->plan.stages[stage];
+  const StageState& ss = c->st[stage];
+  if (n_out) *n_out = (size_t)sp.n_params;
+  if (cap < (size_t)sp.n_params) return fail(c, CDP_EINVAL, "buffer too small");
+  if (version < 0) version = ss.ver;
+  if (c->dry) return fail(c, CDP_ESTATE, "no weights in a dry run");
+  if (version == ss.ver) {
+    HIP_TRY(c, hipStreamSynchronize(c->stream));
+    HIP_TRY(c, hipMemcpy(host, c->fptr(ss.master), (size_t)sp.n_params * 4, hipMemcpyDeviceToHost));
+    return CDP_OK;
+  }
+  if (version != ss.ver - 1 || ss.ring_ver[version & 1] != version) return fail(c, CDP_ESTATE, "that weight version is no longer in the ring");
+  if (sp.has_gamma) return fail(c, CDP_ESTATE, "ring copies of stages with affine layers are folded and cannot be read back");
+  float* tmp = nullptr;
+  HIP_TRY(c, hipMalloc(reinterpret_cast<void**>(&tmp), (size_t)sp.n_params * 4));
+  const char* sl = static_cast<const char*>(c->ptr(ss.slot[version & 1]));
+  hipError_t e = hipSuccess;
+  for (const Op& o : sp.ops) {
+    if (o.kind != OPK_GEMM) continue;
+    if (e == hipSuccess) e = launch_to_f32(sl + o.wf, tmp + o.w_off, o.w_count(), c->plan.dtype, c->stream);
+    if (e == hipSuccess && o.b_off >= 0)
+      e = hipMemcpyAsync(tmp + o.b_off, sl + o.bias_c, (size_t)o.Cout * 4, hipMemcpyDeviceToDevice, c->stream);
+  }
+  if (e == hipSuccess) e = hipStreamSynchronize(c->stream);
+  if (e == hipSuccess) e = hipMemcpy(host, tmp, (size_t)sp.n_params * 4, hipMemcpyDeviceToHost);
+  (void)hipFree(tmp);
+  if (e != hipSuccess) return fail(c, CDP_EHIP, std::string("cdp_get_weights: ") + hipGetErrorString(e));
+  return CDP_OK;
+}
+
+int cdp_get_losses(cdp_ctx* c, int64_t step, float* host, size_t cap) {
+  if (!c || !host) return fail(c, CDP_EINVAL, "bad argument");
+  if (cap < (size_t)c->N) return fail(c, CDP_EINVAL, "buffer too small");
+  if (step < 0 || step >= c->steps_enqueued || step + LOSS_LOG_STEPS <= c->steps_enqueued - 1)
+    return fail(c, CDP_ESTATE, "step is not in the loss log");
+  if (c->heads_done[step % LOSS_LOG_STEPS] < c->N) return fail(c, CDP_ESTATE, "not every micro-batch of that step has reached the head yet");
+  if (c->dry) return fail(c, CDP_ESTATE, "no losses in a dry run");
+  HIP_TRY(c, hipStreamSynchronize(c->stream));
+  HIP_TRY(c, hipMemcpy(host, c->fptr(c->loss_off) + (step % LOSS_LOG_STEPS) * c->N, (size_t)c->N * 4, hipMemcpyDeviceToHost));
+  return CDP_OK;
+}
+
+int cdp_get_trace(const cdp_ctx* c, cdp_trace_rec* out, size_t cap, size_t* n_out) {
+  if (!c) return fail(nullptr, CDP_EINVAL, "ctx is NULL");
+  if (n_out) *n_out = c->trace.size();
+  if (out) memcpy(out, c->trace.data(), std::min(cap, c->trace.size()) * sizeof(cdp_trace_rec));
+  return CDP_OK;
+}
+
+int cdp_get_live_counts(const cdp_ctx* c, int32_t* out, size_t cap, size_t* n_out) {
+  if (!c) return fail(nullptr, CDP_EINVAL, "ctx is NULL");
+  if (n_out) *n_out = c->live_counts.size();
+  if (out) memcpy(out, c->live_counts.data(), std::min(cap, c->live_counts.size()) * sizeof(int32_t));
+  return CDP_OK;
+}
+
+int cdp_get_stats(const cdp_ctx* c, cdp_stats* out) {
+  if (!c || !out) return fail(nullptr, CDP_EINVAL, "bad argument");
+  *out = c->stats;
+  return CDP_OK;
+}
+
+const char* cdp_last_error(const cdp_ctx* c) { return c ? c->err.c_str() : g_last_error.c_str(); }
+
+void cdp_destroy(cdp_ctx* c) { delete c; }
+
+}  // extern "C"

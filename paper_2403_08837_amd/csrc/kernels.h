@@ -1,0 +1,121 @@
+// Kernel-side interface of libcdp: problem descriptors handed to the grouped kernels by
+// value (kernel arguments), and the host launch functions.  Device pointers only.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace cdp {
+
+enum DType : int { DT_F32 = 0, DT_BF16 = 1 };
+
+// ---------------------------------------------------------------------------------
+// Grouped GEMM.  Every contraction of a tick (Linear or convolution; forward, data
+// gradient, weight gradient) is C[r][c] = sum_k A[r][k] * B[c][k] over *virtual*
+// operand matrices.  An operand is either a plain matrix or an on-the-fly im2col view
+// of an NHWC tensor, and is stored either k-contiguous or row-contiguous in memory.
+// ---------------------------------------------------------------------------------
+enum OperandMode : int {
+  OP_PLAIN_K = 0,  // ptr[r*ld + k]                      (k contiguous)
+  OP_PLAIN_R = 1,  // ptr[k*ld + r]                      (r contiguous)
+  OP_CONV_FWD = 2, // r = (b,oh,ow), k = (kh,kw,c):  src[b][oh*s-p+kh][ow*s-p+kw][c]
+  OP_CONV_DGRAD = 3, // r = (b,ih,iw), k = (kh,kw,o): src[b][(ih+p-kh)/s][(iw+p-kw)/s][o]
+  OP_CONV_WGRAD = 4  // r = (kh,kw,c), k = (b,oh,ow): src[b][oh*s-p+kh][ow*s-p+kw][c]
+};
+
+struct ConvGeom {
+  int H, W, C;    // gathered source tensor [*, H, W, C]
+  int OH, OW;     // spatial extent of the position index (b, oh, ow)
+  int KH, KW, stride, pad;
+};
+
+enum EpilogueKind : int {
+  EPI_FWD = 0,    // out = act(acc + bias[c] + res[r][c])            -> T or f32
+  EPI_DGRAD = 1,  // out = mask(acc + add[r][c] (+ out_old))         -> T
+  EPI_WGRAD = 2   // G[r][c] (+)= gamma[r] * acc ; Ggamma[r] += sum_c acc * Wplain[r][c]
+};
+
+struct GemmProb {
+  const void* A;
+  const void* B;
+  void* out;
+  const void* aux0;  // FWD: bias f32[c]   DGRAD: add T[r][c]      WGRAD: gamma f32[r]
+  const void* aux1;  // FWD: res T[r][c]   DGRAD: mask T[r][c]     WGRAD: Wplain T[r][c]
+  void* aux2;        //                                            WGRAD: Ggamma f32[r]
+  int M, N, K;       // C is M x N, reduction length K
+  int lda, ldb, ldo; // leading dims for plain operands / output / aux matrices
+  int a_mode, b_mode;
+  int epi;
+  int flags;         // bit0 relu, bit1 out_f32, bit2 accumulate (DGRAD: += out_old;
+                     // WGRAD: beta = 1), bit3 atomic (WGRAD)
+  int tiles_n;       // tiles along N
+  int splits;        // split-K factor (WGRAD atomic only), >= 1
+  int tile_begin;    // first block of this problem in the launch
+  ConvGeom g;        // geometry of the (single) gathered operand, if any
+};
+
+enum : int { GF_RELU = 1, GF_OUT_F32 = 2, GF_ACCUM = 4, GF_ATOMIC = 8 };
+
+constexpr int GEMM_MAX_PROBS = 24;
+struct GemmBatch {
+  int n;
+  int total_tiles;
+  GemmProb p[GEMM_MAX_PROBS];
+};
+static_assert(sizeof(GemmBatch) <= 4000, "kernel argument block must stay under 4 KiB");
+
+// Tile shape variants (rows x cols of C per workgroup).
+enum TileShape : int { TILE_128x128 = 0, TILE_64x128 = 1, TILE_64x64 = 2, TILE_COUNT = 3 };
+void tile_dims(int shape, int* bm, int* bn);
+
+// Fills tiles_n / tile_begin / total_tiles for the chosen tile shape and launches.
+hipError_t launch_gemm_batch(GemmBatch& batch, int dtype, int tile_shape, hipStream_t stream);
+
+// ---------------------------------------------------------------------------------
+// small kernels
+// ---------------------------------------------------------------------------------
+// fp32 -> T conversion of rows [row0, row0+rows) of the mini-batch, and label copy.
+hipError_t launch_stage_input(const float* x, const int32_t* y, void* x_out, int32_t* y_out,
+                              int rows, int64_t per_row, int dtype, hipStream_t stream);
+
+// Softmax cross-entropy of one micro-batch: logits f32 [B][C] -> loss (mean over rows)
+// written to *loss_out, dlogits = (softmax - onehot)/B as T [B][C].
+hipError_t launch_ce_head(const float* logits, const int32_t* labels, void* dlogits, float* loss_out,
+                          int B, int C, int dtype, hipStream_t stream);
+
+// out[c] += sum_r src[r][c]  (fp32 atomics; out must hold the running sum).
+struct ColsumProb { const void* src; float* out; int rows, cols, ld; };
+constexpr int COLSUM_MAX_PROBS = 32;
+struct ColsumBatch { int n; ColsumProb p[COLSUM_MAX_PROBS]; };
+hipError_t launch_colsum_batch(const ColsumBatch& b, int dtype, hipStream_t stream);
+
+// Vector parameters (bias, gamma, beta): master -= scale*G ; G = 0 ; copy = master.
+hipError_t launch_update_vec(float* master, float* G, float* copy_f32, int64_t n, float scale,
+                             hipStream_t stream);
+
+// Matrix parameters W[O][T][C] (Linear: T = 1):  master -= scale*G (if scale != 0), G = 0
+// if zero_g, then write the compute copies of the new version:
+//   wf[o][t][c] = T(gamma[o]*master)   forward layout
+//   wt[c][t][o] = T(gamma[o]*master)   data-gradient layout
+//   wp[o][t][c] = T(master)            plain copy (only when gamma != NULL)
+struct RepackArgs {
+  float* master; float* G; const float* gamma;
+  void* wf; void* wt; void* wp;
+  int O, T, C; float scale; int zero_g;
+};
+hipError_t launch_repack(const RepackArgs& a, int dtype, hipStream_t stream);
+
+// Max pool (NHWC) forward, and backward by gather (first maximum in (kh,kw) scan order
+// receives the gradient); backward optionally masks with x > 0.
+hipError_t launch_maxpool_fwd(const void* x, void* y, int B, int H, int W, int C, int k, int s, int p,
+                              int dtype, hipStream_t stream);
+hipError_t launch_maxpool_bwd(const void* x, const void* dy, void* dx, int B, int H, int W, int C, int k,
+                              int s, int p, int mask_relu, int dtype, hipStream_t stream);
+// Global average pool forward / backward (backward optionally masks with x > 0).
+hipError_t launch_gap_fwd(const void* x, void* y, int B, int HW, int C, int dtype, hipStream_t stream);
+hipError_t launch_gap_bwd(const void* x, const void* dy, void* dx, int B, int HW, int C, int mask_relu,
+                          int dtype, hipStream_t stream);
+// T -> f32 copy (cdp_get_weights of a ring copy).
+hipError_t launch_to_f32(const void* src, float* dst, int64_t n, int dtype, hipStream_t stream);
+hipError_t launch_fill_f32(float* dst, int64_t n, float v, hipStream_t stream);
+
+}  // namespace cdp

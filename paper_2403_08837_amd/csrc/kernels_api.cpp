@@ -1,0 +1,69 @@
+// C ABI of the kernel-level entry points (include/cdp_kernels.h).
+#include <hip/hip_runtime.h>
+
+#include <cstring>
+
+#include "../../include/cdp.h"
+#include "../../include/cdp_kernels.h"
+#include "kernels.h"
+
+using namespace cdp;
+
+extern "C" {
+
+int cdp_k_gemm(int dtype, int tile_shape, int a_kmajor, int b_kmajor, const void* A, const void* B, float* C, int M, int N,
+               int K, int lda, int ldb, void* stream) {
+  if (!A || !B || !C || M <= 0 || N <= 0 || K <= 0 || tile_shape < 0 || tile_shape >= TILE_COUNT) return CDP_EINVAL;
+  if (dtype != DT_F32 && dtype != DT_BF16) return CDP_EINVAL;
+  GemmBatch b;
+  memset(&b, 0, sizeof(b));
+  b.n = 1;
+  GemmProb& p = b.p[0];
+  p.A = A; p.B = B; p.out = C;
+  p.M = M; p.N = N; p.K = K; p.lda = lda; p.ldb = ldb; p.ldo = N;
+  p.a_mode = a_kmajor ? OP_PLAIN_K : OP_PLAIN_R;
+  p.b_mode = b_kmajor ? OP_PLAIN_K : OP_PLAIN_R;
+  p.epi = EPI_FWD;
+  p.flags = GF_OUT_F32;
+  p.splits = 1;
+  return launch_gemm_batch(b, dtype, tile_shape, static_cast<hipStream_t>(stream)) == hipSuccess ? CDP_OK : CDP_EHIP;
+}
+
+int cdp_k_conv(int dtype, int which, const void* in0, const void* in1, void* out, int B, int H, int W, int Cin, int Cout,
+               int ks, int stride, int pad, void* stream) {
+  if (!in0 || !in1 || !out || B <= 0 || H <= 0 || W <= 0 || Cin <= 0 || Cout <= 0 || ks <= 0 || stride <= 0 || pad < 0)
+    return CDP_EINVAL;
+  if (dtype != DT_F32 && dtype != DT_BF16) return CDP_EINVAL;
+  if (H + 2 * pad < ks || W + 2 * pad < ks) return CDP_EINVAL;
+  const int Ho = (H + 2 * pad - ks) / stride + 1, Wo = (W + 2 * pad - ks) / stride + 1;
+  GemmBatch b;
+  memset(&b, 0, sizeof(b));
+  b.n = 1;
+  GemmProb& p = b.p[0];
+  p.splits = 1;
+  p.A = in0; p.B = in1; p.out = out;
+  ConvGeom& g = p.g;
+  g.KH = ks; g.KW = ks; g.stride = stride; g.pad = pad;
+  if (which == 0) {
+    p.M = B * Ho * Wo; p.N = Cout; p.K = ks * ks * Cin;
+    p.a_mode = OP_CONV_FWD; p.b_mode = OP_PLAIN_K; p.ldb = p.K; p.ldo = Cout;
+    g.H = H; g.W = W; g.C = Cin; g.OH = Ho; g.OW = Wo;
+    p.epi = EPI_FWD;
+  } else if (which == 1) {
+    p.M = B * H * W; p.N = Cin; p.K = ks * ks * Cout;
+    p.a_mode = OP_CONV_DGRAD; p.b_mode = OP_PLAIN_K; p.ldb = p.K; p.ldo = Cin;
+    g.H = Ho; g.W = Wo; g.C = Cout; g.OH = H; g.OW = W;
+    p.epi = EPI_DGRAD;
+  } else if (which == 2) {
+    p.M = Cout; p.N = ks * ks * Cin; p.K = B * Ho * Wo;
+    p.a_mode = OP_PLAIN_R; p.lda = Cout; p.b_mode = OP_CONV_WGRAD; p.ldo = p.N;
+    g.H = H; g.W = W; g.C = Cin; g.OH = Ho; g.OW = Wo;
+    p.epi = EPI_WGRAD;
+  } else {
+    return CDP_EINVAL;
+  }
+  const int shape = p.M <= 64 ? (p.N >= 128 ? TILE_64x128 : TILE_64x64) : (p.N <= 64 ? TILE_64x64 : TILE_128x128);
+  return launch_gemm_batch(b, dtype, shape, static_cast<hipStream_t>(stream)) == hipSuccess ? CDP_OK : CDP_EHIP;
+}
+
+}  // extern "C"

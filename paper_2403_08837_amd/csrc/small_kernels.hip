@@ -1,0 +1,336 @@
+// HBM-bound and latency-bound kernels of the CDP hot path: micro-batch staging, the
+// softmax cross-entropy head (one wavefront per row), bias-gradient column sums, the
+// SGD update with re-layout of the new weight version (Eq. (CDP): theta_{t+1} =
+// theta_t - gamma/N * sum_i grad f_i), pooling.
+#include "kernels.h"
+
+namespace cdp {
+
+__device__ __forceinline__ float bf16_to_f32(uint16_t h) { return __uint_as_float(((uint32_t)h) << 16); }
+__device__ __forceinline__ uint16_t f32_to_bf16(float f) {
+  uint32_t u = __float_as_uint(f);
+  if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x40u);
+  u += 0x7fffu + ((u >> 16) & 1u);
+  return (uint16_t)(u >> 16);
+}
+template <typename T> __device__ __forceinline__ float ld_f32(const T* p, int64_t i);
+template <> __device__ __forceinline__ float ld_f32<uint16_t>(const uint16_t* p, int64_t i) { return bf16_to_f32(p[i]); }
+template <> __device__ __forceinline__ float ld_f32<float>(const float* p, int64_t i) { return p[i]; }
+template <typename T> __device__ __forceinline__ void st_f32(T* p, int64_t i, float v);
+template <> __device__ __forceinline__ void st_f32<uint16_t>(uint16_t* p, int64_t i, float v) { p[i] = f32_to_bf16(v); }
+template <> __device__ __forceinline__ void st_f32<float>(float* p, int64_t i, float v) { p[i] = v; }
+
+#define CDP_DISPATCH(dtype, CALL)                 \
+  do {                                            \
+    if ((dtype) == DT_BF16) { using T = uint16_t; CALL; } \
+    else { using T = float; CALL; }               \
+  } while (0)
+
+static inline int blocks_for(int64_t n, int per_block, int cap = 1 << 20) {
+  int64_t b = (n + per_block - 1) / per_block;
+  if (b < 1) b = 1;
+  if (b > cap) b = cap;
+  return (int)b;
+}
+
+// ---------------------------------------------------------------------------------
+template <typename T>
+__global__ void stage_input_kernel(const float* __restrict__ x, const int32_t* __restrict__ y, T* __restrict__ xo,
+                                   int32_t* __restrict__ yo, int rows, int64_t n) {
+  for (int64_t i = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x) {
+    st_f32<T>(xo, i, x[i]);
+    if (i < rows) yo[i] = y[i];
+  }
+}
+
+hipError_t launch_stage_input(const float* x, const int32_t* y, void* x_out, int32_t* y_out, int rows, int64_t per_row,
+                              int dtype, hipStream_t stream) {
+  int64_t n = (int64_t)rows * per_row;
+  if (n < rows) return hipErrorInvalidValue;
+  CDP_DISPATCH(dtype, hipLaunchKernelGGL((stage_input_kernel<T>), dim3(blocks_for(n, 256 * 4, 4096)), dim3(256), 0, stream,
+                                         x, y, static_cast<T*>(x_out), y_out, rows, n));
+  return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------------
+// One wavefront per row: max, sum of exponentials, loss and gradient.  The per-row
+// losses are reduced over the workgroup's rows; one workgroup handles the whole
+// micro-batch (B <= 1024 rows via a row loop), so the mean needs no atomics.
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+  for (int o = 32; o >= 1; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
+  return v;
+}
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+  for (int o = 32; o >= 1; o >>= 1) v += __shfl_xor(v, o, 64);
+  return v;
+}
+
+template <typename T>
+__global__ __launch_bounds__(256) void ce_head_kernel(const float* __restrict__ logits, const int32_t* __restrict__ labels,
+                                                      T* __restrict__ dlogits, float* __restrict__ loss_out, int B, int C) {
+  __shared__ float part[4];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  float loss_acc = 0.f;
+  const float invB = 1.0f / (float)B;
+  for (int row = wave; row < B; row += 4) {
+    const float* z = logits + (int64_t)row * C;
+    float m = -INFINITY;
+    for (int c = lane; c < C; c += 64) m = fmaxf(m, z[c]);
+    m = wave_max(m);
+    float s = 0.f;
+    for (int c = lane; c < C; c += 64) s += __expf(z[c] - m);
+    s = wave_sum(s);
+    const int y = labels[row];
+    const float inv = 1.0f / s;
+    for (int c = lane; c < C; c += 64) {
+      float p = __expf(z[c] - m) * inv;
+      st_f32<T>(dlogits, (int64_t)row * C + c, (p - (c == y ? 1.f : 0.f)) * invB);
+    }
+    loss_acc += (m + __logf(s)) - z[y];
+  }
+  if (lane == 0) part[wave] = loss_acc;
+  __syncthreads();
+  if (threadIdx.x == 0) *loss_out = (part[0] + part[1] + part[2] + part[3]) * invB;
+}
+
+hipError_t launch_ce_head(const float* logits, const int32_t* labels, void* dlogits, float* loss_out, int B, int C, int dtype,
+                          hipStream_t stream) {
+  CDP_DISPATCH(dtype, hipLaunchKernelGGL((ce_head_kernel<T>), dim3(1), dim3(256), 0, stream, logits, labels,
+                                         static_cast<T*>(dlogits), loss_out, B, C));
+  return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------------
+// Column sums: block = 64 columns x 4 row lanes; grid.y splits the rows; fp32 atomics.
+constexpr int COLSUM_ROWS_PER_BLOCK = 512;
+template <typename T>
+__global__ __launch_bounds__(256) void colsum_kernel(const ColsumBatch b) {
+  __shared__ float red[4][64];
+  const ColsumProb& P = b.p[blockIdx.z];
+  const int col = blockIdx.x * 64 + (threadIdx.x & 63);
+  const int rl = threadIdx.x >> 6;
+  const int r0 = blockIdx.y * COLSUM_ROWS_PER_BLOCK;
+  if (blockIdx.x * 64 >= P.cols || r0 >= P.rows) return;
+  const int r1 = min(P.rows, r0 + COLSUM_ROWS_PER_BLOCK);
+  float s = 0.f;
+  if (col < P.cols)
+    for (int r = r0 + rl; r < r1; r += 4) s += ld_f32<T>(static_cast<const T*>(P.src), (int64_t)r * P.ld + col);
+  red[rl][threadIdx.x & 63] = s;
+  __syncthreads();
+  if (rl == 0 && col < P.cols) atomicAdd(P.out + col, red[0][threadIdx.x] + red[1][threadIdx.x] + red[2][threadIdx.x] + red[3][threadIdx.x]);
+}
+
+hipError_t launch_colsum_batch(const ColsumBatch& b, int dtype, hipStream_t stream) {
+  if (b.n <= 0) return hipSuccess;
+  if (b.n > COLSUM_MAX_PROBS) return hipErrorInvalidValue;
+  int gx = 1, gy = 1;
+  for (int i = 0; i < b.n; ++i) {
+    gx = max(gx, (b.p[i].cols + 63) / 64);
+    gy = max(gy, (b.p[i].rows + COLSUM_ROWS_PER_BLOCK - 1) / COLSUM_ROWS_PER_BLOCK);
+  }
+  CDP_DISPATCH(dtype, hipLaunchKernelGGL((colsum_kernel<T>), dim3(gx, gy, b.n), dim3(256), 0, stream, b));
+  return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------------
+__global__ void update_vec_kernel(float* __restrict__ master, float* __restrict__ G, float* __restrict__ copy, int64_t n,
+                                  float scale) {
+  for (int64_t i = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x) {
+    float w = master[i];
+    if (scale != 0.f) {
+      w -= scale * G[i];
+      master[i] = w;
+    }
+    G[i] = 0.f;
+    copy[i] = w;
+  }
+}
+hipError_t launch_update_vec(float* master, float* G, float* copy_f32, int64_t n, float scale, hipStream_t stream) {
+  if (n <= 0) return hipSuccess;
+  hipLaunchKernelGGL(update_vec_kernel, dim3(blocks_for(n, 256, 1024)), dim3(256), 0, stream, master, G, copy_f32, n, scale);
+  return hipGetLastError();
+}
+
+// W[O][T][C]: tile 64(o) x 64(c) for one tap t.  Reads G and master coalesced along c,
+// writes master / wf / wp coalesced along c and wt coalesced along o via an LDS transpose.
+template <typename T>
+__global__ __launch_bounds__(256) void repack_kernel(const RepackArgs a) {
+  __shared__ float tile[64][65];
+  const int t = blockIdx.z;
+  const int o0 = blockIdx.y * 64, c0 = blockIdx.x * 64;
+  const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
+  T* wf = static_cast<T*>(a.wf);
+  T* wt = static_cast<T*>(a.wt);
+  T* wp = static_cast<T*>(a.wp);
+#pragma unroll 4
+  for (int i = 0; i < 16; ++i) {
+    const int o = o0 + ty + i * 4, c = c0 + tx;
+    float v = 0.f;
+    if (o < a.O && c < a.C) {
+      const int64_t idx = ((int64_t)o * a.T + t) * a.C + c;
+      float w = a.master[idx];
+      if (a.scale != 0.f) {
+        w -= a.scale * a.G[idx];
+        a.master[idx] = w;
+      }
+      if (a.zero_g) a.G[idx] = 0.f;
+      if (wp) st_f32<T>(wp, idx, w);
+      v = a.gamma ? a.gamma[o] * w : w;
+      st_f32<T>(wf, idx, v);
+    }
+    tile[ty + i * 4][tx] = v;
+  }
+  __syncthreads();
+#pragma unroll 4
+  for (int i = 0; i < 16; ++i) {
+    const int c = c0 + ty + i * 4, o = o0 + tx;
+    if (o < a.O && c < a.C) st_f32<T>(wt, ((int64_t)c * a.T + t) * a.O + o, tile[tx][ty + i * 4]);
+  }
+}
+
+hipError_t launch_repack(const RepackArgs& a, int dtype, hipStream_t stream) {
+  if (a.O <= 0 || a.C <= 0 || a.T <= 0) return hipErrorInvalidValue;
+  dim3 grid((a.C + 63) / 64, (a.O + 63) / 64, a.T);
+  CDP_DISPATCH(dtype, hipLaunchKernelGGL((repack_kernel<T>), grid, dim3(256), 0, stream, a));
+  return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------------
+template <typename T>
+__global__ void maxpool_fwd_kernel(const T* __restrict__ x, T* __restrict__ y, int B, int H, int W, int C, int OH, int OW,
+                                   int k, int s, int p) {
+  const int64_t n = (int64_t)B * OH * OW * C;
+  for (int64_t i = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x) {
+    int c = (int)(i % C);
+    int64_t q = i / C;
+    int ow = (int)(q % OW); q /= OW;
+    int oh = (int)(q % OH);
+    int b = (int)(q / OH);
+    float best = -INFINITY;
+    for (int kh = 0; kh < k; ++kh)
+      for (int kw = 0; kw < k; ++kw) {
+        int ih = oh * s - p + kh, iw = ow * s - p + kw;
+        if (ih < 0 || iw < 0 || ih >= H || iw >= W) continue;
+        best = fmaxf(best, ld_f32<T>(x, (((int64_t)b * H + ih) * W + iw) * C + c));
+      }
+    st_f32<T>(y, i, best);
+  }
+}
+
+// dx[b][ih][iw][c] = sum over windows whose first maximum sits at (ih, iw) of dy.
+template <typename T>
+__global__ void maxpool_bwd_kernel(const T* __restrict__ x, const T* __restrict__ dy, T* __restrict__ dx, int B, int H, int W,
+                                   int C, int OH, int OW, int k, int s, int p, int mask_relu) {
+  const int64_t n = (int64_t)B * H * W * C;
+  for (int64_t i = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x) {
+    int c = (int)(i % C);
+    int64_t q = i / C;
+    int iw = (int)(q % W); q /= W;
+    int ih = (int)(q % H);
+    int b = (int)(q / H);
+    const float xv = ld_f32<T>(x, i);
+    float g = 0.f;
+    if (!(mask_relu && !(xv > 0.f))) {
+      // windows (oh, ow) that contain (ih, iw): oh*s - p <= ih <= oh*s - p + k - 1
+      int oh_lo = max(0, (ih + p - k + s) / s), oh_hi = min(OH - 1, (ih + p) / s);
+      int ow_lo = max(0, (iw + p - k + s) / s), ow_hi = min(OW - 1, (iw + p) / s);
+      for (int oh = oh_lo; oh <= oh_hi; ++oh)
+        for (int ow = ow_lo; ow <= ow_hi; ++ow) {
+          // is (ih, iw) the first maximum of this window in (kh, kw) scan order?
+          bool first = true;
+          for (int kh = 0; kh < k && first; ++kh)
+            for (int kw = 0; kw < k; ++kw) {
+              int jh = oh * s - p + kh, jw = ow * s - p + kw;
+              if (jh < 0 || jw < 0 || jh >= H || jw >= W) continue;
+              if (jh == ih && jw == iw) continue;
+              float o = ld_f32<T>(x, (((int64_t)b * H + jh) * W + jw) * C + c);
+              bool before = (jh < ih) || (jh == ih && jw < iw);
+              if (o > xv || (before && o == xv)) { first = false; break; }
+            }
+          if (first) g += ld_f32<T>(dy, (((int64_t)b * OH + oh) * OW + ow) * C + c);
+        }
+    }
+    st_f32<T>(dx, i, g);
+  }
+}
+
+hipError_t launch_maxpool_fwd(const void* x, void* y, int B, int H, int W, int C, int k, int s, int p, int dtype,
+                              hipStream_t stream) {
+  int OH = (H + 2 * p - k) / s + 1, OW = (W + 2 * p - k) / s + 1;
+  int64_t n = (int64_t)B * OH * OW * C;
+  CDP_DISPATCH(dtype, hipLaunchKernelGGL((maxpool_fwd_kernel<T>), dim3(blocks_for(n, 256, 65536)), dim3(256), 0, stream,
+                                         static_cast<const T*>(x), static_cast<T*>(y), B, H, W, C, OH, OW, k, s, p));
+  return hipGetLastError();
+}
+hipError_t launch_maxpool_bwd(const void* x, const void* dy, void* dx, int B, int H, int W, int C, int k, int s, int p,
+                              int mask_relu, int dtype, hipStream_t stream) {
+  int OH = (H + 2 * p - k) / s + 1, OW = (W + 2 * p - k) / s + 1;
+  int64_t n = (int64_t)B * H * W * C;
+  CDP_DISPATCH(dtype, hipLaunchKernelGGL((maxpool_bwd_kernel<T>), dim3(blocks_for(n, 256, 65536)), dim3(256), 0, stream,
+                                         static_cast<const T*>(x), static_cast<const T*>(dy), static_cast<T*>(dx), B, H, W, C,
+                                         OH, OW, k, s, p, mask_relu));
+  return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------------
+template <typename T>
+__global__ void gap_fwd_kernel(const T* __restrict__ x, T* __restrict__ y, int B, int HW, int C) {
+  const int64_t n = (int64_t)B * C;
+  for (int64_t i = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x) {
+    int c = (int)(i % C);
+    int b = (int)(i / C);
+    float s = 0.f;
+    for (int q = 0; q < HW; ++q) s += ld_f32<T>(x, ((int64_t)b * HW + q) * C + c);
+    st_f32<T>(y, i, s / (float)HW);
+  }
+}
+template <typename T>
+__global__ void gap_bwd_kernel(const T* __restrict__ x, const T* __restrict__ dy, T* __restrict__ dx, int B, int HW, int C,
+                               int mask_relu) {
+  const int64_t n = (int64_t)B * HW * C;
+  const float inv = 1.0f / (float)HW;
+  for (int64_t i = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x) {
+    int c = (int)(i % C);
+    int b = (int)(i / ((int64_t)HW * C));
+    float g = ld_f32<T>(dy, (int64_t)b * C + c) * inv;
+    if (mask_relu && !(ld_f32<T>(x, i) > 0.f)) g = 0.f;
+    st_f32<T>(dx, i, g);
+  }
+}
+hipError_t launch_gap_fwd(const void* x, void* y, int B, int HW, int C, int dtype, hipStream_t stream) {
+  CDP_DISPATCH(dtype, hipLaunchKernelGGL((gap_fwd_kernel<T>), dim3(blocks_for((int64_t)B * C, 256, 4096)), dim3(256), 0, stream,
+                                         static_cast<const T*>(x), static_cast<T*>(y), B, HW, C));
+  return hipGetLastError();
+}
+hipError_t launch_gap_bwd(const void* x, const void* dy, void* dx, int B, int HW, int C, int mask_relu, int dtype,
+                          hipStream_t stream) {
+  CDP_DISPATCH(dtype, hipLaunchKernelGGL((gap_bwd_kernel<T>), dim3(blocks_for((int64_t)B * HW * C, 256, 65536)), dim3(256), 0,
+                                         stream, static_cast<const T*>(x), static_cast<const T*>(dy), static_cast<T*>(dx), B, HW,
+                                         C, mask_relu));
+  return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------------
+template <typename T>
+__global__ void to_f32_kernel(const T* __restrict__ src, float* __restrict__ dst, int64_t n) {
+  for (int64_t i = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x)
+    dst[i] = ld_f32<T>(src, i);
+}
+hipError_t launch_to_f32(const void* src, float* dst, int64_t n, int dtype, hipStream_t stream) {
+  if (n <= 0) return hipSuccess;
+  CDP_DISPATCH(dtype, hipLaunchKernelGGL((to_f32_kernel<T>), dim3(blocks_for(n, 256, 4096)), dim3(256), 0, stream,
+                                         static_cast<const T*>(src), dst, n));
+  return hipGetLastError();
+}
+__global__ void fill_f32_kernel(float* __restrict__ dst, int64_t n, float v) {
+  for (int64_t i = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x) dst[i] = v;
+}
+hipError_t launch_fill_f32(float* dst, int64_t n, float v, hipStream_t stream) {
+  if (n <= 0) return hipSuccess;
+  hipLaunchKernelGGL(fill_f32_kernel, dim3(blocks_for(n, 256, 4096)), dim3(256), 0, stream, dst, n, v);
+  return hipGetLastError();
+}
+
+}  // namespace cdp

@@ -1,0 +1,91 @@
+"""Kernel-level parity on the GPU: the tile contraction (every operand layout, tile shape
+and dtype, ragged sizes) and the implicit-GEMM convolution passes against the oracle."""
+import numpy as np
+import pytest
+
+import cdp_workloads as wl
+from oracle import layers as L
+from paper_2403_08837_amd import binding as b
+
+pytestmark = pytest.mark.gpu
+
+
+def _torch():
+    import torch
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    return torch
+
+
+def _dev(a, dtype):
+    torch = _torch()
+    t = torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).cuda()
+    return t.to(torch.bfloat16).contiguous() if dtype == wl.BF16 else t.contiguous()
+
+
+def _rnd(a, dtype):
+    return L.round_bf16(a) if dtype == wl.BF16 else np.asarray(a, dtype=np.float32).astype(np.float64)
+
+
+@pytest.mark.parametrize("dtype", [wl.F32, wl.BF16])
+@pytest.mark.parametrize("shape", [0, 1, 2])
+@pytest.mark.parametrize("a_k,b_k", [(1, 1), (0, 0), (1, 0), (0, 1)])
+@pytest.mark.parametrize("M,N,K", [(8, 64, 64), (64, 200, 136), (130, 257, 70), (333, 129, 515), (5, 7, 3)])
+def test_gemm_all_layouts(dtype, shape, a_k, b_k, M, N, K):
+    torch = _torch()
+    A = wl.random_normal(1, 10 * M + K, M * K).reshape(M, K)
+    Bm = wl.random_normal(2, 10 * N + K, N * K).reshape(N, K)
+    ref = _rnd(A, dtype) @ _rnd(Bm, dtype).T
+    Ad = _dev(A if a_k else A.T, dtype)
+    Bd = _dev(Bm if b_k else Bm.T, dtype)
+    Cd = torch.full((M, N), float("nan"), dtype=torch.float32, device="cuda")
+    b.cdp_k_gemm(dtype, shape, a_k, b_k, Ad.data_ptr(), Bd.data_ptr(), Cd.data_ptr(), M, N, K,
+                 K if a_k else M, K if b_k else N)
+    torch.cuda.synchronize()
+    got = Cd.cpu().numpy().astype(np.float64)
+    tol = 2e-5 * np.sqrt(K) * max(1.0, np.abs(ref).max())
+    assert np.isfinite(got).all()
+    assert np.abs(got - ref).max() <= tol, np.abs(got - ref).max()
+
+
+CONV_CASES = [
+    # B, H, W, Cin, Cout, ks, stride, pad
+    (2, 8, 8, 8, 16, 3, 1, 1),
+    (3, 9, 7, 16, 8, 3, 2, 1),
+    (2, 12, 12, 3, 8, 7, 2, 3),     # stem-like: Cin = 3 takes the element-wise gather path
+    (2, 8, 8, 3, 8, 3, 1, 1),
+    (4, 6, 6, 32, 64, 1, 1, 0),
+    (4, 6, 6, 32, 64, 1, 2, 0),
+    (2, 16, 16, 64, 64, 3, 1, 1),
+    (1, 5, 5, 24, 40, 3, 1, 1),     # channel counts that are multiples of 8 but not of the tile
+]
+
+
+@pytest.mark.parametrize("dtype", [wl.F32, wl.BF16])
+@pytest.mark.parametrize("case", CONV_CASES)
+def test_conv_passes_match_oracle(dtype, case):
+    torch = _torch()
+    B, H, W, Cin, Cout, ks, st, pad = case
+    x = wl.random_normal(3, 1, B * H * W * Cin).reshape(B, H, W, Cin)
+    w = wl.random_normal(3, 2, Cout * ks * ks * Cin).reshape(Cout, ks, ks, Cin) / np.sqrt(ks * ks * Cin)
+    xr, wr = _rnd(x, dtype), _rnd(w, dtype)
+    y = L.conv2d_fwd(xr, wr, st, pad)
+    dy = wl.random_normal(3, 3, y.size).reshape(y.shape)
+    dyr = _rnd(dy, dtype)
+    dx, dw = L.conv2d_bwd(xr, wr, st, pad, dyr)
+    tdt = torch.bfloat16 if dtype == wl.BF16 else torch.float32
+    tol_out = 2.0 ** -7 if dtype == wl.BF16 else 1e-5
+
+    xd, wd, dyd = _dev(x, dtype), _dev(w, dtype), _dev(dy, dtype)
+    yd = torch.full(y.shape, float("nan"), dtype=tdt, device="cuda")
+    b.cdp_k_conv(dtype, 0, xd.data_ptr(), wd.data_ptr(), yd.data_ptr(), B, H, W, Cin, Cout, ks, st, pad)
+    wtd = _dev(np.transpose(w, (3, 1, 2, 0)), dtype)        # [Cin][k][k][Cout]
+    dxd = torch.full(x.shape, float("nan"), dtype=tdt, device="cuda")
+    b.cdp_k_conv(dtype, 1, dyd.data_ptr(), wtd.data_ptr(), dxd.data_ptr(), B, H, W, Cin, Cout, ks, st, pad)
+    dwd = torch.full(w.shape, float("nan"), dtype=torch.float32, device="cuda")
+    b.cdp_k_conv(dtype, 2, dyd.data_ptr(), xd.data_ptr(), dwd.data_ptr(), B, H, W, Cin, Cout, ks, st, pad)
+    torch.cuda.synchronize()
+    for name, got, ref, tol in (("fwd", yd, y, tol_out), ("dgrad", dxd, dx, tol_out), ("wgrad", dwd, dw, 1e-5)):
+        g = got.float().cpu().numpy().astype(np.float64)
+        assert np.isfinite(g).all(), name
+        err = np.abs(g - ref).max() / max(1e-6, np.abs(ref).max())
+        assert err <= tol, (name, err)

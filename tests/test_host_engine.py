@@ -1,0 +1,118 @@
+"""Host logic of libcdp without a GPU: exported symbols, argument checking, and the
+dry-run scheduler / version ring / activation pool against the oracle's timeline."""
+import ctypes
+import os
+import re
+
+import pytest
+
+import cdp_workloads as wl
+from oracle import cdp_oracle as O
+from paper_2403_08837_amd import binding as b
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+RULES = [wl.RULE_DP, wl.RULE_V1, wl.RULE_V2]
+
+
+def test_library_exports_every_declared_symbol():
+    hdr = open(os.path.join(ROOT, "include", "cdp.h")).read() + open(os.path.join(ROOT, "include", "cdp_kernels.h")).read()
+    declared = set(re.findall(r"\b(cdp_[a-z_]+)\s*\(", hdr))
+    assert declared == set(b.EXPORTS), declared ^ set(b.EXPORTS)
+    L = ctypes.CDLL(b.LIB_PATH)
+    for name in declared:
+        assert hasattr(L, name), name
+
+
+def test_enum_values_match_workload_vocabulary():
+    hdr = open(os.path.join(ROOT, "include", "cdp.h")).read()
+    for name, val in [("CDP_LINEAR", wl.LINEAR), ("CDP_RELU", wl.RELU), ("CDP_CONV2D", wl.CONV2D), ("CDP_AFFINE", wl.AFFINE),
+                      ("CDP_ADD", wl.ADD), ("CDP_MAXPOOL", wl.MAXPOOL), ("CDP_GAP", wl.GAP), ("CDP_CE_HEAD", wl.CE_HEAD),
+                      ("CDP_RULE_DP", wl.RULE_DP), ("CDP_RULE_V1", wl.RULE_V1), ("CDP_RULE_V2", wl.RULE_V2),
+                      ("CDP_F32", wl.F32), ("CDP_BF16", wl.BF16)]:
+        assert re.search(r"\b%s = %d\b" % (name, val), hdr), name
+
+
+def _dry(cfg, rule, T):
+    tr = b.Trainer(cfg.stages, cfg.in_shape, cfg.N, cfg.B, cfg.lr, rule, cfg.dtype, dry_run=True)
+    for _ in range(T * 2 * cfg.S):
+        tr.tick_dry(True)
+    tr.drain()
+    return tr
+
+
+@pytest.mark.parametrize("name", ["mlp_mini", "mlp_odd", "cfg1", "cfg2", "cfg3", "cfg4", "cfg5", "resnet50_mini"])
+@pytest.mark.parametrize("rule", RULES)
+def test_trace_and_live_counts_equal_oracle(name, rule):
+    """Tick order and weight-version indexing must match the oracle exactly."""
+    cfg = wl.get_config(name)
+    T = 3
+    tr = _dry(cfg, rule, T)
+    r = O.train_schedule(cfg, None, [None] * T, [None] * T, rule, compute=False)
+    assert tr.trace() == r.trace
+    assert tr.live_counts() == r.live_inputs
+    st = tr.stats()
+    assert st["ticks_run"] == O.total_ticks(cfg.S, cfg.N, O.delay_for(cfg.S, cfg.N, rule), T)
+    assert st["peak_live_stage_inputs"] == max(r.live_inputs)
+    assert st["cur_activation_bytes"] == 0          # everything released after the drain
+    tr.close()
+
+
+def test_activation_pool_is_constant_and_below_dp():
+    """Sec. 4.1: activation memory stays (nearly) constant and about half of DP's."""
+    for name in ["cfg2", "cfg5"]:
+        cfg = wl.get_config(name)
+        cdp = _dry(cfg, wl.RULE_V2, 4).stats()
+        dp = _dry(cfg, wl.RULE_DP, 4).stats()
+        assert cdp["peak_live_stage_inputs"] == cfg.N * (cfg.S + 1) // 2
+        assert dp["peak_live_stage_inputs"] == cfg.N * cfg.S
+        assert cdp["peak_activation_bytes"] < 0.7 * dp["peak_activation_bytes"]
+        assert cdp["pool_span_bytes"] <= 1.01 * cdp["peak_activation_bytes"] + 4096
+
+
+def test_pool_span_stops_growing():
+    cfg = wl.get_config("cfg4")
+    a = _dry(cfg, wl.RULE_V2, 3).stats()["pool_span_bytes"]
+    c = _dry(cfg, wl.RULE_V2, 9).stats()["pool_span_bytes"]
+    assert a == c
+
+
+def test_argument_errors():
+    cfg = wl.get_config("mlp_mini")
+    o = b.make_opts(cfg.dtype, cfg.in_shape, dry_run=True)
+    with pytest.raises(b.CdpError) as e:          # N = 4 does not divide 2S = 6
+        b.cdp_init(cfg.stages, 4, cfg.B, 0.1, wl.RULE_V2, o)
+    assert e.value.code == b.CDP_EINVAL and "divide" in str(e.value)
+    with pytest.raises(b.CdpError):
+        b.cdp_init(cfg.stages, cfg.N, cfg.B, 0.1, 7, o)
+    bad = [list(s) for s in cfg.stages]
+    bad[0] = [wl.Layer(wl.RELU)] + bad[0]
+    with pytest.raises(b.CdpError) as e:
+        b.cdp_init(bad, cfg.N, cfg.B, 0.1, wl.RULE_V2, o)
+    assert "fused group" in str(e.value)
+    bad = [list(s) for s in cfg.stages]
+    bad[1] = [wl.Layer(wl.LINEAR, (17, 16)), wl.Layer(wl.RELU)]
+    with pytest.raises(b.CdpError) as e:
+        b.cdp_init(bad, cfg.N, cfg.B, 0.1, wl.RULE_V2, o)
+    assert "in_features" in str(e.value)
+    ctx = b.cdp_init(cfg.stages, cfg.N, cfg.B, 0.1, wl.RULE_V2, o)
+    with pytest.raises(b.CdpError) as e:
+        b.cdp_set_weights(ctx, 0, [0.0] * 3)
+    assert e.value.code == b.CDP_EINVAL
+    with pytest.raises(b.CdpError) as e:          # first micro-batch needs data
+        b.cdp_tick(ctx, 256, 0)
+    b.cdp_destroy(ctx)
+
+
+def test_drain_then_resume_restarts_cycle():
+    cfg = wl.get_config("mlp_mini")
+    tr = _dry(cfg, wl.RULE_V2, 2)
+    n0 = len(tr.trace())
+    for _ in range(2 * cfg.S):
+        tr.tick_dry(True)
+    tr.drain()
+    t = tr.trace()
+    assert len(t) == n0 + 2 * cfg.S * cfg.N
+    assert {rec[2] for rec in t[n0:]} == {2}
+    # after a drain every stage holds theta_2, so the resumed step reads version 2 everywhere
+    assert {rec[5] for rec in t[n0:]} == {2}
+    tr.close()
