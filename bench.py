@@ -1,0 +1,169 @@
+#!/usr/bin/env python3
+"""Throughput of the CDP hot path on one MI355X.
+
+A "step" is one training step of Cyclic Data Parallelism: 2S ticks, in which every one of
+the N micro-batches of a mini-batch runs the forward and backward of every stage with the
+weight versions of the chosen update rule, all N gradients are accumulated per stage and
+every stage is updated once (Eq. (CDP), Sec. 3.2).  Inputs are synthetic (N(0,1) features,
+uniform labels) and already resident in HBM when the timed region starts.
+
+Prints ONE JSON line.  `--gpus` above 1 is refused: this build runs on one GPU.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+import cdp_workloads as wl  # noqa: E402
+
+HBM_PEAK_GBS = 8000.0           # MI355X HBM3E
+MFMA_PEAK_TFLOPS = {wl.BF16: 2500.0, wl.F32: 157.3}
+WORKLOAD_TEXT = {
+    "cfg1": "Tiny MLP: 4 stages Linear(64->64)+ReLU + 10-class head, N=4 micro-batches of 8, fp32",
+    "cfg2": "CIFAR-shaped MLP: 3072->1024 stem, 8 stages Linear(1024->1024)+ReLU, 10-class head, N=8 micro-batches of 32, bf16",
+    "cfg3": "CIFAR-shaped ResNet-18: 8 BasicBlock stages, N=4 micro-batches of 32, bf16",
+    "cfg4": "ImageNet-shaped ResNet-50: 16 bottleneck stages, N=8 micro-batches of 32, bf16",
+    "cfg5": "Deep wide MLP: 24 stages Linear(4096->4096)+ReLU, 1000-class head, N=16 micro-batches of 64, bf16",
+}
+
+
+def gpu_run(cfg, rule, steps, warmup, n_batches=4):
+    import torch
+    from paper_2403_08837_amd import binding as b
+
+    if not torch.cuda.is_available():
+        raise SystemExit("bench.py needs a GPU; libcdp has no CPU path")
+    tr = b.Trainer(cfg.stages, cfg.in_shape, cfg.N, cfg.B, cfg.lr, rule, cfg.dtype)
+    tr.set_weights(wl.init_params(cfg, 0))
+    data = []
+    for t in range(n_batches):
+        x, y = wl.make_batch(cfg, t, 0)
+        data.append((torch.from_numpy(x).cuda(), torch.from_numpy(y).cuda()))
+    torch.cuda.synchronize()
+    # warm-up: fills the cycle (the first d*(N-1) ticks run fewer than N micro-batches)
+    for t in range(max(warmup, 1)):
+        tr.step(*data[t % n_batches])
+    torch.cuda.synchronize()
+    tr.profile_gemm(True)
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    ev0.record()
+    for t in range(steps):
+        tr.step(*data[(warmup + t) % n_batches])
+    ev1.record()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    gpu_ms = ev0.elapsed_time(ev1)
+    prof = tr.gemm_profile()
+    tr.profile_gemm(False)
+    tr.drain()
+    torch.cuda.synchronize()
+    stats = tr.stats()
+    losses = tr.losses(max(warmup, 1) + steps - 1)
+    tr.close()
+    return dict(wall=wall, gpu_ms=gpu_ms, prof=prof, stats=stats, last_losses=[float(v) for v in losses])
+
+
+def cpu_baseline(cfg, rule, budget_s=15.0):
+    """The oracle as it stands, timed on this host on a bounded number of steps of the same
+    workload (fp64 numpy; it is a reported baseline, never a target)."""
+    from oracle import cdp_oracle as O
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [os.cpu_count() or 1])
+    except Exception:
+        cores = os.cpu_count() or 1
+    p0 = wl.init_params(cfg, 0)
+    xs, ys = wl.make_data(cfg, 1, 0)
+    t0 = time.perf_counter()
+    O.train_schedule(cfg, p0, xs, ys, rule, keep_versions=False)
+    one = time.perf_counter() - t0
+    steps = int(max(1, min(16, budget_s // max(one, 1e-3))))
+    if steps > 1:
+        xs, ys = wl.make_data(cfg, steps, 0)
+        t0 = time.perf_counter()
+        O.train_schedule(cfg, p0, xs, ys, rule, keep_versions=False)
+        total = time.perf_counter() - t0
+    else:
+        total = one
+    return {"value": cfg.N * cfg.B * steps / total, "unit": "samples/s", "cores": int(cores), "kind": "oracle",
+            "sample": "%d full training step(s) of the same workload and rule, fp64 numpy timeline oracle, %.1f s" % (steps, total)}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=None)
+    ap.add_argument("--warmup", type=int, default=None)
+    ap.add_argument("--workload", default="cfg2", choices=sorted(WORKLOAD_TEXT))
+    ap.add_argument("--rule", default="v2", choices=["dp", "v1", "v2"])
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        raise SystemExit("bench.py: this build runs the CDP hot path on ONE GPU; --gpus %d is not supported "
+                         "(no collectives or sharding are part of it)" % args.gpus)
+    cfg = wl.get_config(args.workload)
+    rule = {"dp": wl.RULE_DP, "v1": wl.RULE_V1, "v2": wl.RULE_V2}[args.rule]
+    default_steps = {"cfg1": 200, "cfg2": 200, "cfg3": 20, "cfg4": 5, "cfg5": 20}[args.workload]
+    steps = args.steps if args.steps is not None else default_steps
+    warmup = args.warmup if args.warmup is not None else 3
+    r = gpu_run(cfg, rule, steps, warmup)
+    samples = cfg.N * cfg.B * steps
+    prof = r["prof"]
+    sec = prof["total_ms"] * 1e-3
+    ai = prof["flops"] / max(prof["bytes"], 1.0)
+    ridge = MFMA_PEAK_TFLOPS[cfg.dtype] * 1e12 / (HBM_PEAK_GBS * 1e9)
+    if ai < ridge:
+        roof = {"bound": "hbm", "achieved": prof["bytes"] / sec / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s"}
+    else:
+        roof = {"bound": "mfma", "achieved": prof["flops"] / sec / 1e12, "peak": MFMA_PEAK_TFLOPS[cfg.dtype], "unit": "TFLOP/s"}
+    roof["frac"] = roof["achieved"] / roof["peak"]
+    roof["traffic"] = None
+    roof["kernel"] = "gemm_grouped_kernel"
+    roof["launches"] = prof["launches"]
+    roof["avg_launch_us"] = prof["total_ms"] * 1e3 / max(1, prof["launches"])
+    roof["algorithmic_bytes_per_launch"] = prof["bytes"] / max(1, prof["launches"])
+    roof["algorithmic_flops_per_launch"] = prof["flops"] / max(1, prof["launches"])
+    roof["arithmetic_intensity_flop_per_byte"] = ai
+    roof["mfma_tflops"] = prof["flops"] / sec / 1e12
+    roof["mfma_frac"] = roof["mfma_tflops"] / MFMA_PEAK_TFLOPS[cfg.dtype]
+    roof["gemm_time_share"] = prof["total_ms"] / r["gpu_ms"]
+    out = {
+        "metric": "CDP training samples/sec on 1 MI355X",
+        "value": samples / r["wall"],
+        "unit": "samples/s",
+        "n_gpus": 1,
+        "steps": steps,
+        "warmup": warmup,
+        "ms_per_step": r["wall"] * 1e3 / steps,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "bf16" if cfg.dtype == wl.BF16 else "f32",
+        "data": "synthetic",
+        "config": {"workload": "%s: %s" % (args.workload, WORKLOAD_TEXT[args.workload]), "rule": wl.RULE_NAMES[rule],
+                   "S": cfg.S, "N": cfg.N, "B": cfg.B, "delay_ticks": cfg.delay if rule != wl.RULE_DP else 0},
+        "gpu_ms_per_step": r["gpu_ms"] / steps,
+        "peak_activation_bytes": r["stats"]["peak_activation_bytes"],
+        "dp_activation_bytes": r["stats"]["dp_activation_bytes"],
+        "peak_live_stage_inputs": r["stats"]["peak_live_stage_inputs"],
+        "kernel_launches_per_step": r["stats"]["kernel_launches"] / max(1, r["stats"]["steps_enqueued"]),
+        "last_step_mean_loss": float(np.mean(r["last_losses"])),
+        "roofline": roof,
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(cfg, rule)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -156,6 +156,23 @@ int cdp_get_live_counts(const cdp_ctx* ctx, int32_t* out, size_t cap, size_t* n_
 
 int cdp_get_stats(const cdp_ctx* ctx, cdp_stats* out);
 
+/* Timing of the grouped contraction launches, the dominant kernel of a tick (forward,
+ * data-gradient and weight-gradient tiles of all active (micro-batch, stage) pairs).
+ * While enabled, every such launch is bracketed by two HIP events on the work stream.
+ * flops / bytes are the algorithmic work of the timed launches: 2 * multiply-adds of each
+ * contraction; bytes with every operand read once and every result written once. */
+typedef struct {
+  int64_t launches;
+  double total_ms;   /* sum of per-launch durations */
+  double flops;
+  double bytes;
+} cdp_gemm_profile;
+
+/* enable != 0 starts a fresh measurement, 0 stops recording (synchronises). */
+int cdp_profile_gemm(cdp_ctx* ctx, int enable);
+/* Sums over the launches recorded since the last cdp_profile_gemm (synchronises). */
+int cdp_get_gemm_profile(cdp_ctx* ctx, cdp_gemm_profile* out);
+
 /* Text of the last error on this context (or of the last failed cdp_init /
  * cdp_arena_bytes when ctx is NULL).  Never NULL. */
 const char* cdp_last_error(const cdp_ctx* ctx);

@@ -137,13 +137,14 @@ def train_equation(cfg: wl.Config, params0, xs: Sequence[np.ndarray], ys: Sequen
 def train_schedule(cfg: wl.Config, params0, xs: Sequence[np.ndarray], ys: Sequence[np.ndarray],
                    rule: int, lr: Optional[float] = None,
                    rnd: Callable[[np.ndarray], np.ndarray] = L.identity,
-                   compute: bool = True) -> Result:
+                   compute: bool = True, keep_versions: bool = True) -> Result:
     """Per tick: every active micro-batch runs one stage forward or backward with the
     weight version the rule assigns (forward) or the one its own forward used
     (backward); a backward adds its gradient to the stage accumulator; at the end of
     the tick every stage holding N gradients is updated into the other ring slot and
     the new version becomes visible from the next tick.  ``compute=False`` runs the
-    integer bookkeeping only (trace, versions, live counts)."""
+    integer bookkeeping only (trace, versions, live counts); ``keep_versions=False`` does
+    not retain superseded weight versions (large models)."""
     S, N, B = cfg.S, cfg.N, cfg.B
     lr = cfg.lr if lr is None else lr
     d = delay_for(S, N, rule)
@@ -158,7 +159,7 @@ def train_schedule(cfg: wl.Config, params0, xs: Sequence[np.ndarray], ys: Sequen
     saved: Dict[Tuple[int, int, int], object] = {}
     carry: Dict[Tuple[int, int], object] = {}    # (t, i) -> activation / gradient travelling between stages
     res = Result(params=[], losses=np.zeros((T, N)))
-    if compute:
+    if compute and keep_versions:
         for j in range(S):
             res.versions[(j, 0)] = ring[j][0]
     for tick in range(total_ticks(S, N, d, T)):
@@ -210,7 +211,8 @@ def train_schedule(cfg: wl.Config, params0, xs: Sequence[np.ndarray], ys: Sequen
                     ring[j][new % 2] = [w - (lr / N) * g for w, g in zip(ring[j][ver[j] % 2], G[j])]
                     for a in G[j]:
                         a[...] = 0.0
-                    res.versions[(j, new)] = ring[j][new % 2]
+                    if keep_versions:
+                        res.versions[(j, new)] = ring[j][new % 2]
                 ring_ver[j][new % 2] = new
                 ver[j] = new
                 cnt[j] = 0

@@ -21,7 +21,8 @@ CDP_F32, CDP_BF16 = 0, 1
 
 EXPORTS = ["cdp_arena_bytes", "cdp_init", "cdp_set_weights", "cdp_param_count", "cdp_tick", "cdp_step",
            "cdp_drain", "cdp_get_weights", "cdp_get_losses", "cdp_get_trace", "cdp_get_live_counts",
-           "cdp_get_stats", "cdp_last_error", "cdp_destroy", "cdp_k_gemm", "cdp_k_conv"]
+           "cdp_get_stats", "cdp_last_error", "cdp_destroy", "cdp_profile_gemm", "cdp_get_gemm_profile",
+           "cdp_k_gemm", "cdp_k_conv"]
 
 
 class cdp_layer_desc(C.Structure):
@@ -45,6 +46,10 @@ class cdp_stats(C.Structure):
     _fields_ = [(n, C.c_int64) for n in (
         "ticks_run", "steps_enqueued", "peak_live_stage_inputs", "last_live_stage_inputs", "peak_activation_bytes",
         "cur_activation_bytes", "pool_span_bytes", "dp_activation_bytes", "weight_bytes", "kernel_launches")]
+
+
+class cdp_gemm_profile(C.Structure):
+    _fields_ = [("launches", C.c_int64), ("total_ms", C.c_double), ("flops", C.c_double), ("bytes", C.c_double)]
 
 
 class CdpError(RuntimeError):
@@ -80,6 +85,8 @@ def lib() -> C.CDLL:
         L.cdp_last_error.restype = C.c_char_p
         L.cdp_destroy.argtypes = [vp]
         L.cdp_destroy.restype = None
+        L.cdp_profile_gemm.argtypes = [vp, i32]
+        L.cdp_get_gemm_profile.argtypes = [vp, C.POINTER(cdp_gemm_profile)]
         L.cdp_k_gemm.argtypes = [i32, i32, i32, i32, vp, vp, vp, i32, i32, i32, i32, i32, vp]
         L.cdp_k_conv.argtypes = [i32, i32, vp, vp, vp, i32, i32, i32, i32, i32, i32, i32, i32, vp]
         for name in EXPORTS:
@@ -194,6 +201,16 @@ def cdp_get_stats(ctx) -> dict:
     return {n: int(getattr(s, n)) for n, _ in cdp_stats._fields_}
 
 
+def cdp_profile_gemm(ctx, enable: bool) -> None:
+    _check(lib().cdp_profile_gemm(ctx, int(bool(enable))), ctx)
+
+
+def cdp_get_gemm_profile(ctx) -> dict:
+    p = cdp_gemm_profile()
+    _check(lib().cdp_get_gemm_profile(ctx, C.byref(p)), ctx)
+    return dict(launches=int(p.launches), total_ms=float(p.total_ms), flops=float(p.flops), bytes=float(p.bytes))
+
+
 def cdp_destroy(ctx) -> None:
     lib().cdp_destroy(ctx)
 
@@ -264,6 +281,12 @@ class Trainer:
 
     def stats(self) -> dict:
         return cdp_get_stats(self.ctx)
+
+    def profile_gemm(self, enable: bool) -> None:
+        cdp_profile_gemm(self.ctx, enable)
+
+    def gemm_profile(self) -> dict:
+        return cdp_get_gemm_profile(self.ctx)
 
     def close(self) -> None:
         if self.ctx is not None:

@@ -89,6 +89,7 @@ struct Item {
   const void* p0 = nullptr; const void* p1 = nullptr; void* p2 = nullptr; void* p3 = nullptr;
   int64_t n0 = 0;
   int i[10] = {0};
+  double flops = 0, bytes = 0;  // algorithmic work (contractions only)
 };
 typedef std::vector<std::vector<Item>> Program;
 
@@ -116,6 +117,11 @@ struct cdp_ctx {
   cdp_stats stats;
   int64_t in_features = 0;                    // per-sample input elements
   std::string err;
+  // optional timing of the grouped contraction launches (HIP events on the work stream)
+  bool profiling = false;
+  struct ProfRec { hipEvent_t a, b; double flops, bytes; };
+  std::vector<ProfRec> prof;
+  std::vector<hipEvent_t> event_pool;
 
   void* ptr(int64_t off) const { return reinterpret_cast<void*>(reinterpret_cast<uintptr_t>(arena) + (uintptr_t)off); }
   float* fptr(int64_t off) const { return static_cast<float*>(ptr(off)); }
@@ -245,6 +251,19 @@ GemmProb wgrad_prob(const cdp_ctx* c, const Op& o, const void* dz, const void* x
   return p;
 }
 
+// Algorithmic work of one contraction of a layer: 2 * multiply-adds as the layer defines
+// them (the same count for forward, data gradient and weight gradient), and bytes with
+// every operand read once and the result written once (a read-modify-write counts twice).
+void op_work(const cdp_ctx* c, const Op& o, int pass, bool rmw, bool extra_in, Item* it) {
+  const double eb = c->plan.elem_bytes;
+  const double rows = (double)c->B * o.Hout * o.Wout;
+  const double x = (double)c->B * o.Hin * o.Win * o.Cin, y = rows * o.Cout, w = (double)o.w_count();
+  it->flops = 2.0 * rows * o.Cout * (double)o.K();
+  if (pass == 0) it->bytes = x * eb + w * eb + y * (o.out_f32 ? 4 : eb) + (o.res >= 0 ? y * eb : 0);
+  else if (pass == 1) it->bytes = y * eb + w * eb + x * eb * (rmw ? 2 : 1) + (extra_in ? x * eb : 0);
+  else it->bytes = y * eb + x * eb + w * 4 * (rmw ? 2 : 1) + (o.has_gamma ? w * eb : 0);
+}
+
 int pick_tile(const GemmProb& p) {
   if (p.M <= 64) return p.N >= 128 ? TILE_64x128 : TILE_64x64;
   if (p.N <= 64) return TILE_64x64;
@@ -279,6 +298,7 @@ int build_forward(cdp_ctx* c, int i, int64_t t, int j, int version, const float*
     if (o.kind == OPK_GEMM) {
       it.kind = IT_GEMM;
       it.g = fwd_prob(c, o, c->ptr(r.t[o.in].off), c->ptr(r.t[o.out].off), slot, o.res >= 0 ? c->ptr(r.t[o.res].off) : nullptr);
+      op_work(c, o, 0, false, false, &it);
     } else if (o.kind == OPK_MAXPOOL) {
       it.kind = IT_MAXPOOL_F;
       it.p0 = c->ptr(r.t[o.in].off); it.p2 = c->ptr(r.t[o.out].off);
@@ -361,10 +381,12 @@ int build_backward(cdp_ctx* c, int i, int j, Program* prog, bool first_grad) {
       if (need_dx) {
         Item it; it.kind = IT_GEMM;
         it.g = dgrad_prob(c, o, dz, dx, slot, accumulate ? nullptr : addend[o.in], mask, accumulate);
+        op_work(c, o, 1, accumulate, mask != nullptr, &it);
         at(level).push_back(it);
       }
       Item w; w.kind = IT_GEMM;
       w.g = wgrad_prob(c, o, dz, xin, slot, G, first_grad);
+      op_work(c, o, 2, o.is_conv || !first_grad, false, &w);
       at(level).push_back(w);
       if (o.b_off >= 0) {
         Item b; b.kind = IT_COLSUM;
@@ -404,16 +426,31 @@ int build_backward(cdp_ctx* c, int i, int j, Program* prog, bool first_grad) {
 int launch_level(cdp_ctx* c, std::vector<Item>& items) {
   // grouped contractions, one launch per tile shape (and per GEMM_MAX_PROBS problems)
   for (int shape = 0; shape < TILE_COUNT; ++shape) {
-    std::vector<const GemmProb*> sel;
+    std::vector<const Item*> sel;
     for (const Item& it : items)
-      if (it.kind == IT_GEMM && pick_tile(it.g) == shape) sel.push_back(&it.g);
+      if (it.kind == IT_GEMM && pick_tile(it.g) == shape) sel.push_back(&it);
     // longest reductions first so the tail of the launch is made of short tiles
-    std::stable_sort(sel.begin(), sel.end(), [](const GemmProb* a, const GemmProb* b) { return a->K / a->splits > b->K / b->splits; });
+    std::stable_sort(sel.begin(), sel.end(),
+                     [](const Item* a, const Item* b) { return a->g.K / a->g.splits > b->g.K / b->g.splits; });
     for (size_t k = 0; k < sel.size(); k += GEMM_MAX_PROBS) {
       GemmBatch batch;
       batch.n = (int)std::min<size_t>(GEMM_MAX_PROBS, sel.size() - k);
-      for (int q = 0; q < batch.n; ++q) batch.p[q] = *sel[k + q];
+      for (int q = 0; q < batch.n; ++q) batch.p[q] = sel[k + q]->g;
+      cdp_ctx::ProfRec pr{nullptr, nullptr, 0, 0};
+      const bool timed = c->profiling && c->prof.size() < (1u << 18);
+      if (timed) {
+        for (hipEvent_t* e : {&pr.a, &pr.b}) {
+          if (!c->event_pool.empty()) { *e = c->event_pool.back(); c->event_pool.pop_back(); }
+          else HIP_TRY(c, hipEventCreate(e));
+        }
+        for (int q = 0; q < batch.n; ++q) { pr.flops += sel[k + q]->flops; pr.bytes += sel[k + q]->bytes; }
+        HIP_TRY(c, hipEventRecord(pr.a, c->stream));
+      }
       HIP_TRY(c, launch_gemm_batch(batch, c->plan.dtype, shape, c->stream));
+      if (timed) {
+        HIP_TRY(c, hipEventRecord(pr.b, c->stream));
+        c->prof.push_back(pr);
+      }
       c->stats.kernel_launches++;
     }
   }
@@ -829,8 +866,38 @@ int cdp_get_stats(const cdp_ctx* c, cdp_stats* out) {
   return CDP_OK;
 }
 
+int cdp_profile_gemm(cdp_ctx* c, int enable) {
+  if (!c) return fail(nullptr, CDP_EINVAL, "ctx is NULL");
+  if (c->dry) return fail(c, CDP_ESTATE, "nothing to time in a dry run");
+  HIP_TRY(c, hipStreamSynchronize(c->stream));
+  for (auto& r : c->prof) { c->event_pool.push_back(r.a); c->event_pool.push_back(r.b); }
+  c->prof.clear();
+  c->profiling = enable != 0;
+  return CDP_OK;
+}
+
+int cdp_get_gemm_profile(cdp_ctx* c, cdp_gemm_profile* out) {
+  if (!c || !out) return fail(c, CDP_EINVAL, "bad argument");
+  HIP_TRY(c, hipStreamSynchronize(c->stream));
+  memset(out, 0, sizeof(*out));
+  for (auto& r : c->prof) {
+    float ms = 0.f;
+    HIP_TRY(c, hipEventElapsedTime(&ms, r.a, r.b));
+    out->launches++;
+    out->total_ms += ms;
+    out->flops += r.flops;
+    out->bytes += r.bytes;
+  }
+  return CDP_OK;
+}
+
 const char* cdp_last_error(const cdp_ctx* c) { return c ? c->err.c_str() : g_last_error.c_str(); }
 
-void cdp_destroy(cdp_ctx* c) { delete c; }
+void cdp_destroy(cdp_ctx* c) {
+  if (!c) return;
+  for (auto& r : c->prof) { (void)hipEventDestroy(r.a); (void)hipEventDestroy(r.b); }
+  for (hipEvent_t e : c->event_pool) (void)hipEventDestroy(e);
+  delete c;
+}
 
 }  // extern "C"
