@@ -86,7 +86,7 @@ struct Item {
   int kind;
   GemmProb g;
   ColsumProb c;
-  const void* p0 = nullptr; const void* p1 = nullptr; void* p2 = nullptr; void* p3 = nullptr;
+  const void* p0 = nullptr; const void* p1 = nullptr; void* p2 = nullptr; void* p3 = nullptr; void* p4 = nullptr;
   int64_t n0 = 0;
   int i[10] = {0};
   double flops = 0, bytes = 0;  // algorithmic work (contractions only)
@@ -247,6 +247,7 @@ GemmProb wgrad_prob(const cdp_ctx* c, const Op& o, const void* dz, const void* x
     if (o.has_gamma) { p.aux0 = slot + o.gamma_c; p.aux1 = slot + o.wp; p.aux2 = G + o.g_off; }
   } else {
     p.flags = first ? 0 : GF_ACCUM;
+    if (o.b_off >= 0) p.aux2 = G + o.b_off;  // bias gradient is folded into the weight-gradient kernel
   }
   return p;
 }
@@ -264,10 +265,20 @@ void op_work(const cdp_ctx* c, const Op& o, int pass, bool rmw, bool extra_in, I
   else it->bytes = y * eb + x * eb + w * 4 * (rmw ? 2 : 1) + (o.has_gamma ? w * eb : 0);
 }
 
-int pick_tile(const GemmProb& p) {
-  if (p.M <= 64) return p.N >= 128 ? TILE_64x128 : TILE_64x64;
-  if (p.N <= 64) return TILE_64x64;
-  return TILE_128x128;
+// Launch class of a contraction: which kernel family and tile shape runs it.
+enum LaunchClass { LC_SKINNY_64 = 0, LC_SKINNY_128, LC_LINEAR_DW, LC_GEN_FIRST };  // LC_GEN_FIRST + 2*shape + wgrad
+
+int launch_class(const GemmProb& p, int dtype) {
+  const int vec = dtype == DT_BF16 ? 8 : 4;
+  if (p.epi != EPI_WGRAD && p.a_mode == OP_PLAIN_K && p.b_mode == OP_PLAIN_K && p.M <= 128 && p.K % vec == 0 &&
+      p.lda % vec == 0 && p.ldb % vec == 0)
+    return p.N >= 2048 ? LC_SKINNY_128 : LC_SKINNY_64;
+  if (p.epi == EPI_WGRAD && p.a_mode == OP_PLAIN_R && p.b_mode == OP_PLAIN_R && !(p.flags & GF_ATOMIC) && !p.aux0 && !p.aux1)
+    return LC_LINEAR_DW;
+  int shape;
+  if (p.M <= 64) shape = p.N >= 128 ? TILE_64x128 : TILE_64x64;
+  else shape = p.N <= 64 ? TILE_64x64 : TILE_128x128;
+  return LC_GEN_FIRST + 2 * shape + (p.epi == EPI_WGRAD ? 1 : 0);
 }
 
 // --------------------------------------------------------------------------- programs
@@ -286,6 +297,7 @@ int build_forward(cdp_ctx* c, int i, int64_t t, int j, int version, const float*
     it.p1 = y_dev + (int64_t)i * c->B;
     it.p2 = c->ptr(r.t[0].off);
     it.p3 = static_cast<int32_t*>(c->ptr(c->labels_off)) + (int64_t)i * c->B;
+    it.p4 = c->fptr(c->loss_off) + (t % LOSS_LOG_STEPS) * c->N + i;
     it.i[0] = c->B; it.n0 = c->in_features;
     at(level++).push_back(it);
   } else {
@@ -388,7 +400,7 @@ int build_backward(cdp_ctx* c, int i, int j, Program* prog, bool first_grad) {
       w.g = wgrad_prob(c, o, dz, xin, slot, G, first_grad);
       op_work(c, o, 2, o.is_conv || !first_grad, false, &w);
       at(level).push_back(w);
-      if (o.b_off >= 0) {
+      if (o.b_off >= 0 && o.is_conv) {
         Item b; b.kind = IT_COLSUM;
         b.c.src = dz; b.c.out = G + o.b_off; b.c.rows = c->B * o.Hout * o.Wout; b.c.cols = o.Cout; b.c.ld = o.Cout;
         at(level).push_back(b);
@@ -425,10 +437,10 @@ int build_backward(cdp_ctx* c, int i, int j, Program* prog, bool first_grad) {
 // --------------------------------------------------------------------------- launching
 int launch_level(cdp_ctx* c, std::vector<Item>& items) {
   // grouped contractions, one launch per tile shape (and per GEMM_MAX_PROBS problems)
-  for (int shape = 0; shape < TILE_COUNT; ++shape) {
+  for (int key = 0; key < LC_GEN_FIRST + 2 * TILE_COUNT; ++key) {
     std::vector<const Item*> sel;
     for (const Item& it : items)
-      if (it.kind == IT_GEMM && pick_tile(it.g) == shape) sel.push_back(&it);
+      if (it.kind == IT_GEMM && launch_class(it.g, c->plan.dtype) == key) sel.push_back(&it);
     // longest reductions first so the tail of the launch is made of short tiles
     std::stable_sort(sel.begin(), sel.end(),
                      [](const Item* a, const Item* b) { return a->g.K / a->g.splits > b->g.K / b->g.splits; });
@@ -446,7 +458,9 @@ int launch_level(cdp_ctx* c, std::vector<Item>& items) {
         for (int q = 0; q < batch.n; ++q) { pr.flops += sel[k + q]->flops; pr.bytes += sel[k + q]->bytes; }
         HIP_TRY(c, hipEventRecord(pr.a, c->stream));
       }
-      HIP_TRY(c, launch_gemm_batch(batch, c->plan.dtype, shape, c->stream));
+      if (key == LC_SKINNY_64 || key == LC_SKINNY_128) HIP_TRY(c, launch_linear_skinny(batch, c->plan.dtype, key == LC_SKINNY_128, c->stream));
+      else if (key == LC_LINEAR_DW) HIP_TRY(c, launch_linear_dw(batch, c->plan.dtype, c->stream));
+      else HIP_TRY(c, launch_gemm_batch(batch, c->plan.dtype, (key - LC_GEN_FIRST) / 2, c->stream));
       if (timed) {
         HIP_TRY(c, hipEventRecord(pr.b, c->stream));
         c->prof.push_back(pr);
@@ -474,7 +488,7 @@ int launch_level(cdp_ctx* c, std::vector<Item>& items) {
     switch (it.kind) {
       case IT_STAGE_IN:
         HIP_TRY(c, launch_stage_input(static_cast<const float*>(it.p0), static_cast<const int32_t*>(it.p1), it.p2,
-                                      static_cast<int32_t*>(it.p3), it.i[0], it.n0, dt, c->stream));
+                                      static_cast<int32_t*>(it.p3), static_cast<float*>(it.p4), it.i[0], it.n0, dt, c->stream));
         break;
       case IT_CE:
         HIP_TRY(c, launch_ce_head(static_cast<const float*>(it.p0), static_cast<const int32_t*>(it.p1), it.p2,

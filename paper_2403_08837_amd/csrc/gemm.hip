@@ -22,7 +22,6 @@ __device__ __forceinline__ uint16_t f32_to_bf16_bits(float f) {
 template <typename T> struct Elem;
 template <> struct Elem<uint16_t> {
   static constexpr int VEC = 8;     // elements per 16-byte chunk
-  static constexpr int BK = 32;     // reduction elements per LDS tile
   static constexpr int MFMA_K = 16; // reduction elements per MFMA
   static constexpr int KPL = 8;     // reduction elements per lane per MFMA
   __device__ static __forceinline__ float to_f32(uint16_t v) { return bf16_bits_to_f32(v); }
@@ -30,7 +29,6 @@ template <> struct Elem<uint16_t> {
 };
 template <> struct Elem<float> {
   static constexpr int VEC = 4;
-  static constexpr int BK = 16;
   static constexpr int MFMA_K = 2;
   static constexpr int KPL = 1;
   __device__ static __forceinline__ float to_f32(float v) { return v; }
@@ -104,10 +102,9 @@ __device__ __forceinline__ bool operand_vec_ok(int mode, int ld, const ConvGeom&
   return (g.C % VEC) == 0;
 }
 
-template <typename T, int ROWS>
+template <typename T, int ROWS, int BK>
 struct TileLoader {
   static constexpr int VEC = Elem<T>::VEC;
-  static constexpr int BK = Elem<T>::BK;
   static constexpr int LDP = BK + VEC;  // padded LDS pitch (elements)
   static constexpr int NCH = ROWS * BK / VEC / 256;
   static_assert(NCH >= 1, "tile too small for 256 threads");
@@ -169,10 +166,14 @@ __device__ __forceinline__ v16f mfma_step<float>(const float* a, const float* b,
   return __builtin_amdgcn_mfma_f32_32x32x2f32(*a, *b, acc, 0, 0, 0);
 }
 
-template <typename T, int BM, int BN, int WAVES_M>
+// EPIG selects the epilogue family at compile time: 0 = forward / data gradient (stores
+// activations), 1 = weight gradient (accumulates into the fp32 gradient buffer; the old
+// values of a non-atomic accumulate are fetched before the contraction starts so that
+// their latency overlaps it).
+template <typename T, int BM, int BN, int BK, int WAVES_M, int EPIG>
 __global__ __launch_bounds__(256) void gemm_grouped_kernel(const GemmBatch batch) {
   using E = Elem<T>;
-  constexpr int BK = E::BK, VEC = E::VEC, LDP = BK + VEC;
+  constexpr int VEC = E::VEC, LDP = BK + VEC;
   constexpr int WAVES_N = 4 / WAVES_M;
   constexpr int WTM = BM / WAVES_M, WTN = BN / WAVES_N;
   constexpr int MI = WTM / 32, NI = WTN / 32;
@@ -206,8 +207,8 @@ __global__ __launch_bounds__(256) void gemm_grouped_kernel(const GemmBatch batch
   const bool b_vec = operand_vec_ok<T>(P.b_mode, P.ldb, P.g);
   (void)a_gather;
 
-  TileLoader<T, BM> la;
-  TileLoader<T, BN> lb;
+  TileLoader<T, BM, BK> la;
+  TileLoader<T, BN, BK> lb;
   v16f acc[MI][NI];
 #pragma unroll
   for (int i = 0; i < MI; ++i)
@@ -218,6 +219,24 @@ __global__ __launch_bounds__(256) void gemm_grouped_kernel(const GemmBatch batch
 
   la.fetch(Ap, P.a_mode, P.lda, P.g, P.M, P.K, row0, kt0 * BK, a_vec, tid);
   lb.fetch(Bp, P.b_mode, P.ldb, P.g, P.N, P.K, col0, kt0 * BK, b_vec, tid);
+
+  const int flags = P.flags;
+  constexpr int NOLD = (EPIG == 1) ? MI * NI * 16 : 1;
+  float gold[NOLD];
+  const bool rmw = (EPIG == 1) && (flags & GF_ACCUM) && !(flags & GF_ATOMIC);
+  if constexpr (EPIG == 1) {
+#pragma unroll
+    for (int i = 0; i < MI; ++i)
+#pragma unroll
+      for (int j = 0; j < NI; ++j)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          const int r = row0 + wm * WTM + i * 32 + (v >> 2) * 8 + (lane >> 5) * 4 + (v & 3);
+          const int c = col0 + wn * WTN + j * 32 + (lane & 31);
+          gold[(i * NI + j) * 16 + v] = (rmw && r < P.M && c < P.N) ? static_cast<const float*>(P.out)[(int64_t)r * P.ldo + c] : 0.f;
+        }
+  }
+
   for (int kt = kt0; kt < kt1; ++kt) {
     __syncthreads();  // previous tile fully consumed
     la.store(As, P.a_mode, tid);
@@ -243,7 +262,6 @@ __global__ __launch_bounds__(256) void gemm_grouped_kernel(const GemmBatch batch
   }
 
   // ---- epilogue.  acc[i][j][v]: row = 8*(v/4) + 4*(lane/32) + v%4, col = lane%32 of the 32x32 tile
-  const int flags = P.flags;
 #pragma unroll
   for (int i = 0; i < MI; ++i) {
 #pragma unroll
@@ -251,20 +269,20 @@ __global__ __launch_bounds__(256) void gemm_grouped_kernel(const GemmBatch batch
       const int r = row0 + wm * WTM + i * 32 + (v >> 2) * 8 + (lane >> 5) * 4 + (v & 3);
       float gsum = 0.f;
       float gam = 1.f;
-      if (P.epi == EPI_WGRAD && P.aux0 != nullptr && r < P.M) gam = static_cast<const float*>(P.aux0)[r];
+      if (EPIG == 1 && P.aux0 != nullptr && r < P.M) gam = static_cast<const float*>(P.aux0)[r];
 #pragma unroll
       for (int j = 0; j < NI; ++j) {
         const int c = col0 + wn * WTN + j * 32 + (lane & 31);
         if (r >= P.M || c >= P.N) continue;
         float val = acc[i][j][v];
         const int64_t o = (int64_t)r * P.ldo + c;
-        if (P.epi == EPI_FWD) {
+        if (EPIG == 0 && P.epi == EPI_FWD) {
           if (P.aux0) val += static_cast<const float*>(P.aux0)[c];
           if (P.aux1) val += E::to_f32(static_cast<const T*>(P.aux1)[o]);
           if (flags & GF_RELU) val = fmaxf(val, 0.f);
           if (flags & GF_OUT_F32) static_cast<float*>(P.out)[o] = val;
           else static_cast<T*>(P.out)[o] = E::from_f32(val);
-        } else if (P.epi == EPI_DGRAD) {
+        } else if (EPIG == 0) {  // EPI_DGRAD
           if (P.aux0) val += E::to_f32(static_cast<const T*>(P.aux0)[o]);
           if (flags & GF_ACCUM) val += E::to_f32(static_cast<T*>(P.out)[o]);
           if (P.aux1 && !(E::to_f32(static_cast<const T*>(P.aux1)[o]) > 0.f)) val = 0.f;
@@ -274,10 +292,10 @@ __global__ __launch_bounds__(256) void gemm_grouped_kernel(const GemmBatch batch
           float* G = static_cast<float*>(P.out) + o;
           const float gv = gam * val;
           if (flags & GF_ATOMIC) atomicAdd(G, gv);
-          else *G = (flags & GF_ACCUM) ? (*G + gv) : gv;
+          else *G = gold[(EPIG == 1) ? (i * NI + j) * 16 + v : 0] + gv;
         }
       }
-      if (P.epi == EPI_WGRAD && P.aux2 != nullptr) {  // d gamma[r] = sum_c acc[r][c] * Wplain[r][c]
+      if (EPIG == 1 && P.aux2 != nullptr) {  // d gamma[r] = sum_c acc[r][c] * Wplain[r][c]
 #pragma unroll
         for (int off = 16; off >= 1; off >>= 1) gsum += __shfl_xor(gsum, off, 64);
         if ((lane & 31) == 0 && r < P.M) atomicAdd(static_cast<float*>(P.aux2) + r, gsum);
@@ -294,13 +312,21 @@ void tile_dims(int shape, int* bm, int* bn) {
   }
 }
 
-template <typename T>
+// Reduction depth of one LDS slab per tile shape.  The 64-row shapes serve the small-
+// batch Linear contractions, which stream a weight matrix once (HBM-bound): a deep slab
+// keeps ~50 KB of loads in flight per workgroup.  The square shape serves convolutions
+// and weight gradients.
+template <typename T> struct SlabK;
+template <> struct SlabK<uint16_t> { static constexpr int BIG = 32, SKINNY = 128; };
+template <> struct SlabK<float> { static constexpr int BIG = 16, SKINNY = 64; };
+
+template <typename T, int EPIG>
 static hipError_t launch_typed(const GemmBatch& b, int shape, hipStream_t s) {
   dim3 grid(b.total_tiles), block(256);
   switch (shape) {
-    case TILE_128x128: hipLaunchKernelGGL((gemm_grouped_kernel<T, 128, 128, 2>), grid, block, 0, s, b); break;
-    case TILE_64x128: hipLaunchKernelGGL((gemm_grouped_kernel<T, 64, 128, 2>), grid, block, 0, s, b); break;
-    default: hipLaunchKernelGGL((gemm_grouped_kernel<T, 64, 64, 2>), grid, block, 0, s, b); break;
+    case TILE_128x128: hipLaunchKernelGGL((gemm_grouped_kernel<T, 128, 128, SlabK<T>::BIG, 2, EPIG>), grid, block, 0, s, b); break;
+    case TILE_64x128: hipLaunchKernelGGL((gemm_grouped_kernel<T, 64, 128, SlabK<T>::SKINNY, 2, EPIG>), grid, block, 0, s, b); break;
+    default: hipLaunchKernelGGL((gemm_grouped_kernel<T, 64, 64, SlabK<T>::SKINNY, 2, EPIG>), grid, block, 0, s, b); break;
   }
   return hipGetLastError();
 }
@@ -311,16 +337,19 @@ hipError_t launch_gemm_batch(GemmBatch& b, int dtype, int shape, hipStream_t str
   int bm, bn;
   tile_dims(shape, &bm, &bn);
   int total = 0;
+  const bool wgrad = b.p[0].epi == EPI_WGRAD;
   for (int i = 0; i < b.n; ++i) {
     GemmProb& p = b.p[i];
     if (p.M <= 0 || p.N <= 0 || p.K <= 0 || p.splits < 1) return hipErrorInvalidValue;
+    if ((p.epi == EPI_WGRAD) != wgrad) return hipErrorInvalidValue;  // one epilogue family per launch
     if (p.splits > 1 && !(p.epi == EPI_WGRAD && (p.flags & GF_ATOMIC))) return hipErrorInvalidValue;
     p.tiles_n = (p.N + bn - 1) / bn;
     p.tile_begin = total;
     total += ((p.M + bm - 1) / bm) * p.tiles_n * p.splits;
   }
   b.total_tiles = total;
-  return dtype == DT_BF16 ? launch_typed<uint16_t>(b, shape, stream) : launch_typed<float>(b, shape, stream);
+  if (dtype == DT_BF16) return wgrad ? launch_typed<uint16_t, 1>(b, shape, stream) : launch_typed<uint16_t, 0>(b, shape, stream);
+  return wgrad ? launch_typed<float, 1>(b, shape, stream) : launch_typed<float, 0>(b, shape, stream);
 }
 
 }  // namespace cdp

@@ -70,15 +70,24 @@ void tile_dims(int shape, int* bm, int* bn);
 // Fills tiles_n / tile_begin / total_tiles for the chosen tile shape and launches.
 hipError_t launch_gemm_batch(GemmBatch& batch, int dtype, int tile_shape, hipStream_t stream);
 
+// HBM-streaming variants for Linear layers with a small batch (plain operands only):
+//   skinny: forward / data gradient, operands both k-contiguous; wide = 128-column tiles.
+//   dw:     weight gradient G (+)= dY^T X with A = dY (OP_PLAIN_R), B = X (OP_PLAIN_R),
+//           GF_ACCUM selects accumulate vs overwrite; aux2 = bias-gradient vector or NULL
+//           (same accumulate/overwrite rule).
+hipError_t launch_linear_skinny(GemmBatch& batch, int dtype, bool wide, hipStream_t stream);
+hipError_t launch_linear_dw(GemmBatch& batch, int dtype, hipStream_t stream);
+
 // ---------------------------------------------------------------------------------
 // small kernels
 // ---------------------------------------------------------------------------------
-// fp32 -> T conversion of rows [row0, row0+rows) of the mini-batch, and label copy.
-hipError_t launch_stage_input(const float* x, const int32_t* y, void* x_out, int32_t* y_out,
+// Staging of one micro-batch: fp32 -> T conversion of its rows, label copy, and zeroing
+// of the loss slot its head pass will add into.
+hipError_t launch_stage_input(const float* x, const int32_t* y, void* x_out, int32_t* y_out, float* loss_slot,
                               int rows, int64_t per_row, int dtype, hipStream_t stream);
 
 // Softmax cross-entropy of one micro-batch: logits f32 [B][C] -> loss (mean over rows)
-// written to *loss_out, dlogits = (softmax - onehot)/B as T [B][C].
+// added to *loss_out (zeroed by the staging kernel), dlogits = (softmax - onehot)/B as T [B][C].
 hipError_t launch_ce_head(const float* logits, const int32_t* labels, void* dlogits, float* loss_out,
                           int B, int C, int dtype, hipStream_t stream);
 

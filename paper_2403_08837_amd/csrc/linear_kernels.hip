@@ -1,0 +1,361 @@
+// HBM-streaming contractions of the Linear stages of a CDP tick (gfx950).
+//
+// With a micro-batch of B <= 64 rows every Linear pass reads or updates one weight-
+// sized matrix exactly once for 2*B flops per element, far below the MFMA/HBM ridge, so
+// these kernels are built to keep HBM busy rather than the matrix cores:
+//   * skinny_kernel   C[M][N] = A[M][K] * W[N][K]^T  (forward with W, data gradient with
+//                     the transposed copy W^T): 64-row tiles, 128-deep slabs, one slab of
+//                     loads in flight per workgroup while the previous one is contracted;
+//   * dw_kernel       G[N][K] (+)= dY[M][N]^T * X[M][K] (weight gradient): the old
+//                     accumulator tile is requested before the operands so the read-
+//                     modify-write stream is never waiting on the contraction; the bias
+//                     gradient (column sums of dY) is folded into the first column tile.
+// Workgroups are renumbered so that the tiles of one problem land on one XCD (its L2
+// then holds that problem's activations once), and every workgroup starts its reduction
+// loop at a different slab so that concurrent workgroups do not hit the same HBM
+// channels (weight rows are a power of two apart).
+#include "kernels.h"
+
+namespace cdp {
+
+typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 v8bf16_t;
+typedef __attribute__((__vector_size__(16 * sizeof(float)))) float v16f_t;
+
+namespace {
+
+__device__ __forceinline__ float bf2f(uint16_t h) { return __uint_as_float(((uint32_t)h) << 16); }
+__device__ __forceinline__ uint16_t f2bf(float f) {
+  uint32_t u = __float_as_uint(f);
+  if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x40u);
+  u += 0x7fffu + ((u >> 16) & 1u);
+  return (uint16_t)(u >> 16);
+}
+template <typename T> struct LT;
+template <> struct LT<uint16_t> {
+  static constexpr int VEC = 8, MFMA_K = 16, KPL = 8, SLAB = 128;
+  __device__ static __forceinline__ float to_f32(uint16_t v) { return bf2f(v); }
+  __device__ static __forceinline__ uint16_t from_f32(float f) { return f2bf(f); }
+};
+template <> struct LT<float> {
+  static constexpr int VEC = 4, MFMA_K = 2, KPL = 1, SLAB = 64;
+  __device__ static __forceinline__ float to_f32(float v) { return v; }
+  __device__ static __forceinline__ float from_f32(float f) { return f; }
+};
+
+template <typename T> union Chunk16 {
+  uint4 v;
+  uint2 h[2];
+  T e[16 / sizeof(T)];
+};
+
+// blockIdx -> logical tile: consecutive workgroup ids are dealt round-robin to the 8 XCDs,
+// so XCD x receives the contiguous logical range [x*chunk, (x+1)*chunk).
+__device__ __forceinline__ int xcd_remap(int bid, int total) {
+  const int chunk = (total + 7) >> 3;
+  return (bid & 7) * chunk + (bid >> 3);
+}
+
+__device__ __forceinline__ int find_problem(const GemmBatch& batch, int tile) {
+  int pi = 0;
+  for (int q = 1; q < batch.n; ++q)
+    if (tile >= batch.p[q].tile_begin) pi = q;
+  return pi;
+}
+
+__device__ __forceinline__ v16f_t mfma_bf16(uint4 a, uint4 b, v16f_t c) {
+  return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(v8bf16_t, a), __builtin_bit_cast(v8bf16_t, b), c, 0, 0, 0);
+}
+
+}  // namespace
+
+// ---------------------------------------------------------------------------------
+// skinny_kernel: 64 x BN output tile, waves 2 (rows) x 2 (cols).
+template <typename T, int BN>
+__global__ __launch_bounds__(256) void skinny_kernel(const GemmBatch batch) {
+  using E = LT<T>;
+  constexpr int BM = 64, BK = E::SLAB, VEC = E::VEC, LDP = BK + VEC;
+  constexpr int NA = BM / 16, NB = BN / 16;  // 16-byte chunks per thread and slab
+  constexpr int NI = BN / 64;                // 32-wide MFMA tiles per wave along N
+  __shared__ __attribute__((aligned(16))) T As[BM * LDP];
+  __shared__ __attribute__((aligned(16))) T Bs[BN * LDP];
+
+  const int tile = xcd_remap((int)blockIdx.x, batch.total_tiles);
+  if (tile >= batch.total_tiles) return;
+  const GemmProb& P = batch.p[find_problem(batch, tile)];
+  const int local = tile - P.tile_begin;
+  const int tn = local % P.tiles_n, tm = local / P.tiles_n;
+  const int row0 = tm * BM, col0 = tn * BN;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = wave >> 1, wn = wave & 1;
+
+  const T* __restrict__ Ap = static_cast<const T*>(P.A);
+  const T* __restrict__ Bp = static_cast<const T*>(P.B);
+  const int crow = tid >> 4, ck = (tid & 15) * VEC;  // this thread's chunk: rows crow + 16*i, columns ck..ck+VEC-1
+  int offA[NA], offB[NB];
+#pragma unroll
+  for (int i = 0; i < NA; ++i) {
+    const int r = row0 + crow + 16 * i;
+    offA[i] = r < P.M ? r * P.lda + ck : -1;
+  }
+#pragma unroll
+  for (int i = 0; i < NB; ++i) {
+    const int r = col0 + crow + 16 * i;
+    offB[i] = r < P.N ? r * P.ldb + ck : -1;
+  }
+  uint4 ra[NA], rb[NB];
+  auto fetch = [&](int k0) {
+    const bool kin = k0 + ck < P.K;  // K is a multiple of VEC, so a chunk is inside or outside as a whole
+#pragma unroll
+    for (int i = 0; i < NA; ++i)
+      ra[i] = (kin && offA[i] >= 0) ? *reinterpret_cast<const uint4*>(Ap + offA[i] + k0) : make_uint4(0, 0, 0, 0);
+#pragma unroll
+    for (int i = 0; i < NB; ++i)
+      rb[i] = (kin && offB[i] >= 0) ? *reinterpret_cast<const uint4*>(Bp + offB[i] + k0) : make_uint4(0, 0, 0, 0);
+  };
+
+  v16f_t acc[NI];
+#pragma unroll
+  for (int j = 0; j < NI; ++j)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) acc[j][v] = 0.f;
+
+  const int nslab = (P.K + BK - 1) / BK;
+  int s = (int)(((unsigned)tile * 2654435761u) >> 8) % nslab;  // per-workgroup starting slab
+  fetch(s * BK);
+  for (int it = 0; it < nslab; ++it) {
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < NA; ++i) *reinterpret_cast<uint4*>(As + (crow + 16 * i) * LDP + ck) = ra[i];
+#pragma unroll
+    for (int i = 0; i < NB; ++i) *reinterpret_cast<uint4*>(Bs + (crow + 16 * i) * LDP + ck) = rb[i];
+    __syncthreads();
+    s = (s + 1 == nslab) ? 0 : s + 1;
+    if (it + 1 < nslab) fetch(s * BK);
+    const int kg = (lane >> 5) * E::KPL;
+    const T* ap = As + (wm * 32 + (lane & 31)) * LDP + kg;
+    const T* bp = Bs + (wn * (BN / 2) + (lane & 31)) * LDP + kg;
+#pragma unroll
+    for (int kk = 0; kk < BK; kk += E::MFMA_K) {
+      if constexpr (sizeof(T) == 2) {
+        const uint4 a = *reinterpret_cast<const uint4*>(ap + kk);
+#pragma unroll
+        for (int j = 0; j < NI; ++j) acc[j] = mfma_bf16(a, *reinterpret_cast<const uint4*>(bp + j * 32 * LDP + kk), acc[j]);
+      } else {
+        const float a = ap[kk];
+#pragma unroll
+        for (int j = 0; j < NI; ++j) acc[j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a, bp[j * 32 * LDP + kk], acc[j], 0, 0, 0);
+      }
+    }
+  }
+
+  const int flags = P.flags;
+#pragma unroll
+  for (int j = 0; j < NI; ++j) {
+    const int c = col0 + wn * (BN / 2) + j * 32 + (lane & 31);
+    const float bias = (P.epi == EPI_FWD && P.aux0 != nullptr && c < P.N) ? static_cast<const float*>(P.aux0)[c] : 0.f;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+      const int r = row0 + wm * 32 + (v >> 2) * 8 + (lane >> 5) * 4 + (v & 3);
+      if (r >= P.M || c >= P.N) continue;
+      float val = acc[j][v];
+      const int64_t o = (int64_t)r * P.ldo + c;
+      if (P.epi == EPI_FWD) {
+        val += bias;
+        if (P.aux1) val += E::to_f32(static_cast<const T*>(P.aux1)[o]);
+        if (flags & GF_RELU) val = fmaxf(val, 0.f);
+        if (flags & GF_OUT_F32) static_cast<float*>(P.out)[o] = val;
+        else static_cast<T*>(P.out)[o] = E::from_f32(val);
+      } else {
+        if (P.aux0) val += E::to_f32(static_cast<const T*>(P.aux0)[o]);
+        if (flags & GF_ACCUM) val += E::to_f32(static_cast<T*>(P.out)[o]);
+        if (P.aux1 && !(E::to_f32(static_cast<const T*>(P.aux1)[o]) > 0.f)) val = 0.f;
+        static_cast<T*>(P.out)[o] = E::from_f32(val);
+      }
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------------
+// dw_kernel: G tile of 64 (rows n) x 128 (cols k); wave w owns columns [32w, 32w+32).
+// Operand convention of the batch entry: A = dY [Mb][N] (lda = N), B = X [Mb][K]
+// (ldb = K), out = G [N][K] (ldo = K), P.M = N, P.N = K, P.K = Mb (reduction length);
+// aux2 = bias-gradient vector [N] or NULL.
+template <typename T>
+__global__ __launch_bounds__(256) void dw_kernel(const GemmBatch batch) {
+  using E = LT<T>;
+  constexpr int TN = 64, TK = 128, MB = 64, VEC = E::VEC;
+  constexpr int PD = TN + (sizeof(T) == 2 ? 4 : 4), PX = TK + (sizeof(T) == 2 ? 4 : 4);  // LDS pitches (elements)
+  __shared__ __attribute__((aligned(16))) T Ds[MB * PD];
+  __shared__ __attribute__((aligned(16))) T Xs[MB * PX];
+
+  const int tile = xcd_remap((int)blockIdx.x, batch.total_tiles);
+  if (tile >= batch.total_tiles) return;
+  const GemmProb& P = batch.p[find_problem(batch, tile)];
+  const int local = tile - P.tile_begin;
+  const int tk = local % P.tiles_n, tnn = local / P.tiles_n;
+  const int n0 = tnn * TN, k0 = tk * TK;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int Nn = P.M, Kk = P.N, Mb = P.K;
+  const int flags = P.flags;
+  float* __restrict__ G = static_cast<float*>(P.out);
+
+  // 1. request the old accumulator tile (read-modify-write) before anything else
+  const bool rmw = (flags & GF_ACCUM) != 0;
+  const int gc = k0 + wave * 32 + (lane & 31);
+  float gold[32];
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+      const int r = n0 + i * 32 + (v >> 2) * 8 + (lane >> 5) * 4 + (v & 3);
+      gold[i * 16 + v] = (rmw && r < Nn && gc < Kk) ? G[(int64_t)r * P.ldo + gc] : 0.f;
+    }
+
+  v16f_t acc[2];
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) acc[i][v] = 0.f;
+  float bsum = 0.f;  // bias gradient of column n0 + tid (threads 0..63 of the first column tile)
+
+  const T* __restrict__ Dp = static_cast<const T*>(P.A);
+  const T* __restrict__ Xp = static_cast<const T*>(P.B);
+  const bool dvec = (P.lda % VEC) == 0, xvec = (P.ldb % VEC) == 0;
+  for (int m0 = 0; m0 < Mb; m0 += MB) {
+    if (m0 > 0) __syncthreads();
+    // 2. stage dY[m0.., n0..n0+63] and X[m0.., k0..k0+127] as they lie in memory
+    constexpr int DCH = TN / VEC, XCH = TK / VEC;  // chunks per row
+    for (int id = tid; id < MB * DCH; id += 256) {
+      const int m = id / DCH, c = (id % DCH) * VEC;
+      Chunk16<T> tmp;
+      tmp.v = make_uint4(0, 0, 0, 0);
+      if (m0 + m < Mb) {
+        const T* src = Dp + (int64_t)(m0 + m) * P.lda + n0 + c;
+        if (dvec && n0 + c + VEC <= Nn) {
+          tmp.v = *reinterpret_cast<const uint4*>(src);
+        } else {
+#pragma unroll
+          for (int e = 0; e < VEC; ++e)
+            if (n0 + c + e < Nn) tmp.e[e] = src[e];
+        }
+      }
+      uint2* dst = reinterpret_cast<uint2*>(Ds + m * PD + c);
+      dst[0] = tmp.h[0];
+      dst[1] = tmp.h[1];
+    }
+    for (int id = tid; id < MB * XCH; id += 256) {
+      const int m = id / XCH, c = (id % XCH) * VEC;
+      Chunk16<T> tmp;
+      tmp.v = make_uint4(0, 0, 0, 0);
+      if (m0 + m < Mb) {
+        const T* src = Xp + (int64_t)(m0 + m) * P.ldb + k0 + c;
+        if (xvec && k0 + c + VEC <= Kk) {
+          tmp.v = *reinterpret_cast<const uint4*>(src);
+        } else {
+#pragma unroll
+          for (int e = 0; e < VEC; ++e)
+            if (k0 + c + e < Kk) tmp.e[e] = src[e];
+        }
+      }
+      uint2* dst = reinterpret_cast<uint2*>(Xs + m * PX + c);
+      dst[0] = tmp.h[0];
+      dst[1] = tmp.h[1];
+    }
+    __syncthreads();
+    // 3. contraction over the batch rows; fragments are read transposed out of LDS
+    const int g = lane >> 5, l31 = lane & 31;
+    if constexpr (sizeof(T) == 2) {
+#pragma unroll
+      for (int kk = 0; kk < MB; kk += 16) {
+        const int mb = kk + 8 * g;
+        uint32_t xb[4], da[2][4];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          xb[q] = (uint32_t)Xs[(mb + 2 * q) * PX + wave * 32 + l31] | ((uint32_t)Xs[(mb + 2 * q + 1) * PX + wave * 32 + l31] << 16);
+#pragma unroll
+          for (int i = 0; i < 2; ++i)
+            da[i][q] = (uint32_t)Ds[(mb + 2 * q) * PD + i * 32 + l31] | ((uint32_t)Ds[(mb + 2 * q + 1) * PD + i * 32 + l31] << 16);
+        }
+        const uint4 bv = make_uint4(xb[0], xb[1], xb[2], xb[3]);
+#pragma unroll
+        for (int i = 0; i < 2; ++i) acc[i] = mfma_bf16(make_uint4(da[i][0], da[i][1], da[i][2], da[i][3]), bv, acc[i]);
+      }
+    } else {
+#pragma unroll 8
+      for (int kk = 0; kk < MB; kk += 2) {
+        const float bv = Xs[(kk + g) * PX + wave * 32 + l31];
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+          acc[i] = __builtin_amdgcn_mfma_f32_32x32x2f32(Ds[(kk + g) * PD + i * 32 + l31], bv, acc[i], 0, 0, 0);
+      }
+    }
+    if (tk == 0 && P.aux2 != nullptr && tid < TN) {
+      for (int m = 0; m < MB; ++m) bsum += E::to_f32(Ds[m * PD + tid]);
+    }
+  }
+
+  // 4. accumulate and write back
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+      const int r = n0 + i * 32 + (v >> 2) * 8 + (lane >> 5) * 4 + (v & 3);
+      if (r < Nn && gc < Kk) G[(int64_t)r * P.ldo + gc] = gold[i * 16 + v] + acc[i][v];
+    }
+  if (tk == 0 && P.aux2 != nullptr && tid < TN && n0 + tid < Nn) {
+    float* gb = static_cast<float*>(P.aux2) + n0 + tid;
+    *gb = rmw ? (*gb + bsum) : bsum;
+  }
+}
+
+// ---------------------------------------------------------------------------------
+hipError_t launch_linear_skinny(GemmBatch& b, int dtype, bool wide, hipStream_t stream) {
+  if (b.n <= 0) return hipSuccess;
+  if (b.n > GEMM_MAX_PROBS) return hipErrorInvalidValue;
+  const int bn = wide ? 128 : 64, vec = dtype == DT_BF16 ? 8 : 4;
+  int total = 0;
+  for (int i = 0; i < b.n; ++i) {
+    GemmProb& p = b.p[i];
+    if (p.M <= 0 || p.N <= 0 || p.K <= 0) return hipErrorInvalidValue;
+    if (p.a_mode != OP_PLAIN_K || p.b_mode != OP_PLAIN_K || p.epi == EPI_WGRAD) return hipErrorInvalidValue;
+    if (p.K % vec || p.lda % vec || p.ldb % vec) return hipErrorInvalidValue;
+    if ((int64_t)p.M * p.lda >= (1ll << 31) || (int64_t)p.N * p.ldb >= (1ll << 31)) return hipErrorInvalidValue;
+    p.splits = 1;
+    p.tiles_n = (p.N + bn - 1) / bn;
+    p.tile_begin = total;
+    total += ((p.M + 63) / 64) * p.tiles_n;
+  }
+  b.total_tiles = total;
+  dim3 grid(((total + 7) / 8) * 8), block(256);
+  if (dtype == DT_BF16) {
+    if (wide) hipLaunchKernelGGL((skinny_kernel<uint16_t, 128>), grid, block, 0, stream, b);
+    else hipLaunchKernelGGL((skinny_kernel<uint16_t, 64>), grid, block, 0, stream, b);
+  } else {
+    if (wide) hipLaunchKernelGGL((skinny_kernel<float, 128>), grid, block, 0, stream, b);
+    else hipLaunchKernelGGL((skinny_kernel<float, 64>), grid, block, 0, stream, b);
+  }
+  return hipGetLastError();
+}
+
+hipError_t launch_linear_dw(GemmBatch& b, int dtype, hipStream_t stream) {
+  if (b.n <= 0) return hipSuccess;
+  if (b.n > GEMM_MAX_PROBS) return hipErrorInvalidValue;
+  int total = 0;
+  for (int i = 0; i < b.n; ++i) {
+    GemmProb& p = b.p[i];
+    if (p.M <= 0 || p.N <= 0 || p.K <= 0) return hipErrorInvalidValue;
+    if (p.a_mode != OP_PLAIN_R || p.b_mode != OP_PLAIN_R || p.epi != EPI_WGRAD) return hipErrorInvalidValue;
+    if ((p.flags & GF_ATOMIC) || p.aux0 || p.aux1) return hipErrorInvalidValue;
+    p.splits = 1;
+    p.tiles_n = (p.N + 127) / 128;
+    p.tile_begin = total;
+    total += ((p.M + 63) / 64) * p.tiles_n;
+  }
+  b.total_tiles = total;
+  dim3 grid(((total + 7) / 8) * 8), block(256);
+  if (dtype == DT_BF16) hipLaunchKernelGGL((dw_kernel<uint16_t>), grid, block, 0, stream, b);
+  else hipLaunchKernelGGL((dw_kernel<float>), grid, block, 0, stream, b);
+  return hipGetLastError();
+}
+
+}  // namespace cdp

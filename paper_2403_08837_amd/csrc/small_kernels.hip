@@ -36,26 +36,27 @@ static inline int blocks_for(int64_t n, int per_block, int cap = 1 << 20) {
 // ---------------------------------------------------------------------------------
 template <typename T>
 __global__ void stage_input_kernel(const float* __restrict__ x, const int32_t* __restrict__ y, T* __restrict__ xo,
-                                   int32_t* __restrict__ yo, int rows, int64_t n) {
+                                   int32_t* __restrict__ yo, float* __restrict__ loss_slot, int rows, int64_t n) {
+  if (blockIdx.x == 0 && threadIdx.x == 0) *loss_slot = 0.f;  // the head adds row losses into it
   for (int64_t i = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x) {
     st_f32<T>(xo, i, x[i]);
     if (i < rows) yo[i] = y[i];
   }
 }
 
-hipError_t launch_stage_input(const float* x, const int32_t* y, void* x_out, int32_t* y_out, int rows, int64_t per_row,
-                              int dtype, hipStream_t stream) {
+hipError_t launch_stage_input(const float* x, const int32_t* y, void* x_out, int32_t* y_out, float* loss_slot, int rows,
+                              int64_t per_row, int dtype, hipStream_t stream) {
   int64_t n = (int64_t)rows * per_row;
   if (n < rows) return hipErrorInvalidValue;
   CDP_DISPATCH(dtype, hipLaunchKernelGGL((stage_input_kernel<T>), dim3(blocks_for(n, 256 * 4, 4096)), dim3(256), 0, stream,
-                                         x, y, static_cast<T*>(x_out), y_out, rows, n));
+                                         x, y, static_cast<T*>(x_out), y_out, loss_slot, rows, n));
   return hipGetLastError();
 }
 
 // ---------------------------------------------------------------------------------
-// One wavefront per row: max, sum of exponentials, loss and gradient.  The per-row
-// losses are reduced over the workgroup's rows; one workgroup handles the whole
-// micro-batch (B <= 1024 rows via a row loop), so the mean needs no atomics.
+// One wavefront per row: max, sum of exponentials, loss and gradient; four rows per
+// workgroup.  Row losses are added (fp32 atomic) into *loss_out, which the staging kernel
+// of the same micro-batch has set to zero.
 __device__ __forceinline__ float wave_max(float v) {
 #pragma unroll
   for (int o = 32; o >= 1; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
@@ -70,34 +71,29 @@ __device__ __forceinline__ float wave_sum(float v) {
 template <typename T>
 __global__ __launch_bounds__(256) void ce_head_kernel(const float* __restrict__ logits, const int32_t* __restrict__ labels,
                                                       T* __restrict__ dlogits, float* __restrict__ loss_out, int B, int C) {
-  __shared__ float part[4];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  float loss_acc = 0.f;
+  const int row = blockIdx.x * 4 + wave;
+  if (row >= B) return;
   const float invB = 1.0f / (float)B;
-  for (int row = wave; row < B; row += 4) {
-    const float* z = logits + (int64_t)row * C;
-    float m = -INFINITY;
-    for (int c = lane; c < C; c += 64) m = fmaxf(m, z[c]);
-    m = wave_max(m);
-    float s = 0.f;
-    for (int c = lane; c < C; c += 64) s += __expf(z[c] - m);
-    s = wave_sum(s);
-    const int y = labels[row];
-    const float inv = 1.0f / s;
-    for (int c = lane; c < C; c += 64) {
-      float p = __expf(z[c] - m) * inv;
-      st_f32<T>(dlogits, (int64_t)row * C + c, (p - (c == y ? 1.f : 0.f)) * invB);
-    }
-    loss_acc += (m + __logf(s)) - z[y];
+  const float* z = logits + (int64_t)row * C;
+  float m = -INFINITY;
+  for (int c = lane; c < C; c += 64) m = fmaxf(m, z[c]);
+  m = wave_max(m);
+  float s = 0.f;
+  for (int c = lane; c < C; c += 64) s += expf(z[c] - m);
+  s = wave_sum(s);
+  const int y = labels[row];
+  const float inv = 1.0f / s;
+  for (int c = lane; c < C; c += 64) {
+    float p = expf(z[c] - m) * inv;
+    st_f32<T>(dlogits, (int64_t)row * C + c, (p - (c == y ? 1.f : 0.f)) * invB);
   }
-  if (lane == 0) part[wave] = loss_acc;
-  __syncthreads();
-  if (threadIdx.x == 0) *loss_out = (part[0] + part[1] + part[2] + part[3]) * invB;
+  if (lane == 0) atomicAdd(loss_out, ((m + logf(s)) - z[y]) * invB);
 }
 
 hipError_t launch_ce_head(const float* logits, const int32_t* labels, void* dlogits, float* loss_out, int B, int C, int dtype,
                           hipStream_t stream) {
-  CDP_DISPATCH(dtype, hipLaunchKernelGGL((ce_head_kernel<T>), dim3(1), dim3(256), 0, stream, logits, labels,
+  CDP_DISPATCH(dtype, hipLaunchKernelGGL((ce_head_kernel<T>), dim3((B + 3) / 4), dim3(256), 0, stream, logits, labels,
                                          static_cast<T*>(dlogits), loss_out, B, C));
   return hipGetLastError();
 }
