@@ -75,6 +75,7 @@ class Config:
     lr: float
     steps: int                     # steps for the parity run
     init_gain_last_affine: float = 1.0
+    init_gain_head: float = 1.0    # scale on the classifier weights (the LINEAR feeding CE_HEAD)
     notes: str = ""
 
     @property
@@ -264,11 +265,11 @@ def get_config(name: str) -> Config:
                       dtype=BF16, lr=0.05, steps=50, notes="CIFAR-shaped MLP")
     if name == "cfg3":
         return Config("cfg3", _resnet18_cifar(10), (32, 32, 3), 10, N=4, B=32,
-                      dtype=BF16, lr=0.05, steps=10, init_gain_last_affine=0.25,
+                      dtype=BF16, lr=0.05, steps=10, init_gain_last_affine=0.25, init_gain_head=0.05,
                       notes="CIFAR-shaped ResNet-18")
     if name == "cfg4":
         return Config("cfg4", _resnet50(1000), (224, 224, 3), 1000, N=8, B=32,
-                      dtype=BF16, lr=0.1, steps=4, init_gain_last_affine=0.25,
+                      dtype=BF16, lr=0.01, steps=4, init_gain_last_affine=0.25, init_gain_head=0.05,
                       notes="ImageNet-shaped ResNet-50")
     if name == "cfg5":
         return Config("cfg5", _mlp(4096, 4096, 24, 1000, stem=False), (4096,), 1000, N=16, B=64,
@@ -377,7 +378,9 @@ def init_params(cfg: Config, seed: int = 0) -> List[List[np.ndarray]]:
     Linear / conv weights ~ N(0, 2/fan_in); biases 0; affine gamma 1, beta 0,
     except the affine that feeds a residual ADD, whose gamma is
     ``cfg.init_gain_last_affine`` (keeps activations bounded without
-    normalisation layers).
+    normalisation layers), and the classifier weights, which are scaled by
+    ``cfg.init_gain_head`` (the pooled features are all positive, so a
+    Kaiming-scaled classifier would start with logits of std ~5).
     """
     out: List[List[np.ndarray]] = []
     stream = _STREAM_W
@@ -387,6 +390,8 @@ def init_params(cfg: Config, seed: int = 0) -> List[List[np.ndarray]]:
             if layer.kind == LINEAR:
                 fan_in = layer.p[0]
                 w = random_normal(seed, stream, layer.p[0] * layer.p[1]) * math.sqrt(2.0 / fan_in)
+                if li + 1 < len(st) and st[li + 1].kind == CE_HEAD:
+                    w = w * cfg.init_gain_head
                 stream += 1
                 plist.append(w.astype(np.float32).reshape(layer.p[1], layer.p[0]))
                 plist.append(np.zeros(layer.p[1], dtype=np.float32))

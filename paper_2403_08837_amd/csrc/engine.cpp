@@ -269,9 +269,8 @@ void op_work(const cdp_ctx* c, const Op& o, int pass, bool rmw, bool extra_in, I
 enum LaunchClass { LC_SKINNY_64 = 0, LC_SKINNY_128, LC_LINEAR_DW, LC_GEN_FIRST };  // LC_GEN_FIRST + 2*shape + wgrad
 
 int launch_class(const GemmProb& p, int dtype) {
-  const int vec = dtype == DT_BF16 ? 8 : 4;
-  if (p.epi != EPI_WGRAD && p.a_mode == OP_PLAIN_K && p.b_mode == OP_PLAIN_K && p.M <= 128 && p.K % vec == 0 &&
-      p.lda % vec == 0 && p.ldb % vec == 0)
+  (void)dtype;
+  if (p.epi != EPI_WGRAD && p.a_mode == OP_PLAIN_K && p.b_mode == OP_PLAIN_K && p.M <= 128)
     return p.N >= 2048 ? LC_SKINNY_128 : LC_SKINNY_64;
   if (p.epi == EPI_WGRAD && p.a_mode == OP_PLAIN_R && p.b_mode == OP_PLAIN_R && !(p.flags & GF_ATOMIC) && !p.aux0 && !p.aux1)
     return LC_LINEAR_DW;

@@ -103,14 +103,32 @@ __global__ __launch_bounds__(256) void skinny_kernel(const GemmBatch batch) {
     offB[i] = r < P.N ? r * P.ldb + ck : -1;
   }
   uint4 ra[NA], rb[NB];
+  // rows are 16-byte aligned and K is a whole number of chunks: one vector load per chunk;
+  // otherwise (e.g. a 10-class head) chunks are gathered element by element
+  const bool vec = (P.K % VEC) == 0 && (P.lda % VEC) == 0 && (P.ldb % VEC) == 0;
+  auto gather = [&](const T* src, int k) {
+    Chunk16<T> c;
+    c.v = make_uint4(0, 0, 0, 0);
+#pragma unroll
+    for (int e = 0; e < VEC; ++e)
+      if (k + e < P.K) c.e[e] = src[e];
+    return c.v;
+  };
   auto fetch = [&](int k0) {
-    const bool kin = k0 + ck < P.K;  // K is a multiple of VEC, so a chunk is inside or outside as a whole
+    const bool kin = k0 + ck < P.K;
+    if (vec) {
 #pragma unroll
-    for (int i = 0; i < NA; ++i)
-      ra[i] = (kin && offA[i] >= 0) ? *reinterpret_cast<const uint4*>(Ap + offA[i] + k0) : make_uint4(0, 0, 0, 0);
+      for (int i = 0; i < NA; ++i)
+        ra[i] = (kin && offA[i] >= 0) ? *reinterpret_cast<const uint4*>(Ap + offA[i] + k0) : make_uint4(0, 0, 0, 0);
 #pragma unroll
-    for (int i = 0; i < NB; ++i)
-      rb[i] = (kin && offB[i] >= 0) ? *reinterpret_cast<const uint4*>(Bp + offB[i] + k0) : make_uint4(0, 0, 0, 0);
+      for (int i = 0; i < NB; ++i)
+        rb[i] = (kin && offB[i] >= 0) ? *reinterpret_cast<const uint4*>(Bp + offB[i] + k0) : make_uint4(0, 0, 0, 0);
+    } else {
+#pragma unroll
+      for (int i = 0; i < NA; ++i) ra[i] = (kin && offA[i] >= 0) ? gather(Ap + offA[i] + k0, k0 + ck) : make_uint4(0, 0, 0, 0);
+#pragma unroll
+      for (int i = 0; i < NB; ++i) rb[i] = (kin && offB[i] >= 0) ? gather(Bp + offB[i] + k0, k0 + ck) : make_uint4(0, 0, 0, 0);
+    }
   };
 
   v16f_t acc[NI];
@@ -312,13 +330,12 @@ __global__ __launch_bounds__(256) void dw_kernel(const GemmBatch batch) {
 hipError_t launch_linear_skinny(GemmBatch& b, int dtype, bool wide, hipStream_t stream) {
   if (b.n <= 0) return hipSuccess;
   if (b.n > GEMM_MAX_PROBS) return hipErrorInvalidValue;
-  const int bn = wide ? 128 : 64, vec = dtype == DT_BF16 ? 8 : 4;
+  const int bn = wide ? 128 : 64;
   int total = 0;
   for (int i = 0; i < b.n; ++i) {
     GemmProb& p = b.p[i];
     if (p.M <= 0 || p.N <= 0 || p.K <= 0) return hipErrorInvalidValue;
     if (p.a_mode != OP_PLAIN_K || p.b_mode != OP_PLAIN_K || p.epi == EPI_WGRAD) return hipErrorInvalidValue;
-    if (p.K % vec || p.lda % vec || p.ldb % vec) return hipErrorInvalidValue;
     if ((int64_t)p.M * p.lda >= (1ll << 31) || (int64_t)p.N * p.ldb >= (1ll << 31)) return hipErrorInvalidValue;
     p.splits = 1;
     p.tiles_n = (p.N + bn - 1) / bn;
