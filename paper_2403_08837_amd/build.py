@@ -8,7 +8,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libcdp.so")
-SOURCES = ["gemm.hip", "linear_kernels.hip", "small_kernels.hip", "engine.cpp", "plan.cpp", "kernels_api.cpp"]
+SOURCES = ["gemm.hip", "linear_kernels.hip", "conv_kernels.hip", "small_kernels.hip", "engine.cpp", "plan.cpp", "kernels_api.cpp"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 # packed-fp32 VALU forms are switched off for all device code ("Build")
 DEVICE_FLAGS = ["--offload-arch=gfx950", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]

@@ -1,0 +1,513 @@
+// Implicit-GEMM convolution passes of a CDP tick on gfx950, for channel counts that are a
+// multiple of the reduction slab (bf16: 32, fp32: 16); other shapes (the 3-channel stem)
+// run on the generic kernel of gemm.hip.
+//
+//   conv_gemm_kernel   forward   y[(b,oh,ow)][o]  = sum_{tap,c} x[b][oh*s-p+kh][ow*s-p+kw][c] * wf[o][tap][c]
+//                      data grad dx[(b,ih,iw)][c] = sum_{tap,o} dy[b][(ih+p-kh)/s][(iw+p-kw)/s][o] * wt[c][tap][o]
+//     A slab of the reduction lies inside one tap, so the tap and its address delta are
+//     wavefront-uniform; each thread keeps, per tile row it loads, one base offset and one
+//     bit per tap (inside the image / on the stride lattice).  No division in the k-loop.
+//   conv_wgrad_kernel  G[o][(tap,c)] += gamma[o] * sum_m dy[m][o] * x[pos(m)+tap][c]
+//     reduction over output positions, split across workgroups (fp32 atomics into the zeroed
+//     accumulator); operands are staged as they lie in memory ([m][channels]) and MFMA
+//     fragments are read transposed out of LDS; the per-position address decode is done
+//     once per workgroup into an LDS table.  Also produces d gamma and d beta.
+#include "kernels.h"
+
+namespace cdp {
+
+typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 cv8bf16;
+typedef __attribute__((__vector_size__(16 * sizeof(float)))) float cv16f;
+
+namespace {
+
+__device__ __forceinline__ float cbf2f(uint16_t h) { return __uint_as_float(((uint32_t)h) << 16); }
+__device__ __forceinline__ uint16_t cf2bf(float f) {
+  uint32_t u = __float_as_uint(f);
+  if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x40u);
+  u += 0x7fffu + ((u >> 16) & 1u);
+  return (uint16_t)(u >> 16);
+}
+template <typename T> struct CT;
+template <> struct CT<uint16_t> {
+  static constexpr int VEC = 8, MFMA_K = 16, KPL = 8, BK = 32;
+  __device__ static __forceinline__ float to_f32(uint16_t v) { return cbf2f(v); }
+  __device__ static __forceinline__ uint16_t from_f32(float f) { return cf2bf(f); }
+};
+template <> struct CT<float> {
+  static constexpr int VEC = 4, MFMA_K = 2, KPL = 1, BK = 16;
+  __device__ static __forceinline__ float to_f32(float v) { return v; }
+  __device__ static __forceinline__ float from_f32(float f) { return f; }
+};
+
+template <typename T> union CChunk {
+  uint4 v;
+  uint2 h[2];
+  T e[16 / sizeof(T)];
+};
+
+__device__ __forceinline__ int cfind_problem(const GemmBatch& batch, int tile) {
+  int pi = 0;
+  for (int q = 1; q < batch.n; ++q)
+    if (tile >= batch.p[q].tile_begin) pi = q;
+  return pi;
+}
+
+__device__ __forceinline__ cv16f cmfma_bf16(uint4 a, uint4 b, cv16f c) {
+  return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(cv8bf16, a), __builtin_bit_cast(cv8bf16, b), c, 0, 0, 0);
+}
+
+}  // namespace
+
+// ---------------------------------------------------------------------------------
+// forward / data gradient: 128 x BN tile, waves 2 x 2.
+template <typename T, int BN>
+__global__ __launch_bounds__(256) void conv_gemm_kernel(const GemmBatch batch) {
+  using E = CT<T>;
+  constexpr int BM = 128, BK = E::BK, VEC = E::VEC, LDP = BK + VEC;
+  constexpr int CPR = BK / VEC;                // chunks per tile row (4)
+  constexpr int NA = BM * CPR / 256;           // A chunks per thread (2)
+  constexpr int NB = BN * CPR / 256;           // B chunks per thread (2 or 1)
+  constexpr int WTN = BN / 2, NI = WTN / 32;   // wave tile 64 x WTN
+  __shared__ __attribute__((aligned(16))) T As[BM * LDP];
+  __shared__ __attribute__((aligned(16))) T Bs[BN * LDP];
+
+  const int tile = (int)blockIdx.x;
+  const GemmProb& P = batch.p[cfind_problem(batch, tile)];
+  const int local = tile - P.tile_begin;
+  const int tn = local % P.tiles_n, tm = local / P.tiles_n;
+  const int row0 = tm * BM, col0 = tn * BN;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = wave >> 1, wn = wave & 1;
+  const T* __restrict__ Ap = static_cast<const T*>(P.A);
+  const T* __restrict__ Bp = static_cast<const T*>(P.B);
+  const ConvGeom g = P.g;
+  const int mode = P.a_mode;
+  const int C = (mode == OP_PLAIN_K) ? P.K : g.C;  // channels per tap of the gathered tensor
+
+  // per-row state of the A chunks this thread loads
+  const int arow = tid / CPR, akc = (tid % CPR) * VEC;
+  int abase[NA];
+  unsigned amask[NA];
+#pragma unroll
+  for (int i = 0; i < NA; ++i) {
+    const int r = row0 + arow + i * (256 / CPR);
+    abase[i] = 0;
+    amask[i] = 0;
+    if (r < P.M) {
+      if (mode == OP_PLAIN_K) {
+        abase[i] = r * P.lda;
+        amask[i] = 1u;
+      } else {
+        const int b = r / (g.OH * g.OW);
+        const int rem = r - b * (g.OH * g.OW);
+        const int oh = rem / g.OW, ow = rem - oh * g.OW;
+        if (mode == OP_CONV_FWD) {
+          const int ih0 = oh * g.stride - g.pad, iw0 = ow * g.stride - g.pad;
+          abase[i] = ((b * g.H + ih0) * g.W + iw0) * g.C;
+          for (int kh = 0; kh < g.KH; ++kh)
+            for (int kw = 0; kw < g.KW; ++kw)
+              if (ih0 + kh >= 0 && ih0 + kh < g.H && iw0 + kw >= 0 && iw0 + kw < g.W) amask[i] |= 1u << (kh * g.KW + kw);
+        } else {  // OP_CONV_DGRAD: (oh, ow) is an input position, the gathered tensor is dy
+          const int qh = (oh + g.pad) / g.stride, eh = (oh + g.pad) - qh * g.stride;
+          const int qw = (ow + g.pad) / g.stride, ew = (ow + g.pad) - qw * g.stride;
+          abase[i] = ((b * g.H + qh) * g.W + qw) * g.C;
+          for (int kh = 0; kh < g.KH; ++kh)
+            for (int kw = 0; kw < g.KW; ++kw) {
+              const int uh = kh / g.stride, uw = kw / g.stride;
+              if (kh - uh * g.stride == eh && kw - uw * g.stride == ew && qh - uh >= 0 && qh - uh < g.H && qw - uw >= 0 &&
+                  qw - uw < g.W)
+                amask[i] |= 1u << (kh * g.KW + kw);
+            }
+        }
+      }
+    }
+  }
+  const int brow = tid / CPR;
+  int boff[NB];
+#pragma unroll
+  for (int i = 0; i < NB; ++i) {
+    const int r = col0 + brow + i * (256 / CPR);
+    boff[i] = r < P.N ? r * P.ldb + akc : -1;
+  }
+
+  uint4 ra[NA], rb[NB];
+  // wavefront-uniform position of the current slab: tap index, channel offset inside the tap
+  int tap = 0, c0 = 0, kh = 0, kw = 0;
+  auto fetch = [&](int k0) {
+    int delta;
+    if (mode == OP_PLAIN_K) delta = c0;
+    else if (mode == OP_CONV_FWD) delta = (kh * g.W + kw) * g.C + c0;
+    else delta = -((kh / g.stride) * g.W + (kw / g.stride)) * g.C + c0;
+#pragma unroll
+    for (int i = 0; i < NA; ++i)
+      ra[i] = ((amask[i] >> tap) & 1u) ? *reinterpret_cast<const uint4*>(Ap + abase[i] + delta + akc) : make_uint4(0, 0, 0, 0);
+#pragma unroll
+    for (int i = 0; i < NB; ++i) rb[i] = boff[i] >= 0 ? *reinterpret_cast<const uint4*>(Bp + boff[i] + k0) : make_uint4(0, 0, 0, 0);
+    c0 += BK;
+    if (c0 == C) {
+      c0 = 0;
+      ++tap;
+      if (++kw == g.KW) { kw = 0; ++kh; }
+    }
+  };
+
+  cv16f acc[2][NI];
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int j = 0; j < NI; ++j)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+
+  const int nslab = P.K / BK;
+  fetch(0);
+  for (int it = 0; it < nslab; ++it) {
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < NA; ++i) *reinterpret_cast<uint4*>(As + (arow + i * (256 / CPR)) * LDP + akc) = ra[i];
+#pragma unroll
+    for (int i = 0; i < NB; ++i) *reinterpret_cast<uint4*>(Bs + (brow + i * (256 / CPR)) * LDP + akc) = rb[i];
+    __syncthreads();
+    if (it + 1 < nslab) fetch((it + 1) * BK);
+    const int kg = (lane >> 5) * E::KPL;
+    const T* ap = As + (wm * 64 + (lane & 31)) * LDP + kg;
+    const T* bp = Bs + (wn * WTN + (lane & 31)) * LDP + kg;
+#pragma unroll
+    for (int kk = 0; kk < BK; kk += E::MFMA_K) {
+      if constexpr (sizeof(T) == 2) {
+        uint4 a[2], b[NI];
+#pragma unroll
+        for (int i = 0; i < 2; ++i) a[i] = *reinterpret_cast<const uint4*>(ap + i * 32 * LDP + kk);
+#pragma unroll
+        for (int j = 0; j < NI; ++j) b[j] = *reinterpret_cast<const uint4*>(bp + j * 32 * LDP + kk);
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+#pragma unroll
+          for (int j = 0; j < NI; ++j) acc[i][j] = cmfma_bf16(a[i], b[j], acc[i][j]);
+      } else {
+        float a[2], b[NI];
+#pragma unroll
+        for (int i = 0; i < 2; ++i) a[i] = ap[i * 32 * LDP + kk];
+#pragma unroll
+        for (int j = 0; j < NI; ++j) b[j] = bp[j * 32 * LDP + kk];
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+#pragma unroll
+          for (int j = 0; j < NI; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[i], b[j], acc[i][j], 0, 0, 0);
+      }
+    }
+  }
+
+  const int flags = P.flags;
+#pragma unroll
+  for (int j = 0; j < NI; ++j) {
+    const int c = col0 + wn * WTN + j * 32 + (lane & 31);
+    const float bias = (P.epi == EPI_FWD && P.aux0 != nullptr && c < P.N) ? static_cast<const float*>(P.aux0)[c] : 0.f;
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        const int r = row0 + wm * 64 + i * 32 + (v >> 2) * 8 + (lane >> 5) * 4 + (v & 3);
+        if (r >= P.M || c >= P.N) continue;
+        float val = acc[i][j][v];
+        const int64_t o = (int64_t)r * P.ldo + c;
+        if (P.epi == EPI_FWD) {
+          val += bias;
+          if (P.aux1) val += E::to_f32(static_cast<const T*>(P.aux1)[o]);
+          if (flags & GF_RELU) val = fmaxf(val, 0.f);
+          if (flags & GF_OUT_F32) static_cast<float*>(P.out)[o] = val;
+          else static_cast<T*>(P.out)[o] = E::from_f32(val);
+        } else {
+          if (P.aux0) val += E::to_f32(static_cast<const T*>(P.aux0)[o]);
+          if (flags & GF_ACCUM) val += E::to_f32(static_cast<T*>(P.out)[o]);
+          if (P.aux1 && !(E::to_f32(static_cast<const T*>(P.aux1)[o]) > 0.f)) val = 0.f;
+          static_cast<T*>(P.out)[o] = E::from_f32(val);
+        }
+      }
+  }
+}
+
+// ---------------------------------------------------------------------------------
+// weight gradient.  Batch entry convention (as for the generic kernel): A = dy [Mpos][Cout]
+// (OP_PLAIN_R, lda = Cout), B = x (OP_CONV_WGRAD geometry, or OP_PLAIN_R with ldb = Cin for a
+// 1x1/stride-1 layer), out = G [Cout][taps*Cin] (ldo = taps*Cin), P.M = Cout, P.N = taps*Cin,
+// P.K = Mpos, splits = number of reduction ranges.  aux0 = gamma f32[Cout] or NULL, aux1 = plain
+// weights T[Cout][taps*Cin] or NULL, aux2 = d gamma accumulator or NULL, aux3 = d beta
+// accumulator or NULL.  All accumulators receive fp32 atomic adds.
+constexpr int WG_MAX_SLABS = 16;  // slabs per workgroup (bounds the LDS position table)
+template <typename T> struct WgSlab { static constexpr int MB = sizeof(T) == 2 ? 64 : 32; };  // positions per slab
+static inline int wg_slab(int dtype) { return dtype == DT_BF16 ? 64 : 32; }
+
+template <typename T, int TO>
+__global__ __launch_bounds__(256) void conv_wgrad_kernel(const GemmBatch batch) {
+  using E = CT<T>;
+  constexpr int TC = 128, VEC = E::VEC, MB = WgSlab<T>::MB;
+  constexpr int PAD = (sizeof(T) == 2) ? 4 : 4;
+  constexpr int PD = TO + PAD, PX = TC + PAD;  // LDS pitches (elements)
+  constexpr int WAVES_O = TO / 64;             // 1 or 2
+  constexpr int WAVES_C = 4 / WAVES_O;         // 4 or 2
+  constexpr int WTC = TC / WAVES_C;            // 32 or 64 columns per wave
+  constexpr int NI = WTC / 32;                 // 1 or 2
+  __shared__ __attribute__((aligned(16))) T Ds[MB * PD];
+  __shared__ __attribute__((aligned(16))) T Xs[MB * PX];
+  __shared__ int pos_base[WG_MAX_SLABS * MB];
+  __shared__ int pos_hw[WG_MAX_SLABS * MB];
+
+  const int tile = (int)blockIdx.x;
+  const GemmProb& P = batch.p[cfind_problem(batch, tile)];
+  int local = tile - P.tile_begin;
+  const int split = local % P.splits;
+  local /= P.splits;
+  const int tc = local % P.tiles_n, to = local / P.tiles_n;
+  const int o0 = to * TO, col0 = tc * TC;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wo = wave / WAVES_C, wc = wave % WAVES_C;
+  const int Cout = P.M, Ncol = P.N, Mpos = P.K;
+  const ConvGeom g = P.g;
+  const bool gather = P.b_mode == OP_CONV_WGRAD;
+  const int Cin = gather ? g.C : P.ldb;
+
+  const int nslab_total = (Mpos + MB - 1) / MB;
+  const int per = (nslab_total + P.splits - 1) / P.splits;
+  const int s0 = split * per, s1 = min(nslab_total, s0 + per);
+  if (s0 >= s1) return;
+  const int m_begin = s0 * MB, m_count = min(Mpos, s1 * MB) - m_begin;
+
+  // position table: element offset of x[b][oh*s-p][ow*s-p][0] and the packed (ih0, iw0)
+  for (int q = tid; q < (s1 - s0) * MB; q += 256) {
+    int base = 0, hw = (int)0x80008000u;  // (ih0, iw0) = (-32768, -32768): every tap out of range
+    if (q < m_count) {
+      const int m = m_begin + q;
+      if (gather) {
+        const int b = m / (g.OH * g.OW);
+        const int rem = m - b * (g.OH * g.OW);
+        const int oh = rem / g.OW, ow = rem - oh * g.OW;
+        const int ih0 = oh * g.stride - g.pad, iw0 = ow * g.stride - g.pad;
+        base = ((b * g.H + ih0) * g.W + iw0) * g.C;
+        hw = (int)(((unsigned)(ih0 & 0xffff) << 16) | (unsigned)(iw0 & 0xffff));
+      } else {
+        base = m * P.ldb;
+        hw = 0;
+      }
+    }
+    pos_base[q] = base;
+    pos_hw[q] = hw;
+  }
+
+  // this thread's chunks: dy columns (o) and x columns (tap, c) are fixed, rows advance
+  constexpr int DCH = TO / VEC, XCH = TC / VEC;  // chunks per staged row
+  constexpr int ND = MB * DCH / 256, NX = MB * XCH / 256;
+  const int d_c = (tid % DCH) * VEC, d_m = tid / DCH;   // rows d_m + i * (256 / DCH)
+  const int x_c = (tid % XCH) * VEC, x_m = tid / XCH;   // rows x_m + i * (256 / XCH)
+  const int xcol = col0 + x_c;
+  int x_kh = 0, x_kw = 0, x_delta = 0;
+  const bool xcol_ok = xcol < Ncol;
+  if (xcol_ok) {
+    const int tap = xcol / Cin, c = xcol - tap * Cin;
+    if (gather) {
+      x_kh = tap / g.KW;
+      x_kw = tap - x_kh * g.KW;
+      x_delta = (x_kh * g.W + x_kw) * g.C + c;
+    } else {
+      x_delta = c;
+    }
+  }
+  const T* __restrict__ Dp = static_cast<const T*>(P.A);
+  const T* __restrict__ Xp = static_cast<const T*>(P.B);
+  const bool dcol_ok = o0 + d_c < Cout;  // Cout is a multiple of VEC on this path
+
+  uint4 rd[ND], rx[NX];
+  auto fetch = [&](int s) {  // s = slab index relative to s0; positions s*MB .. s*MB+MB-1 of the table
+#pragma unroll
+    for (int i = 0; i < ND; ++i) {
+      const int q = s * MB + d_m + i * (256 / DCH);
+      rd[i] = (dcol_ok && q < m_count) ? *reinterpret_cast<const uint4*>(Dp + (int64_t)(m_begin + q) * P.lda + o0 + d_c)
+                                       : make_uint4(0, 0, 0, 0);
+    }
+#pragma unroll
+    for (int i = 0; i < NX; ++i) {
+      const int q = s * MB + x_m + i * (256 / XCH);
+      const int hw = pos_hw[q];
+      const int ih = (hw >> 16) + x_kh, iw = (int)(short)(hw & 0xffff) + x_kw;
+      const bool ok = xcol_ok && (!gather || (ih >= 0 && ih < g.H && iw >= 0 && iw < g.W)) && hw != (int)0x80008000u;
+      rx[i] = ok ? *reinterpret_cast<const uint4*>(Xp + pos_base[q] + x_delta) : make_uint4(0, 0, 0, 0);
+    }
+  };
+
+  cv16f acc[2][NI];
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int j = 0; j < NI; ++j)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+  float bsum = 0.f;
+  const bool do_beta = (tc == 0) && P.aux3 != nullptr && tid < TO;
+
+  __syncthreads();  // position table complete
+  fetch(0);
+  const int nslab = s1 - s0;
+  for (int s = 0; s < nslab; ++s) {
+    if (s > 0) __syncthreads();
+#pragma unroll
+    for (int i = 0; i < ND; ++i) {
+      CChunk<T> c;
+      c.v = rd[i];
+      uint2* dst = reinterpret_cast<uint2*>(Ds + (d_m + i * (256 / DCH)) * PD + d_c);
+      dst[0] = c.h[0];
+      dst[1] = c.h[1];
+    }
+#pragma unroll
+    for (int i = 0; i < NX; ++i) {
+      CChunk<T> c;
+      c.v = rx[i];
+      uint2* dst = reinterpret_cast<uint2*>(Xs + (x_m + i * (256 / XCH)) * PX + x_c);
+      dst[0] = c.h[0];
+      dst[1] = c.h[1];
+    }
+    __syncthreads();
+    if (s + 1 < nslab) fetch(s + 1);
+    const int gq = lane >> 5, l31 = lane & 31;
+    if constexpr (sizeof(T) == 2) {
+#pragma unroll
+      for (int kk = 0; kk < MB; kk += 16) {
+        const int mb = kk + 8 * gq;
+        uint4 a[2], b[NI];
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+          const T* p = Ds + mb * PD + wo * 64 + i * 32 + l31;
+          a[i] = make_uint4((uint32_t)p[0] | ((uint32_t)p[PD] << 16), (uint32_t)p[2 * PD] | ((uint32_t)p[3 * PD] << 16),
+                            (uint32_t)p[4 * PD] | ((uint32_t)p[5 * PD] << 16), (uint32_t)p[6 * PD] | ((uint32_t)p[7 * PD] << 16));
+        }
+#pragma unroll
+        for (int j = 0; j < NI; ++j) {
+          const T* p = Xs + mb * PX + wc * WTC + j * 32 + l31;
+          b[j] = make_uint4((uint32_t)p[0] | ((uint32_t)p[PX] << 16), (uint32_t)p[2 * PX] | ((uint32_t)p[3 * PX] << 16),
+                            (uint32_t)p[4 * PX] | ((uint32_t)p[5 * PX] << 16), (uint32_t)p[6 * PX] | ((uint32_t)p[7 * PX] << 16));
+        }
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+#pragma unroll
+          for (int j = 0; j < NI; ++j) acc[i][j] = cmfma_bf16(a[i], b[j], acc[i][j]);
+      }
+    } else {
+#pragma unroll 8
+      for (int kk = 0; kk < MB; kk += 2) {
+        float a[2], b[NI];
+#pragma unroll
+        for (int i = 0; i < 2; ++i) a[i] = Ds[(kk + gq) * PD + wo * 64 + i * 32 + l31];
+#pragma unroll
+        for (int j = 0; j < NI; ++j) b[j] = Xs[(kk + gq) * PX + wc * WTC + j * 32 + l31];
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+#pragma unroll
+          for (int j = 0; j < NI; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[i], b[j], acc[i][j], 0, 0, 0);
+      }
+    }
+    if (do_beta)
+      for (int m = 0; m < MB; ++m) bsum += E::to_f32(Ds[m * PD + tid]);
+  }
+
+  // epilogue: acc rows = o, cols = (tap, c)
+  float* __restrict__ G = static_cast<float*>(P.out);
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+      const int r = o0 + wo * 64 + i * 32 + (v >> 2) * 8 + (lane >> 5) * 4 + (v & 3);
+      const bool rok = r < Cout;
+      const float gam = (rok && P.aux0) ? static_cast<const float*>(P.aux0)[r] : 1.f;
+      float gsum = 0.f;
+#pragma unroll
+      for (int j = 0; j < NI; ++j) {
+        const int c = col0 + wc * WTC + j * 32 + (lane & 31);
+        if (!rok || c >= Ncol) continue;
+        const float val = acc[i][j][v];
+        const int64_t o = (int64_t)r * P.ldo + c;
+        if (P.aux1) gsum += val * E::to_f32(static_cast<const T*>(P.aux1)[o]);
+        atomicAdd(G + o, gam * val);
+      }
+      if (P.aux2 != nullptr) {
+#pragma unroll
+        for (int off = 16; off >= 1; off >>= 1) gsum += __shfl_xor(gsum, off, 64);
+        if ((lane & 31) == 0 && rok) atomicAdd(static_cast<float*>(P.aux2) + r, gsum);
+      }
+    }
+  if (do_beta && o0 + tid < Cout) atomicAdd(static_cast<float*>(P.aux3) + o0 + tid, bsum);
+}
+
+// ---------------------------------------------------------------------------------
+bool conv_fast_eligible(const GemmProb& p, int dtype) {
+  const int bk = dtype == DT_BF16 ? 32 : 16, vec = dtype == DT_BF16 ? 8 : 4;
+  if (p.epi == EPI_WGRAD) {
+    if (p.a_mode != OP_PLAIN_R || !(p.flags & GF_ATOMIC)) return false;
+    if (p.b_mode == OP_CONV_WGRAD) {
+      if (p.g.C % vec || p.g.KH * p.g.KW > 32 || p.g.H >= 32768 || p.g.W >= 32768) return false;
+    } else if (p.b_mode == OP_PLAIN_R) {
+      if (p.ldb % vec || p.N != p.ldb) return false;
+    } else {
+      return false;
+    }
+    return (p.M % vec) == 0 && (p.lda % vec) == 0;
+  }
+  if (p.b_mode != OP_PLAIN_K || p.ldb != p.K || (p.K % bk)) return false;
+  if (p.a_mode == OP_PLAIN_K) return p.lda == p.K;
+  if (p.a_mode == OP_CONV_FWD || p.a_mode == OP_CONV_DGRAD) return (p.g.C % bk) == 0 && p.g.KH * p.g.KW <= 32;
+  return false;
+}
+
+hipError_t launch_conv_gemm(GemmBatch& b, int dtype, bool wide, hipStream_t stream) {
+  if (b.n <= 0) return hipSuccess;
+  if (b.n > GEMM_MAX_PROBS) return hipErrorInvalidValue;
+  const int bn = wide ? 128 : 64;
+  int total = 0;
+  for (int i = 0; i < b.n; ++i) {
+    GemmProb& p = b.p[i];
+    if (p.M <= 0 || p.N <= 0 || p.K <= 0 || p.epi == EPI_WGRAD || !conv_fast_eligible(p, dtype)) return hipErrorInvalidValue;
+    p.splits = 1;
+    p.tiles_n = (p.N + bn - 1) / bn;
+    p.tile_begin = total;
+    total += ((p.M + 127) / 128) * p.tiles_n;
+  }
+  b.total_tiles = total;
+  dim3 grid(total), block(256);
+  if (dtype == DT_BF16) {
+    if (wide) hipLaunchKernelGGL((conv_gemm_kernel<uint16_t, 128>), grid, block, 0, stream, b);
+    else hipLaunchKernelGGL((conv_gemm_kernel<uint16_t, 64>), grid, block, 0, stream, b);
+  } else {
+    if (wide) hipLaunchKernelGGL((conv_gemm_kernel<float, 128>), grid, block, 0, stream, b);
+    else hipLaunchKernelGGL((conv_gemm_kernel<float, 64>), grid, block, 0, stream, b);
+  }
+  return hipGetLastError();
+}
+
+hipError_t launch_conv_wgrad(GemmBatch& b, int dtype, bool wide, hipStream_t stream) {
+  if (b.n <= 0) return hipSuccess;
+  if (b.n > GEMM_MAX_PROBS) return hipErrorInvalidValue;
+  const int to = wide ? 128 : 64;
+  int total = 0;
+  for (int i = 0; i < b.n; ++i) {
+    GemmProb& p = b.p[i];
+    if (p.M <= 0 || p.N <= 0 || p.K <= 0 || p.epi != EPI_WGRAD || !conv_fast_eligible(p, dtype)) return hipErrorInvalidValue;
+    const int nslab = (p.K + wg_slab(dtype) - 1) / wg_slab(dtype);
+    const int min_splits = (nslab + WG_MAX_SLABS - 1) / WG_MAX_SLABS;
+    if (p.splits < min_splits) p.splits = min_splits;
+    if (p.splits > nslab) p.splits = nslab;
+    p.tiles_n = (p.N + 127) / 128;
+    p.tile_begin = total;
+    total += ((p.M + to - 1) / to) * p.tiles_n * p.splits;
+  }
+  b.total_tiles = total;
+  dim3 grid(total), block(256);
+  if (dtype == DT_BF16) {
+    if (wide) hipLaunchKernelGGL((conv_wgrad_kernel<uint16_t, 128>), grid, block, 0, stream, b);
+    else hipLaunchKernelGGL((conv_wgrad_kernel<uint16_t, 64>), grid, block, 0, stream, b);
+  } else {
+    if (wide) hipLaunchKernelGGL((conv_wgrad_kernel<float, 128>), grid, block, 0, stream, b);
+    else hipLaunchKernelGGL((conv_wgrad_kernel<float, 64>), grid, block, 0, stream, b);
+  }
+  return hipGetLastError();
+}
+
+}  // namespace cdp

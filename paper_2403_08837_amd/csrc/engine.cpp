@@ -240,11 +240,18 @@ GemmProb wgrad_prob(const cdp_ctx* c, const Op& o, const void* dz, const void* x
     // accumulators of conv weights are kept zeroed by the update kernel; split the long
     // reduction over output positions and add atomically
     p.flags = GF_ATOMIC;
-    const int tiles = ((p.M + 127) / 128) * ((p.N + 127) / 128);
-    const int ktiles = (p.K + 31) / 32;
-    int splits = std::max(1, std::min((1024 + tiles - 1) / tiles, ktiles / 8));
-    p.splits = std::min(splits, 256);
     if (o.has_gamma) { p.aux0 = slot + o.gamma_c; p.aux1 = slot + o.wp; p.aux2 = G + o.g_off; }
+    if (conv_fast_eligible(p, c->plan.dtype)) {
+      const int to = p.M >= 128 ? 128 : 64;
+      const int tiles = ((p.M + to - 1) / to) * ((p.N + 127) / 128);
+      const int nslab = (p.K + 63) / 64;
+      p.splits = std::max(1, std::min((1536 + tiles - 1) / tiles, std::max(1, nslab / 2)));
+      if (o.b_off >= 0) p.aux3 = G + o.b_off;  // d beta is folded into the weight-gradient kernel
+    } else {
+      const int tiles = ((p.M + 127) / 128) * ((p.N + 127) / 128);
+      const int ktiles = (p.K + 31) / 32;
+      p.splits = std::min(std::max(1, std::min((1024 + tiles - 1) / tiles, ktiles / 8)), 256);
+    }
   } else {
     p.flags = first ? 0 : GF_ACCUM;
     if (o.b_off >= 0) p.aux2 = G + o.b_off;  // bias gradient is folded into the weight-gradient kernel
@@ -266,7 +273,10 @@ void op_work(const cdp_ctx* c, const Op& o, int pass, bool rmw, bool extra_in, I
 }
 
 // Launch class of a contraction: which kernel family and tile shape runs it.
-enum LaunchClass { LC_SKINNY_64 = 0, LC_SKINNY_128, LC_LINEAR_DW, LC_GEN_FIRST };  // LC_GEN_FIRST + 2*shape + wgrad
+enum LaunchClass {
+  LC_SKINNY_64 = 0, LC_SKINNY_128, LC_LINEAR_DW, LC_CONV_64, LC_CONV_128, LC_CWGRAD_64, LC_CWGRAD_128,
+  LC_GEN_FIRST  // LC_GEN_FIRST + 2*shape + wgrad
+};
 
 int launch_class(const GemmProb& p, int dtype) {
   (void)dtype;
@@ -274,6 +284,10 @@ int launch_class(const GemmProb& p, int dtype) {
     return p.N >= 2048 ? LC_SKINNY_128 : LC_SKINNY_64;
   if (p.epi == EPI_WGRAD && p.a_mode == OP_PLAIN_R && p.b_mode == OP_PLAIN_R && !(p.flags & GF_ATOMIC) && !p.aux0 && !p.aux1)
     return LC_LINEAR_DW;
+  if (conv_fast_eligible(p, dtype)) {
+    if (p.epi == EPI_WGRAD) return p.M >= 128 ? LC_CWGRAD_128 : LC_CWGRAD_64;
+    return p.N > 64 ? LC_CONV_128 : LC_CONV_64;
+  }
   int shape;
   if (p.M <= 64) shape = p.N >= 128 ? TILE_64x128 : TILE_64x64;
   else shape = p.N <= 64 ? TILE_64x64 : TILE_128x128;
@@ -399,7 +413,7 @@ int build_backward(cdp_ctx* c, int i, int j, Program* prog, bool first_grad) {
       w.g = wgrad_prob(c, o, dz, xin, slot, G, first_grad);
       op_work(c, o, 2, o.is_conv || !first_grad, false, &w);
       at(level).push_back(w);
-      if (o.b_off >= 0 && o.is_conv) {
+      if (o.b_off >= 0 && o.is_conv && w.g.aux3 == nullptr) {
         Item b; b.kind = IT_COLSUM;
         b.c.src = dz; b.c.out = G + o.b_off; b.c.rows = c->B * o.Hout * o.Wout; b.c.cols = o.Cout; b.c.ld = o.Cout;
         at(level).push_back(b);
@@ -459,6 +473,8 @@ int launch_level(cdp_ctx* c, std::vector<Item>& items) {
       }
       if (key == LC_SKINNY_64 || key == LC_SKINNY_128) HIP_TRY(c, launch_linear_skinny(batch, c->plan.dtype, key == LC_SKINNY_128, c->stream));
       else if (key == LC_LINEAR_DW) HIP_TRY(c, launch_linear_dw(batch, c->plan.dtype, c->stream));
+      else if (key == LC_CONV_64 || key == LC_CONV_128) HIP_TRY(c, launch_conv_gemm(batch, c->plan.dtype, key == LC_CONV_128, c->stream));
+      else if (key == LC_CWGRAD_64 || key == LC_CWGRAD_128) HIP_TRY(c, launch_conv_wgrad(batch, c->plan.dtype, key == LC_CWGRAD_128, c->stream));
       else HIP_TRY(c, launch_gemm_batch(batch, c->plan.dtype, (key - LC_GEN_FIRST) / 2, c->stream));
       if (timed) {
         HIP_TRY(c, hipEventRecord(pr.b, c->stream));

@@ -41,6 +41,7 @@ struct GemmProb {
   const void* aux0;  // FWD: bias f32[c]   DGRAD: add T[r][c]      WGRAD: gamma f32[r]
   const void* aux1;  // FWD: res T[r][c]   DGRAD: mask T[r][c]     WGRAD: Wplain T[r][c]
   void* aux2;        //                                            WGRAD: Ggamma f32[r]
+  void* aux3;        //                                            WGRAD (conv fast path): Gbeta f32[r]
   int M, N, K;       // C is M x N, reduction length K
   int lda, ldb, ldo; // leading dims for plain operands / output / aux matrices
   int a_mode, b_mode;
@@ -77,6 +78,11 @@ hipError_t launch_gemm_batch(GemmBatch& batch, int dtype, int tile_shape, hipStr
 //           (same accumulate/overwrite rule).
 hipError_t launch_linear_skinny(GemmBatch& batch, int dtype, bool wide, hipStream_t stream);
 hipError_t launch_linear_dw(GemmBatch& batch, int dtype, hipStream_t stream);
+
+// Implicit-GEMM convolution fast paths (channel counts that are multiples of the slab).
+bool conv_fast_eligible(const GemmProb& p, int dtype);
+hipError_t launch_conv_gemm(GemmBatch& batch, int dtype, bool wide, hipStream_t stream);   // forward / data gradient
+hipError_t launch_conv_wgrad(GemmBatch& batch, int dtype, bool wide, hipStream_t stream);  // weight gradient (atomic)
 
 // ---------------------------------------------------------------------------------
 // small kernels

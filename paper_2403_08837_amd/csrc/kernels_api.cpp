@@ -62,8 +62,21 @@ int cdp_k_conv(int dtype, int which, const void* in0, const void* in1, void* out
   } else {
     return CDP_EINVAL;
   }
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  // same kernel choice as the engine: the fast implicit-GEMM paths where the shape allows
+  if (which == 2) {
+    p.flags = GF_ATOMIC;
+    if (conv_fast_eligible(p, dtype)) {
+      if (hipMemsetAsync(out, 0, (size_t)p.M * p.N * 4, st) != hipSuccess) return CDP_EHIP;
+      p.splits = 3;
+      return launch_conv_wgrad(b, dtype, p.M >= 128, st) == hipSuccess ? CDP_OK : CDP_EHIP;
+    }
+    p.flags = 0;
+  } else if (conv_fast_eligible(p, dtype)) {
+    return launch_conv_gemm(b, dtype, p.N > 64, st) == hipSuccess ? CDP_OK : CDP_EHIP;
+  }
   const int shape = p.M <= 64 ? (p.N >= 128 ? TILE_64x128 : TILE_64x64) : (p.N <= 64 ? TILE_64x64 : TILE_128x128);
-  return launch_gemm_batch(b, dtype, shape, static_cast<hipStream_t>(stream)) == hipSuccess ? CDP_OK : CDP_EHIP;
+  return launch_gemm_batch(b, dtype, shape, st) == hipSuccess ? CDP_OK : CDP_EHIP;
 }
 
 }  // extern "C"
