@@ -27,9 +27,13 @@ int cdp_k_gemm(int dtype, int tile_shape, int a_kmajor, int b_kmajor, const void
  *   which 0: forward        y[B][Ho][Wo][Cout] (elem type) = conv(x, w),  w[Cout][k][k][Cin]
  *         1: data gradient  dx[B][H][W][Cin]   (elem type) from dy and wt[Cin][k][k][Cout]
  *         2: weight gradient dw[Cout][k][k][Cin] (fp32, overwritten) from dy and x
- * in0/in1: (x, w) | (dy, wt) | (dy, x).  `out` must not alias the inputs. */
+ * in0/in1: (x, w) | (dy, wt) | (dy, x).  `out` must not alias the inputs.
+ * workspace (device, may be NULL): scratch for the split weight-gradient kernel; with at
+ * least 4 * Cout*k*k*Cin * (B*Ho*Wo / 512 + 4) bytes the two-phase path is used when the
+ * shape allows, otherwise the generic single-pass kernel runs. */
 int cdp_k_conv(int dtype, int which, const void* in0, const void* in1, void* out, int B, int H, int W,
-               int Cin, int Cout, int ksize, int stride, int pad, void* stream);
+               int Cin, int Cout, int ksize, int stride, int pad, void* workspace,
+               size_t workspace_bytes, void* stream);
 
 #ifdef __cplusplus
 }

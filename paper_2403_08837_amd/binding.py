@@ -88,7 +88,7 @@ def lib() -> C.CDLL:
         L.cdp_profile_gemm.argtypes = [vp, i32]
         L.cdp_get_gemm_profile.argtypes = [vp, C.POINTER(cdp_gemm_profile)]
         L.cdp_k_gemm.argtypes = [i32, i32, i32, i32, vp, vp, vp, i32, i32, i32, i32, i32, vp]
-        L.cdp_k_conv.argtypes = [i32, i32, vp, vp, vp, i32, i32, i32, i32, i32, i32, i32, i32, vp]
+        L.cdp_k_conv.argtypes = [i32, i32, vp, vp, vp, i32, i32, i32, i32, i32, i32, i32, i32, vp, sz, vp]
         for name in EXPORTS:
             if name not in ("cdp_last_error", "cdp_destroy"):
                 getattr(L, name).restype = C.c_int
@@ -221,8 +221,10 @@ def cdp_k_gemm(dtype, tile_shape, a_kmajor, b_kmajor, A_ptr, B_ptr, C_ptr, M, N,
         raise CdpError(rc, "cdp_k_gemm")
 
 
-def cdp_k_conv(dtype, which, in0_ptr, in1_ptr, out_ptr, B, H, W, Cin, Cout, ks, stride, pad, stream=0) -> None:
-    rc = lib().cdp_k_conv(dtype, which, in0_ptr, in1_ptr, out_ptr, B, H, W, Cin, Cout, ks, stride, pad, stream or None)
+def cdp_k_conv(dtype, which, in0_ptr, in1_ptr, out_ptr, B, H, W, Cin, Cout, ks, stride, pad, ws_ptr=0, ws_bytes=0,
+               stream=0) -> None:
+    rc = lib().cdp_k_conv(dtype, which, in0_ptr, in1_ptr, out_ptr, B, H, W, Cin, Cout, ks, stride, pad, ws_ptr or None,
+                          ws_bytes, stream or None)
     if rc != CDP_OK:
         raise CdpError(rc, "cdp_k_conv")
 

@@ -12,6 +12,8 @@
 //     accumulator); operands are staged as they lie in memory ([m][channels]) and MFMA
 //     fragments are read transposed out of LDS; the per-position address decode is done
 //     once per workgroup into an LDS table.  Also produces d gamma and d beta.
+#include <algorithm>
+
 #include "kernels.h"
 
 namespace cdp {
@@ -232,9 +234,10 @@ __global__ __launch_bounds__(256) void conv_gemm_kernel(const GemmBatch batch) {
 // weight gradient.  Batch entry convention (as for the generic kernel): A = dy [Mpos][Cout]
 // (OP_PLAIN_R, lda = Cout), B = x (OP_CONV_WGRAD geometry, or OP_PLAIN_R with ldb = Cin for a
 // 1x1/stride-1 layer), out = G [Cout][taps*Cin] (ldo = taps*Cin), P.M = Cout, P.N = taps*Cin,
-// P.K = Mpos, splits = number of reduction ranges.  aux0 = gamma f32[Cout] or NULL, aux1 = plain
-// weights T[Cout][taps*Cin] or NULL, aux2 = d gamma accumulator or NULL, aux3 = d beta
-// accumulator or NULL.  All accumulators receive fp32 atomic adds.
+// P.K = Mpos, splits = number of reduction ranges.  Each range writes its partial tile with plain
+// stores: out = partial sums f32 [splits][Cout][taps*Cin], aux3 = partial column sums of dy
+// f32 [splits][Cout] or NULL.  wgrad_reduce_kernel folds the partials into the accumulators
+// (device-wide atomics on a small hot array are an order of magnitude slower than this).
 constexpr int WG_MAX_SLABS = 16;  // slabs per workgroup (bounds the LDS position table)
 template <typename T> struct WgSlab { static constexpr int MB = sizeof(T) == 2 ? 64 : 32; };  // positions per slab
 static inline int wg_slab(int dtype) { return dtype == DT_BF16 ? 64 : 32; }
@@ -271,11 +274,11 @@ __global__ __launch_bounds__(256) void conv_wgrad_kernel(const GemmBatch batch) 
   const int nslab_total = (Mpos + MB - 1) / MB;
   const int per = (nslab_total + P.splits - 1) / P.splits;
   const int s0 = split * per, s1 = min(nslab_total, s0 + per);
-  if (s0 >= s1) return;
-  const int m_begin = s0 * MB, m_count = min(Mpos, s1 * MB) - m_begin;
+  const int nslab = max(0, s1 - s0);  // an empty range still writes its (zero) partial tile
+  const int m_begin = s0 * MB, m_count = max(0, min(Mpos, s1 * MB) - m_begin);
 
   // position table: element offset of x[b][oh*s-p][ow*s-p][0] and the packed (ih0, iw0)
-  for (int q = tid; q < (s1 - s0) * MB; q += 256) {
+  for (int q = tid; q < nslab * MB; q += 256) {
     int base = 0, hw = (int)0x80008000u;  // (ih0, iw0) = (-32768, -32768): every tap out of range
     if (q < m_count) {
       const int m = m_begin + q;
@@ -346,8 +349,7 @@ __global__ __launch_bounds__(256) void conv_wgrad_kernel(const GemmBatch batch) 
   const bool do_beta = (tc == 0) && P.aux3 != nullptr && tid < TO;
 
   __syncthreads();  // position table complete
-  fetch(0);
-  const int nslab = s1 - s0;
+  if (nslab > 0) fetch(0);
   for (int s = 0; s < nslab; ++s) {
     if (s > 0) __syncthreads();
 #pragma unroll
@@ -409,39 +411,78 @@ __global__ __launch_bounds__(256) void conv_wgrad_kernel(const GemmBatch batch) 
       for (int m = 0; m < MB; ++m) bsum += E::to_f32(Ds[m * PD + tid]);
   }
 
-  // epilogue: acc rows = o, cols = (tap, c)
-  float* __restrict__ G = static_cast<float*>(P.out);
+  // epilogue: acc rows = o, cols = (tap, c); plain stores into this range's partial buffer
+  float* __restrict__ part = static_cast<float*>(P.out) + (int64_t)split * Cout * Ncol;
 #pragma unroll
   for (int i = 0; i < 2; ++i)
 #pragma unroll
     for (int v = 0; v < 16; ++v) {
       const int r = o0 + wo * 64 + i * 32 + (v >> 2) * 8 + (lane >> 5) * 4 + (v & 3);
-      const bool rok = r < Cout;
-      const float gam = (rok && P.aux0) ? static_cast<const float*>(P.aux0)[r] : 1.f;
-      float gsum = 0.f;
+      if (r >= Cout) continue;
 #pragma unroll
       for (int j = 0; j < NI; ++j) {
         const int c = col0 + wc * WTC + j * 32 + (lane & 31);
-        if (!rok || c >= Ncol) continue;
-        const float val = acc[i][j][v];
-        const int64_t o = (int64_t)r * P.ldo + c;
-        if (P.aux1) gsum += val * E::to_f32(static_cast<const T*>(P.aux1)[o]);
-        atomicAdd(G + o, gam * val);
-      }
-      if (P.aux2 != nullptr) {
-#pragma unroll
-        for (int off = 16; off >= 1; off >>= 1) gsum += __shfl_xor(gsum, off, 64);
-        if ((lane & 31) == 0 && rok) atomicAdd(static_cast<float*>(P.aux2) + r, gsum);
+        if (c < Ncol) part[(int64_t)r * Ncol + c] = acc[i][j][v];
       }
     }
-  if (do_beta && o0 + tid < Cout) atomicAdd(static_cast<float*>(P.aux3) + o0 + tid, bsum);
+  if (do_beta && o0 + tid < Cout) static_cast<float*>(P.aux3)[(int64_t)split * Cout + o0 + tid] = bsum;
+}
+
+// One workgroup per weight row o:  s[c] = sum_ranges part[.][o][c];  G[o][c] += gamma[o]*s[c];
+// d gamma[o] += sum_c s[c]*Wplain[o][c];  d beta[o] += sum_ranges part_beta[.][o].
+template <typename T>
+__global__ __launch_bounds__(256) void wgrad_reduce_kernel(const WReduceBatch batch) {
+  using E = CT<T>;
+  __shared__ float red[4];
+  const WReduceProb& P = batch.p[blockIdx.y];
+  const int o = blockIdx.x;
+  if (o >= P.Cout) return;
+  const float gam = P.gamma ? P.gamma[o] : 1.f;
+  const int64_t row = (int64_t)o * P.Ncol, stride = (int64_t)P.Cout * P.Ncol;
+  const T* wp = static_cast<const T*>(P.wplain);
+  float dg = 0.f;
+  for (int c = threadIdx.x; c < P.Ncol; c += 256) {
+    float sum = 0.f;
+    for (int q = 0; q < P.splits; ++q) sum += P.part[q * stride + row + c];
+    P.G[row + c] += gam * sum;
+    if (wp) dg += sum * E::to_f32(wp[row + c]);
+  }
+  if (P.Ggamma) {
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) dg += __shfl_xor(dg, off, 64);
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = dg;
+    __syncthreads();
+    if (threadIdx.x == 0) P.Ggamma[o] += red[0] + red[1] + red[2] + red[3];
+  }
+  if (P.Gbeta && threadIdx.x == 64) {
+    float sb = 0.f;
+    for (int q = 0; q < P.splits; ++q) sb += P.part_beta[(int64_t)q * P.Cout + o];
+    P.Gbeta[o] += sb;
+  }
+}
+
+hipError_t launch_wgrad_reduce(const WReduceBatch& b, int dtype, hipStream_t stream) {
+  if (b.n <= 0) return hipSuccess;
+  if (b.n > WREDUCE_MAX_PROBS) return hipErrorInvalidValue;
+  int rows = 1;
+  for (int i = 0; i < b.n; ++i) rows = max(rows, b.p[i].Cout);
+  dim3 grid(rows, b.n), block(256);
+  if (dtype == DT_BF16) hipLaunchKernelGGL((wgrad_reduce_kernel<uint16_t>), grid, block, 0, stream, b);
+  else hipLaunchKernelGGL((wgrad_reduce_kernel<float>), grid, block, 0, stream, b);
+  return hipGetLastError();
+}
+
+int conv_wgrad_splits(const GemmProb& p, int dtype, int wanted) {
+  const int nslab = (p.K + wg_slab(dtype) - 1) / wg_slab(dtype);
+  const int min_splits = (nslab + WG_MAX_SLABS - 1) / WG_MAX_SLABS;
+  return std::max(1, std::min(nslab, std::max(wanted, min_splits)));
 }
 
 // ---------------------------------------------------------------------------------
 bool conv_fast_eligible(const GemmProb& p, int dtype) {
   const int bk = dtype == DT_BF16 ? 32 : 16, vec = dtype == DT_BF16 ? 8 : 4;
   if (p.epi == EPI_WGRAD) {
-    if (p.a_mode != OP_PLAIN_R || !(p.flags & GF_ATOMIC)) return false;
+    if (p.a_mode != OP_PLAIN_R) return false;
     if (p.b_mode == OP_CONV_WGRAD) {
       if (p.g.C % vec || p.g.KH * p.g.KW > 32 || p.g.H >= 32768 || p.g.W >= 32768) return false;
     } else if (p.b_mode == OP_PLAIN_R) {
@@ -490,10 +531,7 @@ hipError_t launch_conv_wgrad(GemmBatch& b, int dtype, bool wide, hipStream_t str
   for (int i = 0; i < b.n; ++i) {
     GemmProb& p = b.p[i];
     if (p.M <= 0 || p.N <= 0 || p.K <= 0 || p.epi != EPI_WGRAD || !conv_fast_eligible(p, dtype)) return hipErrorInvalidValue;
-    const int nslab = (p.K + wg_slab(dtype) - 1) / wg_slab(dtype);
-    const int min_splits = (nslab + WG_MAX_SLABS - 1) / WG_MAX_SLABS;
-    if (p.splits < min_splits) p.splits = min_splits;
-    if (p.splits > nslab) p.splits = nslab;
+    if (p.splits != conv_wgrad_splits(p, dtype, p.splits)) return hipErrorInvalidValue;  // caller sized the partial buffer
     p.tiles_n = (p.N + 127) / 128;
     p.tile_begin = total;
     total += ((p.M + to - 1) / to) * p.tiles_n * p.splits;

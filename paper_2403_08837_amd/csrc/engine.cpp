@@ -81,11 +81,12 @@ struct StageState {
   int ring_ver[2] = {0, 0};
 };
 
-enum ItemKind { IT_GEMM, IT_COLSUM, IT_STAGE_IN, IT_CE, IT_MAXPOOL_F, IT_MAXPOOL_B, IT_GAP_F, IT_GAP_B };
+enum ItemKind { IT_GEMM, IT_COLSUM, IT_WREDUCE, IT_STAGE_IN, IT_CE, IT_MAXPOOL_F, IT_MAXPOOL_B, IT_GAP_F, IT_GAP_B };
 struct Item {
   int kind;
   GemmProb g;
   ColsumProb c;
+  WReduceProb r;
   const void* p0 = nullptr; const void* p1 = nullptr; void* p2 = nullptr; void* p3 = nullptr; void* p4 = nullptr;
   int64_t n0 = 0;
   int i[10] = {0};
@@ -237,16 +238,15 @@ GemmProb wgrad_prob(const cdp_ctx* c, const Op& o, const void* dz, const void* x
   p.out = G + o.w_off; p.ldo = (int)o.K();
   p.epi = EPI_WGRAD;
   if (o.is_conv) {
-    // accumulators of conv weights are kept zeroed by the update kernel; split the long
-    // reduction over output positions and add atomically
+    // accumulators of conv weights are kept zeroed by the update kernel; the long reduction
+    // over output positions is split across workgroups
     p.flags = GF_ATOMIC;
     if (o.has_gamma) { p.aux0 = slot + o.gamma_c; p.aux1 = slot + o.wp; p.aux2 = G + o.g_off; }
     if (conv_fast_eligible(p, c->plan.dtype)) {
+      // two-phase path: build_backward points out / aux3 at a partial-sum workspace
       const int to = p.M >= 128 ? 128 : 64;
       const int tiles = ((p.M + to - 1) / to) * ((p.N + 127) / 128);
-      const int nslab = (p.K + 63) / 64;
-      p.splits = std::max(1, std::min((1536 + tiles - 1) / tiles, std::max(1, nslab / 2)));
-      if (o.b_off >= 0) p.aux3 = G + o.b_off;  // d beta is folded into the weight-gradient kernel
+      p.splits = conv_wgrad_splits(p, c->plan.dtype, (1024 + tiles - 1) / tiles);
     } else {
       const int tiles = ((p.M + 127) / 128) * ((p.N + 127) / 128);
       const int ktiles = (p.K + 31) / 32;
@@ -412,8 +412,26 @@ int build_backward(cdp_ctx* c, int i, int j, Program* prog, bool first_grad) {
       Item w; w.kind = IT_GEMM;
       w.g = wgrad_prob(c, o, dz, xin, slot, G, first_grad);
       op_work(c, o, 2, o.is_conv || !first_grad, false, &w);
+      bool two_phase = false;
+      if (o.is_conv && conv_fast_eligible(w.g, c->plan.dtype)) {
+        // partial sums of every reduction range, folded into the accumulators one level later
+        two_phase = true;
+        const int64_t wn = (int64_t)w.g.splits * o.w_count(), bn = (int64_t)w.g.splits * o.Cout;
+        Block ws;
+        if (!pool_alloc(c, (wn + bn) * 4, &ws)) return fail(c, CDP_ENOMEM, "activation pool exhausted");
+        c->deferred.push_back(ws);
+        float* part = c->fptr(ws.off);
+        Item rd; rd.kind = IT_WREDUCE;
+        rd.r.part = part; rd.r.part_beta = o.b_off >= 0 ? part + wn : nullptr;
+        rd.r.G = G + o.w_off; rd.r.Ggamma = o.has_gamma ? G + o.g_off : nullptr; rd.r.Gbeta = o.b_off >= 0 ? G + o.b_off : nullptr;
+        rd.r.gamma = static_cast<const float*>(w.g.aux0); rd.r.wplain = w.g.aux1;
+        rd.r.Cout = o.Cout; rd.r.Ncol = (int)o.K(); rd.r.splits = w.g.splits;
+        w.g.out = part; w.g.aux0 = nullptr; w.g.aux1 = nullptr; w.g.aux2 = nullptr;
+        w.g.aux3 = o.b_off >= 0 ? part + wn : nullptr;
+        at(level + 1).push_back(rd);
+      }
       at(level).push_back(w);
-      if (o.b_off >= 0 && o.is_conv && w.g.aux3 == nullptr) {
+      if (o.b_off >= 0 && o.is_conv && !two_phase) {
         Item b; b.kind = IT_COLSUM;
         b.c.src = dz; b.c.out = G + o.b_off; b.c.rows = c->B * o.Hout * o.Wout; b.c.cols = o.Cout; b.c.ld = o.Cout;
         at(level).push_back(b);
@@ -496,6 +514,21 @@ int launch_level(cdp_ctx* c, std::vector<Item>& items) {
   }
   if (cb.n) {
     HIP_TRY(c, launch_colsum_batch(cb, c->plan.dtype, c->stream));
+    c->stats.kernel_launches++;
+  }
+  WReduceBatch rb;
+  rb.n = 0;
+  for (const Item& it : items) {
+    if (it.kind != IT_WREDUCE) continue;
+    rb.p[rb.n++] = it.r;
+    if (rb.n == WREDUCE_MAX_PROBS) {
+      HIP_TRY(c, launch_wgrad_reduce(rb, c->plan.dtype, c->stream));
+      c->stats.kernel_launches++;
+      rb.n = 0;
+    }
+  }
+  if (rb.n) {
+    HIP_TRY(c, launch_wgrad_reduce(rb, c->plan.dtype, c->stream));
     c->stats.kernel_launches++;
   }
   const int dt = c->plan.dtype;

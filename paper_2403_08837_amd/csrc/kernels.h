@@ -41,7 +41,7 @@ struct GemmProb {
   const void* aux0;  // FWD: bias f32[c]   DGRAD: add T[r][c]      WGRAD: gamma f32[r]
   const void* aux1;  // FWD: res T[r][c]   DGRAD: mask T[r][c]     WGRAD: Wplain T[r][c]
   void* aux2;        //                                            WGRAD: Ggamma f32[r]
-  void* aux3;        //                                            WGRAD (conv fast path): Gbeta f32[r]
+  void* aux3;        //                                            WGRAD (conv fast path): partial dy column sums
   int M, N, K;       // C is M x N, reduction length K
   int lda, ldb, ldo; // leading dims for plain operands / output / aux matrices
   int a_mode, b_mode;
@@ -82,7 +82,20 @@ hipError_t launch_linear_dw(GemmBatch& batch, int dtype, hipStream_t stream);
 // Implicit-GEMM convolution fast paths (channel counts that are multiples of the slab).
 bool conv_fast_eligible(const GemmProb& p, int dtype);
 hipError_t launch_conv_gemm(GemmBatch& batch, int dtype, bool wide, hipStream_t stream);   // forward / data gradient
-hipError_t launch_conv_wgrad(GemmBatch& batch, int dtype, bool wide, hipStream_t stream);  // weight gradient (atomic)
+// Weight gradient in two phases: launch_conv_wgrad writes per-range partial sums
+// (out = f32 [splits][Cout][Ncol], aux3 = f32 [splits][Cout] or NULL, splits fixed by
+// conv_wgrad_splits), launch_wgrad_reduce folds them into the accumulators.
+int conv_wgrad_splits(const GemmProb& p, int dtype, int wanted);
+hipError_t launch_conv_wgrad(GemmBatch& batch, int dtype, bool wide, hipStream_t stream);
+struct WReduceProb {
+  const float* part; const float* part_beta;  // partial sums [splits][Cout][Ncol], [splits][Cout]
+  float* G; float* Ggamma; float* Gbeta;      // accumulators (Ggamma / Gbeta may be NULL)
+  const float* gamma; const void* wplain;     // gamma f32[Cout], plain weights T[Cout][Ncol] (or NULL)
+  int Cout, Ncol, splits;
+};
+constexpr int WREDUCE_MAX_PROBS = 32;
+struct WReduceBatch { int n; WReduceProb p[WREDUCE_MAX_PROBS]; };
+hipError_t launch_wgrad_reduce(const WReduceBatch& b, int dtype, hipStream_t stream);
 
 // ---------------------------------------------------------------------------------
 // small kernels

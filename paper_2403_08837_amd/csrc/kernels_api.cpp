@@ -30,7 +30,7 @@ int cdp_k_gemm(int dtype, int tile_shape, int a_kmajor, int b_kmajor, const void
 }
 
 int cdp_k_conv(int dtype, int which, const void* in0, const void* in1, void* out, int B, int H, int W, int Cin, int Cout,
-               int ks, int stride, int pad, void* stream) {
+               int ks, int stride, int pad, void* workspace, size_t workspace_bytes, void* stream) {
   if (!in0 || !in1 || !out || B <= 0 || H <= 0 || W <= 0 || Cin <= 0 || Cout <= 0 || ks <= 0 || stride <= 0 || pad < 0)
     return CDP_EINVAL;
   if (dtype != DT_F32 && dtype != DT_BF16) return CDP_EINVAL;
@@ -65,13 +65,21 @@ int cdp_k_conv(int dtype, int which, const void* in0, const void* in1, void* out
   hipStream_t st = static_cast<hipStream_t>(stream);
   // same kernel choice as the engine: the fast implicit-GEMM paths where the shape allows
   if (which == 2) {
-    p.flags = GF_ATOMIC;
-    if (conv_fast_eligible(p, dtype)) {
-      if (hipMemsetAsync(out, 0, (size_t)p.M * p.N * 4, st) != hipSuccess) return CDP_EHIP;
-      p.splits = 3;
-      return launch_conv_wgrad(b, dtype, p.M >= 128, st) == hipSuccess ? CDP_OK : CDP_EHIP;
+    const int splits = conv_wgrad_splits(p, dtype, 3);
+    if (conv_fast_eligible(p, dtype) && workspace && workspace_bytes >= (size_t)splits * p.M * p.N * 4) {
+      // two phases as in the engine: partial sums per reduction range, then the fold
+      WReduceBatch rb;
+      memset(&rb, 0, sizeof(rb));
+      rb.n = 1;
+      rb.p[0].part = static_cast<const float*>(workspace);
+      rb.p[0].G = static_cast<float*>(out);
+      rb.p[0].Cout = p.M; rb.p[0].Ncol = p.N; rb.p[0].splits = splits;
+      p.out = workspace;
+      p.splits = splits;
+      if (launch_fill_f32(static_cast<float*>(out), (int64_t)p.M * p.N, 0.f, st) != hipSuccess) return CDP_EHIP;
+      if (launch_conv_wgrad(b, dtype, p.M >= 128, st) != hipSuccess) return CDP_EHIP;
+      return launch_wgrad_reduce(rb, dtype, st) == hipSuccess ? CDP_OK : CDP_EHIP;
     }
-    p.flags = 0;
   } else if (conv_fast_eligible(p, dtype)) {
     return launch_conv_gemm(b, dtype, p.N > 64, st) == hipSuccess ? CDP_OK : CDP_EHIP;
   }

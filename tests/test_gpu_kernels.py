@@ -82,9 +82,14 @@ def test_conv_passes_match_oracle(dtype, case):
     dxd = torch.full(x.shape, float("nan"), dtype=tdt, device="cuda")
     b.cdp_k_conv(dtype, 1, dyd.data_ptr(), wtd.data_ptr(), dxd.data_ptr(), B, H, W, Cin, Cout, ks, st, pad)
     dwd = torch.full(w.shape, float("nan"), dtype=torch.float32, device="cuda")
-    b.cdp_k_conv(dtype, 2, dyd.data_ptr(), xd.data_ptr(), dwd.data_ptr(), B, H, W, Cin, Cout, ks, st, pad)
+    ws = torch.full((w.size * (y.size // Cout // 1024 + 4),), float("nan"), dtype=torch.float32, device="cuda")
+    b.cdp_k_conv(dtype, 2, dyd.data_ptr(), xd.data_ptr(), dwd.data_ptr(), B, H, W, Cin, Cout, ks, st, pad,
+                 ws.data_ptr(), ws.numel() * 4)
+    dw2 = torch.full(w.shape, float("nan"), dtype=torch.float32, device="cuda")      # single-pass kernel, no workspace
+    b.cdp_k_conv(dtype, 2, dyd.data_ptr(), xd.data_ptr(), dw2.data_ptr(), B, H, W, Cin, Cout, ks, st, pad)
     torch.cuda.synchronize()
-    for name, got, ref, tol in (("fwd", yd, y, tol_out), ("dgrad", dxd, dx, tol_out), ("wgrad", dwd, dw, 1e-5)):
+    for name, got, ref, tol in (("fwd", yd, y, tol_out), ("dgrad", dxd, dx, tol_out), ("wgrad", dwd, dw, 1e-5),
+                                ("wgrad-1pass", dw2, dw, 1e-5)):
         g = got.float().cpu().numpy().astype(np.float64)
         assert np.isfinite(g).all(), name
         err = np.abs(g - ref).max() / max(1e-6, np.abs(ref).max())
