@@ -428,45 +428,59 @@ __global__ __launch_bounds__(256) void conv_wgrad_kernel(const GemmBatch batch) 
   if (do_beta && o0 + tid < Cout) static_cast<float*>(P.aux3)[(int64_t)split * Cout + o0 + tid] = bsum;
 }
 
-// One workgroup per weight row o:  s[c] = sum_ranges part[.][o][c];  G[o][c] += gamma[o]*s[c];
-// d gamma[o] += sum_c s[c]*Wplain[o][c];  d beta[o] += sum_ranges part_beta[.][o].
+// Fold of the partial sums.  Workgroup = 32 columns of one weight row o x 8 range groups:
+//   s[c] = sum_ranges part[.][o][c];  G[o][c] += gamma[o]*s[c];
+//   d gamma[o] += sum_c s[c]*Wplain[o][c]  (one atomic per 32 columns);
+//   d beta[o]  += sum_ranges part_beta[.][o]  (first column chunk only).
 template <typename T>
 __global__ __launch_bounds__(256) void wgrad_reduce_kernel(const WReduceBatch batch) {
   using E = CT<T>;
-  __shared__ float red[4];
-  const WReduceProb& P = batch.p[blockIdx.y];
-  const int o = blockIdx.x;
-  if (o >= P.Cout) return;
-  const float gam = P.gamma ? P.gamma[o] : 1.f;
+  __shared__ float red[8][33];
+  const WReduceProb& P = batch.p[blockIdx.z];
+  const int o = blockIdx.y, c0 = blockIdx.x * 32;
+  if (o >= P.Cout || c0 >= P.Ncol) return;
+  const int cl = threadIdx.x & 31, grp = threadIdx.x >> 5;
+  const int c = c0 + cl;
   const int64_t row = (int64_t)o * P.Ncol, stride = (int64_t)P.Cout * P.Ncol;
-  const T* wp = static_cast<const T*>(P.wplain);
-  float dg = 0.f;
-  for (int c = threadIdx.x; c < P.Ncol; c += 256) {
-    float sum = 0.f;
-    for (int q = 0; q < P.splits; ++q) sum += P.part[q * stride + row + c];
-    P.G[row + c] += gam * sum;
-    if (wp) dg += sum * E::to_f32(wp[row + c]);
-  }
-  if (P.Ggamma) {
+  float sum = 0.f;
+  if (c < P.Ncol)
+    for (int q = grp; q < P.splits; q += 8) sum += P.part[q * stride + row + c];
+  red[grp][cl] = sum;
+  __syncthreads();
+  if (grp == 0) {
+    float tot = 0.f;
 #pragma unroll
-    for (int off = 32; off >= 1; off >>= 1) dg += __shfl_xor(dg, off, 64);
-    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = dg;
-    __syncthreads();
-    if (threadIdx.x == 0) P.Ggamma[o] += red[0] + red[1] + red[2] + red[3];
-  }
-  if (P.Gbeta && threadIdx.x == 64) {
+    for (int k = 0; k < 8; ++k) tot += red[k][cl];
+    float dg = 0.f;
+    if (c < P.Ncol) {
+      const float gam = P.gamma ? P.gamma[o] : 1.f;
+      P.G[row + c] += gam * tot;
+      if (P.wplain) dg = tot * E::to_f32(static_cast<const T*>(P.wplain)[row + c]);
+    }
+    if (P.Ggamma) {  // lanes 0..31 of wavefront 0
+#pragma unroll
+      for (int off = 16; off >= 1; off >>= 1) dg += __shfl_xor(dg, off, 64);
+      if (cl == 0) atomicAdd(P.Ggamma + o, dg);
+    }
+  } else if (grp == 2 && c0 == 0 && P.Gbeta) {  // wavefront 1, lanes 0..31
     float sb = 0.f;
-    for (int q = 0; q < P.splits; ++q) sb += P.part_beta[(int64_t)q * P.Cout + o];
-    P.Gbeta[o] += sb;
+    for (int q = cl; q < P.splits; q += 32) sb += P.part_beta[(int64_t)q * P.Cout + o];
+#pragma unroll
+    for (int off = 16; off >= 1; off >>= 1) sb += __shfl_xor(sb, off, 64);
+    if (cl == 0) P.Gbeta[o] += sb;
   }
 }
 
 hipError_t launch_wgrad_reduce(const WReduceBatch& b, int dtype, hipStream_t stream) {
   if (b.n <= 0) return hipSuccess;
   if (b.n > WREDUCE_MAX_PROBS) return hipErrorInvalidValue;
-  int rows = 1;
-  for (int i = 0; i < b.n; ++i) rows = max(rows, b.p[i].Cout);
-  dim3 grid(rows, b.n), block(256);
+  int rows = 1, chunks = 1;
+  for (int i = 0; i < b.n; ++i) {
+    rows = max(rows, b.p[i].Cout);
+    chunks = max(chunks, (b.p[i].Ncol + 31) / 32);
+  }
+  if (rows > 65535) return hipErrorInvalidValue;
+  dim3 grid(chunks, rows, b.n), block(256);
   if (dtype == DT_BF16) hipLaunchKernelGGL((wgrad_reduce_kernel<uint16_t>), grid, block, 0, stream, b);
   else hipLaunchKernelGGL((wgrad_reduce_kernel<float>), grid, block, 0, stream, b);
   return hipGetLastError();
