@@ -62,17 +62,22 @@ __device__ __forceinline__ cv16f cmfma_bf16(uint4 a, uint4 b, cv16f c) {
 }  // namespace
 
 // ---------------------------------------------------------------------------------
-// forward / data gradient: 128 x BN tile, waves 2 x 2.
-template <typename T, int BN>
+// forward / data gradient: 128 x BN tile, waves 2 x 2, reduction slab BK (a divisor of the
+// channel count).  The epilogue goes through LDS so that results, residuals and masks move
+// as 16-byte vectors along the channel dimension.
+template <typename T, int BN, int BK>
 __global__ __launch_bounds__(256) void conv_gemm_kernel(const GemmBatch batch) {
   using E = CT<T>;
-  constexpr int BM = 128, BK = E::BK, VEC = E::VEC, LDP = BK + VEC;
-  constexpr int CPR = BK / VEC;                // chunks per tile row (4)
-  constexpr int NA = BM * CPR / 256;           // A chunks per thread (2)
-  constexpr int NB = BN * CPR / 256;           // B chunks per thread (2 or 1)
+  constexpr int BM = 128, VEC = E::VEC, LDP = BK + VEC;
+  constexpr int CPR = BK / VEC;                // chunks per tile row
+  constexpr int NA = BM * CPR / 256;           // A chunks per thread
+  constexpr int NB = BN * CPR / 256;           // B chunks per thread
   constexpr int WTN = BN / 2, NI = WTN / 32;   // wave tile 64 x WTN
-  __shared__ __attribute__((aligned(16))) T As[BM * LDP];
-  __shared__ __attribute__((aligned(16))) T Bs[BN * LDP];
+  constexpr int SP = WTN + 4;                  // pitch (floats) of a wave's 32-row staging area
+  constexpr int OPER_BYTES = (BM + BN) * LDP * (int)sizeof(T), STAGE_BYTES = 4 * 32 * SP * 4;
+  __shared__ __attribute__((aligned(16))) unsigned char smem[OPER_BYTES > STAGE_BYTES ? OPER_BYTES : STAGE_BYTES];
+  T* As = reinterpret_cast<T*>(smem);
+  T* Bs = As + BM * LDP;
 
   const int tile = (int)blockIdx.x;
   const GemmProb& P = batch.p[cfind_problem(batch, tile)];
@@ -201,32 +206,68 @@ __global__ __launch_bounds__(256) void conv_gemm_kernel(const GemmBatch batch) {
     }
   }
 
+  // ---- epilogue: 32 rows of the wave tile at a time through LDS (fp32), then 16-byte rows
   const int flags = P.flags;
+  const bool fwd = P.epi == EPI_FWD;
+  float* stage = reinterpret_cast<float*>(smem) + wave * (32 * SP);
+  T* outp = static_cast<T*>(P.out);
+  constexpr int CPS = WTN / VEC;             // chunks per staged row
+  constexpr int NCH = 32 * CPS / 64;         // chunks per lane
 #pragma unroll
-  for (int j = 0; j < NI; ++j) {
-    const int c = col0 + wn * WTN + j * 32 + (lane & 31);
-    const float bias = (P.epi == EPI_FWD && P.aux0 != nullptr && c < P.N) ? static_cast<const float*>(P.aux0)[c] : 0.f;
+  for (int i = 0; i < 2; ++i) {
+    __syncthreads();  // operand tiles (first pass) or the previous staging pass are consumed
 #pragma unroll
-    for (int i = 0; i < 2; ++i)
+    for (int j = 0; j < NI; ++j)
 #pragma unroll
-      for (int v = 0; v < 16; ++v) {
-        const int r = row0 + wm * 64 + i * 32 + (v >> 2) * 8 + (lane >> 5) * 4 + (v & 3);
-        if (r >= P.M || c >= P.N) continue;
-        float val = acc[i][j][v];
-        const int64_t o = (int64_t)r * P.ldo + c;
-        if (P.epi == EPI_FWD) {
-          val += bias;
-          if (P.aux1) val += E::to_f32(static_cast<const T*>(P.aux1)[o]);
-          if (flags & GF_RELU) val = fmaxf(val, 0.f);
-          if (flags & GF_OUT_F32) static_cast<float*>(P.out)[o] = val;
-          else static_cast<T*>(P.out)[o] = E::from_f32(val);
-        } else {
-          if (P.aux0) val += E::to_f32(static_cast<const T*>(P.aux0)[o]);
-          if (flags & GF_ACCUM) val += E::to_f32(static_cast<T*>(P.out)[o]);
-          if (P.aux1 && !(E::to_f32(static_cast<const T*>(P.aux1)[o]) > 0.f)) val = 0.f;
-          static_cast<T*>(P.out)[o] = E::from_f32(val);
+      for (int v = 0; v < 16; ++v) stage[((v >> 2) * 8 + (lane >> 5) * 4 + (v & 3)) * SP + j * 32 + (lane & 31)] = acc[i][j][v];
+    __syncthreads();
+#pragma unroll
+    for (int t = 0; t < NCH; ++t) {
+      const int q = lane + 64 * t;
+      const int sr = q / CPS, sc = (q % CPS) * VEC;
+      const int r = row0 + wm * 64 + i * 32 + sr, c = col0 + wn * WTN + sc;
+      if (r >= P.M || c >= P.N) continue;  // N is a multiple of VEC on this path
+      const int64_t o = (int64_t)r * P.ldo + c;
+      float val[VEC];
+#pragma unroll
+      for (int e = 0; e < VEC; ++e) val[e] = stage[sr * SP + sc + e];
+      CChunk<T> x0, x1, x2, res;
+      if (fwd) {
+        if (P.aux0) {
+#pragma unroll
+          for (int e = 0; e < VEC; ++e) val[e] += static_cast<const float*>(P.aux0)[c + e];
+        }
+        if (P.aux1) {
+          x1.v = *reinterpret_cast<const uint4*>(static_cast<const T*>(P.aux1) + o);
+#pragma unroll
+          for (int e = 0; e < VEC; ++e) val[e] += E::to_f32(x1.e[e]);
+        }
+        if (flags & GF_RELU) {
+#pragma unroll
+          for (int e = 0; e < VEC; ++e) val[e] = fmaxf(val[e], 0.f);
+        }
+      } else {
+        if (P.aux0) {
+          x0.v = *reinterpret_cast<const uint4*>(static_cast<const T*>(P.aux0) + o);
+#pragma unroll
+          for (int e = 0; e < VEC; ++e) val[e] += E::to_f32(x0.e[e]);
+        }
+        if (flags & GF_ACCUM) {
+          x2.v = *reinterpret_cast<const uint4*>(outp + o);
+#pragma unroll
+          for (int e = 0; e < VEC; ++e) val[e] += E::to_f32(x2.e[e]);
+        }
+        if (P.aux1) {
+          x1.v = *reinterpret_cast<const uint4*>(static_cast<const T*>(P.aux1) + o);
+#pragma unroll
+          for (int e = 0; e < VEC; ++e)
+            if (!(E::to_f32(x1.e[e]) > 0.f)) val[e] = 0.f;
         }
       }
+#pragma unroll
+      for (int e = 0; e < VEC; ++e) res.e[e] = E::from_f32(val[e]);
+      *reinterpret_cast<uint4*>(outp + o) = res.v;
+    }
   }
 }
 
@@ -507,32 +548,43 @@ bool conv_fast_eligible(const GemmProb& p, int dtype) {
     return (p.M % vec) == 0 && (p.lda % vec) == 0;
   }
   if (p.b_mode != OP_PLAIN_K || p.ldb != p.K || (p.K % bk)) return false;
+  if ((p.flags & GF_OUT_F32) || (p.N % vec) || (p.ldo % vec)) return false;
   if (p.a_mode == OP_PLAIN_K) return p.lda == p.K;
   if (p.a_mode == OP_CONV_FWD || p.a_mode == OP_CONV_DGRAD) return (p.g.C % bk) == 0 && p.g.KH * p.g.KW <= 32;
   return false;
+}
+
+template <typename T, int BK>
+static void launch_conv_gemm_typed(const GemmBatch& b, bool wide, dim3 grid, hipStream_t stream) {
+  if (wide) hipLaunchKernelGGL((conv_gemm_kernel<T, 128, BK>), grid, dim3(256), 0, stream, b);
+  else hipLaunchKernelGGL((conv_gemm_kernel<T, 64, BK>), grid, dim3(256), 0, stream, b);
 }
 
 hipError_t launch_conv_gemm(GemmBatch& b, int dtype, bool wide, hipStream_t stream) {
   if (b.n <= 0) return hipSuccess;
   if (b.n > GEMM_MAX_PROBS) return hipErrorInvalidValue;
   const int bn = wide ? 128 : 64;
+  const int bk = dtype == DT_BF16 ? 32 : 16;
   int total = 0;
+  bool deep = true;  // every problem allows the double-depth slab
   for (int i = 0; i < b.n; ++i) {
     GemmProb& p = b.p[i];
     if (p.M <= 0 || p.N <= 0 || p.K <= 0 || p.epi == EPI_WGRAD || !conv_fast_eligible(p, dtype)) return hipErrorInvalidValue;
+    const int C = p.a_mode == OP_PLAIN_K ? p.K : p.g.C;
+    if (C % (2 * bk)) deep = false;
     p.splits = 1;
     p.tiles_n = (p.N + bn - 1) / bn;
     p.tile_begin = total;
     total += ((p.M + 127) / 128) * p.tiles_n;
   }
   b.total_tiles = total;
-  dim3 grid(total), block(256);
+  dim3 grid(total);
   if (dtype == DT_BF16) {
-    if (wide) hipLaunchKernelGGL((conv_gemm_kernel<uint16_t, 128>), grid, block, 0, stream, b);
-    else hipLaunchKernelGGL((conv_gemm_kernel<uint16_t, 64>), grid, block, 0, stream, b);
+    if (deep) launch_conv_gemm_typed<uint16_t, 64>(b, wide, grid, stream);
+    else launch_conv_gemm_typed<uint16_t, 32>(b, wide, grid, stream);
   } else {
-    if (wide) hipLaunchKernelGGL((conv_gemm_kernel<float, 128>), grid, block, 0, stream, b);
-    else hipLaunchKernelGGL((conv_gemm_kernel<float, 64>), grid, block, 0, stream, b);
+    if (deep) launch_conv_gemm_typed<float, 32>(b, wide, grid, stream);
+    else launch_conv_gemm_typed<float, 16>(b, wide, grid, stream);
   }
   return hipGetLastError();
 }
