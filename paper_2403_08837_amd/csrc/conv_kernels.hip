@@ -541,7 +541,7 @@ bool conv_fast_eligible(const GemmProb& p, int dtype) {
     if (p.b_mode == OP_CONV_WGRAD) {
       if (p.g.C % vec || p.g.KH * p.g.KW > 32 || p.g.H >= 32768 || p.g.W >= 32768) return false;
     } else if (p.b_mode == OP_PLAIN_R) {
-      if (p.ldb % vec || p.N != p.ldb) return false;
+      if (p.ldb % vec || p.N > p.ldb) return false;
     } else {
       return false;
     }

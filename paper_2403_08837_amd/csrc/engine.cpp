@@ -81,7 +81,7 @@ struct StageState {
   int ring_ver[2] = {0, 0};
 };
 
-enum ItemKind { IT_GEMM, IT_COLSUM, IT_WREDUCE, IT_STAGE_IN, IT_CE, IT_MAXPOOL_F, IT_MAXPOOL_B, IT_GAP_F, IT_GAP_B };
+enum ItemKind { IT_GEMM, IT_COLSUM, IT_WREDUCE, IT_IM2COL, IT_STAGE_IN, IT_CE, IT_MAXPOOL_F, IT_MAXPOOL_B, IT_GAP_F, IT_GAP_B };
 struct Item {
   int kind;
   GemmProb g;
@@ -197,16 +197,18 @@ GemmProb zero_prob() {
   return p;
 }
 
+// x is the layer input, or its im2col buffer [rows][kpad] for a layer with o.kpad > 0.
 GemmProb fwd_prob(const cdp_ctx* c, const Op& o, const void* x, void* y, const char* slot, const void* res) {
   GemmProb p = zero_prob();
   const int rows = c->B * o.Hout * o.Wout;
   p.A = x; p.B = slot + o.wf; p.out = y;
   p.aux0 = o.bias_c >= 0 ? slot + o.bias_c : nullptr;
   p.aux1 = res;
-  p.M = rows; p.N = o.Cout; p.K = (int)o.K();
-  p.ldb = (int)o.K(); p.ldo = o.Cout;
+  p.M = rows; p.N = o.Cout; p.K = o.kpad ? o.kpad : (int)o.K();
+  p.ldb = p.K; p.ldo = o.Cout;
   p.b_mode = OP_PLAIN_K;
-  if (pointwise(o)) { p.a_mode = OP_PLAIN_K; p.lda = o.Cin; }
+  if (o.kpad) { p.a_mode = OP_PLAIN_K; p.lda = o.kpad; }
+  else if (pointwise(o)) { p.a_mode = OP_PLAIN_K; p.lda = o.Cin; }
   else { p.a_mode = OP_CONV_FWD; conv_geom(o, OP_CONV_FWD, &p.g); }
   p.epi = EPI_FWD;
   p.flags = (o.relu ? GF_RELU : 0) | (o.out_f32 ? GF_OUT_F32 : 0);
@@ -231,8 +233,9 @@ GemmProb wgrad_prob(const cdp_ctx* c, const Op& o, const void* dz, const void* x
   GemmProb p = zero_prob();
   const int rows = c->B * o.Hout * o.Wout;
   p.A = dz; p.a_mode = OP_PLAIN_R; p.lda = o.Cout;
-  p.B = x;
-  if (pointwise(o)) { p.b_mode = OP_PLAIN_R; p.ldb = o.Cin; }
+  p.B = x;  // the layer input, or its im2col buffer for o.kpad > 0
+  if (o.kpad) { p.b_mode = OP_PLAIN_R; p.ldb = o.kpad; }
+  else if (pointwise(o)) { p.b_mode = OP_PLAIN_R; p.ldb = o.Cin; }
   else { p.b_mode = OP_CONV_WGRAD; conv_geom(o, OP_CONV_WGRAD, &p.g); }
   p.M = o.Cout; p.N = (int)o.K(); p.K = rows;
   p.out = G + o.w_off; p.ldo = (int)o.K();
@@ -322,7 +325,18 @@ int build_forward(cdp_ctx* c, int i, int64_t t, int j, int version, const float*
     Item it;
     if (o.kind == OPK_GEMM) {
       it.kind = IT_GEMM;
-      it.g = fwd_prob(c, o, c->ptr(r.t[o.in].off), c->ptr(r.t[o.out].off), slot, o.res >= 0 ? c->ptr(r.t[o.res].off) : nullptr);
+      const void* a_src = c->ptr(r.t[o.in].off);
+      if (o.kpad) {  // explicit im2col into a buffer that lives for this tick only
+        Block col;
+        if (!pool_alloc(c, (int64_t)c->B * o.Hout * o.Wout * o.kpad * c->plan.elem_bytes, &col)) return fail(c, CDP_ENOMEM, "activation pool exhausted");
+        c->deferred.push_back(col);
+        Item ic; ic.kind = IT_IM2COL;
+        ic.p0 = a_src; ic.p2 = c->ptr(col.off); ic.i[0] = c->B; ic.i[1] = o.kpad;
+        conv_geom(o, OP_CONV_FWD, &ic.g.g);
+        at(level++).push_back(ic);
+        a_src = c->ptr(col.off);
+      }
+      it.g = fwd_prob(c, o, a_src, c->ptr(r.t[o.out].off), slot, o.res >= 0 ? c->ptr(r.t[o.res].off) : nullptr);
       op_work(c, o, 0, false, false, &it);
     } else if (o.kind == OPK_MAXPOOL) {
       it.kind = IT_MAXPOOL_F;
@@ -410,7 +424,20 @@ int build_backward(cdp_ctx* c, int i, int j, Program* prog, bool first_grad) {
         at(level).push_back(it);
       }
       Item w; w.kind = IT_GEMM;
-      w.g = wgrad_prob(c, o, dz, xin, slot, G, first_grad);
+      const void* w_src = xin;
+      size_t wl = level;  // level of the weight-gradient contraction
+      if (o.kpad) {       // rebuild the im2col buffer (cheaper than keeping it between the passes)
+        Block col;
+        if (!pool_alloc(c, (int64_t)c->B * o.Hout * o.Wout * o.kpad * c->plan.elem_bytes, &col)) return fail(c, CDP_ENOMEM, "activation pool exhausted");
+        c->deferred.push_back(col);
+        Item ic; ic.kind = IT_IM2COL;
+        ic.p0 = xin; ic.p2 = c->ptr(col.off); ic.i[0] = c->B; ic.i[1] = o.kpad;
+        conv_geom(o, OP_CONV_FWD, &ic.g.g);
+        at(level).push_back(ic);
+        w_src = c->ptr(col.off);
+        wl = level + 1;
+      }
+      w.g = wgrad_prob(c, o, dz, w_src, slot, G, first_grad);
       op_work(c, o, 2, o.is_conv || !first_grad, false, &w);
       bool two_phase = false;
       if (o.is_conv && conv_fast_eligible(w.g, c->plan.dtype)) {
@@ -428,13 +455,13 @@ int build_backward(cdp_ctx* c, int i, int j, Program* prog, bool first_grad) {
         rd.r.Cout = o.Cout; rd.r.Ncol = (int)o.K(); rd.r.splits = w.g.splits;
         w.g.out = part; w.g.aux0 = nullptr; w.g.aux1 = nullptr; w.g.aux2 = nullptr;
         w.g.aux3 = o.b_off >= 0 ? part + wn : nullptr;
-        at(level + 1).push_back(rd);
+        at(wl + 1).push_back(rd);
       }
-      at(level).push_back(w);
+      at(wl).push_back(w);
       if (o.b_off >= 0 && o.is_conv && !two_phase) {
         Item b; b.kind = IT_COLSUM;
         b.c.src = dz; b.c.out = G + o.b_off; b.c.rows = c->B * o.Hout * o.Wout; b.c.cols = o.Cout; b.c.ld = o.Cout;
-        at(level).push_back(b);
+        at(wl).push_back(b);
       }
     } else if (need_dx) {
       if (accumulate) return fail(c, CDP_EINVAL, "pooling input with several consumers is not supported");
@@ -538,6 +565,9 @@ int launch_level(cdp_ctx* c, std::vector<Item>& items) {
         HIP_TRY(c, launch_stage_input(static_cast<const float*>(it.p0), static_cast<const int32_t*>(it.p1), it.p2,
                                       static_cast<int32_t*>(it.p3), static_cast<float*>(it.p4), it.i[0], it.n0, dt, c->stream));
         break;
+      case IT_IM2COL:
+        HIP_TRY(c, launch_im2col(it.p0, it.p2, it.i[0], it.g.g, it.i[1], dt, c->stream));
+        break;
       case IT_CE:
         HIP_TRY(c, launch_ce_head(static_cast<const float*>(it.p0), static_cast<const int32_t*>(it.p1), it.p2,
                                   static_cast<float*>(it.p3), it.i[0], it.i[1], dt, c->stream));
@@ -595,6 +625,7 @@ int refresh_slot(cdp_ctx* c, int j, int slot, float scale) {
     a.gamma = o.has_gamma ? reinterpret_cast<const float*>(sl + o.gamma_c) : nullptr;
     a.wf = sl + o.wf; a.wt = sl + o.wt; a.wp = o.has_gamma ? sl + o.wp : nullptr;
     a.O = o.Cout; a.T = o.KH * o.KW; a.C = o.Cin; a.scale = scale;
+    a.ldf = o.kpad ? o.kpad : a.T * a.C;
     a.zero_g = o.is_conv ? 1 : 0;  // conv accumulators take atomic adds and must start at zero
     HIP_TRY(c, launch_repack(a, c->plan.dtype, c->stream));
     c->stats.kernel_launches++;
@@ -879,6 +910,8 @@ int cdp_get_weights(cdp_ctx* c, int stage, int version, float* host, size_t cap,
   }
   if (version != ss.ver - 1 || ss.ring_ver[version & 1] != version) return fail(c, CDP_ESTATE, "that weight version is no longer in the ring");
   if (sp.has_gamma) return fail(c, CDP_ESTATE, "ring copies of stages with affine layers are folded and cannot be read back");
+  for (const Op& o : sp.ops)
+    if (o.kpad) return fail(c, CDP_ESTATE, "ring copies of im2col layers are padded and cannot be read back");
   float* tmp = nullptr;
   HIP_TRY(c, hipMalloc(reinterpret_cast<void**>(&tmp), (size_t)sp.n_params * 4));
   const char* sl = static_cast<const char*>(c->ptr(ss.slot[version & 1]));

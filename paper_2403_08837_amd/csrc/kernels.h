@@ -129,8 +129,13 @@ struct RepackArgs {
   float* master; float* G; const float* gamma;
   void* wf; void* wt; void* wp;
   int O, T, C; float scale; int zero_g;
+  int ldf;  // row length of wf (T*C, or the zero-padded length of an im2col layer)
 };
 hipError_t launch_repack(const RepackArgs& a, int dtype, hipStream_t stream);
+
+// Explicit im2col for layers whose channel count is below one 16-byte chunk (the RGB stem):
+// col[(b,oh,ow)][k] = x[b][oh*s-p+kh][ow*s-p+kw][c], k = (kh*KW+kw)*C+c, zero for k >= KH*KW*C.
+hipError_t launch_im2col(const void* x, void* col, int B, const ConvGeom& g, int kpad, int dtype, hipStream_t stream);
 
 // Max pool (NHWC) forward, and backward by gather (first maximum in (kh,kw) scan order
 // receives the gradient); backward optionally masks with x > 0.

@@ -92,6 +92,7 @@ std::string build_plan(const cdp_stage_desc* stages, int n_stages, const cdp_opt
         op.w_off = poff;
         poff += (int64_t)cout * ks * ks * cin;
         tout.H = op.Hout; tout.W = op.Wout; tout.C = cout;
+        if (cin % (16 / out->elem_bytes) != 0) op.kpad = (int)align_up((int64_t)ks * ks * cin, out->elem_bytes == 2 ? 64 : 32);
         if (j < sd.n_layers && sd.layers[j].kind == CDP_AFFINE && follows(sd.layers[j], j)) {
           if (sd.layers[j].p[0] != cout) return err(s, j, "affine channels do not match the conv");
           op.has_gamma = true;
@@ -164,7 +165,7 @@ std::string build_plan(const cdp_stage_desc* stages, int n_stages, const cdp_opt
     int64_t off = 0;
     for (Op& o : sp.ops) {
       if (o.kind != OPK_GEMM) continue;
-      o.wf = off; off = align_up(off + o.w_count() * out->elem_bytes, 256);
+      o.wf = off; off = align_up(off + (o.kpad ? (int64_t)o.Cout * o.kpad : o.w_count()) * out->elem_bytes, 256);
       o.wt = off; off = align_up(off + o.w_count() * out->elem_bytes, 256);
       if (o.has_gamma) { o.wp = off; off = align_up(off + o.w_count() * out->elem_bytes, 256); sp.has_gamma = true; }
       if (o.b_off >= 0) { o.bias_c = off; off = align_up(off + (int64_t)o.Cout * 4, 256); }

@@ -32,6 +32,8 @@ struct Op {
   int Hin = 1, Win = 1, Hout = 1, Wout = 1;
   int pk = 0, ps = 0, pp = 0;     // pooling window / stride / pad
   int classes = 0;
+  int kpad = 0;                   // > 0: the forward weights are stored with this (zero-padded) row length and the
+                                  // layer runs on an explicit im2col buffer (channel counts below one 16-byte chunk)
   // float offsets inside the stage's flat fp32 parameter block (-1: absent)
   int64_t w_off = -1, b_off = -1, g_off = -1;
   // byte offsets inside one ring slot

@@ -174,7 +174,7 @@ __global__ __launch_bounds__(256) void repack_kernel(const RepackArgs a) {
       if (a.zero_g) a.G[idx] = 0.f;
       if (wp) st_f32<T>(wp, idx, w);
       v = a.gamma ? a.gamma[o] * w : w;
-      st_f32<T>(wf, idx, v);
+      st_f32<T>(wf, (int64_t)o * a.ldf + (int64_t)t * a.C + c, v);
     }
     tile[ty + i * 4][tx] = v;
   }
@@ -190,6 +190,41 @@ hipError_t launch_repack(const RepackArgs& a, int dtype, hipStream_t stream) {
   if (a.O <= 0 || a.C <= 0 || a.T <= 0) return hipErrorInvalidValue;
   dim3 grid((a.C + 63) / 64, (a.O + 63) / 64, a.T);
   CDP_DISPATCH(dtype, hipLaunchKernelGGL((repack_kernel<T>), grid, dim3(256), 0, stream, a));
+  return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------------
+template <typename T>
+__global__ void im2col_kernel(const T* __restrict__ x, T* __restrict__ col, int64_t n_chunks, ConvGeom g, int kpad) {
+  constexpr int VEC = 16 / sizeof(T);
+  const int cpr = kpad / VEC, K = g.KH * g.KW * g.C;
+  for (int64_t i = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; i < n_chunks; i += (int64_t)gridDim.x * blockDim.x) {
+    const int64_t m = i / cpr;
+    const int k0 = (int)(i - m * cpr) * VEC;
+    const int b = (int)(m / (g.OH * g.OW));
+    const int rem = (int)(m - (int64_t)b * (g.OH * g.OW));
+    const int oh = rem / g.OW, ow = rem - oh * g.OW;
+    const int ih0 = oh * g.stride - g.pad, iw0 = ow * g.stride - g.pad;
+    union { uint4 v; T e[VEC]; } out;
+    out.v = make_uint4(0, 0, 0, 0);
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) {
+      const int k = k0 + e;
+      if (k >= K) break;
+      const int tap = k / g.C, c = k - tap * g.C;
+      const int kh = tap / g.KW, kw = tap - kh * g.KW;
+      const int ih = ih0 + kh, iw = iw0 + kw;
+      if (ih >= 0 && ih < g.H && iw >= 0 && iw < g.W) out.e[e] = x[(((int64_t)b * g.H + ih) * g.W + iw) * g.C + c];
+    }
+    *reinterpret_cast<uint4*>(col + i * VEC) = out.v;
+  }
+}
+hipError_t launch_im2col(const void* x, void* col, int B, const ConvGeom& g, int kpad, int dtype, hipStream_t stream) {
+  const int vec = dtype == DT_BF16 ? 8 : 4;
+  if (kpad % vec || kpad < g.KH * g.KW * g.C) return hipErrorInvalidValue;
+  const int64_t n = (int64_t)B * g.OH * g.OW * (kpad / vec);
+  CDP_DISPATCH(dtype, hipLaunchKernelGGL((im2col_kernel<T>), dim3(blocks_for(n, 256, 1 << 20)), dim3(256), 0, stream,
+                                         static_cast<const T*>(x), static_cast<T*>(col), n, g, kpad));
   return hipGetLastError();
 }
 
@@ -252,6 +287,61 @@ __global__ void maxpool_bwd_kernel(const T* __restrict__ x, const T* __restrict_
   }
 }
 
+// Same rule, 16 bytes of channels per thread (C a multiple of the chunk).
+template <typename T>
+__global__ void maxpool_bwd_vec_kernel(const T* __restrict__ x, const T* __restrict__ dy, T* __restrict__ dx, int B, int H, int W,
+                                       int C, int OH, int OW, int k, int s, int p, int mask_relu) {
+  constexpr int VEC = 16 / sizeof(T);
+  union Ch { uint4 v; T e[VEC]; };
+  const int cpp = C / VEC;
+  const int64_t n = (int64_t)B * H * W * cpp;
+  for (int64_t i = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x) {
+    const int c = (int)(i % cpp) * VEC;
+    int64_t q = i / cpp;
+    const int iw = (int)(q % W); q /= W;
+    const int ih = (int)(q % H);
+    const int b = (int)(q / H);
+    Ch xc;
+    xc.v = *reinterpret_cast<const uint4*>(x + (((int64_t)b * H + ih) * W + iw) * C + c);
+    float xv[VEC], g[VEC];
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) { xv[e] = ld_f32<T>(xc.e, e); g[e] = 0.f; }
+    const int oh_lo = max(0, (ih + p - k + s) / s), oh_hi = min(OH - 1, (ih + p) / s);
+    const int ow_lo = max(0, (iw + p - k + s) / s), ow_hi = min(OW - 1, (iw + p) / s);
+    for (int oh = oh_lo; oh <= oh_hi; ++oh)
+      for (int ow = ow_lo; ow <= ow_hi; ++ow) {
+        bool first[VEC];
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) first[e] = true;
+        for (int kh = 0; kh < k; ++kh)
+          for (int kw = 0; kw < k; ++kw) {
+            const int jh = oh * s - p + kh, jw = ow * s - p + kw;
+            if (jh < 0 || jw < 0 || jh >= H || jw >= W || (jh == ih && jw == iw)) continue;
+            Ch oc;
+            oc.v = *reinterpret_cast<const uint4*>(x + (((int64_t)b * H + jh) * W + jw) * C + c);
+            const bool before = (jh < ih) || (jh == ih && jw < iw);
+#pragma unroll
+            for (int e = 0; e < VEC; ++e) {
+              const float o = ld_f32<T>(oc.e, e);
+              if (o > xv[e] || (before && o == xv[e])) first[e] = false;
+            }
+          }
+        Ch dc;
+        dc.v = *reinterpret_cast<const uint4*>(dy + (((int64_t)b * OH + oh) * OW + ow) * C + c);
+#pragma unroll
+        for (int e = 0; e < VEC; ++e)
+          if (first[e]) g[e] += ld_f32<T>(dc.e, e);
+      }
+    Ch out;
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) {
+      const float v = (mask_relu && !(xv[e] > 0.f)) ? 0.f : g[e];
+      st_f32<T>(out.e, e, v);
+    }
+    *reinterpret_cast<uint4*>(dx + (((int64_t)b * H + ih) * W + iw) * C + c) = out.v;
+  }
+}
+
 hipError_t launch_maxpool_fwd(const void* x, void* y, int B, int H, int W, int C, int k, int s, int p, int dtype,
                               hipStream_t stream) {
   int OH = (H + 2 * p - k) / s + 1, OW = (W + 2 * p - k) / s + 1;
@@ -264,6 +354,13 @@ hipError_t launch_maxpool_bwd(const void* x, const void* dy, void* dx, int B, in
                               int mask_relu, int dtype, hipStream_t stream) {
   int OH = (H + 2 * p - k) / s + 1, OW = (W + 2 * p - k) / s + 1;
   int64_t n = (int64_t)B * H * W * C;
+  const int vec = dtype == DT_BF16 ? 8 : 4;
+  if (C % vec == 0) {
+    CDP_DISPATCH(dtype, hipLaunchKernelGGL((maxpool_bwd_vec_kernel<T>), dim3(blocks_for(n / vec, 256, 1 << 20)), dim3(256), 0, stream,
+                                           static_cast<const T*>(x), static_cast<const T*>(dy), static_cast<T*>(dx), B, H, W, C,
+                                           OH, OW, k, s, p, mask_relu));
+    return hipGetLastError();
+  }
   CDP_DISPATCH(dtype, hipLaunchKernelGGL((maxpool_bwd_kernel<T>), dim3(blocks_for(n, 256, 65536)), dim3(256), 0, stream,
                                          static_cast<const T*>(x), static_cast<const T*>(dy), static_cast<T*>(dx), B, H, W, C,
                                          OH, OW, k, s, p, mask_relu));
