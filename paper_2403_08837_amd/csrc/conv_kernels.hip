@@ -469,35 +469,55 @@ __global__ __launch_bounds__(256) void conv_wgrad_kernel(const GemmBatch batch) 
   if (do_beta && o0 + tid < Cout) static_cast<float*>(P.aux3)[(int64_t)split * Cout + o0 + tid] = bsum;
 }
 
-// Fold of the partial sums.  Workgroup = 32 columns of one weight row o x 8 range groups:
+// Fold of the partial sums.  Workgroup = 128 columns of one weight row o (4 per lane) x 8
+// range groups:
 //   s[c] = sum_ranges part[.][o][c];  G[o][c] += gamma[o]*s[c];
-//   d gamma[o] += sum_c s[c]*Wplain[o][c]  (one atomic per 32 columns);
+//   d gamma[o] += sum_c s[c]*Wplain[o][c]  (one atomic per 128 columns);
 //   d beta[o]  += sum_ranges part_beta[.][o]  (first column chunk only).
 template <typename T>
 __global__ __launch_bounds__(256) void wgrad_reduce_kernel(const WReduceBatch batch) {
   using E = CT<T>;
-  __shared__ float red[8][33];
+  __shared__ float4 red[8][32];
   const WReduceProb& P = batch.p[blockIdx.z];
-  const int o = blockIdx.y, c0 = blockIdx.x * 32;
+  const int o = blockIdx.y, c0 = blockIdx.x * 128;
   if (o >= P.Cout || c0 >= P.Ncol) return;
   const int cl = threadIdx.x & 31, grp = threadIdx.x >> 5;
-  const int c = c0 + cl;
+  const int c = c0 + cl * 4;
   const int64_t row = (int64_t)o * P.Ncol, stride = (int64_t)P.Cout * P.Ncol;
-  float sum = 0.f;
-  if (c < P.Ncol)
-    for (int q = grp; q < P.splits; q += 8) sum += P.part[q * stride + row + c];
+  const bool vec4 = (P.Ncol & 3) == 0;  // rows of the partial buffers are 16-byte aligned
+  float4 sum = make_float4(0.f, 0.f, 0.f, 0.f);
+  if (vec4) {
+    if (c < P.Ncol)
+      for (int q = grp; q < P.splits; q += 8) {
+        const float4 v = *reinterpret_cast<const float4*>(P.part + q * stride + row + c);
+        sum.x += v.x; sum.y += v.y; sum.z += v.z; sum.w += v.w;
+      }
+  } else {
+    for (int q = grp; q < P.splits; q += 8) {
+      const float* src = P.part + q * stride + row;
+      if (c + 0 < P.Ncol) sum.x += src[c + 0];
+      if (c + 1 < P.Ncol) sum.y += src[c + 1];
+      if (c + 2 < P.Ncol) sum.z += src[c + 2];
+      if (c + 3 < P.Ncol) sum.w += src[c + 3];
+    }
+  }
   red[grp][cl] = sum;
   __syncthreads();
   if (grp == 0) {
-    float tot = 0.f;
+    float tot[4] = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-    for (int k = 0; k < 8; ++k) tot += red[k][cl];
-    float dg = 0.f;
-    if (c < P.Ncol) {
-      const float gam = P.gamma ? P.gamma[o] : 1.f;
-      P.G[row + c] += gam * tot;
-      if (P.wplain) dg = tot * E::to_f32(static_cast<const T*>(P.wplain)[row + c]);
+    for (int k = 0; k < 8; ++k) {
+      const float4 v = red[k][cl];
+      tot[0] += v.x; tot[1] += v.y; tot[2] += v.z; tot[3] += v.w;
     }
+    const float gam = P.gamma ? P.gamma[o] : 1.f;
+    float dg = 0.f;
+#pragma unroll
+    for (int e = 0; e < 4; ++e)
+      if (c + e < P.Ncol) {
+        P.G[row + c + e] += gam * tot[e];
+        if (P.wplain) dg += tot[e] * E::to_f32(static_cast<const T*>(P.wplain)[row + c + e]);
+      }
     if (P.Ggamma) {  // lanes 0..31 of wavefront 0
 #pragma unroll
       for (int off = 16; off >= 1; off >>= 1) dg += __shfl_xor(dg, off, 64);
@@ -518,7 +538,7 @@ hipError_t launch_wgrad_reduce(const WReduceBatch& b, int dtype, hipStream_t str
   int rows = 1, chunks = 1;
   for (int i = 0; i < b.n; ++i) {
     rows = max(rows, b.p[i].Cout);
-    chunks = max(chunks, (b.p[i].Ncol + 31) / 32);
+    chunks = max(chunks, (b.p[i].Ncol + 127) / 128);
   }
   if (rows > 65535) return hipErrorInvalidValue;
   dim3 grid(chunks, rows, b.n), block(256);
