@@ -137,14 +137,16 @@ def train_equation(cfg: wl.Config, params0, xs: Sequence[np.ndarray], ys: Sequen
 def train_schedule(cfg: wl.Config, params0, xs: Sequence[np.ndarray], ys: Sequence[np.ndarray],
                    rule: int, lr: Optional[float] = None,
                    rnd: Callable[[np.ndarray], np.ndarray] = L.identity,
-                   compute: bool = True, keep_versions: bool = True) -> Result:
+                   compute: bool = True, keep_versions: bool = True,
+                   progress: Optional[Callable[[int, int], None]] = None) -> Result:
     """Per tick: every active micro-batch runs one stage forward or backward with the
     weight version the rule assigns (forward) or the one its own forward used
     (backward); a backward adds its gradient to the stage accumulator; at the end of
     the tick every stage holding N gradients is updated into the other ring slot and
     the new version becomes visible from the next tick.  ``compute=False`` runs the
     integer bookkeeping only (trace, versions, live counts); ``keep_versions=False`` does
-    not retain superseded weight versions (large models)."""
+    not retain superseded weight versions (large models); ``progress(tick, n_ticks)`` is
+    called after every tick."""
     S, N, B = cfg.S, cfg.N, cfg.B
     lr = cfg.lr if lr is None else lr
     d = delay_for(S, N, rule)
@@ -217,6 +219,8 @@ def train_schedule(cfg: wl.Config, params0, xs: Sequence[np.ndarray], ys: Sequen
                 ver[j] = new
                 cnt[j] = 0
                 res.updates.append((tick, j, new))
+        if progress is not None:
+            progress(tick, total_ticks(S, N, d, T))
     assert not saved and not used and all(c == 0 for c in cnt)
     assert all(v == T for v in ver)
     if compute:
