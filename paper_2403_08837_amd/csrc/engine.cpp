@@ -279,16 +279,15 @@ void op_work(const cdp_ctx* c, const Op& o, int pass, bool rmw, bool extra_in, I
 
 // Launch class of a contraction: which kernel family and tile shape runs it.
 enum LaunchClass {
-  LC_SKINNY_64 = 0, LC_SKINNY_128, LC_LINEAR_DW, LC_CONV_64, LC_CONV_128, LC_CWGRAD_64, LC_CWGRAD_128,
+  LC_LINEAR = 0, LC_CONV_64, LC_CONV_128, LC_CWGRAD_64, LC_CWGRAD_128,
   LC_GEN_FIRST  // LC_GEN_FIRST + 2*shape + wgrad
 };
 
 int launch_class(const GemmProb& p, int dtype) {
   (void)dtype;
-  if (p.epi != EPI_WGRAD && p.a_mode == OP_PLAIN_K && p.b_mode == OP_PLAIN_K && p.M <= 128)
-    return p.N >= 2048 ? LC_SKINNY_128 : LC_SKINNY_64;
+  if (p.epi != EPI_WGRAD && p.a_mode == OP_PLAIN_K && p.b_mode == OP_PLAIN_K && p.M <= 128) return LC_LINEAR;
   if (p.epi == EPI_WGRAD && p.a_mode == OP_PLAIN_R && p.b_mode == OP_PLAIN_R && !(p.flags & GF_ATOMIC) && !p.aux0 && !p.aux1)
-    return LC_LINEAR_DW;
+    return LC_LINEAR;
   if (conv_fast_eligible(p, dtype)) {
     if (p.epi == EPI_WGRAD) return p.M >= 128 ? LC_CWGRAD_128 : LC_CWGRAD_64;
     return p.N > 64 ? LC_CONV_128 : LC_CONV_64;
@@ -518,9 +517,13 @@ int launch_level(cdp_ctx* c, std::vector<Item>& items) {
         for (int q = 0; q < batch.n; ++q) { pr.flops += sel[k + q]->flops; pr.bytes += sel[k + q]->bytes; }
         HIP_TRY(c, hipEventRecord(pr.a, c->stream));
       }
-      if (key == LC_SKINNY_64 || key == LC_SKINNY_128) HIP_TRY(c, launch_linear_skinny(batch, c->plan.dtype, key == LC_SKINNY_128, c->stream));
-      else if (key == LC_LINEAR_DW) HIP_TRY(c, launch_linear_dw(batch, c->plan.dtype, c->stream));
-      else if (key == LC_CONV_64 || key == LC_CONV_128) HIP_TRY(c, launch_conv_gemm(batch, c->plan.dtype, key == LC_CONV_128, c->stream));
+      if (key == LC_LINEAR) {
+        // wide column tiles when the forward / data-gradient problems are large enough to fill the chip with them
+        int64_t skinny_cols = 0;
+        for (int q = 0; q < batch.n; ++q)
+          if (batch.p[q].epi != EPI_WGRAD) skinny_cols += batch.p[q].N;
+        HIP_TRY(c, launch_linear_tick(batch, c->plan.dtype, skinny_cols >= 32768, c->stream));
+      } else if (key == LC_CONV_64 || key == LC_CONV_128) HIP_TRY(c, launch_conv_gemm(batch, c->plan.dtype, key == LC_CONV_128, c->stream));
       else if (key == LC_CWGRAD_64 || key == LC_CWGRAD_128) HIP_TRY(c, launch_conv_wgrad(batch, c->plan.dtype, key == LC_CWGRAD_128, c->stream));
       else HIP_TRY(c, launch_gemm_batch(batch, c->plan.dtype, (key - LC_GEN_FIRST) / 2, c->stream));
       if (timed) {

@@ -60,6 +60,7 @@ constexpr int GEMM_MAX_PROBS = 24;
 struct GemmBatch {
   int n;
   int total_tiles;
+  int head_tiles;  // linear_tick_kernel: tiles of the forward / data-gradient problems (listed first)
   GemmProb p[GEMM_MAX_PROBS];
 };
 static_assert(sizeof(GemmBatch) <= 4000, "kernel argument block must stay under 4 KiB");
@@ -76,8 +77,8 @@ hipError_t launch_gemm_batch(GemmBatch& batch, int dtype, int tile_shape, hipStr
 //   dw:     weight gradient G (+)= dY^T X with A = dY (OP_PLAIN_R), B = X (OP_PLAIN_R),
 //           GF_ACCUM selects accumulate vs overwrite; aux2 = bias-gradient vector or NULL
 //           (same accumulate/overwrite rule).
-hipError_t launch_linear_skinny(GemmBatch& batch, int dtype, bool wide, hipStream_t stream);
-hipError_t launch_linear_dw(GemmBatch& batch, int dtype, hipStream_t stream);
+// Both kinds may be mixed in one batch (one launch per tick level).
+hipError_t launch_linear_tick(GemmBatch& batch, int dtype, bool wide, hipStream_t stream);
 
 // Implicit-GEMM convolution fast paths (channel counts that are multiples of the slab).
 bool conv_fast_eligible(const GemmProb& p, int dtype);

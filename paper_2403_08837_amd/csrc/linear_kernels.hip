@@ -3,10 +3,10 @@
 // With a micro-batch of B <= 64 rows every Linear pass reads or updates one weight-
 // sized matrix exactly once for 2*B flops per element, far below the MFMA/HBM ridge, so
 // these kernels are built to keep HBM busy rather than the matrix cores:
-//   * skinny_kernel   C[M][N] = A[M][K] * W[N][K]^T  (forward with W, data gradient with
+//   * skinny tile     C[M][N] = A[M][K] * W[N][K]^T  (forward with W, data gradient with
 //                     the transposed copy W^T): 64-row tiles, 128-deep slabs, one slab of
 //                     loads in flight per workgroup while the previous one is contracted;
-//   * dw_kernel       G[N][K] (+)= dY[M][N]^T * X[M][K] (weight gradient): the old
+//   * dw tile         G[N][K] (+)= dY[M][N]^T * X[M][K] (weight gradient): the old
 //                     accumulator tile is requested before the operands so the read-
 //                     modify-write stream is never waiting on the contraction; the bias
 //                     gradient (column sums of dY) is folded into the first column tile.
@@ -14,6 +14,8 @@
 // then holds that problem's activations once), and every workgroup starts its reduction
 // loop at a different slab so that concurrent workgroups do not hit the same HBM
 // channels (weight rows are a power of two apart).
+#include <algorithm>
+
 #include "kernels.h"
 
 namespace cdp {
@@ -69,19 +71,16 @@ __device__ __forceinline__ v16f_t mfma_bf16(uint4 a, uint4 b, v16f_t c) {
 }  // namespace
 
 // ---------------------------------------------------------------------------------
-// skinny_kernel: 64 x BN output tile, waves 2 (rows) x 2 (cols).
+// skinny tile: 64 x BN outputs, waves 2 (rows) x 2 (cols).
 template <typename T, int BN>
-__global__ __launch_bounds__(256) void skinny_kernel(const GemmBatch batch) {
+__device__ __forceinline__ void skinny_tile(const GemmProb& P, int tile, unsigned char* smem) {
   using E = LT<T>;
   constexpr int BM = 64, BK = E::SLAB, VEC = E::VEC, LDP = BK + VEC;
   constexpr int NA = BM / 16, NB = BN / 16;  // 16-byte chunks per thread and slab
   constexpr int NI = BN / 64;                // 32-wide MFMA tiles per wave along N
-  __shared__ __attribute__((aligned(16))) T As[BM * LDP];
-  __shared__ __attribute__((aligned(16))) T Bs[BN * LDP];
+  T* As = reinterpret_cast<T*>(smem);
+  T* Bs = As + BM * LDP;
 
-  const int tile = xcd_remap((int)blockIdx.x, batch.total_tiles);
-  if (tile >= batch.total_tiles) return;
-  const GemmProb& P = batch.p[find_problem(batch, tile)];
   const int local = tile - P.tile_begin;
   const int tn = local % P.tiles_n, tm = local / P.tiles_n;
   const int row0 = tm * BM, col0 = tn * BN;
@@ -199,16 +198,13 @@ __global__ __launch_bounds__(256) void skinny_kernel(const GemmBatch batch) {
 // (ldb = K), out = G [N][K] (ldo = K), P.M = N, P.N = K, P.K = Mb (reduction length);
 // aux2 = bias-gradient vector [N] or NULL.
 template <typename T>
-__global__ __launch_bounds__(256) void dw_kernel(const GemmBatch batch) {
+__device__ __forceinline__ void dw_tile(const GemmProb& P, int tile, unsigned char* smem) {
   using E = LT<T>;
   constexpr int TN = 64, TK = 128, MB = 64, VEC = E::VEC;
-  constexpr int PD = TN + (sizeof(T) == 2 ? 4 : 4), PX = TK + (sizeof(T) == 2 ? 4 : 4);  // LDS pitches (elements)
-  __shared__ __attribute__((aligned(16))) T Ds[MB * PD];
-  __shared__ __attribute__((aligned(16))) T Xs[MB * PX];
+  constexpr int PD = TN + 4, PX = TK + 4;  // LDS pitches (elements)
+  T* Ds = reinterpret_cast<T*>(smem);
+  T* Xs = Ds + MB * PD;
 
-  const int tile = xcd_remap((int)blockIdx.x, batch.total_tiles);
-  if (tile >= batch.total_tiles) return;
-  const GemmProb& P = batch.p[find_problem(batch, tile)];
   const int local = tile - P.tile_begin;
   const int tk = local % P.tiles_n, tnn = local / P.tiles_n;
   const int n0 = tnn * TN, k0 = tk * TK;
@@ -327,51 +323,63 @@ __global__ __launch_bounds__(256) void dw_kernel(const GemmBatch batch) {
 }
 
 // ---------------------------------------------------------------------------------
-hipError_t launch_linear_skinny(GemmBatch& b, int dtype, bool wide, hipStream_t stream) {
+// One launch for every Linear contraction of a tick level: the tile list mixes forward /
+// data-gradient tiles (skinny) and weight-gradient tiles (dw), so the short read-modify-write
+// tiles fill the machine while the long weight-streaming tiles run.
+template <typename T, int BN>
+__global__ __launch_bounds__(256) void linear_tick_kernel(const GemmBatch batch) {
+  using E = LT<T>;
+  constexpr int SK_BYTES = (64 + BN) * (E::SLAB + E::VEC) * (int)sizeof(T);
+  constexpr int DW_BYTES = 64 * (64 + 4 + 128 + 4) * (int)sizeof(T);
+  __shared__ __attribute__((aligned(16))) unsigned char smem[SK_BYTES > DW_BYTES ? SK_BYTES : DW_BYTES];
+  // the two kinds are spread over the XCDs separately (each XCD gets its share of both)
+  const int head8 = (batch.head_tiles + 7) & ~7;
+  int tile;
+  if ((int)blockIdx.x < head8) {
+    tile = xcd_remap((int)blockIdx.x, batch.head_tiles);
+    if (tile >= batch.head_tiles) return;
+  } else {
+    tile = batch.head_tiles + xcd_remap((int)blockIdx.x - head8, batch.total_tiles - batch.head_tiles);
+    if (tile >= batch.total_tiles) return;
+  }
+  const GemmProb& P = batch.p[find_problem(batch, tile)];
+  if (P.epi == EPI_WGRAD) dw_tile<T>(P, tile, smem);
+  else skinny_tile<T, BN>(P, tile, smem);
+}
+
+hipError_t launch_linear_tick(GemmBatch& b, int dtype, bool wide, hipStream_t stream) {
   if (b.n <= 0) return hipSuccess;
   if (b.n > GEMM_MAX_PROBS) return hipErrorInvalidValue;
   const int bn = wide ? 128 : 64;
+  // forward / data-gradient problems first, weight gradients after them
+  std::stable_partition(b.p, b.p + b.n, [](const GemmProb& p) { return p.epi != EPI_WGRAD; });
   int total = 0;
+  b.head_tiles = 0;
   for (int i = 0; i < b.n; ++i) {
     GemmProb& p = b.p[i];
     if (p.M <= 0 || p.N <= 0 || p.K <= 0) return hipErrorInvalidValue;
-    if (p.a_mode != OP_PLAIN_K || p.b_mode != OP_PLAIN_K || p.epi == EPI_WGRAD) return hipErrorInvalidValue;
-    if ((int64_t)p.M * p.lda >= (1ll << 31) || (int64_t)p.N * p.ldb >= (1ll << 31)) return hipErrorInvalidValue;
     p.splits = 1;
-    p.tiles_n = (p.N + bn - 1) / bn;
+    if (p.epi != EPI_WGRAD) b.head_tiles += ((p.M + 63) / 64) * ((p.N + bn - 1) / bn);
+    if (p.epi == EPI_WGRAD) {
+      if (p.a_mode != OP_PLAIN_R || p.b_mode != OP_PLAIN_R || (p.flags & GF_ATOMIC) || p.aux0 || p.aux1) return hipErrorInvalidValue;
+      p.tiles_n = (p.N + 127) / 128;
+    } else {
+      if (p.a_mode != OP_PLAIN_K || p.b_mode != OP_PLAIN_K) return hipErrorInvalidValue;
+      if ((int64_t)p.M * p.lda >= (1ll << 31) || (int64_t)p.N * p.ldb >= (1ll << 31)) return hipErrorInvalidValue;
+      p.tiles_n = (p.N + bn - 1) / bn;
+    }
     p.tile_begin = total;
     total += ((p.M + 63) / 64) * p.tiles_n;
   }
   b.total_tiles = total;
-  dim3 grid(((total + 7) / 8) * 8), block(256);
+  dim3 grid(((b.head_tiles + 7) / 8) * 8 + ((total - b.head_tiles + 7) / 8) * 8), block(256);
   if (dtype == DT_BF16) {
-    if (wide) hipLaunchKernelGGL((skinny_kernel<uint16_t, 128>), grid, block, 0, stream, b);
-    else hipLaunchKernelGGL((skinny_kernel<uint16_t, 64>), grid, block, 0, stream, b);
+    if (wide) hipLaunchKernelGGL((linear_tick_kernel<uint16_t, 128>), grid, block, 0, stream, b);
+    else hipLaunchKernelGGL((linear_tick_kernel<uint16_t, 64>), grid, block, 0, stream, b);
   } else {
-    if (wide) hipLaunchKernelGGL((skinny_kernel<float, 128>), grid, block, 0, stream, b);
-    else hipLaunchKernelGGL((skinny_kernel<float, 64>), grid, block, 0, stream, b);
+    if (wide) hipLaunchKernelGGL((linear_tick_kernel<float, 128>), grid, block, 0, stream, b);
+    else hipLaunchKernelGGL((linear_tick_kernel<float, 64>), grid, block, 0, stream, b);
   }
-  return hipGetLastError();
-}
-
-hipError_t launch_linear_dw(GemmBatch& b, int dtype, hipStream_t stream) {
-  if (b.n <= 0) return hipSuccess;
-  if (b.n > GEMM_MAX_PROBS) return hipErrorInvalidValue;
-  int total = 0;
-  for (int i = 0; i < b.n; ++i) {
-    GemmProb& p = b.p[i];
-    if (p.M <= 0 || p.N <= 0 || p.K <= 0) return hipErrorInvalidValue;
-    if (p.a_mode != OP_PLAIN_R || p.b_mode != OP_PLAIN_R || p.epi != EPI_WGRAD) return hipErrorInvalidValue;
-    if ((p.flags & GF_ATOMIC) || p.aux0 || p.aux1) return hipErrorInvalidValue;
-    p.splits = 1;
-    p.tiles_n = (p.N + 127) / 128;
-    p.tile_begin = total;
-    total += ((p.M + 63) / 64) * p.tiles_n;
-  }
-  b.total_tiles = total;
-  dim3 grid(((total + 7) / 8) * 8), block(256);
-  if (dtype == DT_BF16) hipLaunchKernelGGL((dw_kernel<uint16_t>), grid, block, 0, stream, b);
-  else hipLaunchKernelGGL((dw_kernel<float>), grid, block, 0, stream, b);
   return hipGetLastError();
 }
 
