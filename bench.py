@@ -107,6 +107,8 @@ def main():
     ap.add_argument("--workload", default="cfg2", choices=sorted(WORKLOAD_TEXT))
     ap.add_argument("--rule", default="v2", choices=["dp", "v1", "v2"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calib-copy", action="store_true",
+                    help="also run one plain 1 GiB device copy (reference for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE)")
     args = ap.parse_args()
     if args.gpus != 1:
         raise SystemExit("bench.py: this build runs the CDP hot path on ONE GPU; --gpus %d is not supported "
@@ -116,6 +118,13 @@ def main():
     default_steps = {"cfg1": 200, "cfg2": 200, "cfg3": 20, "cfg4": 5, "cfg5": 20}[args.workload]
     steps = args.steps if args.steps is not None else default_steps
     warmup = args.warmup if args.warmup is not None else 3
+    if args.calib_copy:
+        import torch
+        src = torch.ones(1 << 28, dtype=torch.float32, device="cuda")   # 1 GiB read + 1 GiB written
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
     r = gpu_run(cfg, rule, steps, warmup)
     samples = cfg.N * cfg.B * steps
     prof = r["prof"]

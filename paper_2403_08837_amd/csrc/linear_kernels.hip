@@ -101,7 +101,10 @@ __device__ __forceinline__ void skinny_tile(const GemmProb& P, int tile, unsigne
     const int r = col0 + crow + 16 * i;
     offB[i] = r < P.N ? r * P.ldb + ck : -1;
   }
-  uint4 ra[NA], rb[NB];
+  // narrow tiles serve small problems whose k-loop is a chain of memory latencies: keep two
+  // slabs of loads in flight; wide tiles are bandwidth-bound and keep occupancy instead
+  constexpr int DEPTH = (BN == 64) ? 2 : 1;
+  uint4 ra[DEPTH][NA], rb[DEPTH][NB];
   // rows are 16-byte aligned and K is a whole number of chunks: one vector load per chunk;
   // otherwise (e.g. a 10-class head) chunks are gathered element by element
   const bool vec = (P.K % VEC) == 0 && (P.lda % VEC) == 0 && (P.ldb % VEC) == 0;
@@ -113,20 +116,20 @@ __device__ __forceinline__ void skinny_tile(const GemmProb& P, int tile, unsigne
       if (k + e < P.K) c.e[e] = src[e];
     return c.v;
   };
-  auto fetch = [&](int k0) {
+  auto fetch = [&](uint4* qa, uint4* qb, int k0) {
     const bool kin = k0 + ck < P.K;
     if (vec) {
 #pragma unroll
       for (int i = 0; i < NA; ++i)
-        ra[i] = (kin && offA[i] >= 0) ? *reinterpret_cast<const uint4*>(Ap + offA[i] + k0) : make_uint4(0, 0, 0, 0);
+        qa[i] = (kin && offA[i] >= 0) ? *reinterpret_cast<const uint4*>(Ap + offA[i] + k0) : make_uint4(0, 0, 0, 0);
 #pragma unroll
       for (int i = 0; i < NB; ++i)
-        rb[i] = (kin && offB[i] >= 0) ? *reinterpret_cast<const uint4*>(Bp + offB[i] + k0) : make_uint4(0, 0, 0, 0);
+        qb[i] = (kin && offB[i] >= 0) ? *reinterpret_cast<const uint4*>(Bp + offB[i] + k0) : make_uint4(0, 0, 0, 0);
     } else {
 #pragma unroll
-      for (int i = 0; i < NA; ++i) ra[i] = (kin && offA[i] >= 0) ? gather(Ap + offA[i] + k0, k0 + ck) : make_uint4(0, 0, 0, 0);
+      for (int i = 0; i < NA; ++i) qa[i] = (kin && offA[i] >= 0) ? gather(Ap + offA[i] + k0, k0 + ck) : make_uint4(0, 0, 0, 0);
 #pragma unroll
-      for (int i = 0; i < NB; ++i) rb[i] = (kin && offB[i] >= 0) ? gather(Bp + offB[i] + k0, k0 + ck) : make_uint4(0, 0, 0, 0);
+      for (int i = 0; i < NB; ++i) qb[i] = (kin && offB[i] >= 0) ? gather(Bp + offB[i] + k0, k0 + ck) : make_uint4(0, 0, 0, 0);
     }
   };
 
@@ -137,17 +140,23 @@ __device__ __forceinline__ void skinny_tile(const GemmProb& P, int tile, unsigne
     for (int v = 0; v < 16; ++v) acc[j][v] = 0.f;
 
   const int nslab = (P.K + BK - 1) / BK;
-  int s = (int)(((unsigned)tile * 2654435761u) >> 8) % nslab;  // per-workgroup starting slab
-  fetch(s * BK);
-  for (int it = 0; it < nslab; ++it) {
+  const int s0 = (int)(((unsigned)tile * 2654435761u) >> 8) % nslab;  // per-workgroup starting slab
+  auto slab_k = [&](int i) { const int q = s0 + i; return (q >= nslab ? q - nslab : q) * BK; };
+#pragma unroll
+  for (int d = 0; d < DEPTH; ++d)
+    if (d < nslab) fetch(ra[d], rb[d], slab_k(d));
+  for (int it0 = 0; it0 < nslab; it0 += DEPTH)
+#pragma unroll
+  for (int d = 0; d < DEPTH; ++d) {
+    const int it = it0 + d;
+    if (it >= nslab) break;
     __syncthreads();
 #pragma unroll
-    for (int i = 0; i < NA; ++i) *reinterpret_cast<uint4*>(As + (crow + 16 * i) * LDP + ck) = ra[i];
+    for (int i = 0; i < NA; ++i) *reinterpret_cast<uint4*>(As + (crow + 16 * i) * LDP + ck) = ra[d][i];
 #pragma unroll
-    for (int i = 0; i < NB; ++i) *reinterpret_cast<uint4*>(Bs + (crow + 16 * i) * LDP + ck) = rb[i];
+    for (int i = 0; i < NB; ++i) *reinterpret_cast<uint4*>(Bs + (crow + 16 * i) * LDP + ck) = rb[d][i];
     __syncthreads();
-    s = (s + 1 == nslab) ? 0 : s + 1;
-    if (it + 1 < nslab) fetch(s * BK);
+    if (it + DEPTH < nslab) fetch(ra[d], rb[d], slab_k(it + DEPTH));
     const int kg = (lane >> 5) * E::KPL;
     const T* ap = As + (wm * 32 + (lane & 31)) * LDP + kg;
     const T* bp = Bs + (wn * (BN / 2) + (lane & 31)) * LDP + kg;
