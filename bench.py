@@ -35,6 +35,24 @@ WORKLOAD_TEXT = {
 }
 
 
+KERNELS = {"cfg1": "linear_tick_kernel<float>", "cfg2": "linear_tick_kernel<bf16,64>", "cfg5": "linear_tick_kernel<bf16,128>",
+           "cfg3": "conv_gemm_kernel + conv_wgrad_kernel (+ linear_tick_kernel for the classifier)",
+           "cfg4": "conv_gemm_kernel + conv_wgrad_kernel (+ linear_tick_kernel for the classifier)"}
+
+
+def measured_traffic(workload):
+    """HBM bytes per contraction launch from the committed rocprofv3 --pmc summary of this
+    workload (profiles/hbm_traffic_<workload>.txt: FETCH_SIZE and WRITE_SIZE, each scaled by
+    what the counter reads for a plain 1 GiB copy), or None when no summary is committed."""
+    path = os.path.join(ROOT, "profiles", "hbm_traffic_%s.txt" % workload)
+    if not os.path.exists(path):
+        return None
+    for line in open(path):
+        if line.startswith("traffic_bytes_per_launch"):
+            return float(line.split("=", 1)[1])
+    return None
+
+
 def gpu_run(cfg, rule, steps, warmup, n_batches=4):
     import torch
     from paper_2403_08837_amd import binding as b
@@ -87,7 +105,7 @@ def cpu_baseline(cfg, rule, budget_s=15.0):
     t0 = time.perf_counter()
     O.train_schedule(cfg, p0, xs, ys, rule, keep_versions=False)
     one = time.perf_counter() - t0
-    steps = int(max(1, min(16, budget_s // max(one, 1e-3))))
+    steps = int(max(1, min(512, budget_s // max(one, 1e-3))))
     if steps > 1:
         xs, ys = wl.make_data(cfg, steps, 0)
         t0 = time.perf_counter()
@@ -99,6 +117,55 @@ def cpu_baseline(cfg, rule, budget_s=15.0):
             "sample": "%d full training step(s) of the same workload and rule, fp64 numpy timeline oracle, %.1f s" % (steps, total)}
 
 
+def run_workload(name, rule, steps, warmup, n_batches=4):
+    cfg = wl.get_config(name)
+    r = gpu_run(cfg, rule, steps, warmup, n_batches)
+    samples = cfg.N * cfg.B * steps
+    prof = r["prof"]
+    sec = prof["total_ms"] * 1e-3
+    ai = prof["flops"] / max(prof["bytes"], 1.0)
+    ridge = MFMA_PEAK_TFLOPS[cfg.dtype] * 1e12 / (HBM_PEAK_GBS * 1e9)
+    if ai < ridge:
+        roof = {"bound": "hbm", "achieved": prof["bytes"] / sec / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s"}
+    else:
+        roof = {"bound": "mfma", "achieved": prof["flops"] / sec / 1e12, "peak": MFMA_PEAK_TFLOPS[cfg.dtype], "unit": "TFLOP/s"}
+    roof["frac"] = roof["achieved"] / roof["peak"]
+    roof["traffic"] = measured_traffic(name)
+    roof["kernel"] = KERNELS[name]
+    roof["launches"] = prof["launches"]
+    roof["avg_launch_us"] = prof["total_ms"] * 1e3 / max(1, prof["launches"])
+    roof["algorithmic_bytes_per_launch"] = prof["bytes"] / max(1, prof["launches"])
+    roof["algorithmic_flops_per_launch"] = prof["flops"] / max(1, prof["launches"])
+    roof["arithmetic_intensity_flop_per_byte"] = ai
+    roof["mfma_tflops"] = prof["flops"] / sec / 1e12
+    roof["mfma_frac"] = roof["mfma_tflops"] / MFMA_PEAK_TFLOPS[cfg.dtype]
+    roof["contraction_time_share"] = prof["total_ms"] / r["gpu_ms"]
+    return {
+        "metric": "CDP training samples/sec on 1 MI355X",
+        "value": samples / r["wall"],
+        "unit": "samples/s",
+        "n_gpus": 1,
+        "steps": steps,
+        "warmup": warmup,
+        "ms_per_step": r["wall"] * 1e3 / steps,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "bf16" if cfg.dtype == wl.BF16 else "f32",
+        "data": "synthetic",
+        "config": {"workload": "%s: %s" % (name, WORKLOAD_TEXT[name]), "rule": wl.RULE_NAMES[rule],
+                   "S": cfg.S, "N": cfg.N, "B": cfg.B, "delay_ticks": cfg.delay if rule != wl.RULE_DP else 0},
+        "gpu_ms_per_step": r["gpu_ms"] / steps,
+        "peak_activation_bytes": r["stats"]["peak_activation_bytes"],
+        "dp_activation_bytes": r["stats"]["dp_activation_bytes"],
+        "tick_workspace_bytes": r["stats"]["scratch_bytes"],
+        "peak_live_stage_inputs": r["stats"]["peak_live_stage_inputs"],
+        "kernel_launches_per_step": r["stats"]["kernel_launches"] / max(1, r["stats"]["steps_enqueued"]),
+        "last_step_mean_loss": float(np.mean(r["last_losses"])),
+        "roofline": roof,
+    }
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -107,6 +174,8 @@ def main():
     ap.add_argument("--workload", default="cfg2", choices=sorted(WORKLOAD_TEXT))
     ap.add_argument("--rule", default="v2", choices=["dp", "v1", "v2"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--also", default="cfg5,cfg4",
+                    help="comma-separated further workloads summarised under \"workloads\" (short runs); empty for none")
     ap.add_argument("--calib-copy", action="store_true",
                     help="also run one plain 1 GiB device copy (reference for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE)")
     args = ap.parse_args()
@@ -125,50 +194,15 @@ def main():
         dst.copy_(src)
         torch.cuda.synchronize()
         del src, dst
-    r = gpu_run(cfg, rule, steps, warmup)
-    samples = cfg.N * cfg.B * steps
-    prof = r["prof"]
-    sec = prof["total_ms"] * 1e-3
-    ai = prof["flops"] / max(prof["bytes"], 1.0)
-    ridge = MFMA_PEAK_TFLOPS[cfg.dtype] * 1e12 / (HBM_PEAK_GBS * 1e9)
-    if ai < ridge:
-        roof = {"bound": "hbm", "achieved": prof["bytes"] / sec / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s"}
-    else:
-        roof = {"bound": "mfma", "achieved": prof["flops"] / sec / 1e12, "peak": MFMA_PEAK_TFLOPS[cfg.dtype], "unit": "TFLOP/s"}
-    roof["frac"] = roof["achieved"] / roof["peak"]
-    roof["traffic"] = None
-    roof["kernel"] = "gemm_grouped_kernel"
-    roof["launches"] = prof["launches"]
-    roof["avg_launch_us"] = prof["total_ms"] * 1e3 / max(1, prof["launches"])
-    roof["algorithmic_bytes_per_launch"] = prof["bytes"] / max(1, prof["launches"])
-    roof["algorithmic_flops_per_launch"] = prof["flops"] / max(1, prof["launches"])
-    roof["arithmetic_intensity_flop_per_byte"] = ai
-    roof["mfma_tflops"] = prof["flops"] / sec / 1e12
-    roof["mfma_frac"] = roof["mfma_tflops"] / MFMA_PEAK_TFLOPS[cfg.dtype]
-    roof["gemm_time_share"] = prof["total_ms"] / r["gpu_ms"]
-    out = {
-        "metric": "CDP training samples/sec on 1 MI355X",
-        "value": samples / r["wall"],
-        "unit": "samples/s",
-        "n_gpus": 1,
-        "steps": steps,
-        "warmup": warmup,
-        "ms_per_step": r["wall"] * 1e3 / steps,
-        "higher_is_better": True,
-        "scaling": "weak",
-        "vs_baseline": None,
-        "dtype": "bf16" if cfg.dtype == wl.BF16 else "f32",
-        "data": "synthetic",
-        "config": {"workload": "%s: %s" % (args.workload, WORKLOAD_TEXT[args.workload]), "rule": wl.RULE_NAMES[rule],
-                   "S": cfg.S, "N": cfg.N, "B": cfg.B, "delay_ticks": cfg.delay if rule != wl.RULE_DP else 0},
-        "gpu_ms_per_step": r["gpu_ms"] / steps,
-        "peak_activation_bytes": r["stats"]["peak_activation_bytes"],
-        "dp_activation_bytes": r["stats"]["dp_activation_bytes"],
-        "peak_live_stage_inputs": r["stats"]["peak_live_stage_inputs"],
-        "kernel_launches_per_step": r["stats"]["kernel_launches"] / max(1, r["stats"]["steps_enqueued"]),
-        "last_step_mean_loss": float(np.mean(r["last_losses"])),
-        "roofline": roof,
-    }
+    out = run_workload(args.workload, rule, steps, warmup)
+    if args.also:
+        out["workloads"] = {}
+        for name in args.also.split(","):
+            name = name.strip()
+            if name and name != args.workload:
+                w = run_workload(name, rule, {"cfg1": 100, "cfg2": 100, "cfg3": 10, "cfg4": 3, "cfg5": 10}[name], 2, n_batches=2)
+                out["workloads"][name] = {k: w[k] for k in ("value", "unit", "ms_per_step", "steps", "dtype", "config",
+                                                            "peak_activation_bytes", "dp_activation_bytes", "roofline")}
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cfg, rule)
     print(json.dumps(out))

@@ -98,12 +98,14 @@ typedef struct {
   int64_t steps_enqueued;
   int64_t peak_live_stage_inputs;   /* max over ticks of retained stage inputs (in-tick)  */
   int64_t last_live_stage_inputs;   /* value in the most recent tick                      */
-  int64_t peak_activation_bytes;    /* high-water mark of bytes in use in the pool        */
+  int64_t peak_activation_bytes;    /* high-water mark of retained activations + gradients
+                                       in flight (the pool); per-tick workspace is separate */
   int64_t cur_activation_bytes;
   int64_t pool_span_bytes;          /* arena bytes the pool ever touched                  */
   int64_t dp_activation_bytes;      /* same stages under lock-step DP: N * sum_j bytes_j  */
   int64_t weight_bytes;             /* ring (2 versions) + fp32 master + fp32 accumulator */
   int64_t kernel_launches;
+  int64_t scratch_bytes;            /* peak per-tick workspace (im2col buffers, partial sums) */
 } cdp_stats;
 
 /* Bytes of device arena the configuration needs (weights ring, master, accumulators,

@@ -45,7 +45,8 @@ class cdp_trace_rec(C.Structure):
 class cdp_stats(C.Structure):
     _fields_ = [(n, C.c_int64) for n in (
         "ticks_run", "steps_enqueued", "peak_live_stage_inputs", "last_live_stage_inputs", "peak_activation_bytes",
-        "cur_activation_bytes", "pool_span_bytes", "dp_activation_bytes", "weight_bytes", "kernel_launches")]
+        "cur_activation_bytes", "pool_span_bytes", "dp_activation_bytes", "weight_bytes", "kernel_launches",
+        "scratch_bytes")]
 
 
 class cdp_gemm_profile(C.Structure):

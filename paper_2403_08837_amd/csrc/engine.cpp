@@ -107,6 +107,7 @@ struct cdp_ctx {
   std::vector<StageState> st;
   int64_t labels_off = 0, loss_off = 0;
   Pool pool;
+  int64_t scratch_base = 0, scratch_cap = -1, scratch_bump = 0;  // per-tick workspace (im2col buffers, partial sums)
   std::vector<std::vector<VisitRecord>> rec;  // [mb][stage]
   std::vector<Block> carry;                   // per micro-batch: activation / gradient between stages
   std::vector<Block> deferred;                // released when the tick's launches are enqueued
@@ -150,6 +151,17 @@ bool pool_alloc(cdp_ctx* c, int64_t bytes, Block* b) {
   if (!c->pool.alloc(bytes, b)) return false;
   c->stats.peak_activation_bytes = std::max<int64_t>(c->stats.peak_activation_bytes, c->pool.in_use);
   c->stats.pool_span_bytes = std::max<int64_t>(c->stats.pool_span_bytes, c->pool.bump);
+  return true;
+}
+
+// Workspace that lives for one tick only (reset when the tick's launches are enqueued).
+bool scratch_alloc(cdp_ctx* c, int64_t bytes, Block* b) {
+  bytes = align_up(std::max<int64_t>(bytes, 1), 256);
+  if (c->scratch_cap >= 0 && c->scratch_bump + bytes > c->scratch_cap) return false;
+  b->off = c->scratch_base + c->scratch_bump;
+  b->bytes = bytes;
+  c->scratch_bump += bytes;
+  c->stats.scratch_bytes = std::max<int64_t>(c->stats.scratch_bytes, c->scratch_bump);
   return true;
 }
 
@@ -329,8 +341,7 @@ int build_forward(cdp_ctx* c, int i, int64_t t, int j, int version, const float*
       const void* a_src = c->ptr(r.t[o.in].off);
       if (o.kpad) {  // explicit im2col into a buffer that lives for this tick only
         Block col;
-        if (!pool_alloc(c, (int64_t)c->B * o.Hout * o.Wout * o.kpad * c->plan.elem_bytes, &col)) return fail(c, CDP_ENOMEM, "activation pool exhausted");
-        c->deferred.push_back(col);
+        if (!scratch_alloc(c, (int64_t)c->B * o.Hout * o.Wout * o.kpad * c->plan.elem_bytes, &col)) return fail(c, CDP_ENOMEM, "tick workspace exhausted");
         Item ic; ic.kind = IT_IM2COL;
         ic.p0 = a_src; ic.p2 = c->ptr(col.off); ic.i[0] = c->B; ic.i[1] = o.kpad;
         conv_geom(o, OP_CONV_FWD, &ic.g.g);
@@ -429,8 +440,7 @@ int build_backward(cdp_ctx* c, int i, int j, Program* prog, bool first_grad) {
       size_t wl = level;  // level of the weight-gradient contraction
       if (o.kpad) {       // rebuild the im2col buffer (cheaper than keeping it between the passes)
         Block col;
-        if (!pool_alloc(c, (int64_t)c->B * o.Hout * o.Wout * o.kpad * c->plan.elem_bytes, &col)) return fail(c, CDP_ENOMEM, "activation pool exhausted");
-        c->deferred.push_back(col);
+        if (!scratch_alloc(c, (int64_t)c->B * o.Hout * o.Wout * o.kpad * c->plan.elem_bytes, &col)) return fail(c, CDP_ENOMEM, "tick workspace exhausted");
         Item ic; ic.kind = IT_IM2COL;
         ic.p0 = xin; ic.p2 = c->ptr(col.off); ic.i[0] = c->B; ic.i[1] = o.kpad;
         conv_geom(o, OP_CONV_FWD, &ic.g.g);
@@ -446,8 +456,7 @@ int build_backward(cdp_ctx* c, int i, int j, Program* prog, bool first_grad) {
         two_phase = true;
         const int64_t wn = (int64_t)w.g.splits * o.w_count(), bn = (int64_t)w.g.splits * o.Cout;
         Block ws;
-        if (!pool_alloc(c, (wn + bn) * 4, &ws)) return fail(c, CDP_ENOMEM, "activation pool exhausted");
-        c->deferred.push_back(ws);
+        if (!scratch_alloc(c, (wn + bn) * 4, &ws)) return fail(c, CDP_ENOMEM, "tick workspace exhausted");
         float* part = c->fptr(ws.off);
         Item rd; rd.kind = IT_WREDUCE;
         rd.r.part = part; rd.r.part_beta = o.b_off >= 0 ? part + wn : nullptr;
@@ -724,6 +733,7 @@ int run_tick(cdp_ctx* c, const float* x_dev, const int32_t* y_dev) {
   }
   for (const Block& b : c->deferred) c->pool.release(b);
   c->deferred.clear();
+  c->scratch_bump = 0;
   c->stats.cur_activation_bytes = c->pool.in_use;
   // SGD update of every stage that now holds N gradients (end of tick)
   for (int j = 0; j < S; ++j) {
@@ -801,22 +811,35 @@ int make_ctx(cdp_ctx** out, const cdp_stage_desc* stages, int n_stages, int N, i
 // =============================================================================== C ABI
 extern "C" {
 
-int cdp_arena_bytes(const cdp_stage_desc* stages, int n_stages, int N, int B, int rule, const cdp_opts* opts, size_t* bytes_out) {
-  if (!bytes_out) return fail(nullptr, CDP_EINVAL, "bytes_out is NULL");
+// Dry simulation of the timeline: the pool and the tick workspace are deterministic, so the
+// footprint found here is the footprint of the real run.
+static int simulate_footprint(const cdp_stage_desc* stages, int n_stages, int N, int B, int rule, const cdp_opts* opts,
+                              int64_t* pool_base, int64_t* pool_span, int64_t* scratch_peak) {
   cdp_ctx* c = nullptr;
   int rc = make_ctx(&c, stages, n_stages, N, B, 0.f, rule, opts, true);
   if (rc) return rc;
-  // dry simulation of the timeline: the pool is deterministic, so the span found here is
-  // the span of the real run
   const float* fake_x = reinterpret_cast<const float*>(uintptr_t(256));
   const int32_t* fake_y = reinterpret_cast<const int32_t*>(uintptr_t(256));
   const int steps = 4;
   for (int t = 0; t < steps && rc == CDP_OK; ++t)
     for (int k = 0; k < 2 * n_stages && rc == CDP_OK; ++k) rc = run_tick(c, fake_x, fake_y);
   while (rc == CDP_OK && inflight(c) > 0) rc = run_tick(c, nullptr, nullptr);
-  if (rc == CDP_OK) *bytes_out = (size_t)(c->pool.base + align_up(c->pool.bump, 256) + 256);
-  else g_last_error = c->err;
+  if (rc == CDP_OK) {
+    *pool_base = c->pool.base;
+    *pool_span = align_up(c->pool.bump, 256);
+    *scratch_peak = align_up(c->stats.scratch_bytes, 256);
+  } else {
+    g_last_error = c->err;
+  }
   delete c;
+  return rc;
+}
+
+int cdp_arena_bytes(const cdp_stage_desc* stages, int n_stages, int N, int B, int rule, const cdp_opts* opts, size_t* bytes_out) {
+  if (!bytes_out) return fail(nullptr, CDP_EINVAL, "bytes_out is NULL");
+  int64_t base = 0, span = 0, scratch = 0;
+  int rc = simulate_footprint(stages, n_stages, N, B, rule, opts, &base, &span, &scratch);
+  if (rc == CDP_OK) *bytes_out = (size_t)(base + span + scratch + 256);
   return rc;
 }
 
@@ -827,9 +850,13 @@ int cdp_init(cdp_ctx** out, const cdp_stage_desc* stages, int n_stages, int N, i
   int rc = make_ctx(&c, stages, n_stages, N, B, lr, rule, opts, false);
   if (rc) return rc;
   if (!c->dry) {
-    size_t need = 0;
-    rc = cdp_arena_bytes(stages, n_stages, N, B, rule, opts, &need);
+    int64_t base = 0, span = 0, scratch = 0;
+    rc = simulate_footprint(stages, n_stages, N, B, rule, opts, &base, &span, &scratch);
     if (rc) { delete c; return rc; }
+    const size_t need = (size_t)(base + span + scratch + 256);
+    c->pool.cap = span;
+    c->scratch_base = base + span;
+    c->scratch_cap = scratch;
     if (!opts->arena || (reinterpret_cast<uintptr_t>(opts->arena) & 255) != 0) {
       delete c;
       return fail(nullptr, CDP_EINVAL, "arena must be a 256-byte aligned device pointer");
