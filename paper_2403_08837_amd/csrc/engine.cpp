@@ -261,9 +261,10 @@ GemmProb wgrad_prob(const cdp_ctx* c, const Op& o, const void* dz, const void* x
       // two-phase path: build_backward points out / aux3 at a partial-sum workspace
       const int to = p.M >= 128 ? 128 : 64;
       const int tiles = ((p.M + to - 1) / to) * ((p.N + 127) / 128);
-      // enough ranges to fill the chip, but no more partial-sum traffic than ~24 MB per layer
-      const int64_t by_bytes = std::max<int64_t>(1, (24ll << 20) / (4 * o.w_count()));
-      p.splits = conv_wgrad_splits(p, c->plan.dtype, (int)std::min<int64_t>((768 + tiles - 1) / tiles, by_bytes));
+      // enough ranges to fill the chip together with the other passes of the tick, but no more
+      // partial-sum traffic than ~8 MB per layer
+      const int64_t by_bytes = std::max<int64_t>(1, (8ll << 20) / (4 * o.w_count()));
+      p.splits = conv_wgrad_splits(p, c->plan.dtype, (int)std::min<int64_t>((384 + tiles - 1) / tiles, by_bytes));
     } else {
       const int tiles = ((p.M + 127) / 128) * ((p.N + 127) / 128);
       const int ktiles = (p.K + 31) / 32;
