@@ -32,12 +32,12 @@ __device__ __forceinline__ uint16_t cf2bf(float f) {
 }
 template <typename T> struct CT;
 template <> struct CT<uint16_t> {
-  static constexpr int VEC = 8, MFMA_K = 16, KPL = 8, BK = 32;
+  static constexpr int VEC = 8, MFMA_K = 16, KPL = 8;
   __device__ static __forceinline__ float to_f32(uint16_t v) { return cbf2f(v); }
   __device__ static __forceinline__ uint16_t from_f32(float f) { return cf2bf(f); }
 };
 template <> struct CT<float> {
-  static constexpr int VEC = 4, MFMA_K = 2, KPL = 1, BK = 16;
+  static constexpr int VEC = 4, MFMA_K = 2, KPL = 1;
   __device__ static __forceinline__ float to_f32(float v) { return v; }
   __device__ static __forceinline__ float from_f32(float f) { return f; }
 };
@@ -65,14 +65,15 @@ __device__ __forceinline__ cv16f cmfma_bf16(uint4 a, uint4 b, cv16f c) {
 // forward / data gradient: 128 x BN tile, waves 2 x 2, reduction slab BK (a divisor of the
 // channel count).  The epilogue goes through LDS so that results, residuals and masks move
 // as 16-byte vectors along the channel dimension.
-template <typename T, int BN, int BK>
+template <typename T, int BM, int BN, int BK>
 __global__ __launch_bounds__(256) void conv_gemm_kernel(const GemmBatch batch) {
   using E = CT<T>;
-  constexpr int BM = 128, VEC = E::VEC, LDP = BK + VEC;
+  constexpr int VEC = E::VEC, LDP = BK + VEC;
+  constexpr int WTM = BM / 2, MI = WTM / 32;   // wave tile WTM x WTN
   constexpr int CPR = BK / VEC;                // chunks per tile row
   constexpr int NA = BM * CPR / 256;           // A chunks per thread
   constexpr int NB = BN * CPR / 256;           // B chunks per thread
-  constexpr int WTN = BN / 2, NI = WTN / 32;   // wave tile 64 x WTN
+  constexpr int WTN = BN / 2, NI = WTN / 32;
   constexpr int SP = WTN + 4;                  // pitch (floats) of a wave's 32-row staging area
   constexpr int OPER_BYTES = (BM + BN) * LDP * (int)sizeof(T), STAGE_BYTES = 4 * 32 * SP * 4;
   __shared__ __attribute__((aligned(16))) unsigned char smem[OPER_BYTES > STAGE_BYTES ? OPER_BYTES : STAGE_BYTES];
@@ -159,9 +160,9 @@ __global__ __launch_bounds__(256) void conv_gemm_kernel(const GemmBatch batch) {
     }
   };
 
-  cv16f acc[2][NI];
+  cv16f acc[MI][NI];
 #pragma unroll
-  for (int i = 0; i < 2; ++i)
+  for (int i = 0; i < MI; ++i)
 #pragma unroll
     for (int j = 0; j < NI; ++j)
 #pragma unroll
@@ -178,28 +179,28 @@ __global__ __launch_bounds__(256) void conv_gemm_kernel(const GemmBatch batch) {
     __syncthreads();
     if (it + 1 < nslab) fetch((it + 1) * BK);
     const int kg = (lane >> 5) * E::KPL;
-    const T* ap = As + (wm * 64 + (lane & 31)) * LDP + kg;
+    const T* ap = As + (wm * WTM + (lane & 31)) * LDP + kg;
     const T* bp = Bs + (wn * WTN + (lane & 31)) * LDP + kg;
 #pragma unroll
     for (int kk = 0; kk < BK; kk += E::MFMA_K) {
       if constexpr (sizeof(T) == 2) {
-        uint4 a[2], b[NI];
+        uint4 a[MI], b[NI];
 #pragma unroll
-        for (int i = 0; i < 2; ++i) a[i] = *reinterpret_cast<const uint4*>(ap + i * 32 * LDP + kk);
+        for (int i = 0; i < MI; ++i) a[i] = *reinterpret_cast<const uint4*>(ap + i * 32 * LDP + kk);
 #pragma unroll
         for (int j = 0; j < NI; ++j) b[j] = *reinterpret_cast<const uint4*>(bp + j * 32 * LDP + kk);
 #pragma unroll
-        for (int i = 0; i < 2; ++i)
+        for (int i = 0; i < MI; ++i)
 #pragma unroll
           for (int j = 0; j < NI; ++j) acc[i][j] = cmfma_bf16(a[i], b[j], acc[i][j]);
       } else {
-        float a[2], b[NI];
+        float a[MI], b[NI];
 #pragma unroll
-        for (int i = 0; i < 2; ++i) a[i] = ap[i * 32 * LDP + kk];
+        for (int i = 0; i < MI; ++i) a[i] = ap[i * 32 * LDP + kk];
 #pragma unroll
         for (int j = 0; j < NI; ++j) b[j] = bp[j * 32 * LDP + kk];
 #pragma unroll
-        for (int i = 0; i < 2; ++i)
+        for (int i = 0; i < MI; ++i)
 #pragma unroll
           for (int j = 0; j < NI; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[i], b[j], acc[i][j], 0, 0, 0);
       }
@@ -214,7 +215,7 @@ __global__ __launch_bounds__(256) void conv_gemm_kernel(const GemmBatch batch) {
   constexpr int CPS = WTN / VEC;             // chunks per staged row
   constexpr int NCH = 32 * CPS / 64;         // chunks per lane
 #pragma unroll
-  for (int i = 0; i < 2; ++i) {
+  for (int i = 0; i < MI; ++i) {
     __syncthreads();  // operand tiles (first pass) or the previous staging pass are consumed
 #pragma unroll
     for (int j = 0; j < NI; ++j)
@@ -225,7 +226,7 @@ __global__ __launch_bounds__(256) void conv_gemm_kernel(const GemmBatch batch) {
     for (int t = 0; t < NCH; ++t) {
       const int q = lane + 64 * t;
       const int sr = q / CPS, sc = (q % CPS) * VEC;
-      const int r = row0 + wm * 64 + i * 32 + sr, c = col0 + wn * WTN + sc;
+      const int r = row0 + wm * WTM + i * 32 + sr, c = col0 + wn * WTN + sc;
       if (r >= P.M || c >= P.N) continue;  // N is a multiple of VEC on this path
       const int64_t o = (int64_t)r * P.ldo + c;
       float val[VEC];
@@ -575,15 +576,41 @@ bool conv_fast_eligible(const GemmProb& p, int dtype) {
 }
 
 template <typename T, int BK>
-static void launch_conv_gemm_typed(const GemmBatch& b, bool wide, dim3 grid, hipStream_t stream) {
-  if (wide) hipLaunchKernelGGL((conv_gemm_kernel<T, 128, BK>), grid, dim3(256), 0, stream, b);
-  else hipLaunchKernelGGL((conv_gemm_kernel<T, 64, BK>), grid, dim3(256), 0, stream, b);
+static void launch_conv_gemm_typed(const GemmBatch& b, int bm, int bn, dim3 grid, hipStream_t stream) {
+  if (bm == 128 && bn == 128) hipLaunchKernelGGL((conv_gemm_kernel<T, 128, 128, BK>), grid, dim3(256), 0, stream, b);
+  else if (bm == 128) hipLaunchKernelGGL((conv_gemm_kernel<T, 128, 64, BK>), grid, dim3(256), 0, stream, b);
+  else if (bn == 128) hipLaunchKernelGGL((conv_gemm_kernel<T, 64, 128, BK>), grid, dim3(256), 0, stream, b);
+  else hipLaunchKernelGGL((conv_gemm_kernel<T, 64, 64, BK>), grid, dim3(256), 0, stream, b);
 }
 
-hipError_t launch_conv_gemm(GemmBatch& b, int dtype, bool wide, hipStream_t stream) {
+// Tile shape for the forward / data-gradient problems of one launch: the largest of
+// 128x128, 64x128, 64x64 (128x64, 64x64 when every output is at most 64 wide) that still
+// yields enough workgroups over the whole launch.
+void conv_gemm_tile(const GemmProb* p, int n, int* bm, int* bn) {
+  const int want = 384;
+  bool narrow = true;
+  for (int i = 0; i < n; ++i) narrow = narrow && p[i].N <= 64;
+  auto tiles = [&](int tm, int tn) {
+    int t = 0;
+    for (int i = 0; i < n; ++i) t += ((p[i].M + tm - 1) / tm) * ((p[i].N + tn - 1) / tn);
+    return t;
+  };
+  if (narrow) {
+    *bn = 64;
+    *bm = tiles(128, 64) >= want ? 128 : 64;
+  } else if (tiles(128, 128) >= want) {
+    *bm = 128; *bn = 128;
+  } else if (tiles(64, 128) >= want) {
+    *bm = 64; *bn = 128;
+  } else {
+    *bm = 64; *bn = 64;
+  }
+}
+
+hipError_t launch_conv_gemm(GemmBatch& b, int dtype, int bm, int bn, hipStream_t stream) {
   if (b.n <= 0) return hipSuccess;
   if (b.n > GEMM_MAX_PROBS) return hipErrorInvalidValue;
-  const int bn = wide ? 128 : 64;
+  if ((bm != 64 && bm != 128) || (bn != 64 && bn != 128)) return hipErrorInvalidValue;
   const int bk = dtype == DT_BF16 ? 32 : 16;
   int total = 0;
   bool deep = true;  // every problem allows the double-depth slab
@@ -595,16 +622,16 @@ hipError_t launch_conv_gemm(GemmBatch& b, int dtype, bool wide, hipStream_t stre
     p.splits = 1;
     p.tiles_n = (p.N + bn - 1) / bn;
     p.tile_begin = total;
-    total += ((p.M + 127) / 128) * p.tiles_n;
+    total += ((p.M + bm - 1) / bm) * p.tiles_n;
   }
   b.total_tiles = total;
   dim3 grid(total);
   if (dtype == DT_BF16) {
-    if (deep) launch_conv_gemm_typed<uint16_t, 64>(b, wide, grid, stream);
-    else launch_conv_gemm_typed<uint16_t, 32>(b, wide, grid, stream);
+    if (deep) launch_conv_gemm_typed<uint16_t, 64>(b, bm, bn, grid, stream);
+    else launch_conv_gemm_typed<uint16_t, 32>(b, bm, bn, grid, stream);
   } else {
-    if (deep) launch_conv_gemm_typed<float, 32>(b, wide, grid, stream);
-    else launch_conv_gemm_typed<float, 16>(b, wide, grid, stream);
+    if (deep) launch_conv_gemm_typed<float, 32>(b, bm, bn, grid, stream);
+    else launch_conv_gemm_typed<float, 16>(b, bm, bn, grid, stream);
   }
   return hipGetLastError();
 }

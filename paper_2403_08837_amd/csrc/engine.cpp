@@ -292,7 +292,7 @@ void op_work(const cdp_ctx* c, const Op& o, int pass, bool rmw, bool extra_in, I
 
 // Launch class of a contraction: which kernel family and tile shape runs it.
 enum LaunchClass {
-  LC_LINEAR = 0, LC_CONV_64, LC_CONV_128, LC_CWGRAD_64, LC_CWGRAD_128,
+  LC_LINEAR = 0, LC_CONV_NARROW, LC_CONV_WIDE, LC_CWGRAD_64, LC_CWGRAD_128,
   LC_GEN_FIRST  // LC_GEN_FIRST + 2*shape + wgrad
 };
 
@@ -303,7 +303,7 @@ int launch_class(const GemmProb& p, int dtype) {
     return LC_LINEAR;
   if (conv_fast_eligible(p, dtype)) {
     if (p.epi == EPI_WGRAD) return p.M >= 128 ? LC_CWGRAD_128 : LC_CWGRAD_64;
-    return p.N > 64 ? LC_CONV_128 : LC_CONV_64;
+    return p.N > 64 ? LC_CONV_WIDE : LC_CONV_NARROW;
   }
   int shape;
   if (p.M <= 64) shape = p.N >= 128 ? TILE_64x128 : TILE_64x64;
@@ -533,7 +533,11 @@ int launch_level(cdp_ctx* c, std::vector<Item>& items) {
         for (int q = 0; q < batch.n; ++q)
           if (batch.p[q].epi != EPI_WGRAD) skinny_cols += batch.p[q].N;
         HIP_TRY(c, launch_linear_tick(batch, c->plan.dtype, skinny_cols >= 32768, c->stream));
-      } else if (key == LC_CONV_64 || key == LC_CONV_128) HIP_TRY(c, launch_conv_gemm(batch, c->plan.dtype, key == LC_CONV_128, c->stream));
+      } else if (key == LC_CONV_NARROW || key == LC_CONV_WIDE) {
+        int bm, bn;
+        conv_gemm_tile(batch.p, batch.n, &bm, &bn);
+        HIP_TRY(c, launch_conv_gemm(batch, c->plan.dtype, bm, bn, c->stream));
+      }
       else if (key == LC_CWGRAD_64 || key == LC_CWGRAD_128) HIP_TRY(c, launch_conv_wgrad(batch, c->plan.dtype, key == LC_CWGRAD_128, c->stream));
       else HIP_TRY(c, launch_gemm_batch(batch, c->plan.dtype, (key - LC_GEN_FIRST) / 2, c->stream));
       if (timed) {

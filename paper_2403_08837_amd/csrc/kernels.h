@@ -82,7 +82,8 @@ hipError_t launch_linear_tick(GemmBatch& batch, int dtype, bool wide, hipStream_
 
 // Implicit-GEMM convolution fast paths (channel counts that are multiples of the slab).
 bool conv_fast_eligible(const GemmProb& p, int dtype);
-hipError_t launch_conv_gemm(GemmBatch& batch, int dtype, bool wide, hipStream_t stream);   // forward / data gradient
+void conv_gemm_tile(const GemmProb* p, int n, int* bm, int* bn);  // tile shape that keeps the chip busy for these problems
+hipError_t launch_conv_gemm(GemmBatch& batch, int dtype, int bm, int bn, hipStream_t stream);  // forward / data gradient
 // Weight gradient in two phases: launch_conv_wgrad writes per-range partial sums
 // (out = f32 [splits][Cout][Ncol], aux3 = f32 [splits][Cout] or NULL, splits fixed by
 // conv_wgrad_splits), launch_wgrad_reduce folds them into the accumulators.

@@ -84,7 +84,9 @@ int cdp_k_conv(int dtype, int which, const void* in0, const void* in1, void* out
       return launch_wgrad_reduce(rb, dtype, st) == hipSuccess ? CDP_OK : CDP_EHIP;
     }
   } else if (conv_fast_eligible(p, dtype)) {
-    return launch_conv_gemm(b, dtype, p.N > 64, st) == hipSuccess ? CDP_OK : CDP_EHIP;
+    int bm, bn;
+    conv_gemm_tile(&p, 1, &bm, &bn);
+    return launch_conv_gemm(b, dtype, bm, bn, st) == hipSuccess ? CDP_OK : CDP_EHIP;
   }
   const int shape = p.M <= 64 ? (p.N >= 128 ? TILE_64x128 : TILE_64x64) : (p.N <= 64 ? TILE_64x64 : TILE_128x128);
   return launch_gemm_batch(b, dtype, shape, st) == hipSuccess ? CDP_OK : CDP_EHIP;
