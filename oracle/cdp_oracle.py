@@ -104,9 +104,23 @@ def _copy_params(p):
 # ---------------------------------------------------------------------------
 # Oracle A: the update equation, literally
 # ---------------------------------------------------------------------------
+def sgd_update(w: np.ndarray, gsum: np.ndarray, v: Optional[np.ndarray], lr: float, N: int,
+               momentum: float, weight_decay: float):
+    """One SGD step on the summed micro-batch gradients.  Plain SGD (Eq. (CDP)):
+    w - (lr/N) gsum.  With momentum / weight decay (the optimiser of Sec. 5
+    "Hyperparameters", in the usual convention): g = gsum/N + wd*w, v = mu*v + g,
+    w - lr*v.  Returns (w_new, v_new)."""
+    if momentum == 0.0 and weight_decay == 0.0:
+        return w - (lr / N) * gsum, v
+    g = gsum / N + weight_decay * w
+    v_new = g if v is None else momentum * v + g
+    return w - lr * v_new, v_new
+
+
 def train_equation(cfg: wl.Config, params0, xs: Sequence[np.ndarray], ys: Sequence[np.ndarray],
                    rule: int, lr: Optional[float] = None,
-                   rnd: Callable[[np.ndarray], np.ndarray] = L.identity) -> Result:
+                   rnd: Callable[[np.ndarray], np.ndarray] = L.identity,
+                   momentum: float = 0.0, weight_decay: float = 0.0) -> Result:
     """theta_{t+1} = theta_t - (lr/N) sum_i grad f_i(theta_hat_{i,t}),
     theta_hat^j_{i,t} = theta^j_t if fresh(i,j) else theta^j_{t-1}, theta_{-1} := theta_0."""
     S, N, B = cfg.S, cfg.N, cfg.B
@@ -114,6 +128,7 @@ def train_equation(cfg: wl.Config, params0, xs: Sequence[np.ndarray], ys: Sequen
     d = delay_for(S, N, rule)
     T = len(xs)
     hist = [_copy_params(params0)]
+    vel = [[None for _ in st] for st in hist[0]]
     losses = np.zeros((T, N))
     for t in range(T):
         cur, prev = hist[t], hist[max(t - 1, 0)]
@@ -127,7 +142,14 @@ def train_equation(cfg: wl.Config, params0, xs: Sequence[np.ndarray], ys: Sequen
             for j in range(S):
                 for a, g in zip(gsum[j], grads[j]):
                     a += g
-        hist.append([[w - (lr / N) * g for w, g in zip(cur[j], gsum[j])] for j in range(S)])
+        new = []
+        for j in range(S):
+            stage_new = []
+            for k, (w, g) in enumerate(zip(cur[j], gsum[j])):
+                w2, vel[j][k] = sgd_update(w, g, vel[j][k], lr, N, momentum, weight_decay)
+                stage_new.append(w2)
+            new.append(stage_new)
+        hist.append(new)
     return Result(params=hist[-1], losses=losses, history=hist)
 
 
@@ -138,7 +160,8 @@ def train_schedule(cfg: wl.Config, params0, xs: Sequence[np.ndarray], ys: Sequen
                    rule: int, lr: Optional[float] = None,
                    rnd: Callable[[np.ndarray], np.ndarray] = L.identity,
                    compute: bool = True, keep_versions: bool = True,
-                   progress: Optional[Callable[[int, int], None]] = None) -> Result:
+                   progress: Optional[Callable[[int, int], None]] = None,
+                   momentum: float = 0.0, weight_decay: float = 0.0) -> Result:
     """Per tick: every active micro-batch runs one stage forward or backward with the
     weight version the rule assigns (forward) or the one its own forward used
     (backward); a backward adds its gradient to the stage accumulator; at the end of
@@ -156,6 +179,7 @@ def train_schedule(cfg: wl.Config, params0, xs: Sequence[np.ndarray], ys: Sequen
     ring_ver = [[0, 0] for _ in range(S)]        # which version each slot currently holds
     ver = [0] * S                                # freshest version of each stage
     G = [[np.zeros_like(a) for a in ring[j][0]] for j in range(S)] if compute else [None] * S
+    vel = [[None for _ in ring[j][0]] for j in range(S)] if compute else [None] * S
     cnt = [0] * S
     used: Dict[Tuple[int, int, int], int] = {}   # (t, i, j) -> version read by the forward
     saved: Dict[Tuple[int, int, int], object] = {}
@@ -210,7 +234,11 @@ def train_schedule(cfg: wl.Config, params0, xs: Sequence[np.ndarray], ys: Sequen
             if cnt[j] == N:
                 new = ver[j] + 1
                 if compute:
-                    ring[j][new % 2] = [w - (lr / N) * g for w, g in zip(ring[j][ver[j] % 2], G[j])]
+                    stage_new = []
+                    for k, (w, g) in enumerate(zip(ring[j][ver[j] % 2], G[j])):
+                        w2, vel[j][k] = sgd_update(w, g, vel[j][k], lr, N, momentum, weight_decay)
+                        stage_new.append(w2)
+                    ring[j][new % 2] = stage_new
                     for a in G[j]:
                         a[...] = 0.0
                     if keep_versions:

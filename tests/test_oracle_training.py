@@ -146,3 +146,43 @@ def test_bf16_emulation_stays_close_to_fp64():
         # their own small range from isolated ReLU sign flips, so they are not the gate
         e = O.stage_rel_err(b.params[j], a.params[j])
         assert 0 < e < 2e-2
+
+
+# --- momentum and weight decay (the optimiser the paper trained with, Sec. 5) -----------------
+@pytest.mark.parametrize("rule", [wl.RULE_DP, wl.RULE_V2])
+def test_momentum_weight_decay_single_microbatch_is_torch_sgd(rule):
+    cfg, p0, xs, ys = _setup("mlp_odd", 5, N=1)
+    tp = to_torch_params(p0)
+    opt = torch.optim.SGD([t for st in tp for t in st], lr=cfg.lr, momentum=0.9, weight_decay=5e-4)
+    for t in range(5):
+        opt.zero_grad()
+        torch_forward(cfg.stages, tp, to_torch_x(xs[t]), torch.tensor(ys[t], dtype=torch.long)).backward()
+        opt.step()
+    r = O.train_schedule(cfg, p0, xs, ys, rule, momentum=0.9, weight_decay=5e-4)
+    for j in range(cfg.S):
+        assert _close(r.params[j], [t.detach().numpy() for t in tp[j]], 1e-10)
+
+
+def test_momentum_dp_minibatch_is_torch_sgd():
+    """Eq. (DP) with N micro-batches: the summed gradient / N is the mini-batch mean gradient."""
+    cfg, p0, xs, ys = _setup("mlp_mini", 4)
+    tp = to_torch_params(p0)
+    opt = torch.optim.SGD([t for st in tp for t in st], lr=cfg.lr, momentum=0.9, weight_decay=1e-3)
+    for t in range(4):
+        opt.zero_grad()
+        torch_forward(cfg.stages, tp, to_torch_x(xs[t]), torch.tensor(ys[t], dtype=torch.long)).backward()
+        opt.step()
+    r = O.train_schedule(cfg, p0, xs, ys, wl.RULE_DP, momentum=0.9, weight_decay=1e-3)
+    for j in range(cfg.S):
+        assert _close(r.params[j], [t.detach().numpy() for t in tp[j]], 1e-10)
+
+
+@pytest.mark.parametrize("rule", RULES)
+def test_momentum_equation_equals_timeline(rule):
+    cfg, p0, xs, ys = _setup("mlp_odd", 4)
+    a = O.train_equation(cfg, p0, xs, ys, rule, momentum=0.9, weight_decay=5e-4)
+    b = O.train_schedule(cfg, p0, xs, ys, rule, momentum=0.9, weight_decay=5e-4)
+    for j in range(cfg.S):
+        assert _close(b.params[j], a.params[j], 1e-12)
+    plain = O.train_schedule(cfg, p0, xs, ys, rule)
+    assert O.max_rel_err(b.params[0], plain.params[0]) > 1e-6
