@@ -86,6 +86,9 @@ typedef struct {
   void* hip_stream;    /* hipStream_t, may be NULL (default stream)                     */
   void* arena;         /* dev, 256-byte aligned, at least cdp_arena_bytes() long        */
   size_t arena_bytes;
+  float momentum;      /* SGD momentum in [0,1); 0 = plain SGD of Eq. (CDP).  With momentum the
+                          arena also holds one fp32 velocity per parameter                 */
+  float weight_decay;  /* L2 coefficient added to the mean gradient (all parameters), >= 0   */
 } cdp_opts;
 
 /* One executed (micro-batch, stage) pass. */
@@ -115,7 +118,9 @@ int cdp_arena_bytes(const cdp_stage_desc* stages, int n_stages, int n_microbatch
 
 /* Create a context.  stages/N/micro_batch/lr/rule are the quantities of Sec. 3
  * (theta = {theta^j}, N micro-batches of size B, learning rate gamma, rule u_{i,j}).
- * Requires N | 2S for the cyclic rules.  Weights start at zero until cdp_set_weights. */
+ * Requires N | 2S for the cyclic rules.  Weights start at zero until cdp_set_weights.
+ * Update of a stage holding N gradients (Sec. 5 "Hyperparameters" optimiser when momentum or
+ * weight decay are set): g = (1/N) sum_i grad f_i + wd*theta, v = momentum*v + g, theta -= lr*v. */
 int cdp_init(cdp_ctx** out, const cdp_stage_desc* stages, int n_stages, int n_microbatches,
              int micro_batch, float lr, int rule, const cdp_opts* opts);
 

@@ -76,7 +76,7 @@ struct VisitRecord {
 };
 
 struct StageState {
-  int64_t master = 0, G = 0, slot[2] = {0, 0};
+  int64_t master = 0, G = 0, V = -1, slot[2] = {0, 0};  // V: velocity (momentum) or -1
   int ver = 0, cnt = 0;
   int ring_ver[2] = {0, 0};
 };
@@ -99,7 +99,7 @@ typedef std::vector<std::vector<Item>> Program;
 struct cdp_ctx {
   ModelPlan plan;
   int S = 0, N = 0, B = 0, d = 0, rule = 0;
-  float lr = 0.f;
+  float lr = 0.f, momentum = 0.f, weight_decay = 0.f;
   bool dry = false;
   hipStream_t stream = nullptr;
   char* arena = nullptr;
@@ -171,7 +171,7 @@ struct StaticLayout {
   int64_t labels_off, loss_off, pool_base, weight_bytes;
 };
 
-StaticLayout static_layout(const ModelPlan& plan, int N, int B) {
+StaticLayout static_layout(const ModelPlan& plan, int N, int B, bool velocity) {
   StaticLayout L;
   int64_t off = 0;
   L.weight_bytes = 0;
@@ -179,6 +179,7 @@ StaticLayout static_layout(const ModelPlan& plan, int N, int B) {
     StageState s;
     s.master = off; off = align_up(off + sp.n_params * 4, 256);
     s.G = off; off = align_up(off + sp.n_params * 4, 256);
+    if (velocity) { s.V = off; off = align_up(off + sp.n_params * 4, 256); }
     s.slot[0] = off; off = align_up(off + sp.slot_bytes, 256);
     s.slot[1] = off; off = align_up(off + sp.slot_bytes, 256);
     L.st.push_back(s);
@@ -621,29 +622,31 @@ int launch_program(cdp_ctx* c, Program& prog) {
 }
 
 // Writes the compute copies of stage j's current master weights into ring slot `slot`;
-// with scale != 0 first applies master -= scale * G (the SGD step of Eq. (CDP)).
-int refresh_slot(cdp_ctx* c, int j, int slot, float scale) {
+// with apply first takes the SGD step of Eq. (CDP) on the master weights.
+int refresh_slot(cdp_ctx* c, int j, int slot, bool apply) {
+  SgdParams sgd{c->lr, 1.0f / (float)c->N, c->momentum, c->weight_decay, apply ? 1 : 0};
   const StagePlan& sp = c->plan.stages[j];
   const StageState& ss = c->st[j];
   char* sl = static_cast<char*>(c->ptr(ss.slot[slot]));
   float* master = c->fptr(ss.master);
   float* G = c->fptr(ss.G);
+  float* V = ss.V >= 0 ? c->fptr(ss.V) : nullptr;
   for (const Op& o : sp.ops) {
     if (o.kind != OPK_GEMM) continue;
     // vector parameters first: the folded weights use the updated gamma
     if (o.g_off >= 0) {
-      HIP_TRY(c, launch_update_vec(master + o.g_off, G + o.g_off, reinterpret_cast<float*>(sl + o.gamma_c), o.Cout, scale, c->stream));
+      HIP_TRY(c, launch_update_vec(master + o.g_off, G + o.g_off, V ? V + o.g_off : nullptr, reinterpret_cast<float*>(sl + o.gamma_c), o.Cout, sgd, c->stream));
       c->stats.kernel_launches++;
     }
     if (o.b_off >= 0) {
-      HIP_TRY(c, launch_update_vec(master + o.b_off, G + o.b_off, reinterpret_cast<float*>(sl + o.bias_c), o.Cout, scale, c->stream));
+      HIP_TRY(c, launch_update_vec(master + o.b_off, G + o.b_off, V ? V + o.b_off : nullptr, reinterpret_cast<float*>(sl + o.bias_c), o.Cout, sgd, c->stream));
       c->stats.kernel_launches++;
     }
     RepackArgs a;
-    a.master = master + o.w_off; a.G = G + o.w_off;
+    a.master = master + o.w_off; a.G = G + o.w_off; a.V = V ? V + o.w_off : nullptr;
     a.gamma = o.has_gamma ? reinterpret_cast<const float*>(sl + o.gamma_c) : nullptr;
     a.wf = sl + o.wf; a.wt = sl + o.wt; a.wp = o.has_gamma ? sl + o.wp : nullptr;
-    a.O = o.Cout; a.T = o.KH * o.KW; a.C = o.Cin; a.scale = scale;
+    a.O = o.Cout; a.T = o.KH * o.KW; a.C = o.Cin; a.sgd = sgd;
     a.ldf = o.kpad ? o.kpad : a.T * a.C;
     a.zero_g = o.is_conv ? 1 : 0;  // conv accumulators take atomic adds and must start at zero
     HIP_TRY(c, launch_repack(a, c->plan.dtype, c->stream));
@@ -746,7 +749,7 @@ int run_tick(cdp_ctx* c, const float* x_dev, const int32_t* y_dev) {
     if (ss.cnt != N) continue;
     const int nv = ss.ver + 1;
     if (!c->dry) {
-      int rc = refresh_slot(c, j, nv & 1, c->lr / (float)N);
+      int rc = refresh_slot(c, j, nv & 1, true);
       if (rc) return rc;
     }
     ss.ring_ver[nv & 1] = nv;
@@ -774,6 +777,8 @@ int check_args(const cdp_stage_desc* stages, int n_stages, int N, int B, int rul
     return fail(nullptr, CDP_EINVAL, "the cyclic schedule needs N to divide 2S (uniform delay d = 2S/N)");
   std::string e = build_plan(stages, n_stages, opts, plan);
   if (!e.empty()) return fail(nullptr, CDP_EINVAL, e);
+  if (!(opts->momentum >= 0.f && opts->momentum < 1.f) || !(opts->weight_decay >= 0.f))
+    return fail(nullptr, CDP_EINVAL, "momentum must be in [0, 1) and weight_decay >= 0");
   if (B > 1024 && plan->stages.back().has_head) return fail(nullptr, CDP_EINVAL, "micro_batch above 1024 is not supported by the loss head");
   return CDP_OK;
 }
@@ -789,7 +794,8 @@ int make_ctx(cdp_ctx** out, const cdp_stage_desc* stages, int n_stages, int N, i
   c->stream = static_cast<hipStream_t>(opts->hip_stream);
   c->arena = c->dry ? nullptr : static_cast<char*>(opts->arena);
   c->arena_bytes = (int64_t)opts->arena_bytes;
-  StaticLayout L = static_layout(c->plan, N, B);
+  c->momentum = opts->momentum; c->weight_decay = opts->weight_decay;
+  StaticLayout L = static_layout(c->plan, N, B, c->momentum != 0.f);
   c->st = L.st;
   c->labels_off = L.labels_off; c->loss_off = L.loss_off;
   c->pool.base = L.pool_base;
@@ -897,7 +903,7 @@ int cdp_set_weights(cdp_ctx* c, int stage, const float* host, size_t n) {
   HIP_TRY(c, hipMemcpyAsync(c->fptr(c->st[stage].master), host, n * 4, hipMemcpyHostToDevice, c->stream));
   HIP_TRY(c, hipStreamSynchronize(c->stream));
   for (int s = 0; s < 2; ++s) {
-    int rc = refresh_slot(c, stage, s, 0.f);
+    int rc = refresh_slot(c, stage, s, false);
     if (rc) return rc;
   }
   return CDP_OK;

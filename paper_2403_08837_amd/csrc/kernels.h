@@ -118,19 +118,25 @@ constexpr int COLSUM_MAX_PROBS = 32;
 struct ColsumBatch { int n; ColsumProb p[COLSUM_MAX_PROBS]; };
 hipError_t launch_colsum_batch(const ColsumBatch& b, int dtype, hipStream_t stream);
 
-// Vector parameters (bias, gamma, beta): master -= scale*G ; G = 0 ; copy = master.
-hipError_t launch_update_vec(float* master, float* G, float* copy_f32, int64_t n, float scale,
+// SGD step on fp32 master parameters from the summed micro-batch gradients G (Eq. (CDP)),
+// optionally with momentum and weight decay (the optimiser of Sec. 5 "Hyperparameters"):
+//   g = G*inv_n + wd*w ;  v = momentum*v + g (when a velocity buffer is given) ;  w -= lr*v.
+// apply == 0 leaves the parameters as they are (initial fill of the ring slots).
+struct SgdParams { float lr, inv_n, momentum, wd; int apply; };
+
+// Vector parameters (bias, gamma, beta): SGD step ; G = 0 ; copy = master.  V may be NULL.
+hipError_t launch_update_vec(float* master, float* G, float* V, float* copy_f32, int64_t n, SgdParams sgd,
                              hipStream_t stream);
 
-// Matrix parameters W[O][T][C] (Linear: T = 1):  master -= scale*G (if scale != 0), G = 0
-// if zero_g, then write the compute copies of the new version:
+// Matrix parameters W[O][T][C] (Linear: T = 1):  SGD step on master (V = velocity or NULL),
+// G = 0 if zero_g, then write the compute copies of the new version:
 //   wf[o][t][c] = T(gamma[o]*master)   forward layout
 //   wt[c][t][o] = T(gamma[o]*master)   data-gradient layout
 //   wp[o][t][c] = T(master)            plain copy (only when gamma != NULL)
 struct RepackArgs {
-  float* master; float* G; const float* gamma;
+  float* master; float* G; float* V; const float* gamma;
   void* wf; void* wt; void* wp;
-  int O, T, C; float scale; int zero_g;
+  int O, T, C; SgdParams sgd; int zero_g;
   int ldf;  // row length of wf (T*C, or the zero-padded length of an im2col layer)
 };
 hipError_t launch_repack(const RepackArgs& a, int dtype, hipStream_t stream);

@@ -131,21 +131,30 @@ hipError_t launch_colsum_batch(const ColsumBatch& b, int dtype, hipStream_t stre
 }
 
 // ---------------------------------------------------------------------------------
-__global__ void update_vec_kernel(float* __restrict__ master, float* __restrict__ G, float* __restrict__ copy, int64_t n,
-                                  float scale) {
+__device__ __forceinline__ float sgd_step(float w, float gsum, float* v, const SgdParams& p) {
+  float g = gsum * p.inv_n + p.wd * w;
+  if (v) {
+    g = p.momentum * (*v) + g;
+    *v = g;
+  }
+  return w - p.lr * g;
+}
+
+__global__ void update_vec_kernel(float* __restrict__ master, float* __restrict__ G, float* __restrict__ V,
+                                  float* __restrict__ copy, int64_t n, SgdParams sgd) {
   for (int64_t i = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x) {
     float w = master[i];
-    if (scale != 0.f) {
-      w -= scale * G[i];
+    if (sgd.apply) {
+      w = sgd_step(w, G[i], V ? V + i : nullptr, sgd);
       master[i] = w;
     }
     G[i] = 0.f;
     copy[i] = w;
   }
 }
-hipError_t launch_update_vec(float* master, float* G, float* copy_f32, int64_t n, float scale, hipStream_t stream) {
+hipError_t launch_update_vec(float* master, float* G, float* V, float* copy_f32, int64_t n, SgdParams sgd, hipStream_t stream) {
   if (n <= 0) return hipSuccess;
-  hipLaunchKernelGGL(update_vec_kernel, dim3(blocks_for(n, 256, 1024)), dim3(256), 0, stream, master, G, copy_f32, n, scale);
+  hipLaunchKernelGGL(update_vec_kernel, dim3(blocks_for(n, 256, 1024)), dim3(256), 0, stream, master, G, V, copy_f32, n, sgd);
   return hipGetLastError();
 }
 
@@ -167,8 +176,8 @@ __global__ __launch_bounds__(256) void repack_kernel(const RepackArgs a) {
     if (o < a.O && c < a.C) {
       const int64_t idx = ((int64_t)o * a.T + t) * a.C + c;
       float w = a.master[idx];
-      if (a.scale != 0.f) {
-        w -= a.scale * a.G[idx];
+      if (a.sgd.apply) {
+        w = sgd_step(w, a.G[idx], a.V ? a.V + idx : nullptr, a.sgd);
         a.master[idx] = w;
       }
       if (a.zero_g) a.G[idx] = 0.f;

@@ -49,10 +49,11 @@ class Progress:
                 f.write(line)
 
 
-def run_gpu(cfg, rule, T, p0, xs, ys, lr=None):
+def run_gpu(cfg, rule, T, p0, xs, ys, lr=None, momentum=0.0, weight_decay=0.0):
     import torch
     assert torch.cuda.is_available(), "GPU tests need a GPU"
-    tr = b.Trainer(cfg.stages, cfg.in_shape, cfg.N, cfg.B, cfg.lr if lr is None else lr, rule, cfg.dtype)
+    tr = b.Trainer(cfg.stages, cfg.in_shape, cfg.N, cfg.B, cfg.lr if lr is None else lr, rule, cfg.dtype,
+                   momentum=momentum, weight_decay=weight_decay)
     tr.set_weights(p0)
     keep = []
     for t in range(T):
@@ -69,16 +70,18 @@ def run_gpu(cfg, rule, T, p0, xs, ys, lr=None):
     return out
 
 
-def check(cfg, rule, T, seed=0, lr=None, tensor_tol=0.5, capfd=None):
+def check(cfg, rule, T, seed=0, lr=None, tensor_tol=0.5, capfd=None, momentum=0.0, weight_decay=0.0):
     xs, ys = wl.make_data(cfg, T, seed)
     p0 = wl.init_params(cfg, seed)
-    ref = O.train_schedule(cfg, p0, xs, ys, rule, lr=lr, keep_versions=False, progress=Progress(cfg.name, capfd))
-    got = run_gpu(cfg, rule, T, p0, xs, ys, lr=lr)
+    ref = O.train_schedule(cfg, p0, xs, ys, rule, lr=lr, keep_versions=False, progress=Progress(cfg.name, capfd),
+                           momentum=momentum, weight_decay=weight_decay)
+    got = run_gpu(cfg, rule, T, p0, xs, ys, lr=lr, momentum=momentum, weight_decay=weight_decay)
     f32 = cfg.dtype == wl.F32
     assert got["trace"] == ref.trace
     assert got["live"] == ref.live_inputs
     emu = ref if (f32 or tensor_tol is None) else O.train_schedule(cfg, p0, xs, ys, rule, lr=lr, rnd=OL.round_bf16,
-                                                                   keep_versions=False)
+                                                                   keep_versions=False, momentum=momentum,
+                                                                   weight_decay=weight_decay)
     worst_t, worst_s, worst_u = 0.0, 0.0, 0.0
     for j in range(cfg.S):
         worst_t = max(worst_t, O.max_rel_err(got["weights"][j], ref.params[j]))
@@ -214,6 +217,14 @@ def test_cfg4_resnet50_bf16_full_config_sampled():
         for g, w0 in zip(got["weights"][j], p0[j]):
             assert np.isfinite(g).all()
         assert any(np.abs(g - w0).max() > 0 for g, w0 in zip(got["weights"][j], p0[j]))
+
+
+@pytest.mark.parametrize("name,rule", [("mlp_odd", wl.RULE_V2), ("mlp_odd", wl.RULE_V1), ("resnet18_mini_f32", wl.RULE_V2),
+                                       ("cfg2_mini", wl.RULE_V2), ("resnet18_mini", wl.RULE_DP)])
+def test_momentum_and_weight_decay(name, rule):
+    """SGD with momentum 0.9 and weight decay 5e-4 (the optimiser of Sec. 5 "Hyperparameters")."""
+    cfg = wl.get_config(name)
+    check(cfg, rule, cfg.steps, momentum=0.9, weight_decay=5e-4)
 
 
 def test_ring_copy_of_previous_version():
