@@ -6,7 +6,8 @@ Notation (0-indexed; the paper is 1-indexed and takes #stages = #micro-batches):
   S  number of stages, N number of micro-batches, B micro-batch size,
   d  start delay between consecutive micro-batches in ticks ("time steps").
      The paper fixes d = 2 for S = N (Sec. 3.2, "Algorithmic description"); here
-     d = 2S/N so that the cycle closes for S != N (a reading).
+     d = 2S/N so that the cycle closes for S != N (a reading of the paper's
+     "uniform delay"; it requires N | 2S).
   tick   one forward or one backward of one stage (Sec. 3.1, "Disadvantages of DP")
   step t indexes theta_t; one step = 2S ticks.
   phase p of a micro-batch in its own pass: p < S forward of stage p,

@@ -10,7 +10,7 @@ CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libcdp.so")
 SOURCES = ["gemm.hip", "linear_kernels.hip", "conv_kernels.hip", "small_kernels.hip", "engine.cpp", "plan.cpp", "kernels_api.cpp"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-# packed-fp32 VALU forms are switched off for all device code ("Build")
+# packed-fp32 VALU forms are switched off for all device code: the compiler then emits scalar fp32 ops only
 # fp32 atomic adds go to coarse-grained device memory (the arena): use the hardware instruction, not a CAS loop
 DEVICE_FLAGS = ["--offload-arch=gfx950", "-munsafe-fp-atomics", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 COMMON = ["-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function", "-D__HIP_PLATFORM_AMD__"]

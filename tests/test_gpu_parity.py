@@ -24,14 +24,14 @@ RULES = [wl.RULE_DP, wl.RULE_V1, wl.RULE_V2]
 
 
 class Progress:
-    """Progress lines of a long oracle run, written past pytest's capture (and appended to
-    gpurun_out/progress.log when that folder exists) so that a slow CPU reference is not
-    mistaken for a hang."""
+    """Progress lines of a long oracle run, written past pytest's capture (and appended to the
+    file named by CDP_PROGRESS_FILE, if set) so that a slow CPU reference is not mistaken
+    for a hang."""
 
     def __init__(self, label, capfd=None, every_s=20.0):
         import os, time
         self.label, self.every, self.t0, self.last, self.capfd = label, every_s, time.time(), time.time(), capfd
-        self.path = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "gpurun_out")
+        self.path = os.environ.get("CDP_PROGRESS_FILE", "")
 
     def __call__(self, tick, n_ticks):
         import os, sys, time
@@ -44,8 +44,8 @@ class Progress:
             with self.capfd.disabled():
                 sys.stdout.write(line)
                 sys.stdout.flush()
-        if os.path.isdir(self.path):
-            with open(os.path.join(self.path, "progress.log"), "a") as f:
+        if self.path:
+            with open(self.path, "a") as f:
                 f.write(line)
 
 
