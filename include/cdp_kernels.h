@@ -19,7 +19,9 @@ extern "C" {
  *   dtype      0 fp32, 1 bf16 (operand element type)
  *   tile_shape 0: 128x128, 1: 64x128, 2: 64x64 workgroup tile of the generic kernel;
  *              3: 64x64, 4: 64x128 tile of the weight-streaming kernel the Linear stages
- *              use (needs a_kmajor = b_kmajor = 1)
+ *              use; 5: the same kernel as launched by the engine, which gives problems of
+ *              at most 32 rows with 16-byte-chunked operands 32x32 tiles whose waves split
+ *              the reduction (3..5 need a_kmajor = b_kmajor = 1)
  *   a_kmajor   1: A[m][k] at A[m*lda + k]   0: A[m][k] at A[k*lda + m]
  *   b_kmajor   1: B[n][k] at B[n*ldb + k]   0: B[n][k] at B[k*ldb + n] */
 int cdp_k_gemm(int dtype, int tile_shape, int a_kmajor, int b_kmajor, const void* A, const void* B,

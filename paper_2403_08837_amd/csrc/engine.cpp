@@ -533,7 +533,7 @@ int launch_level(cdp_ctx* c, std::vector<Item>& items) {
         int64_t skinny_cols = 0;
         for (int q = 0; q < batch.n; ++q)
           if (batch.p[q].epi != EPI_WGRAD) skinny_cols += batch.p[q].N;
-        HIP_TRY(c, launch_linear_tick(batch, c->plan.dtype, skinny_cols >= 32768, c->stream));
+        HIP_TRY(c, launch_linear_tick(batch, c->plan.dtype, skinny_cols >= 32768, true, c->stream));
       } else if (key == LC_CONV_NARROW || key == LC_CONV_WIDE) {
         int bm, bn;
         conv_gemm_tile(batch.p, batch.n, &bm, &bn);

@@ -54,7 +54,7 @@ struct GemmProb {
   ConvGeom g;        // geometry of the (single) gathered operand, if any
 };
 
-enum : int { GF_RELU = 1, GF_OUT_F32 = 2, GF_ACCUM = 4, GF_ATOMIC = 8 };
+enum : int { GF_RELU = 1, GF_OUT_F32 = 2, GF_ACCUM = 4, GF_ATOMIC = 8, GF_THIN = 16 /* set by launch_linear_tick */ };
 
 constexpr int GEMM_MAX_PROBS = 24;
 struct GemmBatch {
@@ -77,8 +77,10 @@ hipError_t launch_gemm_batch(GemmBatch& batch, int dtype, int tile_shape, hipStr
 //   dw:     weight gradient G (+)= dY^T X with A = dY (OP_PLAIN_R), B = X (OP_PLAIN_R),
 //           GF_ACCUM selects accumulate vs overwrite; aux2 = bias-gradient vector or NULL
 //           (same accumulate/overwrite rule).
-// Both kinds may be mixed in one batch (one launch per tick level).
-hipError_t launch_linear_tick(GemmBatch& batch, int dtype, bool wide, hipStream_t stream);
+//   thin:   forward / data gradient of problems with at most 32 rows and 16-byte-chunked
+//           operands (chosen per problem when allow_thin): no staging, split reduction.
+// All kinds may be mixed in one batch (one launch per tick level).
+hipError_t launch_linear_tick(GemmBatch& batch, int dtype, bool wide, bool allow_thin, hipStream_t stream);
 
 // Implicit-GEMM convolution fast paths (channel counts that are multiples of the slab).
 bool conv_fast_eligible(const GemmProb& p, int dtype);

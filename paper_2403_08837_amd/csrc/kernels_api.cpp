@@ -13,7 +13,7 @@ extern "C" {
 
 int cdp_k_gemm(int dtype, int tile_shape, int a_kmajor, int b_kmajor, const void* A, const void* B, float* C, int M, int N,
                int K, int lda, int ldb, void* stream) {
-  if (!A || !B || !C || M <= 0 || N <= 0 || K <= 0 || tile_shape < 0 || tile_shape >= TILE_COUNT + 2) return CDP_EINVAL;
+  if (!A || !B || !C || M <= 0 || N <= 0 || K <= 0 || tile_shape < 0 || tile_shape >= TILE_COUNT + 3) return CDP_EINVAL;
   if (tile_shape >= TILE_COUNT && !(a_kmajor && b_kmajor)) return CDP_EINVAL;
   if (dtype != DT_F32 && dtype != DT_BF16) return CDP_EINVAL;
   GemmBatch b;
@@ -28,7 +28,7 @@ int cdp_k_gemm(int dtype, int tile_shape, int a_kmajor, int b_kmajor, const void
   p.flags = GF_OUT_F32;
   p.splits = 1;
   if (tile_shape >= TILE_COUNT)
-    return launch_linear_tick(b, dtype, tile_shape == TILE_COUNT + 1, static_cast<hipStream_t>(stream)) == hipSuccess ? CDP_OK : CDP_EHIP;
+    return launch_linear_tick(b, dtype, tile_shape == TILE_COUNT + 1, tile_shape == TILE_COUNT + 2, static_cast<hipStream_t>(stream)) == hipSuccess ? CDP_OK : CDP_EHIP;
   return launch_gemm_batch(b, dtype, tile_shape, static_cast<hipStream_t>(stream)) == hipSuccess ? CDP_OK : CDP_EHIP;
 }
 

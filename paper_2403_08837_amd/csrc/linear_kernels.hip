@@ -70,6 +70,26 @@ __device__ __forceinline__ v16f_t mfma_bf16(uint4 a, uint4 b, v16f_t c) {
 
 }  // namespace
 
+// Epilogue of one output element of a forward (bias, residual, ReLU) or data-gradient
+// (addend, accumulate, ReLU mask) contraction.
+template <typename T>
+__device__ __forceinline__ void store_result(const GemmProb& P, int r, int c, float val, float bias) {
+  using E = LT<T>;
+  const int64_t o = (int64_t)r * P.ldo + c;
+  if (P.epi == EPI_FWD) {
+    val += bias;
+    if (P.aux1) val += E::to_f32(static_cast<const T*>(P.aux1)[o]);
+    if (P.flags & GF_RELU) val = fmaxf(val, 0.f);
+    if (P.flags & GF_OUT_F32) static_cast<float*>(P.out)[o] = val;
+    else static_cast<T*>(P.out)[o] = E::from_f32(val);
+  } else {
+    if (P.aux0) val += E::to_f32(static_cast<const T*>(P.aux0)[o]);
+    if (P.flags & GF_ACCUM) val += E::to_f32(static_cast<T*>(P.out)[o]);
+    if (P.aux1 && !(E::to_f32(static_cast<const T*>(P.aux1)[o]) > 0.f)) val = 0.f;
+    static_cast<T*>(P.out)[o] = E::from_f32(val);
+  }
+}
+
 // ---------------------------------------------------------------------------------
 // skinny tile: 64 x BN outputs, waves 2 (rows) x 2 (cols).
 template <typename T, int BN>
@@ -174,7 +194,6 @@ __device__ __forceinline__ void skinny_tile(const GemmProb& P, int tile, unsigne
     }
   }
 
-  const int flags = P.flags;
 #pragma unroll
   for (int j = 0; j < NI; ++j) {
     const int c = col0 + wn * (BN / 2) + j * 32 + (lane & 31);
@@ -183,21 +202,90 @@ __device__ __forceinline__ void skinny_tile(const GemmProb& P, int tile, unsigne
     for (int v = 0; v < 16; ++v) {
       const int r = row0 + wm * 32 + (v >> 2) * 8 + (lane >> 5) * 4 + (v & 3);
       if (r >= P.M || c >= P.N) continue;
-      float val = acc[j][v];
-      const int64_t o = (int64_t)r * P.ldo + c;
-      if (P.epi == EPI_FWD) {
-        val += bias;
-        if (P.aux1) val += E::to_f32(static_cast<const T*>(P.aux1)[o]);
-        if (flags & GF_RELU) val = fmaxf(val, 0.f);
-        if (flags & GF_OUT_F32) static_cast<float*>(P.out)[o] = val;
-        else static_cast<T*>(P.out)[o] = E::from_f32(val);
-      } else {
-        if (P.aux0) val += E::to_f32(static_cast<const T*>(P.aux0)[o]);
-        if (flags & GF_ACCUM) val += E::to_f32(static_cast<T*>(P.out)[o]);
-        if (P.aux1 && !(E::to_f32(static_cast<const T*>(P.aux1)[o]) > 0.f)) val = 0.f;
-        static_cast<T*>(P.out)[o] = E::from_f32(val);
+      store_result<T>(P, r, c, acc[j][v], bias);
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------------
+// thin tile: problems of at most 32 rows whose operands are whole 16-byte chunks.  A
+// workgroup owns 32 x 32 outputs and its four waves split the reduction: wave w takes
+// slabs w, w+4, ...  Nothing is staged: a lane loads its MFMA fragments straight from
+// memory, and because the order of the reduction index is free as long as both operands
+// agree, lane (row, half) reads one contiguous 128-byte run of its row per slab (half 0
+// the first run, half 1 the second) instead of interleaved 16-byte pieces.  The k-loop has
+// no barrier; the partial tiles meet once in LDS, each wave finishing 8 of the 32 rows.
+template <typename T>
+__device__ __forceinline__ void thin_tile(const GemmProb& P, int tile, unsigned char* smem) {
+  using E = LT<T>;
+  constexpr int VEC = E::VEC, CH = 8, RUN = CH * VEC, SLAB = 2 * RUN;
+  const int col0 = (tile - P.tile_begin) * 32;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int r31 = lane & 31, g = lane >> 5;
+  // rows past the end are read from the last valid row: they only reach outputs that are not stored
+  const T* __restrict__ ap = static_cast<const T*>(P.A) + (int64_t)min(r31, P.M - 1) * P.lda + g * RUN;
+  const T* __restrict__ bp = static_cast<const T*>(P.B) + (int64_t)min(col0 + r31, P.N - 1) * P.ldb + g * RUN;
+  const int nslab = (P.K + SLAB - 1) / SLAB;
+  const int s0 = (int)(((unsigned)tile * 2654435761u) >> 8) % nslab;
+  auto slab_k = [&](int i) { const int q = s0 + i; return (q >= nslab ? q - nslab : q) * SLAB; };
+
+  uint4 ra[2][CH], rb[2][CH];
+  auto fetch = [&](uint4* qa, uint4* qb, int k0) {
+    if (k0 + SLAB <= P.K) {
+#pragma unroll
+      for (int c = 0; c < CH; ++c) {
+        qa[c] = *reinterpret_cast<const uint4*>(ap + k0 + c * VEC);
+        qb[c] = *reinterpret_cast<const uint4*>(bp + k0 + c * VEC);
+      }
+    } else {  // last, partial slab: chunks past K are zero in both operands
+#pragma unroll
+      for (int c = 0; c < CH; ++c) {
+        const bool kin = k0 + g * RUN + c * VEC < P.K;
+        qa[c] = kin ? *reinterpret_cast<const uint4*>(ap + k0 + c * VEC) : make_uint4(0, 0, 0, 0);
+        qb[c] = kin ? *reinterpret_cast<const uint4*>(bp + k0 + c * VEC) : make_uint4(0, 0, 0, 0);
       }
     }
+  };
+  v16f_t acc;
+#pragma unroll
+  for (int v = 0; v < 16; ++v) acc[v] = 0.f;
+  auto contract = [&](const uint4* qa, const uint4* qb) {
+#pragma unroll
+    for (int c = 0; c < CH; ++c) {
+      if constexpr (sizeof(T) == 2) {
+        acc = mfma_bf16(qa[c], qb[c], acc);
+      } else {
+        acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(qa[c].x), __uint_as_float(qb[c].x), acc, 0, 0, 0);
+        acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(qa[c].y), __uint_as_float(qb[c].y), acc, 0, 0, 0);
+        acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(qa[c].z), __uint_as_float(qb[c].z), acc, 0, 0, 0);
+        acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(qa[c].w), __uint_as_float(qb[c].w), acc, 0, 0, 0);
+      }
+    }
+  };
+  int s = wave;
+  if (s < nslab) fetch(ra[0], rb[0], slab_k(s));
+  if (s + 4 < nslab) fetch(ra[1], rb[1], slab_k(s + 4));
+  for (; s < nslab; s += 8) {
+    contract(ra[0], rb[0]);
+    if (s + 8 < nslab) fetch(ra[0], rb[0], slab_k(s + 8));
+    if (s + 4 < nslab) {
+      contract(ra[1], rb[1]);
+      if (s + 12 < nslab) fetch(ra[1], rb[1], slab_k(s + 12));
+    }
+  }
+
+  float* red = reinterpret_cast<float*>(smem);  // [4 waves][16][64 lanes]
+#pragma unroll
+  for (int v = 0; v < 16; ++v) red[(wave * 16 + v) * 64 + lane] = acc[v];
+  __syncthreads();
+  const int c = col0 + r31;
+  const float bias = (P.epi == EPI_FWD && P.aux0 != nullptr && c < P.N) ? static_cast<const float*>(P.aux0)[c] : 0.f;
+#pragma unroll
+  for (int q = 0; q < 4; ++q) {
+    const int v = wave * 4 + q;
+    const float val = (red[v * 64 + lane] + red[(16 + v) * 64 + lane]) + (red[(32 + v) * 64 + lane] + red[(48 + v) * 64 + lane]);
+    const int r = wave * 8 + g * 4 + q;
+    if (r < P.M && c < P.N) store_result<T>(P, r, c, val, bias);
   }
 }
 
@@ -333,13 +421,14 @@ __device__ __forceinline__ void dw_tile(const GemmProb& P, int tile, unsigned ch
 
 // ---------------------------------------------------------------------------------
 // One launch for every Linear contraction of a tick level: the tile list mixes forward /
-// data-gradient tiles (skinny) and weight-gradient tiles (dw), so the short read-modify-write
-// tiles fill the machine while the long weight-streaming tiles run.
-template <typename T, int BN>
+// data-gradient tiles (skinny or thin) and weight-gradient tiles (dw), so the short read-
+// modify-write tiles fill the machine while the long weight-streaming tiles run.
+template <typename T, int BN, bool THIN>
 __global__ __launch_bounds__(256) void linear_tick_kernel(const GemmBatch batch) {
   using E = LT<T>;
   constexpr int SK_BYTES = (64 + BN) * (E::SLAB + E::VEC) * (int)sizeof(T);
   constexpr int DW_BYTES = 64 * (64 + 4 + 128 + 4) * (int)sizeof(T);
+  static_assert(SK_BYTES >= 4 * 16 * 64 * 4, "the thin tile's partial sums must fit");
   __shared__ __attribute__((aligned(16))) unsigned char smem[SK_BYTES > DW_BYTES ? SK_BYTES : DW_BYTES];
   // the two kinds are spread over the XCDs separately (each XCD gets its share of both)
   const int head8 = (batch.head_tiles + 7) & ~7;
@@ -352,43 +441,76 @@ __global__ __launch_bounds__(256) void linear_tick_kernel(const GemmBatch batch)
     if (tile >= batch.total_tiles) return;
   }
   const GemmProb& P = batch.p[find_problem(batch, tile)];
-  if (P.epi == EPI_WGRAD) dw_tile<T>(P, tile, smem);
-  else skinny_tile<T, BN>(P, tile, smem);
+  if (P.epi == EPI_WGRAD) {
+    dw_tile<T>(P, tile, smem);
+  } else {
+    if constexpr (THIN) {
+      if (P.flags & GF_THIN) {
+        thin_tile<T>(P, tile, smem);
+        return;
+      }
+    }
+    skinny_tile<T, BN>(P, tile, smem);
+  }
 }
 
-hipError_t launch_linear_tick(GemmBatch& b, int dtype, bool wide, hipStream_t stream) {
+namespace {
+template <typename T>
+void launch_variant(const GemmBatch& b, bool wide, bool thin, dim3 grid, hipStream_t stream) {
+  const dim3 block(256);
+  if (thin) {
+    if (wide) hipLaunchKernelGGL((linear_tick_kernel<T, 128, true>), grid, block, 0, stream, b);
+    else hipLaunchKernelGGL((linear_tick_kernel<T, 64, true>), grid, block, 0, stream, b);
+  } else {
+    if (wide) hipLaunchKernelGGL((linear_tick_kernel<T, 128, false>), grid, block, 0, stream, b);
+    else hipLaunchKernelGGL((linear_tick_kernel<T, 64, false>), grid, block, 0, stream, b);
+  }
+}
+}  // namespace
+
+hipError_t launch_linear_tick(GemmBatch& b, int dtype, bool wide, bool allow_thin, hipStream_t stream) {
   if (b.n <= 0) return hipSuccess;
   if (b.n > GEMM_MAX_PROBS) return hipErrorInvalidValue;
   const int bn = wide ? 128 : 64;
+  const int vec = dtype == DT_BF16 ? 8 : 4;
   // forward / data-gradient problems first, weight gradients after them
   std::stable_partition(b.p, b.p + b.n, [](const GemmProb& p) { return p.epi != EPI_WGRAD; });
   int total = 0;
+  bool any_thin = false;
   b.head_tiles = 0;
   for (int i = 0; i < b.n; ++i) {
     GemmProb& p = b.p[i];
     if (p.M <= 0 || p.N <= 0 || p.K <= 0) return hipErrorInvalidValue;
     p.splits = 1;
-    if (p.epi != EPI_WGRAD) b.head_tiles += ((p.M + 63) / 64) * ((p.N + bn - 1) / bn);
+    p.flags &= ~GF_THIN;
+    int tiles;
     if (p.epi == EPI_WGRAD) {
       if (p.a_mode != OP_PLAIN_R || p.b_mode != OP_PLAIN_R || (p.flags & GF_ATOMIC) || p.aux0 || p.aux1) return hipErrorInvalidValue;
       p.tiles_n = (p.N + 127) / 128;
+      tiles = ((p.M + 63) / 64) * p.tiles_n;
     } else {
       if (p.a_mode != OP_PLAIN_K || p.b_mode != OP_PLAIN_K) return hipErrorInvalidValue;
       if ((int64_t)p.M * p.lda >= (1ll << 31) || (int64_t)p.N * p.ldb >= (1ll << 31)) return hipErrorInvalidValue;
-      p.tiles_n = (p.N + bn - 1) / bn;
+      const bool chunked = p.K % vec == 0 && p.lda % vec == 0 && p.ldb % vec == 0 &&
+                           reinterpret_cast<uintptr_t>(p.A) % 16 == 0 && reinterpret_cast<uintptr_t>(p.B) % 16 == 0;
+      if (allow_thin && p.M <= 32 && chunked) {
+        p.flags |= GF_THIN;
+        any_thin = true;
+        p.tiles_n = (p.N + 31) / 32;
+        tiles = p.tiles_n;
+      } else {
+        p.tiles_n = (p.N + bn - 1) / bn;
+        tiles = ((p.M + 63) / 64) * p.tiles_n;
+      }
+      b.head_tiles += tiles;
     }
     p.tile_begin = total;
-    total += ((p.M + 63) / 64) * p.tiles_n;
+    total += tiles;
   }
   b.total_tiles = total;
-  dim3 grid(((b.head_tiles + 7) / 8) * 8 + ((total - b.head_tiles + 7) / 8) * 8), block(256);
-  if (dtype == DT_BF16) {
-    if (wide) hipLaunchKernelGGL((linear_tick_kernel<uint16_t, 128>), grid, block, 0, stream, b);
-    else hipLaunchKernelGGL((linear_tick_kernel<uint16_t, 64>), grid, block, 0, stream, b);
-  } else {
-    if (wide) hipLaunchKernelGGL((linear_tick_kernel<float, 128>), grid, block, 0, stream, b);
-    else hipLaunchKernelGGL((linear_tick_kernel<float, 64>), grid, block, 0, stream, b);
-  }
+  const dim3 grid(((b.head_tiles + 7) / 8) * 8 + ((total - b.head_tiles + 7) / 8) * 8);
+  if (dtype == DT_BF16) launch_variant<uint16_t>(b, wide, any_thin, grid, stream);
+  else launch_variant<float>(b, wide, any_thin, grid, stream);
   return hipGetLastError();
 }
 

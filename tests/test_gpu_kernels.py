@@ -27,9 +27,10 @@ def _rnd(a, dtype):
 
 
 @pytest.mark.parametrize("dtype", [wl.F32, wl.BF16])
-@pytest.mark.parametrize("shape", [0, 1, 2, 3, 4])
+@pytest.mark.parametrize("shape", [0, 1, 2, 3, 4, 5])
 @pytest.mark.parametrize("a_k,b_k", [(1, 1), (0, 0), (1, 0), (0, 1)])
-@pytest.mark.parametrize("M,N,K", [(8, 64, 64), (64, 200, 136), (130, 257, 70), (333, 129, 515), (5, 7, 3), (32, 300, 1100)])
+@pytest.mark.parametrize("M,N,K", [(8, 64, 64), (64, 200, 136), (130, 257, 70), (333, 129, 515), (5, 7, 3), (32, 300, 1100),
+                                   (32, 1024, 1024), (17, 200, 3072), (32, 96, 136), (1, 40, 8), (9, 33, 2056)])
 def test_gemm_all_layouts(dtype, shape, a_k, b_k, M, N, K):
     torch = _torch()
     if shape >= 3 and not (a_k and b_k):
