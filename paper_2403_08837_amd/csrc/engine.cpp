@@ -91,6 +91,8 @@ struct Item {
   int64_t n0 = 0;
   int i[10] = {0};
   double flops = 0, bytes = 0;  // algorithmic work (contractions only)
+  bool fused_update = false;    // IT_GEMM weight gradient of a Linear layer that also takes the SGD step (u)
+  LinUpdate u;
 };
 typedef std::vector<std::vector<Item>> Program;
 
@@ -291,6 +293,12 @@ void op_work(const cdp_ctx* c, const Op& o, int pass, bool rmw, bool extra_in, I
   else it->bytes = y * eb + x * eb + w * 4 * (rmw ? 2 : 1) + (o.has_gamma ? w * eb : 0);
 }
 
+// Linear layers whose weight gradient runs in the HBM-streaming kernel can take their SGD
+// step inside that kernel (LinUpdate).
+bool linear_update_fusable(const Op& o) {
+  return o.kind == OPK_GEMM && !o.is_conv && !o.has_gamma && o.kpad == 0;
+}
+
 // Launch class of a contraction: which kernel family and tile shape runs it.
 enum LaunchClass {
   LC_LINEAR = 0, LC_CONV_NARROW, LC_CONV_WIDE, LC_CWGRAD_64, LC_CWGRAD_128,
@@ -383,7 +391,7 @@ int build_forward(cdp_ctx* c, int i, int64_t t, int j, int version, const float*
   return CDP_OK;
 }
 
-int build_backward(cdp_ctx* c, int i, int j, Program* prog, bool first_grad) {
+int build_backward(cdp_ctx* c, int i, int j, Program* prog, bool first_grad, bool fuse_update) {
   const StagePlan& sp = c->plan.stages[j];
   VisitRecord& r = c->rec[i][j];
   if (!r.live) return fail(c, CDP_ESTATE, "backward without a matching forward");
@@ -452,6 +460,22 @@ int build_backward(cdp_ctx* c, int i, int j, Program* prog, bool first_grad) {
       }
       w.g = wgrad_prob(c, o, dz, w_src, slot, G, first_grad);
       op_work(c, o, 2, o.is_conv || !first_grad, false, &w);
+      if (fuse_update && linear_update_fusable(o)) {
+        // this gradient is the N-th of the step: its contraction also takes the SGD step and
+        // writes the new version into the other ring slot (which no pass of this tick reads)
+        char* nslot = static_cast<char*>(c->ptr(ss.slot[(ss.ver + 1) & 1]));
+        float* master = c->fptr(ss.master);
+        float* V = ss.V >= 0 ? c->fptr(ss.V) : nullptr;
+        w.fused_update = true;
+        w.u.master = master + o.w_off; w.u.V = V ? V + o.w_off : nullptr;
+        w.u.wf = nslot + o.wf; w.u.wt = nslot + o.wt;
+        w.u.bmaster = o.b_off >= 0 ? master + o.b_off : nullptr;
+        w.u.bV = (o.b_off >= 0 && V) ? V + o.b_off : nullptr;
+        w.u.bcopy = o.b_off >= 0 ? reinterpret_cast<float*>(nslot + o.bias_c) : nullptr;
+        w.u.sgd = SgdParams{c->lr, 1.0f / (float)c->N, c->momentum, c->weight_decay, 1};
+        // master read + write, both compute copies written, accumulator not written back
+        w.bytes += (double)o.w_count() * (4 + 2 * c->plan.elem_bytes + (V ? 8 : 0));
+      }
       bool two_phase = false;
       if (o.is_conv && conv_fast_eligible(w.g, c->plan.dtype)) {
         // partial sums of every reduction range, folded into the accumulators one level later
@@ -517,7 +541,16 @@ int launch_level(cdp_ctx* c, std::vector<Item>& items) {
     for (size_t k = 0; k < sel.size(); k += GEMM_MAX_PROBS) {
       GemmBatch batch;
       batch.n = (int)std::min<size_t>(GEMM_MAX_PROBS, sel.size() - k);
-      for (int q = 0; q < batch.n; ++q) batch.p[q] = sel[k + q]->g;
+      batch.n_upd = 0;
+      for (int q = 0; q < batch.n; ++q) {
+        batch.p[q] = sel[k + q]->g;
+        batch.p[q].upd = 0;
+        if (sel[k + q]->fused_update) {
+          if (batch.n_upd == LIN_UPD_MAX) return fail(c, CDP_ESTATE, "internal: too many fused updates in one launch");
+          batch.upd[batch.n_upd] = sel[k + q]->u;
+          batch.p[q].upd = ++batch.n_upd;
+        }
+      }
       cdp_ctx::ProfRec pr{nullptr, nullptr, 0, 0};
       const bool timed = c->profiling && c->prof.size() < (1u << 18);
       if (timed) {
@@ -623,7 +656,7 @@ int launch_program(cdp_ctx* c, Program& prog) {
 
 // Writes the compute copies of stage j's current master weights into ring slot `slot`;
 // with apply first takes the SGD step of Eq. (CDP) on the master weights.
-int refresh_slot(cdp_ctx* c, int j, int slot, bool apply) {
+int refresh_slot(cdp_ctx* c, int j, int slot, bool apply, bool linear_done = false) {
   SgdParams sgd{c->lr, 1.0f / (float)c->N, c->momentum, c->weight_decay, apply ? 1 : 0};
   const StagePlan& sp = c->plan.stages[j];
   const StageState& ss = c->st[j];
@@ -633,6 +666,7 @@ int refresh_slot(cdp_ctx* c, int j, int slot, bool apply) {
   float* V = ss.V >= 0 ? c->fptr(ss.V) : nullptr;
   for (const Op& o : sp.ops) {
     if (o.kind != OPK_GEMM) continue;
+    if (linear_done && linear_update_fusable(o)) continue;  // updated by its weight-gradient kernel
     // vector parameters first: the folded weights use the updated gamma
     if (o.g_off >= 0) {
       HIP_TRY(c, launch_update_vec(master + o.g_off, G + o.g_off, V ? V + o.g_off : nullptr, reinterpret_cast<float*>(sl + o.gamma_c), o.Cout, sgd, c->stream));
@@ -699,21 +733,37 @@ int run_tick(cdp_ctx* c, const float* x_dev, const int32_t* y_dev) {
   if (c->live_counts.size() < TRACE_CAP) c->live_counts.push_back(live);
   c->weights_locked = c->weights_locked || !act.empty();
 
+  // weight version of every pass: forward by the update rule, backward as its own forward
+  for (Visit& v : act) {
+    const StageState& ss = c->st[v.j];
+    if (v.dir == 0) {
+      if (c->rule == CDP_RULE_V2) v.version = ss.ver;
+      else if (c->rule == CDP_RULE_V1) v.version = (int)std::max<int64_t>(v.t - 1, 0);
+      else v.version = (int)v.t;
+    } else {
+      v.version = c->rec[v.i][v.j].version;
+    }
+    if (ss.ring_ver[v.version & 1] != v.version)
+      return fail(c, CDP_ESTATE, v.dir == 0 ? "internal: weight version left the ring before its forward"
+                                            : "internal: weight version left the ring before its backward");
+  }
   std::vector<Program> progs(act.size());
+  std::vector<char> fused(S, 0);
   for (size_t a = 0; a < act.size(); ++a) {
     Visit& v = act[a];
     StageState& ss = c->st[v.j];
     int rc;
     if (v.dir == 0) {
-      if (c->rule == CDP_RULE_V2) v.version = ss.ver;
-      else if (c->rule == CDP_RULE_V1) v.version = (int)std::max<int64_t>(v.t - 1, 0);
-      else v.version = (int)v.t;
-      if (ss.ring_ver[v.version & 1] != v.version) return fail(c, CDP_ESTATE, "internal: weight version left the ring before its forward");
       rc = build_forward(c, v.i, v.t, v.j, v.version, x_dev, y_dev, &progs[a]);
     } else {
-      v.version = c->rec[v.i][v.j].version;
-      if (ss.ring_ver[v.version & 1] != v.version) return fail(c, CDP_ESTATE, "internal: weight version left the ring before its backward");
-      rc = build_backward(c, v.i, v.j, &progs[a], ss.cnt == 0);
+      // The backward that brings the N-th gradient may take the SGD step inside its weight-
+      // gradient kernels, provided no pass of this tick reads the ring slot the new version
+      // goes to (under CDP-v1 the backward itself still reads it).
+      bool fuse = ss.cnt == N - 1;
+      for (const Visit& o : act)
+        if (o.j == v.j && ((o.version ^ (ss.ver + 1)) & 1) == 0) fuse = false;
+      rc = build_backward(c, v.i, v.j, &progs[a], ss.cnt == 0, fuse);
+      if (fuse) fused[v.j] = 1;
       ss.cnt++;
     }
     if (rc) return rc;
@@ -749,7 +799,7 @@ int run_tick(cdp_ctx* c, const float* x_dev, const int32_t* y_dev) {
     if (ss.cnt != N) continue;
     const int nv = ss.ver + 1;
     if (!c->dry) {
-      int rc = refresh_slot(c, j, nv & 1, true);
+      int rc = refresh_slot(c, j, nv & 1, true, fused[j] != 0);
       if (rc) return rc;
     }
     ss.ring_ver[nv & 1] = nv;

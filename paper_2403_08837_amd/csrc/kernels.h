@@ -51,17 +51,40 @@ struct GemmProb {
   int tiles_n;       // tiles along N
   int splits;        // split-K factor (WGRAD atomic only), >= 1
   int tile_begin;    // first block of this problem in the launch
+  int upd;           // linear_tick_kernel, WGRAD: 1 + index into GemmBatch::upd of a fused SGD step, 0 = none
   ConvGeom g;        // geometry of the (single) gathered operand, if any
 };
 
 enum : int { GF_RELU = 1, GF_OUT_F32 = 2, GF_ACCUM = 4, GF_ATOMIC = 8, GF_THIN = 16 /* set by launch_linear_tick */ };
 
+// SGD step on fp32 master parameters from the summed micro-batch gradients G (Eq. (CDP)),
+// optionally with momentum and weight decay (the optimiser of Sec. 5 "Hyperparameters"):
+//   g = G*inv_n + wd*w ;  v = momentum*v + g (when a velocity buffer is given) ;  w -= lr*v.
+// apply == 0 leaves the parameters as they are (initial fill of the ring slots).
+struct SgdParams { float lr, inv_n, momentum, wd; int apply; };
+
+// SGD step of a Linear layer fused into the weight-gradient contraction that delivers the
+// N-th micro-batch gradient of the step: the tile that completes sum_i g_i applies the step
+// to its part of the fp32 master weights and writes the compute copies of the new version
+// (forward layout wf[n][k] and data-gradient layout wt[k][n]) into the other ring slot.
+// The accumulator is not written: the next step's first gradient overwrites it.
+struct LinUpdate {
+  float* master; float* V;                  // fp32 [N][K]; V = velocity or NULL
+  void* wf; void* wt;                       // compute copies of the new version
+  float* bmaster; float* bV; float* bcopy;  // bias: master, velocity or NULL, fp32 copy in the new slot (bmaster NULL: no bias)
+  SgdParams sgd;
+};
+
 constexpr int GEMM_MAX_PROBS = 24;
+constexpr int LIN_UPD_MAX = 2;
 struct GemmBatch {
   int n;
   int total_tiles;
   int head_tiles;  // linear_tick_kernel: tiles of the forward / data-gradient problems (listed first)
+  int upd_tiles;   // linear_tick_kernel: tiles of the weight gradients with a fused SGD step (listed next)
+  int n_upd;
   GemmProb p[GEMM_MAX_PROBS];
+  LinUpdate upd[LIN_UPD_MAX];
 };
 static_assert(sizeof(GemmBatch) <= 4000, "kernel argument block must stay under 4 KiB");
 
@@ -120,11 +143,6 @@ constexpr int COLSUM_MAX_PROBS = 32;
 struct ColsumBatch { int n; ColsumProb p[COLSUM_MAX_PROBS]; };
 hipError_t launch_colsum_batch(const ColsumBatch& b, int dtype, hipStream_t stream);
 
-// SGD step on fp32 master parameters from the summed micro-batch gradients G (Eq. (CDP)),
-// optionally with momentum and weight decay (the optimiser of Sec. 5 "Hyperparameters"):
-//   g = G*inv_n + wd*w ;  v = momentum*v + g (when a velocity buffer is given) ;  w -= lr*v.
-// apply == 0 leaves the parameters as they are (initial fill of the ring slots).
-struct SgdParams { float lr, inv_n, momentum, wd; int apply; };
 
 // Vector parameters (bias, gamma, beta): SGD step ; G = 0 ; copy = master.  V may be NULL.
 hipError_t launch_update_vec(float* master, float* G, float* V, float* copy_f32, int64_t n, SgdParams sgd,

@@ -17,6 +17,7 @@
 #include <algorithm>
 
 #include "kernels.h"
+#include "sgd_step.h"
 
 namespace cdp {
 
@@ -295,7 +296,7 @@ __device__ __forceinline__ void thin_tile(const GemmProb& P, int tile, unsigned 
 // (ldb = K), out = G [N][K] (ldo = K), P.M = N, P.N = K, P.K = Mb (reduction length);
 // aux2 = bias-gradient vector [N] or NULL.
 template <typename T>
-__device__ __forceinline__ void dw_tile(const GemmProb& P, int tile, unsigned char* smem) {
+__device__ __forceinline__ void dw_tile(const GemmBatch& batch, const GemmProb& P, int tile, unsigned char* smem) {
   using E = LT<T>;
   constexpr int TN = 64, TK = 128, MB = 64, VEC = E::VEC;
   constexpr int PD = TN + 4, PX = TK + 4;  // LDS pitches (elements)
@@ -310,8 +311,15 @@ __device__ __forceinline__ void dw_tile(const GemmProb& P, int tile, unsigned ch
   const int flags = P.flags;
   float* __restrict__ G = static_cast<float*>(P.out);
 
-  // 1. request the old accumulator tile (read-modify-write) before anything else
+  // 1. request the old accumulator tile (read-modify-write) before anything else.  A tile that
+  // also takes the SGD step requests its master weights (and velocities) now as well and keeps
+  // one combined value per element, so that only this micro-batch's share is missing:
+  //   plain / weight decay:  w' = [w - lr*(Gold/N + wd*w)] - (lr/N)*acc
+  //   momentum:              v' = [mu*v + Gold/N + wd*w] + acc/N ,  w' = w - lr*v'
   const bool rmw = (flags & GF_ACCUM) != 0;
+  const bool upd = P.upd != 0;
+  const LinUpdate& U = batch.upd[upd ? P.upd - 1 : 0];
+  const bool mom = upd && U.V != nullptr;
   const int gc = k0 + wave * 32 + (lane & 31);
   float gold[32];
 #pragma unroll
@@ -319,7 +327,15 @@ __device__ __forceinline__ void dw_tile(const GemmProb& P, int tile, unsigned ch
 #pragma unroll
     for (int v = 0; v < 16; ++v) {
       const int r = n0 + i * 32 + (v >> 2) * 8 + (lane >> 5) * 4 + (v & 3);
-      gold[i * 16 + v] = (rmw && r < Nn && gc < Kk) ? G[(int64_t)r * P.ldo + gc] : 0.f;
+      const bool inb = r < Nn && gc < Kk;
+      const int64_t idx = (int64_t)r * P.ldo + gc;
+      float g0 = (rmw && inb) ? G[idx] : 0.f;
+      if (upd && inb) {
+        const float w = U.master[idx];
+        const float gw = g0 * U.sgd.inv_n + U.sgd.wd * w;
+        g0 = mom ? U.sgd.momentum * U.V[idx] + gw : w - U.sgd.lr * gw;
+      }
+      gold[i * 16 + v] = g0;
     }
 
   v16f_t acc[2];
@@ -405,17 +421,94 @@ __device__ __forceinline__ void dw_tile(const GemmProb& P, int tile, unsigned ch
     }
   }
 
-  // 4. accumulate and write back
+  if (!upd) {
+    // 4. accumulate and write back
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        const int r = n0 + i * 32 + (v >> 2) * 8 + (lane >> 5) * 4 + (v & 3);
+        if (r < Nn && gc < Kk) G[(int64_t)r * P.ldo + gc] = gold[i * 16 + v] + acc[i][v];
+      }
+    if (tk == 0 && P.aux2 != nullptr && tid < TN && n0 + tid < Nn) {
+      float* gb = static_cast<float*>(P.aux2) + n0 + tid;
+      *gb = rmw ? (*gb + bsum) : bsum;
+    }
+    return;
+  }
+
+  // 4'. this contraction completes the sum over the micro-batches: take the SGD step on the
+  // tile's master weights and write both compute copies of the new version
+  constexpr int PW = TK + (sizeof(T) == 2 ? 2 : 1);  // LDS pitch of the new-weight tile [TN][TK]
+  T* Ws = reinterpret_cast<T*>(smem);
+  __syncthreads();  // the operand tiles in LDS are no longer read
 #pragma unroll
   for (int i = 0; i < 2; ++i)
 #pragma unroll
     for (int v = 0; v < 16; ++v) {
-      const int r = n0 + i * 32 + (v >> 2) * 8 + (lane >> 5) * 4 + (v & 3);
-      if (r < Nn && gc < Kk) G[(int64_t)r * P.ldo + gc] = gold[i * 16 + v] + acc[i][v];
+      const int rl = i * 32 + (v >> 2) * 8 + (lane >> 5) * 4 + (v & 3);
+      const int r = n0 + rl;
+      float w = 0.f;
+      if (r < Nn && gc < Kk) {
+        const int64_t idx = (int64_t)r * P.ldo + gc;
+        if (mom) {
+          const float vel = gold[i * 16 + v] + acc[i][v] * U.sgd.inv_n;
+          U.V[idx] = vel;
+          w = U.master[idx] - U.sgd.lr * vel;
+        } else {
+          w = gold[i * 16 + v] - (U.sgd.lr * U.sgd.inv_n) * acc[i][v];
+        }
+        U.master[idx] = w;
+      }
+      Ws[rl * PW + wave * 32 + (lane & 31)] = E::from_f32(w);
     }
-  if (tk == 0 && P.aux2 != nullptr && tid < TN && n0 + tid < Nn) {
-    float* gb = static_cast<float*>(P.aux2) + n0 + tid;
-    *gb = rmw ? (*gb + bsum) : bsum;
+  __syncthreads();
+  T* __restrict__ wf = static_cast<T*>(U.wf);
+  T* __restrict__ wt = static_cast<T*>(U.wt);
+  {  // forward layout: rows n, 16-byte chunks along k
+    constexpr int CPR = TK / VEC;
+    const bool al = (Kk % VEC) == 0;
+    for (int id = tid; id < TN * CPR; id += 256) {
+      const int n = id / CPR, ck = (id % CPR) * VEC;
+      if (n0 + n >= Nn || k0 + ck >= Kk) continue;
+      Chunk16<T> tmp;
+#pragma unroll
+      for (int e = 0; e < VEC; ++e) tmp.e[e] = Ws[n * PW + ck + e];
+      T* dst = wf + (int64_t)(n0 + n) * Kk + k0 + ck;
+      if (al) {
+        *reinterpret_cast<uint4*>(dst) = tmp.v;
+      } else {
+#pragma unroll
+        for (int e = 0; e < VEC; ++e)
+          if (k0 + ck + e < Kk) dst[e] = tmp.e[e];
+      }
+    }
+  }
+  {  // data-gradient layout: rows k, 16-byte chunks along n (read transposed out of LDS)
+    constexpr int CPR = TN / VEC;
+    const bool al = (Nn % VEC) == 0;
+    for (int id = tid; id < TK * CPR; id += 256) {
+      const int k = id / CPR, cn = (id % CPR) * VEC;
+      if (k0 + k >= Kk || n0 + cn >= Nn) continue;
+      Chunk16<T> tmp;
+#pragma unroll
+      for (int e = 0; e < VEC; ++e) tmp.e[e] = Ws[(cn + e) * PW + k];
+      T* dst = wt + (int64_t)(k0 + k) * Nn + n0 + cn;
+      if (al) {
+        *reinterpret_cast<uint4*>(dst) = tmp.v;
+      } else {
+#pragma unroll
+        for (int e = 0; e < VEC; ++e)
+          if (n0 + cn + e < Nn) dst[e] = tmp.e[e];
+      }
+    }
+  }
+  if (tk == 0 && U.bmaster != nullptr && tid < TN && n0 + tid < Nn) {
+    const int n = n0 + tid;
+    const float gb = (rmw ? static_cast<const float*>(P.aux2)[n] : 0.f) + bsum;
+    const float b = sgd_step(U.bmaster[n], gb, U.bV ? U.bV + n : nullptr, U.sgd);
+    U.bmaster[n] = b;
+    U.bcopy[n] = b;
   }
 }
 
@@ -430,19 +523,29 @@ __global__ __launch_bounds__(256) void linear_tick_kernel(const GemmBatch batch)
   constexpr int DW_BYTES = 64 * (64 + 4 + 128 + 4) * (int)sizeof(T);
   static_assert(SK_BYTES >= 4 * 16 * 64 * 4, "the thin tile's partial sums must fit");
   __shared__ __attribute__((aligned(16))) unsigned char smem[SK_BYTES > DW_BYTES ? SK_BYTES : DW_BYTES];
-  // the two kinds are spread over the XCDs separately (each XCD gets its share of both)
-  const int head8 = (batch.head_tiles + 7) & ~7;
+  // Tile order: forward / data-gradient tiles, weight-gradient tiles that also take the SGD
+  // step, plain weight-gradient tiles.  The first and the last kind are spread over the XCDs
+  // separately (each XCD gets a contiguous share of both, so a problem's activations sit in
+  // one L2); the longer update tiles stay in launch order, which deals them round-robin to
+  // all XCDs.
+  const int head8 = (batch.head_tiles + 7) & ~7, upd8 = (batch.upd_tiles + 7) & ~7;
+  const int bid = (int)blockIdx.x;
   int tile;
-  if ((int)blockIdx.x < head8) {
-    tile = xcd_remap((int)blockIdx.x, batch.head_tiles);
+  if (bid < head8) {
+    tile = xcd_remap(bid, batch.head_tiles);
     if (tile >= batch.head_tiles) return;
+  } else if (bid < head8 + upd8) {
+    tile = bid - head8;
+    if (tile >= batch.upd_tiles) return;
+    tile += batch.head_tiles;
   } else {
-    tile = batch.head_tiles + xcd_remap((int)blockIdx.x - head8, batch.total_tiles - batch.head_tiles);
+    const int first = batch.head_tiles + batch.upd_tiles;
+    tile = first + xcd_remap(bid - head8 - upd8, batch.total_tiles - first);
     if (tile >= batch.total_tiles) return;
   }
   const GemmProb& P = batch.p[find_problem(batch, tile)];
   if (P.epi == EPI_WGRAD) {
-    dw_tile<T>(P, tile, smem);
+    dw_tile<T>(batch, P, tile, smem);
   } else {
     if constexpr (THIN) {
       if (P.flags & GF_THIN) {
@@ -474,10 +577,13 @@ hipError_t launch_linear_tick(GemmBatch& b, int dtype, bool wide, bool allow_thi
   const int bn = wide ? 128 : 64;
   const int vec = dtype == DT_BF16 ? 8 : 4;
   // forward / data-gradient problems first, weight gradients after them
-  std::stable_partition(b.p, b.p + b.n, [](const GemmProb& p) { return p.epi != EPI_WGRAD; });
+  GemmProb* wg = std::stable_partition(b.p, b.p + b.n, [](const GemmProb& p) { return p.epi != EPI_WGRAD; });
+  // weight gradients that also take the SGD step have the longest tiles: start them first
+  std::stable_partition(wg, b.p + b.n, [](const GemmProb& p) { return p.upd != 0; });
   int total = 0;
   bool any_thin = false;
   b.head_tiles = 0;
+  b.upd_tiles = 0;
   for (int i = 0; i < b.n; ++i) {
     GemmProb& p = b.p[i];
     if (p.M <= 0 || p.N <= 0 || p.K <= 0) return hipErrorInvalidValue;
@@ -486,8 +592,15 @@ hipError_t launch_linear_tick(GemmBatch& b, int dtype, bool wide, bool allow_thi
     int tiles;
     if (p.epi == EPI_WGRAD) {
       if (p.a_mode != OP_PLAIN_R || p.b_mode != OP_PLAIN_R || (p.flags & GF_ATOMIC) || p.aux0 || p.aux1) return hipErrorInvalidValue;
+      if (p.upd < 0 || p.upd > b.n_upd || b.n_upd > LIN_UPD_MAX) return hipErrorInvalidValue;
+      if (p.upd) {
+        const LinUpdate& u = b.upd[p.upd - 1];
+        if (p.ldo != p.N) return hipErrorInvalidValue;
+        if (!u.master || !u.wf || !u.wt || (u.bmaster && (!u.bcopy || !p.aux2))) return hipErrorInvalidValue;
+      }
       p.tiles_n = (p.N + 127) / 128;
       tiles = ((p.M + 63) / 64) * p.tiles_n;
+      if (p.upd) b.upd_tiles += tiles;
     } else {
       if (p.a_mode != OP_PLAIN_K || p.b_mode != OP_PLAIN_K) return hipErrorInvalidValue;
       if ((int64_t)p.M * p.lda >= (1ll << 31) || (int64_t)p.N * p.ldb >= (1ll << 31)) return hipErrorInvalidValue;
@@ -508,7 +621,7 @@ hipError_t launch_linear_tick(GemmBatch& b, int dtype, bool wide, bool allow_thi
     total += tiles;
   }
   b.total_tiles = total;
-  const dim3 grid(((b.head_tiles + 7) / 8) * 8 + ((total - b.head_tiles + 7) / 8) * 8);
+  const dim3 grid(((b.head_tiles + 7) / 8) * 8 + ((b.upd_tiles + 7) / 8) * 8 + ((total - b.head_tiles - b.upd_tiles + 7) / 8) * 8);
   if (dtype == DT_BF16) launch_variant<uint16_t>(b, wide, any_thin, grid, stream);
   else launch_variant<float>(b, wide, any_thin, grid, stream);
   return hipGetLastError();

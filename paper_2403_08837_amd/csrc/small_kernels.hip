@@ -3,6 +3,7 @@
 // SGD update with re-layout of the new weight version (Eq. (CDP): theta_{t+1} =
 // theta_t - gamma/N * sum_i grad f_i), pooling.
 #include "kernels.h"
+#include "sgd_step.h"
 
 namespace cdp {
 
@@ -131,15 +132,6 @@ hipError_t launch_colsum_batch(const ColsumBatch& b, int dtype, hipStream_t stre
 }
 
 // ---------------------------------------------------------------------------------
-__device__ __forceinline__ float sgd_step(float w, float gsum, float* v, const SgdParams& p) {
-  float g = gsum * p.inv_n + p.wd * w;
-  if (v) {
-    g = p.momentum * (*v) + g;
-    *v = g;
-  }
-  return w - p.lr * g;
-}
-
 __global__ void update_vec_kernel(float* __restrict__ master, float* __restrict__ G, float* __restrict__ V,
                                   float* __restrict__ copy, int64_t n, SgdParams sgd) {
   for (int64_t i = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x) {
