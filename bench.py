@@ -53,13 +53,13 @@ def measured_traffic(workload):
     return None
 
 
-def gpu_run(cfg, rule, steps, warmup, n_batches=4):
+def gpu_run(cfg, rule, steps, warmup, n_batches=4, dp_batched=False):
     import torch
     from paper_2403_08837_amd import binding as b
 
     if not torch.cuda.is_available():
         raise SystemExit("bench.py needs a GPU; libcdp has no CPU path")
-    tr = b.Trainer(cfg.stages, cfg.in_shape, cfg.N, cfg.B, cfg.lr, rule, cfg.dtype)
+    tr = b.Trainer(cfg.stages, cfg.in_shape, cfg.N, cfg.B, cfg.lr, rule, cfg.dtype, dp_batched=dp_batched)
     tr.set_weights(wl.init_params(cfg, 0))
     data = []
     for t in range(n_batches):
@@ -117,9 +117,9 @@ def cpu_baseline(cfg, rule, budget_s=15.0):
             "sample": "%d full training step(s) of the same workload and rule, fp64 numpy timeline oracle, %.1f s" % (steps, total)}
 
 
-def run_workload(name, rule, steps, warmup, n_batches=4):
+def run_workload(name, rule, steps, warmup, n_batches=4, dp_batched=False):
     cfg = wl.get_config(name)
-    r = gpu_run(cfg, rule, steps, warmup, n_batches)
+    r = gpu_run(cfg, rule, steps, warmup, n_batches, dp_batched)
     samples = cfg.N * cfg.B * steps
     prof = r["prof"]
     sec = prof["total_ms"] * 1e-3
@@ -153,7 +153,8 @@ def run_workload(name, rule, steps, warmup, n_batches=4):
         "vs_baseline": None,
         "dtype": "bf16" if cfg.dtype == wl.BF16 else "f32",
         "data": "synthetic",
-        "config": {"workload": "%s: %s" % (name, WORKLOAD_TEXT[name]), "rule": wl.RULE_NAMES[rule],
+        "config": {"workload": "%s: %s" % (name, WORKLOAD_TEXT[name]),
+                   "rule": wl.RULE_NAMES[rule] + ("_batched" if dp_batched else ""),
                    "S": cfg.S, "N": cfg.N, "B": cfg.B, "delay_ticks": cfg.delay if rule != wl.RULE_DP else 0},
         "gpu_ms_per_step": r["gpu_ms"] / steps,
         "peak_activation_bytes": r["stats"]["peak_activation_bytes"],
@@ -166,13 +167,26 @@ def run_workload(name, rule, steps, warmup, n_batches=4):
     }
 
 
+def lockstep_summary(name, steps):
+    """The same workload under the lock-step DP timeline with one batched pass per stage: what
+    the cyclic schedule trades (weights re-read per micro-batch) for its smaller activation
+    footprint (Table 1, single-GPU rows)."""
+    w = run_workload(name, wl.RULE_DP, steps, 2, n_batches=2, dp_batched=True)
+    return {"value": w["value"], "unit": w["unit"], "ms_per_step": w["ms_per_step"], "steps": steps,
+            "peak_activation_bytes": w["peak_activation_bytes"], "peak_live_stage_inputs": w["peak_live_stage_inputs"]}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=None)
     ap.add_argument("--warmup", type=int, default=None)
     ap.add_argument("--workload", default="cfg2", choices=sorted(WORKLOAD_TEXT))
-    ap.add_argument("--rule", default="v2", choices=["dp", "v1", "v2"])
+    ap.add_argument("--rule", default="v2", choices=["dp", "dp_batched", "v1", "v2"],
+                    help="dp: lock-step timeline pass by pass; dp_batched: lock-step with the N micro-batches of a "
+                         "step as one batch per stage pass (the throughput baseline of the cyclic rules v1 / v2)")
+    ap.add_argument("--no-dp-baseline", action="store_true",
+                    help="skip the short lock-step (dp_batched) run of the same workload reported under \"lockstep_dp\"")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--also", default="cfg5,cfg4",
                     help="comma-separated further workloads summarised under \"workloads\" (short runs); empty for none")
@@ -183,7 +197,8 @@ def main():
         raise SystemExit("bench.py: this build runs the CDP hot path on ONE GPU; --gpus %d is not supported "
                          "(no collectives or sharding are part of it)" % args.gpus)
     cfg = wl.get_config(args.workload)
-    rule = {"dp": wl.RULE_DP, "v1": wl.RULE_V1, "v2": wl.RULE_V2}[args.rule]
+    rule = {"dp": wl.RULE_DP, "dp_batched": wl.RULE_DP, "v1": wl.RULE_V1, "v2": wl.RULE_V2}[args.rule]
+    batched = args.rule == "dp_batched"
     default_steps = {"cfg1": 200, "cfg2": 200, "cfg3": 20, "cfg4": 5, "cfg5": 20}[args.workload]
     steps = args.steps if args.steps is not None else default_steps
     warmup = args.warmup if args.warmup is not None else 3
@@ -194,15 +209,20 @@ def main():
         dst.copy_(src)
         torch.cuda.synchronize()
         del src, dst
-    out = run_workload(args.workload, rule, steps, warmup)
+    out = run_workload(args.workload, rule, steps, warmup, dp_batched=batched)
     if args.also:
         out["workloads"] = {}
         for name in args.also.split(","):
             name = name.strip()
             if name and name != args.workload:
-                w = run_workload(name, rule, {"cfg1": 100, "cfg2": 100, "cfg3": 10, "cfg4": 3, "cfg5": 10}[name], 2, n_batches=2)
+                short = {"cfg1": 100, "cfg2": 100, "cfg3": 10, "cfg4": 3, "cfg5": 10}[name]
+                w = run_workload(name, rule, short, 2, n_batches=2, dp_batched=batched)
                 out["workloads"][name] = {k: w[k] for k in ("value", "unit", "ms_per_step", "steps", "dtype", "config",
                                                             "peak_activation_bytes", "dp_activation_bytes", "roofline")}
+                if not args.no_dp_baseline and not batched:
+                    out["workloads"][name]["lockstep_dp"] = lockstep_summary(name, short)
+    if not args.no_dp_baseline and not batched:
+        out["lockstep_dp"] = lockstep_summary(args.workload, max(2, steps // 4))
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cfg, rule)
     print(json.dumps(out))

@@ -89,6 +89,12 @@ typedef struct {
   float momentum;      /* SGD momentum in [0,1); 0 = plain SGD of Eq. (CDP).  With momentum the
                           arena also holds one fp32 velocity per parameter                 */
   float weight_decay;  /* L2 coefficient added to the mean gradient (all parameters), >= 0   */
+  int32_t dp_batched;  /* only with CDP_RULE_DP: 1 runs the lock-step timeline of Sec. 3.1 with the N
+                          micro-batches of a step as ONE batch of N*micro_batch rows per stage pass
+                          (every weight matrix is read once per pass instead of N times): the
+                          throughput baseline the cyclic schedule is compared with.  Same update
+                          (Eq. (DP)), same trace, live counts and per-micro-batch losses as the
+                          pass-by-pass DP run; summation order inside a contraction differs.     */
 } cdp_opts;
 
 /* One executed (micro-batch, stage) pass. */

@@ -101,6 +101,7 @@ typedef std::vector<std::vector<Item>> Program;
 struct cdp_ctx {
   ModelPlan plan;
   int S = 0, N = 0, B = 0, d = 0, rule = 0;
+  int groups = 1;  // lock-step batched DP: the caller's micro-batches run as one batch of groups * (caller's B) rows (then N = 1)
   float lr = 0.f, momentum = 0.f, weight_decay = 0.f;
   bool dry = false;
   hipStream_t stream = nullptr;
@@ -173,7 +174,7 @@ struct StaticLayout {
   int64_t labels_off, loss_off, pool_base, weight_bytes;
 };
 
-StaticLayout static_layout(const ModelPlan& plan, int N, int B, bool velocity) {
+StaticLayout static_layout(const ModelPlan& plan, int N, int B, int groups, bool velocity) {
   StaticLayout L;
   int64_t off = 0;
   L.weight_bytes = 0;
@@ -188,7 +189,7 @@ StaticLayout static_layout(const ModelPlan& plan, int N, int B, bool velocity) {
   }
   L.weight_bytes = off;
   L.labels_off = off; off = align_up(off + (int64_t)N * B * 4, 256);
-  L.loss_off = off; off = align_up(off + (int64_t)LOSS_LOG_STEPS * N * 4, 256);
+  L.loss_off = off; off = align_up(off + (int64_t)LOSS_LOG_STEPS * N * groups * 4, 256);
   L.pool_base = off;
   return L;
 }
@@ -336,8 +337,8 @@ int build_forward(cdp_ctx* c, int i, int64_t t, int j, int version, const float*
     it.p1 = y_dev + (int64_t)i * c->B;
     it.p2 = c->ptr(r.t[0].off);
     it.p3 = static_cast<int32_t*>(c->ptr(c->labels_off)) + (int64_t)i * c->B;
-    it.p4 = c->fptr(c->loss_off) + (t % LOSS_LOG_STEPS) * c->N + i;
-    it.i[0] = c->B; it.n0 = c->in_features;
+    it.p4 = c->fptr(c->loss_off) + ((t % LOSS_LOG_STEPS) * c->N + i) * c->groups;
+    it.i[0] = c->B; it.i[1] = c->groups; it.n0 = c->in_features;
     at(level++).push_back(it);
   } else {
     r.t[0] = c->carry[i];
@@ -373,8 +374,8 @@ int build_forward(cdp_ctx* c, int i, int64_t t, int j, int version, const float*
       it.p0 = c->ptr(r.t[o.in].off);
       it.p1 = static_cast<int32_t*>(c->ptr(c->labels_off)) + (int64_t)i * c->B;
       it.p2 = c->ptr(r.t[o.out].off);
-      it.p3 = c->fptr(c->loss_off) + (t % LOSS_LOG_STEPS) * c->N + i;
-      it.i[0] = c->B; it.i[1] = o.classes;
+      it.p3 = c->fptr(c->loss_off) + ((t % LOSS_LOG_STEPS) * c->N + i) * c->groups;
+      it.i[0] = c->B; it.i[1] = o.classes; it.i[2] = c->B / c->groups;
     }
     at(level++).push_back(it);
   }
@@ -616,14 +617,14 @@ int launch_level(cdp_ctx* c, std::vector<Item>& items) {
     switch (it.kind) {
       case IT_STAGE_IN:
         HIP_TRY(c, launch_stage_input(static_cast<const float*>(it.p0), static_cast<const int32_t*>(it.p1), it.p2,
-                                      static_cast<int32_t*>(it.p3), static_cast<float*>(it.p4), it.i[0], it.n0, dt, c->stream));
+                                      static_cast<int32_t*>(it.p3), static_cast<float*>(it.p4), it.i[1], it.i[0], it.n0, dt, c->stream));
         break;
       case IT_IM2COL:
         HIP_TRY(c, launch_im2col(it.p0, it.p2, it.i[0], it.g.g, it.i[1], dt, c->stream));
         break;
       case IT_CE:
         HIP_TRY(c, launch_ce_head(static_cast<const float*>(it.p0), static_cast<const int32_t*>(it.p1), it.p2,
-                                  static_cast<float*>(it.p3), it.i[0], it.i[1], dt, c->stream));
+                                  static_cast<float*>(it.p3), it.i[0], it.i[1], it.i[2], dt, c->stream));
         break;
       case IT_MAXPOOL_F:
         HIP_TRY(c, launch_maxpool_fwd(it.p0, it.p2, it.i[0], it.i[1], it.i[2], it.i[3], it.i[4], it.i[5], it.i[6], dt, c->stream));
@@ -728,6 +729,7 @@ int run_tick(cdp_ctx* c, const float* x_dev, const int32_t* y_dev) {
   int live = n_fwd;
   for (int i = 0; i < N; ++i)
     for (int j = 0; j < S; ++j) live += c->rec[i][j].live ? 1 : 0;
+  live *= c->groups;  // a batched pass holds the stage inputs of all the caller's micro-batches
   c->stats.last_live_stage_inputs = live;
   c->stats.peak_live_stage_inputs = std::max<int64_t>(c->stats.peak_live_stage_inputs, live);
   if (c->live_counts.size() < TRACE_CAP) c->live_counts.push_back(live);
@@ -767,7 +769,9 @@ int run_tick(cdp_ctx* c, const float* x_dev, const int32_t* y_dev) {
       ss.cnt++;
     }
     if (rc) return rc;
-    if (c->trace.size() < TRACE_CAP) c->trace.push_back(cdp_trace_rec{(int32_t)c->tick, v.i, (int32_t)v.t, v.j, v.dir, v.version});
+    for (int q = 0; q < c->groups; ++q)
+      if (c->trace.size() < TRACE_CAP)
+        c->trace.push_back(cdp_trace_rec{(int32_t)c->tick, v.i * c->groups + q, (int32_t)v.t, v.j, v.dir, v.version});
   }
   if (!c->dry) {
     if (c->rule == CDP_RULE_DP) {
@@ -829,7 +833,10 @@ int check_args(const cdp_stage_desc* stages, int n_stages, int N, int B, int rul
   if (!e.empty()) return fail(nullptr, CDP_EINVAL, e);
   if (!(opts->momentum >= 0.f && opts->momentum < 1.f) || !(opts->weight_decay >= 0.f))
     return fail(nullptr, CDP_EINVAL, "momentum must be in [0, 1) and weight_decay >= 0");
-  if (B > 1024 && plan->stages.back().has_head) return fail(nullptr, CDP_EINVAL, "micro_batch above 1024 is not supported by the loss head");
+  if (opts->dp_batched && rule != CDP_RULE_DP) return fail(nullptr, CDP_EINVAL, "dp_batched needs CDP_RULE_DP");
+  if (opts->dp_batched && N > 256) return fail(nullptr, CDP_EINVAL, "dp_batched supports at most 256 micro-batches");
+  if ((int64_t)B * (opts->dp_batched ? N : 1) > 1024 && plan->stages.back().has_head)
+    return fail(nullptr, CDP_EINVAL, "a head pass over more than 1024 rows is not supported");
   return CDP_OK;
 }
 
@@ -838,6 +845,13 @@ int make_ctx(cdp_ctx** out, const cdp_stage_desc* stages, int n_stages, int N, i
   cdp_ctx* c = new cdp_ctx();
   int rc = check_args(stages, n_stages, N, B, rule, opts, &c->plan);
   if (rc) { delete c; return rc; }
+  if (opts->dp_batched) {
+    // lock-step executor: one pass per stage over all N*B rows; f = (1/N) sum_i f_i is the mean
+    // loss over those rows, so the update of Eq. (DP) is that of a single micro-batch
+    c->groups = N;
+    B *= N;
+    N = 1;
+  }
   c->S = n_stages; c->N = N; c->B = B; c->rule = rule; c->lr = lr;
   c->d = rule == CDP_RULE_DP ? 0 : 2 * n_stages / N;
   c->dry = force_dry || opts->dry_run != 0;
@@ -845,7 +859,7 @@ int make_ctx(cdp_ctx** out, const cdp_stage_desc* stages, int n_stages, int N, i
   c->arena = c->dry ? nullptr : static_cast<char*>(opts->arena);
   c->arena_bytes = (int64_t)opts->arena_bytes;
   c->momentum = opts->momentum; c->weight_decay = opts->weight_decay;
-  StaticLayout L = static_layout(c->plan, N, B, c->momentum != 0.f);
+  StaticLayout L = static_layout(c->plan, N, B, c->groups, c->momentum != 0.f);
   c->st = L.st;
   c->labels_off = L.labels_off; c->loss_off = L.loss_off;
   c->pool.base = L.pool_base;
@@ -1024,13 +1038,14 @@ int cdp_get_weights(cdp_ctx* c, int stage, int version, float* host, size_t cap,
 
 int cdp_get_losses(cdp_ctx* c, int64_t step, float* host, size_t cap) {
   if (!c || !host) return fail(c, CDP_EINVAL, "bad argument");
-  if (cap < (size_t)c->N) return fail(c, CDP_EINVAL, "buffer too small");
+  const size_t n_loss = (size_t)c->N * c->groups;
+  if (cap < n_loss) return fail(c, CDP_EINVAL, "buffer too small");
   if (step < 0 || step >= c->steps_enqueued || step + LOSS_LOG_STEPS <= c->steps_enqueued - 1)
     return fail(c, CDP_ESTATE, "step is not in the loss log");
   if (c->heads_done[step % LOSS_LOG_STEPS] < c->N) return fail(c, CDP_ESTATE, "not every micro-batch of that step has reached the head yet");
   if (c->dry) return fail(c, CDP_ESTATE, "no losses in a dry run");
   HIP_TRY(c, hipStreamSynchronize(c->stream));
-  HIP_TRY(c, hipMemcpy(host, c->fptr(c->loss_off) + (step % LOSS_LOG_STEPS) * c->N, (size_t)c->N * 4, hipMemcpyDeviceToHost));
+  HIP_TRY(c, hipMemcpy(host, c->fptr(c->loss_off) + (step % LOSS_LOG_STEPS) * n_loss, n_loss * 4, hipMemcpyDeviceToHost));
   return CDP_OK;
 }
 

@@ -128,14 +128,15 @@ hipError_t launch_wgrad_reduce(const WReduceBatch& b, int dtype, hipStream_t str
 // small kernels
 // ---------------------------------------------------------------------------------
 // Staging of one micro-batch: fp32 -> T conversion of its rows, label copy, and zeroing
-// of the loss slot its head pass will add into.
-hipError_t launch_stage_input(const float* x, const int32_t* y, void* x_out, int32_t* y_out, float* loss_slot,
+// of the n_slots (<= 256) loss slots its head pass will add into.
+hipError_t launch_stage_input(const float* x, const int32_t* y, void* x_out, int32_t* y_out, float* loss_slot, int n_slots,
                               int rows, int64_t per_row, int dtype, hipStream_t stream);
 
-// Softmax cross-entropy of one micro-batch: logits f32 [B][C] -> loss (mean over rows)
-// added to *loss_out (zeroed by the staging kernel), dlogits = (softmax - onehot)/B as T [B][C].
+// Softmax cross-entropy of one batch: logits f32 [B][C] -> dlogits = (softmax - onehot)/B as
+// T [B][C]; the mean loss of every group of rows_per_slot consecutive rows (a divisor of B) is
+// added to loss_out[group] (zeroed by the staging kernel).
 hipError_t launch_ce_head(const float* logits, const int32_t* labels, void* dlogits, float* loss_out,
-                          int B, int C, int dtype, hipStream_t stream);
+                          int B, int C, int rows_per_slot, int dtype, hipStream_t stream);
 
 // out[c] += sum_r src[r][c]  (fp32 atomics; out must hold the running sum).
 struct ColsumProb { const void* src; float* out; int rows, cols, ld; };

@@ -37,20 +37,20 @@ static inline int blocks_for(int64_t n, int per_block, int cap = 1 << 20) {
 // ---------------------------------------------------------------------------------
 template <typename T>
 __global__ void stage_input_kernel(const float* __restrict__ x, const int32_t* __restrict__ y, T* __restrict__ xo,
-                                   int32_t* __restrict__ yo, float* __restrict__ loss_slot, int rows, int64_t n) {
-  if (blockIdx.x == 0 && threadIdx.x == 0) *loss_slot = 0.f;  // the head adds row losses into it
+                                   int32_t* __restrict__ yo, float* __restrict__ loss_slot, int n_slots, int rows, int64_t n) {
+  if (blockIdx.x == 0 && (int)threadIdx.x < n_slots) loss_slot[threadIdx.x] = 0.f;  // the head adds row losses into them
   for (int64_t i = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x) {
     st_f32<T>(xo, i, x[i]);
     if (i < rows) yo[i] = y[i];
   }
 }
 
-hipError_t launch_stage_input(const float* x, const int32_t* y, void* x_out, int32_t* y_out, float* loss_slot, int rows,
-                              int64_t per_row, int dtype, hipStream_t stream) {
+hipError_t launch_stage_input(const float* x, const int32_t* y, void* x_out, int32_t* y_out, float* loss_slot, int n_slots,
+                              int rows, int64_t per_row, int dtype, hipStream_t stream) {
   int64_t n = (int64_t)rows * per_row;
-  if (n < rows) return hipErrorInvalidValue;
+  if (n < rows || n_slots < 1 || n_slots > 256) return hipErrorInvalidValue;
   CDP_DISPATCH(dtype, hipLaunchKernelGGL((stage_input_kernel<T>), dim3(blocks_for(n, 256 * 4, 4096)), dim3(256), 0, stream,
-                                         x, y, static_cast<T*>(x_out), y_out, loss_slot, rows, n));
+                                         x, y, static_cast<T*>(x_out), y_out, loss_slot, n_slots, rows, n));
   return hipGetLastError();
 }
 
@@ -71,7 +71,8 @@ __device__ __forceinline__ float wave_sum(float v) {
 
 template <typename T>
 __global__ __launch_bounds__(256) void ce_head_kernel(const float* __restrict__ logits, const int32_t* __restrict__ labels,
-                                                      T* __restrict__ dlogits, float* __restrict__ loss_out, int B, int C) {
+                                                      T* __restrict__ dlogits, float* __restrict__ loss_out, int B, int C,
+                                                      int rows_per_slot) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int row = blockIdx.x * 4 + wave;
   if (row >= B) return;
@@ -89,13 +90,14 @@ __global__ __launch_bounds__(256) void ce_head_kernel(const float* __restrict__ 
     float p = expf(z[c] - m) * inv;
     st_f32<T>(dlogits, (int64_t)row * C + c, (p - (c == y ? 1.f : 0.f)) * invB);
   }
-  if (lane == 0) atomicAdd(loss_out, ((m + logf(s)) - z[y]) * invB);
+  if (lane == 0) atomicAdd(loss_out + row / rows_per_slot, ((m + logf(s)) - z[y]) / (float)rows_per_slot);
 }
 
-hipError_t launch_ce_head(const float* logits, const int32_t* labels, void* dlogits, float* loss_out, int B, int C, int dtype,
-                          hipStream_t stream) {
+hipError_t launch_ce_head(const float* logits, const int32_t* labels, void* dlogits, float* loss_out, int B, int C,
+                          int rows_per_slot, int dtype, hipStream_t stream) {
+  if (rows_per_slot <= 0 || B % rows_per_slot != 0) return hipErrorInvalidValue;
   CDP_DISPATCH(dtype, hipLaunchKernelGGL((ce_head_kernel<T>), dim3((B + 3) / 4), dim3(256), 0, stream, logits, labels,
-                                         static_cast<T*>(dlogits), loss_out, B, C));
+                                         static_cast<T*>(dlogits), loss_out, B, C, rows_per_slot));
   return hipGetLastError();
 }
 

@@ -49,11 +49,11 @@ class Progress:
                 f.write(line)
 
 
-def run_gpu(cfg, rule, T, p0, xs, ys, lr=None, momentum=0.0, weight_decay=0.0):
+def run_gpu(cfg, rule, T, p0, xs, ys, lr=None, momentum=0.0, weight_decay=0.0, dp_batched=False):
     import torch
     assert torch.cuda.is_available(), "GPU tests need a GPU"
     tr = b.Trainer(cfg.stages, cfg.in_shape, cfg.N, cfg.B, cfg.lr if lr is None else lr, rule, cfg.dtype,
-                   momentum=momentum, weight_decay=weight_decay)
+                   momentum=momentum, weight_decay=weight_decay, dp_batched=dp_batched)
     tr.set_weights(p0)
     keep = []
     for t in range(T):
@@ -70,12 +70,12 @@ def run_gpu(cfg, rule, T, p0, xs, ys, lr=None, momentum=0.0, weight_decay=0.0):
     return out
 
 
-def check(cfg, rule, T, seed=0, lr=None, tensor_tol=0.5, capfd=None, momentum=0.0, weight_decay=0.0):
+def check(cfg, rule, T, seed=0, lr=None, tensor_tol=0.5, capfd=None, momentum=0.0, weight_decay=0.0, dp_batched=False):
     xs, ys = wl.make_data(cfg, T, seed)
     p0 = wl.init_params(cfg, seed)
     ref = O.train_schedule(cfg, p0, xs, ys, rule, lr=lr, keep_versions=False, progress=Progress(cfg.name, capfd),
                            momentum=momentum, weight_decay=weight_decay)
-    got = run_gpu(cfg, rule, T, p0, xs, ys, lr=lr, momentum=momentum, weight_decay=weight_decay)
+    got = run_gpu(cfg, rule, T, p0, xs, ys, lr=lr, momentum=momentum, weight_decay=weight_decay, dp_batched=dp_batched)
     f32 = cfg.dtype == wl.F32
     assert got["trace"] == ref.trace
     assert got["live"] == ref.live_inputs
@@ -124,6 +124,21 @@ def test_cfg1_tiny_mlp_fp32(rule):
 def test_small_mlp_bf16(name, rule):
     cfg = wl.get_config(name)
     check(cfg, rule, cfg.steps)
+
+
+@pytest.mark.parametrize("name", ["mlp_mini", "mlp_odd", "cfg1", "resnet18_mini_f32", "resnet50_mini_f32", "cfg2_mini",
+                                  "cfg5_mini", "resnet18_mini"])
+def test_lockstep_batched_dp_matches_dp_oracle(name):
+    """The lock-step executor (all N micro-batches of a step as one batch per stage pass) against
+    the oracle's DP rule: same trace, live counts, per-micro-batch losses and weights."""
+    cfg = wl.get_config(name)
+    got, _ = check(cfg, wl.RULE_DP, cfg.steps, dp_batched=True)
+    assert got["stats"]["peak_live_stage_inputs"] == cfg.N * cfg.S
+
+
+def test_lockstep_batched_dp_momentum():
+    cfg = wl.get_config("mlp_mini")
+    check(cfg, wl.RULE_DP, 4, momentum=0.9, weight_decay=5e-4, dp_batched=True)
 
 
 def test_single_microbatch_and_zero_lr():

@@ -32,8 +32,8 @@ def test_enum_values_match_workload_vocabulary():
         assert re.search(r"\b%s = %d\b" % (name, val), hdr), name
 
 
-def _dry(cfg, rule, T):
-    tr = b.Trainer(cfg.stages, cfg.in_shape, cfg.N, cfg.B, cfg.lr, rule, cfg.dtype, dry_run=True)
+def _dry(cfg, rule, T, dp_batched=False):
+    tr = b.Trainer(cfg.stages, cfg.in_shape, cfg.N, cfg.B, cfg.lr, rule, cfg.dtype, dry_run=True, dp_batched=dp_batched)
     for _ in range(T * 2 * cfg.S):
         tr.tick_dry(True)
     tr.drain()
@@ -55,6 +55,24 @@ def test_trace_and_live_counts_equal_oracle(name, rule):
     assert st["peak_live_stage_inputs"] == max(r.live_inputs)
     assert st["cur_activation_bytes"] == 0          # everything released after the drain
     tr.close()
+
+
+@pytest.mark.parametrize("name", ["mlp_mini", "cfg2", "cfg3", "cfg5"])
+def test_lockstep_batched_dp_keeps_the_dp_timeline(name):
+    """One batched pass per stage stands for the N lock-step passes of Fig. 1a: same trace,
+    same live counts, and the same activation bytes as the pass-by-pass DP run."""
+    cfg = wl.get_config(name)
+    T = 2
+    tr = _dry(cfg, wl.RULE_DP, T, dp_batched=True)
+    r = O.train_schedule(cfg, None, [None] * T, [None] * T, wl.RULE_DP, compute=False)
+    assert tr.trace() == r.trace
+    assert tr.live_counts() == r.live_inputs
+    assert tr.stats()["peak_live_stage_inputs"] == cfg.N * cfg.S
+    plain = _dry(cfg, wl.RULE_DP, T).stats()
+    assert abs(tr.stats()["peak_activation_bytes"] - plain["peak_activation_bytes"]) <= 0.15 * plain["peak_activation_bytes"]  # 256-byte block rounding at tiny sizes
+    tr.close()
+    with pytest.raises(b.CdpError):
+        b.Trainer(cfg.stages, cfg.in_shape, cfg.N, cfg.B, cfg.lr, wl.RULE_V2, cfg.dtype, dry_run=True, dp_batched=True)
 
 
 def test_activation_pool_is_constant_and_below_dp():
