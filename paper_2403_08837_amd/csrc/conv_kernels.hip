@@ -15,6 +15,7 @@
 #include <algorithm>
 
 #include "kernels.h"
+#include "mfma_frag.h"
 
 namespace cdp {
 
@@ -288,7 +289,7 @@ template <typename T, int TO>
 __global__ __launch_bounds__(256) void conv_wgrad_kernel(const GemmBatch batch) {
   using E = CT<T>;
   constexpr int TC = 128, VEC = E::VEC, MB = WgSlab<T>::MB;
-  constexpr int PAD = (sizeof(T) == 2) ? 4 : 4;
+  constexpr int PAD = (sizeof(T) == 2) ? 16 : 4;  // bf16: pitch of 32 bytes modulo 128 for the transposing LDS read
   constexpr int PD = TO + PAD, PX = TC + PAD;  // LDS pitches (elements)
   constexpr int WAVES_O = TO / 64;             // 1 or 2
   constexpr int WAVES_C = 4 / WAVES_O;         // 4 or 2
@@ -416,20 +417,11 @@ __global__ __launch_bounds__(256) void conv_wgrad_kernel(const GemmBatch batch) 
     if constexpr (sizeof(T) == 2) {
 #pragma unroll
       for (int kk = 0; kk < MB; kk += 16) {
-        const int mb = kk + 8 * gq;
         uint4 a[2], b[NI];
 #pragma unroll
-        for (int i = 0; i < 2; ++i) {
-          const T* p = Ds + mb * PD + wo * 64 + i * 32 + l31;
-          a[i] = make_uint4((uint32_t)p[0] | ((uint32_t)p[PD] << 16), (uint32_t)p[2 * PD] | ((uint32_t)p[3 * PD] << 16),
-                            (uint32_t)p[4 * PD] | ((uint32_t)p[5 * PD] << 16), (uint32_t)p[6 * PD] | ((uint32_t)p[7 * PD] << 16));
-        }
+        for (int i = 0; i < 2; ++i) a[i] = frag_tr_bf16(Ds, PD, kk, wo * 64 + i * 32, lane);
 #pragma unroll
-        for (int j = 0; j < NI; ++j) {
-          const T* p = Xs + mb * PX + wc * WTC + j * 32 + l31;
-          b[j] = make_uint4((uint32_t)p[0] | ((uint32_t)p[PX] << 16), (uint32_t)p[2 * PX] | ((uint32_t)p[3 * PX] << 16),
-                            (uint32_t)p[4 * PX] | ((uint32_t)p[5 * PX] << 16), (uint32_t)p[6 * PX] | ((uint32_t)p[7 * PX] << 16));
-        }
+        for (int j = 0; j < NI; ++j) b[j] = frag_tr_bf16(Xs, PX, kk, wc * WTC + j * 32, lane);
 #pragma unroll
         for (int i = 0; i < 2; ++i)
 #pragma unroll

@@ -17,6 +17,7 @@
 #include <algorithm>
 
 #include "kernels.h"
+#include "mfma_frag.h"
 #include "sgd_step.h"
 
 namespace cdp {
@@ -299,7 +300,10 @@ template <typename T>
 __device__ __forceinline__ void dw_tile(const GemmBatch& batch, const GemmProb& P, int tile, unsigned char* smem) {
   using E = LT<T>;
   constexpr int TN = 64, TK = 128, MB = 64, VEC = E::VEC;
-  constexpr int PD = TN + 4, PX = TK + 4;  // LDS pitches (elements)
+  // LDS pitches (elements): bf16 fragments are read with the transposing LDS read, which wants
+  // 32 bytes modulo 128 between consecutive rows; fp32 fragments are plain column reads
+  constexpr int PAD = sizeof(T) == 2 ? 16 : 4;
+  constexpr int PD = TN + PAD, PX = TK + PAD;
   T* Ds = reinterpret_cast<T*>(smem);
   T* Xs = Ds + MB * PD;
 
@@ -394,18 +398,9 @@ __device__ __forceinline__ void dw_tile(const GemmBatch& batch, const GemmProb& 
     if constexpr (sizeof(T) == 2) {
 #pragma unroll
       for (int kk = 0; kk < MB; kk += 16) {
-        const int mb = kk + 8 * g;
-        uint32_t xb[4], da[2][4];
+        const uint4 bv = frag_tr_bf16(Xs, PX, kk, wave * 32, lane);
 #pragma unroll
-        for (int q = 0; q < 4; ++q) {
-          xb[q] = (uint32_t)Xs[(mb + 2 * q) * PX + wave * 32 + l31] | ((uint32_t)Xs[(mb + 2 * q + 1) * PX + wave * 32 + l31] << 16);
-#pragma unroll
-          for (int i = 0; i < 2; ++i)
-            da[i][q] = (uint32_t)Ds[(mb + 2 * q) * PD + i * 32 + l31] | ((uint32_t)Ds[(mb + 2 * q + 1) * PD + i * 32 + l31] << 16);
-        }
-        const uint4 bv = make_uint4(xb[0], xb[1], xb[2], xb[3]);
-#pragma unroll
-        for (int i = 0; i < 2; ++i) acc[i] = mfma_bf16(make_uint4(da[i][0], da[i][1], da[i][2], da[i][3]), bv, acc[i]);
+        for (int i = 0; i < 2; ++i) acc[i] = mfma_bf16(frag_tr_bf16(Ds, PD, kk, i * 32, lane), bv, acc[i]);
       }
     } else {
 #pragma unroll 8
@@ -520,7 +515,7 @@ template <typename T, int BN, bool THIN>
 __global__ __launch_bounds__(256) void linear_tick_kernel(const GemmBatch batch) {
   using E = LT<T>;
   constexpr int SK_BYTES = (64 + BN) * (E::SLAB + E::VEC) * (int)sizeof(T);
-  constexpr int DW_BYTES = 64 * (64 + 4 + 128 + 4) * (int)sizeof(T);
+  constexpr int DW_BYTES = 64 * (64 + 128 + 2 * (sizeof(T) == 2 ? 16 : 4)) * (int)sizeof(T);
   static_assert(SK_BYTES >= 4 * 16 * 64 * 4, "the thin tile's partial sums must fit");
   __shared__ __attribute__((aligned(16))) unsigned char smem[SK_BYTES > DW_BYTES ? SK_BYTES : DW_BYTES];
   // Tile order: forward / data-gradient tiles, weight-gradient tiles that also take the SGD
