@@ -463,7 +463,7 @@ __global__ __launch_bounds__(256) void conv_wgrad_kernel(const GemmBatch batch) 
 }
 
 // Fold of the partial sums.  Workgroup = 128 columns of one weight row o (4 per lane) x 8
-// range groups:
+// range groups; the workgroups of all problems form one flat list:
 //   s[c] = sum_ranges part[.][o][c];  G[o][c] += gamma[o]*s[c];
 //   d gamma[o] += sum_c s[c]*Wplain[o][c]  (one atomic per 128 columns);
 //   d beta[o]  += sum_ranges part_beta[.][o]  (first column chunk only).
@@ -471,9 +471,14 @@ template <typename T>
 __global__ __launch_bounds__(256) void wgrad_reduce_kernel(const WReduceBatch batch) {
   using E = CT<T>;
   __shared__ float4 red[8][32];
-  const WReduceProb& P = batch.p[blockIdx.z];
-  const int o = blockIdx.y, c0 = blockIdx.x * 128;
-  if (o >= P.Cout || c0 >= P.Ncol) return;
+  int pi = 0;
+  for (int q = 1; q < batch.n; ++q)
+    if ((int)blockIdx.x >= batch.p[q].tile_begin) pi = q;
+  const WReduceProb& P = batch.p[pi];
+  const int chunks = (P.Ncol + 127) >> 7;
+  const int local = (int)blockIdx.x - P.tile_begin;
+  const int o = local / chunks, c0 = (local - o * chunks) * 128;
+  if (o >= P.Cout) return;
   const int cl = threadIdx.x & 31, grp = threadIdx.x >> 5;
   const int c = c0 + cl * 4;
   const int64_t row = (int64_t)o * P.Ncol, stride = (int64_t)P.Cout * P.Ncol;
@@ -525,16 +530,17 @@ __global__ __launch_bounds__(256) void wgrad_reduce_kernel(const WReduceBatch ba
   }
 }
 
-hipError_t launch_wgrad_reduce(const WReduceBatch& b, int dtype, hipStream_t stream) {
+hipError_t launch_wgrad_reduce(WReduceBatch& b, int dtype, hipStream_t stream) {
   if (b.n <= 0) return hipSuccess;
   if (b.n > WREDUCE_MAX_PROBS) return hipErrorInvalidValue;
-  int rows = 1, chunks = 1;
+  int64_t total = 0;
   for (int i = 0; i < b.n; ++i) {
-    rows = max(rows, b.p[i].Cout);
-    chunks = max(chunks, (b.p[i].Ncol + 127) / 128);
+    if (b.p[i].Cout <= 0 || b.p[i].Ncol <= 0 || b.p[i].splits <= 0) return hipErrorInvalidValue;
+    b.p[i].tile_begin = (int)total;
+    total += (int64_t)b.p[i].Cout * ((b.p[i].Ncol + 127) / 128);
+    if (total >= (1ll << 31)) return hipErrorInvalidValue;
   }
-  if (rows > 65535) return hipErrorInvalidValue;
-  dim3 grid(chunks, rows, b.n), block(256);
+  dim3 grid((unsigned)total), block(256);
   if (dtype == DT_BF16) hipLaunchKernelGGL((wgrad_reduce_kernel<uint16_t>), grid, block, 0, stream, b);
   else hipLaunchKernelGGL((wgrad_reduce_kernel<float>), grid, block, 0, stream, b);
   return hipGetLastError();

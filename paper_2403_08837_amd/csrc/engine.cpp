@@ -508,6 +508,12 @@ int build_backward(cdp_ctx* c, int i, int j, Program* prog, bool first_grad, boo
       if (o.kind == OPK_MAXPOOL) {
         it.i[0] = c->B; it.i[1] = o.Hin; it.i[2] = o.Win; it.i[3] = o.Cin; it.i[4] = o.pk; it.i[5] = o.ps; it.i[6] = o.pp;
         it.i[7] = tin.relu ? 1 : 0;
+        // tick workspace for the windows' argmax indices (one byte per pooled element)
+        Block ws;
+        const int64_t nb = (int64_t)c->B * o.Hout * o.Wout * o.Cout;
+        if (!scratch_alloc(c, nb, &ws)) return fail(c, CDP_ENOMEM, "tick workspace exhausted");
+        it.p3 = c->ptr(ws.off);
+        it.n0 = nb;
       } else {
         it.i[0] = c->B; it.i[1] = o.Hin * o.Win; it.i[2] = o.Cin; it.i[3] = tin.relu ? 1 : 0;
       }
@@ -631,7 +637,8 @@ int launch_level(cdp_ctx* c, std::vector<Item>& items) {
         break;
       case IT_MAXPOOL_B:
         HIP_TRY(c, launch_maxpool_bwd(it.p0, it.p1, it.p2, it.i[0], it.i[1], it.i[2], it.i[3], it.i[4], it.i[5], it.i[6],
-                                      it.i[7], dt, c->stream));
+                                      it.i[7], it.p3, it.n0, dt, c->stream));
+        c->stats.kernel_launches++;  // two kernels
         break;
       case IT_GAP_F:
         HIP_TRY(c, launch_gap_fwd(it.p0, it.p2, it.i[0], it.i[1], it.i[2], dt, c->stream));

@@ -119,10 +119,11 @@ struct WReduceProb {
   float* G; float* Ggamma; float* Gbeta;      // accumulators (Ggamma / Gbeta may be NULL)
   const float* gamma; const void* wplain;     // gamma f32[Cout], plain weights T[Cout][Ncol] (or NULL)
   int Cout, Ncol, splits;
+  int tile_begin;  // first workgroup of this problem in the launch (set by launch_wgrad_reduce)
 };
 constexpr int WREDUCE_MAX_PROBS = 32;
 struct WReduceBatch { int n; WReduceProb p[WREDUCE_MAX_PROBS]; };
-hipError_t launch_wgrad_reduce(const WReduceBatch& b, int dtype, hipStream_t stream);
+hipError_t launch_wgrad_reduce(WReduceBatch& b, int dtype, hipStream_t stream);
 
 // ---------------------------------------------------------------------------------
 // small kernels
@@ -170,8 +171,11 @@ hipError_t launch_im2col(const void* x, void* col, int B, const ConvGeom& g, int
 // receives the gradient); backward optionally masks with x > 0.
 hipError_t launch_maxpool_fwd(const void* x, void* y, int B, int H, int W, int C, int k, int s, int p,
                               int dtype, hipStream_t stream);
+// With a workspace of at least B*OH*OW*C bytes (and C a multiple of the 16-byte chunk) the
+// backward first records every window's first maximum there, then gathers.
 hipError_t launch_maxpool_bwd(const void* x, const void* dy, void* dx, int B, int H, int W, int C, int k,
-                              int s, int p, int mask_relu, int dtype, hipStream_t stream);
+                              int s, int p, int mask_relu, void* workspace, int64_t workspace_bytes, int dtype,
+                              hipStream_t stream);
 // Global average pool forward / backward (backward optionally masks with x > 0).
 hipError_t launch_gap_fwd(const void* x, void* y, int B, int HW, int C, int dtype, hipStream_t stream);
 hipError_t launch_gap_bwd(const void* x, const void* dy, void* dx, int B, int HW, int C, int mask_relu,

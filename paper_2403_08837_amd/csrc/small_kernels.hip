@@ -197,10 +197,13 @@ hipError_t launch_repack(const RepackArgs& a, int dtype, hipStream_t stream) {
 }
 
 // ---------------------------------------------------------------------------------
+// One 16-byte chunk of a column row per thread.  Inside a filter row kh the index k = (kw, c)
+// runs over KW*C elements that are contiguous in x, so (kh, offset in the filter row) is
+// stepped along the chunk and each filter row needs one bounds test on its offset range.
 template <typename T>
 __global__ void im2col_kernel(const T* __restrict__ x, T* __restrict__ col, int64_t n_chunks, ConvGeom g, int kpad) {
   constexpr int VEC = 16 / sizeof(T);
-  const int cpr = kpad / VEC, K = g.KH * g.KW * g.C;
+  const int cpr = kpad / VEC, RW = g.KW * g.C, K = g.KH * RW;
   for (int64_t i = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; i < n_chunks; i += (int64_t)gridDim.x * blockDim.x) {
     const int64_t m = i / cpr;
     const int k0 = (int)(i - m * cpr) * VEC;
@@ -208,16 +211,19 @@ __global__ void im2col_kernel(const T* __restrict__ x, T* __restrict__ col, int6
     const int rem = (int)(m - (int64_t)b * (g.OH * g.OW));
     const int oh = rem / g.OW, ow = rem - oh * g.OW;
     const int ih0 = oh * g.stride - g.pad, iw0 = ow * g.stride - g.pad;
+    // offsets r in [r_lo, r_hi) of a filter row fall inside the image
+    const int r_lo = max(0, -iw0) * g.C, r_hi = min(g.KW, g.W - iw0) * g.C;
+    int kh = k0 / RW, r = k0 - kh * RW;
+    const T* row = x + (((int64_t)b * g.H + ih0 + kh) * g.W + iw0) * g.C;  // x[b][ih0+kh][iw0][0]
     union { uint4 v; T e[VEC]; } out;
     out.v = make_uint4(0, 0, 0, 0);
 #pragma unroll
     for (int e = 0; e < VEC; ++e) {
-      const int k = k0 + e;
-      if (k >= K) break;
-      const int tap = k / g.C, c = k - tap * g.C;
-      const int kh = tap / g.KW, kw = tap - kh * g.KW;
-      const int ih = ih0 + kh, iw = iw0 + kw;
-      if (ih >= 0 && ih < g.H && iw >= 0 && iw < g.W) out.e[e] = x[(((int64_t)b * g.H + ih) * g.W + iw) * g.C + c];
+      if (k0 + e < K) {
+        const int ih = ih0 + kh;
+        if (ih >= 0 && ih < g.H && r >= r_lo && r < r_hi) out.e[e] = row[r];
+        if (++r == RW) { r = 0; ++kh; row += (int64_t)g.W * g.C; }
+      }
     }
     *reinterpret_cast<uint4*>(col + i * VEC) = out.v;
   }
@@ -353,11 +359,109 @@ hipError_t launch_maxpool_fwd(const void* x, void* y, int B, int H, int W, int C
                                          static_cast<const T*>(x), static_cast<T*>(y), B, H, W, C, OH, OW, k, s, p));
   return hipGetLastError();
 }
+// Backward in two steps when a workspace is given: every window's first maximum (tap index
+// in (kh, kw) scan order, one byte per output element), then a gather in which an input
+// position compares its tap index in each window that covers it.  Each window is scanned
+// once instead of once per covered position.
+template <typename T>
+__global__ void maxpool_argmax_kernel(const T* __restrict__ x, uint8_t* __restrict__ idx, int B, int H, int W, int C, int OH,
+                                      int OW, int k, int s, int p) {
+  constexpr int VEC = 16 / sizeof(T);
+  union Ch { uint4 v; T e[VEC]; };
+  union Ix { uint2 v; uint8_t e[8]; };
+  const int cpp = C / VEC;
+  const int64_t n = (int64_t)B * OH * OW * cpp;
+  for (int64_t i = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x) {
+    const int c = (int)(i % cpp) * VEC;
+    int64_t q = i / cpp;
+    const int ow = (int)(q % OW); q /= OW;
+    const int oh = (int)(q % OH);
+    const int b = (int)(q / OH);
+    float best[VEC];
+    Ix arg;
+    arg.v = make_uint2(0xffffffffu, 0xffffffffu);  // 255: no tap inside the image
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) best[e] = -INFINITY;
+    for (int kh = 0; kh < k; ++kh)
+      for (int kw = 0; kw < k; ++kw) {
+        const int jh = oh * s - p + kh, jw = ow * s - p + kw;
+        if (jh < 0 || jw < 0 || jh >= H || jw >= W) continue;
+        Ch xc;
+        xc.v = *reinterpret_cast<const uint4*>(x + (((int64_t)b * H + jh) * W + jw) * C + c);
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) {
+          const float v = ld_f32<T>(xc.e, e);
+          if (v > best[e] || arg.e[e] == 255) { best[e] = v; arg.e[e] = (uint8_t)(kh * k + kw); }
+        }
+      }
+    uint8_t* dst = idx + i * VEC;
+    if (VEC == 8) *reinterpret_cast<uint2*>(dst) = arg.v;
+    else *reinterpret_cast<uint32_t*>(dst) = arg.v.x;
+  }
+}
+
+template <typename T>
+__global__ void maxpool_bwd_idx_kernel(const T* __restrict__ x, const T* __restrict__ dy, const uint8_t* __restrict__ idx,
+                                       T* __restrict__ dx, int B, int H, int W, int C, int OH, int OW, int k, int s, int p,
+                                       int mask_relu) {
+  constexpr int VEC = 16 / sizeof(T);
+  union Ch { uint4 v; T e[VEC]; };
+  union Ix { uint2 v; uint8_t e[8]; };
+  const int cpp = C / VEC;
+  const int64_t n = (int64_t)B * H * W * cpp;
+  for (int64_t i = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x) {
+    const int c = (int)(i % cpp) * VEC;
+    int64_t q = i / cpp;
+    const int iw = (int)(q % W); q /= W;
+    const int ih = (int)(q % H);
+    const int b = (int)(q / H);
+    float g[VEC];
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) g[e] = 0.f;
+    const int oh_lo = max(0, (ih + p - k + s) / s), oh_hi = min(OH - 1, (ih + p) / s);
+    const int ow_lo = max(0, (iw + p - k + s) / s), ow_hi = min(OW - 1, (iw + p) / s);
+    for (int oh = oh_lo; oh <= oh_hi; ++oh)
+      for (int ow = ow_lo; ow <= ow_hi; ++ow) {
+        const int tap = (ih - (oh * s - p)) * k + (iw - (ow * s - p));
+        const int64_t o = (((int64_t)b * OH + oh) * OW + ow) * C + c;
+        Ix a;
+        if (VEC == 8) a.v = *reinterpret_cast<const uint2*>(idx + o);
+        else a.v = make_uint2(*reinterpret_cast<const uint32_t*>(idx + o), 0u);
+        Ch dc;
+        dc.v = *reinterpret_cast<const uint4*>(dy + o);
+#pragma unroll
+        for (int e = 0; e < VEC; ++e)
+          if (a.e[e] == tap) g[e] += ld_f32<T>(dc.e, e);
+      }
+    Ch out;
+    if (mask_relu) {
+      Ch xc;
+      xc.v = *reinterpret_cast<const uint4*>(x + (((int64_t)b * H + ih) * W + iw) * C + c);
+#pragma unroll
+      for (int e = 0; e < VEC; ++e)
+        if (!(ld_f32<T>(xc.e, e) > 0.f)) g[e] = 0.f;
+    }
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) st_f32<T>(out.e, e, g[e]);
+    *reinterpret_cast<uint4*>(dx + (((int64_t)b * H + ih) * W + iw) * C + c) = out.v;
+  }
+}
+
 hipError_t launch_maxpool_bwd(const void* x, const void* dy, void* dx, int B, int H, int W, int C, int k, int s, int p,
-                              int mask_relu, int dtype, hipStream_t stream) {
+                              int mask_relu, void* workspace, int64_t workspace_bytes, int dtype, hipStream_t stream) {
   int OH = (H + 2 * p - k) / s + 1, OW = (W + 2 * p - k) / s + 1;
   int64_t n = (int64_t)B * H * W * C;
   const int vec = dtype == DT_BF16 ? 8 : 4;
+  const int64_t n_out = (int64_t)B * OH * OW * C;
+  if (C % vec == 0 && workspace != nullptr && workspace_bytes >= n_out && k * k < 255) {
+    uint8_t* idx = static_cast<uint8_t*>(workspace);
+    CDP_DISPATCH(dtype, hipLaunchKernelGGL((maxpool_argmax_kernel<T>), dim3(blocks_for(n_out / vec, 256, 1 << 20)), dim3(256), 0,
+                                           stream, static_cast<const T*>(x), idx, B, H, W, C, OH, OW, k, s, p));
+    CDP_DISPATCH(dtype, hipLaunchKernelGGL((maxpool_bwd_idx_kernel<T>), dim3(blocks_for(n / vec, 256, 1 << 20)), dim3(256), 0,
+                                           stream, static_cast<const T*>(x), static_cast<const T*>(dy), idx, static_cast<T*>(dx),
+                                           B, H, W, C, OH, OW, k, s, p, mask_relu));
+    return hipGetLastError();
+  }
   if (C % vec == 0) {
     CDP_DISPATCH(dtype, hipLaunchKernelGGL((maxpool_bwd_vec_kernel<T>), dim3(blocks_for(n / vec, 256, 1 << 20)), dim3(256), 0, stream,
                                            static_cast<const T*>(x), static_cast<const T*>(dy), static_cast<T*>(dx), B, H, W, C,
