@@ -462,8 +462,11 @@ __global__ __launch_bounds__(256) void conv_wgrad_kernel(const GemmBatch batch) 
   if (do_beta && o0 + tid < Cout) static_cast<float*>(P.aux3)[(int64_t)split * Cout + o0 + tid] = bsum;
 }
 
-// Fold of the partial sums.  Workgroup = 128 columns of one weight row o (4 per lane) x 8
-// range groups; the workgroups of all problems form one flat list:
+// Fold of the partial sums.  A workgroup is 8 groups of 32 lanes; a lane owns 4 of the 128
+// columns of its group's weight row.  Depending on the number of ranges, `rg` = 1, 2, 4 or 8
+// groups share one row (each summing every rg-th range) and the workgroup covers 8/rg rows,
+// so layers with few ranges still give every lane work and layers with hundreds of ranges
+// still split the long sum.  The workgroups of all problems form one flat list.
 //   s[c] = sum_ranges part[.][o][c];  G[o][c] += gamma[o]*s[c];
 //   d gamma[o] += sum_c s[c]*Wplain[o][c]  (one atomic per 128 columns);
 //   d beta[o]  += sum_ranges part_beta[.][o]  (first column chunk only).
@@ -475,23 +478,42 @@ __global__ __launch_bounds__(256) void wgrad_reduce_kernel(const WReduceBatch ba
   for (int q = 1; q < batch.n; ++q)
     if ((int)blockIdx.x >= batch.p[q].tile_begin) pi = q;
   const WReduceProb& P = batch.p[pi];
+  const int rg = P.rg, rows_per_wg = 8 / rg;
   const int chunks = (P.Ncol + 127) >> 7;
   const int local = (int)blockIdx.x - P.tile_begin;
-  const int o = local / chunks, c0 = (local - o * chunks) * 128;
-  if (o >= P.Cout) return;
+  const int ob = local / chunks, c0 = (local - ob * chunks) * 128;
   const int cl = threadIdx.x & 31, grp = threadIdx.x >> 5;
+  const int o = ob * rows_per_wg + grp / rg, q0 = grp % rg;
   const int c = c0 + cl * 4;
+  const bool row_ok = o < P.Cout;
   const int64_t row = (int64_t)o * P.Ncol, stride = (int64_t)P.Cout * P.Ncol;
   const bool vec4 = (P.Ncol & 3) == 0;  // rows of the partial buffers are 16-byte aligned
   float4 sum = make_float4(0.f, 0.f, 0.f, 0.f);
-  if (vec4) {
-    if (c < P.Ncol)
-      for (int q = grp; q < P.splits; q += 8) {
-        const float4 v = *reinterpret_cast<const float4*>(P.part + q * stride + row + c);
+  if (row_ok && vec4) {
+    if (c < P.Ncol) {
+      // four independent loads in flight per lane
+      const float* src = P.part + row + c;
+      float4 s1 = sum, s2 = sum, s3 = sum;
+      int q = q0;
+      for (; q + 3 * rg < P.splits; q += 4 * rg) {
+        const float4 v0 = *reinterpret_cast<const float4*>(src + q * stride);
+        const float4 v1 = *reinterpret_cast<const float4*>(src + (q + rg) * stride);
+        const float4 v2 = *reinterpret_cast<const float4*>(src + (q + 2 * rg) * stride);
+        const float4 v3 = *reinterpret_cast<const float4*>(src + (q + 3 * rg) * stride);
+        sum.x += v0.x; sum.y += v0.y; sum.z += v0.z; sum.w += v0.w;
+        s1.x += v1.x; s1.y += v1.y; s1.z += v1.z; s1.w += v1.w;
+        s2.x += v2.x; s2.y += v2.y; s2.z += v2.z; s2.w += v2.w;
+        s3.x += v3.x; s3.y += v3.y; s3.z += v3.z; s3.w += v3.w;
+      }
+      for (; q < P.splits; q += rg) {
+        const float4 v = *reinterpret_cast<const float4*>(src + q * stride);
         sum.x += v.x; sum.y += v.y; sum.z += v.z; sum.w += v.w;
       }
-  } else {
-    for (int q = grp; q < P.splits; q += 8) {
+      sum.x += (s1.x + s2.x) + s3.x; sum.y += (s1.y + s2.y) + s3.y;
+      sum.z += (s1.z + s2.z) + s3.z; sum.w += (s1.w + s2.w) + s3.w;
+    }
+  } else if (row_ok) {
+    for (int q = q0; q < P.splits; q += rg) {
       const float* src = P.part + q * stride + row;
       if (c + 0 < P.Ncol) sum.x += src[c + 0];
       if (c + 1 < P.Ncol) sum.y += src[c + 1];
@@ -501,27 +523,26 @@ __global__ __launch_bounds__(256) void wgrad_reduce_kernel(const WReduceBatch ba
   }
   red[grp][cl] = sum;
   __syncthreads();
-  if (grp == 0) {
-    float tot[4] = {0.f, 0.f, 0.f, 0.f};
+  if (!row_ok || q0 != 0) return;
+  float tot[4] = {0.f, 0.f, 0.f, 0.f};
+  for (int k = 0; k < rg; ++k) {
+    const float4 v = red[grp + k][cl];
+    tot[0] += v.x; tot[1] += v.y; tot[2] += v.z; tot[3] += v.w;
+  }
+  const float gam = P.gamma ? P.gamma[o] : 1.f;
+  float dg = 0.f;
 #pragma unroll
-    for (int k = 0; k < 8; ++k) {
-      const float4 v = red[k][cl];
-      tot[0] += v.x; tot[1] += v.y; tot[2] += v.z; tot[3] += v.w;
+  for (int e = 0; e < 4; ++e)
+    if (c + e < P.Ncol) {
+      P.G[row + c + e] += gam * tot[e];
+      if (P.wplain) dg += tot[e] * E::to_f32(static_cast<const T*>(P.wplain)[row + c + e]);
     }
-    const float gam = P.gamma ? P.gamma[o] : 1.f;
-    float dg = 0.f;
+  if (P.Ggamma) {  // the 32 lanes of this group (shuffles stay inside a half wavefront)
 #pragma unroll
-    for (int e = 0; e < 4; ++e)
-      if (c + e < P.Ncol) {
-        P.G[row + c + e] += gam * tot[e];
-        if (P.wplain) dg += tot[e] * E::to_f32(static_cast<const T*>(P.wplain)[row + c + e]);
-      }
-    if (P.Ggamma) {  // lanes 0..31 of wavefront 0
-#pragma unroll
-      for (int off = 16; off >= 1; off >>= 1) dg += __shfl_xor(dg, off, 64);
-      if (cl == 0) atomicAdd(P.Ggamma + o, dg);
-    }
-  } else if (grp == 2 && c0 == 0 && P.Gbeta) {  // wavefront 1, lanes 0..31
+    for (int off = 16; off >= 1; off >>= 1) dg += __shfl_xor(dg, off, 64);
+    if (cl == 0) atomicAdd(P.Ggamma + o, dg);
+  }
+  if (c0 == 0 && P.Gbeta) {
     float sb = 0.f;
     for (int q = cl; q < P.splits; q += 32) sb += P.part_beta[(int64_t)q * P.Cout + o];
 #pragma unroll
@@ -535,9 +556,12 @@ hipError_t launch_wgrad_reduce(WReduceBatch& b, int dtype, hipStream_t stream) {
   if (b.n > WREDUCE_MAX_PROBS) return hipErrorInvalidValue;
   int64_t total = 0;
   for (int i = 0; i < b.n; ++i) {
-    if (b.p[i].Cout <= 0 || b.p[i].Ncol <= 0 || b.p[i].splits <= 0) return hipErrorInvalidValue;
-    b.p[i].tile_begin = (int)total;
-    total += (int64_t)b.p[i].Cout * ((b.p[i].Ncol + 127) / 128);
+    WReduceProb& p = b.p[i];
+    if (p.Cout <= 0 || p.Ncol <= 0 || p.splits <= 0) return hipErrorInvalidValue;
+    p.rg = p.splits <= 8 ? 1 : p.splits <= 16 ? 2 : p.splits <= 32 ? 4 : 8;
+    const int rows_per_wg = 8 / p.rg;
+    p.tile_begin = (int)total;
+    total += (int64_t)((p.Cout + rows_per_wg - 1) / rows_per_wg) * ((p.Ncol + 127) / 128);
     if (total >= (1ll << 31)) return hipErrorInvalidValue;
   }
   dim3 grid((unsigned)total), block(256);

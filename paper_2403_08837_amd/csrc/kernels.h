@@ -120,6 +120,7 @@ struct WReduceProb {
   const float* gamma; const void* wplain;     // gamma f32[Cout], plain weights T[Cout][Ncol] (or NULL)
   int Cout, Ncol, splits;
   int tile_begin;  // first workgroup of this problem in the launch (set by launch_wgrad_reduce)
+  int rg;          // groups of 32 lanes that share one weight row (set by launch_wgrad_reduce)
 };
 constexpr int WREDUCE_MAX_PROBS = 32;
 struct WReduceBatch { int n; WReduceProb p[WREDUCE_MAX_PROBS]; };
