@@ -43,7 +43,8 @@ KIND_NAMES = {LINEAR: "linear", RELU: "relu", CONV2D: "conv2d", AFFINE: "affine"
 RULE_DP = 0
 RULE_V1 = 1
 RULE_V2 = 2
-RULE_NAMES = {RULE_DP: "dp", RULE_V1: "cdp_v1", RULE_V2: "cdp_v2"}
+RULE_MASK = 3   # per (micro-batch, stage) choice between the v2 and the v1 selector
+RULE_NAMES = {RULE_DP: "dp", RULE_V1: "cdp_v1", RULE_V2: "cdp_v2", RULE_MASK: "cdp_mask"}
 
 # compute dtypes (must equal enum cdp_dtype)
 F32 = 0

@@ -40,7 +40,7 @@ FWD, BWD = 0, 1
 # ---------------------------------------------------------------------------
 # schedule (integers only)
 # ---------------------------------------------------------------------------
-def delay_for(S: int, N: int, rule: int) -> int:
+def delay_for(S: int, N: int, rule: int) -> int:  # every cyclic rule (v1, v2, masks) shares the delay
     """Uniform start delay.  DP: all micro-batches in lock-step (Fig. 1a)."""
     if rule == wl.RULE_DP:
         return 0
@@ -68,7 +68,7 @@ def total_ticks(S: int, N: int, d: int, T: int) -> int:
     return 2 * S * T + d * (N - 1) if T > 0 else 0
 
 
-def fresh_closed_form(rule: int, S: int, N: int, d: int, i: int, j: int) -> bool:
+def fresh_closed_form(rule: int, S: int, N: int, d: int, i: int, j: int, mask=None) -> bool:
     """u_{i,j} = a (use theta_t) iff this returns True, else b (theta_{t-1}).
 
     DP: always theta_t (Eq. (DP)).  v1: always theta_{t-1} (Eq. (CDP-v1)).
@@ -76,12 +76,18 @@ def fresh_closed_form(rule: int, S: int, N: int, d: int, i: int, j: int) -> bool
     from the timeline: stage j receives its N-th gradient of step t-1 at tick
     2S*t + 2S - d - 1 - j, micro-batch i of step t reads stage j at tick
     2S*t + d*i + j, hence fresh iff d*(i+1) + 2*j >= 2S.
+    RULE_MASK (the rules "in between" of Sec. 3.2, "Update rules"): theta_t where
+    mask[i][j] is set AND theta_t is already in memory (the v2 condition), else theta_{t-1};
+    an all-ones mask is v2, an all-zeros mask is v1.
     """
     if rule == wl.RULE_DP:
         return True
     if rule == wl.RULE_V1:
         return False
-    return d * (i + 1) + 2 * j >= 2 * S
+    avail = d * (i + 1) + 2 * j >= 2 * S
+    if rule == wl.RULE_MASK:
+        return bool(mask[i][j]) and avail
+    return avail
 
 
 # ---------------------------------------------------------------------------
@@ -121,7 +127,7 @@ def sgd_update(w: np.ndarray, gsum: np.ndarray, v: Optional[np.ndarray], lr: flo
 def train_equation(cfg: wl.Config, params0, xs: Sequence[np.ndarray], ys: Sequence[np.ndarray],
                    rule: int, lr: Optional[float] = None,
                    rnd: Callable[[np.ndarray], np.ndarray] = L.identity,
-                   momentum: float = 0.0, weight_decay: float = 0.0) -> Result:
+                   momentum: float = 0.0, weight_decay: float = 0.0, mask=None) -> Result:
     """theta_{t+1} = theta_t - (lr/N) sum_i grad f_i(theta_hat_{i,t}),
     theta_hat^j_{i,t} = theta^j_t if fresh(i,j) else theta^j_{t-1}, theta_{-1} := theta_0."""
     S, N, B = cfg.S, cfg.N, cfg.B
@@ -135,7 +141,7 @@ def train_equation(cfg: wl.Config, params0, xs: Sequence[np.ndarray], ys: Sequen
         cur, prev = hist[t], hist[max(t - 1, 0)]
         gsum = [[np.zeros_like(a) for a in st] for st in cur]
         for i in range(N):
-            mix = [cur[j] if fresh_closed_form(rule, S, N, d, i, j) else prev[j] for j in range(S)]
+            mix = [cur[j] if fresh_closed_form(rule, S, N, d, i, j, mask) else prev[j] for j in range(S)]
             x = np.asarray(xs[t][i * B:(i + 1) * B], dtype=np.float64)
             y = np.asarray(ys[t][i * B:(i + 1) * B])
             loss, grads = L.model_forward_backward(cfg.stages, mix, rnd(x), y, rnd)
@@ -162,7 +168,7 @@ def train_schedule(cfg: wl.Config, params0, xs: Sequence[np.ndarray], ys: Sequen
                    rnd: Callable[[np.ndarray], np.ndarray] = L.identity,
                    compute: bool = True, keep_versions: bool = True,
                    progress: Optional[Callable[[int, int], None]] = None,
-                   momentum: float = 0.0, weight_decay: float = 0.0) -> Result:
+                   momentum: float = 0.0, weight_decay: float = 0.0, mask=None, bwd_fresh: bool = False) -> Result:
     """Per tick: every active micro-batch runs one stage forward or backward with the
     weight version the rule assigns (forward) or the one its own forward used
     (backward); a backward adds its gradient to the stage accumulator; at the end of
@@ -170,7 +176,16 @@ def train_schedule(cfg: wl.Config, params0, xs: Sequence[np.ndarray], ys: Sequen
     the new version becomes visible from the next tick.  ``compute=False`` runs the
     integer bookkeeping only (trace, versions, live counts); ``keep_versions=False`` does
     not retain superseded weight versions (large models); ``progress(tick, n_ticks)`` is
-    called after every tick."""
+    called after every tick.
+
+    ``mask`` (RULE_MASK): N x S array; forward (i, j) reads the freshest version where
+    mask[i][j] is set, theta_{t-1} elsewhere.
+    ``bwd_fresh``: the variant Sec. 3.2 alludes to when it says that no second copy of
+    the parameters is needed: the backward reads the parameters that are freshest in
+    memory at ITS tick (every parameter the backward formulas touch), on the activations
+    its forward saved.  The applied gradient is then no longer the gradient of f_i at one
+    point, so this variant has no counterpart in the equation oracle; the trace records the
+    version the backward read."""
     S, N, B = cfg.S, cfg.N, cfg.B
     lr = cfg.lr if lr is None else lr
     d = delay_for(S, N, rule)
@@ -197,9 +212,9 @@ def train_schedule(cfg: wl.Config, params0, xs: Sequence[np.ndarray], ys: Sequen
         res.live_inputs.append(live)
         for (i, t, j, dr) in act:
             if dr == FWD:
-                if rule == wl.RULE_V2:
+                if rule == wl.RULE_V2 or (rule == wl.RULE_MASK and mask[i][j]):
                     v = ver[j]                      # freshest parameters in memory
-                elif rule == wl.RULE_V1:
+                elif rule == wl.RULE_V1 or rule == wl.RULE_MASK:
                     v = max(t - 1, 0)               # theta_{t-1}
                 else:
                     v = t                           # theta_t
@@ -220,6 +235,8 @@ def train_schedule(cfg: wl.Config, params0, xs: Sequence[np.ndarray], ys: Sequen
                     saved[(t, i, j)] = True
             else:
                 v = used.pop((t, i, j))
+                if bwd_fresh:
+                    v = ver[j]
                 assert ring_ver[j][v % 2] == v, "ring depth 2 violated (bwd)"
                 sv = saved.pop((t, i, j))
                 if compute:

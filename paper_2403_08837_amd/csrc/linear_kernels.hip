@@ -212,21 +212,21 @@ __device__ __forceinline__ void skinny_tile(const GemmProb& P, int tile, unsigne
 // ---------------------------------------------------------------------------------
 // thin tile: problems of at most 32 rows whose operands are whole 16-byte chunks.  A
 // workgroup owns 32 x 32 outputs and its four waves split the reduction: wave w takes
-// slabs w, w+4, ...  Nothing is staged: a lane loads its MFMA fragments straight from
-// memory, and because the order of the reduction index is free as long as both operands
-// agree, lane (row, half) reads one contiguous 128-byte run of its row per slab (half 0
-// the first run, half 1 the second) instead of interleaved 16-byte pieces.  The k-loop has
-// no barrier; the partial tiles meet once in LDS, each wave finishing 8 of the 32 rows.
+// slabs w, w+4, ...  Nothing is staged: a lane loads its MFMA fragments (16 bytes of its row
+// per reduction step) straight from memory, both halves of the wavefront together covering 32
+// contiguous bytes of each of 32 rows per load instruction (measured: 1.7x the rate of
+// giving every lane a 128-byte run of its own).  The k-loop has no barrier; the partial tiles
+// meet once in LDS, each wave finishing 8 of the 32 rows.
 template <typename T>
 __device__ __forceinline__ void thin_tile(const GemmProb& P, int tile, unsigned char* smem) {
   using E = LT<T>;
-  constexpr int VEC = E::VEC, CH = 8, RUN = CH * VEC, SLAB = 2 * RUN;
+  constexpr int VEC = E::VEC, CH = 8, SLAB = 2 * CH * VEC;  // chunk c of lane (row, g) holds k = 2*VEC*c + VEC*g ...
   const int col0 = (tile - P.tile_begin) * 32;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int r31 = lane & 31, g = lane >> 5;
   // rows past the end are read from the last valid row: they only reach outputs that are not stored
-  const T* __restrict__ ap = static_cast<const T*>(P.A) + (int64_t)min(r31, P.M - 1) * P.lda + g * RUN;
-  const T* __restrict__ bp = static_cast<const T*>(P.B) + (int64_t)min(col0 + r31, P.N - 1) * P.ldb + g * RUN;
+  const T* __restrict__ ap = static_cast<const T*>(P.A) + (int64_t)min(r31, P.M - 1) * P.lda + g * VEC;
+  const T* __restrict__ bp = static_cast<const T*>(P.B) + (int64_t)min(col0 + r31, P.N - 1) * P.ldb + g * VEC;
   const int nslab = (P.K + SLAB - 1) / SLAB;
   const int s0 = (int)(((unsigned)tile * 2654435761u) >> 8) % nslab;
   auto slab_k = [&](int i) { const int q = s0 + i; return (q >= nslab ? q - nslab : q) * SLAB; };
@@ -236,15 +236,15 @@ __device__ __forceinline__ void thin_tile(const GemmProb& P, int tile, unsigned 
     if (k0 + SLAB <= P.K) {
 #pragma unroll
       for (int c = 0; c < CH; ++c) {
-        qa[c] = *reinterpret_cast<const uint4*>(ap + k0 + c * VEC);
-        qb[c] = *reinterpret_cast<const uint4*>(bp + k0 + c * VEC);
+        qa[c] = *reinterpret_cast<const uint4*>(ap + k0 + 2 * c * VEC);
+        qb[c] = *reinterpret_cast<const uint4*>(bp + k0 + 2 * c * VEC);
       }
     } else {  // last, partial slab: chunks past K are zero in both operands
 #pragma unroll
       for (int c = 0; c < CH; ++c) {
-        const bool kin = k0 + g * RUN + c * VEC < P.K;
-        qa[c] = kin ? *reinterpret_cast<const uint4*>(ap + k0 + c * VEC) : make_uint4(0, 0, 0, 0);
-        qb[c] = kin ? *reinterpret_cast<const uint4*>(bp + k0 + c * VEC) : make_uint4(0, 0, 0, 0);
+        const bool kin = k0 + (2 * c + g) * VEC < P.K;
+        qa[c] = kin ? *reinterpret_cast<const uint4*>(ap + k0 + 2 * c * VEC) : make_uint4(0, 0, 0, 0);
+        qb[c] = kin ? *reinterpret_cast<const uint4*>(bp + k0 + 2 * c * VEC) : make_uint4(0, 0, 0, 0);
       }
     }
   };

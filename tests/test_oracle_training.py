@@ -186,3 +186,130 @@ def test_momentum_equation_equals_timeline(rule):
         assert _close(b.params[j], a.params[j], 1e-12)
     plain = O.train_schedule(cfg, p0, xs, ys, rule)
     assert O.max_rel_err(b.params[0], plain.params[0]) > 1e-6
+
+
+# ---------------------------------------------------------------------------
+# rules between v1 and v2 (Sec. 3.2, "Update rules"), and the backward that reads the
+# freshest parameters
+# ---------------------------------------------------------------------------
+def _rand_mask(cfg, seed):
+    return np.random.default_rng(seed).integers(0, 2, (cfg.N, cfg.S))
+
+
+@pytest.mark.parametrize("name", ["mlp_mini", "mlp_odd", "resnet18_mini"])
+def test_mask_rule_with_constant_masks_is_v1_and_v2(name):
+    cfg, p0, xs, ys = _setup(name, 3)
+    for const, rule in ((1, wl.RULE_V2), (0, wl.RULE_V1)):
+        m = np.full((cfg.N, cfg.S), const)
+        a = O.train_schedule(cfg, p0, xs, ys, wl.RULE_MASK, mask=m)
+        b = O.train_schedule(cfg, p0, xs, ys, rule)
+        assert a.trace == b.trace and a.live_inputs == b.live_inputs
+        assert np.array_equal(a.losses, b.losses)
+        for j in range(cfg.S):
+            for u, v in zip(a.params[j], b.params[j]):
+                assert np.array_equal(u, v)
+
+
+@pytest.mark.parametrize("name", ["mlp_mini", "mlp_odd", "resnet18_mini"])
+@pytest.mark.parametrize("seed", [1, 2])
+def test_mask_rule_equation_equals_timeline(name, seed):
+    cfg, p0, xs, ys = _setup(name, 3)
+    m = _rand_mask(cfg, seed)
+    a = O.train_equation(cfg, p0, xs, ys, wl.RULE_MASK, mask=m)
+    b = O.train_schedule(cfg, p0, xs, ys, wl.RULE_MASK, mask=m)
+    for j in range(cfg.S):
+        assert _close(b.params[j], a.params[j], 1e-12)
+    assert np.abs(a.losses - b.losses).max() < 1e-12
+
+
+def test_mask_rule_gradient_point_with_autograd():
+    """Micro-batch i is differentiated at theta^j_t where the mask allows it AND the v2
+    condition j >= N-i+1 (1-indexed, S = N) holds, at theta^j_{t-1} elsewhere."""
+    cfg, p0, xs, ys = _setup("mlp_mini", 4)
+    N, B = cfg.N, cfg.B
+    m = _rand_mask(cfg, 5)
+    assert 0 < m.sum() < m.size
+    r = O.train_schedule(cfg, p0, xs, ys, wl.RULE_MASK, mask=m)
+    for t in range(4):
+        gsum = None
+        for i1 in range(1, N + 1):
+            mix = [r.versions[(j1 - 1, t if (m[i1 - 1][j1 - 1] and j1 >= N - i1 + 1) else max(t - 1, 0))]
+                   for j1 in range(1, N + 1)]
+            sl = slice((i1 - 1) * B, i1 * B)
+            _, g = _torch_grads(cfg, mix, xs[t][sl], ys[t][sl])
+            gsum = g if gsum is None else [[a + b for a, b in zip(x, y)] for x, y in zip(gsum, g)]
+        for j in range(N):
+            want = [w - cfg.lr / N * gw for w, gw in zip(r.versions[(j, t)], gsum[j])]
+            assert _close(r.versions[(j, t + 1)], want, 1e-10)
+    v1 = O.train_schedule(cfg, p0, xs, ys, wl.RULE_V1)
+    v2 = O.train_schedule(cfg, p0, xs, ys, wl.RULE_V2)
+    assert not _close(r.params[1], v1.params[1], 1e-6) and not _close(r.params[1], v2.params[1], 1e-6)
+
+
+def test_bwd_fresh_degenerate_cases_are_the_exact_rules():
+    """One micro-batch, the lock-step rule and the first step never see two versions."""
+    cfg, p0, xs, ys = _setup("mlp_odd", 3, N=1)
+    a = O.train_schedule(cfg, p0, xs, ys, wl.RULE_V2, bwd_fresh=True)
+    b = O.train_schedule(cfg, p0, xs, ys, wl.RULE_V2)
+    assert a.trace == b.trace
+    for j in range(cfg.S):
+        assert all(np.array_equal(u, v) for u, v in zip(a.params[j], b.params[j]))
+    cfg, p0, xs, ys = _setup("mlp_mini", 3)
+    a = O.train_schedule(cfg, p0, xs, ys, wl.RULE_DP, bwd_fresh=True)
+    b = O.train_schedule(cfg, p0, xs, ys, wl.RULE_DP)
+    for j in range(cfg.S):
+        assert all(np.array_equal(u, v) for u, v in zip(a.params[j], b.params[j]))
+    a = O.train_schedule(cfg, p0, xs[:1], ys[:1], wl.RULE_V2, bwd_fresh=True)
+    b = O.train_schedule(cfg, p0, xs[:1], ys[:1], wl.RULE_V2)
+    for j in range(cfg.S):
+        assert all(np.array_equal(u, v) for u, v in zip(a.params[j], b.params[j]))
+
+
+def test_bwd_fresh_reads_the_freshest_version_and_matches_autograd_surrogate():
+    """(a) every backward record carries the number of updates its stage has received before
+    that tick; (b) the applied gradient equals backpropagation in which the Jacobian with
+    respect to a layer's input is taken with the backward's parameters and everything else
+    (values, ReLU masks, weight gradients) with the forward's.  Built with torch autograd:
+    linear(x) = linear(x.detach(); W_f) + (x W_b^T - (x W_b^T).detach())."""
+    cfg, p0, xs, ys = _setup("mlp_mini", 4)
+    N, B, S = cfg.N, cfg.B, cfg.S
+    r = O.train_schedule(cfg, p0, xs, ys, wl.RULE_V2, bwd_fresh=True)
+    exact = O.train_schedule(cfg, p0, xs, ys, wl.RULE_V2)
+    assert not _close(r.params[1], exact.params[1], 1e-6)       # it is a different iteration
+    n_upd = {}
+    for (tick, i, t, j, dr, v) in r.trace:
+        if dr == O.BWD:
+            assert v == sum(1 for (ut, uj, _) in r.updates if uj == j and ut < tick)
+    vf = {(t, i, j): v for (_, i, t, j, dr, v) in r.trace if dr == O.FWD}
+    vb = {(t, i, j): v for (_, i, t, j, dr, v) in r.trace if dr == O.BWD}
+    assert any(vf[k] != vb[k] for k in vf)
+
+    def surrogate(t, i):
+        pf = [to_torch_params([r.versions[(j, vf[(t, i, j)])]])[0] for j in range(S)]
+        pb = [[torch.tensor(np.asarray(a)) for a in r.versions[(j, vb[(t, i, j)])]] for j in range(S)]
+        h = to_torch_x(xs[t][i * B:(i + 1) * B])
+        y = torch.tensor(np.asarray(ys[t][i * B:(i + 1) * B]), dtype=torch.long)
+        for j in range(S):
+            k = 0
+            for layer in cfg.stages[j]:
+                if layer.kind == wl.LINEAR:
+                    Wf, bf, Wb = pf[j][k], pf[j][k + 1], pb[j][k]
+                    lin_b = h @ Wb.T
+                    h = torch.nn.functional.linear(h.detach(), Wf, bf) + (lin_b - lin_b.detach())
+                    k += 2
+                elif layer.kind == wl.RELU:
+                    h = torch.relu(h)
+                else:
+                    assert layer.kind == wl.CE_HEAD
+                    h = torch.nn.functional.cross_entropy(h, y)
+        h.backward()
+        return [[p.grad.numpy() for p in st] for st in pf]
+
+    for t in range(4):
+        gsum = None
+        for i in range(N):
+            g = surrogate(t, i)
+            gsum = g if gsum is None else [[a + b for a, b in zip(x, y)] for x, y in zip(gsum, g)]
+        for j in range(S):
+            want = [w - cfg.lr / N * gw for w, gw in zip(r.versions[(j, t)], gsum[j])]
+            assert _close(r.versions[(j, t + 1)], want, 1e-10)
