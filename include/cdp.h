@@ -43,7 +43,9 @@ typedef enum {
 typedef enum {
   CDP_RULE_DP = 0, /* Eq. (DP):     every gradient of step t at theta_t               */
   CDP_RULE_V1 = 1, /* Eq. (CDP-v1): every gradient of step t at theta_{t-1}           */
-  CDP_RULE_V2 = 2  /* Eq. (CDP-v2): freshest version in memory when the stage is read */
+  CDP_RULE_V2 = 2, /* Eq. (CDP-v2): freshest version in memory when the stage is read */
+  CDP_RULE_MASK = 3 /* a rule in between (Sec. 3.2, "Update rules"): cdp_opts.fresh_mask says, per
+                       (micro-batch, stage), v2's choice (1) or v1's (0)                  */
 } cdp_rule;
 
 /* Arithmetic of the contractions.  Accumulation, master weights, gradient
@@ -95,6 +97,13 @@ typedef struct {
                           throughput baseline the cyclic schedule is compared with.  Same update
                           (Eq. (DP)), same trace, live counts and per-micro-batch losses as the
                           pass-by-pass DP run; summation order inside a contraction differs.     */
+  const uint8_t* fresh_mask; /* host, N*S bytes, [micro-batch][stage]; read at cdp_init; needed by (and only
+                                by) CDP_RULE_MASK.  All ones is CDP_RULE_V2, all zeros CDP_RULE_V1.   */
+  int32_t bwd_fresh;   /* 1: the backward of a stage reads the parameters that are freshest in memory at
+                          its own tick instead of the version its forward read (the variant Sec. 3.2
+                          alludes to: no second copy of the parameters needed).  The applied gradient is
+                          then not the gradient of f_i at one point.  The trace records the version the
+                          backward read.  Not combined with dp_batched.                              */
 } cdp_opts;
 
 /* One executed (micro-batch, stage) pass. */

@@ -101,6 +101,8 @@ typedef std::vector<std::vector<Item>> Program;
 struct cdp_ctx {
   ModelPlan plan;
   int S = 0, N = 0, B = 0, d = 0, rule = 0;
+  std::vector<uint8_t> fresh_mask;  // CDP_RULE_MASK: [micro-batch][stage]
+  bool bwd_fresh = false;           // backward reads the freshest version
   int groups = 1;  // lock-step batched DP: the caller's micro-batches run as one batch of groups * (caller's B) rows (then N = 1)
   float lr = 0.f, momentum = 0.f, weight_decay = 0.f;
   bool dry = false;
@@ -245,7 +247,10 @@ GemmProb dgrad_prob(const cdp_ctx* c, const Op& o, const void* dz, void* dx, con
   return p;
 }
 
-GemmProb wgrad_prob(const cdp_ctx* c, const Op& o, const void* dz, const void* x, const char* slot, float* G, bool first) {
+// slot: weight version the backward reads (gamma of the affine); slot_f: version the forward read (the plain
+// weights that rebuild the pre-affine activation in the gamma gradient).
+GemmProb wgrad_prob(const cdp_ctx* c, const Op& o, const void* dz, const void* x, const char* slot, const char* slot_f,
+                    float* G, bool first) {
   GemmProb p = zero_prob();
   const int rows = c->B * o.Hout * o.Wout;
   p.A = dz; p.a_mode = OP_PLAIN_R; p.lda = o.Cout;
@@ -260,7 +265,7 @@ GemmProb wgrad_prob(const cdp_ctx* c, const Op& o, const void* dz, const void* x
     // accumulators of conv weights are kept zeroed by the update kernel; the long reduction
     // over output positions is split across workgroups
     p.flags = GF_ATOMIC;
-    if (o.has_gamma) { p.aux0 = slot + o.gamma_c; p.aux1 = slot + o.wp; p.aux2 = G + o.g_off; }
+    if (o.has_gamma) { p.aux0 = slot + o.gamma_c; p.aux1 = slot_f + o.wp; p.aux2 = G + o.g_off; }
     if (conv_fast_eligible(p, c->plan.dtype)) {
       // two-phase path: build_backward points out / aux3 at a partial-sum workspace
       const int to = p.M >= 128 ? 128 : 64;
@@ -392,12 +397,13 @@ int build_forward(cdp_ctx* c, int i, int64_t t, int j, int version, const float*
   return CDP_OK;
 }
 
-int build_backward(cdp_ctx* c, int i, int j, Program* prog, bool first_grad, bool fuse_update) {
+int build_backward(cdp_ctx* c, int i, int j, int version, Program* prog, bool first_grad, bool fuse_update) {
   const StagePlan& sp = c->plan.stages[j];
   VisitRecord& r = c->rec[i][j];
   if (!r.live) return fail(c, CDP_ESTATE, "backward without a matching forward");
   const StageState& ss = c->st[j];
-  const char* slot = static_cast<const char*>(c->ptr(ss.slot[r.version & 1]));
+  const char* slot = static_cast<const char*>(c->ptr(ss.slot[version & 1]));      // parameters the backward reads
+  const char* slot_f = static_cast<const char*>(c->ptr(ss.slot[r.version & 1]));  // parameters its forward read
   float* G = c->fptr(ss.G);
   const int nt = (int)sp.tensors.size(), last = nt - 1;
   std::vector<const void*> g(nt, nullptr), addend(nt, nullptr);
@@ -459,7 +465,7 @@ int build_backward(cdp_ctx* c, int i, int j, Program* prog, bool first_grad, boo
         w_src = c->ptr(col.off);
         wl = level + 1;
       }
-      w.g = wgrad_prob(c, o, dz, w_src, slot, G, first_grad);
+      w.g = wgrad_prob(c, o, dz, w_src, slot, slot_f, G, first_grad);
       op_work(c, o, 2, o.is_conv || !first_grad, false, &w);
       if (fuse_update && linear_update_fusable(o)) {
         // this gradient is the N-th of the step: its contraction also takes the SGD step and
@@ -746,11 +752,12 @@ int run_tick(cdp_ctx* c, const float* x_dev, const int32_t* y_dev) {
   for (Visit& v : act) {
     const StageState& ss = c->st[v.j];
     if (v.dir == 0) {
-      if (c->rule == CDP_RULE_V2) v.version = ss.ver;
-      else if (c->rule == CDP_RULE_V1) v.version = (int)std::max<int64_t>(v.t - 1, 0);
-      else v.version = (int)v.t;
+      const bool freshest = c->rule == CDP_RULE_V2 || (c->rule == CDP_RULE_MASK && c->fresh_mask[(size_t)v.i * S + v.j]);
+      if (freshest) v.version = ss.ver;
+      else if (c->rule == CDP_RULE_DP) v.version = (int)v.t;
+      else v.version = (int)std::max<int64_t>(v.t - 1, 0);
     } else {
-      v.version = c->rec[v.i][v.j].version;
+      v.version = c->bwd_fresh ? ss.ver : c->rec[v.i][v.j].version;
     }
     if (ss.ring_ver[v.version & 1] != v.version)
       return fail(c, CDP_ESTATE, v.dir == 0 ? "internal: weight version left the ring before its forward"
@@ -771,7 +778,7 @@ int run_tick(cdp_ctx* c, const float* x_dev, const int32_t* y_dev) {
       bool fuse = ss.cnt == N - 1;
       for (const Visit& o : act)
         if (o.j == v.j && ((o.version ^ (ss.ver + 1)) & 1) == 0) fuse = false;
-      rc = build_backward(c, v.i, v.j, &progs[a], ss.cnt == 0, fuse);
+      rc = build_backward(c, v.i, v.j, v.version, &progs[a], ss.cnt == 0, fuse);
       if (fuse) fused[v.j] = 1;
       ss.cnt++;
     }
@@ -833,7 +840,11 @@ int run_tick(cdp_ctx* c, const float* x_dev, const int32_t* y_dev) {
 int check_args(const cdp_stage_desc* stages, int n_stages, int N, int B, int rule, const cdp_opts* opts, ModelPlan* plan) {
   if (!stages || !opts) return fail(nullptr, CDP_EINVAL, "stages/opts is NULL");
   if (N <= 0 || B <= 0) return fail(nullptr, CDP_EINVAL, "N and micro_batch must be positive");
-  if (rule != CDP_RULE_DP && rule != CDP_RULE_V1 && rule != CDP_RULE_V2) return fail(nullptr, CDP_EINVAL, "unknown update rule");
+  if (rule != CDP_RULE_DP && rule != CDP_RULE_V1 && rule != CDP_RULE_V2 && rule != CDP_RULE_MASK)
+    return fail(nullptr, CDP_EINVAL, "unknown update rule");
+  if ((rule == CDP_RULE_MASK) != (opts->fresh_mask != nullptr))
+    return fail(nullptr, CDP_EINVAL, "fresh_mask is needed by, and only by, CDP_RULE_MASK");
+  if (opts->bwd_fresh && opts->dp_batched) return fail(nullptr, CDP_EINVAL, "bwd_fresh cannot be combined with dp_batched");
   if (rule != CDP_RULE_DP && (2 * n_stages) % N != 0)
     return fail(nullptr, CDP_EINVAL, "the cyclic schedule needs N to divide 2S (uniform delay d = 2S/N)");
   std::string e = build_plan(stages, n_stages, opts, plan);
@@ -859,6 +870,8 @@ int make_ctx(cdp_ctx** out, const cdp_stage_desc* stages, int n_stages, int N, i
     B *= N;
     N = 1;
   }
+  if (rule == CDP_RULE_MASK) c->fresh_mask.assign(opts->fresh_mask, opts->fresh_mask + (size_t)N * n_stages);
+  c->bwd_fresh = opts->bwd_fresh != 0;
   c->S = n_stages; c->N = N; c->B = B; c->rule = rule; c->lr = lr;
   c->d = rule == CDP_RULE_DP ? 0 : 2 * n_stages / N;
   c->dry = force_dry || opts->dry_run != 0;

@@ -49,11 +49,11 @@ class Progress:
                 f.write(line)
 
 
-def run_gpu(cfg, rule, T, p0, xs, ys, lr=None, momentum=0.0, weight_decay=0.0, dp_batched=False):
+def run_gpu(cfg, rule, T, p0, xs, ys, lr=None, momentum=0.0, weight_decay=0.0, dp_batched=False, mask=None, bwd_fresh=False):
     import torch
     assert torch.cuda.is_available(), "GPU tests need a GPU"
     tr = b.Trainer(cfg.stages, cfg.in_shape, cfg.N, cfg.B, cfg.lr if lr is None else lr, rule, cfg.dtype,
-                   momentum=momentum, weight_decay=weight_decay, dp_batched=dp_batched)
+                   momentum=momentum, weight_decay=weight_decay, dp_batched=dp_batched, fresh_mask=mask, bwd_fresh=bwd_fresh)
     tr.set_weights(p0)
     keep = []
     for t in range(T):
@@ -70,18 +70,20 @@ def run_gpu(cfg, rule, T, p0, xs, ys, lr=None, momentum=0.0, weight_decay=0.0, d
     return out
 
 
-def check(cfg, rule, T, seed=0, lr=None, tensor_tol=0.5, capfd=None, momentum=0.0, weight_decay=0.0, dp_batched=False):
+def check(cfg, rule, T, seed=0, lr=None, tensor_tol=0.5, capfd=None, momentum=0.0, weight_decay=0.0, dp_batched=False,
+          mask=None, bwd_fresh=False):
     xs, ys = wl.make_data(cfg, T, seed)
     p0 = wl.init_params(cfg, seed)
     ref = O.train_schedule(cfg, p0, xs, ys, rule, lr=lr, keep_versions=False, progress=Progress(cfg.name, capfd),
-                           momentum=momentum, weight_decay=weight_decay)
-    got = run_gpu(cfg, rule, T, p0, xs, ys, lr=lr, momentum=momentum, weight_decay=weight_decay, dp_batched=dp_batched)
+                           momentum=momentum, weight_decay=weight_decay, mask=mask, bwd_fresh=bwd_fresh)
+    got = run_gpu(cfg, rule, T, p0, xs, ys, lr=lr, momentum=momentum, weight_decay=weight_decay, dp_batched=dp_batched,
+                  mask=mask, bwd_fresh=bwd_fresh)
     f32 = cfg.dtype == wl.F32
     assert got["trace"] == ref.trace
     assert got["live"] == ref.live_inputs
     emu = ref if (f32 or tensor_tol is None) else O.train_schedule(cfg, p0, xs, ys, rule, lr=lr, rnd=OL.round_bf16,
                                                                    keep_versions=False, momentum=momentum,
-                                                                   weight_decay=weight_decay)
+                                                                   weight_decay=weight_decay, mask=mask, bwd_fresh=bwd_fresh)
     worst_t, worst_s, worst_u = 0.0, 0.0, 0.0
     for j in range(cfg.S):
         worst_t = max(worst_t, O.max_rel_err(got["weights"][j], ref.params[j]))
@@ -139,6 +141,22 @@ def test_lockstep_batched_dp_matches_dp_oracle(name):
 def test_lockstep_batched_dp_momentum():
     cfg = wl.get_config("mlp_mini")
     check(cfg, wl.RULE_DP, 4, momentum=0.9, weight_decay=5e-4, dp_batched=True)
+
+
+@pytest.mark.parametrize("name", ["mlp_mini", "mlp_odd", "resnet18_mini_f32", "resnet50_mini_f32", "cfg2_mini", "resnet18_mini"])
+def test_rules_between_v1_and_v2(name):
+    """A per-(micro-batch, stage) mask of v2 / v1 choices (Sec. 3.2, "Update rules")."""
+    cfg = wl.get_config(name)
+    m = np.random.default_rng(7).integers(0, 2, (cfg.N, cfg.S))
+    check(cfg, wl.RULE_MASK, cfg.steps, mask=m)
+
+
+@pytest.mark.parametrize("name", ["mlp_mini", "mlp_odd", "resnet18_mini_f32", "resnet50_mini_f32", "cfg5_mini"])
+def test_backward_with_freshest_parameters(name):
+    """The backward reads the version that is freshest at its tick (the forward's plain weights
+    still rebuild the pre-affine activation of folded conv+affine layers)."""
+    cfg = wl.get_config(name)
+    check(cfg, wl.RULE_V2, cfg.steps, bwd_fresh=True)
 
 
 def test_single_microbatch_and_zero_lr():

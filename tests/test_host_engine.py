@@ -75,6 +75,30 @@ def test_lockstep_batched_dp_keeps_the_dp_timeline(name):
         b.Trainer(cfg.stages, cfg.in_shape, cfg.N, cfg.B, cfg.lr, wl.RULE_V2, cfg.dtype, dry_run=True, dp_batched=True)
 
 
+@pytest.mark.parametrize("name", ["mlp_mini", "mlp_odd", "cfg3", "cfg5"])
+def test_mask_rule_and_bwd_fresh_trace_equals_oracle(name):
+    import numpy as np
+    cfg = wl.get_config(name)
+    T = 3
+    m = np.random.default_rng(3).integers(0, 2, (cfg.N, cfg.S))
+    for kw in (dict(rule=wl.RULE_MASK, fresh_mask=m), dict(rule=wl.RULE_V2, bwd_fresh=True),
+               dict(rule=wl.RULE_MASK, fresh_mask=m, bwd_fresh=True)):
+        rule = kw.pop("rule")
+        tr = b.Trainer(cfg.stages, cfg.in_shape, cfg.N, cfg.B, cfg.lr, rule, cfg.dtype, dry_run=True, **kw)
+        for _ in range(T * 2 * cfg.S):
+            tr.tick_dry(True)
+        tr.drain()
+        r = O.train_schedule(cfg, None, [None] * T, [None] * T, rule, compute=False, mask=kw.get("fresh_mask"),
+                             bwd_fresh=kw.get("bwd_fresh", False))
+        assert tr.trace() == r.trace
+        assert tr.live_counts() == r.live_inputs
+        tr.close()
+    with pytest.raises(b.CdpError):   # a mask without the mask rule, and the reverse
+        b.Trainer(cfg.stages, cfg.in_shape, cfg.N, cfg.B, cfg.lr, wl.RULE_V2, cfg.dtype, dry_run=True, fresh_mask=m)
+    with pytest.raises(b.CdpError):
+        b.Trainer(cfg.stages, cfg.in_shape, cfg.N, cfg.B, cfg.lr, wl.RULE_MASK, cfg.dtype, dry_run=True)
+
+
 def test_activation_pool_is_constant_and_below_dp():
     """Sec. 4.1: activation memory stays (nearly) constant and about half of DP's."""
     for name in ["cfg2", "cfg5"]:
