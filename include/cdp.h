@@ -185,9 +185,12 @@ int cdp_get_stats(const cdp_ctx* ctx, cdp_stats* out);
  * contraction; bytes with every operand read once and every result written once. */
 typedef struct {
   int64_t launches;
-  double total_ms;   /* sum of per-launch durations */
+  double total_ms;   /* sum of the event-to-event times of the launches */
   double flops;
   double bytes;
+  double empty_pair_ms; /* what an event pair with nothing between reads on this stream (median of 32
+                           pairs taken when recording was enabled): the bracket's own share of every
+                           event-to-event time, to be subtracted per launch                          */
 } cdp_gemm_profile;
 
 /* enable != 0 starts a fresh measurement, 0 stops recording (synchronises). */

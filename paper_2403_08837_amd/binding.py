@@ -52,7 +52,8 @@ class cdp_stats(C.Structure):
 
 
 class cdp_gemm_profile(C.Structure):
-    _fields_ = [("launches", C.c_int64), ("total_ms", C.c_double), ("flops", C.c_double), ("bytes", C.c_double)]
+    _fields_ = [("launches", C.c_int64), ("total_ms", C.c_double), ("flops", C.c_double), ("bytes", C.c_double),
+                ("empty_pair_ms", C.c_double)]
 
 
 class CdpError(RuntimeError):
@@ -221,7 +222,8 @@ def cdp_profile_gemm(ctx, enable: bool) -> None:
 def cdp_get_gemm_profile(ctx) -> dict:
     p = cdp_gemm_profile()
     _check(lib().cdp_get_gemm_profile(ctx, C.byref(p)), ctx)
-    return dict(launches=int(p.launches), total_ms=float(p.total_ms), flops=float(p.flops), bytes=float(p.bytes))
+    return dict(launches=int(p.launches), total_ms=float(p.total_ms), flops=float(p.flops), bytes=float(p.bytes),
+                empty_pair_ms=float(p.empty_pair_ms))
 
 
 def cdp_destroy(ctx) -> None:

@@ -103,6 +103,7 @@ struct cdp_ctx {
   int S = 0, N = 0, B = 0, d = 0, rule = 0;
   std::vector<uint8_t> fresh_mask;  // CDP_RULE_MASK: [micro-batch][stage]
   bool bwd_fresh = false;           // backward reads the freshest version
+  double empty_pair_ms = 0.0;       // event-to-event time of an empty bracket (cdp_profile_gemm)
   int groups = 1;  // lock-step batched DP: the caller's micro-batches run as one batch of groups * (caller's B) rows (then N = 1)
   float lr = 0.f, momentum = 0.f, weight_decay = 0.f;
   bool dry = false;
@@ -1096,6 +1097,22 @@ int cdp_profile_gemm(cdp_ctx* c, int enable) {
   for (auto& r : c->prof) { c->event_pool.push_back(r.a); c->event_pool.push_back(r.b); }
   c->prof.clear();
   c->profiling = enable != 0;
+  if (c->profiling) {
+    // the bracket's own cost: event pairs with nothing between them, median of 32
+    constexpr int PAIRS = 32;
+    hipEvent_t ev[2 * PAIRS];
+    for (int k = 0; k < 2 * PAIRS; ++k) {
+      if (!c->event_pool.empty()) { ev[k] = c->event_pool.back(); c->event_pool.pop_back(); }
+      else HIP_TRY(c, hipEventCreate(&ev[k]));
+    }
+    for (int k = 0; k < 2 * PAIRS; ++k) HIP_TRY(c, hipEventRecord(ev[k], c->stream));
+    HIP_TRY(c, hipStreamSynchronize(c->stream));
+    std::vector<float> gap(PAIRS);
+    for (int k = 0; k < PAIRS; ++k) HIP_TRY(c, hipEventElapsedTime(&gap[k], ev[2 * k], ev[2 * k + 1]));
+    std::sort(gap.begin(), gap.end());
+    c->empty_pair_ms = gap[PAIRS / 2];
+    for (int k = 0; k < 2 * PAIRS; ++k) c->event_pool.push_back(ev[k]);
+  }
   return CDP_OK;
 }
 
@@ -1111,6 +1128,7 @@ int cdp_get_gemm_profile(cdp_ctx* c, cdp_gemm_profile* out) {
     out->flops += r.flops;
     out->bytes += r.bytes;
   }
+  out->empty_pair_ms = c->empty_pair_ms;
   return CDP_OK;
 }
 

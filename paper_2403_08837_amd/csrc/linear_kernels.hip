@@ -220,7 +220,7 @@ __device__ __forceinline__ void skinny_tile(const GemmProb& P, int tile, unsigne
 template <typename T>
 __device__ __forceinline__ void thin_tile(const GemmProb& P, int tile, unsigned char* smem) {
   using E = LT<T>;
-  constexpr int VEC = E::VEC, CH = 8, SLAB = 2 * CH * VEC;  // chunk c of lane (row, g) holds k = 2*VEC*c + VEC*g ...
+  constexpr int VEC = E::VEC, CH = 4, SLAB = 2 * CH * VEC;  // chunk c of lane (row, g) holds k = 2*VEC*c + VEC*g ...
   const int col0 = (tile - P.tile_begin) * 32;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int r31 = lane & 31, g = lane >> 5;
