@@ -66,7 +66,7 @@ __device__ __forceinline__ cv16f cmfma_bf16(uint4 a, uint4 b, cv16f c) {
 // forward / data gradient: 128 x BN tile, waves 2 x 2, reduction slab BK (a divisor of the
 // channel count).  The epilogue goes through LDS so that results, residuals and masks move
 // as 16-byte vectors along the channel dimension.
-template <typename T, int BM, int BN, int BK>
+template <typename T, int BM, int BN, int BK, bool DB>
 __global__ __launch_bounds__(256) void conv_gemm_kernel(const GemmBatch batch) {
   using E = CT<T>;
   constexpr int VEC = E::VEC, LDP = BK + VEC;
@@ -76,10 +76,11 @@ __global__ __launch_bounds__(256) void conv_gemm_kernel(const GemmBatch batch) {
   constexpr int NB = BN * CPR / 256;           // B chunks per thread
   constexpr int WTN = BN / 2, NI = WTN / 32;
   constexpr int SP = WTN + 4;                  // pitch (floats) of a wave's 32-row staging area
-  constexpr int OPER_BYTES = (BM + BN) * LDP * (int)sizeof(T), STAGE_BYTES = 4 * 32 * SP * 4;
-  __shared__ __attribute__((aligned(16))) unsigned char smem[OPER_BYTES > STAGE_BYTES ? OPER_BYTES : STAGE_BYTES];
-  T* As = reinterpret_cast<T*>(smem);
-  T* Bs = As + BM * LDP;
+  // one or two (DB) operand buffers; the epilogue staging reuses the space.
+  // Size: conv_gemm_lds_bytes<T, BM, BN, BK, DB>().
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  constexpr int BUF = (BM + BN) * LDP;  // elements per operand buffer
+  T* const As0 = reinterpret_cast<T*>(smem);
 
   const int tile = (int)blockIdx.x;
   const GemmProb& P = batch.p[cfind_problem(batch, tile)];
@@ -169,16 +170,16 @@ __global__ __launch_bounds__(256) void conv_gemm_kernel(const GemmBatch batch) {
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
-  const int nslab = P.K / BK;
-  fetch(0);
-  for (int it = 0; it < nslab; ++it) {
-    __syncthreads();
+  auto stash = [&](int buf) {  // registers -> operand buffer `buf`
+    T* As = As0 + buf * BUF;
+    T* Bs = As + BM * LDP;
 #pragma unroll
     for (int i = 0; i < NA; ++i) *reinterpret_cast<uint4*>(As + (arow + i * (256 / CPR)) * LDP + akc) = ra[i];
 #pragma unroll
     for (int i = 0; i < NB; ++i) *reinterpret_cast<uint4*>(Bs + (brow + i * (256 / CPR)) * LDP + akc) = rb[i];
-    __syncthreads();
-    if (it + 1 < nslab) fetch((it + 1) * BK);
+  };
+  auto contract = [&](const T* As) {
+    const T* Bs = As + BM * LDP;
     const int kg = (lane >> 5) * E::KPL;
     const T* ap = As + (wm * WTM + (lane & 31)) * LDP + kg;
     const T* bp = Bs + (wn * WTN + (lane & 31)) * LDP + kg;
@@ -205,6 +206,36 @@ __global__ __launch_bounds__(256) void conv_gemm_kernel(const GemmBatch batch) {
 #pragma unroll
           for (int j = 0; j < NI; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[i], b[j], acc[i][j], 0, 0, 0);
       }
+    }
+  };
+  const int nslab = P.K / BK;
+  if constexpr (DB) {
+    // Two operand buffers (small problems, whose k-loop is a chain of latencies): while slab
+    // `it` is contracted out of one buffer the loads of slab it+1 are in flight; they are
+    // written to the other buffer after the contraction and the loads of slab it+2 are
+    // issued.  One barrier per slab.
+    fetch(0);
+    stash(0);
+    if (nslab > 1) fetch(BK);
+    __syncthreads();
+    for (int it = 0; it < nslab; ++it) {
+      contract(As0 + (it & 1) * BUF);
+      if (it + 1 < nslab) {
+        stash((it + 1) & 1);  // last read in iteration it-1, which every wave has left (barrier below)
+        if (it + 2 < nslab) fetch((it + 2) * BK);
+      }
+      __syncthreads();
+    }
+  } else {
+    // One operand buffer (large launches, where more workgroups per CU hide the latency):
+    // the next slab's loads are in flight while the current one is contracted.
+    fetch(0);
+    for (int it = 0; it < nslab; ++it) {
+      __syncthreads();
+      stash(0);
+      __syncthreads();
+      if (it + 1 < nslab) fetch((it + 1) * BK);
+      contract(As0);
     }
   }
 
@@ -597,12 +628,27 @@ bool conv_fast_eligible(const GemmProb& p, int dtype) {
   return false;
 }
 
+template <typename T, int BM, int BN, int BK, bool DB>
+constexpr int conv_gemm_lds_bytes() {
+  constexpr int oper = (DB ? 2 : 1) * (BM + BN) * (BK + 16 / (int)sizeof(T)) * (int)sizeof(T);
+  constexpr int stage = 4 * 32 * (BN / 2 + 4) * 4;
+  return oper > stage ? oper : stage;
+}
+
+template <typename T, int BM, int BN, int BK, bool DB>
+static hipError_t launch_conv_gemm_inst(const GemmBatch& b, dim3 grid, hipStream_t stream) {
+  constexpr int lds = conv_gemm_lds_bytes<T, BM, BN, BK, DB>();
+  static_assert(lds <= 64 * 1024, "stays within the default dynamic LDS limit");
+  hipLaunchKernelGGL((conv_gemm_kernel<T, BM, BN, BK, DB>), grid, dim3(256), lds, stream, b);
+  return hipGetLastError();
+}
+
 template <typename T, int BK>
-static void launch_conv_gemm_typed(const GemmBatch& b, int bm, int bn, dim3 grid, hipStream_t stream) {
-  if (bm == 128 && bn == 128) hipLaunchKernelGGL((conv_gemm_kernel<T, 128, 128, BK>), grid, dim3(256), 0, stream, b);
-  else if (bm == 128) hipLaunchKernelGGL((conv_gemm_kernel<T, 128, 64, BK>), grid, dim3(256), 0, stream, b);
-  else if (bn == 128) hipLaunchKernelGGL((conv_gemm_kernel<T, 64, 128, BK>), grid, dim3(256), 0, stream, b);
-  else hipLaunchKernelGGL((conv_gemm_kernel<T, 64, 64, BK>), grid, dim3(256), 0, stream, b);
+static hipError_t launch_conv_gemm_typed(const GemmBatch& b, int bm, int bn, dim3 grid, hipStream_t stream) {
+  if (bm == 128 && bn == 128) return launch_conv_gemm_inst<T, 128, 128, BK, false>(b, grid, stream);
+  if (bm == 128) return launch_conv_gemm_inst<T, 128, 64, BK, false>(b, grid, stream);
+  if (bn == 128) return launch_conv_gemm_inst<T, 64, 128, BK, true>(b, grid, stream);
+  return launch_conv_gemm_inst<T, 64, 64, BK, true>(b, grid, stream);
 }
 
 // Tile shape for the forward / data-gradient problems of one launch: the largest of
@@ -648,14 +694,10 @@ hipError_t launch_conv_gemm(GemmBatch& b, int dtype, int bm, int bn, hipStream_t
   }
   b.total_tiles = total;
   dim3 grid(total);
-  if (dtype == DT_BF16) {
-    if (deep) launch_conv_gemm_typed<uint16_t, 64>(b, bm, bn, grid, stream);
-    else launch_conv_gemm_typed<uint16_t, 32>(b, bm, bn, grid, stream);
-  } else {
-    if (deep) launch_conv_gemm_typed<float, 32>(b, bm, bn, grid, stream);
-    else launch_conv_gemm_typed<float, 16>(b, bm, bn, grid, stream);
-  }
-  return hipGetLastError();
+  if (dtype == DT_BF16) return deep ? launch_conv_gemm_typed<uint16_t, 64>(b, bm, bn, grid, stream)
+                                    : launch_conv_gemm_typed<uint16_t, 32>(b, bm, bn, grid, stream);
+  return deep ? launch_conv_gemm_typed<float, 32>(b, bm, bn, grid, stream)
+              : launch_conv_gemm_typed<float, 16>(b, bm, bn, grid, stream);
 }
 
 hipError_t launch_conv_wgrad(GemmBatch& b, int dtype, bool wide, hipStream_t stream) {
