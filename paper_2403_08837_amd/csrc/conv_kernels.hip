@@ -312,7 +312,7 @@ __global__ __launch_bounds__(256) void conv_gemm_kernel(const GemmBatch batch) {
 // stores: out = partial sums f32 [splits][Cout][taps*Cin], aux3 = partial column sums of dy
 // f32 [splits][Cout] or NULL.  wgrad_reduce_kernel folds the partials into the accumulators
 // (device-wide atomics on a small hot array are an order of magnitude slower than this).
-constexpr int WG_MAX_SLABS = 16;  // slabs per workgroup (bounds the LDS position table)
+constexpr int WG_MAX_SLABS = 16;  // slabs per chunk of a workgroup's range (size of the LDS position table)
 template <typename T> struct WgSlab { static constexpr int MB = sizeof(T) == 2 ? 64 : 32; };  // positions per slab
 static inline int wg_slab(int dtype) { return dtype == DT_BF16 ? 64 : 32; }
 
@@ -351,27 +351,6 @@ __global__ __launch_bounds__(256) void conv_wgrad_kernel(const GemmBatch batch) 
   const int nslab = max(0, s1 - s0);  // an empty range still writes its (zero) partial tile
   const int m_begin = s0 * MB, m_count = max(0, min(Mpos, s1 * MB) - m_begin);
 
-  // position table: element offset of x[b][oh*s-p][ow*s-p][0] and the packed (ih0, iw0)
-  for (int q = tid; q < nslab * MB; q += 256) {
-    int base = 0, hw = (int)0x80008000u;  // (ih0, iw0) = (-32768, -32768): every tap out of range
-    if (q < m_count) {
-      const int m = m_begin + q;
-      if (gather) {
-        const int b = m / (g.OH * g.OW);
-        const int rem = m - b * (g.OH * g.OW);
-        const int oh = rem / g.OW, ow = rem - oh * g.OW;
-        const int ih0 = oh * g.stride - g.pad, iw0 = ow * g.stride - g.pad;
-        base = ((b * g.H + ih0) * g.W + iw0) * g.C;
-        hw = (int)(((unsigned)(ih0 & 0xffff) << 16) | (unsigned)(iw0 & 0xffff));
-      } else {
-        base = m * P.ldb;
-        hw = 0;
-      }
-    }
-    pos_base[q] = base;
-    pos_hw[q] = hw;
-  }
-
   // this thread's chunks: dy columns (o) and x columns (tap, c) are fixed, rows advance
   constexpr int DCH = TO / VEC, XCH = TC / VEC;  // chunks per staged row
   constexpr int ND = MB * DCH / 256, NX = MB * XCH / 256;
@@ -395,10 +374,11 @@ __global__ __launch_bounds__(256) void conv_wgrad_kernel(const GemmBatch batch) 
   const bool dcol_ok = o0 + d_c < Cout;  // Cout is a multiple of VEC on this path
 
   uint4 rd[ND], rx[NX];
-  auto fetch = [&](int s) {  // s = slab index relative to s0; positions s*MB .. s*MB+MB-1 of the table
+  int chunk_q0 = 0;  // first position (relative to m_begin) of the chunk the table describes
+  auto fetch = [&](int s) {  // s = slab index inside the chunk; positions s*MB .. s*MB+MB-1 of the table
 #pragma unroll
     for (int i = 0; i < ND; ++i) {
-      const int q = s * MB + d_m + i * (256 / DCH);
+      const int q = chunk_q0 + s * MB + d_m + i * (256 / DCH);
       rd[i] = (dcol_ok && q < m_count) ? *reinterpret_cast<const uint4*>(Dp + (int64_t)(m_begin + q) * P.lda + o0 + d_c)
                                        : make_uint4(0, 0, 0, 0);
     }
@@ -422,9 +402,35 @@ __global__ __launch_bounds__(256) void conv_wgrad_kernel(const GemmBatch batch) 
   float bsum = 0.f;
   const bool do_beta = (tc == 0) && P.aux3 != nullptr && tid < TO;
 
+  // The range is walked in chunks of at most WG_MAX_SLABS slabs; per chunk the positions are
+  // decoded once into the LDS table.
+  for (int cs = 0; cs < nslab; cs += WG_MAX_SLABS) {
+  const int cn = min(WG_MAX_SLABS, nslab - cs);
+  chunk_q0 = cs * MB;
+  __syncthreads();  // the previous chunk's table and operand tiles are consumed
+  // position table: element offset of x[b][oh*s-p][ow*s-p][0] and the packed (ih0, iw0)
+  for (int q = tid; q < cn * MB; q += 256) {
+    int base = 0, hw = (int)0x80008000u;  // (ih0, iw0) = (-32768, -32768): every tap out of range
+    if (chunk_q0 + q < m_count) {
+      const int m = m_begin + chunk_q0 + q;
+      if (gather) {
+        const int b = m / (g.OH * g.OW);
+        const int rem = m - b * (g.OH * g.OW);
+        const int oh = rem / g.OW, ow = rem - oh * g.OW;
+        const int ih0 = oh * g.stride - g.pad, iw0 = ow * g.stride - g.pad;
+        base = ((b * g.H + ih0) * g.W + iw0) * g.C;
+        hw = (int)(((unsigned)(ih0 & 0xffff) << 16) | (unsigned)(iw0 & 0xffff));
+      } else {
+        base = m * P.ldb;
+        hw = 0;
+      }
+    }
+    pos_base[q] = base;
+    pos_hw[q] = hw;
+  }
   __syncthreads();  // position table complete
-  if (nslab > 0) fetch(0);
-  for (int s = 0; s < nslab; ++s) {
+  fetch(0);
+  for (int s = 0; s < cn; ++s) {
     if (s > 0) __syncthreads();
 #pragma unroll
     for (int i = 0; i < ND; ++i) {
@@ -443,7 +449,7 @@ __global__ __launch_bounds__(256) void conv_wgrad_kernel(const GemmBatch batch) 
       dst[1] = c.h[1];
     }
     __syncthreads();
-    if (s + 1 < nslab) fetch(s + 1);
+    if (s + 1 < cn) fetch(s + 1);
     const int gq = lane >> 5, l31 = lane & 31;
     if constexpr (sizeof(T) == 2) {
 #pragma unroll
@@ -474,6 +480,7 @@ __global__ __launch_bounds__(256) void conv_wgrad_kernel(const GemmBatch batch) 
     }
     if (do_beta)
       for (int m = 0; m < MB; ++m) bsum += E::to_f32(Ds[m * PD + tid]);
+  }
   }
 
   // epilogue: acc rows = o, cols = (tap, c); plain stores into this range's partial buffer
@@ -602,6 +609,8 @@ hipError_t launch_wgrad_reduce(WReduceBatch& b, int dtype, hipStream_t stream) {
 }
 
 int conv_wgrad_splits(const GemmProb& p, int dtype, int wanted) {
+  // at least one range per WG_MAX_SLABS slabs: longer ranges measured slower (fewer workgroups) even
+  // though they write fewer partial sums
   const int nslab = (p.K + wg_slab(dtype) - 1) / wg_slab(dtype);
   const int min_splits = (nslab + WG_MAX_SLABS - 1) / WG_MAX_SLABS;
   return std::max(1, std::min(nslab, std::max(wanted, min_splits)));
