@@ -679,29 +679,54 @@ int refresh_slot(cdp_ctx* c, int j, int slot, bool apply, bool linear_done = fal
   float* master = c->fptr(ss.master);
   float* G = c->fptr(ss.G);
   float* V = ss.V >= 0 ? c->fptr(ss.V) : nullptr;
+  // two launches per stage: every vector parameter (the folded weights use the updated gamma),
+  // then every weight matrix
+  VecUpdateBatch vb;
+  vb.n = 0;
+  RepackBatch rb;
+  rb.n = 0;
+  auto flush_vec = [&]() -> int {
+    if (vb.n) {
+      HIP_TRY(c, launch_update_vec_batch(vb, sgd, c->stream));
+      c->stats.kernel_launches++;
+      vb.n = 0;
+    }
+    return CDP_OK;
+  };
+  auto flush_mat = [&]() -> int {
+    if (rb.n) {
+      HIP_TRY(c, launch_repack_batch(rb, c->plan.dtype, c->stream));
+      c->stats.kernel_launches++;
+      rb.n = 0;
+    }
+    return CDP_OK;
+  };
+  auto add_vec = [&](int64_t off, int64_t copy_off, int n) -> int {
+    if (vb.n == VEC_UPDATE_MAX) { int rc = flush_vec(); if (rc) return rc; }
+    vb.v[vb.n++] = VecUpdate{master + off, G + off, V ? V + off : nullptr, reinterpret_cast<float*>(sl + copy_off), n};
+    return CDP_OK;
+  };
   for (const Op& o : sp.ops) {
     if (o.kind != OPK_GEMM) continue;
     if (linear_done && linear_update_fusable(o)) continue;  // updated by its weight-gradient kernel
-    // vector parameters first: the folded weights use the updated gamma
-    if (o.g_off >= 0) {
-      HIP_TRY(c, launch_update_vec(master + o.g_off, G + o.g_off, V ? V + o.g_off : nullptr, reinterpret_cast<float*>(sl + o.gamma_c), o.Cout, sgd, c->stream));
-      c->stats.kernel_launches++;
-    }
-    if (o.b_off >= 0) {
-      HIP_TRY(c, launch_update_vec(master + o.b_off, G + o.b_off, V ? V + o.b_off : nullptr, reinterpret_cast<float*>(sl + o.bias_c), o.Cout, sgd, c->stream));
-      c->stats.kernel_launches++;
-    }
-    RepackArgs a;
+    if (o.g_off >= 0) { int rc = add_vec(o.g_off, o.gamma_c, o.Cout); if (rc) return rc; }
+    if (o.b_off >= 0) { int rc = add_vec(o.b_off, o.bias_c, o.Cout); if (rc) return rc; }
+  }
+  { int rc = flush_vec(); if (rc) return rc; }
+  for (const Op& o : sp.ops) {
+    if (o.kind != OPK_GEMM) continue;
+    if (linear_done && linear_update_fusable(o)) continue;
+    if (rb.n == REPACK_MAX) { int rc = flush_mat(); if (rc) return rc; }
+    RepackArgs& a = rb.a[rb.n++];
     a.master = master + o.w_off; a.G = G + o.w_off; a.V = V ? V + o.w_off : nullptr;
     a.gamma = o.has_gamma ? reinterpret_cast<const float*>(sl + o.gamma_c) : nullptr;
     a.wf = sl + o.wf; a.wt = sl + o.wt; a.wp = o.has_gamma ? sl + o.wp : nullptr;
     a.O = o.Cout; a.T = o.KH * o.KW; a.C = o.Cin; a.sgd = sgd;
     a.ldf = o.kpad ? o.kpad : a.T * a.C;
-    a.zero_g = o.is_conv ? 1 : 0;  // conv accumulators take atomic adds and must start at zero
-    HIP_TRY(c, launch_repack(a, c->plan.dtype, c->stream));
-    c->stats.kernel_launches++;
+    a.zero_g = o.is_conv ? 1 : 0;  // conv accumulators are added into and must start at zero
+    a.tile_begin = 0;
   }
-  return CDP_OK;
+  return flush_mat();
 }
 
 int inflight(const cdp_ctx* c) {

@@ -148,21 +148,29 @@ hipError_t launch_colsum_batch(const ColsumBatch& b, int dtype, hipStream_t stre
 
 
 // Vector parameters (bias, gamma, beta): SGD step ; G = 0 ; copy = master.  V may be NULL.
-hipError_t launch_update_vec(float* master, float* G, float* V, float* copy_f32, int64_t n, SgdParams sgd,
-                             hipStream_t stream);
+// All vectors of a stage go in one launch.
+struct VecUpdate { float* master; float* G; float* V; float* copy; int64_t n; };
+constexpr int VEC_UPDATE_MAX = 24;
+struct VecUpdateBatch { int n; VecUpdate v[VEC_UPDATE_MAX]; };
+hipError_t launch_update_vec_batch(const VecUpdateBatch& b, SgdParams sgd, hipStream_t stream);
 
 // Matrix parameters W[O][T][C] (Linear: T = 1):  SGD step on master (V = velocity or NULL),
 // G = 0 if zero_g, then write the compute copies of the new version:
 //   wf[o][t][c] = T(gamma[o]*master)   forward layout
 //   wt[c][t][o] = T(gamma[o]*master)   data-gradient layout
 //   wp[o][t][c] = T(master)            plain copy (only when gamma != NULL)
+// gamma points at the already updated fp32 copy in the new ring slot.  All matrices of a stage
+// go in one launch.
 struct RepackArgs {
   float* master; float* G; float* V; const float* gamma;
   void* wf; void* wt; void* wp;
   int O, T, C; SgdParams sgd; int zero_g;
-  int ldf;  // row length of wf (T*C, or the zero-padded length of an im2col layer)
+  int ldf;         // row length of wf (T*C, or the zero-padded length of an im2col layer)
+  int tile_begin;  // first workgroup of this matrix in the launch (set by launch_repack_batch)
 };
-hipError_t launch_repack(const RepackArgs& a, int dtype, hipStream_t stream);
+constexpr int REPACK_MAX = 12;
+struct RepackBatch { int n; RepackArgs a[REPACK_MAX]; };
+hipError_t launch_repack_batch(RepackBatch& b, int dtype, hipStream_t stream);
 
 // Explicit im2col for layers whose channel count is below one 16-byte chunk (the RGB stem):
 // col[(b,oh,ow)][k] = x[b][oh*s-p+kh][ow*s-p+kw][c], k = (kh*KW+kw)*C+c, zero for k >= KH*KW*C.

@@ -134,31 +134,47 @@ hipError_t launch_colsum_batch(const ColsumBatch& b, int dtype, hipStream_t stre
 }
 
 // ---------------------------------------------------------------------------------
-__global__ void update_vec_kernel(float* __restrict__ master, float* __restrict__ G, float* __restrict__ V,
-                                  float* __restrict__ copy, int64_t n, SgdParams sgd) {
-  for (int64_t i = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x) {
-    float w = master[i];
+// Vector parameters of a stage (bias, gamma, beta of all its layers) in one launch: block y
+// picks the vector, blocks x stride over its elements.
+__global__ void update_vec_kernel(const VecUpdateBatch b, SgdParams sgd) {
+  const VecUpdate& u = b.v[blockIdx.y];
+  for (int64_t i = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; i < u.n; i += (int64_t)gridDim.x * blockDim.x) {
+    float w = u.master[i];
     if (sgd.apply) {
-      w = sgd_step(w, G[i], V ? V + i : nullptr, sgd);
-      master[i] = w;
+      w = sgd_step(w, u.G[i], u.V ? u.V + i : nullptr, sgd);
+      u.master[i] = w;
     }
-    G[i] = 0.f;
-    copy[i] = w;
+    u.G[i] = 0.f;
+    u.copy[i] = w;
   }
 }
-hipError_t launch_update_vec(float* master, float* G, float* V, float* copy_f32, int64_t n, SgdParams sgd, hipStream_t stream) {
-  if (n <= 0) return hipSuccess;
-  hipLaunchKernelGGL(update_vec_kernel, dim3(blocks_for(n, 256, 1024)), dim3(256), 0, stream, master, G, V, copy_f32, n, sgd);
+hipError_t launch_update_vec_batch(const VecUpdateBatch& b, SgdParams sgd, hipStream_t stream) {
+  if (b.n <= 0) return hipSuccess;
+  if (b.n > VEC_UPDATE_MAX) return hipErrorInvalidValue;
+  int64_t longest = 1;
+  for (int i = 0; i < b.n; ++i) {
+    if (b.v[i].n <= 0 || !b.v[i].master || !b.v[i].G || !b.v[i].copy) return hipErrorInvalidValue;
+    longest = b.v[i].n > longest ? b.v[i].n : longest;
+  }
+  hipLaunchKernelGGL(update_vec_kernel, dim3(blocks_for(longest, 256, 1024), b.n), dim3(256), 0, stream, b, sgd);
   return hipGetLastError();
 }
 
 // W[O][T][C]: tile 64(o) x 64(c) for one tap t.  Reads G and master coalesced along c,
 // writes master / wf / wp coalesced along c and wt coalesced along o via an LDS transpose.
+// The tiles of all matrices of a stage form one flat list.
 template <typename T>
-__global__ __launch_bounds__(256) void repack_kernel(const RepackArgs a) {
+__global__ __launch_bounds__(256) void repack_kernel(const RepackBatch batch) {
   __shared__ float tile[64][65];
-  const int t = blockIdx.z;
-  const int o0 = blockIdx.y * 64, c0 = blockIdx.x * 64;
+  int pi = 0;
+  for (int q = 1; q < batch.n; ++q)
+    if ((int)blockIdx.x >= batch.a[q].tile_begin) pi = q;
+  const RepackArgs& a = batch.a[pi];
+  int local = (int)blockIdx.x - a.tile_begin;
+  const int tiles_c = (a.C + 63) / 64, tiles_o = (a.O + 63) / 64;
+  const int c0 = (local % tiles_c) * 64;
+  local /= tiles_c;
+  const int o0 = (local % tiles_o) * 64, t = local / tiles_o;
   const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
   T* wf = static_cast<T*>(a.wf);
   T* wt = static_cast<T*>(a.wt);
@@ -189,10 +205,18 @@ __global__ __launch_bounds__(256) void repack_kernel(const RepackArgs a) {
   }
 }
 
-hipError_t launch_repack(const RepackArgs& a, int dtype, hipStream_t stream) {
-  if (a.O <= 0 || a.C <= 0 || a.T <= 0) return hipErrorInvalidValue;
-  dim3 grid((a.C + 63) / 64, (a.O + 63) / 64, a.T);
-  CDP_DISPATCH(dtype, hipLaunchKernelGGL((repack_kernel<T>), grid, dim3(256), 0, stream, a));
+hipError_t launch_repack_batch(RepackBatch& b, int dtype, hipStream_t stream) {
+  if (b.n <= 0) return hipSuccess;
+  if (b.n > REPACK_MAX) return hipErrorInvalidValue;
+  int64_t total = 0;
+  for (int i = 0; i < b.n; ++i) {
+    RepackArgs& a = b.a[i];
+    if (a.O <= 0 || a.C <= 0 || a.T <= 0) return hipErrorInvalidValue;
+    a.tile_begin = (int)total;
+    total += (int64_t)((a.C + 63) / 64) * ((a.O + 63) / 64) * a.T;
+    if (total >= (1ll << 31)) return hipErrorInvalidValue;
+  }
+  CDP_DISPATCH(dtype, hipLaunchKernelGGL((repack_kernel<T>), dim3((unsigned)total), dim3(256), 0, stream, b));
   return hipGetLastError();
 }
 
