@@ -375,10 +375,49 @@ __global__ void maxpool_bwd_vec_kernel(const T* __restrict__ x, const T* __restr
   }
 }
 
+// 16 bytes of channels per thread (C a multiple of the chunk).
+template <typename T>
+__global__ void maxpool_fwd_vec_kernel(const T* __restrict__ x, T* __restrict__ y, int B, int H, int W, int C, int OH, int OW,
+                                       int k, int s, int p) {
+  constexpr int VEC = 16 / sizeof(T);
+  union Ch { uint4 v; T e[VEC]; };
+  const int cpp = C / VEC;
+  const int64_t n = (int64_t)B * OH * OW * cpp;
+  for (int64_t i = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x) {
+    const int c = (int)(i % cpp) * VEC;
+    int64_t q = i / cpp;
+    const int ow = (int)(q % OW); q /= OW;
+    const int oh = (int)(q % OH);
+    const int b = (int)(q / OH);
+    float best[VEC];
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) best[e] = -INFINITY;
+    for (int kh = 0; kh < k; ++kh)
+      for (int kw = 0; kw < k; ++kw) {
+        const int ih = oh * s - p + kh, iw = ow * s - p + kw;
+        if (ih < 0 || iw < 0 || ih >= H || iw >= W) continue;
+        Ch xc;
+        xc.v = *reinterpret_cast<const uint4*>(x + (((int64_t)b * H + ih) * W + iw) * C + c);
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) best[e] = fmaxf(best[e], ld_f32<T>(xc.e, e));
+      }
+    Ch out;
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) st_f32<T>(out.e, e, best[e]);
+    *reinterpret_cast<uint4*>(y + i * VEC) = out.v;
+  }
+}
+
 hipError_t launch_maxpool_fwd(const void* x, void* y, int B, int H, int W, int C, int k, int s, int p, int dtype,
                               hipStream_t stream) {
   int OH = (H + 2 * p - k) / s + 1, OW = (W + 2 * p - k) / s + 1;
   int64_t n = (int64_t)B * OH * OW * C;
+  const int vec = dtype == DT_BF16 ? 8 : 4;
+  if (C % vec == 0) {
+    CDP_DISPATCH(dtype, hipLaunchKernelGGL((maxpool_fwd_vec_kernel<T>), dim3(blocks_for(n / vec, 256, 1 << 20)), dim3(256), 0, stream,
+                                           static_cast<const T*>(x), static_cast<T*>(y), B, H, W, C, OH, OW, k, s, p));
+    return hipGetLastError();
+  }
   CDP_DISPATCH(dtype, hipLaunchKernelGGL((maxpool_fwd_kernel<T>), dim3(blocks_for(n, 256, 65536)), dim3(256), 0, stream,
                                          static_cast<const T*>(x), static_cast<T*>(y), B, H, W, C, OH, OW, k, s, p));
   return hipGetLastError();
