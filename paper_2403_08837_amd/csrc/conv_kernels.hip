@@ -609,10 +609,13 @@ hipError_t launch_wgrad_reduce(WReduceBatch& b, int dtype, hipStream_t stream) {
 }
 
 int conv_wgrad_splits(const GemmProb& p, int dtype, int wanted) {
-  // at least one range per WG_MAX_SLABS slabs: longer ranges measured slower (fewer workgroups) even
-  // though they write fewer partial sums
+  // Short ranges (one per WG_MAX_SLABS slabs) measured faster than few long ones as long as the
+  // launch is short of workgroups, even though they write more partial sums; a layer with
+  // enough tiles of its own does not need them.
   const int nslab = (p.K + wg_slab(dtype) - 1) / wg_slab(dtype);
-  const int min_splits = (nslab + WG_MAX_SLABS - 1) / WG_MAX_SLABS;
+  const int to = p.M >= 128 ? 128 : 64;
+  const int tiles = ((p.M + to - 1) / to) * ((p.N + 127) / 128);
+  const int min_splits = std::min((nslab + WG_MAX_SLABS - 1) / WG_MAX_SLABS, (1024 + tiles - 1) / tiles);
   return std::max(1, std::min(nslab, std::max(wanted, min_splits)));
 }
 

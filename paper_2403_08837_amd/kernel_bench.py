@@ -1,0 +1,102 @@
+#!/usr/bin/env python3
+"""Times single contractions through the kernel-level C ABI (cdp_k_gemm / cdp_k_conv) on the
+shapes the five workloads are made of, and prints achieved TFLOP/s and GB/s per shape.
+
+  python -m paper_2403_08837_amd.kernel_bench            # bf16, all shapes
+
+Bytes are algorithmic: every operand read once, the result written once.  A weight gradient
+through cdp_k_conv is three launches (clear, partial sums, fold); inside the engine the clear
+does not exist and the other two are shared by all layers of a tick level.
+"""
+from __future__ import annotations
+
+import argparse
+
+import torch
+
+from . import binding as b
+
+HBM_PEAK, MFMA_PEAK = 8000.0, 2500.0   # GB/s, TFLOP/s (bf16 dense)
+
+
+def _time(call, reps):
+    for _ in range(3):
+        call()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(reps):
+        call()
+    e1.record()
+    torch.cuda.synchronize()
+    return e0.elapsed_time(e1) * 1e3 / reps   # microseconds per call
+
+
+def linear(M, N, K, shape, reps=200):
+    A = torch.randn(M, K, device="cuda").bfloat16()
+    W = torch.randn(N, K, device="cuda").bfloat16()
+    C = torch.empty(M, N, device="cuda")
+    us = _time(lambda: b.cdp_k_gemm(1, shape, 1, 1, A.data_ptr(), W.data_ptr(), C.data_ptr(), M, N, K, K, K), reps)
+    flops, byts = 2.0 * M * N * K, 2.0 * (M * K + N * K) + 4.0 * M * N
+    return us, flops / us / 1e6, byts / us / 1e3
+
+
+def conv(which, B, H, W, Cin, Cout, ks, st, pad, reps=20):
+    Ho, Wo = (H + 2 * pad - ks) // st + 1, (W + 2 * pad - ks) // st + 1
+    x = torch.randn(B, H, W, Cin, device="cuda").bfloat16()
+    w = torch.randn(Cout, ks, ks, Cin, device="cuda").bfloat16()
+    wt = w.permute(3, 1, 2, 0).contiguous()
+    dy = torch.randn(B, Ho, Wo, Cout, device="cuda").bfloat16()
+    y = torch.empty(B, Ho, Wo, Cout, device="cuda", dtype=torch.bfloat16)
+    dx = torch.empty_like(x)
+    dw = torch.empty(Cout, ks, ks, Cin, device="cuda")
+    ws = torch.empty(64 << 20, device="cuda", dtype=torch.float32)
+    if which == 0:
+        call = lambda: b.cdp_k_conv(1, 0, x.data_ptr(), w.data_ptr(), y.data_ptr(), B, H, W, Cin, Cout, ks, st, pad)
+    elif which == 1:
+        call = lambda: b.cdp_k_conv(1, 1, dy.data_ptr(), wt.data_ptr(), dx.data_ptr(), B, H, W, Cin, Cout, ks, st, pad)
+    else:
+        call = lambda: b.cdp_k_conv(1, 2, dy.data_ptr(), x.data_ptr(), dw.data_ptr(), B, H, W, Cin, Cout, ks, st, pad,
+                                    ws.data_ptr(), ws.numel() * 4)
+    us = _time(call, reps)
+    flops = 2.0 * B * Ho * Wo * Cout * ks * ks * Cin
+    byts = 2.0 * (B * H * W * Cin + B * Ho * Wo * Cout) + (4 if which == 2 else 2) * Cout * ks * ks * Cin
+    return us, flops / us / 1e6, byts / us / 1e3
+
+
+LINEAR_SHAPES = [  # (label, M, N, K, tile_shape)
+    ("cfg2 layer  32x1024x1024 (thin tiles)", 32, 1024, 1024, 5),
+    ("cfg2 stem   32x1024x3072 (thin tiles)", 32, 1024, 3072, 5),
+    ("cfg5 layer  64x4096x4096 (64x128 tiles)", 64, 4096, 4096, 4),
+    ("8 x cfg5    64x32768x4096 (64x128 tiles)", 64, 32768, 4096, 4),
+]
+CONV_SHAPES = [  # ResNet-50 layers of one micro-batch of 32, and two large compute-bound shapes
+    ("s1 1x1 256->64  56x56", 32, 56, 56, 256, 64, 1, 1, 0), ("s1 3x3 64->64   56x56", 32, 56, 56, 64, 64, 3, 1, 1),
+    ("s1 1x1 64->256  56x56", 32, 56, 56, 64, 256, 1, 1, 0), ("s2 3x3 128->128 28x28", 32, 28, 28, 128, 128, 3, 1, 1),
+    ("s3 1x1 1024->256 14x14", 32, 14, 14, 1024, 256, 1, 1, 0), ("s3 3x3 256->256 14x14", 32, 14, 14, 256, 256, 3, 1, 1),
+    ("s4 3x3 512->512 7x7", 32, 7, 7, 512, 512, 3, 1, 1), ("s4 1x1 512->2048 7x7", 32, 7, 7, 512, 2048, 1, 1, 0),
+    ("large 1x1 2048->2048, 25088 rows", 32, 28, 28, 2048, 2048, 1, 1, 0),
+    ("large 3x3 512->512, 25088 rows", 32, 28, 28, 512, 512, 3, 1, 1),
+]
+
+
+def main():
+    argparse.ArgumentParser(description=__doc__).parse_args()
+    if not torch.cuda.is_available():
+        raise SystemExit("kernel_bench needs a GPU")
+    torch.zeros(1).cuda()
+    print("# Linear contractions (cdp_k_gemm, bf16): us, TFLOP/s, GB/s, fraction of the HBM peak of %.0f GB/s" % HBM_PEAK)
+    for label, M, N, K, shape in LINEAR_SHAPES:
+        us, tf, gb = linear(M, N, K, shape)
+        print("%-42s %8.1f us %7.1f TFLOP/s %7.0f GB/s  hbm %.2f" % (label, us, tf, gb, gb / HBM_PEAK), flush=True)
+    print("# Convolution passes (cdp_k_conv, bf16): us, TFLOP/s (fraction of %.0f), GB/s (fraction of %.0f)" % (MFMA_PEAK, HBM_PEAK))
+    for s in CONV_SHAPES:
+        parts = []
+        for which, name in ((0, "fwd"), (1, "dgrad"), (2, "wgrad")):
+            us, tf, gb = conv(which, *s[1:])
+            parts.append("%s %7.1f us %6.1f TF/s (%.2f) %5.0f GB/s (%.2f)" % (name, us, tf, tf / MFMA_PEAK, gb, gb / HBM_PEAK))
+        print("%-34s %s" % (s[0], " | ".join(parts)), flush=True)
+
+
+if __name__ == "__main__":
+    main()
