@@ -335,6 +335,7 @@ int build_forward(cdp_ctx* c, int i, int64_t t, int j, int version, const float*
   r.t.assign(sp.tensors.size(), Block());
   const char* slot = static_cast<const char*>(c->ptr(c->st[j].slot[version & 1]));
   size_t level = 0;
+  bool first_reads_f32 = false;
   auto at = [&](size_t l) -> std::vector<Item>& { if (prog->size() <= l) prog->resize(l + 1); return (*prog)[l]; };
   if (j == 0) {
     if (!pool_alloc(c, tensor_bytes(c, sp.tensors[0]), &r.t[0])) return fail(c, CDP_ENOMEM, "activation pool exhausted");
@@ -345,7 +346,14 @@ int build_forward(cdp_ctx* c, int i, int64_t t, int j, int version, const float*
     it.p3 = static_cast<int32_t*>(c->ptr(c->labels_off)) + (int64_t)i * c->B;
     it.p4 = c->fptr(c->loss_off) + ((t % LOSS_LOG_STEPS) * c->N + i) * c->groups;
     it.i[0] = c->B; it.i[1] = c->groups; it.n0 = c->in_features;
-    at(level++).push_back(it);
+    at(level).push_back(it);
+    // A first Linear layer that runs in the streaming kernel reads the caller's fp32 rows itself
+    // (rounding them as the staging kernel does), so it shares the level with the staging; the
+    // staged copy is what the backward pass and any other consumer read.
+    const Op& o0 = sp.ops.front();
+    first_reads_f32 = o0.kind == OPK_GEMM && !o0.is_conv && o0.kpad == 0 && o0.in == 0 && c->B <= 128 &&
+                      reinterpret_cast<uintptr_t>(it.p0) % 16 == 0;
+    if (!first_reads_f32) ++level;
   } else {
     r.t[0] = c->carry[i];
     c->carry[i] = Block();
@@ -366,6 +374,10 @@ int build_forward(cdp_ctx* c, int i, int64_t t, int j, int version, const float*
         a_src = c->ptr(col.off);
       }
       it.g = fwd_prob(c, o, a_src, c->ptr(r.t[o.out].off), slot, o.res >= 0 ? c->ptr(r.t[o.res].off) : nullptr);
+      if (first_reads_f32 && &o == &sp.ops.front()) {
+        it.g.A = x_dev + (int64_t)i * c->B * c->in_features;
+        it.g.flags |= GF_A_F32;
+      }
       op_work(c, o, 0, false, false, &it);
     } else if (o.kind == OPK_MAXPOOL) {
       it.kind = IT_MAXPOOL_F;

@@ -55,7 +55,11 @@ struct GemmProb {
   ConvGeom g;        // geometry of the (single) gathered operand, if any
 };
 
-enum : int { GF_RELU = 1, GF_OUT_F32 = 2, GF_ACCUM = 4, GF_ATOMIC = 8, GF_THIN = 16 /* set by launch_linear_tick */ };
+enum : int {
+  GF_RELU = 1, GF_OUT_F32 = 2, GF_ACCUM = 4, GF_ATOMIC = 8,
+  GF_THIN = 16,  // set by launch_linear_tick
+  GF_A_F32 = 32  // linear_tick_kernel, forward: A holds fp32 values, rounded to the compute type on load
+};
 
 // SGD step on fp32 master parameters from the summed micro-batch gradients G (Eq. (CDP)),
 // optionally with momentum and weight decay (the optimiser of Sec. 5 "Hyperparameters"):

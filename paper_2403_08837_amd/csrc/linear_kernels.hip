@@ -72,6 +72,20 @@ __device__ __forceinline__ v16f_t mfma_bf16(uint4 a, uint4 b, v16f_t c) {
 
 }  // namespace
 
+// One 16-byte chunk of operand elements read from an fp32 matrix and rounded to T (RNE), the
+// same conversion the staging kernel applies: a first Linear layer can read the caller's
+// fp32 micro-batch directly.
+template <typename T>
+__device__ __forceinline__ uint4 load_chunk_f32(const float* src) {
+  if constexpr (sizeof(T) == 4) {
+    return *reinterpret_cast<const uint4*>(src);
+  } else {
+    const float4 lo = *reinterpret_cast<const float4*>(src), hi = *reinterpret_cast<const float4*>(src + 4);
+    return make_uint4((uint32_t)f2bf(lo.x) | ((uint32_t)f2bf(lo.y) << 16), (uint32_t)f2bf(lo.z) | ((uint32_t)f2bf(lo.w) << 16),
+                      (uint32_t)f2bf(hi.x) | ((uint32_t)f2bf(hi.y) << 16), (uint32_t)f2bf(hi.z) | ((uint32_t)f2bf(hi.w) << 16));
+  }
+}
+
 // Epilogue of one output element of a forward (bias, residual, ReLU) or data-gradient
 // (addend, accumulate, ReLU mask) contraction.
 template <typename T>
@@ -130,6 +144,8 @@ __device__ __forceinline__ void skinny_tile(const GemmProb& P, int tile, unsigne
   // rows are 16-byte aligned and K is a whole number of chunks: one vector load per chunk;
   // otherwise (e.g. a 10-class head) chunks are gathered element by element
   const bool vec = (P.K % VEC) == 0 && (P.lda % VEC) == 0 && (P.ldb % VEC) == 0;
+  const bool a_f32 = (P.flags & GF_A_F32) != 0;  // A holds fp32 values (same leading dimension in elements)
+  const float* __restrict__ Apf = static_cast<const float*>(P.A);
   auto gather = [&](const T* src, int k) {
     Chunk16<T> c;
     c.v = make_uint4(0, 0, 0, 0);
@@ -138,18 +154,33 @@ __device__ __forceinline__ void skinny_tile(const GemmProb& P, int tile, unsigne
       if (k + e < P.K) c.e[e] = src[e];
     return c.v;
   };
+  auto gather_f32 = [&](const float* src, int k) {
+    Chunk16<T> c;
+    c.v = make_uint4(0, 0, 0, 0);
+#pragma unroll
+    for (int e = 0; e < VEC; ++e)
+      if (k + e < P.K) c.e[e] = E::from_f32(src[e]);
+    return c.v;
+  };
   auto fetch = [&](uint4* qa, uint4* qb, int k0) {
     const bool kin = k0 + ck < P.K;
     if (vec) {
 #pragma unroll
-      for (int i = 0; i < NA; ++i)
-        qa[i] = (kin && offA[i] >= 0) ? *reinterpret_cast<const uint4*>(Ap + offA[i] + k0) : make_uint4(0, 0, 0, 0);
+      for (int i = 0; i < NA; ++i) {
+        if (!(kin && offA[i] >= 0)) qa[i] = make_uint4(0, 0, 0, 0);
+        else if (a_f32) qa[i] = load_chunk_f32<T>(Apf + offA[i] + k0);
+        else qa[i] = *reinterpret_cast<const uint4*>(Ap + offA[i] + k0);
+      }
 #pragma unroll
       for (int i = 0; i < NB; ++i)
         qb[i] = (kin && offB[i] >= 0) ? *reinterpret_cast<const uint4*>(Bp + offB[i] + k0) : make_uint4(0, 0, 0, 0);
     } else {
 #pragma unroll
-      for (int i = 0; i < NA; ++i) qa[i] = (kin && offA[i] >= 0) ? gather(Ap + offA[i] + k0, k0 + ck) : make_uint4(0, 0, 0, 0);
+      for (int i = 0; i < NA; ++i) {
+        if (!(kin && offA[i] >= 0)) qa[i] = make_uint4(0, 0, 0, 0);
+        else if (a_f32) qa[i] = gather_f32(Apf + offA[i] + k0, k0 + ck);
+        else qa[i] = gather(Ap + offA[i] + k0, k0 + ck);
+      }
 #pragma unroll
       for (int i = 0; i < NB; ++i) qb[i] = (kin && offB[i] >= 0) ? gather(Bp + offB[i] + k0, k0 + ck) : make_uint4(0, 0, 0, 0);
     }
@@ -225,7 +256,10 @@ __device__ __forceinline__ void thin_tile(const GemmProb& P, int tile, unsigned 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int r31 = lane & 31, g = lane >> 5;
   // rows past the end are read from the last valid row: they only reach outputs that are not stored
-  const T* __restrict__ ap = static_cast<const T*>(P.A) + (int64_t)min(r31, P.M - 1) * P.lda + g * VEC;
+  const bool a_f32 = (P.flags & GF_A_F32) != 0;
+  const int64_t a_off = (int64_t)min(r31, P.M - 1) * P.lda + g * VEC;
+  const T* __restrict__ ap = static_cast<const T*>(P.A) + a_off;
+  const float* __restrict__ apf = static_cast<const float*>(P.A) + a_off;
   const T* __restrict__ bp = static_cast<const T*>(P.B) + (int64_t)min(col0 + r31, P.N - 1) * P.ldb + g * VEC;
   const int nslab = (P.K + SLAB - 1) / SLAB;
   const int s0 = (int)(((unsigned)tile * 2654435761u) >> 8) % nslab;
@@ -236,14 +270,15 @@ __device__ __forceinline__ void thin_tile(const GemmProb& P, int tile, unsigned 
     if (k0 + SLAB <= P.K) {
 #pragma unroll
       for (int c = 0; c < CH; ++c) {
-        qa[c] = *reinterpret_cast<const uint4*>(ap + k0 + 2 * c * VEC);
+        qa[c] = a_f32 ? load_chunk_f32<T>(apf + k0 + 2 * c * VEC) : *reinterpret_cast<const uint4*>(ap + k0 + 2 * c * VEC);
         qb[c] = *reinterpret_cast<const uint4*>(bp + k0 + 2 * c * VEC);
       }
     } else {  // last, partial slab: chunks past K are zero in both operands
 #pragma unroll
       for (int c = 0; c < CH; ++c) {
         const bool kin = k0 + (2 * c + g) * VEC < P.K;
-        qa[c] = kin ? *reinterpret_cast<const uint4*>(ap + k0 + 2 * c * VEC) : make_uint4(0, 0, 0, 0);
+        if (!kin) qa[c] = make_uint4(0, 0, 0, 0);
+        else qa[c] = a_f32 ? load_chunk_f32<T>(apf + k0 + 2 * c * VEC) : *reinterpret_cast<const uint4*>(ap + k0 + 2 * c * VEC);
         qb[c] = kin ? *reinterpret_cast<const uint4*>(bp + k0 + 2 * c * VEC) : make_uint4(0, 0, 0, 0);
       }
     }
@@ -599,6 +634,9 @@ hipError_t launch_linear_tick(GemmBatch& b, int dtype, bool wide, bool allow_thi
     } else {
       if (p.a_mode != OP_PLAIN_K || p.b_mode != OP_PLAIN_K) return hipErrorInvalidValue;
       if ((int64_t)p.M * p.lda >= (1ll << 31) || (int64_t)p.N * p.ldb >= (1ll << 31)) return hipErrorInvalidValue;
+      if ((p.flags & GF_A_F32) && (reinterpret_cast<uintptr_t>(p.A) % 16 != 0 || p.lda % 4 != 0) && p.K % vec == 0 &&
+          p.lda % vec == 0 && p.ldb % vec == 0)
+        return hipErrorInvalidValue;  // vector path on an fp32 operand needs 16-byte aligned rows
       const bool chunked = p.K % vec == 0 && p.lda % vec == 0 && p.ldb % vec == 0 &&
                            reinterpret_cast<uintptr_t>(p.A) % 16 == 0 && reinterpret_cast<uintptr_t>(p.B) % 16 == 0;
       if (allow_thin && p.M <= 32 && chunked) {
