@@ -358,7 +358,10 @@ int build_forward(cdp_ctx* c, int i, int64_t t, int j, int version, const float*
     r.t[0] = c->carry[i];
     c->carry[i] = Block();
   }
-  for (const Op& o : sp.ops) {
+  bool ce_fused = false;
+  for (size_t oi = 0; oi < sp.ops.size(); ++oi) {
+    const Op& o = sp.ops[oi];
+    if (o.kind == OPK_CE && ce_fused) continue;  // computed in the epilogue of the classifier's contraction
     if (!pool_alloc(c, tensor_bytes(c, sp.tensors[o.out]), &r.t[o.out])) return fail(c, CDP_ENOMEM, "activation pool exhausted");
     Item it;
     if (o.kind == OPK_GEMM) {
@@ -379,6 +382,21 @@ int build_forward(cdp_ctx* c, int i, int64_t t, int j, int version, const float*
         it.g.flags |= GF_A_F32;
       }
       op_work(c, o, 0, false, false, &it);
+      // A classifier of at most 32 classes on at most 32 rows is a single thin tile of the
+      // streaming kernel, which then applies the loss head in its epilogue: the logits are
+      // never stored, the tile writes dlogits and adds the row losses to their slots.
+      const int vec = 16 / c->plan.elem_bytes;
+      if (o.out_f32 && !o.is_conv && oi + 1 < sp.ops.size() && sp.ops[oi + 1].kind == OPK_CE && sp.ops[oi + 1].in == o.out &&
+          c->B <= 32 && o.Cout <= 32 && o.Cin % vec == 0) {
+        const Op& ce = sp.ops[oi + 1];
+        if (!pool_alloc(c, tensor_bytes(c, sp.tensors[ce.out]), &r.t[ce.out])) return fail(c, CDP_ENOMEM, "activation pool exhausted");
+        it.g.out = c->ptr(r.t[ce.out].off);
+        it.g.flags = (it.g.flags & ~GF_OUT_F32) | GF_CE;
+        it.g.aux2 = static_cast<int32_t*>(c->ptr(c->labels_off)) + (int64_t)i * c->B;
+        it.g.aux3 = c->fptr(c->loss_off) + ((t % LOSS_LOG_STEPS) * c->N + i) * c->groups;
+        it.g.g.H = c->B / c->groups;
+        ce_fused = true;
+      }
     } else if (o.kind == OPK_MAXPOOL) {
       it.kind = IT_MAXPOOL_F;
       it.p0 = c->ptr(r.t[o.in].off); it.p2 = c->ptr(r.t[o.out].off);

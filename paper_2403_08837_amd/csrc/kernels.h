@@ -58,7 +58,9 @@ struct GemmProb {
 enum : int {
   GF_RELU = 1, GF_OUT_F32 = 2, GF_ACCUM = 4, GF_ATOMIC = 8,
   GF_THIN = 16,  // set by launch_linear_tick
-  GF_A_F32 = 32  // linear_tick_kernel, forward: A holds fp32 values, rounded to the compute type on load
+  GF_A_F32 = 32, // linear_tick_kernel, forward: A holds fp32 values, rounded to the compute type on load
+  GF_CE = 64     // linear_tick_kernel, thin forward tile with N <= 32 classes: softmax cross-entropy in the epilogue
+                 // (out = dlogits T[M][N], aux2 = int32 labels, aux3 = loss slots, g.H = rows per loss slot)
 };
 
 // SGD step on fp32 master parameters from the summed micro-batch gradients G (Eq. (CDP)),

@@ -317,12 +317,36 @@ __device__ __forceinline__ void thin_tile(const GemmProb& P, int tile, unsigned 
   __syncthreads();
   const int c = col0 + r31;
   const float bias = (P.epi == EPI_FWD && P.aux0 != nullptr && c < P.N) ? static_cast<const float*>(P.aux0)[c] : 0.f;
+  const bool ce = (P.flags & GF_CE) != 0;
 #pragma unroll
   for (int q = 0; q < 4; ++q) {
     const int v = wave * 4 + q;
     const float val = (red[v * 64 + lane] + red[(16 + v) * 64 + lane]) + (red[(32 + v) * 64 + lane] + red[(48 + v) * 64 + lane]);
     const int r = wave * 8 + g * 4 + q;
-    if (r < P.M && c < P.N) store_result<T>(P, r, c, val, bias);
+    if (!ce) {
+      if (r < P.M && c < P.N) store_result<T>(P, r, c, val, bias);
+      continue;
+    }
+    // Loss head on the logits row this half wavefront holds (one class per lane, N <= 32):
+    // softmax cross-entropy, dlogits = (softmax - onehot) / rows, row loss added to its slot.
+    // out = dlogits T[M][N], aux2 = labels, aux3 = loss slots, g.H = rows per loss slot.
+    const bool cls = c < P.N;
+    const float z = cls ? val + bias : -INFINITY;
+    float m = z;
+#pragma unroll
+    for (int off = 16; off >= 1; off >>= 1) m = fmaxf(m, __shfl_xor(m, off, 64));
+    const float e = cls ? expf(z - m) : 0.f;
+    float sum = e;
+#pragma unroll
+    for (int off = 16; off >= 1; off >>= 1) sum += __shfl_xor(sum, off, 64);
+    const int y = r < P.M ? static_cast<const int32_t*>(P.aux2)[r] : -1;
+    float own = (cls && c == y) ? (m + logf(sum)) - z : 0.f;  // the row's loss sits in the lane of its label
+#pragma unroll
+    for (int off = 16; off >= 1; off >>= 1) own += __shfl_xor(own, off, 64);
+    if (r < P.M) {
+      if (cls) static_cast<T*>(P.out)[(int64_t)r * P.ldo + c] = E::from_f32((e / sum - (c == y ? 1.f : 0.f)) / (float)P.M);
+      if (r31 == 0) atomicAdd(static_cast<float*>(P.aux3) + r / P.g.H, own / (float)P.g.H);
+    }
   }
 }
 
@@ -639,6 +663,9 @@ hipError_t launch_linear_tick(GemmBatch& b, int dtype, bool wide, bool allow_thi
         return hipErrorInvalidValue;  // vector path on an fp32 operand needs 16-byte aligned rows
       const bool chunked = p.K % vec == 0 && p.lda % vec == 0 && p.ldb % vec == 0 &&
                            reinterpret_cast<uintptr_t>(p.A) % 16 == 0 && reinterpret_cast<uintptr_t>(p.B) % 16 == 0;
+      if ((p.flags & GF_CE) && !(allow_thin && p.M <= 32 && chunked && p.N <= 32 && p.epi == EPI_FWD && p.aux2 && p.aux3 &&
+                                 p.g.H > 0 && p.M % p.g.H == 0))
+        return hipErrorInvalidValue;  // the fused loss head exists in the thin tile only
       if (allow_thin && p.M <= 32 && chunked) {
         p.flags |= GF_THIN;
         any_thin = true;
