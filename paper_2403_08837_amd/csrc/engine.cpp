@@ -91,6 +91,7 @@ struct Item {
   int64_t n0 = 0;
   int i[10] = {0};
   double flops = 0, bytes = 0;  // algorithmic work (contractions only)
+  bool done = false;            // already carried by another launch of its level
   bool fused_update = false;    // IT_GEMM weight gradient of a Linear layer that also takes the SGD step (u)
   LinUpdate u;
 };
@@ -586,6 +587,19 @@ int launch_level(cdp_ctx* c, std::vector<Item>& items) {
       GemmBatch batch;
       batch.n = (int)std::min<size_t>(GEMM_MAX_PROBS, sel.size() - k);
       batch.n_upd = 0;
+      batch.copy_tiles = 0;
+      if (key == LC_LINEAR && k == 0) {
+        // a micro-batch that starts in this tick: its staging rides on this launch
+        for (Item& si : items)
+          if (si.kind == IT_STAGE_IN && !si.done && (int64_t)si.i[0] * si.n0 < (1ll << 40)) {
+            batch.sc = StageCopy{static_cast<const float*>(si.p0), static_cast<const int32_t*>(si.p1), si.p2,
+                                 static_cast<int32_t*>(si.p3), static_cast<float*>(si.p4), si.i[1], si.i[0],
+                                 (int64_t)si.i[0] * si.n0};
+            batch.copy_tiles = (int)((batch.sc.n + STAGE_COPY_ELEMS - 1) / STAGE_COPY_ELEMS);
+            si.done = true;
+            break;
+          }
+      }
       for (int q = 0; q < batch.n; ++q) {
         batch.p[q] = sel[k + q]->g;
         batch.p[q].upd = 0;
@@ -659,6 +673,7 @@ int launch_level(cdp_ctx* c, std::vector<Item>& items) {
   for (const Item& it : items) {
     switch (it.kind) {
       case IT_STAGE_IN:
+        if (it.done) continue;
         HIP_TRY(c, launch_stage_input(static_cast<const float*>(it.p0), static_cast<const int32_t*>(it.p1), it.p2,
                                       static_cast<int32_t*>(it.p3), static_cast<float*>(it.p4), it.i[1], it.i[0], it.n0, dt, c->stream));
         break;

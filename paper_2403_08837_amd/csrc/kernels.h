@@ -81,6 +81,17 @@ struct LinUpdate {
   SgdParams sgd;
 };
 
+// Staging of a micro-batch that starts in this tick, carried by the tick's first Linear launch
+// as extra tiles: fp32 -> T conversion of its rows, label copy, zeroing of its loss slots
+// (what launch_stage_input does as a kernel of its own).
+struct StageCopy {
+  const float* x; const int32_t* y;  // caller's rows [rows][per_row] and labels [rows]
+  void* xo; int32_t* yo;             // staged copies
+  float* loss; int n_slots;          // loss slots to clear
+  int rows; int64_t n;               // n = rows * per_row
+};
+constexpr int STAGE_COPY_ELEMS = 8192;  // elements per copy tile
+
 constexpr int GEMM_MAX_PROBS = 24;
 constexpr int LIN_UPD_MAX = 2;
 struct GemmBatch {
@@ -89,8 +100,10 @@ struct GemmBatch {
   int head_tiles;  // linear_tick_kernel: tiles of the forward / data-gradient problems (listed first)
   int upd_tiles;   // linear_tick_kernel: tiles of the weight gradients with a fused SGD step (listed next)
   int n_upd;
+  int copy_tiles;  // linear_tick_kernel: tiles of the staging copy `sc` (listed last), 0 = none
   GemmProb p[GEMM_MAX_PROBS];
   LinUpdate upd[LIN_UPD_MAX];
+  StageCopy sc;
 };
 static_assert(sizeof(GemmBatch) <= 4000, "kernel argument block must stay under 4 KiB");
 

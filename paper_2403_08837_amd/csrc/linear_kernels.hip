@@ -594,6 +594,20 @@ __global__ __launch_bounds__(256) void linear_tick_kernel(const GemmBatch batch)
     tile += batch.head_tiles;
   } else {
     const int first = batch.head_tiles + batch.upd_tiles;
+    const int rest8 = (batch.total_tiles - first + 7) & ~7;
+    if (bid >= head8 + upd8 + rest8) {  // staging copy of the micro-batch that starts in this tick
+      const StageCopy& sc = batch.sc;
+      const int ct = bid - (head8 + upd8 + rest8);
+      if (ct == 0) {
+        for (int i = threadIdx.x; i < sc.n_slots; i += 256) sc.loss[i] = 0.f;
+        for (int i = threadIdx.x; i < sc.rows; i += 256) sc.yo[i] = sc.y[i];
+      }
+      const int64_t lo = (int64_t)ct * STAGE_COPY_ELEMS;
+      const int64_t hi = lo + STAGE_COPY_ELEMS < sc.n ? lo + STAGE_COPY_ELEMS : sc.n;
+      T* __restrict__ xo = static_cast<T*>(sc.xo);
+      for (int64_t i = lo + threadIdx.x; i < hi; i += 256) xo[i] = E::from_f32(sc.x[i]);
+      return;
+    }
     tile = first + xcd_remap(bid - head8 - upd8, batch.total_tiles - first);
     if (tile >= batch.total_tiles) return;
   }
@@ -681,7 +695,11 @@ hipError_t launch_linear_tick(GemmBatch& b, int dtype, bool wide, bool allow_thi
     total += tiles;
   }
   b.total_tiles = total;
-  const dim3 grid(((b.head_tiles + 7) / 8) * 8 + ((b.upd_tiles + 7) / 8) * 8 + ((total - b.head_tiles - b.upd_tiles + 7) / 8) * 8);
+  if (b.copy_tiles < 0 || (b.copy_tiles > 0 && (!b.sc.x || !b.sc.y || !b.sc.xo || !b.sc.yo || !b.sc.loss || b.sc.n <= 0 ||
+                                                b.copy_tiles != (int)((b.sc.n + STAGE_COPY_ELEMS - 1) / STAGE_COPY_ELEMS))))
+    return hipErrorInvalidValue;
+  const dim3 grid(((b.head_tiles + 7) / 8) * 8 + ((b.upd_tiles + 7) / 8) * 8 + ((total - b.head_tiles - b.upd_tiles + 7) / 8) * 8 +
+                  b.copy_tiles);
   if (dtype == DT_BF16) launch_variant<uint16_t>(b, wide, any_thin, grid, stream);
   else launch_variant<float>(b, wide, any_thin, grid, stream);
   return hipGetLastError();
