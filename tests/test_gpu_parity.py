@@ -279,3 +279,63 @@ def test_ring_copy_of_previous_version():
             tr.weights(j, version=0)
         assert e.value.code == b.CDP_ESTATE
     tr.close()
+
+
+@pytest.mark.parametrize("name", ["cfg1", "cfg2_mini"])
+def test_tick_by_tick_and_unaligned_inputs_give_the_same_weights(name):
+    """Three ways to feed the same three steps: cdp_step; cdp_tick with the mini-batch pointer on
+    every tick of its step and NULL during the drain; cdp_step on input rows that are not
+    16-byte aligned (the first layer then reads the staged copy instead of the caller's rows).
+    Tick by tick gives bit-identical weights (the same launches); the unaligned run groups its
+    launches differently and agrees with the oracle and with the first run at the usual tolerance;
+    the logged losses agree to fp32 rounding."""
+    import torch
+    cfg = wl.get_config(name)
+    T = 3
+    xs, ys = wl.make_data(cfg, T)
+    p0 = wl.init_params(cfg)
+    ref = O.train_schedule(cfg, p0, xs, ys, wl.RULE_V2, keep_versions=False)
+
+    def run(mode):
+        tr = b.Trainer(cfg.stages, cfg.in_shape, cfg.N, cfg.B, cfg.lr, wl.RULE_V2, cfg.dtype)
+        tr.set_weights(p0)
+        keep = []
+        for t in range(T):
+            x, y = torch.from_numpy(xs[t]).cuda(), torch.from_numpy(ys[t]).cuda()
+            if mode == "unaligned":
+                big = torch.empty(x.numel() + 1, dtype=torch.float32, device="cuda")
+                big[1:].copy_(x.reshape(-1))
+                x = big[1:].view(x.shape)
+                assert x.data_ptr() % 16 != 0
+            keep.append((x, y))
+            if mode == "tick":
+                for _ in range(2 * cfg.S):
+                    tr.tick(x, y)
+            else:
+                tr.step(x, y)
+        tr.drain()
+        torch.cuda.synchronize()
+        w = [tr.weights(j) for j in range(cfg.S)]
+        losses = np.stack([tr.losses(t) for t in range(T)])
+        trace = tr.trace()
+        tr.close()
+        return w, losses, trace
+
+    base = run("step")
+    assert base[2] == ref.trace
+    tol = 1e-4 if cfg.dtype == wl.F32 else 2e-2
+    for j in range(cfg.S):
+        err = O.stage_rel_err(wl.unflatten_params(base[0][j], cfg.stages[j]), ref.params[j])
+        assert err <= tol, err
+    for mode in ("tick", "unaligned"):
+        got = run(mode)
+        assert got[2] == base[2]
+        assert np.allclose(got[1], base[1], rtol=1e-6, atol=0), mode   # row losses meet in fp32 atomic adds
+        for j in range(cfg.S):
+            if mode == "tick":
+                assert np.array_equal(got[0][j], base[0][j]), (mode, j)   # the same launches in the same order
+            else:
+                # other launch grouping, hence another summation order inside the contractions
+                w = wl.unflatten_params(got[0][j], cfg.stages[j])
+                assert O.stage_rel_err(w, ref.params[j]) <= tol, (mode, j)
+                assert O.stage_rel_err(w, wl.unflatten_params(base[0][j], cfg.stages[j])) <= tol, (mode, j)
