@@ -947,7 +947,9 @@ int make_ctx(cdp_ctx** out, const cdp_stage_desc* stages, int n_stages, int N, i
   c->d = rule == CDP_RULE_DP ? 0 : 2 * n_stages / N;
   c->dry = force_dry || opts->dry_run != 0;
   c->stream = static_cast<hipStream_t>(opts->hip_stream);
-  c->arena = c->dry ? nullptr : static_cast<char*>(opts->arena);
+  // a dry run never touches memory; a non-null stand-in base keeps the address arithmetic of the
+  // launch lists well defined
+  c->arena = c->dry ? reinterpret_cast<char*>(uintptr_t(1) << 30) : static_cast<char*>(opts->arena);
   c->arena_bytes = (int64_t)opts->arena_bytes;
   c->momentum = opts->momentum; c->weight_decay = opts->weight_decay;
   StaticLayout L = static_layout(c->plan, N, B, c->groups, c->momentum != 0.f);
