@@ -35,9 +35,15 @@ ADD = 5       # p = (src2,)   y = tensor[src] + tensor[src2]
 MAXPOOL = 6   # p = (ksize, stride, pad)
 GAP = 7       # p = ()   global average pool NHWC -> [B, C]
 CE_HEAD = 8   # p = (classes,)  mean softmax cross-entropy over the micro-batch
+LAYERNORM = 9   # p = (channels,)  over the channel axis of every position     params: gamma[c], beta[c]
+GELU = 10       # p = ()   x * Phi(x), exact (erf) form
+TOKENS = 12     # p = ()   [H, W, C] -> [1, H*W, C]: the patch grid read as one row of tokens (no data movement)
+ATTENTION = 11  # p = (heads,)  self-attention core on tokens [B, 1, T, 3*D] = (q | k | v) per token,
+                #              each D = heads * dh wide: out[B, 1, T, D] = softmax(q k^T / sqrt(dh)) v per head
 
 KIND_NAMES = {LINEAR: "linear", RELU: "relu", CONV2D: "conv2d", AFFINE: "affine",
-              ADD: "add", MAXPOOL: "maxpool", GAP: "gap", CE_HEAD: "ce_head"}
+              ADD: "add", MAXPOOL: "maxpool", GAP: "gap", CE_HEAD: "ce_head", LAYERNORM: "layernorm",
+              GELU: "gelu", ATTENTION: "attention", TOKENS: "tokens"}
 
 # update rules (must equal enum cdp_rule)
 RULE_DP = 0
@@ -99,7 +105,7 @@ def layer_param_shapes(layer: Layer) -> List[Tuple[int, ...]]:
     if k == CONV2D:
         cin, cout, ks = p[0], p[1], p[2]
         return [(cout, ks, ks, cin)]
-    if k == AFFINE:
+    if k in (AFFINE, LAYERNORM):
         return [(p[0],), (p[0],)]
     return []
 
@@ -112,8 +118,18 @@ def layer_out_shape(layer: Layer, in_shape: Tuple[int, ...],
         n_in = int(np.prod(in_shape))
         assert n_in == p[0], (in_shape, p)
         return (p[1],)
-    if k in (RELU, AFFINE):
+    if k in (RELU, AFFINE, GELU):
         return tuple(in_shape)
+    if k == LAYERNORM:
+        assert in_shape[-1] == p[0], (in_shape, p)
+        return tuple(in_shape)
+    if k == TOKENS:
+        h, w, c = in_shape
+        return (1, h * w, c)
+    if k == ATTENTION:
+        h, w, c = in_shape
+        assert h == 1 and c % (3 * p[0]) == 0, (in_shape, p)
+        return (1, w, c // 3)
     if k == ADD:
         assert tuple(shapes[p[0]]) == tuple(in_shape), (shapes[p[0]], in_shape)
         return tuple(in_shape)
@@ -256,6 +272,33 @@ def _resnet50(classes: int, widths=(64, 128, 256, 512), depths=(3, 4, 6, 3)) -> 
     return stages
 
 
+def _vit(image: int, patch: int, dim: int, heads: int, depth: int, classes: int) -> List[List[Layer]]:
+    """ViT-shaped stages on tokens kept as a [1, T, D] "image": patch embedding (a patch x patch /
+    patch convolution, then the patch grid is read as one row of T tokens), one pre-norm
+    transformer block per stage, mean pooling over the tokens and a linear classifier.  A
+    token-wise linear map is a 1x1 convolution followed by a per-channel affine (scale and bias;
+    the scale is an extra parameter a plain ViT does not have, initialised to 1)."""
+    def block(base: int) -> List[Layer]:
+        ls = [Layer(LAYERNORM, (dim,), src=base)]
+        ls += _conv_affine(dim, 3 * dim, 1, 1, 0) + [Layer(ATTENTION, (heads,))]
+        ls += _conv_affine(dim, dim, 1, 1, 0) + [Layer(ADD, (base,))]
+        mid = base + len(ls)
+        ls += [Layer(LAYERNORM, (dim,))]
+        ls += _conv_affine(dim, 4 * dim, 1, 1, 0) + [Layer(GELU)]
+        ls += _conv_affine(4 * dim, dim, 1, 1, 0) + [Layer(ADD, (mid,))]
+        return ls
+    stages: List[List[Layer]] = []
+    for j in range(depth):
+        st: List[Layer] = []
+        if j == 0:
+            st += _conv_affine(3, dim, patch, patch, 0) + [Layer(TOKENS)]
+        st += block(len(st))
+        if j == depth - 1:
+            st += [Layer(LAYERNORM, (dim,)), Layer(GAP), Layer(LINEAR, (dim, classes)), Layer(CE_HEAD, (classes,))]
+        stages.append(st)
+    return stages
+
+
 def get_config(name: str) -> Config:
     """The five benchmark configurations plus reduced "mini" variants for tests."""
     if name == "cfg1":
@@ -298,6 +341,16 @@ def get_config(name: str) -> Config:
     if name == "resnet50_mini":  # 16 bottleneck stages at 1/8 width, 32x32 images
         return Config("resnet50_mini", _resnet50(20, widths=(8, 16, 32, 64)), (32, 32, 3), 20,
                       N=8, B=2, dtype=BF16, lr=0.05, steps=4, init_gain_last_affine=0.25)
+    if name == "vit_mini":       # 4 transformer-block stages, 16 tokens of width 32, 4 heads
+        return Config("vit_mini", _vit(16, 4, 32, 4, 4, 10), (16, 16, 3), 10, N=4, B=4, dtype=BF16, lr=0.05, steps=5,
+                      init_gain_last_affine=0.25, init_gain_head=0.2)
+    if name == "vit_mini_f32":
+        c = get_config("vit_mini")
+        c.name, c.dtype = "vit_mini_f32", F32
+        return c
+    if name == "vit_b16":        # ViT-B/16-shaped: 196 tokens of width 768, 12 heads, 12 block stages
+        return Config("vit_b16", _vit(224, 16, 768, 12, 12, 1000), (224, 224, 3), 1000, N=8, B=32, dtype=BF16, lr=0.01,
+                      steps=2, init_gain_last_affine=0.25, init_gain_head=0.2, notes="ViT-B/16-shaped")
     if name == "resnet50_mini_f32":
         c = get_config("resnet50_mini")
         c.name, c.dtype = "resnet50_mini_f32", F32
@@ -402,6 +455,9 @@ def init_params(cfg: Config, seed: int = 0) -> List[List[np.ndarray]]:
                 w = random_normal(seed, stream, cout * fan_in) * math.sqrt(2.0 / fan_in)
                 stream += 1
                 plist.append(w.astype(np.float32).reshape(cout, ks, ks, cin))
+            elif layer.kind == LAYERNORM:
+                plist.append(np.ones(layer.p[0], dtype=np.float32))
+                plist.append(np.zeros(layer.p[0], dtype=np.float32))
             elif layer.kind == AFFINE:
                 feeds_add = li + 1 < len(st) and st[li + 1].kind == ADD
                 g = cfg.init_gain_last_affine if feeds_add else 1.0

@@ -130,6 +130,83 @@ def gap_bwd(x_shape, dy: Array) -> Array:
     return np.broadcast_to(dy[:, None, None, :] / (H * Wd), x_shape).copy()
 
 
+LN_EPS = 1e-5
+
+
+def layernorm_fwd(x: Array, gamma: Array, beta: Array) -> Array:
+    """y = (x - mean) / sqrt(var + eps) * gamma + beta over the last axis (biased variance)."""
+    mu = x.mean(axis=-1, keepdims=True)
+    var = ((x - mu) ** 2).mean(axis=-1, keepdims=True)
+    return (x - mu) / np.sqrt(var + LN_EPS) * gamma + beta
+
+
+def layernorm_bwd(x: Array, gamma: Array, dy: Array):
+    """With xh = (x - mean) * rstd and g = dy * gamma:
+    dx = rstd * (g - mean(g) - xh * mean(g * xh)); dgamma = sum dy * xh; dbeta = sum dy."""
+    C = x.shape[-1]
+    mu = x.mean(axis=-1, keepdims=True)
+    var = ((x - mu) ** 2).mean(axis=-1, keepdims=True)
+    rstd = 1.0 / np.sqrt(var + LN_EPS)
+    xh = (x - mu) * rstd
+    g = dy * gamma
+    dx = rstd * (g - g.mean(axis=-1, keepdims=True) - xh * (g * xh).mean(axis=-1, keepdims=True))
+    return dx, (dy * xh).reshape(-1, C).sum(axis=0), dy.reshape(-1, C).sum(axis=0)
+
+
+def _erf(x: Array) -> Array:
+    from scipy.special import erf
+    return erf(x)
+
+
+def gelu_fwd(x: Array) -> Array:
+    """x * Phi(x) with Phi the standard normal CDF."""
+    return 0.5 * x * (1.0 + _erf(x / np.sqrt(2.0)))
+
+
+def gelu_bwd(x: Array, dy: Array) -> Array:
+    """d/dx [x Phi(x)] = Phi(x) + x phi(x)."""
+    return dy * (0.5 * (1.0 + _erf(x / np.sqrt(2.0))) + x * np.exp(-0.5 * x * x) / np.sqrt(2.0 * np.pi))
+
+
+def _split_qkv(qkv: Array, heads: int):
+    Bn, one, T, C3 = qkv.shape
+    D = C3 // 3
+    dh = D // heads
+    q, k, v = (qkv[:, 0, :, i * D:(i + 1) * D].reshape(Bn, T, heads, dh).transpose(0, 2, 1, 3) for i in range(3))
+    return q, k, v, dh   # each [B, heads, T, dh]
+
+
+def attention_fwd(qkv: Array, heads: int, rnd: Callable[[Array], Array] = None):
+    """Per head: P = softmax(q k^T / sqrt(dh)) over the keys, out = P v.  Returns (out, P);
+    P is what the backward pass keeps (rounded like a stored tensor when rnd is given)."""
+    q, k, v, dh = _split_qkv(qkv, heads)
+    s = (q @ k.transpose(0, 1, 3, 2)) / np.sqrt(dh)
+    s = s - s.max(axis=-1, keepdims=True)
+    e = np.exp(s)
+    P = e / e.sum(axis=-1, keepdims=True)
+    if rnd is not None:
+        P = rnd(P)
+    o = P @ v                                             # [B, heads, T, dh]
+    Bn, _, T, _ = o.shape
+    return o.transpose(0, 2, 1, 3).reshape(Bn, 1, T, heads * dh), P
+
+
+def attention_bwd(qkv: Array, P: Array, heads: int, dout: Array, rnd: Callable[[Array], Array] = None) -> Array:
+    """dv = P^T do; dP = do v^T; ds = P * (dP - rowsum(dP * P)) / sqrt(dh); dq = ds k; dk = ds^T q."""
+    q, k, v, dh = _split_qkv(qkv, heads)
+    Bn, _, T, D = dout.shape
+    do = dout[:, 0].reshape(Bn, T, heads, dh).transpose(0, 2, 1, 3)
+    dv = P.transpose(0, 1, 3, 2) @ do
+    dP = do @ v.transpose(0, 1, 3, 2)
+    ds = P * (dP - (dP * P).sum(axis=-1, keepdims=True)) / np.sqrt(dh)
+    if rnd is not None:
+        ds = rnd(ds)
+    dq = ds @ k
+    dk = ds.transpose(0, 1, 3, 2) @ q
+    parts = [t.transpose(0, 2, 1, 3).reshape(Bn, T, D) for t in (dq, dk, dv)]
+    return np.concatenate(parts, axis=-1)[:, None, :, :]
+
+
 def ce_fwd(logits: Array, labels: Array):
     """loss = mean_b [ logsumexp(z_b) - z_b[y_b] ];  dz = (softmax(z) - onehot(y)) / B."""
     Bn = logits.shape[0]
@@ -163,7 +240,7 @@ def materialized(stage: Sequence[wl.Layer]) -> List[bool]:
     m = [True] * (len(stage) + 1)
     for k, layer in enumerate(stage):
         nxt = stage[k + 1] if k + 1 < len(stage) else None
-        if nxt is not None and nxt.src < 0 and nxt.kind in (wl.RELU, wl.AFFINE, wl.ADD, wl.CE_HEAD):
+        if nxt is not None and nxt.src < 0 and nxt.kind in (wl.RELU, wl.AFFINE, wl.ADD, wl.CE_HEAD, wl.TOKENS):
             m[k + 1] = False
     return m
 
@@ -196,6 +273,14 @@ def stage_forward(stage: Sequence[wl.Layer], params: Sequence[Array], x: Array,
             y, a = maxpool_fwd(src, p[0], p[1], p[2])
         elif kind == wl.GAP:
             y = gap_fwd(src)
+        elif kind == wl.LAYERNORM:
+            y = layernorm_fwd(src, lp[k][0], lp[k][1])   # fp32 parameters on the device path as well
+        elif kind == wl.GELU:
+            y = gelu_fwd(src)
+        elif kind == wl.TOKENS:
+            y = src.reshape(src.shape[0], 1, src.shape[1] * src.shape[2], src.shape[3])
+        elif kind == wl.ATTENTION:
+            y, a = attention_fwd(src, p[0], None if rnd is identity else rnd)
         elif kind == wl.CE_HEAD:
             assert labels is not None and k == len(stage) - 1
             loss, a = ce_fwd(src, labels)
@@ -257,6 +342,15 @@ def stage_backward(stage: Sequence[wl.Layer], params: Sequence[Array], saved, dy
             dx = maxpool_bwd(src.shape, aux[k], p[0], p[1], p[2], g)
         elif kind == wl.GAP:
             dx = gap_bwd(src.shape, g)
+        elif kind == wl.LAYERNORM:
+            dx, dg, dbeta = layernorm_bwd(src, lp[k][0], g)
+            grads[k] = [dg, dbeta]
+        elif kind == wl.GELU:
+            dx = gelu_bwd(src, g)
+        elif kind == wl.TOKENS:
+            dx = g.reshape(src.shape)
+        elif kind == wl.ATTENTION:
+            dx = attention_bwd(src, aux[k], p[0], g, None if rnd is identity else rnd)
         else:
             raise ValueError(kind)
         acc(si, dx)

@@ -209,6 +209,19 @@ def torch_forward(stages, params, x, y):
                 out = F.max_pool2d(src, layer.p[0], layer.p[1], layer.p[2])
             elif layer.kind == wl.GAP:
                 out = src.mean(dim=(2, 3))
+            elif layer.kind == wl.LAYERNORM:      # channels are dim 1 in NCHW
+                out = F.layer_norm(src.permute(0, 2, 3, 1), (layer.p[0],), plist[k], plist[k + 1], eps=1e-5).permute(0, 3, 1, 2); k += 2
+            elif layer.kind == wl.GELU:
+                out = F.gelu(src)
+            elif layer.kind == wl.TOKENS:
+                out = src.reshape(src.shape[0], src.shape[1], 1, src.shape[2] * src.shape[3])
+            elif layer.kind == wl.ATTENTION:
+                Bn, C3, _, T = src.shape
+                heads, D = layer.p[0], C3 // 3
+                tok = src[:, :, 0, :].permute(0, 2, 1)                       # [B, T, 3D]
+                q, kk, v = (tok[:, :, i * D:(i + 1) * D].reshape(Bn, T, heads, D // heads).transpose(1, 2) for i in range(3))
+                o = F.scaled_dot_product_attention(q, kk, v)                  # [B, heads, T, dh]
+                out = o.transpose(1, 2).reshape(Bn, T, D).permute(0, 2, 1)[:, :, None, :]
             elif layer.kind == wl.CE_HEAD:
                 out = F.cross_entropy(src, y, reduction="mean")
             tensors.append(out)
@@ -225,7 +238,7 @@ def to_torch_x(x):
     return t.permute(0, 3, 1, 2) if t.dim() == 4 else t
 
 
-@pytest.mark.parametrize("name", ["mlp_odd", "resnet18_mini", "resnet50_mini"])
+@pytest.mark.parametrize("name", ["mlp_odd", "resnet18_mini", "resnet50_mini", "vit_mini"])
 def test_whole_network_gradient_matches_torch_autograd(name):
     cfg = wl.get_config(name)
     params = wl.init_params(cfg, seed=3)
@@ -243,3 +256,64 @@ def test_whole_network_gradient_matches_torch_autograd(name):
         for g, t in zip(gs, ts):
             ref = t.grad.numpy()
             assert np.abs(g - ref).max() <= 1e-10 * max(1e-3, np.abs(ref).max())
+
+
+# --- transformer layers -----------------------------------------------------------
+def test_layernorm_closed_forms_and_fd():
+    x = _rand((3, 1, 5, 12), 1) * 2.0 + 0.7
+    g, bta = 1.0 + 0.3 * _rand((12,), 2), 0.2 * _rand((12,), 3)
+    y = L.layernorm_fwd(x, np.ones(12), np.zeros(12))
+    assert np.abs(y.mean(axis=-1)).max() < 1e-12                       # zero mean per position
+    assert np.abs((y ** 2).mean(axis=-1) - 1.0).max() < 1e-4           # unit variance up to eps
+    ref = torch.nn.functional.layer_norm(torch.tensor(x), (12,), torch.tensor(g), torch.tensor(bta), eps=1e-5).numpy()
+    assert np.abs(L.layernorm_fwd(x, g, bta) - ref).max() < 1e-12
+    w = _rand(x.shape, 4)
+    dx, dg, db = L.layernorm_bwd(x, g, w)
+    _fd_check(lambda: float((L.layernorm_fwd(x, g, bta) * w).sum()), x, dx)
+    _fd_check(lambda: float((L.layernorm_fwd(x, g, bta) * w).sum()), g, dg)
+    _fd_check(lambda: float((L.layernorm_fwd(x, g, bta) * w).sum()), bta, db)
+    assert np.abs(dx.sum(axis=-1)).max() < 1e-10                       # shifts of a position's input do not matter
+
+
+def test_gelu_closed_forms_and_fd():
+    assert L.gelu_fwd(np.zeros(1))[0] == 0.0
+    assert abs(L.gelu_bwd(np.zeros(1), np.ones(1))[0] - 0.5) < 1e-15
+    x = _rand((4, 7), 5) * 2.0
+    assert np.abs(L.gelu_fwd(x) - torch.nn.functional.gelu(torch.tensor(x)).numpy()).max() < 1e-12
+    assert np.abs(L.gelu_fwd(np.array([20.0, -20.0])) - np.array([20.0, 0.0])).max() < 1e-12
+    w = _rand(x.shape, 6)
+    _fd_check(lambda: float((L.gelu_fwd(x) * w).sum()), x, L.gelu_bwd(x, w))
+
+
+def test_attention_definition_library_and_fd():
+    Bn, T, heads, dh = 2, 5, 3, 4
+    D = heads * dh
+    qkv = _rand((Bn, 1, T, 3 * D), 7)
+    out, P = L.attention_fwd(qkv, heads)
+    assert np.abs(P.sum(axis=-1) - 1.0).max() < 1e-12 and (P > 0).all()
+    # brute force from the definition, one (sample, head, query) at a time
+    for b in range(Bn):
+        for h in range(heads):
+            q = qkv[b, 0, :, h * dh:(h + 1) * dh]
+            k = qkv[b, 0, :, D + h * dh:D + (h + 1) * dh]
+            v = qkv[b, 0, :, 2 * D + h * dh:2 * D + (h + 1) * dh]
+            for t in range(T):
+                sc = np.array([q[t] @ k[u] for u in range(T)]) / math.sqrt(dh)
+                p = np.exp(sc - sc.max()); p /= p.sum()
+                assert np.abs(sum(p[u] * v[u] for u in range(T)) - out[b, 0, t, h * dh:(h + 1) * dh]).max() < 1e-12
+    # identical keys: uniform attention, the output is the mean value
+    same = qkv.copy()
+    same[:, :, :, D:2 * D] = same[:, :, :1, D:2 * D]
+    o2, P2 = L.attention_fwd(same, heads)
+    assert np.abs(P2 - 1.0 / T).max() < 1e-12
+    assert np.abs(o2 - same[:, :, :, 2 * D:].mean(axis=2, keepdims=True)).max() < 1e-12
+    w = _rand(out.shape, 8)
+    dqkv = L.attention_bwd(qkv, P, heads, w)
+    _fd_check(lambda: float((L.attention_fwd(qkv, heads)[0] * w).sum()), qkv, dqkv)
+
+
+def test_fd_transformer_block_stage():
+    cfg = wl.get_config("vit_mini")
+    _stage_fd(cfg.stages[1], (1, 16, 32), seed=3)
+    _stage_fd(cfg.stages[0], (16, 16, 3), seed=4)
+    _stage_fd(cfg.stages[3], (1, 16, 32), labels=np.array([1, 0, 7]), seed=5)

@@ -31,11 +31,11 @@ def _close(a, b, tol=1e-10):
     return O.max_rel_err(a, b) <= tol
 
 
-@pytest.mark.parametrize("name", ["mlp_mini", "mlp_odd", "resnet18_mini"])
+@pytest.mark.parametrize("name", ["mlp_mini", "mlp_odd", "resnet18_mini", "vit_mini"])
 @pytest.mark.parametrize("rule", RULES)
 def test_equation_oracle_equals_timeline_oracle(name, rule):
     """Eq. (CDP) with the closed-form selector == tick-by-tick execution with the ring."""
-    cfg, p0, xs, ys = _setup(name, 4 if name != "resnet18_mini" else 3)
+    cfg, p0, xs, ys = _setup(name, 4 if name in ("mlp_mini", "mlp_odd") else 3)
     a = O.train_equation(cfg, p0, xs, ys, rule)
     b = O.train_schedule(cfg, p0, xs, ys, rule)
     for j in range(cfg.S):
@@ -45,7 +45,7 @@ def test_equation_oracle_equals_timeline_oracle(name, rule):
     assert np.abs(a.losses - b.losses).max() < 1e-12
 
 
-@pytest.mark.parametrize("name", ["mlp_mini", "resnet18_mini"])
+@pytest.mark.parametrize("name", ["mlp_mini", "resnet18_mini", "vit_mini"])
 def test_first_step_is_textbook_minibatch_sgd_under_every_rule(name):
     """theta_{-1} := theta_0, so theta_1 = theta_0 - lr * grad of the mean loss over all
     N*B samples (Eq. (DP)) whatever the rule; the gradient comes from torch autograd."""
