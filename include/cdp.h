@@ -60,13 +60,21 @@ typedef enum {
   CDP_ADD = 5,     /* p = {src2}  y = tensor[src] + tensor[src2]                       */
   CDP_MAXPOOL = 6, /* p = {k, stride, pad}                                             */
   CDP_GAP = 7,     /* p = {}      global average pool [B,H,W,C] -> [B,C]               */
-  CDP_CE_HEAD = 8  /* p = {classes} mean softmax cross-entropy of the micro-batch      */
+  CDP_CE_HEAD = 8, /* p = {classes} mean softmax cross-entropy of the micro-batch      */
+  /* ViT-shaped stages (the homogeneous stages of Sec. 5 "Memory"); tokens are kept as [B,1,T,D]: */
+  CDP_LAYERNORM = 9,  /* p = {channels}  over the channel axis     params gamma[c], beta[c] */
+  CDP_GELU = 10,      /* p = {}          x * Phi(x), exact form                             */
+  CDP_ATTENTION = 11, /* p = {heads}     [B,1,T,3D] = (q|k|v) per token -> [B,1,T,D]:
+                                         softmax(q k^T / sqrt(D/heads)) v per head          */
+  CDP_TOKENS = 12     /* p = {}          [B,H,W,C] -> [B,1,H*W,C], no data movement; directly
+                                         after CONV2D [AFFINE]                              */
 } cdp_layer_kind;
 
 /* One layer of a stage.  Tensors of a stage are numbered: 0 = stage input, k+1 =
  * output of layer k.  src = tensor read by the layer, -1 = output of the previous
  * layer.  Supported sequences (fused into one kernel each):
- *   LINEAR [RELU] | CONV2D [AFFINE] [ADD] [RELU] | MAXPOOL | GAP | LINEAR CE_HEAD.
+ *   LINEAR [RELU] | CONV2D [AFFINE] [TOKENS] [ADD] [RELU] | MAXPOOL | GAP | LINEAR CE_HEAD |
+ *   LAYERNORM | GELU | ATTENTION.
  * CE_HEAD must be the last layer of the last stage and only there. */
 typedef struct {
   int32_t kind;

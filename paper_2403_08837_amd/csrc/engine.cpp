@@ -81,13 +81,15 @@ struct StageState {
   int ring_ver[2] = {0, 0};
 };
 
-enum ItemKind { IT_GEMM, IT_COLSUM, IT_WREDUCE, IT_IM2COL, IT_STAGE_IN, IT_CE, IT_MAXPOOL_F, IT_MAXPOOL_B, IT_GAP_F, IT_GAP_B };
+enum ItemKind { IT_GEMM, IT_COLSUM, IT_WREDUCE, IT_IM2COL, IT_STAGE_IN, IT_CE, IT_MAXPOOL_F, IT_MAXPOOL_B, IT_GAP_F, IT_GAP_B,
+                IT_LN_F, IT_LN_B, IT_GELU_F, IT_GELU_B, IT_ATTN_F, IT_ATTN_B };
 struct Item {
   int kind;
   GemmProb g;
   ColsumProb c;
   WReduceProb r;
   const void* p0 = nullptr; const void* p1 = nullptr; void* p2 = nullptr; void* p3 = nullptr; void* p4 = nullptr;
+  const void* p5 = nullptr; void* p6 = nullptr;
   int64_t n0 = 0;
   int i[10] = {0};
   double flops = 0, bytes = 0;  // algorithmic work (contractions only)
@@ -406,6 +408,23 @@ int build_forward(cdp_ctx* c, int i, int64_t t, int j, int version, const float*
       it.kind = IT_GAP_F;
       it.p0 = c->ptr(r.t[o.in].off); it.p2 = c->ptr(r.t[o.out].off);
       it.i[0] = c->B; it.i[1] = o.Hin * o.Win; it.i[2] = o.Cin;
+    } else if (o.kind == OPK_LN) {
+      it.kind = IT_LN_F;
+      it.p0 = c->ptr(r.t[o.in].off); it.p2 = c->ptr(r.t[o.out].off);
+      it.p1 = slot + o.gamma_c; it.p5 = slot + o.bias_c;
+      it.i[0] = c->B * o.Hin * o.Win; it.i[1] = o.Cin;
+    } else if (o.kind == OPK_GELU) {
+      it.kind = IT_GELU_F;
+      it.p0 = c->ptr(r.t[o.in].off); it.p2 = c->ptr(r.t[o.out].off);
+      it.n0 = (int64_t)c->B * o.Hin * o.Win * o.Cin;
+    } else if (o.kind == OPK_ATTN) {
+      // scores of all (sample, head) pairs in fp32: tick workspace
+      if (!pool_alloc(c, tensor_bytes(c, sp.tensors[o.aux]), &r.t[o.aux])) return fail(c, CDP_ENOMEM, "activation pool exhausted");
+      Block ws;
+      if (!scratch_alloc(c, (int64_t)c->B * o.heads * o.Win * o.Win * 4, &ws)) return fail(c, CDP_ENOMEM, "tick workspace exhausted");
+      it.kind = IT_ATTN_F;
+      it.p0 = c->ptr(r.t[o.in].off); it.p2 = c->ptr(r.t[o.out].off); it.p3 = c->ptr(r.t[o.aux].off); it.p4 = c->ptr(ws.off);
+      it.i[0] = c->B; it.i[1] = o.Win; it.i[2] = o.Cout; it.i[3] = o.heads;
     } else {  // OPK_CE
       it.kind = IT_CE;
       it.p0 = c->ptr(r.t[o.in].off);
@@ -538,6 +557,37 @@ int build_backward(cdp_ctx* c, int i, int j, int version, Program* prog, bool fi
         b.c.src = dz; b.c.out = G + o.b_off; b.c.rows = c->B * o.Hout * o.Wout; b.c.cols = o.Cout; b.c.ld = o.Cout;
         at(wl).push_back(b);
       }
+    } else if (o.kind == OPK_LN) {
+      // d gamma / d beta are needed even when the input gradient is not; the input may also be
+      // the residual operand of a later layer, whose gradient is added here
+      if (accumulate) return fail(c, CDP_EINVAL, "layernorm input with an earlier gradient is not supported");
+      Block tmp;
+      if (!need_dx) {
+        if (!scratch_alloc(c, tensor_bytes(c, tin), &tmp)) return fail(c, CDP_ENOMEM, "tick workspace exhausted");
+        dx = c->ptr(tmp.off);
+      }
+      Item it; it.kind = IT_LN_B;
+      it.p0 = xin; it.p1 = dz; it.p2 = dx; it.p5 = need_dx ? addend[o.in] : nullptr;
+      it.p3 = const_cast<char*>(slot + o.gamma_c); it.p4 = G + o.g_off; it.p6 = G + o.b_off;
+      it.i[0] = c->B * o.Hin * o.Win; it.i[1] = o.Cin;
+      at(level).push_back(it);
+    } else if (need_dx && (o.kind == OPK_GELU || o.kind == OPK_ATTN)) {
+      if (accumulate || addend[o.in]) return fail(c, CDP_EINVAL, "gelu / attention input with another use is not supported");
+      Item it;
+      it.p0 = xin; it.p1 = dz; it.p2 = dx;
+      if (o.kind == OPK_GELU) {
+        it.kind = IT_GELU_B;
+        it.n0 = (int64_t)c->B * o.Hin * o.Win * o.Cin;
+      } else {
+        const int64_t tt = (int64_t)c->B * o.heads * o.Win * o.Win;
+        Block w1, w2;
+        if (!scratch_alloc(c, tt * 4, &w1) || !scratch_alloc(c, tt * c->plan.elem_bytes, &w2))
+          return fail(c, CDP_ENOMEM, "tick workspace exhausted");
+        it.kind = IT_ATTN_B;
+        it.p5 = c->ptr(r.t[o.aux].off); it.p3 = c->ptr(w1.off); it.p4 = c->ptr(w2.off);
+        it.i[0] = c->B; it.i[1] = o.Win; it.i[2] = o.Cout; it.i[3] = o.heads;
+      }
+      at(level).push_back(it);
     } else if (need_dx) {
       if (accumulate) return fail(c, CDP_EINVAL, "pooling input with several consumers is not supported");
       Item it;
@@ -695,6 +745,30 @@ int launch_level(cdp_ctx* c, std::vector<Item>& items) {
       case IT_GAP_F:
         HIP_TRY(c, launch_gap_fwd(it.p0, it.p2, it.i[0], it.i[1], it.i[2], dt, c->stream));
         break;
+      case IT_LN_F:
+        HIP_TRY(c, launch_layernorm_fwd(it.p0, static_cast<const float*>(it.p1), static_cast<const float*>(it.p5), it.p2, it.i[0],
+                                        it.i[1], dt, c->stream));
+        break;
+      case IT_LN_B:
+        HIP_TRY(c, launch_layernorm_bwd(it.p0, it.p1, it.p5, static_cast<const float*>(it.p3), it.p2, static_cast<float*>(it.p4),
+                                        static_cast<float*>(it.p6), it.i[0], it.i[1], dt, c->stream));
+        break;
+      case IT_GELU_F:
+        HIP_TRY(c, launch_gelu_fwd(it.p0, it.p2, it.n0, dt, c->stream));
+        break;
+      case IT_GELU_B:
+        HIP_TRY(c, launch_gelu_bwd(it.p0, it.p1, it.p2, it.n0, dt, c->stream));
+        break;
+      case IT_ATTN_F:
+        HIP_TRY(c, launch_attention_fwd(it.p0, it.p3, it.p2, static_cast<float*>(it.p4), it.i[0], it.i[1], it.i[2], it.i[3], dt,
+                                        c->stream));
+        c->stats.kernel_launches += 2;  // three kernels
+        break;
+      case IT_ATTN_B:
+        HIP_TRY(c, launch_attention_bwd(it.p0, it.p5, it.p1, it.p2, static_cast<float*>(it.p3), it.p4, it.i[0], it.i[1], it.i[2],
+                                        it.i[3], dt, c->stream));
+        c->stats.kernel_launches += 5;  // six kernels
+        break;
       case IT_GAP_B:
         HIP_TRY(c, launch_gap_bwd(it.p0, it.p1, it.p2, it.i[0], it.i[1], it.i[2], it.i[3], dt, c->stream));
         break;
@@ -752,7 +826,7 @@ int refresh_slot(cdp_ctx* c, int j, int slot, bool apply, bool linear_done = fal
     return CDP_OK;
   };
   for (const Op& o : sp.ops) {
-    if (o.kind != OPK_GEMM) continue;
+    if (o.kind != OPK_GEMM && o.kind != OPK_LN) continue;
     if (linear_done && linear_update_fusable(o)) continue;  // updated by its weight-gradient kernel
     if (o.g_off >= 0) { int rc = add_vec(o.g_off, o.gamma_c, o.Cout); if (rc) return rc; }
     if (o.b_off >= 0) { int rc = add_vec(o.b_off, o.bias_c, o.Cout); if (rc) return rc; }

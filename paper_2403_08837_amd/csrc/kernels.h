@@ -208,6 +208,24 @@ hipError_t launch_maxpool_bwd(const void* x, const void* dy, void* dx, int B, in
 hipError_t launch_gap_fwd(const void* x, void* y, int B, int HW, int C, int dtype, hipStream_t stream);
 hipError_t launch_gap_bwd(const void* x, const void* dy, void* dx, int B, int HW, int C, int mask_relu,
                           int dtype, hipStream_t stream);
+// ViT-shaped stages (transformer_kernels.hip).  LayerNorm over the C channels of `rows` rows
+// (C <= 1024), fp32 gamma / beta; the backward adds `add` (may be NULL) to dx and accumulates
+// d gamma / d beta into Ggamma / Gbeta with fp32 atomics (the accumulators hold running sums).
+hipError_t launch_layernorm_fwd(const void* x, const float* gamma, const float* beta, void* y, int rows, int C, int dtype,
+                                hipStream_t stream);
+hipError_t launch_layernorm_bwd(const void* x, const void* dy, const void* add, const float* gamma, void* dx, float* Ggamma,
+                                float* Gbeta, int rows, int C, int dtype, hipStream_t stream);
+// Exact GELU and its derivative, elementwise.
+hipError_t launch_gelu_fwd(const void* x, void* y, int64_t n, int dtype, hipStream_t stream);
+hipError_t launch_gelu_bwd(const void* x, const void* dy, void* dx, int64_t n, int dtype, hipStream_t stream);
+// Self-attention core on qkv[B][T][3*D] (q | k | v per token; T <= 1024): P[B][heads][T][T] are the
+// attention probabilities (written by the forward, read by the backward), out / dout [B][T][D];
+// ws: fp32 [B][heads][T][T] scratch; ws_ds: T [B][heads][T][T] scratch.
+hipError_t launch_attention_fwd(const void* qkv, void* P, void* out, float* ws, int B, int T, int D, int heads, int dtype,
+                                hipStream_t stream);
+hipError_t launch_attention_bwd(const void* qkv, const void* P, const void* dout, void* dqkv, float* ws_dp, void* ws_ds, int B,
+                                int T, int D, int heads, int dtype, hipStream_t stream);
+
 // T -> f32 copy (cdp_get_weights of a ring copy).
 hipError_t launch_to_f32(const void* src, float* dst, int64_t n, int dtype, hipStream_t stream);
 hipError_t launch_fill_f32(float* dst, int64_t n, float v, hipStream_t stream);

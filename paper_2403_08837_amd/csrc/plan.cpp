@@ -102,6 +102,11 @@ std::string build_plan(const cdp_stage_desc* stages, int n_stages, const cdp_opt
           poff += cout;
           ++j;
         }
+        if (j < sd.n_layers && sd.layers[j].kind == CDP_TOKENS && follows(sd.layers[j], j)) {
+          tout.W = tout.H * tout.W;  // the patch grid read as one row of tokens: same memory
+          tout.H = 1;
+          ++j;
+        }
         if (j < sd.n_layers && sd.layers[j].kind == CDP_ADD && follows(sd.layers[j], j)) {
           const int s2 = sd.layers[j].p[0];
           if (s2 < 0 || s2 > j || map[s2] < 0) return err(s, j, "add src2 is not a materialised tensor");
@@ -128,6 +133,39 @@ std::string build_plan(const cdp_stage_desc* stages, int n_stages, const cdp_opt
         op.kind = OPK_GAP;
         op.Hin = tin.H; op.Win = tin.W; op.Cin = op.Cout = tin.C;
         tout.C = tin.C;
+      } else if ((L.kind == CDP_LAYERNORM || L.kind == CDP_GELU || L.kind == CDP_ATTENTION) && tin.relu) {
+        return err(s, i, "layernorm / gelu / attention directly on a ReLU output is not supported");
+      } else if (L.kind == CDP_LAYERNORM) {
+        if (L.p[0] != tin.C || tin.C > 1024) return err(s, i, "layernorm channels must match its input and be at most 1024");
+        if (tin.f32) return err(s, i, "layernorm cannot read logits");
+        op.kind = OPK_LN;
+        op.Hin = op.Hout = tin.H; op.Win = op.Wout = tin.W; op.Cin = op.Cout = tin.C;
+        op.g_off = poff;
+        poff += tin.C;
+        op.b_off = poff;
+        poff += tin.C;
+        tout.H = tin.H; tout.W = tin.W; tout.C = tin.C;
+      } else if (L.kind == CDP_GELU) {
+        if (tin.f32) return err(s, i, "gelu cannot read logits");
+        op.kind = OPK_GELU;
+        op.Hin = op.Hout = tin.H; op.Win = op.Wout = tin.W; op.Cin = op.Cout = tin.C;
+        tout.H = tin.H; tout.W = tin.W; tout.C = tin.C;
+      } else if (L.kind == CDP_ATTENTION) {
+        const int heads = L.p[0];
+        if (heads <= 0 || tin.H != 1 || tin.C % (3 * heads) != 0 || tin.W > 1024 || tin.f32)
+          return err(s, i, "attention needs tokens [1, T <= 1024, 3*D] with D a multiple of heads");
+        op.kind = OPK_ATTN;
+        op.heads = heads;
+        op.Hin = op.Hout = 1; op.Win = op.Wout = tin.W; op.Cin = tin.C; op.Cout = tin.C / 3;
+        tout.H = 1; tout.W = tin.W; tout.C = tin.C / 3;
+        // the attention probabilities [heads][T][T] are a saved tensor of their own
+        TensorInfo tp;
+        tp.H = heads; tp.W = tin.W; tp.C = tin.W;
+        tp.consumed = true;
+        tp.n_consumers = 1;
+        tp.producer = (int)sp.ops.size();
+        op.aux = (int)sp.tensors.size();
+        sp.tensors.push_back(tp);
       } else if (L.kind == CDP_CE_HEAD) {
         if (s != n_stages - 1 || i != sd.n_layers - 1) return err(s, i, "ce_head must be the last layer of the last stage");
         if (!tin.f32 || tin.per_sample() != L.p[0]) return err(s, i, "ce_head must follow a linear layer with `classes` outputs");
@@ -158,12 +196,19 @@ std::string build_plan(const cdp_stage_desc* stages, int n_stages, const cdp_opt
       if (t.is_residual && !t.consumed && t.relu) return err(s, (int)k, "a ReLU output used only as residual is not supported");
       if (t.n_consumers > 1 || t.is_residual)
         for (const Op& o : sp.ops)
-          if (o.in == (int)k && o.kind != OPK_GEMM) return err(s, (int)k, "a pooled tensor must have a single consumer");
+          if (o.in == (int)k && o.kind != OPK_GEMM && o.kind != OPK_LN)
+            return err(s, (int)k, "a tensor read by a pooling, GELU or attention layer must have no other use");
     }
     if ((s == n_stages - 1) != sp.has_head) return err(s, 0, "the last stage, and only it, must end in ce_head");
     // ring slot layout
     int64_t off = 0;
     for (Op& o : sp.ops) {
+      if (o.kind == OPK_LN) {  // fp32 copies of gamma and beta
+        o.gamma_c = off; off = align_up(off + (int64_t)o.Cout * 4, 256);
+        o.bias_c = off; off = align_up(off + (int64_t)o.Cout * 4, 256);
+        sp.has_gamma = true;
+        continue;
+      }
       if (o.kind != OPK_GEMM) continue;
       o.wf = off; off = align_up(off + (o.kpad ? (int64_t)o.Cout * o.kpad : o.w_count()) * out->elem_bytes, 256);
       o.wt = off; off = align_up(off + o.w_count() * out->elem_bytes, 256);

@@ -22,7 +22,7 @@ struct TensorInfo {
   int64_t per_sample() const { return (int64_t)H * W * C; }
 };
 
-enum OpKind { OPK_GEMM = 0, OPK_MAXPOOL = 1, OPK_GAP = 2, OPK_CE = 3 };
+enum OpKind { OPK_GEMM = 0, OPK_MAXPOOL = 1, OPK_GAP = 2, OPK_CE = 3, OPK_LN = 4, OPK_GELU = 5, OPK_ATTN = 6 };
 
 struct Op {
   int kind = OPK_GEMM;
@@ -32,6 +32,8 @@ struct Op {
   int Hin = 1, Win = 1, Hout = 1, Wout = 1;
   int pk = 0, ps = 0, pp = 0;     // pooling window / stride / pad
   int classes = 0;
+  int heads = 0;                  // OPK_ATTN
+  int aux = -1;                   // OPK_ATTN: tensor id of the attention probabilities kept for the backward
   int kpad = 0;                   // > 0: the forward weights are stored with this (zero-padded) row length and the
                                   // layer runs on an explicit im2col buffer (channel counts below one 16-byte chunk)
   // float offsets inside the stage's flat fp32 parameter block (-1: absent)

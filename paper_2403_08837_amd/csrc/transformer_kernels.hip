@@ -1,0 +1,388 @@
+// Kernels of ViT-shaped stages (the homogeneous stages of Sec. 5, "Memory"): LayerNorm,
+// GELU and the self-attention core.  Token-wise linear maps run on the convolution path as
+// 1x1 convolutions; what is here is first-version code built for correctness: one wavefront
+// per token row for LayerNorm and the softmax, and a plain LDS-tiled batched product for the
+// attention contractions (about a tenth of a block's flops at 196 tokens).
+#include "kernels.h"
+
+namespace cdp {
+
+namespace {
+
+__device__ __forceinline__ float t_bf2f(uint16_t h) { return __uint_as_float(((uint32_t)h) << 16); }
+__device__ __forceinline__ uint16_t t_f2bf(float f) {
+  uint32_t u = __float_as_uint(f);
+  if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x40u);
+  u += 0x7fffu + ((u >> 16) & 1u);
+  return (uint16_t)(u >> 16);
+}
+template <typename T> __device__ __forceinline__ float tld(const T* p, int64_t i);
+template <> __device__ __forceinline__ float tld<uint16_t>(const uint16_t* p, int64_t i) { return t_bf2f(p[i]); }
+template <> __device__ __forceinline__ float tld<float>(const float* p, int64_t i) { return p[i]; }
+template <typename T> __device__ __forceinline__ void tst(T* p, int64_t i, float v);
+template <> __device__ __forceinline__ void tst<uint16_t>(uint16_t* p, int64_t i, float v) { p[i] = t_f2bf(v); }
+template <> __device__ __forceinline__ void tst<float>(float* p, int64_t i, float v) { p[i] = v; }
+
+#define CDP_TDISPATCH(dtype, CALL)                        \
+  do {                                                    \
+    if ((dtype) == DT_BF16) { using T = uint16_t; CALL; } \
+    else { using T = float; CALL; }                       \
+  } while (0)
+
+__device__ __forceinline__ float wsum(float v) {
+#pragma unroll
+  for (int o = 32; o >= 1; o >>= 1) v += __shfl_xor(v, o, 64);
+  return v;
+}
+__device__ __forceinline__ float wmax(float v) {
+#pragma unroll
+  for (int o = 32; o >= 1; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
+  return v;
+}
+
+constexpr float LN_EPS = 1e-5f;
+constexpr int LN_MAX_PER_LANE = 16;  // channels <= 1024
+
+}  // namespace
+
+// ---------------------------------------------------------------------------------
+// LayerNorm over the channels of every row: one wavefront per row, lane l owns channels
+// l, l+64, ...  y = (x - mean) * rstd * gamma + beta (biased variance, eps = 1e-5).
+template <typename T>
+__global__ __launch_bounds__(256) void layernorm_fwd_kernel(const T* __restrict__ x, const float* __restrict__ gamma,
+                                                            const float* __restrict__ beta, T* __restrict__ y, int rows, int C) {
+  const int lane = threadIdx.x & 63, row = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (row >= rows) return;
+  const T* xr = x + (int64_t)row * C;
+  float v[LN_MAX_PER_LANE];
+  float s = 0.f;
+#pragma unroll
+  for (int q = 0; q < LN_MAX_PER_LANE; ++q) {
+    const int c = lane + 64 * q;
+    v[q] = c < C ? tld<T>(xr, c) : 0.f;
+    s += v[q];
+  }
+  const float mean = wsum(s) / (float)C;
+  float ss = 0.f;
+#pragma unroll
+  for (int q = 0; q < LN_MAX_PER_LANE; ++q) {
+    const int c = lane + 64 * q;
+    const float d = c < C ? v[q] - mean : 0.f;
+    ss += d * d;
+  }
+  const float rstd = rsqrtf(wsum(ss) / (float)C + LN_EPS);
+#pragma unroll
+  for (int q = 0; q < LN_MAX_PER_LANE; ++q) {
+    const int c = lane + 64 * q;
+    if (c < C) tst<T>(y, (int64_t)row * C + c, (v[q] - mean) * rstd * gamma[c] + beta[c]);
+  }
+}
+
+// Backward: with xh = (x - mean) * rstd and g = dy * gamma,
+//   dx = rstd * (g - mean(g) - xh * mean(g * xh)) (+ add), dgamma += sum dy * xh, dbeta += sum dy.
+// A workgroup walks LN_ROWS_PER_WG rows (16 per wavefront); the column sums are kept per lane,
+// combined over the four wavefronts in LDS and added to the accumulators once per workgroup.
+constexpr int LN_ROWS_PER_WG = 64;
+template <typename T>
+__global__ __launch_bounds__(256) void layernorm_bwd_kernel(const T* __restrict__ x, const T* __restrict__ dy,
+                                                            const T* __restrict__ add, const float* __restrict__ gamma,
+                                                            T* __restrict__ dx, float* __restrict__ Ggamma,
+                                                            float* __restrict__ Gbeta, int rows, int C) {
+  __shared__ float red[2][4][64 * LN_MAX_PER_LANE];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  float dg[LN_MAX_PER_LANE], db[LN_MAX_PER_LANE], gam[LN_MAX_PER_LANE];
+#pragma unroll
+  for (int q = 0; q < LN_MAX_PER_LANE; ++q) {
+    dg[q] = 0.f;
+    db[q] = 0.f;
+    const int c = lane + 64 * q;
+    gam[q] = c < C ? gamma[c] : 0.f;
+  }
+  for (int k = 0; k < LN_ROWS_PER_WG / 4; ++k) {
+    const int row = blockIdx.x * LN_ROWS_PER_WG + wave * (LN_ROWS_PER_WG / 4) + k;
+    if (row >= rows) break;
+    const int64_t base = (int64_t)row * C;
+    float v[LN_MAX_PER_LANE], d[LN_MAX_PER_LANE];
+    float s = 0.f;
+#pragma unroll
+    for (int q = 0; q < LN_MAX_PER_LANE; ++q) {
+      const int c = lane + 64 * q;
+      v[q] = c < C ? tld<T>(x, base + c) : 0.f;
+      d[q] = c < C ? tld<T>(dy, base + c) : 0.f;
+      s += v[q];
+    }
+    const float mean = wsum(s) / (float)C;
+    float ss = 0.f;
+#pragma unroll
+    for (int q = 0; q < LN_MAX_PER_LANE; ++q) {
+      const int c = lane + 64 * q;
+      const float t = c < C ? v[q] - mean : 0.f;
+      ss += t * t;
+    }
+    const float rstd = rsqrtf(wsum(ss) / (float)C + LN_EPS);
+    float sg = 0.f, sgx = 0.f;
+#pragma unroll
+    for (int q = 0; q < LN_MAX_PER_LANE; ++q) {
+      const int c = lane + 64 * q;
+      const float xh = c < C ? (v[q] - mean) * rstd : 0.f;
+      const float g = d[q] * gam[q];
+      v[q] = xh;
+      sg += g;
+      sgx += g * xh;
+      dg[q] += d[q] * xh;
+      db[q] += d[q];
+    }
+    const float mg = wsum(sg) / (float)C, mgx = wsum(sgx) / (float)C;
+#pragma unroll
+    for (int q = 0; q < LN_MAX_PER_LANE; ++q) {
+      const int c = lane + 64 * q;
+      if (c < C) {
+        float r = rstd * (d[q] * gam[q] - mg - v[q] * mgx);
+        if (add) r += tld<T>(add, base + c);
+        tst<T>(dx, base + c, r);
+      }
+    }
+  }
+#pragma unroll
+  for (int q = 0; q < LN_MAX_PER_LANE; ++q) {
+    red[0][wave][lane + 64 * q] = dg[q];
+    red[1][wave][lane + 64 * q] = db[q];
+  }
+  __syncthreads();
+  for (int c = threadIdx.x; c < C; c += 256) {
+    atomicAdd(Ggamma + c, (red[0][0][c] + red[0][1][c]) + (red[0][2][c] + red[0][3][c]));
+    atomicAdd(Gbeta + c, (red[1][0][c] + red[1][1][c]) + (red[1][2][c] + red[1][3][c]));
+  }
+}
+
+hipError_t launch_layernorm_fwd(const void* x, const float* gamma, const float* beta, void* y, int rows, int C, int dtype,
+                                hipStream_t stream) {
+  if (rows <= 0 || C <= 0 || C > 64 * LN_MAX_PER_LANE) return hipErrorInvalidValue;
+  CDP_TDISPATCH(dtype, hipLaunchKernelGGL((layernorm_fwd_kernel<T>), dim3((rows + 3) / 4), dim3(256), 0, stream,
+                                          static_cast<const T*>(x), gamma, beta, static_cast<T*>(y), rows, C));
+  return hipGetLastError();
+}
+hipError_t launch_layernorm_bwd(const void* x, const void* dy, const void* add, const float* gamma, void* dx, float* Ggamma,
+                                float* Gbeta, int rows, int C, int dtype, hipStream_t stream) {
+  if (rows <= 0 || C <= 0 || C > 64 * LN_MAX_PER_LANE) return hipErrorInvalidValue;
+  CDP_TDISPATCH(dtype, hipLaunchKernelGGL((layernorm_bwd_kernel<T>), dim3((rows + LN_ROWS_PER_WG - 1) / LN_ROWS_PER_WG), dim3(256),
+                                          0, stream, static_cast<const T*>(x), static_cast<const T*>(dy),
+                                          static_cast<const T*>(add), gamma, static_cast<T*>(dx), Ggamma, Gbeta, rows, C));
+  return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------------
+// GELU, exact form: y = x * Phi(x);  dx = dy * (Phi(x) + x * phi(x)).
+template <typename T>
+__global__ void gelu_fwd_kernel(const T* __restrict__ x, T* __restrict__ y, int64_t n) {
+  for (int64_t i = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x) {
+    const float v = tld<T>(x, i);
+    tst<T>(y, i, 0.5f * v * (1.f + erff(v * 0.70710678118654752f)));
+  }
+}
+template <typename T>
+__global__ void gelu_bwd_kernel(const T* __restrict__ x, const T* __restrict__ dy, T* __restrict__ dx, int64_t n) {
+  for (int64_t i = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x) {
+    const float v = tld<T>(x, i);
+    const float cdf = 0.5f * (1.f + erff(v * 0.70710678118654752f));
+    const float pdf = 0.3989422804014327f * expf(-0.5f * v * v);
+    tst<T>(dx, i, tld<T>(dy, i) * (cdf + v * pdf));
+  }
+}
+hipError_t launch_gelu_fwd(const void* x, void* y, int64_t n, int dtype, hipStream_t stream) {
+  if (n <= 0) return hipErrorInvalidValue;
+  const int blocks = (int)((n + 1023) / 1024 < (1 << 20) ? (n + 1023) / 1024 : (1 << 20));
+  CDP_TDISPATCH(dtype, hipLaunchKernelGGL((gelu_fwd_kernel<T>), dim3(blocks), dim3(256), 0, stream, static_cast<const T*>(x),
+                                          static_cast<T*>(y), n));
+  return hipGetLastError();
+}
+hipError_t launch_gelu_bwd(const void* x, const void* dy, void* dx, int64_t n, int dtype, hipStream_t stream) {
+  if (n <= 0) return hipErrorInvalidValue;
+  const int blocks = (int)((n + 1023) / 1024 < (1 << 20) ? (n + 1023) / 1024 : (1 << 20));
+  CDP_TDISPATCH(dtype, hipLaunchKernelGGL((gelu_bwd_kernel<T>), dim3(blocks), dim3(256), 0, stream, static_cast<const T*>(x),
+                                          static_cast<const T*>(dy), static_cast<T*>(dx), n));
+  return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------------
+// Batched product C[z][i][j] = alpha * sum_k A[z][i][k] * B[z][j][k] with arbitrary element
+// strides; batch z = (sample, head) with its own pair of offsets per operand.  32 x 32 outputs
+// per workgroup, 2 x 2 per thread, 32-deep slabs through LDS (fp32).
+struct BmmOperand {
+  const void* p;
+  int64_t s_sample, s_head, s_row, s_k;  // element strides
+};
+struct BmmArgs {
+  BmmOperand A, B;
+  void* C;
+  int64_t c_sample, c_head, c_row, c_col;
+  int M, N, K, heads;
+  float alpha;
+  int c_f32;  // C holds fp32, else T
+};
+
+template <typename T>
+__global__ __launch_bounds__(256) void bmm_kernel(const BmmArgs a) {
+  __shared__ float As[32][33], Bs[32][33];
+  const int z = blockIdx.z, sample = z / a.heads, head = z % a.heads;
+  const int i0 = blockIdx.y * 32, j0 = blockIdx.x * 32;
+  const T* Ap = static_cast<const T*>(a.A.p) + sample * a.A.s_sample + head * a.A.s_head;
+  const T* Bp = static_cast<const T*>(a.B.p) + sample * a.B.s_sample + head * a.B.s_head;
+  const int tx = threadIdx.x & 15, ty = threadIdx.x >> 4;  // outputs (2*ty + {0,1}, 2*tx + {0,1})
+  float acc[2][2] = {{0.f, 0.f}, {0.f, 0.f}};
+  for (int k0 = 0; k0 < a.K; k0 += 32) {
+    for (int e = threadIdx.x; e < 1024; e += 256) {
+      const int r = e >> 5, k = e & 31;
+      As[r][k] = (i0 + r < a.M && k0 + k < a.K) ? tld<T>(Ap, (int64_t)(i0 + r) * a.A.s_row + (int64_t)(k0 + k) * a.A.s_k) : 0.f;
+      Bs[r][k] = (j0 + r < a.N && k0 + k < a.K) ? tld<T>(Bp, (int64_t)(j0 + r) * a.B.s_row + (int64_t)(k0 + k) * a.B.s_k) : 0.f;
+    }
+    __syncthreads();
+#pragma unroll 8
+    for (int k = 0; k < 32; ++k) {
+      const float a0 = As[2 * ty][k], a1 = As[2 * ty + 1][k], b0 = Bs[2 * tx][k], b1 = Bs[2 * tx + 1][k];
+      acc[0][0] += a0 * b0; acc[0][1] += a0 * b1; acc[1][0] += a1 * b0; acc[1][1] += a1 * b1;
+    }
+    __syncthreads();
+  }
+  const int64_t cbase = sample * a.c_sample + head * a.c_head;
+#pragma unroll
+  for (int di = 0; di < 2; ++di)
+#pragma unroll
+    for (int dj = 0; dj < 2; ++dj) {
+      const int i = i0 + 2 * ty + di, j = j0 + 2 * tx + dj;
+      if (i >= a.M || j >= a.N) continue;
+      const int64_t o = cbase + (int64_t)i * a.c_row + (int64_t)j * a.c_col;
+      if (a.c_f32) static_cast<float*>(a.C)[o] = a.alpha * acc[di][dj];
+      else tst<T>(static_cast<T*>(a.C), o, a.alpha * acc[di][dj]);
+    }
+}
+
+static hipError_t launch_bmm(const BmmArgs& a, int batch, int dtype, hipStream_t stream) {
+  if (a.M <= 0 || a.N <= 0 || a.K <= 0 || batch <= 0 || batch > 65535) return hipErrorInvalidValue;
+  dim3 grid((a.N + 31) / 32, (a.M + 31) / 32, batch);
+  CDP_TDISPATCH(dtype, hipLaunchKernelGGL((bmm_kernel<T>), grid, dim3(256), 0, stream, a));
+  return hipGetLastError();
+}
+
+// Row softmax of fp32 scores into T probabilities, one wavefront per row (length <= 1024).
+template <typename T>
+__global__ __launch_bounds__(256) void softmax_fwd_kernel(const float* __restrict__ s, T* __restrict__ p, int64_t rows, int n) {
+  const int lane = threadIdx.x & 63;
+  const int64_t row = blockIdx.x * (int64_t)4 + (threadIdx.x >> 6);
+  if (row >= rows) return;
+  const float* sr = s + row * n;
+  float v[LN_MAX_PER_LANE];
+  float m = -INFINITY;
+#pragma unroll
+  for (int q = 0; q < LN_MAX_PER_LANE; ++q) {
+    const int c = lane + 64 * q;
+    v[q] = c < n ? sr[c] : -INFINITY;
+    m = fmaxf(m, v[q]);
+  }
+  m = wmax(m);
+  float sum = 0.f;
+#pragma unroll
+  for (int q = 0; q < LN_MAX_PER_LANE; ++q) {
+    v[q] = (lane + 64 * q) < n ? expf(v[q] - m) : 0.f;
+    sum += v[q];
+  }
+  const float inv = 1.f / wsum(sum);
+#pragma unroll
+  for (int q = 0; q < LN_MAX_PER_LANE; ++q) {
+    const int c = lane + 64 * q;
+    if (c < n) tst<T>(p, row * n + c, v[q] * inv);
+  }
+}
+// ds = P * (dP - sum_k dP_k P_k) * scale, rows as above.
+template <typename T>
+__global__ __launch_bounds__(256) void softmax_bwd_kernel(const T* __restrict__ p, const float* __restrict__ dp, T* __restrict__ ds,
+                                                          int64_t rows, int n, float scale) {
+  const int lane = threadIdx.x & 63;
+  const int64_t row = blockIdx.x * (int64_t)4 + (threadIdx.x >> 6);
+  if (row >= rows) return;
+  float pv[LN_MAX_PER_LANE], dv[LN_MAX_PER_LANE];
+  float dot = 0.f;
+#pragma unroll
+  for (int q = 0; q < LN_MAX_PER_LANE; ++q) {
+    const int c = lane + 64 * q;
+    pv[q] = c < n ? tld<T>(p, row * n + c) : 0.f;
+    dv[q] = c < n ? dp[row * n + c] : 0.f;
+    dot += pv[q] * dv[q];
+  }
+  dot = wsum(dot);
+#pragma unroll
+  for (int q = 0; q < LN_MAX_PER_LANE; ++q) {
+    const int c = lane + 64 * q;
+    if (c < n) tst<T>(ds, row * n + c, pv[q] * (dv[q] - dot) * scale);
+  }
+}
+
+// Self-attention core on qkv[B][T][3*D] (q | k | v per token, head h in columns h*dh..):
+// forward  S = q k^T / sqrt(dh) (fp32 workspace), P = softmax(S) (kept for the backward), out = P v;
+// backward dv = P^T do, dP = do v^T (fp32 workspace), ds = P * (dP - rowsum(dP * P)) / sqrt(dh),
+//          dq = ds k, dk = ds^T q, written into dqkv[B][T][3*D].
+hipError_t launch_attention_fwd(const void* qkv, void* P, void* out, float* ws, int B, int NT, int D, int heads, int dtype,
+                                hipStream_t stream) {
+  if (B <= 0 || NT <= 0 || NT > 64 * LN_MAX_PER_LANE || heads <= 0 || D % heads) return hipErrorInvalidValue;
+  const int dh = D / heads;
+  const int64_t tok = 3ll * D, TT = (int64_t)NT * NT;
+  const float scale = 1.0f / sqrtf((float)dh);
+  const char* base = static_cast<const char*>(qkv);
+  const int eb = dtype == DT_BF16 ? 2 : 4;
+  BmmArgs s;  // S[z][q][key] = scale * sum_j q[q][j] k[key][j]
+  s.A = BmmOperand{base, NT * tok, dh, tok, 1};
+  s.B = BmmOperand{base + (int64_t)D * eb, NT * tok, dh, tok, 1};
+  s.C = ws; s.c_sample = heads * TT; s.c_head = TT; s.c_row = NT; s.c_col = 1;
+  s.M = NT; s.N = NT; s.K = dh; s.heads = heads; s.alpha = scale; s.c_f32 = 1;
+  hipError_t e = launch_bmm(s, B * heads, dtype, stream);
+  if (e != hipSuccess) return e;
+  const int64_t rows = (int64_t)B * heads * NT;
+  CDP_TDISPATCH(dtype, hipLaunchKernelGGL((softmax_fwd_kernel<T>), dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, stream, ws,
+                                          static_cast<T*>(P), rows, NT));
+  if ((e = hipGetLastError()) != hipSuccess) return e;
+  BmmArgs o;  // out[z][q][j] = sum_key P[q][key] v[key][j]
+  o.A = BmmOperand{P, heads * TT, TT, NT, 1};
+  o.B = BmmOperand{base + 2ll * D * eb, NT * tok, dh, 1, tok};
+  o.C = out; o.c_sample = (int64_t)NT * D; o.c_head = dh; o.c_row = D; o.c_col = 1;
+  o.M = NT; o.N = dh; o.K = NT; o.heads = heads; o.alpha = 1.f; o.c_f32 = 0;
+  return launch_bmm(o, B * heads, dtype, stream);
+}
+
+hipError_t launch_attention_bwd(const void* qkv, const void* P, const void* dout, void* dqkv, float* ws_dp, void* ws_ds, int B,
+                                int NT, int D, int heads, int dtype, hipStream_t stream) {
+  if (B <= 0 || NT <= 0 || NT > 64 * LN_MAX_PER_LANE || heads <= 0 || D % heads) return hipErrorInvalidValue;
+  const int dh = D / heads;
+  const int64_t tok = 3ll * D, TT = (int64_t)NT * NT;
+  const float scale = 1.0f / sqrtf((float)dh);
+  const int eb = dtype == DT_BF16 ? 2 : 4;
+  const char* base = static_cast<const char*>(qkv);
+  char* dbase = static_cast<char*>(dqkv);
+  const BmmOperand Pqk{P, heads * TT, TT, NT, 1};    // rows = query, k = key
+  const BmmOperand Pkq{P, heads * TT, TT, 1, NT};    // rows = key,   k = query
+  const BmmOperand dOqj{dout, (int64_t)NT * D, dh, D, 1};  // rows = query, k = j
+  const BmmOperand dOjq{dout, (int64_t)NT * D, dh, 1, D};  // rows = j,     k = query
+  hipError_t e;
+  BmmArgs a;
+  // dv[key][j] = sum_q P[q][key] do[q][j]
+  a.A = Pkq; a.B = dOjq; a.C = dbase + 2ll * D * eb; a.c_sample = NT * tok; a.c_head = dh; a.c_row = tok; a.c_col = 1;
+  a.M = NT; a.N = dh; a.K = NT; a.heads = heads; a.alpha = 1.f; a.c_f32 = 0;
+  if ((e = launch_bmm(a, B * heads, dtype, stream)) != hipSuccess) return e;
+  // dP[q][key] = sum_j do[q][j] v[key][j]
+  a.A = dOqj; a.B = BmmOperand{base + 2ll * D * eb, NT * tok, dh, tok, 1}; a.C = ws_dp;
+  a.c_sample = heads * TT; a.c_head = TT; a.c_row = NT; a.c_col = 1; a.M = NT; a.N = NT; a.K = dh; a.c_f32 = 1;
+  if ((e = launch_bmm(a, B * heads, dtype, stream)) != hipSuccess) return e;
+  const int64_t rows = (int64_t)B * heads * NT;
+  CDP_TDISPATCH(dtype, hipLaunchKernelGGL((softmax_bwd_kernel<T>), dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, stream,
+                                          static_cast<const T*>(P), ws_dp, static_cast<T*>(ws_ds), rows, NT, scale));
+  if ((e = hipGetLastError()) != hipSuccess) return e;
+  const BmmOperand dSqk{ws_ds, heads * TT, TT, NT, 1}, dSkq{ws_ds, heads * TT, TT, 1, NT};
+  // dq[q][j] = sum_key ds[q][key] k[key][j]
+  a.A = dSqk; a.B = BmmOperand{base + (int64_t)D * eb, NT * tok, dh, 1, tok}; a.C = dbase;
+  a.c_sample = NT * tok; a.c_head = dh; a.c_row = tok; a.c_col = 1; a.M = NT; a.N = dh; a.K = NT; a.c_f32 = 0;
+  if ((e = launch_bmm(a, B * heads, dtype, stream)) != hipSuccess) return e;
+  // dk[key][j] = sum_q ds[q][key] q[q][j]
+  a.A = dSkq; a.B = BmmOperand{base, NT * tok, dh, 1, tok}; a.C = dbase + (int64_t)D * eb;
+  return launch_bmm(a, B * heads, dtype, stream);
+}
+
+}  // namespace cdp

@@ -339,3 +339,19 @@ def test_tick_by_tick_and_unaligned_inputs_give_the_same_weights(name):
                 w = wl.unflatten_params(got[0][j], cfg.stages[j])
                 assert O.stage_rel_err(w, ref.params[j]) <= tol, (mode, j)
                 assert O.stage_rel_err(w, wl.unflatten_params(base[0][j], cfg.stages[j])) <= tol, (mode, j)
+
+
+@pytest.mark.parametrize("rule", RULES)
+def test_vit_mini_fp32_all_rules(rule):
+    """ViT-shaped stages (LayerNorm, attention, GELU, residuals around token-wise linear maps)."""
+    cfg = wl.get_config("vit_mini_f32")
+    check(cfg, rule, cfg.steps)
+
+
+def test_vit_mini_bf16_and_variants():
+    cfg = wl.get_config("vit_mini")
+    check(cfg, wl.RULE_V2, cfg.steps)
+    cfg = wl.get_config("vit_mini_f32")
+    check(cfg, wl.RULE_DP, 3, dp_batched=True)
+    check(cfg, wl.RULE_V2, 3, momentum=0.9, weight_decay=5e-4)
+    check(cfg, wl.RULE_V2, 3, bwd_fresh=True)

@@ -27,6 +27,8 @@ def test_enum_values_match_workload_vocabulary():
     hdr = open(os.path.join(ROOT, "include", "cdp.h")).read()
     for name, val in [("CDP_LINEAR", wl.LINEAR), ("CDP_RELU", wl.RELU), ("CDP_CONV2D", wl.CONV2D), ("CDP_AFFINE", wl.AFFINE),
                       ("CDP_ADD", wl.ADD), ("CDP_MAXPOOL", wl.MAXPOOL), ("CDP_GAP", wl.GAP), ("CDP_CE_HEAD", wl.CE_HEAD),
+                      ("CDP_LAYERNORM", wl.LAYERNORM), ("CDP_GELU", wl.GELU), ("CDP_ATTENTION", wl.ATTENTION),
+                      ("CDP_TOKENS", wl.TOKENS), ("CDP_RULE_MASK", wl.RULE_MASK),
                       ("CDP_RULE_DP", wl.RULE_DP), ("CDP_RULE_V1", wl.RULE_V1), ("CDP_RULE_V2", wl.RULE_V2),
                       ("CDP_F32", wl.F32), ("CDP_BF16", wl.BF16)]:
         assert re.search(r"\b%s = %d\b" % (name, val), hdr), name
@@ -40,7 +42,8 @@ def _dry(cfg, rule, T, dp_batched=False):
     return tr
 
 
-@pytest.mark.parametrize("name", ["mlp_mini", "mlp_odd", "cfg1", "cfg2", "cfg3", "cfg4", "cfg5", "resnet50_mini"])
+@pytest.mark.parametrize("name", ["mlp_mini", "mlp_odd", "cfg1", "cfg2", "cfg3", "cfg4", "cfg5", "resnet50_mini", "vit_mini",
+                                  "vit_b16"])
 @pytest.mark.parametrize("rule", RULES)
 def test_trace_and_live_counts_equal_oracle(name, rule):
     """Tick order and weight-version indexing must match the oracle exactly."""
