@@ -32,12 +32,14 @@ WORKLOAD_TEXT = {
     "cfg3": "CIFAR-shaped ResNet-18: 8 BasicBlock stages, N=4 micro-batches of 32, bf16",
     "cfg4": "ImageNet-shaped ResNet-50: 16 bottleneck stages, N=8 micro-batches of 32, bf16",
     "cfg5": "Deep wide MLP: 24 stages Linear(4096->4096)+ReLU, 1000-class head, N=16 micro-batches of 64, bf16",
+    "vit_b16": "ViT-B/16-shaped: 12 transformer-block stages on 196 tokens of width 768, N=8 micro-batches of 32, bf16",
 }
 
 
 KERNELS = {"cfg1": "linear_tick_kernel<float>", "cfg2": "linear_tick_kernel<bf16,64>", "cfg5": "linear_tick_kernel<bf16,128>",
            "cfg3": "conv_gemm_kernel + conv_wgrad_kernel (+ linear_tick_kernel for the classifier)",
-           "cfg4": "conv_gemm_kernel + conv_wgrad_kernel (+ linear_tick_kernel for the classifier)"}
+           "cfg4": "conv_gemm_kernel + conv_wgrad_kernel (+ linear_tick_kernel for the classifier)",
+           "vit_b16": "conv_gemm_kernel + conv_wgrad_kernel on the token-wise linear maps (attention and LayerNorm kernels are not in this figure)"}
 
 
 def measured_traffic(workload):
@@ -216,7 +218,7 @@ def main():
     cfg = wl.get_config(args.workload)
     rule = {"dp": wl.RULE_DP, "dp_batched": wl.RULE_DP, "v1": wl.RULE_V1, "v2": wl.RULE_V2}[args.rule]
     batched = args.rule == "dp_batched"
-    default_steps = {"cfg1": 200, "cfg2": 200, "cfg3": 20, "cfg4": 5, "cfg5": 20}[args.workload]
+    default_steps = {"cfg1": 200, "cfg2": 200, "cfg3": 20, "cfg4": 5, "cfg5": 20, "vit_b16": 5}[args.workload]
     steps = args.steps if args.steps is not None else default_steps
     warmup = args.warmup if args.warmup is not None else 3
     if args.calib_copy:
@@ -232,7 +234,7 @@ def main():
         for name in args.also.split(","):
             name = name.strip()
             if name and name != args.workload:
-                short = {"cfg1": 100, "cfg2": 100, "cfg3": 10, "cfg4": 3, "cfg5": 10}[name]
+                short = {"cfg1": 100, "cfg2": 100, "cfg3": 10, "cfg4": 3, "cfg5": 10, "vit_b16": 3}[name]
                 w = run_workload(name, rule, short, 2, n_batches=2, dp_batched=batched)
                 out["workloads"][name] = {k: w[k] for k in ("value", "unit", "ms_per_step", "steps", "dtype", "config",
                                                             "peak_activation_bytes", "dp_activation_bytes", "roofline")}
