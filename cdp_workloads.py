@@ -348,6 +348,13 @@ def get_config(name: str) -> Config:
         c = get_config("vit_mini")
         c.name, c.dtype = "vit_mini_f32", F32
         return c
+    if name == "vit_odd":        # 9 tokens of width 24, heads of width 6: nothing a multiple of four
+        return Config("vit_odd", _vit(12, 4, 24, 4, 2, 5), (12, 12, 3), 5, N=4, B=3, dtype=F32, lr=0.05, steps=4,
+                      init_gain_last_affine=0.25, init_gain_head=0.2)
+    if name == "vit_odd_bf16":
+        c = get_config("vit_odd")
+        c.name, c.dtype = "vit_odd_bf16", BF16
+        return c
     if name == "vit_b16":        # ViT-B/16-shaped: 196 tokens of width 768, 12 heads, 12 block stages
         return Config("vit_b16", _vit(224, 16, 768, 12, 12, 1000), (224, 224, 3), 1000, N=8, B=32, dtype=BF16, lr=0.01,
                       steps=2, init_gain_last_affine=0.25, init_gain_head=0.2, notes="ViT-B/16-shaped")

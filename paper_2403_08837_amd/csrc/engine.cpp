@@ -89,7 +89,7 @@ struct Item {
   ColsumProb c;
   WReduceProb r;
   const void* p0 = nullptr; const void* p1 = nullptr; void* p2 = nullptr; void* p3 = nullptr; void* p4 = nullptr;
-  const void* p5 = nullptr; void* p6 = nullptr;
+  const void* p5 = nullptr; void* p6 = nullptr; void* p7 = nullptr;
   int64_t n0 = 0;
   int i[10] = {0};
   double flops = 0, bytes = 0;  // algorithmic work (contractions only)
@@ -570,6 +570,9 @@ int build_backward(cdp_ctx* c, int i, int j, int version, Program* prog, bool fi
       it.p0 = xin; it.p1 = dz; it.p2 = dx; it.p5 = need_dx ? addend[o.in] : nullptr;
       it.p3 = const_cast<char*>(slot + o.gamma_c); it.p4 = G + o.g_off; it.p6 = G + o.b_off;
       it.i[0] = c->B * o.Hin * o.Win; it.i[1] = o.Cin;
+      Block part;  // per-workgroup partial sums of d gamma / d beta
+      if (!scratch_alloc(c, layernorm_bwd_workspace_bytes(it.i[0], it.i[1]), &part)) return fail(c, CDP_ENOMEM, "tick workspace exhausted");
+      it.p7 = c->ptr(part.off);
       at(level).push_back(it);
     } else if (need_dx && (o.kind == OPK_GELU || o.kind == OPK_ATTN)) {
       if (accumulate || addend[o.in]) return fail(c, CDP_EINVAL, "gelu / attention input with another use is not supported");
@@ -751,7 +754,8 @@ int launch_level(cdp_ctx* c, std::vector<Item>& items) {
         break;
       case IT_LN_B:
         HIP_TRY(c, launch_layernorm_bwd(it.p0, it.p1, it.p5, static_cast<const float*>(it.p3), it.p2, static_cast<float*>(it.p4),
-                                        static_cast<float*>(it.p6), it.i[0], it.i[1], dt, c->stream));
+                                        static_cast<float*>(it.p6), static_cast<float*>(it.p7), it.i[0], it.i[1], dt, c->stream));
+        c->stats.kernel_launches++;  // two kernels
         break;
       case IT_GELU_F:
         HIP_TRY(c, launch_gelu_fwd(it.p0, it.p2, it.n0, dt, c->stream));

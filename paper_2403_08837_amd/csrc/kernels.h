@@ -209,12 +209,14 @@ hipError_t launch_gap_fwd(const void* x, void* y, int B, int HW, int C, int dtyp
 hipError_t launch_gap_bwd(const void* x, const void* dy, void* dx, int B, int HW, int C, int mask_relu,
                           int dtype, hipStream_t stream);
 // ViT-shaped stages (transformer_kernels.hip).  LayerNorm over the C channels of `rows` rows
-// (C <= 1024), fp32 gamma / beta; the backward adds `add` (may be NULL) to dx and accumulates
-// d gamma / d beta into Ggamma / Gbeta with fp32 atomics (the accumulators hold running sums).
+// (C <= 1024), fp32 gamma / beta; the backward adds `add` (may be NULL) to dx and adds d gamma /
+// d beta to the running sums Ggamma / Gbeta through per-workgroup partial sums in `workspace`
+// (layernorm_bwd_workspace_bytes) and a small fold kernel.
 hipError_t launch_layernorm_fwd(const void* x, const float* gamma, const float* beta, void* y, int rows, int C, int dtype,
                                 hipStream_t stream);
+int64_t layernorm_bwd_workspace_bytes(int rows, int C);
 hipError_t launch_layernorm_bwd(const void* x, const void* dy, const void* add, const float* gamma, void* dx, float* Ggamma,
-                                float* Gbeta, int rows, int C, int dtype, hipStream_t stream);
+                                float* Gbeta, float* workspace, int rows, int C, int dtype, hipStream_t stream);
 // Exact GELU and its derivative, elementwise.
 hipError_t launch_gelu_fwd(const void* x, void* y, int64_t n, int dtype, hipStream_t stream);
 hipError_t launch_gelu_bwd(const void* x, const void* dy, void* dx, int64_t n, int dtype, hipStream_t stream);

@@ -1,8 +1,7 @@
 // Kernels of ViT-shaped stages (the homogeneous stages of Sec. 5, "Memory"): LayerNorm,
 // GELU and the self-attention core.  Token-wise linear maps run on the convolution path as
-// 1x1 convolutions; what is here is first-version code built for correctness: one wavefront
-// per token row for LayerNorm and the softmax, and a plain LDS-tiled batched product for the
-// attention contractions (about a tenth of a block's flops at 196 tokens).
+// 1x1 convolutions.  LayerNorm and the softmax take one wavefront per token row; the attention
+// contractions (about a tenth of a block's flops at 196 tokens) are a batched MFMA product.
 #include "kernels.h"
 
 namespace cdp {
@@ -81,13 +80,12 @@ __global__ __launch_bounds__(256) void layernorm_fwd_kernel(const T* __restrict_
 // Backward: with xh = (x - mean) * rstd and g = dy * gamma,
 //   dx = rstd * (g - mean(g) - xh * mean(g * xh)) (+ add), dgamma += sum dy * xh, dbeta += sum dy.
 // A workgroup walks LN_ROWS_PER_WG rows (16 per wavefront); the column sums are kept per lane,
-// combined over the four wavefronts in LDS and added to the accumulators once per workgroup.
-constexpr int LN_ROWS_PER_WG = 64;
+// combined over the four wavefronts in LDS and written as one partial row per workgroup.
+constexpr int LN_ROWS_PER_WG = 32;
 template <typename T>
 __global__ __launch_bounds__(256) void layernorm_bwd_kernel(const T* __restrict__ x, const T* __restrict__ dy,
                                                             const T* __restrict__ add, const float* __restrict__ gamma,
-                                                            T* __restrict__ dx, float* __restrict__ Ggamma,
-                                                            float* __restrict__ Gbeta, int rows, int C) {
+                                                            T* __restrict__ dx, float* __restrict__ part, int rows, int C) {
   __shared__ float red[2][4][64 * LN_MAX_PER_LANE];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   float dg[LN_MAX_PER_LANE], db[LN_MAX_PER_LANE], gam[LN_MAX_PER_LANE];
@@ -149,10 +147,31 @@ __global__ __launch_bounds__(256) void layernorm_bwd_kernel(const T* __restrict_
     red[1][wave][lane + 64 * q] = db[q];
   }
   __syncthreads();
+  // per-workgroup partial sums; layernorm_fold_kernel adds them to the accumulators (device-wide
+  // atomics on these small hot vectors cost far more than the whole pass)
+  float* pg = part + (int64_t)blockIdx.x * 2 * C;
   for (int c = threadIdx.x; c < C; c += 256) {
-    atomicAdd(Ggamma + c, (red[0][0][c] + red[0][1][c]) + (red[0][2][c] + red[0][3][c]));
-    atomicAdd(Gbeta + c, (red[1][0][c] + red[1][1][c]) + (red[1][2][c] + red[1][3][c]));
+    pg[c] = (red[0][0][c] + red[0][1][c]) + (red[0][2][c] + red[0][3][c]);
+    pg[C + c] = (red[1][0][c] + red[1][1][c]) + (red[1][2][c] + red[1][3][c]);
   }
+}
+
+__global__ void layernorm_fold_kernel(const float* __restrict__ part, int n_part, float* __restrict__ Ggamma,
+                                      float* __restrict__ Gbeta, int C) {
+  const int c = blockIdx.x * blockDim.x + threadIdx.x;
+  if (c >= 2 * C) return;
+  float s0 = 0.f, s1 = 0.f, s2 = 0.f, s3 = 0.f;
+  int k = 0;
+  for (; k + 3 < n_part; k += 4) {
+    s0 += part[(int64_t)k * 2 * C + c];
+    s1 += part[(int64_t)(k + 1) * 2 * C + c];
+    s2 += part[(int64_t)(k + 2) * 2 * C + c];
+    s3 += part[(int64_t)(k + 3) * 2 * C + c];
+  }
+  for (; k < n_part; ++k) s0 += part[(int64_t)k * 2 * C + c];
+  const float s = (s0 + s1) + (s2 + s3);
+  if (c < C) Ggamma[c] += s;
+  else Gbeta[c - C] += s;
 }
 
 hipError_t launch_layernorm_fwd(const void* x, const float* gamma, const float* beta, void* y, int rows, int C, int dtype,
@@ -162,12 +181,19 @@ hipError_t launch_layernorm_fwd(const void* x, const float* gamma, const float* 
                                           static_cast<const T*>(x), gamma, beta, static_cast<T*>(y), rows, C));
   return hipGetLastError();
 }
+int64_t layernorm_bwd_workspace_bytes(int rows, int C) {
+  return (int64_t)((rows + LN_ROWS_PER_WG - 1) / LN_ROWS_PER_WG) * 2 * C * 4;
+}
 hipError_t launch_layernorm_bwd(const void* x, const void* dy, const void* add, const float* gamma, void* dx, float* Ggamma,
-                                float* Gbeta, int rows, int C, int dtype, hipStream_t stream) {
-  if (rows <= 0 || C <= 0 || C > 64 * LN_MAX_PER_LANE) return hipErrorInvalidValue;
-  CDP_TDISPATCH(dtype, hipLaunchKernelGGL((layernorm_bwd_kernel<T>), dim3((rows + LN_ROWS_PER_WG - 1) / LN_ROWS_PER_WG), dim3(256),
-                                          0, stream, static_cast<const T*>(x), static_cast<const T*>(dy),
-                                          static_cast<const T*>(add), gamma, static_cast<T*>(dx), Ggamma, Gbeta, rows, C));
+                                float* Gbeta, float* workspace, int rows, int C, int dtype, hipStream_t stream) {
+  if (rows <= 0 || C <= 0 || C > 64 * LN_MAX_PER_LANE || !workspace) return hipErrorInvalidValue;
+  const int wgs = (rows + LN_ROWS_PER_WG - 1) / LN_ROWS_PER_WG;
+  CDP_TDISPATCH(dtype, hipLaunchKernelGGL((layernorm_bwd_kernel<T>), dim3(wgs), dim3(256), 0, stream, static_cast<const T*>(x),
+                                          static_cast<const T*>(dy), static_cast<const T*>(add), gamma, static_cast<T*>(dx),
+                                          workspace, rows, C));
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL(layernorm_fold_kernel, dim3((2 * C + 255) / 256), dim3(256), 0, stream, workspace, wgs, Ggamma, Gbeta, C);
   return hipGetLastError();
 }
 
@@ -206,8 +232,11 @@ hipError_t launch_gelu_bwd(const void* x, const void* dy, void* dx, int64_t n, i
 
 // ---------------------------------------------------------------------------------
 // Batched product C[z][i][j] = alpha * sum_k A[z][i][k] * B[z][j][k] with arbitrary element
-// strides; batch z = (sample, head) with its own pair of offsets per operand.  32 x 32 outputs
-// per workgroup, 2 x 2 per thread, 32-deep slabs through LDS (fp32).
+// strides; batch z = (sample, head) with its own pair of offsets per operand.  A workgroup owns
+// 64 x 64 outputs (four wavefronts, one 32 x 32 MFMA accumulator each) and walks the reduction
+// in 32-deep slabs staged through LDS as tile[row][k]; an operand whose k (mode 1) or row
+// (mode 2) index is contiguous in memory is fetched four elements at a time, anything else
+// element by element (mode 0).
 struct BmmOperand {
   const void* p;
   int64_t s_sample, s_head, s_row, s_k;  // element strides
@@ -219,47 +248,119 @@ struct BmmArgs {
   int M, N, K, heads;
   float alpha;
   int c_f32;  // C holds fp32, else T
+  int mode_a, mode_b;
 };
+
+typedef float bmm_v16f __attribute__((ext_vector_type(16)));
+typedef __bf16 bmm_v8bf __attribute__((ext_vector_type(8)));
+template <typename T> struct BmmTile;
+template <> struct BmmTile<uint16_t> { static constexpr int PITCH = 40; typedef uint2 vec4; };
+template <> struct BmmTile<float> { static constexpr int PITCH = 33; typedef float4 vec4; };
+
+__device__ __forceinline__ void bmm_put4(uint16_t* dst, int stride, uint2 v) {
+  if (stride == 1) { *reinterpret_cast<uint2*>(dst) = v; return; }
+  dst[0] = (uint16_t)(v.x & 0xffffu); dst[stride] = (uint16_t)(v.x >> 16);
+  dst[2 * stride] = (uint16_t)(v.y & 0xffffu); dst[3 * stride] = (uint16_t)(v.y >> 16);
+}
+__device__ __forceinline__ void bmm_put4(float* dst, int stride, float4 v) {
+  dst[0] = v.x; dst[stride] = v.y; dst[2 * stride] = v.z; dst[3 * stride] = v.w;
+}
+
+// tile[r][k] = op[row0 + r][k0 + k] for r < 64, k < 32, zero outside rows x K.
+template <typename T>
+__device__ __forceinline__ void bmm_stage(T* tile, const T* base, int64_t s_row, int64_t s_k, int mode, int row0, int rows,
+                                          int k0, int K) {
+  constexpr int PITCH = BmmTile<T>::PITCH;
+  typedef typename BmmTile<T>::vec4 vec4;
+  if (mode == 1) {
+    for (int e = threadIdx.x; e < 512; e += 256) {
+      const int r = e >> 3, k = (e & 7) * 4;
+      vec4 v = {};
+      if (row0 + r < rows && k0 + k < K) v = *reinterpret_cast<const vec4*>(base + (int64_t)(row0 + r) * s_row + (k0 + k));
+      bmm_put4(tile + r * PITCH + k, 1, v);
+    }
+  } else if (mode == 2) {
+    for (int e = threadIdx.x; e < 512; e += 256) {
+      const int k = e >> 4, r = (e & 15) * 4;
+      vec4 v = {};
+      if (row0 + r < rows && k0 + k < K) v = *reinterpret_cast<const vec4*>(base + (row0 + r) + (int64_t)(k0 + k) * s_k);
+      bmm_put4(tile + r * PITCH + k, PITCH, v);
+    }
+  } else {
+    for (int e = threadIdx.x; e < 2048; e += 256) {
+      const int r = e >> 5, k = e & 31;
+      T v = T(0);
+      if (row0 + r < rows && k0 + k < K) v = base[(int64_t)(row0 + r) * s_row + (int64_t)(k0 + k) * s_k];
+      tile[r * PITCH + k] = v;
+    }
+  }
+}
 
 template <typename T>
 __global__ __launch_bounds__(256) void bmm_kernel(const BmmArgs a) {
-  __shared__ float As[32][33], Bs[32][33];
+  constexpr int PITCH = BmmTile<T>::PITCH;
+  __shared__ __attribute__((aligned(16))) T As[64 * PITCH];
+  __shared__ __attribute__((aligned(16))) T Bs[64 * PITCH];
   const int z = blockIdx.z, sample = z / a.heads, head = z % a.heads;
-  const int i0 = blockIdx.y * 32, j0 = blockIdx.x * 32;
+  const int i0 = blockIdx.y * 64, j0 = blockIdx.x * 64;
   const T* Ap = static_cast<const T*>(a.A.p) + sample * a.A.s_sample + head * a.A.s_head;
   const T* Bp = static_cast<const T*>(a.B.p) + sample * a.B.s_sample + head * a.B.s_head;
-  const int tx = threadIdx.x & 15, ty = threadIdx.x >> 4;  // outputs (2*ty + {0,1}, 2*tx + {0,1})
-  float acc[2][2] = {{0.f, 0.f}, {0.f, 0.f}};
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, wm = wave >> 1, wn = wave & 1;
+  const int l31 = lane & 31, hi = lane >> 5;
+  // wavefronts whose 32 x 32 block lies outside the product still help staging
+  const bool live = i0 + wm * 32 < a.M && j0 + wn * 32 < a.N;
+  bmm_v16f acc;
+#pragma unroll
+  for (int v = 0; v < 16; ++v) acc[v] = 0.f;
   for (int k0 = 0; k0 < a.K; k0 += 32) {
-    for (int e = threadIdx.x; e < 1024; e += 256) {
-      const int r = e >> 5, k = e & 31;
-      As[r][k] = (i0 + r < a.M && k0 + k < a.K) ? tld<T>(Ap, (int64_t)(i0 + r) * a.A.s_row + (int64_t)(k0 + k) * a.A.s_k) : 0.f;
-      Bs[r][k] = (j0 + r < a.N && k0 + k < a.K) ? tld<T>(Bp, (int64_t)(j0 + r) * a.B.s_row + (int64_t)(k0 + k) * a.B.s_k) : 0.f;
-    }
+    bmm_stage<T>(As, Ap, a.A.s_row, a.A.s_k, a.mode_a, i0, a.M, k0, a.K);
+    bmm_stage<T>(Bs, Bp, a.B.s_row, a.B.s_k, a.mode_b, j0, a.N, k0, a.K);
     __syncthreads();
-#pragma unroll 8
-    for (int k = 0; k < 32; ++k) {
-      const float a0 = As[2 * ty][k], a1 = As[2 * ty + 1][k], b0 = Bs[2 * tx][k], b1 = Bs[2 * tx + 1][k];
-      acc[0][0] += a0 * b0; acc[0][1] += a0 * b1; acc[1][0] += a1 * b0; acc[1][1] += a1 * b1;
+    if (live) {
+      const T* ar = As + (wm * 32 + l31) * PITCH;
+      const T* br = Bs + (wn * 32 + l31) * PITCH;
+      if constexpr (sizeof(T) == 2) {
+#pragma unroll
+        for (int kk = 0; kk < 32; kk += 16) {
+          const uint4 av = *reinterpret_cast<const uint4*>(ar + kk + 8 * hi);
+          const uint4 bv = *reinterpret_cast<const uint4*>(br + kk + 8 * hi);
+          acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bmm_v8bf, av), __builtin_bit_cast(bmm_v8bf, bv), acc, 0, 0, 0);
+        }
+      } else {
+#pragma unroll
+        for (int kk = 0; kk < 32; kk += 2) acc = __builtin_amdgcn_mfma_f32_32x32x2f32(ar[kk + hi], br[kk + hi], acc, 0, 0, 0);
+      }
     }
     __syncthreads();
   }
+  if (!live) return;
+  // acc[v]: row = 8*(v/4) + 4*(lane/32) + v%4, column = lane%32 of the wavefront's block
   const int64_t cbase = sample * a.c_sample + head * a.c_head;
+  const int j = j0 + wn * 32 + l31;
+  if (j >= a.N) return;
 #pragma unroll
-  for (int di = 0; di < 2; ++di)
-#pragma unroll
-    for (int dj = 0; dj < 2; ++dj) {
-      const int i = i0 + 2 * ty + di, j = j0 + 2 * tx + dj;
-      if (i >= a.M || j >= a.N) continue;
-      const int64_t o = cbase + (int64_t)i * a.c_row + (int64_t)j * a.c_col;
-      if (a.c_f32) static_cast<float*>(a.C)[o] = a.alpha * acc[di][dj];
-      else tst<T>(static_cast<T*>(a.C), o, a.alpha * acc[di][dj]);
-    }
+  for (int v = 0; v < 16; ++v) {
+    const int i = i0 + wm * 32 + (v >> 2) * 8 + hi * 4 + (v & 3);
+    if (i >= a.M) continue;
+    const int64_t o = cbase + (int64_t)i * a.c_row + (int64_t)j * a.c_col;
+    if (a.c_f32) static_cast<float*>(a.C)[o] = a.alpha * acc[v];
+    else tst<T>(static_cast<T*>(a.C), o, a.alpha * acc[v]);
+  }
 }
 
-static hipError_t launch_bmm(const BmmArgs& a, int batch, int dtype, hipStream_t stream) {
+static int bmm_mode(const BmmOperand& op, int rows, int K, int eb) {
+  const bool base_ok = reinterpret_cast<uintptr_t>(op.p) % (4 * eb) == 0 && op.s_sample % 4 == 0 && op.s_head % 4 == 0;
+  if (base_ok && op.s_k == 1 && op.s_row % 4 == 0 && K % 4 == 0) return 1;
+  if (base_ok && op.s_row == 1 && op.s_k % 4 == 0 && rows % 4 == 0) return 2;
+  return 0;
+}
+
+static hipError_t launch_bmm(BmmArgs a, int batch, int dtype, hipStream_t stream) {
   if (a.M <= 0 || a.N <= 0 || a.K <= 0 || batch <= 0 || batch > 65535) return hipErrorInvalidValue;
-  dim3 grid((a.N + 31) / 32, (a.M + 31) / 32, batch);
+  const int eb = dtype == DT_BF16 ? 2 : 4;
+  a.mode_a = bmm_mode(a.A, a.M, a.K, eb);
+  a.mode_b = bmm_mode(a.B, a.N, a.K, eb);
+  dim3 grid((a.N + 63) / 64, (a.M + 63) / 64, batch);
   CDP_TDISPATCH(dtype, hipLaunchKernelGGL((bmm_kernel<T>), grid, dim3(256), 0, stream, a));
   return hipGetLastError();
 }

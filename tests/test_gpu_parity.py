@@ -355,3 +355,49 @@ def test_vit_mini_bf16_and_variants():
     check(cfg, wl.RULE_DP, 3, dp_batched=True)
     check(cfg, wl.RULE_V2, 3, momentum=0.9, weight_decay=5e-4)
     check(cfg, wl.RULE_V2, 3, bwd_fresh=True)
+
+
+@pytest.mark.parametrize("name,rule", [("vit_odd", wl.RULE_V2), ("vit_odd", wl.RULE_V1), ("vit_odd_bf16", wl.RULE_V2)])
+def test_vit_odd_shapes(name, rule):
+    """9 tokens of width 24 in heads of width 6, micro-batches of 3: no extent is a multiple of
+    four, so the attention products take their element-wise staging path and every tile is ragged."""
+    cfg = wl.get_config(name)
+    check(cfg, rule, cfg.steps)
+
+
+def test_vit_b16_full_shapes_single_microbatch(capfd):
+    """Every stage of the ViT-B/16-shaped workload at its real shape (B = 32, 196 tokens of width
+    768, 12 heads, 12 block stages, 1000 classes) with one micro-batch per step, where CDP-v2 is
+    plain SGD: 2 steps against the oracle at the stated weight tolerance."""
+    cfg = wl.get_config("vit_b16")
+    cfg.N = 1
+    check(cfg, wl.RULE_V2, 2, tensor_tol=None, capfd=capfd)
+
+
+def test_vit_b16_full_config_sampled():
+    """N = 8 micro-batches as benchmarked: exact tick trace / live counts against the oracle's
+    bookkeeping, the objective of two sampled micro-batches of the first step against an oracle
+    forward pass, and finite weights that moved."""
+    cfg = wl.get_config("vit_b16")
+    T = 2
+    xs, ys = wl.make_data(cfg, T, 0)
+    p0 = wl.init_params(cfg, 0)
+    got = run_gpu(cfg, wl.RULE_V2, T, p0, xs, ys)
+    ref = O.train_schedule(cfg, None, [None] * T, [None] * T, wl.RULE_V2, compute=False)
+    assert got["trace"] == ref.trace and got["live"] == ref.live_inputs
+    assert got["stats"]["peak_live_stage_inputs"] == 52
+    assert got["stats"]["peak_activation_bytes"] < 0.7 * got["stats"]["dp_activation_bytes"]
+    p64 = [[np.asarray(a, dtype=np.float64) for a in st] for st in p0]
+    for i in (0, cfg.N - 1):
+        sl = slice(i * cfg.B, (i + 1) * cfg.B)
+        h = np.asarray(xs[0][sl], dtype=np.float64)
+        for j, st in enumerate(cfg.stages):
+            h, _ = OL.stage_forward(st, p64[j], h, ys[0][sl] if j == cfg.S - 1 else None)
+        print("vit_b16 micro-batch %d: loss gpu %.5f oracle %.5f" % (i, got["losses"][0, i], h))
+        assert abs(got["losses"][0, i] - h) <= 2e-2 * abs(h)
+    assert np.isfinite(got["losses"]).all()
+    for j in range(cfg.S):
+        for g, w0 in zip(got["weights"][j], p0[j]):
+            assert np.isfinite(g).all()
+        assert any(np.abs(g - w0).max() > 0 for g, w0 in zip(got["weights"][j], p0[j]))
+

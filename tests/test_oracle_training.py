@@ -31,7 +31,7 @@ def _close(a, b, tol=1e-10):
     return O.max_rel_err(a, b) <= tol
 
 
-@pytest.mark.parametrize("name", ["mlp_mini", "mlp_odd", "resnet18_mini", "vit_mini"])
+@pytest.mark.parametrize("name", ["mlp_mini", "mlp_odd", "resnet18_mini", "vit_mini", "vit_odd"])
 @pytest.mark.parametrize("rule", RULES)
 def test_equation_oracle_equals_timeline_oracle(name, rule):
     """Eq. (CDP) with the closed-form selector == tick-by-tick execution with the ring."""
