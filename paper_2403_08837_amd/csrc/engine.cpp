@@ -743,7 +743,7 @@ int launch_level(cdp_ctx* c, std::vector<Item>& items) {
       case IT_MAXPOOL_B:
         HIP_TRY(c, launch_maxpool_bwd(it.p0, it.p1, it.p2, it.i[0], it.i[1], it.i[2], it.i[3], it.i[4], it.i[5], it.i[6],
                                       it.i[7], it.p3, it.n0, dt, c->stream));
-        c->stats.kernel_launches++;  // two kernels
+        c->stats.kernel_launches += 2;  // three kernels
         break;
       case IT_GAP_F:
         HIP_TRY(c, launch_gap_fwd(it.p0, it.p2, it.i[0], it.i[1], it.i[2], dt, c->stream));
@@ -755,7 +755,7 @@ int launch_level(cdp_ctx* c, std::vector<Item>& items) {
       case IT_LN_B:
         HIP_TRY(c, launch_layernorm_bwd(it.p0, it.p1, it.p5, static_cast<const float*>(it.p3), it.p2, static_cast<float*>(it.p4),
                                         static_cast<float*>(it.p6), static_cast<float*>(it.p7), it.i[0], it.i[1], dt, c->stream));
-        c->stats.kernel_launches++;  // two kernels
+        c->stats.kernel_launches += 2;  // three kernels
         break;
       case IT_GELU_F:
         HIP_TRY(c, launch_gelu_fwd(it.p0, it.p2, it.n0, dt, c->stream));

@@ -210,8 +210,8 @@ hipError_t launch_gap_bwd(const void* x, const void* dy, void* dx, int B, int HW
                           int dtype, hipStream_t stream);
 // ViT-shaped stages (transformer_kernels.hip).  LayerNorm over the C channels of `rows` rows
 // (C <= 1024), fp32 gamma / beta; the backward adds `add` (may be NULL) to dx and adds d gamma /
-// d beta to the running sums Ggamma / Gbeta through per-workgroup partial sums in `workspace`
-// (layernorm_bwd_workspace_bytes) and a small fold kernel.
+// d beta to the running sums Ggamma / Gbeta through row statistics and per-workgroup partial
+// sums in `workspace` (layernorm_bwd_workspace_bytes) and a small fold kernel.
 hipError_t launch_layernorm_fwd(const void* x, const float* gamma, const float* beta, void* y, int rows, int C, int dtype,
                                 hipStream_t stream);
 int64_t layernorm_bwd_workspace_bytes(int rows, int C);

@@ -79,99 +79,108 @@ __global__ __launch_bounds__(256) void layernorm_fwd_kernel(const T* __restrict_
 
 // Backward: with xh = (x - mean) * rstd and g = dy * gamma,
 //   dx = rstd * (g - mean(g) - xh * mean(g * xh)) (+ add), dgamma += sum dy * xh, dbeta += sum dy.
-// A workgroup walks LN_ROWS_PER_WG rows (16 per wavefront); the column sums are kept per lane,
-// combined over the four wavefronts in LDS and written as one partial row per workgroup.
+// Three kernels: the row pass (one wavefront per row, like the forward; leaves mean and rstd of
+// every row in `stats`), the column pass (a workgroup sums LN_ROWS_PER_WG rows with threads
+// owning columns, no cross-lane traffic, one partial row per workgroup) and the fold of the
+// partial rows into the running sums.  Device-wide atomics on these small hot vectors, or a
+// row pass that also carries the column sums, cost several times the whole pass.
 constexpr int LN_ROWS_PER_WG = 32;
 template <typename T>
-__global__ __launch_bounds__(256) void layernorm_bwd_kernel(const T* __restrict__ x, const T* __restrict__ dy,
-                                                            const T* __restrict__ add, const float* __restrict__ gamma,
-                                                            T* __restrict__ dx, float* __restrict__ part, int rows, int C) {
-  __shared__ float red[2][4][64 * LN_MAX_PER_LANE];
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  float dg[LN_MAX_PER_LANE], db[LN_MAX_PER_LANE], gam[LN_MAX_PER_LANE];
+__global__ __launch_bounds__(256) void layernorm_bwd_rows_kernel(const T* __restrict__ x, const T* __restrict__ dy,
+                                                                 const T* __restrict__ add, const float* __restrict__ gamma,
+                                                                 T* __restrict__ dx, float* __restrict__ stats, int rows, int C) {
+  const int lane = threadIdx.x & 63, row = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (row >= rows) return;
+  const int64_t base = (int64_t)row * C;
+  float v[LN_MAX_PER_LANE], g[LN_MAX_PER_LANE];
+  float s = 0.f;
 #pragma unroll
   for (int q = 0; q < LN_MAX_PER_LANE; ++q) {
-    dg[q] = 0.f;
-    db[q] = 0.f;
     const int c = lane + 64 * q;
-    gam[q] = c < C ? gamma[c] : 0.f;
+    v[q] = c < C ? tld<T>(x, base + c) : 0.f;
+    g[q] = c < C ? tld<T>(dy, base + c) * gamma[c] : 0.f;
+    s += v[q];
   }
-  for (int k = 0; k < LN_ROWS_PER_WG / 4; ++k) {
-    const int row = blockIdx.x * LN_ROWS_PER_WG + wave * (LN_ROWS_PER_WG / 4) + k;
-    if (row >= rows) break;
-    const int64_t base = (int64_t)row * C;
-    float v[LN_MAX_PER_LANE], d[LN_MAX_PER_LANE];
-    float s = 0.f;
-#pragma unroll
-    for (int q = 0; q < LN_MAX_PER_LANE; ++q) {
-      const int c = lane + 64 * q;
-      v[q] = c < C ? tld<T>(x, base + c) : 0.f;
-      d[q] = c < C ? tld<T>(dy, base + c) : 0.f;
-      s += v[q];
-    }
-    const float mean = wsum(s) / (float)C;
-    float ss = 0.f;
-#pragma unroll
-    for (int q = 0; q < LN_MAX_PER_LANE; ++q) {
-      const int c = lane + 64 * q;
-      const float t = c < C ? v[q] - mean : 0.f;
-      ss += t * t;
-    }
-    const float rstd = rsqrtf(wsum(ss) / (float)C + LN_EPS);
-    float sg = 0.f, sgx = 0.f;
-#pragma unroll
-    for (int q = 0; q < LN_MAX_PER_LANE; ++q) {
-      const int c = lane + 64 * q;
-      const float xh = c < C ? (v[q] - mean) * rstd : 0.f;
-      const float g = d[q] * gam[q];
-      v[q] = xh;
-      sg += g;
-      sgx += g * xh;
-      dg[q] += d[q] * xh;
-      db[q] += d[q];
-    }
-    const float mg = wsum(sg) / (float)C, mgx = wsum(sgx) / (float)C;
-#pragma unroll
-    for (int q = 0; q < LN_MAX_PER_LANE; ++q) {
-      const int c = lane + 64 * q;
-      if (c < C) {
-        float r = rstd * (d[q] * gam[q] - mg - v[q] * mgx);
-        if (add) r += tld<T>(add, base + c);
-        tst<T>(dx, base + c, r);
-      }
-    }
-  }
+  const float mean = wsum(s) / (float)C;
+  float ss = 0.f;
 #pragma unroll
   for (int q = 0; q < LN_MAX_PER_LANE; ++q) {
-    red[0][wave][lane + 64 * q] = dg[q];
-    red[1][wave][lane + 64 * q] = db[q];
+    const int c = lane + 64 * q;
+    const float t = c < C ? v[q] - mean : 0.f;
+    ss += t * t;
   }
-  __syncthreads();
-  // per-workgroup partial sums; layernorm_fold_kernel adds them to the accumulators (device-wide
-  // atomics on these small hot vectors cost far more than the whole pass)
-  float* pg = part + (int64_t)blockIdx.x * 2 * C;
-  for (int c = threadIdx.x; c < C; c += 256) {
-    pg[c] = (red[0][0][c] + red[0][1][c]) + (red[0][2][c] + red[0][3][c]);
-    pg[C + c] = (red[1][0][c] + red[1][1][c]) + (red[1][2][c] + red[1][3][c]);
+  const float rstd = rsqrtf(wsum(ss) / (float)C + LN_EPS);
+  float sg = 0.f, sgx = 0.f;
+#pragma unroll
+  for (int q = 0; q < LN_MAX_PER_LANE; ++q) {
+    const int c = lane + 64 * q;
+    v[q] = c < C ? (v[q] - mean) * rstd : 0.f;
+    sg += g[q];
+    sgx += g[q] * v[q];
+  }
+  const float mg = wsum(sg) / (float)C, mgx = wsum(sgx) / (float)C;
+#pragma unroll
+  for (int q = 0; q < LN_MAX_PER_LANE; ++q) {
+    const int c = lane + 64 * q;
+    if (c < C) {
+      float r = rstd * (g[q] - mg - v[q] * mgx);
+      if (add) r += tld<T>(add, base + c);
+      tst<T>(dx, base + c, r);
+    }
+  }
+  if (lane == 0) {
+    stats[2 * (int64_t)row] = mean;
+    stats[2 * (int64_t)row + 1] = rstd;
   }
 }
 
-__global__ void layernorm_fold_kernel(const float* __restrict__ part, int n_part, float* __restrict__ Ggamma,
-                                      float* __restrict__ Gbeta, int C) {
-  const int c = blockIdx.x * blockDim.x + threadIdx.x;
-  if (c >= 2 * C) return;
-  float s0 = 0.f, s1 = 0.f, s2 = 0.f, s3 = 0.f;
-  int k = 0;
-  for (; k + 3 < n_part; k += 4) {
-    s0 += part[(int64_t)k * 2 * C + c];
-    s1 += part[(int64_t)(k + 1) * 2 * C + c];
-    s2 += part[(int64_t)(k + 2) * 2 * C + c];
-    s3 += part[(int64_t)(k + 3) * 2 * C + c];
+template <typename T>
+__global__ __launch_bounds__(256) void layernorm_bwd_cols_kernel(const T* __restrict__ x, const T* __restrict__ dy,
+                                                                 const float* __restrict__ stats, float* __restrict__ part,
+                                                                 int rows, int C) {
+  __shared__ float st[2 * LN_ROWS_PER_WG];
+  const int r0 = blockIdx.x * LN_ROWS_PER_WG;
+  const int nr = min(LN_ROWS_PER_WG, rows - r0);
+  if (threadIdx.x < 2 * nr) st[threadIdx.x] = stats[2 * (int64_t)r0 + threadIdx.x];
+  __syncthreads();
+  float* pg = part + (int64_t)blockIdx.x * 2 * C;
+  for (int c = threadIdx.x; c < C; c += 256) {
+    float dg = 0.f, db = 0.f;
+    const T* xp = x + (int64_t)r0 * C + c;
+    const T* dp = dy + (int64_t)r0 * C + c;
+#pragma unroll 8
+    for (int r = 0; r < nr; ++r) {
+      const float d = tld<T>(dp, (int64_t)r * C);
+      dg += d * (tld<T>(xp, (int64_t)r * C) - st[2 * r]) * st[2 * r + 1];
+      db += d;
+    }
+    pg[c] = dg;
+    pg[C + c] = db;
   }
-  for (; k < n_part; ++k) s0 += part[(int64_t)k * 2 * C + c];
-  const float s = (s0 + s1) + (s2 + s3);
-  if (c < C) Ggamma[c] += s;
-  else Gbeta[c - C] += s;
+}
+
+// Column sums of the n_part partial rows (2C wide): 64 columns x 4 row groups per workgroup.
+__global__ __launch_bounds__(256) void layernorm_fold_kernel(const float* __restrict__ part, int n_part, float* __restrict__ Ggamma,
+                                                             float* __restrict__ Gbeta, int C) {
+  __shared__ float red[4][64];
+  const int col = threadIdx.x & 63, grp = threadIdx.x >> 6;
+  const int c = blockIdx.x * 64 + col;
+  float s0 = 0.f, s1 = 0.f;
+  if (c < 2 * C) {
+    int k = grp;
+    for (; k + 4 < n_part; k += 8) {
+      s0 += part[(int64_t)k * 2 * C + c];
+      s1 += part[(int64_t)(k + 4) * 2 * C + c];
+    }
+    if (k < n_part) s0 += part[(int64_t)k * 2 * C + c];
+  }
+  red[grp][col] = s0 + s1;
+  __syncthreads();
+  if (grp == 0 && c < 2 * C) {
+    const float s = (red[0][col] + red[1][col]) + (red[2][col] + red[3][col]);
+    if (c < C) Ggamma[c] += s;
+    else Gbeta[c - C] += s;
+  }
 }
 
 hipError_t launch_layernorm_fwd(const void* x, const float* gamma, const float* beta, void* y, int rows, int C, int dtype,
@@ -181,52 +190,96 @@ hipError_t launch_layernorm_fwd(const void* x, const float* gamma, const float* 
                                           static_cast<const T*>(x), gamma, beta, static_cast<T*>(y), rows, C));
   return hipGetLastError();
 }
+static int64_t ln_stats_bytes(int rows) { return ((int64_t)rows * 8 + 255) / 256 * 256; }
 int64_t layernorm_bwd_workspace_bytes(int rows, int C) {
-  return (int64_t)((rows + LN_ROWS_PER_WG - 1) / LN_ROWS_PER_WG) * 2 * C * 4;
+  return ln_stats_bytes(rows) + (int64_t)((rows + LN_ROWS_PER_WG - 1) / LN_ROWS_PER_WG) * 2 * C * 4;
 }
 hipError_t launch_layernorm_bwd(const void* x, const void* dy, const void* add, const float* gamma, void* dx, float* Ggamma,
                                 float* Gbeta, float* workspace, int rows, int C, int dtype, hipStream_t stream) {
   if (rows <= 0 || C <= 0 || C > 64 * LN_MAX_PER_LANE || !workspace) return hipErrorInvalidValue;
   const int wgs = (rows + LN_ROWS_PER_WG - 1) / LN_ROWS_PER_WG;
-  CDP_TDISPATCH(dtype, hipLaunchKernelGGL((layernorm_bwd_kernel<T>), dim3(wgs), dim3(256), 0, stream, static_cast<const T*>(x),
-                                          static_cast<const T*>(dy), static_cast<const T*>(add), gamma, static_cast<T*>(dx),
-                                          workspace, rows, C));
+  float* stats = workspace;
+  float* part = workspace + ln_stats_bytes(rows) / 4;
+  CDP_TDISPATCH(dtype, hipLaunchKernelGGL((layernorm_bwd_rows_kernel<T>), dim3((rows + 3) / 4), dim3(256), 0, stream,
+                                          static_cast<const T*>(x), static_cast<const T*>(dy), static_cast<const T*>(add), gamma,
+                                          static_cast<T*>(dx), stats, rows, C));
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  hipLaunchKernelGGL(layernorm_fold_kernel, dim3((2 * C + 255) / 256), dim3(256), 0, stream, workspace, wgs, Ggamma, Gbeta, C);
+  CDP_TDISPATCH(dtype, hipLaunchKernelGGL((layernorm_bwd_cols_kernel<T>), dim3(wgs), dim3(256), 0, stream, static_cast<const T*>(x),
+                                          static_cast<const T*>(dy), stats, part, rows, C));
+  if ((e = hipGetLastError()) != hipSuccess) return e;
+  hipLaunchKernelGGL(layernorm_fold_kernel, dim3((2 * C + 63) / 64), dim3(256), 0, stream, part, wgs, Ggamma, Gbeta, C);
   return hipGetLastError();
 }
 
 // ---------------------------------------------------------------------------------
 // GELU, exact form: y = x * Phi(x);  dx = dy * (Phi(x) + x * phi(x)).
+// The first n4 groups of four elements go through 8- / 16-byte accesses, the rest one by one.
+__device__ __forceinline__ void t_ld4(const uint16_t* p, int64_t g, float* v) {
+  const uint2 u = reinterpret_cast<const uint2*>(p)[g];
+  v[0] = __uint_as_float(u.x << 16); v[1] = __uint_as_float(u.x & 0xffff0000u);
+  v[2] = __uint_as_float(u.y << 16); v[3] = __uint_as_float(u.y & 0xffff0000u);
+}
+__device__ __forceinline__ void t_ld4(const float* p, int64_t g, float* v) {
+  const float4 u = reinterpret_cast<const float4*>(p)[g];
+  v[0] = u.x; v[1] = u.y; v[2] = u.z; v[3] = u.w;
+}
+__device__ __forceinline__ void t_st4(uint16_t* p, int64_t g, const float* v) {
+  uint2 u;
+  u.x = (uint32_t)t_f2bf(v[0]) | ((uint32_t)t_f2bf(v[1]) << 16);
+  u.y = (uint32_t)t_f2bf(v[2]) | ((uint32_t)t_f2bf(v[3]) << 16);
+  reinterpret_cast<uint2*>(p)[g] = u;
+}
+__device__ __forceinline__ void t_st4(float* p, int64_t g, const float* v) {
+  reinterpret_cast<float4*>(p)[g] = make_float4(v[0], v[1], v[2], v[3]);
+}
+__device__ __forceinline__ float gelu_f(float v) { return 0.5f * v * (1.f + erff(v * 0.70710678118654752f)); }
+__device__ __forceinline__ float gelu_df(float v) {
+  return 0.5f * (1.f + erff(v * 0.70710678118654752f)) + v * 0.3989422804014327f * expf(-0.5f * v * v);
+}
+
 template <typename T>
-__global__ void gelu_fwd_kernel(const T* __restrict__ x, T* __restrict__ y, int64_t n) {
-  for (int64_t i = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x) {
-    const float v = tld<T>(x, i);
-    tst<T>(y, i, 0.5f * v * (1.f + erff(v * 0.70710678118654752f)));
+__global__ void gelu_fwd_kernel(const T* __restrict__ x, T* __restrict__ y, int64_t n, int64_t n4) {
+  const int64_t t0 = blockIdx.x * (int64_t)blockDim.x + threadIdx.x, step = (int64_t)gridDim.x * blockDim.x;
+  for (int64_t g = t0; g < n4; g += step) {
+    float v[4];
+    t_ld4(x, g, v);
+#pragma unroll
+    for (int e = 0; e < 4; ++e) v[e] = gelu_f(v[e]);
+    t_st4(y, g, v);
   }
+  for (int64_t i = 4 * n4 + t0; i < n; i += step) tst<T>(y, i, gelu_f(tld<T>(x, i)));
 }
 template <typename T>
-__global__ void gelu_bwd_kernel(const T* __restrict__ x, const T* __restrict__ dy, T* __restrict__ dx, int64_t n) {
-  for (int64_t i = blockIdx.x * (int64_t)blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x) {
-    const float v = tld<T>(x, i);
-    const float cdf = 0.5f * (1.f + erff(v * 0.70710678118654752f));
-    const float pdf = 0.3989422804014327f * expf(-0.5f * v * v);
-    tst<T>(dx, i, tld<T>(dy, i) * (cdf + v * pdf));
+__global__ void gelu_bwd_kernel(const T* __restrict__ x, const T* __restrict__ dy, T* __restrict__ dx, int64_t n, int64_t n4) {
+  const int64_t t0 = blockIdx.x * (int64_t)blockDim.x + threadIdx.x, step = (int64_t)gridDim.x * blockDim.x;
+  for (int64_t g = t0; g < n4; g += step) {
+    float v[4], d[4];
+    t_ld4(x, g, v);
+    t_ld4(dy, g, d);
+#pragma unroll
+    for (int e = 0; e < 4; ++e) v[e] = d[e] * gelu_df(v[e]);
+    t_st4(dx, g, v);
   }
+  for (int64_t i = 4 * n4 + t0; i < n; i += step) tst<T>(dx, i, tld<T>(dy, i) * gelu_df(tld<T>(x, i)));
 }
+static bool aligned16(const void* p) { return reinterpret_cast<uintptr_t>(p) % 16 == 0; }
 hipError_t launch_gelu_fwd(const void* x, void* y, int64_t n, int dtype, hipStream_t stream) {
   if (n <= 0) return hipErrorInvalidValue;
-  const int blocks = (int)((n + 1023) / 1024 < (1 << 20) ? (n + 1023) / 1024 : (1 << 20));
+  const int64_t n4 = aligned16(x) && aligned16(y) ? n / 4 : 0;
+  const int64_t want = (n4 + (n - 4 * n4) + 255) / 256;
+  const int blocks = (int)(want < (1 << 20) ? want : (1 << 20));
   CDP_TDISPATCH(dtype, hipLaunchKernelGGL((gelu_fwd_kernel<T>), dim3(blocks), dim3(256), 0, stream, static_cast<const T*>(x),
-                                          static_cast<T*>(y), n));
+                                          static_cast<T*>(y), n, n4));
   return hipGetLastError();
 }
 hipError_t launch_gelu_bwd(const void* x, const void* dy, void* dx, int64_t n, int dtype, hipStream_t stream) {
   if (n <= 0) return hipErrorInvalidValue;
-  const int blocks = (int)((n + 1023) / 1024 < (1 << 20) ? (n + 1023) / 1024 : (1 << 20));
+  const int64_t n4 = aligned16(x) && aligned16(dy) && aligned16(dx) ? n / 4 : 0;
+  const int64_t want = (n4 + (n - 4 * n4) + 255) / 256;
+  const int blocks = (int)(want < (1 << 20) ? want : (1 << 20));
   CDP_TDISPATCH(dtype, hipLaunchKernelGGL((gelu_bwd_kernel<T>), dim3(blocks), dim3(256), 0, stream, static_cast<const T*>(x),
-                                          static_cast<const T*>(dy), static_cast<T*>(dx), n));
+                                          static_cast<const T*>(dy), static_cast<T*>(dx), n, n4));
   return hipGetLastError();
 }
 
