@@ -77,20 +77,29 @@ CONV_SHAPES = [  # ResNet-50 layers of one micro-batch of 32, and two large comp
     ("s4 3x3 512->512 7x7", 32, 7, 7, 512, 512, 3, 1, 1), ("s4 1x1 512->2048 7x7", 32, 7, 7, 512, 2048, 1, 1, 0),
     ("large 1x1 2048->2048, 25088 rows", 32, 28, 28, 2048, 2048, 1, 1, 0),
     ("large 3x3 512->512, 25088 rows", 32, 28, 28, 512, 512, 3, 1, 1),
+    # token-wise linear maps of a ViT-B/16-shaped block, one micro-batch of 32 x 196 tokens
+    ("vit qkv 768->2304, 6272 rows", 32, 14, 14, 768, 2304, 1, 1, 0), ("vit proj 768->768, 6272 rows", 32, 14, 14, 768, 768, 1, 1, 0),
+    ("vit fc1 768->3072, 6272 rows", 32, 14, 14, 768, 3072, 1, 1, 0), ("vit fc2 3072->768, 6272 rows", 32, 14, 14, 3072, 768, 1, 1, 0),
 ]
 
 
 def main():
-    argparse.ArgumentParser(description=__doc__).parse_args()
+    ap = argparse.ArgumentParser(description=__doc__)
+    ap.add_argument("--only", default="", help="run only the shapes whose label contains this text")
+    args = ap.parse_args()
     if not torch.cuda.is_available():
         raise SystemExit("kernel_bench needs a GPU")
     torch.zeros(1).cuda()
     print("# Linear contractions (cdp_k_gemm, bf16): us, TFLOP/s, GB/s, fraction of the HBM peak of %.0f GB/s" % HBM_PEAK)
     for label, M, N, K, shape in LINEAR_SHAPES:
+        if args.only not in label:
+            continue
         us, tf, gb = linear(M, N, K, shape)
         print("%-42s %8.1f us %7.1f TFLOP/s %7.0f GB/s  hbm %.2f" % (label, us, tf, gb, gb / HBM_PEAK), flush=True)
     print("# Convolution passes (cdp_k_conv, bf16): us, TFLOP/s (fraction of %.0f), GB/s (fraction of %.0f)" % (MFMA_PEAK, HBM_PEAK))
     for s in CONV_SHAPES:
+        if args.only not in s[0]:
+            continue
         parts = []
         for which, name in ((0, "fwd"), (1, "dgrad"), (2, "wgrad")):
             us, tf, gb = conv(which, *s[1:])
