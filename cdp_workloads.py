@@ -325,6 +325,12 @@ def get_config(name: str) -> Config:
     if name == "mlp_odd":        # odd delay d=3, ragged sizes, stem + 2-layer head
         return Config("mlp_odd", _mlp(40, 72, 6, 7, stem=True), (40,), 7, N=4, B=5,
                       dtype=F32, lr=0.05, steps=6)
+    if name == "mlp_longk":      # long, ragged reduction in the stem (1100 inputs), 40-wide layers, B = 5
+        return Config("mlp_longk", _mlp(1100, 40, 4, 7, stem=True), (1100,), 7, N=4, B=5,
+                      dtype=F32, lr=0.05, steps=4)
+    if name == "mlp_longk_bf16":  # 2120 inputs: 34 slabs of 64, the last one partial
+        return Config("mlp_longk_bf16", _mlp(2120, 136, 4, 10, stem=True), (2120,), 10, N=4, B=24,
+                      dtype=BF16, lr=0.02, steps=4)
     if name == "cfg2_mini":      # bf16, several tiles + ragged tail
         return Config("cfg2_mini", _mlp(200, 136, 4, 10, stem=True), (200,), 10, N=4, B=24,
                       dtype=BF16, lr=0.05, steps=8)

@@ -114,7 +114,7 @@ struct cdp_ctx {
   char* arena = nullptr;
   int64_t arena_bytes = 0;
   std::vector<StageState> st;
-  int64_t labels_off = 0, loss_off = 0;
+  int64_t labels_off = 0, loss_off = 0, thin_ws_off = 0;
   Pool pool;
   int64_t scratch_base = 0, scratch_cap = -1, scratch_bump = 0;  // per-tick workspace (im2col buffers, partial sums)
   std::vector<std::vector<VisitRecord>> rec;  // [mb][stage]
@@ -177,7 +177,7 @@ bool scratch_alloc(cdp_ctx* c, int64_t bytes, Block* b) {
 // --------------------------------------------------------------------------- layouts
 struct StaticLayout {
   std::vector<StageState> st;
-  int64_t labels_off, loss_off, pool_base, weight_bytes;
+  int64_t labels_off, loss_off, thin_ws_off, pool_base, weight_bytes;
 };
 
 StaticLayout static_layout(const ModelPlan& plan, int N, int B, int groups, bool velocity) {
@@ -196,6 +196,7 @@ StaticLayout static_layout(const ModelPlan& plan, int N, int B, int groups, bool
   L.weight_bytes = off;
   L.labels_off = off; off = align_up(off + (int64_t)N * B * 4, 256);
   L.loss_off = off; off = align_up(off + (int64_t)LOSS_LOG_STEPS * N * groups * 4, 256);
+  L.thin_ws_off = off; off = align_up(off + THIN_WS_BYTES, 256);
   L.pool_base = off;
   return L;
 }
@@ -641,6 +642,8 @@ int launch_level(cdp_ctx* c, std::vector<Item>& items) {
       batch.n = (int)std::min<size_t>(GEMM_MAX_PROBS, sel.size() - k);
       batch.n_upd = 0;
       batch.copy_tiles = 0;
+      batch.thin_ws = c->fptr(c->thin_ws_off);  // zeroed at init, left zero by every launch
+      batch.thin_cnt = reinterpret_cast<unsigned int*>(c->fptr(c->thin_ws_off) + (int64_t)THIN_WS_SLOTS * 1024);
       if (key == LC_LINEAR && k == 0) {
         // a micro-batch that starts in this tick: its staging rides on this launch
         for (Item& si : items)
@@ -1032,7 +1035,7 @@ int make_ctx(cdp_ctx** out, const cdp_stage_desc* stages, int n_stages, int N, i
   c->momentum = opts->momentum; c->weight_decay = opts->weight_decay;
   StaticLayout L = static_layout(c->plan, N, B, c->groups, c->momentum != 0.f);
   c->st = L.st;
-  c->labels_off = L.labels_off; c->loss_off = L.loss_off;
+  c->labels_off = L.labels_off; c->loss_off = L.loss_off; c->thin_ws_off = L.thin_ws_off;
   c->pool.base = L.pool_base;
   c->pool.cap = c->dry ? -1 : c->arena_bytes - L.pool_base;
   c->rec.assign(N, std::vector<VisitRecord>(n_stages));

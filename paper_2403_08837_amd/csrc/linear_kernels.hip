@@ -59,6 +59,11 @@ __device__ __forceinline__ int xcd_remap(int bid, int total) {
   return (bid & 7) * chunk + (bid >> 3);
 }
 
+// Rows of a weight-gradient tile that takes the SGD step (tiles_n is set).
+__host__ __device__ __forceinline__ int dw_update_rows(const GemmProb& p) {
+  return ((p.M + 63) / 64) * p.tiles_n < 512 ? 32 : 64;
+}
+
 __device__ __forceinline__ int find_problem(const GemmBatch& batch, int tile) {
   int pi = 0;
   for (int q = 1; q < batch.n; ++q)
@@ -249,10 +254,14 @@ __device__ __forceinline__ void skinny_tile(const GemmProb& P, int tile, unsigne
 // giving every lane a 128-byte run of its own).  The k-loop has no barrier; the partial tiles
 // meet once in LDS, each wave finishing 8 of the 32 rows.
 template <typename T>
-__device__ __forceinline__ void thin_tile(const GemmProb& P, int tile, unsigned char* smem) {
+__device__ __forceinline__ void thin_tile(const GemmBatch& batch, const GemmProb& P, int tile, unsigned char* smem) {
   using E = LT<T>;
   constexpr int VEC = E::VEC, CH = 4, SLAB = 2 * CH * VEC;  // chunk c of lane (row, g) holds k = 2*VEC*c + VEC*g ...
-  const int col0 = (tile - P.tile_begin) * 32;
+  // a long reduction is shared by P.splits workgroups (neighbours in the tile list), each
+  // taking a contiguous range of slabs; the one that finishes last adds the partial tiles
+  const int ks = P.splits, local = tile - P.tile_begin;
+  const int split = local % ks;
+  const int col0 = (local / ks) * 32;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int r31 = lane & 31, g = lane >> 5;
   // rows past the end are read from the last valid row: they only reach outputs that are not stored
@@ -261,9 +270,10 @@ __device__ __forceinline__ void thin_tile(const GemmProb& P, int tile, unsigned 
   const T* __restrict__ ap = static_cast<const T*>(P.A) + a_off;
   const float* __restrict__ apf = static_cast<const float*>(P.A) + a_off;
   const T* __restrict__ bp = static_cast<const T*>(P.B) + (int64_t)min(col0 + r31, P.N - 1) * P.ldb + g * VEC;
-  const int nslab = (P.K + SLAB - 1) / SLAB;
-  const int s0 = (int)(((unsigned)tile * 2654435761u) >> 8) % nslab;
-  auto slab_k = [&](int i) { const int q = s0 + i; return (q >= nslab ? q - nslab : q) * SLAB; };
+  const int nslab_all = (P.K + SLAB - 1) / SLAB, per = (nslab_all + ks - 1) / ks;
+  const int sb = split * per, nslab = max(0, min(nslab_all, sb + per) - sb);
+  const int s0 = nslab > 0 ? (int)(((unsigned)tile * 2654435761u) >> 8) % nslab : 0;
+  auto slab_k = [&](int i) { const int q = s0 + i; return (sb + (q >= nslab ? q - nslab : q)) * SLAB; };
 
   uint4 ra[2][CH], rb[2][CH];
   auto fetch = [&](uint4* qa, uint4* qb, int k0) {
@@ -318,10 +328,44 @@ __device__ __forceinline__ void thin_tile(const GemmProb& P, int tile, unsigned 
   const int c = col0 + r31;
   const float bias = (P.epi == EPI_FWD && P.aux0 != nullptr && c < P.N) ? static_cast<const float*>(P.aux0)[c] : 0.f;
   const bool ce = (P.flags & GF_CE) != 0;
+  float vals[4];
 #pragma unroll
   for (int q = 0; q < 4; ++q) {
     const int v = wave * 4 + q;
-    const float val = (red[v * 64 + lane] + red[(16 + v) * 64 + lane]) + (red[(32 + v) * 64 + lane] + red[(48 + v) * 64 + lane]);
+    vals[q] = (red[v * 64 + lane] + red[(16 + v) * 64 + lane]) + (red[(32 + v) * 64 + lane] + red[(48 + v) * 64 + lane]);
+  }
+  if (ks > 1) {
+    // partial tile -> workspace slot of this workgroup; the last of the ks workgroups to get
+    // here (counter of the output tile) sums the slots in a fixed order and finishes the tile
+    // Partials and counter are device-scope atomics (they bypass the per-XCD L2), ordered by
+    // waiting for the stores to complete; a device-scope fence here would write back every
+    // dirty L2 line of the weight-gradient tiles that share the launch.
+    float* slot = batch.thin_ws + (int64_t)tile * 1024;
+#pragma unroll
+    for (int q = 0; q < 4; ++q)
+      __hip_atomic_store(slot + (wave * 4 + q) * 64 + lane, vals[q], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");  // the stores above have completed
+    __syncthreads();  // also: every wave has read its share of `red`
+    unsigned int* cnt = batch.thin_cnt + (tile - split);
+    if (tid == 0) {
+      const unsigned int arrived = atomicAdd(cnt, 1u);
+      red[0] = arrived == (unsigned)(ks - 1) ? 1.f : 0.f;
+      if (arrived == (unsigned)(ks - 1)) atomicExch(cnt, 0u);  // ready for the next launch
+    }
+    __syncthreads();
+    if (red[0] == 0.f) return;
+    const float* first = batch.thin_ws + (int64_t)(tile - split) * 1024;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      float sum = 0.f;
+      for (int sp = 0; sp < ks; ++sp)
+        sum += __hip_atomic_load(first + (int64_t)sp * 1024 + (wave * 4 + q) * 64 + lane, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      vals[q] = sum;
+    }
+  }
+#pragma unroll
+  for (int q = 0; q < 4; ++q) {
+    const float val = vals[q];
     const int r = wave * 8 + g * 4 + q;
     if (!ce) {
       if (r < P.M && c < P.N) store_result<T>(P, r, c, val, bias);
@@ -351,18 +395,20 @@ __device__ __forceinline__ void thin_tile(const GemmProb& P, int tile, unsigned 
 }
 
 // ---------------------------------------------------------------------------------
-// dw_kernel: G tile of 64 (rows n) x 128 (cols k); wave w owns columns [32w, 32w+32).
+// dw_kernel: G tile of TN = 64 (rows n) x 128 (cols k); wave w owns columns [32w, 32w+32).
+// Tiles that also take the SGD step are 32 rows high when the matrix has few of them
+// (dw_update_rows): twice as many workgroups share the longest tiles of the launch.
 // Operand convention of the batch entry: A = dY [Mb][N] (lda = N), B = X [Mb][K]
 // (ldb = K), out = G [N][K] (ldo = K), P.M = N, P.N = K, P.K = Mb (reduction length);
 // aux2 = bias-gradient vector [N] or NULL.
-template <typename T>
+template <typename T, int TN>
 __device__ __forceinline__ void dw_tile(const GemmBatch& batch, const GemmProb& P, int tile, unsigned char* smem) {
   using E = LT<T>;
-  constexpr int TN = 64, TK = 128, MB = 64, VEC = E::VEC;
+  constexpr int TK = 128, MB = 64, VEC = E::VEC, NI2 = TN / 32;
   // LDS pitches (elements): bf16 fragments are read with the transposing LDS read, which wants
   // 32 bytes modulo 128 between consecutive rows; fp32 fragments are plain column reads
   constexpr int PAD = sizeof(T) == 2 ? 16 : 4;
-  constexpr int PD = TN + PAD, PX = TK + PAD;
+  constexpr int PD = 64 + PAD, PX = TK + PAD;  // one pitch for both tile heights
   T* Ds = reinterpret_cast<T*>(smem);
   T* Xs = Ds + MB * PD;
 
@@ -384,9 +430,9 @@ __device__ __forceinline__ void dw_tile(const GemmBatch& batch, const GemmProb& 
   const LinUpdate& U = batch.upd[upd ? P.upd - 1 : 0];
   const bool mom = upd && U.V != nullptr;
   const int gc = k0 + wave * 32 + (lane & 31);
-  float gold[32];
+  float gold[16 * NI2];
 #pragma unroll
-  for (int i = 0; i < 2; ++i)
+  for (int i = 0; i < NI2; ++i)
 #pragma unroll
     for (int v = 0; v < 16; ++v) {
       const int r = n0 + i * 32 + (v >> 2) * 8 + (lane >> 5) * 4 + (v & 3);
@@ -401,9 +447,9 @@ __device__ __forceinline__ void dw_tile(const GemmBatch& batch, const GemmProb& 
       gold[i * 16 + v] = g0;
     }
 
-  v16f_t acc[2];
+  v16f_t acc[NI2];
 #pragma unroll
-  for (int i = 0; i < 2; ++i)
+  for (int i = 0; i < NI2; ++i)
 #pragma unroll
     for (int v = 0; v < 16; ++v) acc[i][v] = 0.f;
   float bsum = 0.f;  // bias gradient of column n0 + tid (threads 0..63 of the first column tile)
@@ -459,14 +505,14 @@ __device__ __forceinline__ void dw_tile(const GemmBatch& batch, const GemmProb& 
       for (int kk = 0; kk < MB; kk += 16) {
         const uint4 bv = frag_tr_bf16(Xs, PX, kk, wave * 32, lane);
 #pragma unroll
-        for (int i = 0; i < 2; ++i) acc[i] = mfma_bf16(frag_tr_bf16(Ds, PD, kk, i * 32, lane), bv, acc[i]);
+        for (int i = 0; i < NI2; ++i) acc[i] = mfma_bf16(frag_tr_bf16(Ds, PD, kk, i * 32, lane), bv, acc[i]);
       }
     } else {
 #pragma unroll 8
       for (int kk = 0; kk < MB; kk += 2) {
         const float bv = Xs[(kk + g) * PX + wave * 32 + l31];
 #pragma unroll
-        for (int i = 0; i < 2; ++i)
+        for (int i = 0; i < NI2; ++i)
           acc[i] = __builtin_amdgcn_mfma_f32_32x32x2f32(Ds[(kk + g) * PD + i * 32 + l31], bv, acc[i], 0, 0, 0);
       }
     }
@@ -478,7 +524,7 @@ __device__ __forceinline__ void dw_tile(const GemmBatch& batch, const GemmProb& 
   if (!upd) {
     // 4. accumulate and write back
 #pragma unroll
-    for (int i = 0; i < 2; ++i)
+    for (int i = 0; i < NI2; ++i)
 #pragma unroll
       for (int v = 0; v < 16; ++v) {
         const int r = n0 + i * 32 + (v >> 2) * 8 + (lane >> 5) * 4 + (v & 3);
@@ -497,7 +543,7 @@ __device__ __forceinline__ void dw_tile(const GemmBatch& batch, const GemmProb& 
   T* Ws = reinterpret_cast<T*>(smem);
   __syncthreads();  // the operand tiles in LDS are no longer read
 #pragma unroll
-  for (int i = 0; i < 2; ++i)
+  for (int i = 0; i < NI2; ++i)
 #pragma unroll
     for (int v = 0; v < 16; ++v) {
       const int rl = i * 32 + (v >> 2) * 8 + (lane >> 5) * 4 + (v & 3);
@@ -613,11 +659,12 @@ __global__ __launch_bounds__(256) void linear_tick_kernel(const GemmBatch batch)
   }
   const GemmProb& P = batch.p[find_problem(batch, tile)];
   if (P.epi == EPI_WGRAD) {
-    dw_tile<T>(batch, P, tile, smem);
+    if (P.upd && dw_update_rows(P) == 32) dw_tile<T, 32>(batch, P, tile, smem);
+    else dw_tile<T, 64>(batch, P, tile, smem);
   } else {
     if constexpr (THIN) {
       if (P.flags & GF_THIN) {
-        thin_tile<T>(P, tile, smem);
+        thin_tile<T>(batch, P, tile, smem);
         return;
       }
     }
@@ -650,6 +697,7 @@ hipError_t launch_linear_tick(GemmBatch& b, int dtype, bool wide, bool allow_thi
   std::stable_partition(wg, b.p + b.n, [](const GemmProb& p) { return p.upd != 0; });
   int total = 0;
   bool any_thin = false;
+  const bool split_ok = b.thin_ws != nullptr && b.thin_cnt != nullptr;
   b.head_tiles = 0;
   b.upd_tiles = 0;
   for (int i = 0; i < b.n; ++i) {
@@ -668,7 +716,11 @@ hipError_t launch_linear_tick(GemmBatch& b, int dtype, bool wide, bool allow_thi
       }
       p.tiles_n = (p.N + 127) / 128;
       tiles = ((p.M + 63) / 64) * p.tiles_n;
-      if (p.upd) b.upd_tiles += tiles;
+      if (p.upd) {
+        const int rows = dw_update_rows(p);
+        tiles = ((p.M + rows - 1) / rows) * p.tiles_n;
+        b.upd_tiles += tiles;
+      }
     } else {
       if (p.a_mode != OP_PLAIN_K || p.b_mode != OP_PLAIN_K) return hipErrorInvalidValue;
       if ((int64_t)p.M * p.lda >= (1ll << 31) || (int64_t)p.N * p.ldb >= (1ll << 31)) return hipErrorInvalidValue;
@@ -684,7 +736,10 @@ hipError_t launch_linear_tick(GemmBatch& b, int dtype, bool wide, bool allow_thi
         p.flags |= GF_THIN;
         any_thin = true;
         p.tiles_n = (p.N + 31) / 32;
-        tiles = p.tiles_n;
+        // reductions of 32 slabs and more are cut into ranges of about 16 slabs (at most 4)
+        const int nslab = (p.K + 8 * vec - 1) / (8 * vec);
+        if (split_ok && nslab >= 32 && !(p.flags & GF_CE)) p.splits = std::min(4, nslab / 16);
+        tiles = p.tiles_n * p.splits;
       } else {
         p.tiles_n = (p.N + bn - 1) / bn;
         tiles = ((p.M + 63) / 64) * p.tiles_n;
@@ -695,6 +750,11 @@ hipError_t launch_linear_tick(GemmBatch& b, int dtype, bool wide, bool allow_thi
     total += tiles;
   }
   b.total_tiles = total;
+  if (b.head_tiles > THIN_WS_SLOTS && split_ok) {
+    // split tiles address the workspace by their tile number: lay the launch out again without them
+    b.thin_ws = nullptr;
+    return launch_linear_tick(b, dtype, wide, allow_thin, stream);
+  }
   if (b.copy_tiles < 0 || (b.copy_tiles > 0 && (!b.sc.x || !b.sc.y || !b.sc.xo || !b.sc.yo || !b.sc.loss || b.sc.n <= 0 ||
                                                 b.copy_tiles != (int)((b.sc.n + STAGE_COPY_ELEMS - 1) / STAGE_COPY_ELEMS))))
     return hipErrorInvalidValue;

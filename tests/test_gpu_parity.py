@@ -401,3 +401,13 @@ def test_vit_b16_full_config_sampled():
             assert np.isfinite(g).all()
         assert any(np.abs(g - w0).max() > 0 for g, w0 in zip(got["weights"][j], p0[j]))
 
+
+@pytest.mark.parametrize("name,rule", [("mlp_longk", wl.RULE_V2), ("mlp_longk", wl.RULE_V1), ("mlp_longk", wl.RULE_DP),
+                                       ("mlp_longk_bf16", wl.RULE_V2)])
+def test_long_reduction_shared_by_several_workgroups(name, rule):
+    """A stem whose reduction is long enough that the thin forward tiles split it over several
+    workgroups (partial tiles in the workspace, the last arrival finishes the tile), with a
+    ragged last slab and ragged output tiles."""
+    cfg = wl.get_config(name)
+    check(cfg, rule, cfg.steps)
+

@@ -42,7 +42,7 @@ def _dry(cfg, rule, T, dp_batched=False):
     return tr
 
 
-@pytest.mark.parametrize("name", ["mlp_mini", "mlp_odd", "cfg1", "cfg2", "cfg3", "cfg4", "cfg5", "resnet50_mini", "vit_mini", "vit_odd",
+@pytest.mark.parametrize("name", ["mlp_mini", "mlp_odd", "cfg1", "cfg2", "cfg3", "cfg4", "cfg5", "resnet50_mini", "vit_mini", "vit_odd", "mlp_longk",
                                   "vit_b16"])
 @pytest.mark.parametrize("rule", RULES)
 def test_trace_and_live_counts_equal_oracle(name, rule):
