@@ -361,6 +361,9 @@ def get_config(name: str) -> Config:
         c = get_config("vit_odd")
         c.name, c.dtype = "vit_odd_bf16", BF16
         return c
+    if name == "vit_long":       # 324 tokens of width 16 in 2 heads
+        return Config("vit_long", _vit(36, 2, 16, 2, 2, 5), (36, 36, 3), 5, N=2, B=2, dtype=F32, lr=0.05, steps=3,
+                      init_gain_last_affine=0.25, init_gain_head=0.2)
     if name == "vit_b16":        # ViT-B/16-shaped: 196 tokens of width 768, 12 heads, 12 block stages
         return Config("vit_b16", _vit(224, 16, 768, 12, 12, 1000), (224, 224, 3), 1000, N=8, B=32, dtype=BF16, lr=0.01,
                       steps=2, init_gain_last_affine=0.25, init_gain_head=0.2, notes="ViT-B/16-shaped")
