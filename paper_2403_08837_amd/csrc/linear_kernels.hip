@@ -248,11 +248,8 @@ __device__ __forceinline__ void skinny_tile(const GemmProb& P, int tile, unsigne
 // ---------------------------------------------------------------------------------
 // thin tile: problems of at most 32 rows whose operands are whole 16-byte chunks.  A
 // workgroup owns 32 x 32 outputs and its four waves split the reduction: wave w takes
-// slabs w, w+4, ...  Nothing is staged: a lane loads its MFMA fragments (16 bytes of its row
-// per reduction step) straight from memory, both halves of the wavefront together covering 32
-// contiguous bytes of each of 32 rows per load instruction (measured: 1.7x the rate of
-// giving every lane a 128-byte run of its own).  The k-loop has no barrier; the partial tiles
-// meet once in LDS, each wave finishing 8 of the 32 rows.
+// slabs w, w+4, ... through a staging block of its own.  The k-loop has no barrier; the
+// partial tiles meet once in LDS, each wave finishing 8 of the 32 rows.
 template <typename T>
 __device__ __forceinline__ void thin_tile(const GemmBatch& batch, const GemmProb& P, int tile, unsigned char* smem) {
   using E = LT<T>;
@@ -264,33 +261,41 @@ __device__ __forceinline__ void thin_tile(const GemmBatch& batch, const GemmProb
   const int col0 = (local / ks) * 32;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int r31 = lane & 31, g = lane >> 5;
-  // rows past the end are read from the last valid row: they only reach outputs that are not stored
   const bool a_f32 = (P.flags & GF_A_F32) != 0;
-  const int64_t a_off = (int64_t)min(r31, P.M - 1) * P.lda + g * VEC;
-  const T* __restrict__ ap = static_cast<const T*>(P.A) + a_off;
-  const float* __restrict__ apf = static_cast<const float*>(P.A) + a_off;
-  const T* __restrict__ bp = static_cast<const T*>(P.B) + (int64_t)min(col0 + r31, P.N - 1) * P.ldb + g * VEC;
+  // Operands reach the MFMA through a staging block of this wavefront's own in LDS: a slab of
+  // 32 rows x 128 bytes per operand is fetched with four load instructions whose lanes cover
+  // whole 128-byte row pieces (lane l: row 8j + l/8, 16-byte chunk l%8), a quarter of the
+  // cache-line requests that loading the fragments directly (32 rows x 32 bytes per
+  // instruction) makes - the request rate of the CU, not latency, bounded the k-loop - then
+  // written to LDS and read back as fragments.  No barrier: the block is private to the
+  // wavefront, whose LDS instructions execute in order.
+  constexpr int LP = SLAB + VEC;  // LDS pitch (elements): 144 bytes, fragment reads of 32 rows hit 32 distinct bank groups
+  T* const stA = reinterpret_cast<T*>(smem) + wave * (2 * 32 * LP);
+  T* const stB = stA + 32 * LP;
+  const int lrow = lane >> 3, lk = (lane & 7) * VEC;
+  // rows past the end are read from the last valid row: they only reach outputs that are not stored
+  const T* __restrict__ Ap = static_cast<const T*>(P.A);
+  const float* __restrict__ Apf = static_cast<const float*>(P.A);
+  const T* __restrict__ Bp = static_cast<const T*>(P.B);
+  int offA[4], offB[4];
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    offA[j] = min(8 * j + lrow, P.M - 1) * P.lda + lk;
+    offB[j] = min(col0 + 8 * j + lrow, P.N - 1) * P.ldb + lk;
+  }
   const int nslab_all = (P.K + SLAB - 1) / SLAB, per = (nslab_all + ks - 1) / ks;
   const int sb = split * per, nslab = max(0, min(nslab_all, sb + per) - sb);
   const int s0 = nslab > 0 ? (int)(((unsigned)tile * 2654435761u) >> 8) % nslab : 0;
   auto slab_k = [&](int i) { const int q = s0 + i; return (sb + (q >= nslab ? q - nslab : q)) * SLAB; };
 
-  uint4 ra[2][CH], rb[2][CH];
+  uint4 ra[2][4], rb[2][4];
   auto fetch = [&](uint4* qa, uint4* qb, int k0) {
-    if (k0 + SLAB <= P.K) {
+    const bool kin = k0 + lk < P.K;  // chunks past K are zero in both operands (last, partial slab)
 #pragma unroll
-      for (int c = 0; c < CH; ++c) {
-        qa[c] = a_f32 ? load_chunk_f32<T>(apf + k0 + 2 * c * VEC) : *reinterpret_cast<const uint4*>(ap + k0 + 2 * c * VEC);
-        qb[c] = *reinterpret_cast<const uint4*>(bp + k0 + 2 * c * VEC);
-      }
-    } else {  // last, partial slab: chunks past K are zero in both operands
-#pragma unroll
-      for (int c = 0; c < CH; ++c) {
-        const bool kin = k0 + (2 * c + g) * VEC < P.K;
-        if (!kin) qa[c] = make_uint4(0, 0, 0, 0);
-        else qa[c] = a_f32 ? load_chunk_f32<T>(apf + k0 + 2 * c * VEC) : *reinterpret_cast<const uint4*>(ap + k0 + 2 * c * VEC);
-        qb[c] = kin ? *reinterpret_cast<const uint4*>(bp + k0 + 2 * c * VEC) : make_uint4(0, 0, 0, 0);
-      }
+    for (int j = 0; j < 4; ++j) {
+      if (!kin) qa[j] = make_uint4(0, 0, 0, 0);
+      else qa[j] = a_f32 ? load_chunk_f32<T>(Apf + offA[j] + k0) : *reinterpret_cast<const uint4*>(Ap + offA[j] + k0);
+      qb[j] = kin ? *reinterpret_cast<const uint4*>(Bp + offB[j] + k0) : make_uint4(0, 0, 0, 0);
     }
   };
   v16f_t acc;
@@ -298,16 +303,32 @@ __device__ __forceinline__ void thin_tile(const GemmBatch& batch, const GemmProb
   for (int v = 0; v < 16; ++v) acc[v] = 0.f;
   auto contract = [&](const uint4* qa, const uint4* qb) {
 #pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      *reinterpret_cast<uint4*>(stA + (8 * j + lrow) * LP + lk) = qa[j];
+      *reinterpret_cast<uint4*>(stB + (8 * j + lrow) * LP + lk) = qb[j];
+    }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    uint4 fa[CH], fb[CH];
+#pragma unroll
+    for (int c = 0; c < CH; ++c) {  // chunk c of lane (row, g) holds k = 2*VEC*c + VEC*g ...
+      fa[c] = *reinterpret_cast<const uint4*>(stA + r31 * LP + 2 * VEC * c + VEC * g);
+      fb[c] = *reinterpret_cast<const uint4*>(stB + r31 * LP + 2 * VEC * c + VEC * g);
+    }
+#pragma unroll
     for (int c = 0; c < CH; ++c) {
       if constexpr (sizeof(T) == 2) {
-        acc = mfma_bf16(qa[c], qb[c], acc);
+        acc = mfma_bf16(fa[c], fb[c], acc);
       } else {
-        acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(qa[c].x), __uint_as_float(qb[c].x), acc, 0, 0, 0);
-        acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(qa[c].y), __uint_as_float(qb[c].y), acc, 0, 0, 0);
-        acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(qa[c].z), __uint_as_float(qb[c].z), acc, 0, 0, 0);
-        acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(qa[c].w), __uint_as_float(qb[c].w), acc, 0, 0, 0);
+        acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(fa[c].x), __uint_as_float(fb[c].x), acc, 0, 0, 0);
+        acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(fa[c].y), __uint_as_float(fb[c].y), acc, 0, 0, 0);
+        acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(fa[c].z), __uint_as_float(fb[c].z), acc, 0, 0, 0);
+        acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(fa[c].w), __uint_as_float(fb[c].w), acc, 0, 0, 0);
       }
     }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();  // the fragments are in registers before the block is written again
   };
   int s = wave;
   if (s < nslab) fetch(ra[0], rb[0], slab_k(s));
@@ -320,6 +341,7 @@ __device__ __forceinline__ void thin_tile(const GemmBatch& batch, const GemmProb
       if (s + 12 < nslab) fetch(ra[1], rb[1], slab_k(s + 12));
     }
   }
+  __syncthreads();  // the partial sums below reuse the staging blocks of all wavefronts
 
   float* red = reinterpret_cast<float*>(smem);  // [4 waves][16][64 lanes]
 #pragma unroll
@@ -621,8 +643,10 @@ __global__ __launch_bounds__(256) void linear_tick_kernel(const GemmBatch batch)
   using E = LT<T>;
   constexpr int SK_BYTES = (64 + BN) * (E::SLAB + E::VEC) * (int)sizeof(T);
   constexpr int DW_BYTES = 64 * (64 + 128 + 2 * (sizeof(T) == 2 ? 16 : 4)) * (int)sizeof(T);
-  static_assert(SK_BYTES >= 4 * 16 * 64 * 4, "the thin tile's partial sums must fit");
-  __shared__ __attribute__((aligned(16))) unsigned char smem[SK_BYTES > DW_BYTES ? SK_BYTES : DW_BYTES];
+  constexpr int TH_BYTES = THIN ? 4 * 2 * 32 * (2 * 4 * E::VEC + E::VEC) * (int)sizeof(T) : 0;  // thin tile: staging blocks of the four wavefronts
+  static_assert(TH_BYTES == 0 || TH_BYTES >= 4 * 16 * 64 * 4, "the thin tile's partial sums must fit");
+  constexpr int SM_BYTES = SK_BYTES > DW_BYTES ? (SK_BYTES > TH_BYTES ? SK_BYTES : TH_BYTES) : (DW_BYTES > TH_BYTES ? DW_BYTES : TH_BYTES);
+  __shared__ __attribute__((aligned(16))) unsigned char smem[SM_BYTES];
   // Tile order: forward / data-gradient tiles, weight-gradient tiles that also take the SGD
   // step, plain weight-gradient tiles.  The first and the last kind are spread over the XCDs
   // separately (each XCD gets a contiguous share of both, so a problem's activations sit in
