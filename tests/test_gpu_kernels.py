@@ -97,3 +97,37 @@ def test_conv_passes_match_oracle(dtype, case):
         assert np.isfinite(g).all(), name
         err = np.abs(g - ref).max() / max(1e-6, np.abs(ref).max())
         assert err <= tol, (name, err)
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("dtype", [wl.F32, wl.BF16])
+@pytest.mark.parametrize("which", ["fwd", "dgrad"])
+def test_conv_gemm_many_tiles(dtype, which):
+    """A 1x1 convolution with 8100 positions and 4040 output (forward) or input (data gradient)
+    channels: about two thousand of the largest tiles (several rounds over the chip), ragged in
+    both directions."""
+    torch = _torch()
+    B, H, W = 4, 45, 45
+    Cin, Cout = (128, 4040) if which == "fwd" else (4040, 128)
+    x = wl.random_normal(5, 1, B * H * W * Cin).reshape(B, H, W, Cin)
+    w = wl.random_normal(5, 2, Cout * Cin).reshape(Cout, 1, 1, Cin) / np.sqrt(Cin)
+    xr, wr = _rnd(x, dtype), _rnd(w, dtype)
+    tdt = torch.bfloat16 if dtype == wl.BF16 else torch.float32
+    tol = 2.0 ** -7 if dtype == wl.BF16 else 1e-5
+    if which == "fwd":
+        ref = L.conv2d_fwd(xr, wr, 1, 0)
+        xd, wd = _dev(x, dtype), _dev(w, dtype)
+        got = torch.full(ref.shape, float("nan"), dtype=tdt, device="cuda")
+        b.cdp_k_conv(dtype, 0, xd.data_ptr(), wd.data_ptr(), got.data_ptr(), B, H, W, Cin, Cout, 1, 1, 0)
+    else:
+        dy = wl.random_normal(5, 3, B * H * W * Cout).reshape(B, H, W, Cout)
+        dyr = _rnd(dy, dtype)
+        ref, _ = L.conv2d_bwd(xr, wr, 1, 0, dyr)
+        dyd, wtd = _dev(dy, dtype), _dev(np.transpose(w, (3, 1, 2, 0)), dtype)
+        got = torch.full(x.shape, float("nan"), dtype=tdt, device="cuda")
+        b.cdp_k_conv(dtype, 1, dyd.data_ptr(), wtd.data_ptr(), got.data_ptr(), B, H, W, Cin, Cout, 1, 1, 0)
+    torch.cuda.synchronize()
+    g = got.float().cpu().numpy().astype(np.float64)
+    assert np.isfinite(g).all()
+    assert np.abs(g - ref).max() / np.abs(ref).max() <= tol
+
