@@ -939,11 +939,23 @@ int run_tick(cdp_ctx* c, const float* x_dev, const int32_t* y_dev) {
       if (c->trace.size() < TRACE_CAP)
         c->trace.push_back(cdp_trace_rec{(int32_t)c->tick, v.i * c->groups + q, (int32_t)v.t, v.j, v.dir, v.version});
   }
+  // The folds of the convolution weight-gradient partial sums feed nothing before the end-of-
+  // tick update: they leave their levels and run together as the last launch of the program.
+  auto defer_folds = [](Program& p) {
+    std::vector<Item> folds;
+    for (auto& level : p) {
+      auto keep = std::stable_partition(level.begin(), level.end(), [](const Item& it) { return it.kind != IT_WREDUCE; });
+      folds.insert(folds.end(), keep, level.end());
+      level.erase(keep, level.end());
+    }
+    if (!folds.empty()) p.push_back(std::move(folds));
+  };
   if (!c->dry) {
     if (c->rule == CDP_RULE_DP) {
       // lock-step: all micro-batches hit the same stage, so passes run one after another
       // (their weight gradients share one accumulator)
       for (auto& p : progs) {
+        defer_folds(p);
         int rc = launch_program(c, p);
         if (rc) return rc;
       }
@@ -955,6 +967,7 @@ int run_tick(cdp_ctx* c, const float* x_dev, const int32_t* y_dev) {
         if (merged.size() < p.size()) merged.resize(p.size());
         for (size_t l = 0; l < p.size(); ++l) merged[l].insert(merged[l].end(), p[l].begin(), p[l].end());
       }
+      defer_folds(merged);
       int rc = launch_program(c, merged);
       if (rc) return rc;
     }
