@@ -84,7 +84,11 @@ __global__ __launch_bounds__(256) void conv_gemm_kernel(const GemmBatch batch) {
 
   const int tile = (int)blockIdx.x;
   const GemmProb& P = batch.p[cfind_problem(batch, tile)];
-  const int local = tile - P.tile_begin;
+  // a long reduction of a small launch is shared by P.splits workgroups (neighbours in the
+  // tile list); the last of them to finish adds the partial tiles and runs the epilogue
+  constexpr bool SPLIT = BM == 64 && BN == 64;  // the launcher splits only launches of the smallest tiles
+  const int ks = SPLIT ? P.splits : 1, split = (tile - P.tile_begin) % ks;
+  const int local = (tile - P.tile_begin) / ks;
   const int tn = local % P.tiles_n, tm = local / P.tiles_n;
   const int row0 = tm * BM, col0 = tn * BN;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -143,7 +147,11 @@ __global__ __launch_bounds__(256) void conv_gemm_kernel(const GemmBatch batch) {
 
   uint4 ra[NA], rb[NB];
   // wavefront-uniform position of the current slab: tap index, channel offset inside the tap
-  int tap = 0, c0 = 0, kh = 0, kw = 0;
+  const int nslab_all = P.K / BK, per = (nslab_all + ks - 1) / ks;
+  const int s_begin = split * per, nslab = max(0, min(nslab_all, s_begin + per) - s_begin);
+  const int kbeg = s_begin * BK;
+  int tap = kbeg / C, c0 = kbeg - tap * C, kh = 0, kw = 0;
+  if (mode != OP_PLAIN_K) { kh = tap / g.KW; kw = tap - kh * g.KW; }
   auto fetch = [&](int k0) {
     int delta;
     if (mode == OP_PLAIN_K) delta = c0;
@@ -208,34 +216,79 @@ __global__ __launch_bounds__(256) void conv_gemm_kernel(const GemmBatch batch) {
       }
     }
   };
-  const int nslab = P.K / BK;
   if constexpr (DB) {
     // Two operand buffers (small problems, whose k-loop is a chain of latencies): while slab
     // `it` is contracted out of one buffer the loads of slab it+1 are in flight; they are
     // written to the other buffer after the contraction and the loads of slab it+2 are
     // issued.  One barrier per slab.
-    fetch(0);
-    stash(0);
-    if (nslab > 1) fetch(BK);
+    if (nslab > 0) {
+      fetch(kbeg);
+      stash(0);
+    }
+    if (nslab > 1) fetch(kbeg + BK);
     __syncthreads();
     for (int it = 0; it < nslab; ++it) {
       contract(As0 + (it & 1) * BUF);
       if (it + 1 < nslab) {
         stash((it + 1) & 1);  // last read in iteration it-1, which every wave has left (barrier below)
-        if (it + 2 < nslab) fetch((it + 2) * BK);
+        if (it + 2 < nslab) fetch(kbeg + (it + 2) * BK);
       }
       __syncthreads();
     }
   } else {
     // One operand buffer (large launches, where more workgroups per CU hide the latency):
     // the next slab's loads are in flight while the current one is contracted.
-    fetch(0);
+    if (nslab > 0) fetch(kbeg);
     for (int it = 0; it < nslab; ++it) {
       __syncthreads();
       stash(0);
       __syncthreads();
-      if (it + 1 < nslab) fetch((it + 1) * BK);
+      if (it + 1 < nslab) fetch(kbeg + (it + 1) * BK);
       contract(As0);
+    }
+  }
+
+  if (SPLIT && ks > 1) {
+    // Partial tile -> this workgroup's slot of the workspace, in register order (lane-contiguous).
+    // Partials and counter are device-scope atomics (they bypass the per-XCD L2) ordered by
+    // waiting for the stores; the last arrival sums the slots in a fixed order.
+    float* slot = batch.thin_ws + (int64_t)tile * (BM * BN);
+#pragma unroll
+    for (int i = 0; i < MI; ++i)
+#pragma unroll
+      for (int j = 0; j < NI; ++j)
+#pragma unroll
+        for (int v = 0; v < 16; ++v)
+          __hip_atomic_store(slot + ((i * NI + j) * 16 + v) * 256 + tid, acc[i][j][v], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");  // the stores above have completed
+    __syncthreads();  // also: the operand tiles are no longer read
+    unsigned int* cnt = batch.thin_cnt + (tile - split);
+    int* flag = reinterpret_cast<int*>(smem);
+    if (tid == 0) {
+      const unsigned int arrived = atomicAdd(cnt, 1u);
+      *flag = arrived == (unsigned)(ks - 1);
+      if (arrived == (unsigned)(ks - 1)) atomicExch(cnt, 0u);  // ready for the next launch
+    }
+    __syncthreads();
+    if (!*flag) return;
+    const float* first = batch.thin_ws + (int64_t)(tile - split) * (BM * BN);
+#pragma unroll
+    for (int i = 0; i < MI; ++i)
+#pragma unroll
+      for (int j = 0; j < NI; ++j)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+    for (int sp = 0; sp < ks; ++sp) {  // one round trip per slot: all of a slot's loads are issued together
+      const float* src = first + (int64_t)sp * (BM * BN) + tid;
+      float part[MI * NI * 16];
+#pragma unroll
+      for (int e = 0; e < MI * NI * 16; ++e) part[e] = __hip_atomic_load(src + e * 256, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+#pragma unroll
+      for (int i = 0; i < MI; ++i)
+#pragma unroll
+        for (int j = 0; j < NI; ++j)
+#pragma unroll
+          for (int v = 0; v < 16; ++v) acc[i][j][v] += part[(i * NI + j) * 16 + v];
     }
   }
 
@@ -703,6 +756,27 @@ hipError_t launch_conv_gemm(GemmBatch& b, int dtype, int bm, int bn, hipStream_t
     p.tiles_n = (p.N + bn - 1) / bn;
     p.tile_begin = total;
     total += ((p.M + bm - 1) / bm) * p.tiles_n;
+  }
+  // A launch short of workgroups shares its long reductions: about 640 workgroups in all,
+  // ranges of at least 4 slabs, at most 8 per tile, while the partial tiles fit the workspace.
+  // (64 x 64 tiles only: the partial tile of a larger one costs more than the shorter chain saves)
+  if (b.thin_ws && b.thin_cnt && total < 512 && bm == 64 && bn == 64) {
+    const int slab = deep ? 2 * bk : bk, want = (640 + total - 1) / total;
+    int split_total = 0;
+    for (int i = 0; i < b.n; ++i) {
+      GemmProb& p = b.p[i];
+      p.splits = std::max(1, std::min(std::min(want, 8), p.K / slab / 4));
+      split_total += ((p.M + bm - 1) / bm) * p.tiles_n * p.splits;
+    }
+    if (split_total <= CONV_SPLIT_SLOTS && (int64_t)split_total * bm * bn * 4 <= CONV_SPLIT_WS_BYTES) {
+      total = 0;
+      for (int i = 0; i < b.n; ++i) {
+        b.p[i].tile_begin = total;
+        total += ((b.p[i].M + bm - 1) / bm) * b.p[i].tiles_n * b.p[i].splits;
+      }
+    } else {
+      for (int i = 0; i < b.n; ++i) b.p[i].splits = 1;
+    }
   }
   b.total_tiles = total;
   dim3 grid(total);

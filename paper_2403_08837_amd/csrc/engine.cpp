@@ -114,7 +114,7 @@ struct cdp_ctx {
   char* arena = nullptr;
   int64_t arena_bytes = 0;
   std::vector<StageState> st;
-  int64_t labels_off = 0, loss_off = 0, thin_ws_off = 0;
+  int64_t labels_off = 0, loss_off = 0, thin_ws_off = 0, conv_ws_off = -1;
   Pool pool;
   int64_t scratch_base = 0, scratch_cap = -1, scratch_bump = 0;  // per-tick workspace (im2col buffers, partial sums)
   std::vector<std::vector<VisitRecord>> rec;  // [mb][stage]
@@ -177,7 +177,7 @@ bool scratch_alloc(cdp_ctx* c, int64_t bytes, Block* b) {
 // --------------------------------------------------------------------------- layouts
 struct StaticLayout {
   std::vector<StageState> st;
-  int64_t labels_off, loss_off, thin_ws_off, pool_base, weight_bytes;
+  int64_t labels_off, loss_off, thin_ws_off, conv_ws_off, pool_base, weight_bytes;
 };
 
 StaticLayout static_layout(const ModelPlan& plan, int N, int B, int groups, bool velocity) {
@@ -197,6 +197,11 @@ StaticLayout static_layout(const ModelPlan& plan, int N, int B, int groups, bool
   L.labels_off = off; off = align_up(off + (int64_t)N * B * 4, 256);
   L.loss_off = off; off = align_up(off + (int64_t)LOSS_LOG_STEPS * N * groups * 4, 256);
   L.thin_ws_off = off; off = align_up(off + THIN_WS_BYTES, 256);
+  L.conv_ws_off = -1;
+  for (const StagePlan& sp : plan.stages)
+    for (const Op& o : sp.ops)
+      if (o.kind == OPK_GEMM && o.is_conv) L.conv_ws_off = 0;
+  if (L.conv_ws_off == 0) { L.conv_ws_off = off; off = align_up(off + CONV_SPLIT_WS_BYTES + CONV_SPLIT_SLOTS * 4, 256); }
   L.pool_base = off;
   return L;
 }
@@ -682,6 +687,13 @@ int launch_level(cdp_ctx* c, std::vector<Item>& items) {
           if (batch.p[q].epi != EPI_WGRAD) skinny_cols += batch.p[q].N;
         HIP_TRY(c, launch_linear_tick(batch, c->plan.dtype, skinny_cols >= 32768, true, c->stream));
       } else if (key == LC_CONV_NARROW || key == LC_CONV_WIDE) {
+        if (c->conv_ws_off >= 0) {  // zeroed at init, counters left zero by every launch
+          batch.thin_ws = c->fptr(c->conv_ws_off);
+          batch.thin_cnt = reinterpret_cast<unsigned int*>(static_cast<char*>(c->ptr(c->conv_ws_off)) + CONV_SPLIT_WS_BYTES);
+        } else {
+          batch.thin_ws = nullptr;
+          batch.thin_cnt = nullptr;
+        }
         int bm, bn;
         conv_gemm_tile(batch.p, batch.n, &bm, &bn);
         HIP_TRY(c, launch_conv_gemm(batch, c->plan.dtype, bm, bn, c->stream));
@@ -1048,7 +1060,7 @@ int make_ctx(cdp_ctx** out, const cdp_stage_desc* stages, int n_stages, int N, i
   c->momentum = opts->momentum; c->weight_decay = opts->weight_decay;
   StaticLayout L = static_layout(c->plan, N, B, c->groups, c->momentum != 0.f);
   c->st = L.st;
-  c->labels_off = L.labels_off; c->loss_off = L.loss_off; c->thin_ws_off = L.thin_ws_off;
+  c->labels_off = L.labels_off; c->loss_off = L.loss_off; c->thin_ws_off = L.thin_ws_off; c->conv_ws_off = L.conv_ws_off;
   c->pool.base = L.pool_base;
   c->pool.cap = c->dry ? -1 : c->arena_bytes - L.pool_base;
   c->rec.assign(N, std::vector<VisitRecord>(n_stages));

@@ -103,7 +103,9 @@ struct GemmBatch {
   int copy_tiles;  // linear_tick_kernel: tiles of the staging copy `sc` (listed last), 0 = none
   // linear_tick_kernel: room for thin tiles that split a long reduction over several workgroups
   // (THIN_WS_SLOTS partial tiles of 32 x 32 floats and as many counters, which must be zero
-  // before the launch and are zero again after it), or NULL: no thin tile is split
+  // before the launch and are zero again after it), or NULL: no thin tile is split.
+  // conv_gemm_kernel: the same for the tiles of a small launch (CONV_SPLIT_WS_BYTES of partial
+  // tiles, CONV_SPLIT_SLOTS counters)
   float* thin_ws;
   unsigned int* thin_cnt;
   GemmProb p[GEMM_MAX_PROBS];
@@ -128,6 +130,8 @@ hipError_t launch_gemm_batch(GemmBatch& batch, int dtype, int tile_shape, hipStr
 //           operands (chosen per problem when allow_thin): no staging, split reduction.
 // All kinds may be mixed in one batch (one launch per tick level).
 hipError_t launch_linear_tick(GemmBatch& batch, int dtype, bool wide, bool allow_thin, hipStream_t stream);
+constexpr int CONV_SPLIT_SLOTS = 2048;
+constexpr int64_t CONV_SPLIT_WS_BYTES = 32ll << 20;
 constexpr int THIN_WS_SLOTS = 1024;
 constexpr int64_t THIN_WS_BYTES = (int64_t)THIN_WS_SLOTS * (32 * 32 * 4 + 4);  // partial tiles, then counters
 

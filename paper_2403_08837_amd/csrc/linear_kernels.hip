@@ -378,11 +378,14 @@ __device__ __forceinline__ void thin_tile(const GemmBatch& batch, const GemmProb
     if (red[0] == 0.f) return;
     const float* first = batch.thin_ws + (int64_t)(tile - split) * 1024;
 #pragma unroll
-    for (int q = 0; q < 4; ++q) {
-      float sum = 0.f;
-      for (int sp = 0; sp < ks; ++sp)
-        sum += __hip_atomic_load(first + (int64_t)sp * 1024 + (wave * 4 + q) * 64 + lane, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-      vals[q] = sum;
+    for (int q = 0; q < 4; ++q) vals[q] = 0.f;
+    for (int sp = 0; sp < ks; ++sp) {  // one round trip per slot
+      float part[4];
+#pragma unroll
+      for (int q = 0; q < 4; ++q)
+        part[q] = __hip_atomic_load(first + (int64_t)sp * 1024 + (wave * 4 + q) * 64 + lane, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+#pragma unroll
+      for (int q = 0; q < 4; ++q) vals[q] += part[q];
     }
   }
 #pragma unroll
