@@ -42,6 +42,37 @@ __device__ __forceinline__ float wmax(float v) {
 constexpr float LN_EPS = 1e-5f;
 constexpr int LN_MAX_PER_LANE = 16;  // channels <= 1024
 
+// 16-byte chunks of a row: 8 bf16 or 4 fp32 values.
+template <typename T> struct RowChunk;
+template <> struct RowChunk<uint16_t> {
+  static constexpr int N = 8;
+  __device__ static __forceinline__ void load(const uint16_t* p, float* v) {
+    const uint4 u = *reinterpret_cast<const uint4*>(p);
+    v[0] = __uint_as_float(u.x << 16); v[1] = __uint_as_float(u.x & 0xffff0000u);
+    v[2] = __uint_as_float(u.y << 16); v[3] = __uint_as_float(u.y & 0xffff0000u);
+    v[4] = __uint_as_float(u.z << 16); v[5] = __uint_as_float(u.z & 0xffff0000u);
+    v[6] = __uint_as_float(u.w << 16); v[7] = __uint_as_float(u.w & 0xffff0000u);
+  }
+  __device__ static __forceinline__ void store(uint16_t* p, const float* v) {
+    uint4 u;
+    u.x = (uint32_t)t_f2bf(v[0]) | ((uint32_t)t_f2bf(v[1]) << 16);
+    u.y = (uint32_t)t_f2bf(v[2]) | ((uint32_t)t_f2bf(v[3]) << 16);
+    u.z = (uint32_t)t_f2bf(v[4]) | ((uint32_t)t_f2bf(v[5]) << 16);
+    u.w = (uint32_t)t_f2bf(v[6]) | ((uint32_t)t_f2bf(v[7]) << 16);
+    *reinterpret_cast<uint4*>(p) = u;
+  }
+};
+template <> struct RowChunk<float> {
+  static constexpr int N = 4;
+  __device__ static __forceinline__ void load(const float* p, float* v) {
+    const float4 u = *reinterpret_cast<const float4*>(p);
+    v[0] = u.x; v[1] = u.y; v[2] = u.z; v[3] = u.w;
+  }
+  __device__ static __forceinline__ void store(float* p, const float* v) {
+    *reinterpret_cast<float4*>(p) = make_float4(v[0], v[1], v[2], v[3]);
+  }
+};
+
 }  // namespace
 
 // ---------------------------------------------------------------------------------
@@ -74,6 +105,108 @@ __global__ __launch_bounds__(256) void layernorm_fwd_kernel(const T* __restrict_
   for (int q = 0; q < LN_MAX_PER_LANE; ++q) {
     const int c = lane + 64 * q;
     if (c < C) tst<T>(y, (int64_t)row * C + c, (v[q] - mean) * rstd * gamma[c] + beta[c]);
+  }
+}
+
+// The same with 16-byte accesses, for rows that are whole 16-byte chunks: lane l owns chunks
+// l, l + 64, ... of its row.
+template <typename T>
+__global__ __launch_bounds__(256) void layernorm_fwd_vec_kernel(const T* __restrict__ x, const float* __restrict__ gamma,
+                                                                const float* __restrict__ beta, T* __restrict__ y, int rows, int C) {
+  constexpr int N = RowChunk<T>::N, Q = LN_MAX_PER_LANE / N;
+  const int lane = threadIdx.x & 63, row = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (row >= rows) return;
+  const int64_t base = (int64_t)row * C;
+  float v[Q][N];
+  float s = 0.f;
+#pragma unroll
+  for (int q = 0; q < Q; ++q) {
+    const int c = (lane + 64 * q) * N;
+    if (c < C) {
+      RowChunk<T>::load(x + base + c, v[q]);
+#pragma unroll
+      for (int e = 0; e < N; ++e) s += v[q][e];
+    }
+  }
+  const float mean = wsum(s) / (float)C;
+  float ss = 0.f;
+#pragma unroll
+  for (int q = 0; q < Q; ++q)
+    if ((lane + 64 * q) * N < C) {
+#pragma unroll
+      for (int e = 0; e < N; ++e) ss += (v[q][e] - mean) * (v[q][e] - mean);
+    }
+  const float rstd = rsqrtf(wsum(ss) / (float)C + LN_EPS);
+#pragma unroll
+  for (int q = 0; q < Q; ++q) {
+    const int c = (lane + 64 * q) * N;
+    if (c < C) {
+      float o[N];
+#pragma unroll
+      for (int e = 0; e < N; ++e) o[e] = (v[q][e] - mean) * rstd * gamma[c + e] + beta[c + e];
+      RowChunk<T>::store(y + base + c, o);
+    }
+  }
+}
+
+template <typename T>
+__global__ __launch_bounds__(256) void layernorm_bwd_rows_vec_kernel(const T* __restrict__ x, const T* __restrict__ dy,
+                                                                     const T* __restrict__ add, const float* __restrict__ gamma,
+                                                                     T* __restrict__ dx, float* __restrict__ stats, int rows, int C) {
+  constexpr int N = RowChunk<T>::N, Q = LN_MAX_PER_LANE / N;
+  const int lane = threadIdx.x & 63, row = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (row >= rows) return;
+  const int64_t base = (int64_t)row * C;
+  float v[Q][N], g[Q][N];
+  float s = 0.f;
+#pragma unroll
+  for (int q = 0; q < Q; ++q) {
+    const int c = (lane + 64 * q) * N;
+    if (c < C) {
+      RowChunk<T>::load(x + base + c, v[q]);
+      RowChunk<T>::load(dy + base + c, g[q]);
+#pragma unroll
+      for (int e = 0; e < N; ++e) {
+        g[q][e] *= gamma[c + e];
+        s += v[q][e];
+      }
+    }
+  }
+  const float mean = wsum(s) / (float)C;
+  float ss = 0.f;
+#pragma unroll
+  for (int q = 0; q < Q; ++q)
+    if ((lane + 64 * q) * N < C) {
+#pragma unroll
+      for (int e = 0; e < N; ++e) ss += (v[q][e] - mean) * (v[q][e] - mean);
+    }
+  const float rstd = rsqrtf(wsum(ss) / (float)C + LN_EPS);
+  float sg = 0.f, sgx = 0.f;
+#pragma unroll
+  for (int q = 0; q < Q; ++q)
+    if ((lane + 64 * q) * N < C) {
+#pragma unroll
+      for (int e = 0; e < N; ++e) {
+        v[q][e] = (v[q][e] - mean) * rstd;
+        sg += g[q][e];
+        sgx += g[q][e] * v[q][e];
+      }
+    }
+  const float mg = wsum(sg) / (float)C, mgx = wsum(sgx) / (float)C;
+#pragma unroll
+  for (int q = 0; q < Q; ++q) {
+    const int c = (lane + 64 * q) * N;
+    if (c < C) {
+      float o[N], a[N];
+      if (add) RowChunk<T>::load(add + base + c, a);
+#pragma unroll
+      for (int e = 0; e < N; ++e) o[e] = rstd * (g[q][e] - mg - v[q][e] * mgx) + (add ? a[e] : 0.f);
+      RowChunk<T>::store(dx + base + c, o);
+    }
+  }
+  if (lane == 0) {
+    stats[2 * (int64_t)row] = mean;
+    stats[2 * (int64_t)row + 1] = rstd;
   }
 }
 
@@ -183,11 +316,21 @@ __global__ __launch_bounds__(256) void layernorm_fold_kernel(const float* __rest
   }
 }
 
+// rows of C elements at p are whole, 16-byte aligned chunks
+static bool ln_vec_ok(const void* p, int C, int eb) {
+  return p == nullptr || (reinterpret_cast<uintptr_t>(p) % 16 == 0 && (C * eb) % 16 == 0);
+}
+
 hipError_t launch_layernorm_fwd(const void* x, const float* gamma, const float* beta, void* y, int rows, int C, int dtype,
                                 hipStream_t stream) {
   if (rows <= 0 || C <= 0 || C > 64 * LN_MAX_PER_LANE) return hipErrorInvalidValue;
-  CDP_TDISPATCH(dtype, hipLaunchKernelGGL((layernorm_fwd_kernel<T>), dim3((rows + 3) / 4), dim3(256), 0, stream,
-                                          static_cast<const T*>(x), gamma, beta, static_cast<T*>(y), rows, C));
+  const int eb = dtype == DT_BF16 ? 2 : 4;
+  if (ln_vec_ok(x, C, eb) && ln_vec_ok(y, C, eb))
+    CDP_TDISPATCH(dtype, hipLaunchKernelGGL((layernorm_fwd_vec_kernel<T>), dim3((rows + 3) / 4), dim3(256), 0, stream,
+                                            static_cast<const T*>(x), gamma, beta, static_cast<T*>(y), rows, C));
+  else
+    CDP_TDISPATCH(dtype, hipLaunchKernelGGL((layernorm_fwd_kernel<T>), dim3((rows + 3) / 4), dim3(256), 0, stream,
+                                            static_cast<const T*>(x), gamma, beta, static_cast<T*>(y), rows, C));
   return hipGetLastError();
 }
 static int64_t ln_stats_bytes(int rows) { return ((int64_t)rows * 8 + 255) / 256 * 256; }
@@ -200,9 +343,15 @@ hipError_t launch_layernorm_bwd(const void* x, const void* dy, const void* add, 
   const int wgs = (rows + LN_ROWS_PER_WG - 1) / LN_ROWS_PER_WG;
   float* stats = workspace;
   float* part = workspace + ln_stats_bytes(rows) / 4;
-  CDP_TDISPATCH(dtype, hipLaunchKernelGGL((layernorm_bwd_rows_kernel<T>), dim3((rows + 3) / 4), dim3(256), 0, stream,
-                                          static_cast<const T*>(x), static_cast<const T*>(dy), static_cast<const T*>(add), gamma,
-                                          static_cast<T*>(dx), stats, rows, C));
+  const int eb = dtype == DT_BF16 ? 2 : 4;
+  if (ln_vec_ok(x, C, eb) && ln_vec_ok(dy, C, eb) && ln_vec_ok(add, C, eb) && ln_vec_ok(dx, C, eb))
+    CDP_TDISPATCH(dtype, hipLaunchKernelGGL((layernorm_bwd_rows_vec_kernel<T>), dim3((rows + 3) / 4), dim3(256), 0, stream,
+                                            static_cast<const T*>(x), static_cast<const T*>(dy), static_cast<const T*>(add), gamma,
+                                            static_cast<T*>(dx), stats, rows, C));
+  else
+    CDP_TDISPATCH(dtype, hipLaunchKernelGGL((layernorm_bwd_rows_kernel<T>), dim3((rows + 3) / 4), dim3(256), 0, stream,
+                                            static_cast<const T*>(x), static_cast<const T*>(dy), static_cast<const T*>(add), gamma,
+                                            static_cast<T*>(dx), stats, rows, C));
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   CDP_TDISPATCH(dtype, hipLaunchKernelGGL((layernorm_bwd_cols_kernel<T>), dim3(wgs), dim3(256), 0, stream, static_cast<const T*>(x),
@@ -471,6 +620,75 @@ __global__ __launch_bounds__(256) void softmax_bwd_kernel(const T* __restrict__ 
   }
 }
 
+// The two softmax kernels with 4-element accesses, for row lengths that are multiples of 4
+// (fp32 rows are then whole 16-byte chunks, T rows whole 8- or 16-byte chunks): lane l owns
+// chunks l, l + 64, ... of its row.
+template <typename T>
+__global__ __launch_bounds__(256) void softmax_fwd_vec_kernel(const float* __restrict__ s, T* __restrict__ p, int64_t rows, int n) {
+  constexpr int Q = LN_MAX_PER_LANE / 4;
+  const int lane = threadIdx.x & 63;
+  const int64_t row = blockIdx.x * (int64_t)4 + (threadIdx.x >> 6);
+  if (row >= rows) return;
+  const float* sr = s + row * n;
+  float v[Q][4];
+  float m = -INFINITY;
+#pragma unroll
+  for (int q = 0; q < Q; ++q) {
+    const int c = (lane + 64 * q) * 4;
+    if (c < n) {
+      t_ld4(sr, lane + 64 * q, v[q]);
+#pragma unroll
+      for (int e = 0; e < 4; ++e) m = fmaxf(m, v[q][e]);
+    }
+  }
+  m = wmax(m);
+  float sum = 0.f;
+#pragma unroll
+  for (int q = 0; q < Q; ++q)
+    if ((lane + 64 * q) * 4 < n) {
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        v[q][e] = expf(v[q][e] - m);
+        sum += v[q][e];
+      }
+    }
+  const float inv = 1.f / wsum(sum);
+  T* pr = p + row * n;
+#pragma unroll
+  for (int q = 0; q < Q; ++q)
+    if ((lane + 64 * q) * 4 < n) {
+#pragma unroll
+      for (int e = 0; e < 4; ++e) v[q][e] *= inv;
+      t_st4(pr, lane + 64 * q, v[q]);
+    }
+}
+template <typename T>
+__global__ __launch_bounds__(256) void softmax_bwd_vec_kernel(const T* __restrict__ p, const float* __restrict__ dp, T* __restrict__ ds,
+                                                              int64_t rows, int n, float scale) {
+  constexpr int Q = LN_MAX_PER_LANE / 4;
+  const int lane = threadIdx.x & 63;
+  const int64_t row = blockIdx.x * (int64_t)4 + (threadIdx.x >> 6);
+  if (row >= rows) return;
+  float pv[Q][4], dv[Q][4];
+  float dot = 0.f;
+#pragma unroll
+  for (int q = 0; q < Q; ++q)
+    if ((lane + 64 * q) * 4 < n) {
+      t_ld4(p + row * n, lane + 64 * q, pv[q]);
+      t_ld4(dp + row * n, lane + 64 * q, dv[q]);
+#pragma unroll
+      for (int e = 0; e < 4; ++e) dot += pv[q][e] * dv[q][e];
+    }
+  dot = wsum(dot);
+#pragma unroll
+  for (int q = 0; q < Q; ++q)
+    if ((lane + 64 * q) * 4 < n) {
+#pragma unroll
+      for (int e = 0; e < 4; ++e) pv[q][e] = pv[q][e] * (dv[q][e] - dot) * scale;
+      t_st4(ds + row * n, lane + 64 * q, pv[q]);
+    }
+}
+
 // Self-attention core on qkv[B][T][3*D] (q | k | v per token, head h in columns h*dh..):
 // forward  S = q k^T / sqrt(dh) (fp32 workspace), P = softmax(S) (kept for the backward), out = P v;
 // backward dv = P^T do, dP = do v^T (fp32 workspace), ds = P * (dP - rowsum(dP * P)) / sqrt(dh),
@@ -491,8 +709,12 @@ hipError_t launch_attention_fwd(const void* qkv, void* P, void* out, float* ws, 
   hipError_t e = launch_bmm(s, B * heads, dtype, stream);
   if (e != hipSuccess) return e;
   const int64_t rows = (int64_t)B * heads * NT;
-  CDP_TDISPATCH(dtype, hipLaunchKernelGGL((softmax_fwd_kernel<T>), dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, stream, ws,
-                                          static_cast<T*>(P), rows, NT));
+  if (NT % 4 == 0 && aligned16(ws) && aligned16(P))
+    CDP_TDISPATCH(dtype, hipLaunchKernelGGL((softmax_fwd_vec_kernel<T>), dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, stream, ws,
+                                            static_cast<T*>(P), rows, NT));
+  else
+    CDP_TDISPATCH(dtype, hipLaunchKernelGGL((softmax_fwd_kernel<T>), dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, stream, ws,
+                                            static_cast<T*>(P), rows, NT));
   if ((e = hipGetLastError()) != hipSuccess) return e;
   BmmArgs o;  // out[z][q][j] = sum_key P[q][key] v[key][j]
   o.A = BmmOperand{P, heads * TT, TT, NT, 1};
@@ -526,8 +748,12 @@ hipError_t launch_attention_bwd(const void* qkv, const void* P, const void* dout
   a.c_sample = heads * TT; a.c_head = TT; a.c_row = NT; a.c_col = 1; a.M = NT; a.N = NT; a.K = dh; a.c_f32 = 1;
   if ((e = launch_bmm(a, B * heads, dtype, stream)) != hipSuccess) return e;
   const int64_t rows = (int64_t)B * heads * NT;
-  CDP_TDISPATCH(dtype, hipLaunchKernelGGL((softmax_bwd_kernel<T>), dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, stream,
-                                          static_cast<const T*>(P), ws_dp, static_cast<T*>(ws_ds), rows, NT, scale));
+  if (NT % 4 == 0 && aligned16(P) && aligned16(ws_dp) && aligned16(ws_ds))
+    CDP_TDISPATCH(dtype, hipLaunchKernelGGL((softmax_bwd_vec_kernel<T>), dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, stream,
+                                            static_cast<const T*>(P), ws_dp, static_cast<T*>(ws_ds), rows, NT, scale));
+  else
+    CDP_TDISPATCH(dtype, hipLaunchKernelGGL((softmax_bwd_kernel<T>), dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, stream,
+                                            static_cast<const T*>(P), ws_dp, static_cast<T*>(ws_ds), rows, NT, scale));
   if ((e = hipGetLastError()) != hipSuccess) return e;
   const BmmOperand dSqk{ws_ds, heads * TT, TT, NT, 1}, dSkq{ws_ds, heads * TT, TT, 1, NT};
   // dq[q][j] = sum_key ds[q][key] k[key][j]

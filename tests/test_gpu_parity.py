@@ -360,8 +360,9 @@ def test_vit_mini_bf16_and_variants():
 @pytest.mark.parametrize("name,rule", [("vit_odd", wl.RULE_V2), ("vit_odd", wl.RULE_V1), ("vit_odd_bf16", wl.RULE_V2),
                                        ("vit_long", wl.RULE_V2)])
 def test_vit_odd_shapes(name, rule):
-    """9 tokens of width 24 in heads of width 6, micro-batches of 3: no extent is a multiple of
-    four, so the attention products take their element-wise staging path and every tile is ragged.
+    """9 tokens of width 20 in heads of width 5, micro-batches of 3: no extent is a multiple of
+    four, so the attention products take their element-wise staging path, every tile is ragged and
+    (in bf16) LayerNorm rows are not whole 16-byte chunks.
     vit_long has 324 tokens (more than one 256-wide pass of the softmax lanes, six ragged 64-row tiles)."""
     cfg = wl.get_config(name)
     check(cfg, rule, cfg.steps)
