@@ -260,7 +260,10 @@ __global__ __launch_bounds__(256) void conv_gemm_kernel(const GemmBatch batch) {
 #pragma unroll
         for (int v = 0; v < 16; ++v)
           __hip_atomic_store(slot + ((i * NI + j) * 16 + v) * 256 + tid, acc[i][j][v], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");  // the stores above have completed
+    // every store above has been acknowledged before this wavefront reaches the barrier (a
+    // workgroup-scope fence alone does not wait for global stores)
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
     __syncthreads();  // also: the operand tiles are no longer read
     unsigned int* cnt = batch.thin_cnt + (tile - split);
     int* flag = reinterpret_cast<int*>(smem);

@@ -366,7 +366,10 @@ __device__ __forceinline__ void thin_tile(const GemmBatch& batch, const GemmProb
 #pragma unroll
     for (int q = 0; q < 4; ++q)
       __hip_atomic_store(slot + (wave * 4 + q) * 64 + lane, vals[q], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");  // the stores above have completed
+    // every store above has been acknowledged before this wavefront reaches the barrier (a
+    // workgroup-scope fence alone does not wait for global stores)
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
     __syncthreads();  // also: every wave has read its share of `red`
     unsigned int* cnt = batch.thin_cnt + (tile - split);
     if (tid == 0) {
