@@ -328,6 +328,10 @@ def get_config(name: str) -> Config:
     if name == "mlp_longk":      # long, ragged reduction in the stem (1100 inputs), 40-wide layers, B = 5
         return Config("mlp_longk", _mlp(1100, 40, 4, 7, stem=True), (1100,), 7, N=4, B=5,
                       dtype=F32, lr=0.05, steps=4)
+    if name == "mlp_longk_b40":  # the same stem with micro-batches of 40 rows: 64-row tiles
+        c = get_config("mlp_longk")
+        c.name, c.B = "mlp_longk_b40", 40
+        return c
     if name == "mlp_longk_bf16":  # 2120 inputs: 34 slabs of 64, the last one partial
         return Config("mlp_longk_bf16", _mlp(2120, 136, 4, 10, stem=True), (2120,), 10, N=4, B=24,
                       dtype=BF16, lr=0.02, steps=4)

@@ -108,6 +108,7 @@ struct GemmBatch {
   // tiles, CONV_SPLIT_SLOTS counters)
   float* thin_ws;
   unsigned int* thin_cnt;
+  int slot_floats;  // linear_tick_kernel: floats per partial-tile slot of this launch (set by launch_linear_tick)
   GemmProb p[GEMM_MAX_PROBS];
   LinUpdate upd[LIN_UPD_MAX];
   StageCopy sc;

@@ -114,7 +114,7 @@ __device__ __forceinline__ void store_result(const GemmProb& P, int r, int c, fl
 // ---------------------------------------------------------------------------------
 // skinny tile: 64 x BN outputs, waves 2 (rows) x 2 (cols).
 template <typename T, int BN>
-__device__ __forceinline__ void skinny_tile(const GemmProb& P, int tile, unsigned char* smem) {
+__device__ __forceinline__ void skinny_tile(const GemmBatch& batch, const GemmProb& P, int tile, unsigned char* smem) {
   using E = LT<T>;
   constexpr int BM = 64, BK = E::SLAB, VEC = E::VEC, LDP = BK + VEC;
   constexpr int NA = BM / 16, NB = BN / 16;  // 16-byte chunks per thread and slab
@@ -122,7 +122,11 @@ __device__ __forceinline__ void skinny_tile(const GemmProb& P, int tile, unsigne
   T* As = reinterpret_cast<T*>(smem);
   T* Bs = As + BM * LDP;
 
-  const int local = tile - P.tile_begin;
+  // 64-column tiles of a launch short of workgroups share a long reduction among P.splits
+  // workgroups (neighbours in the tile list), as the thin tiles do
+  constexpr bool SPLIT = BN == 64;
+  const int ks = SPLIT ? P.splits : 1, split = (tile - P.tile_begin) % ks;
+  const int local = (tile - P.tile_begin) / ks;
   const int tn = local % P.tiles_n, tm = local / P.tiles_n;
   const int row0 = tm * BM, col0 = tn * BN;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -197,9 +201,10 @@ __device__ __forceinline__ void skinny_tile(const GemmProb& P, int tile, unsigne
 #pragma unroll
     for (int v = 0; v < 16; ++v) acc[j][v] = 0.f;
 
-  const int nslab = (P.K + BK - 1) / BK;
-  const int s0 = (int)(((unsigned)tile * 2654435761u) >> 8) % nslab;  // per-workgroup starting slab
-  auto slab_k = [&](int i) { const int q = s0 + i; return (q >= nslab ? q - nslab : q) * BK; };
+  const int nslab_all = (P.K + BK - 1) / BK, per = (nslab_all + ks - 1) / ks;
+  const int sb = split * per, nslab = max(0, min(nslab_all, sb + per) - sb);
+  const int s0 = nslab > 0 ? (int)(((unsigned)tile * 2654435761u) >> 8) % nslab : 0;  // per-workgroup starting slab
+  auto slab_k = [&](int i) { const int q = s0 + i; return (sb + (q >= nslab ? q - nslab : q)) * BK; };
 #pragma unroll
   for (int d = 0; d < DEPTH; ++d)
     if (d < nslab) fetch(ra[d], rb[d], slab_k(d));
@@ -232,6 +237,37 @@ __device__ __forceinline__ void skinny_tile(const GemmProb& P, int tile, unsigne
     }
   }
 
+  if constexpr (SPLIT) {
+    if (ks > 1) {
+      // partial tile (register order) -> this workgroup's slot; the last arrival adds the slots in order
+      float* slot = batch.thin_ws + (int64_t)tile * batch.slot_floats;
+#pragma unroll
+      for (int v = 0; v < 16; ++v) __hip_atomic_store(slot + v * 256 + tid, acc[0][v], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // the stores are acknowledged before the barrier
+      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+      __syncthreads();  // also: the operand tiles are no longer read
+      unsigned int* cnt = batch.thin_cnt + (tile - split);
+      int* flag = reinterpret_cast<int*>(smem);
+      if (tid == 0) {
+        const unsigned int arrived = atomicAdd(cnt, 1u);
+        *flag = arrived == (unsigned)(ks - 1);
+        if (arrived == (unsigned)(ks - 1)) atomicExch(cnt, 0u);  // ready for the next launch
+      }
+      __syncthreads();
+      if (!*flag) return;
+      const float* first = batch.thin_ws + (int64_t)(tile - split) * batch.slot_floats + tid;
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[0][v] = 0.f;
+      for (int sp = 0; sp < ks; ++sp) {  // one round trip per slot
+        float part[16];
+#pragma unroll
+        for (int v = 0; v < 16; ++v)
+          part[v] = __hip_atomic_load(first + (int64_t)sp * batch.slot_floats + v * 256, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[0][v] += part[v];
+      }
+    }
+  }
 #pragma unroll
   for (int j = 0; j < NI; ++j) {
     const int c = col0 + wn * (BN / 2) + j * 32 + (lane & 31);
@@ -362,7 +398,7 @@ __device__ __forceinline__ void thin_tile(const GemmBatch& batch, const GemmProb
     // Partials and counter are device-scope atomics (they bypass the per-XCD L2), ordered by
     // waiting for the stores to complete; a device-scope fence here would write back every
     // dirty L2 line of the weight-gradient tiles that share the launch.
-    float* slot = batch.thin_ws + (int64_t)tile * 1024;
+    float* slot = batch.thin_ws + (int64_t)tile * batch.slot_floats;
 #pragma unroll
     for (int q = 0; q < 4; ++q)
       __hip_atomic_store(slot + (wave * 4 + q) * 64 + lane, vals[q], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -379,14 +415,14 @@ __device__ __forceinline__ void thin_tile(const GemmBatch& batch, const GemmProb
     }
     __syncthreads();
     if (red[0] == 0.f) return;
-    const float* first = batch.thin_ws + (int64_t)(tile - split) * 1024;
+    const float* first = batch.thin_ws + (int64_t)(tile - split) * batch.slot_floats;
 #pragma unroll
     for (int q = 0; q < 4; ++q) vals[q] = 0.f;
     for (int sp = 0; sp < ks; ++sp) {  // one round trip per slot
       float part[4];
 #pragma unroll
       for (int q = 0; q < 4; ++q)
-        part[q] = __hip_atomic_load(first + (int64_t)sp * 1024 + (wave * 4 + q) * 64 + lane, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        part[q] = __hip_atomic_load(first + (int64_t)sp * batch.slot_floats + (wave * 4 + q) * 64 + lane, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 #pragma unroll
       for (int q = 0; q < 4; ++q) vals[q] += part[q];
     }
@@ -698,7 +734,7 @@ __global__ __launch_bounds__(256) void linear_tick_kernel(const GemmBatch batch)
         return;
       }
     }
-    skinny_tile<T, BN>(P, tile, smem);
+    skinny_tile<T, BN>(batch, P, tile, smem);
   }
 }
 
@@ -728,6 +764,7 @@ hipError_t launch_linear_tick(GemmBatch& b, int dtype, bool wide, bool allow_thi
   int total = 0;
   bool any_thin = false;
   const bool split_ok = b.thin_ws != nullptr && b.thin_cnt != nullptr;
+  bool skinny_split = false;
   b.head_tiles = 0;
   b.upd_tiles = 0;
   for (int i = 0; i < b.n; ++i) {
@@ -773,6 +810,14 @@ hipError_t launch_linear_tick(GemmBatch& b, int dtype, bool wide, bool allow_thi
       } else {
         p.tiles_n = (p.N + bn - 1) / bn;
         tiles = ((p.M + 63) / 64) * p.tiles_n;
+        // few 64-column tiles with a long reduction (a classifier on its own in a launch):
+        // ranges of at least 4 slabs of 128, at most 8 per tile
+        const int nslab = (p.K + 16 * vec - 1) / (16 * vec);
+        if (split_ok && !wide && tiles <= 64 && nslab >= 8) {
+          p.splits = std::min(8, nslab / 4);
+          tiles *= p.splits;
+          skinny_split = true;
+        }
       }
       b.head_tiles += tiles;
     }
@@ -780,7 +825,9 @@ hipError_t launch_linear_tick(GemmBatch& b, int dtype, bool wide, bool allow_thi
     total += tiles;
   }
   b.total_tiles = total;
-  if (b.head_tiles > THIN_WS_SLOTS && split_ok) {
+  // partial tiles are addressed by tile number: one slot size per launch
+  b.slot_floats = skinny_split ? 64 * 64 : 32 * 32;
+  if ((int64_t)b.head_tiles * b.slot_floats > (int64_t)THIN_WS_SLOTS * 1024 && split_ok) {
     // split tiles address the workspace by their tile number: lay the launch out again without them
     b.thin_ws = nullptr;
     return launch_linear_tick(b, dtype, wide, allow_thin, stream);

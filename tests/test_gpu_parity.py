@@ -406,11 +406,11 @@ def test_vit_b16_full_config_sampled():
 
 
 @pytest.mark.parametrize("name,rule", [("mlp_longk", wl.RULE_V2), ("mlp_longk", wl.RULE_V1), ("mlp_longk", wl.RULE_DP),
-                                       ("mlp_longk_bf16", wl.RULE_V2)])
+                                       ("mlp_longk_bf16", wl.RULE_V2), ("mlp_longk_b40", wl.RULE_V2)])
 def test_long_reduction_shared_by_several_workgroups(name, rule):
     """A stem whose reduction is long enough that the thin forward tiles split it over several
     workgroups (partial tiles in the workspace, the last arrival finishes the tile), with a
-    ragged last slab and ragged output tiles."""
+    ragged last slab and ragged output tiles; with 40 rows the 64-row tiles do the same."""
     cfg = wl.get_config(name)
     check(cfg, rule, cfg.steps)
 
