@@ -59,9 +59,10 @@ __device__ __forceinline__ int xcd_remap(int bid, int total) {
   return (bid & 7) * chunk + (bid >> 3);
 }
 
-// Rows of a weight-gradient tile that takes the SGD step (tiles_n is set).
-__host__ __device__ __forceinline__ int dw_update_rows(const GemmProb& p) {
-  return ((p.M + 63) / 64) * p.tiles_n < 512 ? 32 : 64;
+// Rows of a weight-gradient tile (tiles_n is set).
+__host__ __device__ __forceinline__ int dw_tile_rows(const GemmProb& p) {
+  // (a long reduction, as in the lock-step run's batched passes, re-stages its operands per tile: keep 64 rows)
+  return ((p.M + 63) / 64) * p.tiles_n < 512 && (p.K <= 64 || p.upd) ? 32 : 64;
 }
 
 __device__ __forceinline__ int find_problem(const GemmBatch& batch, int tile) {
@@ -460,8 +461,8 @@ __device__ __forceinline__ void thin_tile(const GemmBatch& batch, const GemmProb
 
 // ---------------------------------------------------------------------------------
 // dw_kernel: G tile of TN = 64 (rows n) x 128 (cols k); wave w owns columns [32w, 32w+32).
-// Tiles that also take the SGD step are 32 rows high when the matrix has few of them
-// (dw_update_rows): twice as many workgroups share the longest tiles of the launch.
+// Tiles are 32 rows high when the matrix has few of them (dw_tile_rows): twice as many
+// workgroups share what are the longest tiles of a small launch.
 // Operand convention of the batch entry: A = dY [Mb][N] (lda = N), B = X [Mb][K]
 // (ldb = K), out = G [N][K] (ldo = K), P.M = N, P.N = K, P.K = Mb (reduction length);
 // aux2 = bias-gradient vector [N] or NULL.
@@ -725,7 +726,7 @@ __global__ __launch_bounds__(256) void linear_tick_kernel(const GemmBatch batch)
   }
   const GemmProb& P = batch.p[find_problem(batch, tile)];
   if (P.epi == EPI_WGRAD) {
-    if (P.upd && dw_update_rows(P) == 32) dw_tile<T, 32>(batch, P, tile, smem);
+    if (dw_tile_rows(P) == 32) dw_tile<T, 32>(batch, P, tile, smem);
     else dw_tile<T, 64>(batch, P, tile, smem);
   } else {
     if constexpr (THIN) {
@@ -783,10 +784,10 @@ hipError_t launch_linear_tick(GemmBatch& b, int dtype, bool wide, bool allow_thi
       }
       p.tiles_n = (p.N + 127) / 128;
       tiles = ((p.M + 63) / 64) * p.tiles_n;
-      if (p.upd) {
-        const int rows = dw_update_rows(p);
+      {
+        const int rows = dw_tile_rows(p);
         tiles = ((p.M + rows - 1) / rows) * p.tiles_n;
-        b.upd_tiles += tiles;
+        if (p.upd) b.upd_tiles += tiles;
       }
     } else {
       if (p.a_mode != OP_PLAIN_K || p.b_mode != OP_PLAIN_K) return hipErrorInvalidValue;
@@ -810,10 +811,10 @@ hipError_t launch_linear_tick(GemmBatch& b, int dtype, bool wide, bool allow_thi
       } else {
         p.tiles_n = (p.N + bn - 1) / bn;
         tiles = ((p.M + 63) / 64) * p.tiles_n;
-        // few 64-column tiles with a long reduction (a classifier on its own in a launch):
+        // few (at most 32) 64-column tiles with a long reduction (a classifier on its own in a launch):
         // ranges of at least 4 slabs of 128, at most 8 per tile
         const int nslab = (p.K + 16 * vec - 1) / (16 * vec);
-        if (split_ok && !wide && tiles <= 64 && nslab >= 8) {
+        if (split_ok && !wide && tiles <= 32 && nslab >= 8) {
           p.splits = std::min(8, nslab / 4);
           tiles *= p.splits;
           skinny_split = true;
