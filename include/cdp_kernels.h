@@ -39,6 +39,28 @@ int cdp_k_conv(int dtype, int which, const void* in0, const void* in1, void* out
                int Cin, int Cout, int ksize, int stride, int pad, void* workspace,
                size_t workspace_bytes, void* stream);
 
+/* The kernels of ViT-shaped stages (the homogeneous stages of Sec. 5 "Memory") on their own.
+ * Element type of x / dy / out / qkv / P / dout by `dtype`; gamma, beta and their gradients fp32.
+ *
+ * LayerNorm over the last axis of x[rows][C] (C <= 1024, eps 1e-5, biased variance):
+ *   backward 0: out = y = (x - mean) * rstd * gamma + beta       (dy, add, dgamma, dbeta, workspace unused)
+ *   backward 1: out = dx (+ add, may be NULL); dgamma[C] += sum dy * xhat; dbeta[C] += sum dy;
+ *               workspace: 8 * rows + 8 * C * ceil(rows / 32) + 256 bytes (CDP_EINVAL if smaller). */
+int cdp_k_layernorm(int dtype, int backward, const void* x, const void* dy, const void* add, const float* gamma,
+                    const float* beta, void* out, float* dgamma, float* dbeta, void* workspace,
+                    size_t workspace_bytes, int rows, int C, void* stream);
+
+/* Exact GELU on n elements: backward 0: out = x * Phi(x); backward 1: out = dy * (Phi(x) + x * phi(x)). */
+int cdp_k_gelu(int dtype, int backward, const void* x, const void* dy, void* out, int64_t n, void* stream);
+
+/* Multi-head self-attention core on qkv[B][T][3*D] (q | k | v per token, head h in columns
+ * h*D/heads..; T <= 1024):
+ *   backward 0: P[B][heads][T][T] = softmax(q k^T / sqrt(D/heads)) (written), out[B][T][D] = P v
+ *   backward 1: out = dqkv[B][T][3*D] from P (read) and dout[B][T][D]
+ * workspace: 4 * B*heads*T*T bytes (forward), (4 + element size) * B*heads*T*T + 256 bytes (backward). */
+int cdp_k_attention(int dtype, int backward, const void* qkv, void* P, const void* dout, void* out, void* workspace,
+                    size_t workspace_bytes, int B, int T, int D, int heads, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -22,7 +22,7 @@ CDP_F32, CDP_BF16 = 0, 1
 EXPORTS = ["cdp_arena_bytes", "cdp_init", "cdp_set_weights", "cdp_param_count", "cdp_tick", "cdp_step",
            "cdp_drain", "cdp_get_weights", "cdp_get_losses", "cdp_get_trace", "cdp_get_live_counts",
            "cdp_get_stats", "cdp_last_error", "cdp_destroy", "cdp_profile_gemm", "cdp_get_gemm_profile",
-           "cdp_k_gemm", "cdp_k_conv"]
+           "cdp_k_gemm", "cdp_k_conv", "cdp_k_layernorm", "cdp_k_gelu", "cdp_k_attention"]
 
 
 class cdp_layer_desc(C.Structure):
@@ -93,6 +93,9 @@ def lib() -> C.CDLL:
         L.cdp_get_gemm_profile.argtypes = [vp, C.POINTER(cdp_gemm_profile)]
         L.cdp_k_gemm.argtypes = [i32, i32, i32, i32, vp, vp, vp, i32, i32, i32, i32, i32, vp]
         L.cdp_k_conv.argtypes = [i32, i32, vp, vp, vp, i32, i32, i32, i32, i32, i32, i32, i32, vp, sz, vp]
+        L.cdp_k_layernorm.argtypes = [i32, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, i32, i32, vp]
+        L.cdp_k_gelu.argtypes = [i32, i32, vp, vp, vp, C.c_int64, vp]
+        L.cdp_k_attention.argtypes = [i32, i32, vp, vp, vp, vp, vp, sz, i32, i32, i32, i32, vp]
         for name in EXPORTS:
             if name not in ("cdp_last_error", "cdp_destroy"):
                 getattr(L, name).restype = C.c_int
@@ -242,6 +245,27 @@ def cdp_k_conv(dtype, which, in0_ptr, in1_ptr, out_ptr, B, H, W, Cin, Cout, ks, 
                           ws_bytes, stream or None)
     if rc != CDP_OK:
         raise CdpError(rc, "cdp_k_conv")
+
+
+def cdp_k_layernorm(dtype, backward, x_ptr, dy_ptr, add_ptr, gamma_ptr, beta_ptr, out_ptr, dgamma_ptr, dbeta_ptr, ws_ptr,
+                    ws_bytes, rows, C_, stream=0) -> None:
+    rc = lib().cdp_k_layernorm(dtype, backward, x_ptr, dy_ptr or None, add_ptr or None, gamma_ptr, beta_ptr or None, out_ptr,
+                               dgamma_ptr or None, dbeta_ptr or None, ws_ptr or None, ws_bytes, rows, C_, stream or None)
+    if rc != CDP_OK:
+        raise CdpError(rc, "cdp_k_layernorm")
+
+
+def cdp_k_gelu(dtype, backward, x_ptr, dy_ptr, out_ptr, n, stream=0) -> None:
+    rc = lib().cdp_k_gelu(dtype, backward, x_ptr, dy_ptr or None, out_ptr, n, stream or None)
+    if rc != CDP_OK:
+        raise CdpError(rc, "cdp_k_gelu")
+
+
+def cdp_k_attention(dtype, backward, qkv_ptr, P_ptr, dout_ptr, out_ptr, ws_ptr, ws_bytes, B, T, D, heads, stream=0) -> None:
+    rc = lib().cdp_k_attention(dtype, backward, qkv_ptr, P_ptr, dout_ptr or None, out_ptr, ws_ptr, ws_bytes, B, T, D, heads,
+                               stream or None)
+    if rc != CDP_OK:
+        raise CdpError(rc, "cdp_k_attention")
 
 
 # ---- convenience wrapper used by tests and bench -------------------------------------------

@@ -92,4 +92,42 @@ int cdp_k_conv(int dtype, int which, const void* in0, const void* in1, void* out
   return launch_gemm_batch(b, dtype, shape, st) == hipSuccess ? CDP_OK : CDP_EHIP;
 }
 
+int cdp_k_layernorm(int dtype, int backward, const void* x, const void* dy, const void* add, const float* gamma,
+                    const float* beta, void* out, float* dgamma, float* dbeta, void* workspace, size_t workspace_bytes,
+                    int rows, int C, void* stream) {
+  if (!x || !gamma || !out || rows <= 0 || C <= 0 || C > 1024 || (dtype != DT_F32 && dtype != DT_BF16)) return CDP_EINVAL;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  if (!backward) {
+    if (!beta) return CDP_EINVAL;
+    return launch_layernorm_fwd(x, gamma, beta, out, rows, C, dtype, st) == hipSuccess ? CDP_OK : CDP_EHIP;
+  }
+  if (!dy || !dgamma || !dbeta || !workspace || (int64_t)workspace_bytes < layernorm_bwd_workspace_bytes(rows, C)) return CDP_EINVAL;
+  return launch_layernorm_bwd(x, dy, add, gamma, out, dgamma, dbeta, static_cast<float*>(workspace), rows, C, dtype, st) == hipSuccess
+             ? CDP_OK : CDP_EHIP;
+}
+
+int cdp_k_gelu(int dtype, int backward, const void* x, const void* dy, void* out, int64_t n, void* stream) {
+  if (!x || !out || n <= 0 || (backward && !dy) || (dtype != DT_F32 && dtype != DT_BF16)) return CDP_EINVAL;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  const hipError_t e = backward ? launch_gelu_bwd(x, dy, out, n, dtype, st) : launch_gelu_fwd(x, out, n, dtype, st);
+  return e == hipSuccess ? CDP_OK : CDP_EHIP;
+}
+
+int cdp_k_attention(int dtype, int backward, const void* qkv, void* P, const void* dout, void* out, void* workspace,
+                    size_t workspace_bytes, int B, int T, int D, int heads, void* stream) {
+  if (!qkv || !P || !out || !workspace || B <= 0 || T <= 0 || T > 1024 || D <= 0 || heads <= 0 || D % heads ||
+      (dtype != DT_F32 && dtype != DT_BF16))
+    return CDP_EINVAL;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  const int64_t tt = (int64_t)B * heads * T * T;
+  if (!backward) {
+    if ((int64_t)workspace_bytes < 4 * tt) return CDP_EINVAL;
+    return launch_attention_fwd(qkv, P, out, static_cast<float*>(workspace), B, T, D, heads, dtype, st) == hipSuccess ? CDP_OK : CDP_EHIP;
+  }
+  const int64_t dp_bytes = (4 * tt + 255) / 256 * 256;
+  if (!dout || (int64_t)workspace_bytes < dp_bytes + tt * (dtype == DT_BF16 ? 2 : 4)) return CDP_EINVAL;
+  return launch_attention_bwd(qkv, P, dout, out, static_cast<float*>(workspace), static_cast<char*>(workspace) + dp_bytes, B, T, D,
+                              heads, dtype, st) == hipSuccess ? CDP_OK : CDP_EHIP;
+}
+
 }  // extern "C"

@@ -1,5 +1,6 @@
 """Kernel-level parity on the GPU: the tile contraction (every operand layout, tile shape
-and dtype, ragged sizes) and the implicit-GEMM convolution passes against the oracle."""
+and dtype, ragged sizes), the implicit-GEMM convolution passes and the kernels of the ViT-shaped
+stages (LayerNorm, GELU, attention core) against the oracle."""
 import numpy as np
 import pytest
 
@@ -130,4 +131,96 @@ def test_conv_gemm_many_tiles(dtype, which):
     g = got.float().cpu().numpy().astype(np.float64)
     assert np.isfinite(g).all()
     assert np.abs(g - ref).max() / np.abs(ref).max() <= tol
+
+
+def _close(got, ref, tol, what):
+    g = got.float().cpu().numpy().astype(np.float64).reshape(ref.shape)
+    assert np.isfinite(g).all(), what
+    err = np.abs(g - ref).max() / max(1e-6, np.abs(ref).max())
+    assert err <= tol, (what, err)
+
+
+@pytest.mark.parametrize("dtype", [wl.F32, wl.BF16])
+@pytest.mark.parametrize("rows,C", [(6272, 768), (100, 20), (37, 1000), (5, 3)])
+def test_layernorm_kernels_match_oracle(dtype, rows, C):
+    """Forward and backward (with a residual addend and running gamma / beta sums) at the
+    ViT-B/16 shape and at ragged ones (rows that are not whole 16-byte chunks take the
+    element-wise kernels)."""
+    torch = _torch()
+    tdt = torch.bfloat16 if dtype == wl.BF16 else torch.float32
+    x = wl.random_normal(7, 1, rows * C).reshape(rows, C) * 1.5 + 0.3
+    dy = wl.random_normal(7, 2, rows * C).reshape(rows, C)
+    add = wl.random_normal(7, 3, rows * C).reshape(rows, C)
+    gamma = 1.0 + 0.2 * wl.random_normal(7, 4, C)
+    beta = 0.1 * wl.random_normal(7, 5, C)
+    g0, b0 = wl.random_normal(7, 6, C), wl.random_normal(7, 7, C)   # running sums the backward adds to
+    xr, dyr, addr = _rnd(x, dtype), _rnd(dy, dtype), _rnd(add, dtype)
+    gam, bet = _rnd(gamma, wl.F32), _rnd(beta, wl.F32)
+    y = L.layernorm_fwd(xr, gam, bet)
+    dx, dg, db = L.layernorm_bwd(xr, gam, dyr)
+    xd, dyd, addd = _dev(x, dtype), _dev(dy, dtype), _dev(add, dtype)
+    gd, bd = _dev(gamma, wl.F32), _dev(beta, wl.F32)
+    yd = torch.full((rows, C), float("nan"), dtype=tdt, device="cuda")
+    b.cdp_k_layernorm(dtype, 0, xd.data_ptr(), 0, 0, gd.data_ptr(), bd.data_ptr(), yd.data_ptr(), 0, 0, 0, 0, rows, C)
+    dxd = torch.full((rows, C), float("nan"), dtype=tdt, device="cuda")
+    dgd, dbd = _dev(g0, wl.F32), _dev(b0, wl.F32)
+    ws = torch.full((2 * rows + 2 * C * ((rows + 31) // 32) + 64,), float("nan"), dtype=torch.float32, device="cuda")
+    b.cdp_k_layernorm(dtype, 1, xd.data_ptr(), dyd.data_ptr(), addd.data_ptr(), gd.data_ptr(), 0, dxd.data_ptr(),
+                      dgd.data_ptr(), dbd.data_ptr(), ws.data_ptr(), ws.numel() * 4, rows, C)
+    torch.cuda.synchronize()
+    tol = 2.0 ** -7 if dtype == wl.BF16 else 1e-5
+    _close(yd, y, tol, "y")
+    _close(dxd, dx + addr, tol, "dx")
+    _close(dgd, _rnd(g0, wl.F32) + dg, 1e-5, "dgamma")
+    _close(dbd, _rnd(b0, wl.F32) + db, 1e-5, "dbeta")
+
+
+@pytest.mark.parametrize("dtype", [wl.F32, wl.BF16])
+def test_gelu_kernels_match_oracle(dtype):
+    torch = _torch()
+    tdt = torch.bfloat16 if dtype == wl.BF16 else torch.float32
+    n = 1000003   # not a multiple of the vector width: the tail runs element by element
+    x = wl.random_normal(8, 1, n) * 2.0
+    dy = wl.random_normal(8, 2, n)
+    xr, dyr = _rnd(x, dtype), _rnd(dy, dtype)
+    xd, dyd = _dev(x, dtype), _dev(dy, dtype)
+    yd = torch.full((n,), float("nan"), dtype=tdt, device="cuda")
+    dxd = torch.full((n,), float("nan"), dtype=tdt, device="cuda")
+    b.cdp_k_gelu(dtype, 0, xd.data_ptr(), 0, yd.data_ptr(), n)
+    b.cdp_k_gelu(dtype, 1, xd.data_ptr(), dyd.data_ptr(), dxd.data_ptr(), n)
+    torch.cuda.synchronize()
+    tol = 2.0 ** -7 if dtype == wl.BF16 else 2e-6
+    _close(yd, L.gelu_fwd(xr), tol, "gelu")
+    _close(dxd, L.gelu_bwd(xr, dyr), tol, "dgelu")
+
+
+@pytest.mark.parametrize("dtype", [wl.F32, wl.BF16])
+@pytest.mark.parametrize("B,T,D,heads", [(2, 196, 768, 12), (3, 9, 20, 4), (1, 324, 16, 2), (2, 16, 32, 4)])
+def test_attention_kernels_match_oracle(dtype, B, T, D, heads):
+    """Probabilities, output and the gradient with respect to q | k | v: the ViT-B/16 shape,
+    a shape where nothing is a multiple of four (element-wise staging, ragged tiles), 324
+    tokens, and the reduced test shape."""
+    torch = _torch()
+    tdt = torch.bfloat16 if dtype == wl.BF16 else torch.float32
+    eb = 2 if dtype == wl.BF16 else 4
+    qkv = wl.random_normal(9, 1, B * T * 3 * D).reshape(B, 1, T, 3 * D)
+    dout = wl.random_normal(9, 2, B * T * D).reshape(B, 1, T, D)
+    qr, dor = _rnd(qkv, dtype), _rnd(dout, dtype)
+    rnd = (lambda a: _rnd(a, dtype))
+    out, P = L.attention_fwd(qr, heads, rnd)
+    dqkv = L.attention_bwd(qr, P, heads, dor, rnd)
+    qd, dod = _dev(qkv, dtype), _dev(dout, dtype)
+    tt = B * heads * T * T
+    Pd = torch.full((B, heads, T, T), float("nan"), dtype=tdt, device="cuda")
+    outd = torch.full((B, T, D), float("nan"), dtype=tdt, device="cuda")
+    dqd = torch.full((B, T, 3 * D), float("nan"), dtype=tdt, device="cuda")
+    ws = torch.full((2 * tt + 128,), float("nan"), dtype=torch.float32, device="cuda")
+    b.cdp_k_attention(dtype, 0, qd.data_ptr(), Pd.data_ptr(), 0, outd.data_ptr(), ws.data_ptr(), ws.numel() * 4, B, T, D, heads)
+    b.cdp_k_attention(dtype, 1, qd.data_ptr(), Pd.data_ptr(), dod.data_ptr(), dqd.data_ptr(), ws.data_ptr(), ws.numel() * 4,
+                      B, T, D, heads)
+    torch.cuda.synchronize()
+    tol = 2.0 ** -6 if dtype == wl.BF16 else 2e-5
+    _close(Pd, P, tol, "P")
+    _close(outd, out, tol, "out")
+    _close(dqd, dqkv, tol, "dqkv")
 
