@@ -64,6 +64,47 @@ def conv(which, B, H, W, Cin, Cout, ks, st, pad, reps=20):
     return us, flops / us / 1e6, byts / us / 1e3
 
 
+def vit_kernels(reps=50):
+    """LayerNorm, GELU and the attention core at the ViT-B/16 shapes of one micro-batch (bf16):
+    (label, microseconds, algorithmic GB/s)."""
+    rows, D, H, T, Bn = 6272, 768, 12, 196, 32
+    bf = torch.bfloat16
+    x = torch.randn(rows, D, device="cuda").to(bf)
+    dy = torch.randn(rows, D, device="cuda").to(bf)
+    out = torch.empty_like(x)
+    gam, bet = torch.ones(D, device="cuda"), torch.zeros(D, device="cuda")
+    dg, db = torch.zeros(D, device="cuda"), torch.zeros(D, device="cuda")
+    ws = torch.empty(2 * rows + 2 * D * ((rows + 31) // 32) + 64, device="cuda")
+    res = []
+    us = _time(lambda: b.cdp_k_layernorm(1, 0, x.data_ptr(), 0, 0, gam.data_ptr(), bet.data_ptr(), out.data_ptr(), 0, 0, 0, 0,
+                                         rows, D), reps)
+    res.append(("layernorm fwd 6272x768", us, 2 * 2.0 * rows * D / us / 1e3))
+    us = _time(lambda: b.cdp_k_layernorm(1, 1, x.data_ptr(), dy.data_ptr(), 0, gam.data_ptr(), 0, out.data_ptr(), dg.data_ptr(),
+                                         db.data_ptr(), ws.data_ptr(), ws.numel() * 4, rows, D), reps)
+    res.append(("layernorm bwd 6272x768 (3 kernels)", us, 5 * 2.0 * rows * D / us / 1e3))
+    n = rows * 4 * D
+    xg, dyg = torch.randn(n, device="cuda").to(bf), torch.randn(n, device="cuda").to(bf)
+    og = torch.empty_like(xg)
+    us = _time(lambda: b.cdp_k_gelu(1, 0, xg.data_ptr(), 0, og.data_ptr(), n), reps)
+    res.append(("gelu fwd 6272x3072", us, 2 * 2.0 * n / us / 1e3))
+    us = _time(lambda: b.cdp_k_gelu(1, 1, xg.data_ptr(), dyg.data_ptr(), og.data_ptr(), n), reps)
+    res.append(("gelu bwd 6272x3072", us, 3 * 2.0 * n / us / 1e3))
+    qkv = torch.randn(Bn, T, 3 * D, device="cuda").to(bf)
+    do = torch.randn(Bn, T, D, device="cuda").to(bf)
+    tt = Bn * H * T * T
+    P = torch.empty(tt, device="cuda", dtype=bf)
+    o = torch.empty(Bn, T, D, device="cuda", dtype=bf)
+    dq = torch.empty_like(qkv)
+    wsa = torch.empty(2 * tt + 128, device="cuda")
+    us = _time(lambda: b.cdp_k_attention(1, 0, qkv.data_ptr(), P.data_ptr(), 0, o.data_ptr(), wsa.data_ptr(), wsa.numel() * 4,
+                                         Bn, T, D, H), reps)
+    res.append(("attention fwd 32x12 heads, 196 tokens (3 kernels)", us, 2.0 * (qkv.numel() + tt + o.numel()) / us / 1e3))
+    us = _time(lambda: b.cdp_k_attention(1, 1, qkv.data_ptr(), P.data_ptr(), do.data_ptr(), dq.data_ptr(), wsa.data_ptr(),
+                                         wsa.numel() * 4, Bn, T, D, H), reps)
+    res.append(("attention bwd 32x12 heads, 196 tokens (5 kernels)", us, 2.0 * (2 * qkv.numel() + tt + do.numel()) / us / 1e3))
+    return res
+
+
 LINEAR_SHAPES = [  # (label, M, N, K, tile_shape)
     ("cfg2 layer  32x1024x1024 (thin tiles)", 32, 1024, 1024, 5),
     ("cfg2 stem   32x1024x3072 (thin tiles)", 32, 1024, 3072, 5),
@@ -96,6 +137,10 @@ def main():
             continue
         us, tf, gb = linear(M, N, K, shape)
         print("%-42s %8.1f us %7.1f TFLOP/s %7.0f GB/s  hbm %.2f" % (label, us, tf, gb, gb / HBM_PEAK), flush=True)
+    if args.only in "vit kernels":
+        print("# Kernels of the ViT-shaped stages (bf16): us, algorithmic GB/s (inputs and outputs once), fraction of %.0f" % HBM_PEAK)
+        for label, us, gb in vit_kernels():
+            print("%-52s %8.1f us %7.0f GB/s  hbm %.2f" % (label, us, gb, gb / HBM_PEAK), flush=True)
     print("# Convolution passes (cdp_k_conv, bf16): us, TFLOP/s (fraction of %.0f), GB/s (fraction of %.0f)" % (MFMA_PEAK, HBM_PEAK))
     for s in CONV_SHAPES:
         if args.only not in s[0]:
