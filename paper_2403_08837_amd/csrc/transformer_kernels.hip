@@ -28,15 +28,27 @@ template <> __device__ __forceinline__ void tst<float>(float* p, int64_t i, floa
     else { using T = float; CALL; }                       \
   } while (0)
 
+// Wavefront-wide sum / maximum, result in every lane: four rotations inside the 16-lane rows on
+// the VALU (DPP row_ror 1, 2, 4, 8), then two exchanges through the LDS crossbar (instead of six).
+template <int CTRL>
+__device__ __forceinline__ float dpp_rot(float x) {
+  return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), CTRL, 0xf, 0xf, false));
+}
 __device__ __forceinline__ float wsum(float v) {
-#pragma unroll
-  for (int o = 32; o >= 1; o >>= 1) v += __shfl_xor(v, o, 64);
-  return v;
+  v += dpp_rot<0x121>(v);
+  v += dpp_rot<0x122>(v);
+  v += dpp_rot<0x124>(v);
+  v += dpp_rot<0x128>(v);
+  v += __shfl_xor(v, 16, 64);
+  return v + __shfl_xor(v, 32, 64);
 }
 __device__ __forceinline__ float wmax(float v) {
-#pragma unroll
-  for (int o = 32; o >= 1; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
-  return v;
+  v = fmaxf(v, dpp_rot<0x121>(v));
+  v = fmaxf(v, dpp_rot<0x122>(v));
+  v = fmaxf(v, dpp_rot<0x124>(v));
+  v = fmaxf(v, dpp_rot<0x128>(v));
+  v = fmaxf(v, __shfl_xor(v, 16, 64));
+  return fmaxf(v, __shfl_xor(v, 32, 64));
 }
 
 constexpr float LN_EPS = 1e-5f;
