@@ -119,9 +119,10 @@ __global__ __launch_bounds__(256) void conv_gemm_kernel(const GemmBatch batch) {
         if (mode == OP_CONV_FWD) {
           const int ih0 = oh * g.stride - g.pad, iw0 = ow * g.stride - g.pad;
           abase[i] = ((b * g.H + ih0) * g.W + iw0) * g.C;
-          for (int kh = 0; kh < g.KH; ++kh)
-            for (int kw = 0; kw < g.KW; ++kw)
-              if (ih0 + kh >= 0 && ih0 + kh < g.H && iw0 + kw >= 0 && iw0 + kw < g.W) amask[i] |= 1u << (kh * g.KW + kw);
+          // taps inside the image: the columns kw with 0 <= iw0 + kw < W, for every row kh with 0 <= ih0 + kh < H
+          const int kw_lo = max(0, -iw0), kw_hi = min(g.KW, g.W - iw0);
+          const unsigned cols = kw_hi > kw_lo ? ((1u << kw_hi) - 1u) & ~((1u << kw_lo) - 1u) : 0u;
+          for (int kh = max(0, -ih0); kh < min(g.KH, g.H - ih0); ++kh) amask[i] |= cols << (kh * g.KW);
         } else {  // OP_CONV_DGRAD: (oh, ow) is an input position, the gathered tensor is dy
           const int qh = (oh + g.pad) / g.stride, eh = (oh + g.pad) - qh * g.stride;
           const int qw = (ow + g.pad) / g.stride, ew = (ow + g.pad) - qw * g.stride;
