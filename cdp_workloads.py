@@ -371,6 +371,10 @@ def get_config(name: str) -> Config:
     if name == "vit_b16":        # ViT-B/16-shaped: 196 tokens of width 768, 12 heads, 12 block stages
         return Config("vit_b16", _vit(224, 16, 768, 12, 12, 1000), (224, 224, 3), 1000, N=8, B=32, dtype=BF16, lr=0.01,
                       steps=2, init_gain_last_affine=0.25, init_gain_head=0.2, notes="ViT-B/16-shaped")
+    if name == "cfg4_s64":       # the ResNet-50 configuration with 64x64 inputs: every stage at its real channel widths,
+        c = get_config("cfg4")   # N = 8 micro-batches of 32, at 1/12 of the oracle's cost
+        c.name, c.in_shape, c.steps = "cfg4_s64", (64, 64, 3), 3
+        return c
     if name == "resnet50_mini_f32":
         c = get_config("resnet50_mini")
         c.name, c.dtype = "resnet50_mini_f32", F32

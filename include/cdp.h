@@ -184,6 +184,15 @@ int cdp_get_trace(const cdp_ctx* ctx, cdp_trace_rec* out, size_t cap, size_t* n_
 /* In-tick count of retained stage inputs for every tick run so far. Host-only. */
 int cdp_get_live_counts(const cdp_ctx* ctx, int32_t* out, size_t cap, size_t* n_out);
 
+/* In-tick activation bytes for every tick run so far (Sec. 4.1: the memory the cyclic schedule keeps
+ * nearly constant over the time steps; Table 1, rows "Single-GPU").  kind 0: bytes retained for a later
+ * backward (stage inputs and the intermediates a backward reads; same counting as the live count: a
+ * forward of the tick has stored, a backward of the tick has not released); kind 1: everything the
+ * activation pool holds while the tick's kernels run (adds activations / gradients travelling between
+ * stages).  Constant over steady-state ticks for homogeneous stages except for the head's extra
+ * tensors, periodic with the delay d in general.  Host-only. */
+int cdp_get_live_bytes(const cdp_ctx* ctx, int kind, int64_t* out, size_t cap, size_t* n_out);
+
 int cdp_get_stats(const cdp_ctx* ctx, cdp_stats* out);
 
 /* Timing of the grouped contraction launches, the dominant kernel of a tick (forward,

@@ -125,11 +125,11 @@ def sgd_update(w: np.ndarray, gsum: np.ndarray, v: Optional[np.ndarray], lr: flo
 
 
 def train_equation(cfg: wl.Config, params0, xs: Sequence[np.ndarray], ys: Sequence[np.ndarray],
-                   rule: int, lr: Optional[float] = None,
-                   rnd: Callable[[np.ndarray], np.ndarray] = L.identity,
+                   rule: int, lr: Optional[float] = None, stage_impl=None,
                    momentum: float = 0.0, weight_decay: float = 0.0, mask=None) -> Result:
     """theta_{t+1} = theta_t - (lr/N) sum_i grad f_i(theta_hat_{i,t}),
-    theta_hat^j_{i,t} = theta^j_t if fresh(i,j) else theta^j_{t-1}, theta_{-1} := theta_0."""
+    theta_hat^j_{i,t} = theta^j_t if fresh(i,j) else theta^j_{t-1}, theta_{-1} := theta_0.
+    ``stage_impl``: see train_schedule."""
     S, N, B = cfg.S, cfg.N, cfg.B
     lr = cfg.lr if lr is None else lr
     d = delay_for(S, N, rule)
@@ -144,7 +144,7 @@ def train_equation(cfg: wl.Config, params0, xs: Sequence[np.ndarray], ys: Sequen
             mix = [cur[j] if fresh_closed_form(rule, S, N, d, i, j, mask) else prev[j] for j in range(S)]
             x = np.asarray(xs[t][i * B:(i + 1) * B], dtype=np.float64)
             y = np.asarray(ys[t][i * B:(i + 1) * B])
-            loss, grads = L.model_forward_backward(cfg.stages, mix, rnd(x), y, rnd)
+            loss, grads = L.model_forward_backward(cfg.stages, mix, x, y, stage_impl)
             losses[t, i] = loss
             for j in range(S):
                 for a, g in zip(gsum[j], grads[j]):
@@ -164,8 +164,7 @@ def train_equation(cfg: wl.Config, params0, xs: Sequence[np.ndarray], ys: Sequen
 # Oracle B: the execution timeline, tick by tick
 # ---------------------------------------------------------------------------
 def train_schedule(cfg: wl.Config, params0, xs: Sequence[np.ndarray], ys: Sequence[np.ndarray],
-                   rule: int, lr: Optional[float] = None,
-                   rnd: Callable[[np.ndarray], np.ndarray] = L.identity,
+                   rule: int, lr: Optional[float] = None, stage_impl=None,
                    compute: bool = True, keep_versions: bool = True,
                    progress: Optional[Callable[[int, int], None]] = None,
                    momentum: float = 0.0, weight_decay: float = 0.0, mask=None, bwd_fresh: bool = False) -> Result:
@@ -177,6 +176,11 @@ def train_schedule(cfg: wl.Config, params0, xs: Sequence[np.ndarray], ys: Sequen
     integer bookkeeping only (trace, versions, live counts); ``keep_versions=False`` does
     not retain superseded weight versions (large models); ``progress(tick, n_ticks)`` is
     called after every tick.
+
+    ``stage_impl`` (tests only): an object with prepare_input(x), forward(stage, params, x,
+    labels) and backward(stage, params, saved, dy) that stands in for the identity and for
+    layers.stage_forward / layers.stage_backward, e.g. a copy of them that rounds stored
+    tensors to a storage format.  The timeline, the rule and the update stay the ones here.
 
     ``mask`` (RULE_MASK): N x S array; forward (i, j) reads the freshest version where
     mask[i][j] is set, theta_{t-1} elsewhere.
@@ -190,6 +194,8 @@ def train_schedule(cfg: wl.Config, params0, xs: Sequence[np.ndarray], ys: Sequen
     lr = cfg.lr if lr is None else lr
     d = delay_for(S, N, rule)
     T = len(xs)
+    stage_fwd = L.stage_forward if stage_impl is None else stage_impl.forward
+    stage_bwd = L.stage_backward if stage_impl is None else stage_impl.backward
     ring = [[_copy_params([params0[j]])[0], _copy_params([params0[j]])[0]] for j in range(S)] if compute \
         else [[None, None] for _ in range(S)]
     ring_ver = [[0, 0] for _ in range(S)]        # which version each slot currently holds
@@ -222,9 +228,11 @@ def train_schedule(cfg: wl.Config, params0, xs: Sequence[np.ndarray], ys: Sequen
                 used[(t, i, j)] = v
                 if compute:
                     if j == 0:
-                        carry[(t, i)] = rnd(np.asarray(xs[t][i * B:(i + 1) * B], dtype=np.float64))
+                        carry[(t, i)] = np.asarray(xs[t][i * B:(i + 1) * B], dtype=np.float64)
+                        if stage_impl is not None:
+                            carry[(t, i)] = stage_impl.prepare_input(carry[(t, i)])
                     lab = np.asarray(ys[t][i * B:(i + 1) * B]) if j == S - 1 else None
-                    out, sv = L.stage_forward(cfg.stages[j], ring[j][v % 2], carry[(t, i)], lab, rnd)
+                    out, sv = stage_fwd(cfg.stages[j], ring[j][v % 2], carry[(t, i)], lab)
                     saved[(t, i, j)] = sv
                     if j == S - 1:
                         res.losses[t, i] = out
@@ -240,7 +248,7 @@ def train_schedule(cfg: wl.Config, params0, xs: Sequence[np.ndarray], ys: Sequen
                 assert ring_ver[j][v % 2] == v, "ring depth 2 violated (bwd)"
                 sv = saved.pop((t, i, j))
                 if compute:
-                    dx, grads = L.stage_backward(cfg.stages[j], ring[j][v % 2], sv, carry[(t, i)], rnd)
+                    dx, grads = stage_bwd(cfg.stages[j], ring[j][v % 2], sv, carry[(t, i)])
                     carry[(t, i)] = dx
                     if j == 0:
                         del carry[(t, i)]

@@ -33,10 +33,6 @@ def round_bf16(a: Array) -> Array:
     return u.astype(np.uint32).view(np.float32).reshape(f.shape).astype(np.float64)
 
 
-def identity(a: Array) -> Array:
-    return a
-
-
 # ---------------------------------------------------------------------------
 # individual layers
 # ---------------------------------------------------------------------------
@@ -61,7 +57,8 @@ def conv2d_fwd(x: Array, W: Array, stride: int, pad: int) -> Array:
     for kh in range(KH):
         for kw in range(KW):
             xs = xp[:, kh:kh + stride * (Ho - 1) + 1:stride, kw:kw + stride * (Wo - 1) + 1:stride, :]
-            y += xs @ W[:, kh, kw, :].T
+            # one matrix product per tap on contiguous copies (a strided view would take numpy's slow path)
+            y += (np.ascontiguousarray(xs).reshape(-1, C) @ np.ascontiguousarray(W[:, kh, kw, :].T)).reshape(Bn, Ho, Wo, O)
     return y
 
 
@@ -72,13 +69,13 @@ def conv2d_bwd(x: Array, W: Array, stride: int, pad: int, dy: Array):
     xp = np.pad(x, ((0, 0), (pad, pad), (pad, pad), (0, 0)))
     dxp = np.zeros_like(xp)
     dW = np.zeros_like(W)
-    dy2 = dy.reshape(-1, O)
+    dy2 = np.ascontiguousarray(dy).reshape(-1, O)
     for kh in range(KH):
         for kw in range(KW):
             sl = (slice(None), slice(kh, kh + stride * (Ho - 1) + 1, stride),
                   slice(kw, kw + stride * (Wo - 1) + 1, stride), slice(None))
-            dW[:, kh, kw, :] = dy2.T @ xp[sl].reshape(-1, C)
-            dxp[sl] += dy @ W[:, kh, kw, :]
+            dW[:, kh, kw, :] = dy2.T @ np.ascontiguousarray(xp[sl]).reshape(-1, C)
+            dxp[sl] += (dy2 @ np.ascontiguousarray(W[:, kh, kw, :])).reshape(Bn, Ho, Wo, C)
     dx = dxp[:, pad:pad + H, pad:pad + Wd, :]
     return dx, dW
 
@@ -176,35 +173,54 @@ def _split_qkv(qkv: Array, heads: int):
     return q, k, v, dh   # each [B, heads, T, dh]
 
 
-def attention_fwd(qkv: Array, heads: int, rnd: Callable[[Array], Array] = None):
-    """Per head: P = softmax(q k^T / sqrt(dh)) over the keys, out = P v.  Returns (out, P);
-    P is what the backward pass keeps (rounded like a stored tensor when rnd is given)."""
+def attention_probs(qkv: Array, heads: int) -> Array:
+    """P[b, h] = softmax over the keys of q k^T / sqrt(dh), per sample and head: [B, heads, T, T]."""
     q, k, v, dh = _split_qkv(qkv, heads)
     s = (q @ k.transpose(0, 1, 3, 2)) / np.sqrt(dh)
     s = s - s.max(axis=-1, keepdims=True)
     e = np.exp(s)
-    P = e / e.sum(axis=-1, keepdims=True)
-    if rnd is not None:
-        P = rnd(P)
+    return e / e.sum(axis=-1, keepdims=True)
+
+
+def attention_apply(qkv: Array, P: Array, heads: int) -> Array:
+    """out = P v per head, heads concatenated along the channel axis: [B, 1, T, D]."""
+    q, k, v, dh = _split_qkv(qkv, heads)
     o = P @ v                                             # [B, heads, T, dh]
     Bn, _, T, _ = o.shape
-    return o.transpose(0, 2, 1, 3).reshape(Bn, 1, T, heads * dh), P
+    return o.transpose(0, 2, 1, 3).reshape(Bn, 1, T, heads * dh)
 
 
-def attention_bwd(qkv: Array, P: Array, heads: int, dout: Array, rnd: Callable[[Array], Array] = None) -> Array:
-    """dv = P^T do; dP = do v^T; ds = P * (dP - rowsum(dP * P)) / sqrt(dh); dq = ds k; dk = ds^T q."""
+def attention_fwd(qkv: Array, heads: int):
+    """Per head: P = softmax(q k^T / sqrt(dh)) over the keys, out = P v.  Returns (out, P);
+    P is what the backward pass keeps."""
+    P = attention_probs(qkv, heads)
+    return attention_apply(qkv, P, heads), P
+
+
+def attention_score_grad(qkv: Array, P: Array, heads: int, dout: Array) -> Array:
+    """ds = P * (dP - rowsum(dP * P)) / sqrt(dh) with dP = do v^T: gradient of the scaled scores."""
+    q, k, v, dh = _split_qkv(qkv, heads)
+    Bn, _, T, D = dout.shape
+    do = dout[:, 0].reshape(Bn, T, heads, dh).transpose(0, 2, 1, 3)
+    dP = do @ v.transpose(0, 1, 3, 2)
+    return P * (dP - (dP * P).sum(axis=-1, keepdims=True)) / np.sqrt(dh)
+
+
+def attention_input_grad(qkv: Array, P: Array, ds: Array, heads: int, dout: Array) -> Array:
+    """dq = ds k; dk = ds^T q; dv = P^T do, laid out like qkv."""
     q, k, v, dh = _split_qkv(qkv, heads)
     Bn, _, T, D = dout.shape
     do = dout[:, 0].reshape(Bn, T, heads, dh).transpose(0, 2, 1, 3)
     dv = P.transpose(0, 1, 3, 2) @ do
-    dP = do @ v.transpose(0, 1, 3, 2)
-    ds = P * (dP - (dP * P).sum(axis=-1, keepdims=True)) / np.sqrt(dh)
-    if rnd is not None:
-        ds = rnd(ds)
     dq = ds @ k
     dk = ds.transpose(0, 1, 3, 2) @ q
     parts = [t.transpose(0, 2, 1, 3).reshape(Bn, T, D) for t in (dq, dk, dv)]
     return np.concatenate(parts, axis=-1)[:, None, :, :]
+
+
+def attention_bwd(qkv: Array, P: Array, heads: int, dout: Array) -> Array:
+    """dv = P^T do; dP = do v^T; ds = P * (dP - rowsum(dP * P)) / sqrt(dh); dq = ds k; dk = ds^T q."""
+    return attention_input_grad(qkv, P, attention_score_grad(qkv, P, heads, dout), heads, dout)
 
 
 def ce_fwd(logits: Array, labels: Array):
@@ -233,25 +249,12 @@ def split_params(stage: Sequence[wl.Layer], params: Sequence[Array]) -> List[Lis
     return out
 
 
-def materialized(stage: Sequence[wl.Layer]) -> List[bool]:
-    """materialized[k+1]: tensor k+1 is written to memory by a fused kernel of the
-    bf16 device path (the next layer is not an elementwise follower of it).  Only
-    used by the optional rounding emulation."""
-    m = [True] * (len(stage) + 1)
-    for k, layer in enumerate(stage):
-        nxt = stage[k + 1] if k + 1 < len(stage) else None
-        if nxt is not None and nxt.src < 0 and nxt.kind in (wl.RELU, wl.AFFINE, wl.ADD, wl.CE_HEAD, wl.TOKENS):
-            m[k + 1] = False
-    return m
-
-
 def stage_forward(stage: Sequence[wl.Layer], params: Sequence[Array], x: Array,
-                  labels: Optional[Array] = None, rnd: Callable[[Array], Array] = identity):
+                  labels: Optional[Array] = None):
     """Run every layer in order.  Returns (output, saved) where output is the last
     tensor, or the scalar loss if the stage ends in a CE head; ``saved`` holds what
     the backward pass needs."""
     lp = split_params(stage, params)
-    mat = materialized(stage)
     tensors: List[Array] = [x]
     aux: List[object] = []
     loss = None
@@ -260,13 +263,13 @@ def stage_forward(stage: Sequence[wl.Layer], params: Sequence[Array], x: Array,
         kind, p = layer.kind, layer.p
         a = None
         if kind == wl.LINEAR:
-            y = linear_fwd(src, rnd(lp[k][0]), rnd(lp[k][1]))
+            y = linear_fwd(src, lp[k][0], lp[k][1])
         elif kind == wl.RELU:
             y = np.maximum(src, 0.0)
         elif kind == wl.CONV2D:
-            y = conv2d_fwd(src, rnd(lp[k][0]), p[3], p[4])
+            y = conv2d_fwd(src, lp[k][0], p[3], p[4])
         elif kind == wl.AFFINE:
-            y = affine_fwd(src, rnd(lp[k][0]), rnd(lp[k][1]))
+            y = affine_fwd(src, lp[k][0], lp[k][1])
         elif kind == wl.ADD:
             y = src + tensors[p[0]]
         elif kind == wl.MAXPOOL:
@@ -274,35 +277,30 @@ def stage_forward(stage: Sequence[wl.Layer], params: Sequence[Array], x: Array,
         elif kind == wl.GAP:
             y = gap_fwd(src)
         elif kind == wl.LAYERNORM:
-            y = layernorm_fwd(src, lp[k][0], lp[k][1])   # fp32 parameters on the device path as well
+            y = layernorm_fwd(src, lp[k][0], lp[k][1])
         elif kind == wl.GELU:
             y = gelu_fwd(src)
         elif kind == wl.TOKENS:
             y = src.reshape(src.shape[0], 1, src.shape[1] * src.shape[2], src.shape[3])
         elif kind == wl.ATTENTION:
-            y, a = attention_fwd(src, p[0], None if rnd is identity else rnd)
+            y, a = attention_fwd(src, p[0])
         elif kind == wl.CE_HEAD:
             assert labels is not None and k == len(stage) - 1
             loss, a = ce_fwd(src, labels)
-            a = rnd(a)
             y = np.zeros(())
         else:
             raise ValueError(kind)
-        if mat[k + 1] and kind != wl.CE_HEAD:
-            y = rnd(y)
         tensors.append(y)
         aux.append(a)
     saved = {"tensors": tensors, "aux": aux}
     return (loss if loss is not None else tensors[-1]), saved
 
 
-def stage_backward(stage: Sequence[wl.Layer], params: Sequence[Array], saved, dy: Optional[Array],
-                   rnd: Callable[[Array], Array] = identity, need_dx: bool = True):
+def stage_backward(stage: Sequence[wl.Layer], params: Sequence[Array], saved, dy: Optional[Array]):
     """Vector-Jacobian product of the whole stage.  ``dy`` is the gradient of the
     micro-batch objective with respect to the stage output (None for a stage that
     ends in the CE head).  Returns (dx, grads) with grads ordered like params."""
     lp = split_params(stage, params)
-    mat = materialized(stage)
     tensors, aux = saved["tensors"], saved["aux"]
     dt: List[Optional[Array]] = [None] * len(tensors)
 
@@ -322,18 +320,16 @@ def stage_backward(stage: Sequence[wl.Layer], params: Sequence[Array], saved, dy
             continue
         g = dt[k + 1]
         assert g is not None, "tensor %d has no consumer" % (k + 1)
-        if mat[k + 1]:
-            g = rnd(g)
         if kind == wl.LINEAR:
-            dx, dW, db = linear_bwd(src, rnd(lp[k][0]), g)
+            dx, dW, db = linear_bwd(src, lp[k][0], g)
             grads[k] = [dW, db]
         elif kind == wl.RELU:
             dx = g * (src > 0)
         elif kind == wl.CONV2D:
-            dx, dW = conv2d_bwd(src, rnd(lp[k][0]), p[3], p[4], g)
+            dx, dW = conv2d_bwd(src, lp[k][0], p[3], p[4], g)
             grads[k] = [dW]
         elif kind == wl.AFFINE:
-            dx, dg, dbeta = affine_bwd(src, rnd(lp[k][0]), g)
+            dx, dg, dbeta = affine_bwd(src, lp[k][0], g)
             grads[k] = [dg, dbeta]
         elif kind == wl.ADD:
             dx = g
@@ -350,28 +346,29 @@ def stage_backward(stage: Sequence[wl.Layer], params: Sequence[Array], saved, dy
         elif kind == wl.TOKENS:
             dx = g.reshape(src.shape)
         elif kind == wl.ATTENTION:
-            dx = attention_bwd(src, aux[k], p[0], g, None if rnd is identity else rnd)
+            dx = attention_bwd(src, aux[k], p[0], g)
         else:
             raise ValueError(kind)
         acc(si, dx)
     flat = [g for gl in grads for g in gl]
-    dx0 = dt[0]
-    if dx0 is not None:
-        dx0 = rnd(dx0)
-    return dx0, flat
+    return dt[0], flat
 
 
-def model_forward_backward(stages, params_per_stage, x, labels, rnd=identity):
+def model_forward_backward(stages, params_per_stage, x, labels, stage_impl=None):
     """Ordinary whole-network forward and backward on one micro-batch, each stage
-    j evaluated at params_per_stage[j].  Returns (loss, grads per stage)."""
+    j evaluated at params_per_stage[j].  Returns (loss, grads per stage).
+    ``stage_impl`` (tests only): an object whose prepare_input / forward / backward replace
+    the identity, stage_forward and stage_backward of this module."""
+    fwd = stage_forward if stage_impl is None else stage_impl.forward
+    bwd = stage_backward if stage_impl is None else stage_impl.backward
     saved = []
-    h = x
+    h = x if stage_impl is None else stage_impl.prepare_input(x)
     for j, st in enumerate(stages):
-        h, sv = stage_forward(st, params_per_stage[j], h, labels if j == len(stages) - 1 else None, rnd)
+        h, sv = fwd(st, params_per_stage[j], h, labels if j == len(stages) - 1 else None)
         saved.append(sv)
     loss = h
     grads = [None] * len(stages)
     dy = None
     for j in range(len(stages) - 1, -1, -1):
-        dy, grads[j] = stage_backward(stages[j], params_per_stage[j], saved[j], dy, rnd)
+        dy, grads[j] = bwd(stages[j], params_per_stage[j], saved[j], dy)
     return loss, grads

@@ -21,7 +21,7 @@ CDP_F32, CDP_BF16 = 0, 1
 
 EXPORTS = ["cdp_arena_bytes", "cdp_init", "cdp_set_weights", "cdp_param_count", "cdp_tick", "cdp_step",
            "cdp_drain", "cdp_get_weights", "cdp_get_losses", "cdp_get_trace", "cdp_get_live_counts",
-           "cdp_get_stats", "cdp_last_error", "cdp_destroy", "cdp_profile_gemm", "cdp_get_gemm_profile",
+           "cdp_get_live_bytes", "cdp_get_stats", "cdp_last_error", "cdp_destroy", "cdp_profile_gemm", "cdp_get_gemm_profile",
            "cdp_k_gemm", "cdp_k_conv", "cdp_k_layernorm", "cdp_k_gelu", "cdp_k_attention"]
 
 
@@ -84,6 +84,7 @@ def lib() -> C.CDLL:
         L.cdp_get_losses.argtypes = [vp, C.c_int64, C.POINTER(C.c_float), sz]
         L.cdp_get_trace.argtypes = [vp, C.POINTER(cdp_trace_rec), sz, C.POINTER(sz)]
         L.cdp_get_live_counts.argtypes = [vp, C.POINTER(C.c_int32), sz, C.POINTER(sz)]
+        L.cdp_get_live_bytes.argtypes = [vp, i32, C.POINTER(C.c_int64), sz, C.POINTER(sz)]
         L.cdp_get_stats.argtypes = [vp, C.POINTER(cdp_stats)]
         L.cdp_last_error.argtypes = [vp]
         L.cdp_last_error.restype = C.c_char_p
@@ -212,6 +213,14 @@ def cdp_get_live_counts(ctx) -> List[int]:
     return list(buf[:n.value])
 
 
+def cdp_get_live_bytes(ctx, kind: int = 0) -> List[int]:
+    n = C.c_size_t(0)
+    _check(lib().cdp_get_live_bytes(ctx, kind, None, 0, C.byref(n)), ctx)
+    buf = (C.c_int64 * max(1, n.value))()
+    _check(lib().cdp_get_live_bytes(ctx, kind, buf, n.value, C.byref(n)), ctx)
+    return list(buf[:n.value])
+
+
 def cdp_get_stats(ctx) -> dict:
     s = cdp_stats()
     _check(lib().cdp_get_stats(ctx, C.byref(s)), ctx)
@@ -325,6 +334,9 @@ class Trainer:
 
     def live_counts(self):
         return cdp_get_live_counts(self.ctx)
+
+    def live_bytes(self, kind: int = 0):
+        return cdp_get_live_bytes(self.ctx, kind)
 
     def stats(self) -> dict:
         return cdp_get_stats(self.ctx)

@@ -125,6 +125,7 @@ struct cdp_ctx {
   std::vector<int> heads_done;                // per logged step: head passes run
   std::vector<cdp_trace_rec> trace;
   std::vector<int32_t> live_counts;
+  std::vector<int64_t> live_bytes[2];         // per tick: retained for a backward | everything the pool holds (in-tick)
   cdp_stats stats;
   int64_t in_features = 0;                    // per-sample input elements
   std::string err;
@@ -910,6 +911,13 @@ int run_tick(cdp_ctx* c, const float* x_dev, const int32_t* y_dev) {
   c->stats.last_live_stage_inputs = live;
   c->stats.peak_live_stage_inputs = std::max<int64_t>(c->stats.peak_live_stage_inputs, live);
   if (c->live_counts.size() < TRACE_CAP) c->live_counts.push_back(live);
+  // bytes retained for a later backward by the passes of earlier ticks (a backward of this tick has
+  // not released its record yet); the forwards of this tick are added below
+  int64_t retained = 0;
+  for (int i = 0; i < N; ++i)
+    for (int j = 0; j < S; ++j)
+      if (c->rec[i][j].live)
+        for (const Block& b : c->rec[i][j].t) retained += b.valid() ? b.bytes : 0;
   c->weights_locked = c->weights_locked || !act.empty();
 
   // weight version of every pass: forward by the update rule, backward as its own forward
@@ -950,6 +958,13 @@ int run_tick(cdp_ctx* c, const float* x_dev, const int32_t* y_dev) {
     for (int q = 0; q < c->groups; ++q)
       if (c->trace.size() < TRACE_CAP)
         c->trace.push_back(cdp_trace_rec{(int32_t)c->tick, v.i * c->groups + q, (int32_t)v.t, v.j, v.dir, v.version});
+  }
+  for (const Visit& v : act)
+    if (v.dir == 0)
+      for (const Block& b : c->rec[v.i][v.j].t) retained += b.valid() ? b.bytes : 0;
+  if (c->live_bytes[0].size() < TRACE_CAP) {
+    c->live_bytes[0].push_back(retained);
+    c->live_bytes[1].push_back(c->pool.in_use);  // nothing released during the tick has been returned yet
   }
   // The folds of the convolution weight-gradient partial sums feed nothing before the end-of-
   // tick update: they leave their levels and run together as the last launch of the program.
@@ -1259,6 +1274,14 @@ int cdp_get_live_counts(const cdp_ctx* c, int32_t* out, size_t cap, size_t* n_ou
   if (!c) return fail(nullptr, CDP_EINVAL, "ctx is NULL");
   if (n_out) *n_out = c->live_counts.size();
   if (out) memcpy(out, c->live_counts.data(), std::min(cap, c->live_counts.size()) * sizeof(int32_t));
+  return CDP_OK;
+}
+
+int cdp_get_live_bytes(const cdp_ctx* c, int kind, int64_t* out, size_t cap, size_t* n_out) {
+  if (!c || kind < 0 || kind > 1) return fail(nullptr, CDP_EINVAL, "bad argument");
+  const std::vector<int64_t>& v = c->live_bytes[kind];
+  if (n_out) *n_out = v.size();
+  if (out) memcpy(out, v.data(), std::min(cap, v.size()) * sizeof(int64_t));
   return CDP_OK;
 }
 

@@ -207,9 +207,10 @@ def test_attention_kernels_match_oracle(dtype, B, T, D, heads):
     qkv = wl.random_normal(9, 1, B * T * 3 * D).reshape(B, 1, T, 3 * D)
     dout = wl.random_normal(9, 2, B * T * D).reshape(B, 1, T, D)
     qr, dor = _rnd(qkv, dtype), _rnd(dout, dtype)
-    rnd = (lambda a: _rnd(a, dtype))
-    out, P = L.attention_fwd(qr, heads, rnd)
-    dqkv = L.attention_bwd(qr, P, heads, dor, rnd)
+    # the stored probabilities and the stored score gradient carry the element type's rounding
+    P = _rnd(L.attention_probs(qr, heads), dtype)
+    out = L.attention_apply(qr, P, heads)
+    dqkv = L.attention_input_grad(qr, P, _rnd(L.attention_score_grad(qr, P, heads, dor), dtype), heads, dor)
     qd, dod = _dev(qkv, dtype), _dev(dout, dtype)
     tt = B * heads * T * T
     Pd = torch.full((B, heads, T, T), float("nan"), dtype=tdt, device="cuda")

@@ -1,15 +1,15 @@
 """End-to-end parity of libcdp (through the C ABI) with the CPU oracle on the same seeded
 inputs: final weights of every stage, every micro-batch loss, and the exact tick trace.
 
-Tolerances (max|w_gpu - w_ref| / max|w_ref|):
-  fp32 configurations: 1e-4 per parameter tensor;
-  bf16 configurations (fp32 accumulate and master weights): 2e-2 per stage vector theta^j.
-  A single tensor that starts at zero (a bias) has a tiny range of its own, and bf16
-  rounding alone moves its update by tens of percent (the oracle run with bf16 rounding
-  at the device path's rounding points differs from the fp64 oracle by the same amount).
-  So per tensor the bf16 check is against that rounding-emulating oracle run, on the
-  applied update in L2: |u_gpu - u_emu| <= 0.5 |u_emu| with u = w_final - w_0, which
-  catches a missing, mis-scaled or misplaced gradient of any single tensor.
+Acceptance criteria (tests/parity_gates.py):
+  fp32 runs: max|w_gpu - w_ref| / max|w_ref| <= 1e-4 for every parameter tensor;
+  bf16 runs: <= 2e-2 over every stage vector theta^j, and per tensor the error of the applied
+  update at most K = 3 times the error of the oracle run again with bf16 rounding wherever a
+  bf16 path stores a value (tests/bf16_emulation.py), both measured against the fp64 oracle.
+Every bf16 configuration is ALSO run with fp32 arithmetic (`also_f32`) at the same shapes, in the
+same launch grouping, against the same oracle run at the fp32 criterion: that is the run which
+would expose a wrong weight version, a dropped micro-batch gradient or a misplaced tile at full
+size, below the bf16 noise floor.
 """
 import numpy as np
 import pytest
@@ -18,6 +18,8 @@ import cdp_workloads as wl
 from oracle import cdp_oracle as O
 from oracle import layers as OL
 from paper_2403_08837_amd import binding as b
+from bf16_emulation import Bf16Storage
+import parity_gates as G
 
 pytestmark = pytest.mark.gpu
 RULES = [wl.RULE_DP, wl.RULE_V1, wl.RULE_V2]
@@ -49,10 +51,11 @@ class Progress:
                 f.write(line)
 
 
-def run_gpu(cfg, rule, T, p0, xs, ys, lr=None, momentum=0.0, weight_decay=0.0, dp_batched=False, mask=None, bwd_fresh=False):
+def run_gpu(cfg, rule, T, p0, xs, ys, lr=None, momentum=0.0, weight_decay=0.0, dp_batched=False, mask=None, bwd_fresh=False,
+            dtype=None):
     import torch
     assert torch.cuda.is_available(), "GPU tests need a GPU"
-    tr = b.Trainer(cfg.stages, cfg.in_shape, cfg.N, cfg.B, cfg.lr if lr is None else lr, rule, cfg.dtype,
+    tr = b.Trainer(cfg.stages, cfg.in_shape, cfg.N, cfg.B, cfg.lr if lr is None else lr, rule, cfg.dtype if dtype is None else dtype,
                    momentum=momentum, weight_decay=weight_decay, dp_batched=dp_batched, fresh_mask=mask, bwd_fresh=bwd_fresh)
     tr.set_weights(p0)
     keep = []
@@ -65,46 +68,70 @@ def run_gpu(cfg, rule, T, p0, xs, ys, lr=None, momentum=0.0, weight_decay=0.0, d
     torch.cuda.synchronize()
     weights = [wl.unflatten_params(tr.weights(j), cfg.stages[j]) for j in range(cfg.S)]
     losses = np.stack([tr.losses(t) for t in range(T)])
-    out = dict(weights=weights, losses=losses, trace=tr.trace(), live=tr.live_counts(), stats=tr.stats())
+    out = dict(weights=weights, losses=losses, trace=tr.trace(), live=tr.live_counts(), stats=tr.stats(),
+               live_bytes=tr.live_bytes())
     tr.close()
+    del keep
+    torch.cuda.empty_cache()
     return out
 
 
-def check(cfg, rule, T, seed=0, lr=None, tensor_tol=0.5, capfd=None, momentum=0.0, weight_decay=0.0, dp_batched=False,
-          mask=None, bwd_fresh=False):
+def say(capfd, line):
+    """Result lines of the long tests, written past pytest's capture."""
+    import sys
+    if capfd is not None:
+        with capfd.disabled():
+            sys.stdout.write(line + "\n")
+            sys.stdout.flush()
+    else:
+        print(line)
+
+
+def check(cfg, rule, T, seed=0, lr=None, emulate=True, also_f32=False, capfd=None, momentum=0.0, weight_decay=0.0,
+          dp_batched=False, mask=None, bwd_fresh=False):
+    """One oracle run (fp64), the library in the configuration's arithmetic, and for bf16
+    configurations optionally the bf16-storage yardstick (`emulate`) and the library again in fp32
+    (`also_f32`)."""
+    import time
     xs, ys = wl.make_data(cfg, T, seed)
     p0 = wl.init_params(cfg, seed)
-    ref = O.train_schedule(cfg, p0, xs, ys, rule, lr=lr, keep_versions=False, progress=Progress(cfg.name, capfd),
-                           momentum=momentum, weight_decay=weight_decay, mask=mask, bwd_fresh=bwd_fresh)
-    got = run_gpu(cfg, rule, T, p0, xs, ys, lr=lr, momentum=momentum, weight_decay=weight_decay, dp_batched=dp_batched,
-                  mask=mask, bwd_fresh=bwd_fresh)
+    kw = dict(lr=lr, momentum=momentum, weight_decay=weight_decay, mask=mask, bwd_fresh=bwd_fresh)
+    t0 = time.time()
+    ref = O.train_schedule(cfg, p0, xs, ys, rule, keep_versions=False, progress=Progress(cfg.name, capfd), **kw)
+    t_ref = time.time() - t0
+    got = run_gpu(cfg, rule, T, p0, xs, ys, dp_batched=dp_batched, **kw)
     f32 = cfg.dtype == wl.F32
     assert got["trace"] == ref.trace
     assert got["live"] == ref.live_inputs
-    emu = ref if (f32 or tensor_tol is None) else O.train_schedule(cfg, p0, xs, ys, rule, lr=lr, rnd=OL.round_bf16,
-                                                                   keep_versions=False, momentum=momentum,
-                                                                   weight_decay=weight_decay, mask=mask, bwd_fresh=bwd_fresh)
-    worst_t, worst_s, worst_u = 0.0, 0.0, 0.0
-    for j in range(cfg.S):
-        worst_t = max(worst_t, O.max_rel_err(got["weights"][j], ref.params[j]))
-        worst_s = max(worst_s, O.stage_rel_err(got["weights"][j], ref.params[j]))
-        for g, r, w0 in zip(got["weights"][j], emu.params[j], p0[j]):
-            u_ref = r - np.asarray(w0, dtype=np.float64)
-            den = float(np.linalg.norm(u_ref))
-            if den > 0:
-                worst_u = max(worst_u, float(np.linalg.norm(g - r)) / den)
-    loss_err = np.abs(got["losses"] - ref.losses).max() / max(1e-6, np.abs(ref.losses).max())
-    print("%s rule=%d T=%d: tensor err %.3e stage err %.3e update-L2 err %.3e loss err %.3e"
-          % (cfg.name, rule, T, worst_t, worst_s, worst_u, loss_err))
     assert np.isfinite(got["losses"]).all()
+    den = max(1e-6, np.abs(ref.losses).max())
+    loss_err = np.abs(got["losses"] - ref.losses).max() / den
+    tag = "%s rule=%d T=%d" % (cfg.name, rule, T)
     if f32:
-        assert worst_t <= 1e-4, worst_t
+        ok, worst, where = G.f32_gate(got["weights"], ref.params)
+        say(capfd, "%s fp32: tensor err %.3e at %s, loss err %.3e (oracle %.0f s)" % (tag, worst, where, loss_err, t_ref))
+        assert ok, (worst, where)
         assert loss_err <= 1e-4, loss_err
-    else:
-        assert worst_s <= 2e-2, worst_s
-        if tensor_tol is not None:
-            assert worst_u <= tensor_tol, worst_u
-        assert loss_err <= 1e-1, loss_err     # micro-batch losses of a few samples; weights are the gate
+        return got, ref
+    emu = None
+    if emulate:
+        t0 = time.time()
+        emu = O.train_schedule(cfg, p0, xs, ys, rule, keep_versions=False, stage_impl=Bf16Storage,
+                               progress=Progress(cfg.name + " bf16-storage", capfd), **kw).params
+        t_ref += time.time() - t0
+    ok, rep = G.bf16_gate(got["weights"], ref.params, emu, p0)
+    say(capfd, "%s bf16: stage err %.3e, tensor max-rel %.3e, update err / bound worst %.2f %s, loss err %.3e (oracle %.0f s)"
+        % (tag, rep["stage_err"], rep["tensor_max_rel"], rep["worst_ratio"], rep["worst"], loss_err, t_ref))
+    assert ok, rep["failed"][:8]
+    assert loss_err <= 1e-1, loss_err     # micro-batch losses of a few samples; weights are the gate
+    if also_f32:
+        g32 = run_gpu(cfg, rule, T, p0, xs, ys, dp_batched=dp_batched, dtype=wl.F32, **kw)
+        assert g32["trace"] == ref.trace and g32["live"] == ref.live_inputs
+        ok, worst, where = G.f32_gate(g32["weights"], ref.params)
+        l32 = np.abs(g32["losses"] - ref.losses).max() / den
+        say(capfd, "%s same shapes in fp32: tensor err %.3e at %s, loss err %.3e" % (tag, worst, where, l32))
+        assert ok, (worst, where)
+        assert l32 <= 1e-4, l32
     return got, ref
 
 
@@ -184,72 +211,71 @@ def test_resnet_mini_bf16(name):
     check(cfg, wl.RULE_V2, cfg.steps)
 
 
-def test_cfg2_cifar_mlp_bf16_few_steps():
-    check(wl.get_config("cfg2"), wl.RULE_V2, 5)
+def test_cfg2_cifar_mlp_bf16_few_steps(capfd):
+    check(wl.get_config("cfg2"), wl.RULE_V2, 5, also_f32=True, capfd=capfd)
 
 
 def test_cfg2_cifar_mlp_bf16_full(capfd):
-    """All 50 steps.  Rounding differences grow along a 50-step ReLU-net trajectory, so only
-    the stated weight tolerance is checked here; the per-tensor check is on the 5-step run."""
+    """All 50 steps.  Rounding differences grow along a 50-step ReLU-net trajectory (the bf16-storage
+    yardstick itself is 25-70 % away from the fp64 trajectory in the update of single tensors by
+    then), so the fp32 run of the same 50 steps is the sharp check here."""
     cfg = wl.get_config("cfg2")
-    got, _ = check(cfg, wl.RULE_V2, cfg.steps, tensor_tol=None, capfd=capfd)
+    got, _ = check(cfg, wl.RULE_V2, cfg.steps, also_f32=True, capfd=capfd)
     st = got["stats"]
     assert st["peak_live_stage_inputs"] == 36
     assert st["peak_activation_bytes"] < 0.7 * st["dp_activation_bytes"] * 1.2
 
 
+def steady_ticks(cfg, T):
+    """Ticks in which all N micro-batches are in flight."""
+    return range(cfg.delay * (cfg.N - 1), 2 * cfg.S * T)
+
+
 def test_cfg5_deep_wide_mlp_bf16_full_size(capfd):
-    """24 x Linear(4096->4096), N=16 micro-batches of 64, d=3: full size, 2 steps + drain (the second
-    step mixes theta_0 and theta_1 per the v2 rule), in the launch configuration bench.py times."""
+    """24 x Linear(4096->4096), N=16 micro-batches of 64, d=3: full size, 3 steps + drain, in the launch
+    configuration bench.py times: versions t-1, t, t+1 of a stage are distinct, and version t+1 overwrites
+    the ring slot of t-1 while t is still being read."""
     cfg = wl.get_config("cfg5")
-    got, _ = check(cfg, wl.RULE_V2, 2, tensor_tol=None, capfd=capfd)
+    got, _ = check(cfg, wl.RULE_V2, 3, also_f32=True, capfd=capfd)
     st = got["stats"]
     assert st["peak_live_stage_inputs"] == 200
     assert st["peak_activation_bytes"] < 0.6 * 2 * st["dp_activation_bytes"]
+    # homogeneous stages: 200 retained stage inputs in every steady-state tick (plus the head's hidden
+    # activation and dlogits while a micro-batch sits between the last stage's forward and backward)
+    lb = [got["live_bytes"][k] for k in steady_ticks(cfg, 3)]
+    unit = cfg.B * 4096 * 2
+    assert min(lb) == 200 * unit and max(lb) == 201 * unit + cfg.B * 1000 * 2, (min(lb), max(lb))
 
 
 def test_cfg3_resnet18_bf16_full_size(capfd):
     cfg = wl.get_config("cfg3")
-    got, _ = check(cfg, wl.RULE_V2, 2, tensor_tol=None, capfd=capfd)
+    got, _ = check(cfg, wl.RULE_V2, 3, also_f32=True, capfd=capfd)
     assert got["stats"]["peak_live_stage_inputs"] == 18
+    # heterogeneous stages: the retained bytes are periodic in the tick with the delay as period
+    lb = [got["live_bytes"][k] for k in steady_ticks(cfg, 3)]
+    assert len(set(lb)) <= cfg.delay and all(lb[k] == lb[k + cfg.delay] for k in range(len(lb) - cfg.delay))
 
 
-def test_cfg4_resnet50_bf16_full_shapes_single_microbatch(capfd):
-    """The oracle needs minutes per ImageNet-shaped mini-batch, so the full-size check of the
-    ResNet-50 configuration is split: here every stage runs at its real shape (B = 32,
-    224x224 inputs, all 16 bottleneck stages, 1000 classes) with one micro-batch per step,
-    where CDP-v2 is plain SGD; 2 steps against the oracle at the stated weight tolerance."""
-    cfg = wl.get_config("cfg4")
-    cfg.N = 1
-    check(cfg, wl.RULE_V2, 2, tensor_tol=None, capfd=capfd)
-
-
-def test_cfg4_resnet50_bf16_full_config_sampled():
-    """N = 8 micro-batches as benchmarked: exact tick trace / live counts against the oracle's
-    bookkeeping, the objectives f_i(theta_0) of two sampled micro-batches of the first step
-    against an oracle forward pass (theta_{-1} = theta_0, so every rule reads theta_0 there),
-    and finite weights that moved."""
-    cfg = wl.get_config("cfg4")
-    T = 2
-    xs, ys = wl.make_data(cfg, T, 0)
-    p0 = wl.init_params(cfg, 0)
-    got = run_gpu(cfg, wl.RULE_V2, T, p0, xs, ys)
-    ref = O.train_schedule(cfg, None, [None] * T, [None] * T, wl.RULE_V2, compute=False)
-    assert got["trace"] == ref.trace and got["live"] == ref.live_inputs
+def test_cfg4_resnet50_reduced_images_all_microbatches(capfd):
+    """The ResNet-50 configuration as benchmarked (16 bottleneck stages at their real channel widths,
+    N = 8 micro-batches of 32, d = 4, 1000 classes) on 64x64 inputs, 3 steps + drain: the mixing of
+    theta_t and theta_{t-1} per Eq. (CDP-v2) and the weight-gradient accumulation over 8 micro-batches
+    on these layers, at a twelfth of the oracle's cost."""
+    cfg = wl.get_config("cfg4_s64")
+    got, _ = check(cfg, wl.RULE_V2, 3, also_f32=True, capfd=capfd)
     assert got["stats"]["peak_live_stage_inputs"] == 68
-    p64 = [[np.asarray(a, dtype=np.float64) for a in st] for st in p0]
-    for i in (0, cfg.N - 1):
-        sl = slice(i * cfg.B, (i + 1) * cfg.B)
-        h = np.asarray(xs[0][sl], dtype=np.float64)
-        for j, st in enumerate(cfg.stages):
-            h, _ = OL.stage_forward(st, p64[j], h, ys[0][sl] if j == cfg.S - 1 else None)
-        print("cfg4 micro-batch %d: loss gpu %.5f oracle %.5f" % (i, got["losses"][0, i], h))
-        assert abs(got["losses"][0, i] - h) <= 2e-2 * abs(h)
-    assert np.isfinite(got["losses"]).all()
-    for j in range(cfg.S):
-        for g, w0 in zip(got["weights"][j], p0[j]):
-            assert np.isfinite(g).all()
-        assert any(np.abs(g - w0).max() > 0 for g, w0 in zip(got["weights"][j], p0[j]))
+
+
+def test_cfg4_resnet50_bf16_full_config_weights(capfd):
+    """N = 8 micro-batches of 32 at 224x224 as benchmarked, 2 steps + drain (the second step mixes theta_0
+    and theta_1 per Eq. (CDP-v2)): weights of every stage and all 16 objectives against the oracle, in
+    bf16 at the stage criterion and in fp32 per tensor.  (The bf16-storage yardstick would double the
+    oracle's minutes; it is taken on the reduced-image run above.)"""
+    cfg = wl.get_config("cfg4")
+    got, _ = check(cfg, wl.RULE_V2, 2, emulate=False, also_f32=True, capfd=capfd)
+    assert got["stats"]["peak_live_stage_inputs"] == 68
+    lb = [got["live_bytes"][k] for k in steady_ticks(cfg, 2)]
+    assert len(set(lb)) <= cfg.delay
 
 
 @pytest.mark.parametrize("name,rule", [("mlp_odd", wl.RULE_V2), ("mlp_odd", wl.RULE_V1), ("resnet18_mini_f32", wl.RULE_V2),
@@ -325,7 +351,7 @@ def test_tick_by_tick_and_unaligned_inputs_give_the_same_weights(name):
     assert base[2] == ref.trace
     tol = 1e-4 if cfg.dtype == wl.F32 else 2e-2
     for j in range(cfg.S):
-        err = O.stage_rel_err(wl.unflatten_params(base[0][j], cfg.stages[j]), ref.params[j])
+        err = G.stage_max_rel(wl.unflatten_params(base[0][j], cfg.stages[j]), ref.params[j])
         assert err <= tol, err
     for mode in ("tick", "unaligned"):
         got = run(mode)
@@ -337,8 +363,8 @@ def test_tick_by_tick_and_unaligned_inputs_give_the_same_weights(name):
             else:
                 # other launch grouping, hence another summation order inside the contractions
                 w = wl.unflatten_params(got[0][j], cfg.stages[j])
-                assert O.stage_rel_err(w, ref.params[j]) <= tol, (mode, j)
-                assert O.stage_rel_err(w, wl.unflatten_params(base[0][j], cfg.stages[j])) <= tol, (mode, j)
+                assert G.stage_max_rel(w, ref.params[j]) <= tol, (mode, j)
+                assert G.stage_max_rel(w, wl.unflatten_params(base[0][j], cfg.stages[j])) <= tol, (mode, j)
 
 
 @pytest.mark.parametrize("rule", RULES)
@@ -374,7 +400,7 @@ def test_vit_b16_full_shapes_single_microbatch(capfd):
     plain SGD: 2 steps against the oracle at the stated weight tolerance."""
     cfg = wl.get_config("vit_b16")
     cfg.N = 1
-    check(cfg, wl.RULE_V2, 2, tensor_tol=None, capfd=capfd)
+    check(cfg, wl.RULE_V2, 2, also_f32=True, capfd=capfd)
 
 
 def test_vit_b16_full_config_sampled():

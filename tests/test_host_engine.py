@@ -161,3 +161,29 @@ def test_drain_then_resume_restarts_cycle():
     # after a drain every stage holds theta_2, so the resumed step reads version 2 everywhere
     assert {rec[5] for rec in t[n0:]} == {2}
     tr.close()
+
+
+@pytest.mark.parametrize("name", ["cfg2", "cfg3", "cfg4", "cfg5", "vit_b16", "mlp_odd"])
+def test_retained_activation_bytes_per_tick_are_periodic(name):
+    """Sec. 4.1: the cyclic schedule keeps the activation memory (nearly) constant over the time steps.
+    In steady state the bytes retained for later backward passes repeat with the delay d as period
+    (stages of different sizes, and the head's extra tensors, give up to d distinct values), and the
+    high-water mark of the pool is the maximum of the in-tick series."""
+    cfg = wl.get_config(name)
+    T = 3
+    tr = _dry(cfg, wl.RULE_V2, T)
+    d = cfg.delay
+    kept, held = tr.live_bytes(0), tr.live_bytes(1)
+    assert len(kept) == len(held) == tr.stats()["ticks_run"]
+    steady = range(d * (cfg.N - 1), 2 * cfg.S * T)
+    ks = [kept[k] for k in steady]
+    assert len(set(ks)) <= d
+    assert all(ks[k] == ks[k + d] for k in range(len(ks) - d))
+    assert all(h >= k > 0 for h, k in zip((held[k] for k in steady), ks))
+    assert max(held) == tr.stats()["peak_activation_bytes"]
+    if name == "cfg5":
+        # 200 retained stage inputs of 64 x 4096 bf16; while a micro-batch sits between the forward and the
+        # backward of the last stage that record also holds the hidden activation and dlogits
+        unit = cfg.B * 4096 * 2
+        assert min(ks) == 200 * unit and max(ks) == 200 * unit + unit + cfg.B * 1000 * 2
+    tr.close()

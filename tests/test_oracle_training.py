@@ -8,6 +8,7 @@ import cdp_workloads as wl
 from oracle import cdp_oracle as O
 from oracle import layers as L
 from test_oracle_layers import torch_forward, to_torch_params, to_torch_x
+from bf16_emulation import Bf16Storage
 
 RULES = [wl.RULE_DP, wl.RULE_V1, wl.RULE_V2]
 
@@ -140,7 +141,7 @@ def test_rules_differ_after_the_first_step():
 def test_bf16_emulation_stays_close_to_fp64():
     cfg, p0, xs, ys = _setup("cfg2_mini", 3)
     a = O.train_schedule(cfg, p0, xs, ys, wl.RULE_V2)
-    b = O.train_schedule(cfg, p0, xs, ys, wl.RULE_V2, rnd=L.round_bf16)
+    b = O.train_schedule(cfg, p0, xs, ys, wl.RULE_V2, stage_impl=Bf16Storage)
     for j in range(cfg.S):
         # per stage vector theta^j; single tensors that start at zero (biases) see O(10%) of
         # their own small range from isolated ReLU sign flips, so they are not the gate
