@@ -39,6 +39,21 @@ int cdp_k_conv(int dtype, int which, const void* in0, const void* in1, void* out
                int Cin, int Cout, int ksize, int stride, int pad, void* workspace,
                size_t workspace_bytes, void* stream);
 
+/* For callers that cannot allocate device memory (code under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc): the weight gradient of cdp_k_conv (which = 2, two-phase path) with the
+ * partial sums of its reduction ranges in a device array that is part of the library image
+ * (CDP_STATIC_SCRATCH_BYTES per GPU, held until the process ends) instead of a caller's workspace.
+ * dw[Cout][k][k][Cin] (fp32, overwritten) from dy[B][Ho][Wo][Cout] and x[B][H][W][Cin] (element type by
+ * dtype).  Calls no hipMalloc / hipFree and no allocating library routine.
+ * Errors: CDP_EINVAL for shapes the two-phase kernels do not take (channel counts that are not whole
+ * 16-byte chunks, more than 32 taps); CDP_ENOMEM when the partial sums (4 * Cout*k*k*Cin * ranges bytes)
+ * exceed the array - cdp_last_error(NULL) then says how many bytes were needed; CDP_EHIP.
+ * All calls on one GPU share that GPU's array: calls that overlap in time on one GPU (different streams,
+ * different threads) race.  Nothing in the array has to be cleared between calls. */
+#define CDP_STATIC_SCRATCH_BYTES (16u << 20)
+int cdp_k_conv_wgrad_static(int dtype, const void* dy, const void* x, float* dw, int B, int H, int W, int Cin,
+                            int Cout, int ksize, int stride, int pad, void* stream);
+
 /* The kernels of ViT-shaped stages (the homogeneous stages of Sec. 5 "Memory") on their own.
  * Element type of x / dy / out / qkv / P / dout by `dtype`; gamma, beta and their gradients fp32.
  *

@@ -22,7 +22,7 @@ CDP_F32, CDP_BF16 = 0, 1
 EXPORTS = ["cdp_arena_bytes", "cdp_init", "cdp_set_weights", "cdp_param_count", "cdp_tick", "cdp_step",
            "cdp_drain", "cdp_get_weights", "cdp_get_losses", "cdp_get_trace", "cdp_get_live_counts",
            "cdp_get_live_bytes", "cdp_get_stats", "cdp_last_error", "cdp_destroy", "cdp_profile_gemm", "cdp_get_gemm_profile",
-           "cdp_k_gemm", "cdp_k_conv", "cdp_k_layernorm", "cdp_k_gelu", "cdp_k_attention"]
+           "cdp_k_gemm", "cdp_k_conv", "cdp_k_conv_wgrad_static", "cdp_k_layernorm", "cdp_k_gelu", "cdp_k_attention"]
 
 
 class cdp_layer_desc(C.Structure):
@@ -94,6 +94,7 @@ def lib() -> C.CDLL:
         L.cdp_get_gemm_profile.argtypes = [vp, C.POINTER(cdp_gemm_profile)]
         L.cdp_k_gemm.argtypes = [i32, i32, i32, i32, vp, vp, vp, i32, i32, i32, i32, i32, vp]
         L.cdp_k_conv.argtypes = [i32, i32, vp, vp, vp, i32, i32, i32, i32, i32, i32, i32, i32, vp, sz, vp]
+        L.cdp_k_conv_wgrad_static.argtypes = [i32, vp, vp, vp, i32, i32, i32, i32, i32, i32, i32, i32, vp]
         L.cdp_k_layernorm.argtypes = [i32, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, i32, i32, vp]
         L.cdp_k_gelu.argtypes = [i32, i32, vp, vp, vp, C.c_int64, vp]
         L.cdp_k_attention.argtypes = [i32, i32, vp, vp, vp, vp, vp, sz, i32, i32, i32, i32, vp]
@@ -254,6 +255,12 @@ def cdp_k_conv(dtype, which, in0_ptr, in1_ptr, out_ptr, B, H, W, Cin, Cout, ks, 
                           ws_bytes, stream or None)
     if rc != CDP_OK:
         raise CdpError(rc, "cdp_k_conv")
+
+
+def cdp_k_conv_wgrad_static(dtype, dy_ptr, x_ptr, dw_ptr, B, H, W, Cin, Cout, ks, stride, pad, stream=0) -> None:
+    rc = lib().cdp_k_conv_wgrad_static(dtype, dy_ptr, x_ptr, dw_ptr, B, H, W, Cin, Cout, ks, stride, pad, stream or None)
+    if rc != CDP_OK:
+        raise CdpError(rc, "cdp_k_conv_wgrad_static: " + lib().cdp_last_error(None).decode())
 
 
 def cdp_k_layernorm(dtype, backward, x_ptr, dy_ptr, add_ptr, gamma_ptr, beta_ptr, out_ptr, dgamma_ptr, dbeta_ptr, ws_ptr,

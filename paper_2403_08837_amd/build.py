@@ -8,7 +8,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libcdp.so")
-SOURCES = ["gemm.hip", "linear_kernels.hip", "conv_kernels.hip", "small_kernels.hip", "transformer_kernels.hip", "engine.cpp", "plan.cpp", "kernels_api.cpp"]
+SOURCES = ["gemm.hip", "linear_kernels.hip", "conv_kernels.hip", "small_kernels.hip", "transformer_kernels.hip", "static_scratch.hip", "engine.cpp", "plan.cpp", "kernels_api.cpp"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 # packed-fp32 VALU forms are switched off for all device code: the compiler then emits scalar fp32 ops only
 # fp32 atomic adds go to coarse-grained device memory (the arena): use the hardware instruction, not a CAS loop

@@ -141,6 +141,15 @@ struct cdp_ctx {
 
 namespace {
 
+}  // namespace
+
+// Error text of calls that have no context (the kernel-level entry points); read by cdp_last_error(NULL).
+namespace cdp {
+void set_global_error(const std::string& msg) { g_last_error = msg; }
+}  // namespace cdp
+
+namespace {
+
 int fail(cdp_ctx* c, int code, const std::string& msg) {
   if (c) c->err = msg;
   g_last_error = msg;

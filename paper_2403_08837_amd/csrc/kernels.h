@@ -4,7 +4,12 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <string>
+
 namespace cdp {
+
+// Text for cdp_last_error(NULL) (thread-local), set by entry points that have no context.
+void set_global_error(const std::string& msg);
 
 enum DType : int { DT_F32 = 0, DT_BF16 = 1 };
 
