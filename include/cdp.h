@@ -10,7 +10,9 @@
  *
  * Conventions
  *   - every function returns CDP_OK (0) or a negative cdp_status; nothing throws;
- *     a failed call leaves the context as it was (CDP_EINVAL) or unusable (CDP_EHIP);
+ *     a call that fails before it changed anything leaves the context as it was; a tick that fails
+ *     half-way (arena exhausted, a HIP error) leaves a context that refuses further ticks with
+ *     CDP_ESTATE and can only be read and destroyed;
  *   - "dev" pointers are HIP device pointers, "host" pointers are ordinary host memory;
  *   - the caller owns every pointer it passes (inputs, labels, output buffers, the
  *     arena, the stream); the library owns only cdp_ctx and sub-allocates the arena;
@@ -154,20 +156,25 @@ int cdp_set_weights(cdp_ctx* ctx, int stage, const float* host_f32, size_t n);
 /* Number of fp32 parameters of a stage. */
 int cdp_param_count(const cdp_ctx* ctx, int stage, size_t* n_out);
 
-/* Advance one tick.  x_dev: fp32 [N*B, in_dims...] and y_dev: int32 [N*B] of the
+/* Advance one tick = one "time step" of Sec. 3.1 / Sec. 3.2 "Algorithmic description": every micro-batch in
+ * flight runs the forward or the backward of the one stage the timeline of Fig. 1 assigns to it, with the
+ * weight version u_{i,j} of Eq. (CDP) selects; stages that then hold N gradients are updated.  x_dev: fp32 [N*B, in_dims...] and y_dev: int32 [N*B] of the
  * mini-batch whose micro-batches may start in this tick (the step tick/(2S)); they are
  * read only in ticks where a micro-batch starts (x) -- labels are copied at that time.
  * May be NULL in ticks where no micro-batch starts (the drain). */
 int cdp_tick(cdp_ctx* ctx, const float* x_dev, const int32_t* y_dev);
 
-/* Enqueue mini-batch t (the next one) and run its 2S ticks.  x_dev/y_dev as above;
+/* One training step t of Eq. (CDP) as the timeline executes it: enqueue mini-batch t (the next one) and run the 2S
+ * ticks in which its N micro-batches start (the last of them finishes d*(N-1) ticks into the following steps, Fig. 1).  x_dev/y_dev as above;
  * they must stay valid until the enqueued work has run. */
 int cdp_step(cdp_ctx* ctx, const float* x_dev, const int32_t* y_dev);
 
-/* Run the remaining d*(N-1) ticks so that every stage reaches theta_T. */
+/* Run the remaining d*(N-1) ticks so that every stage reaches theta_T: the tail of the cyclic timeline of
+ * Sec. 3.2 (micro-batch i starts d*i ticks after micro-batch 0) with no new mini-batch entering. */
 int cdp_drain(cdp_ctx* ctx);
 
-/* Copy a stage's parameters to host fp32 (synchronises the stream).  version = -1:
+/* theta^j_t of Eq. (CDP): copy a stage's parameters to host fp32 (synchronises the stream).  The ring holds the two
+ * versions Eq. (CDP) can ask for, theta_t and theta_{t-1}.  version = -1:
  * freshest (fp32 master values); version = freshest-1: the compute-precision copy
  * still held in the ring (its folded/rounded form is not inverted: CDP_ESTATE for
  * stages with AFFINE layers).  Any other version: CDP_ESTATE. */

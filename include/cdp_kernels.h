@@ -14,8 +14,8 @@ extern "C" {
 #endif
 
 /* C[M][N] (fp32, row-major, ldc = N) = A * B^T with fp32 accumulation, the tile
- * contraction used by every stage forward / backward of a tick (Sec. 3.1: "forward and
- * backward pass over the micro-batch").
+ * contraction used by every stage forward / backward of a tick (Sec. 3.1: the forward and
+ * backward computation of a stage on one micro-batch).
  *   dtype      0 fp32, 1 bf16 (operand element type)
  *   tile_shape 0: 128x128, 1: 64x128, 2: 64x64 workgroup tile of the generic kernel;
  *              3: 64x64, 4: 64x128 tile of the weight-streaming kernel the Linear stages
@@ -31,6 +31,9 @@ int cdp_k_gemm(int dtype, int tile_shape, int a_kmajor, int b_kmajor, const void
  *   which 0: forward        y[B][Ho][Wo][Cout] (elem type) = conv(x, w),  w[Cout][k][k][Cin]
  *         1: data gradient  dx[B][H][W][Cin]   (elem type) from dy and wt[Cin][k][k][Cout]
  *         2: weight gradient dw[Cout][k][k][Cin] (fp32, overwritten) from dy and x
+ *         3, 4: as 0, 1 on the 256 x 256 tile whatever the size (the engine and which = 0, 1 choose it only
+ *               for launches that fill the chip); CDP_EINVAL unless bf16 with channel counts that are
+ *               multiples of 64
  * in0/in1: (x, w) | (dy, wt) | (dy, x).  `out` must not alias the inputs.
  * workspace (device, may be NULL): scratch for the split weight-gradient kernel; with at
  * least 4 * Cout*k*k*Cin * (B*Ho*Wo / 512 + 4) bytes the two-phase path is used when the

@@ -20,8 +20,8 @@ Two trainers:
     micro-batch.
   * ``train_schedule``  -- the tick-by-tick execution timeline of Fig. 1 with a
     two-slot weight ring per stage, gradient accumulators and activation
-    bookkeeping; the selector is *operational* (v2: "freshest parameters in
-    memory", Sec. 3.2).  It also records the tick trace and live-buffer counts.
+    bookkeeping; the selector is *operational* (v2: the freshest version held in
+    memory, Sec. 3.2).  It also records the tick trace and live-buffer counts.
 Their agreement is one of the pins; the others are in tests/test_oracle_*.py.
 """
 from __future__ import annotations

@@ -4,7 +4,7 @@ TEST INFRASTRUCTURE ONLY (see package docstring).  Everything is plain numpy in
 float64, NHWC for images, one function pair per layer kind, no fusion and no
 blocking: each formula is the textbook definition of the layer and of its
 vector-Jacobian product.  The paper treats a stage as an opaque differentiable
-module (Sec. 3.1, "forward and backward pass over the micro-batch"); the layer
+module whose forward and backward run on one micro-batch (Sec. 3.1); the layer
 set here is what the benchmark configurations need.
 
 Pins (tests/test_oracle_layers.py): finite differences in fp64 for every

@@ -7,60 +7,19 @@
 //     A slab of the reduction lies inside one tap, so the tap and its address delta are
 //     wavefront-uniform; each thread keeps, per tile row it loads, one base offset and one
 //     bit per tap (inside the image / on the stride lattice).  No division in the k-loop.
-//   conv_wgrad_kernel  G[o][(tap,c)] += gamma[o] * sum_m dy[m][o] * x[pos(m)+tap][c]
-//     reduction over output positions, split across workgroups (fp32 atomics into the zeroed
-//     accumulator); operands are staged as they lie in memory ([m][channels]) and MFMA
-//     fragments are read transposed out of LDS; the per-position address decode is done
-//     once per workgroup into an LDS table.  Also produces d gamma and d beta.
+//   conv_wgrad_kernel  part[range][o][(tap,c)] = sum_{m in range} dy[m][o] * x[pos(m)+tap][c]
+//     reduction over output positions, cut into ranges that write partial tiles with plain
+//     stores; operands are staged as they lie in memory ([m][channels]) and MFMA fragments are
+//     read transposed out of LDS; the per-position address decode is done once per workgroup
+//     into an LDS table.  wgrad_reduce_kernel folds the ranges into G (scaled by gamma) and
+//     produces d gamma and d beta.
 #include <algorithm>
 
+#include "elem.h"
 #include "kernels.h"
 #include "mfma_frag.h"
 
 namespace cdp {
-
-typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 cv8bf16;
-typedef __attribute__((__vector_size__(16 * sizeof(float)))) float cv16f;
-
-namespace {
-
-__device__ __forceinline__ float cbf2f(uint16_t h) { return __uint_as_float(((uint32_t)h) << 16); }
-__device__ __forceinline__ uint16_t cf2bf(float f) {
-  uint32_t u = __float_as_uint(f);
-  if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x40u);
-  u += 0x7fffu + ((u >> 16) & 1u);
-  return (uint16_t)(u >> 16);
-}
-template <typename T> struct CT;
-template <> struct CT<uint16_t> {
-  static constexpr int VEC = 8, MFMA_K = 16, KPL = 8;
-  __device__ static __forceinline__ float to_f32(uint16_t v) { return cbf2f(v); }
-  __device__ static __forceinline__ uint16_t from_f32(float f) { return cf2bf(f); }
-};
-template <> struct CT<float> {
-  static constexpr int VEC = 4, MFMA_K = 2, KPL = 1;
-  __device__ static __forceinline__ float to_f32(float v) { return v; }
-  __device__ static __forceinline__ float from_f32(float f) { return f; }
-};
-
-template <typename T> union CChunk {
-  uint4 v;
-  uint2 h[2];
-  T e[16 / sizeof(T)];
-};
-
-__device__ __forceinline__ int cfind_problem(const GemmBatch& batch, int tile) {
-  int pi = 0;
-  for (int q = 1; q < batch.n; ++q)
-    if (tile >= batch.p[q].tile_begin) pi = q;
-  return pi;
-}
-
-__device__ __forceinline__ cv16f cmfma_bf16(uint4 a, uint4 b, cv16f c) {
-  return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(cv8bf16, a), __builtin_bit_cast(cv8bf16, b), c, 0, 0, 0);
-}
-
-}  // namespace
 
 // ---------------------------------------------------------------------------------
 // forward / data gradient: 128 x BN tile, waves 2 x 2, reduction slab BK (a divisor of the
@@ -68,7 +27,7 @@ __device__ __forceinline__ cv16f cmfma_bf16(uint4 a, uint4 b, cv16f c) {
 // as 16-byte vectors along the channel dimension.
 template <typename T, int BM, int BN, int BK, bool DB>
 __global__ __launch_bounds__(256) void conv_gemm_kernel(const GemmBatch batch) {
-  using E = CT<T>;
+  using E = Elem<T>;
   constexpr int VEC = E::VEC, LDP = BK + VEC;
   constexpr int WTM = BM / 2, MI = WTM / 32;   // wave tile WTM x WTN
   constexpr int CPR = BK / VEC;                // chunks per tile row
@@ -83,7 +42,7 @@ __global__ __launch_bounds__(256) void conv_gemm_kernel(const GemmBatch batch) {
   T* const As0 = reinterpret_cast<T*>(smem);
 
   const int tile = (int)blockIdx.x;
-  const GemmProb& P = batch.p[cfind_problem(batch, tile)];
+  const GemmProb& P = batch.p[find_problem(batch, tile)];
   // a long reduction of a small launch is shared by P.splits workgroups (neighbours in the
   // tile list); the last of them to finish adds the partial tiles and runs the epilogue
   constexpr bool SPLIT = BM == 64 && BN == 64;  // the launcher splits only launches of the smallest tiles
@@ -171,7 +130,7 @@ __global__ __launch_bounds__(256) void conv_gemm_kernel(const GemmBatch batch) {
     }
   };
 
-  cv16f acc[MI][NI];
+  v16f_t acc[MI][NI];
 #pragma unroll
   for (int i = 0; i < MI; ++i)
 #pragma unroll
@@ -203,7 +162,7 @@ __global__ __launch_bounds__(256) void conv_gemm_kernel(const GemmBatch batch) {
 #pragma unroll
         for (int i = 0; i < MI; ++i)
 #pragma unroll
-          for (int j = 0; j < NI; ++j) acc[i][j] = cmfma_bf16(a[i], b[j], acc[i][j]);
+          for (int j = 0; j < NI; ++j) acc[i][j] = mfma_bf16(a[i], b[j], acc[i][j]);
       } else {
         float a[MI], b[NI];
 #pragma unroll
@@ -321,7 +280,7 @@ __global__ __launch_bounds__(256) void conv_gemm_kernel(const GemmBatch batch) {
       float val[VEC];
 #pragma unroll
       for (int e = 0; e < VEC; ++e) val[e] = stage[sr * SP + sc + e];
-      CChunk<T> x0, x1, x2, res;
+      Chunk16<T> x0, x1, x2, res;
       if (fwd) {
         if (P.aux0) {
 #pragma unroll
@@ -375,7 +334,7 @@ static inline int wg_slab(int dtype) { return dtype == DT_BF16 ? 64 : 32; }
 
 template <typename T, int TO>
 __global__ __launch_bounds__(256) void conv_wgrad_kernel(const GemmBatch batch) {
-  using E = CT<T>;
+  using E = Elem<T>;
   constexpr int TC = 128, VEC = E::VEC, MB = WgSlab<T>::MB;
   constexpr int PAD = (sizeof(T) == 2) ? 16 : 4;  // bf16: pitch of 32 bytes modulo 128 for the transposing LDS read
   constexpr int PD = TO + PAD, PX = TC + PAD;  // LDS pitches (elements)
@@ -389,7 +348,7 @@ __global__ __launch_bounds__(256) void conv_wgrad_kernel(const GemmBatch batch) 
   __shared__ int pos_hw[WG_MAX_SLABS * MB];
 
   const int tile = (int)blockIdx.x;
-  const GemmProb& P = batch.p[cfind_problem(batch, tile)];
+  const GemmProb& P = batch.p[find_problem(batch, tile)];
   int local = tile - P.tile_begin;
   const int split = local % P.splits;
   local /= P.splits;
@@ -449,7 +408,7 @@ __global__ __launch_bounds__(256) void conv_wgrad_kernel(const GemmBatch batch) 
     }
   };
 
-  cv16f acc[2][NI];
+  v16f_t acc[2][NI];
 #pragma unroll
   for (int i = 0; i < 2; ++i)
 #pragma unroll
@@ -491,7 +450,7 @@ __global__ __launch_bounds__(256) void conv_wgrad_kernel(const GemmBatch batch) 
     if (s > 0) __syncthreads();
 #pragma unroll
     for (int i = 0; i < ND; ++i) {
-      CChunk<T> c;
+      Chunk16<T> c;
       c.v = rd[i];
       uint2* dst = reinterpret_cast<uint2*>(Ds + (d_m + i * (256 / DCH)) * PD + d_c);
       dst[0] = c.h[0];
@@ -499,7 +458,7 @@ __global__ __launch_bounds__(256) void conv_wgrad_kernel(const GemmBatch batch) 
     }
 #pragma unroll
     for (int i = 0; i < NX; ++i) {
-      CChunk<T> c;
+      Chunk16<T> c;
       c.v = rx[i];
       uint2* dst = reinterpret_cast<uint2*>(Xs + (x_m + i * (256 / XCH)) * PX + x_c);
       dst[0] = c.h[0];
@@ -519,7 +478,7 @@ __global__ __launch_bounds__(256) void conv_wgrad_kernel(const GemmBatch batch) 
 #pragma unroll
         for (int i = 0; i < 2; ++i)
 #pragma unroll
-          for (int j = 0; j < NI; ++j) acc[i][j] = cmfma_bf16(a[i], b[j], acc[i][j]);
+          for (int j = 0; j < NI; ++j) acc[i][j] = mfma_bf16(a[i], b[j], acc[i][j]);
       }
     } else {
 #pragma unroll 8
@@ -567,7 +526,7 @@ __global__ __launch_bounds__(256) void conv_wgrad_kernel(const GemmBatch batch) 
 //   d beta[o]  += sum_ranges part_beta[.][o]  (first column chunk only).
 template <typename T>
 __global__ __launch_bounds__(256) void wgrad_reduce_kernel(const WReduceBatch batch) {
-  using E = CT<T>;
+  using E = Elem<T>;
   __shared__ float4 red[8][32];
   int pi = 0;
   for (int q = 1; q < batch.n; ++q)

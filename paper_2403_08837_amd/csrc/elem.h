@@ -1,0 +1,57 @@
+// Element types of the contractions (bf16 as raw 16-bit words, fp32) and the small device helpers
+// every kernel file uses: conversions, per-type constants, 16-byte chunks, problem lookup, MFMA call.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "kernels.h"
+
+namespace cdp {
+
+typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 v8bf16_t;
+typedef __attribute__((__vector_size__(16 * sizeof(float)))) float v16f_t;
+
+__device__ __forceinline__ float bf16_to_f32(uint16_t h) { return __uint_as_float(((uint32_t)h) << 16); }
+__device__ __forceinline__ uint16_t f32_to_bf16(float f) {
+  uint32_t u = __float_as_uint(f);
+  if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x40u);  // quiet NaN
+  u += 0x7fffu + ((u >> 16) & 1u);                                            // round to nearest even
+  return (uint16_t)(u >> 16);
+}
+
+template <typename T> struct Elem;
+template <> struct Elem<uint16_t> {
+  static constexpr int VEC = 8;      // elements per 16-byte chunk
+  static constexpr int MFMA_K = 16;  // reduction elements per MFMA
+  static constexpr int KPL = 8;      // reduction elements per lane per MFMA
+  __device__ static __forceinline__ float to_f32(uint16_t v) { return bf16_to_f32(v); }
+  __device__ static __forceinline__ uint16_t from_f32(float f) { return f32_to_bf16(f); }
+};
+template <> struct Elem<float> {
+  static constexpr int VEC = 4, MFMA_K = 2, KPL = 1;
+  __device__ static __forceinline__ float to_f32(float v) { return v; }
+  __device__ static __forceinline__ float from_f32(float f) { return f; }
+};
+
+template <typename T> __device__ __forceinline__ float ld_f32(const T* p, int64_t i) { return Elem<T>::to_f32(p[i]); }
+template <typename T> __device__ __forceinline__ void st_f32(T* p, int64_t i, float v) { p[i] = Elem<T>::from_f32(v); }
+
+template <typename T> union Chunk16 {
+  uint4 v;
+  uint2 h[2];
+  T e[16 / sizeof(T)];
+};
+
+// Problem of a launch that owns tile number `tile` (problems are listed by ascending tile_begin).
+__device__ __forceinline__ int find_problem(const GemmBatch& batch, int tile) {
+  int pi = 0;
+  for (int q = 1; q < batch.n; ++q)
+    if (tile >= batch.p[q].tile_begin) pi = q;
+  return pi;
+}
+
+__device__ __forceinline__ v16f_t mfma_bf16(uint4 a, uint4 b, v16f_t c) {
+  return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(v8bf16_t, a), __builtin_bit_cast(v8bf16_t, b), c, 0, 0, 0);
+}
+
+}  // namespace cdp

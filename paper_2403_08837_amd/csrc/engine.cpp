@@ -95,6 +95,7 @@ struct Item {
   double flops = 0, bytes = 0;  // algorithmic work (contractions only)
   bool done = false;            // already carried by another launch of its level
   bool fused_update = false;    // IT_GEMM weight gradient of a Linear layer that also takes the SGD step (u)
+  bool big_tile = false;        // IT_GEMM forward / data gradient that runs on the 256 x 256 tile in this launch
   LinUpdate u;
 };
 typedef std::vector<std::vector<Item>> Program;
@@ -122,6 +123,7 @@ struct cdp_ctx {
   std::vector<Block> deferred;                // released when the tick's launches are enqueued
   int64_t tick = 0, origin_tick = 0, origin_step = 0, steps_enqueued = 0;
   bool weights_locked = false;
+  bool poisoned = false;                      // a tick failed half-way: the timeline state is no longer consistent
   std::vector<int> heads_done;                // per logged step: head passes run
   std::vector<cdp_trace_rec> trace;
   std::vector<int32_t> live_counts;
@@ -328,7 +330,8 @@ bool linear_update_fusable(const Op& o) {
 // Launch class of a contraction: which kernel family and tile shape runs it.
 enum LaunchClass {
   LC_LINEAR = 0, LC_CONV_NARROW, LC_CONV_WIDE, LC_CWGRAD_64, LC_CWGRAD_128,
-  LC_GEN_FIRST  // LC_GEN_FIRST + 2*shape + wgrad
+  LC_GEN_FIRST,  // LC_GEN_FIRST + 2*shape + wgrad
+  LC_CONV_256 = LC_GEN_FIRST + 2 * TILE_COUNT  // chosen per launch (launch_level), never by launch_class
 };
 
 int launch_class(const GemmProb& p, int dtype) {
@@ -644,11 +647,27 @@ int build_backward(cdp_ctx* c, int i, int j, int version, Program* prog, bool fi
 
 // --------------------------------------------------------------------------- launching
 int launch_level(cdp_ctx* c, std::vector<Item>& items) {
+  // The wide forward / data-gradient problems that the 256 x 256 tile takes move to a launch of their
+  // own when together they fill the chip with mostly-full tiles.
+  {
+    std::vector<Item*> big;
+    std::vector<GemmProb> probs;
+    for (Item& it : items) {
+      it.big_tile = false;
+      if (it.kind == IT_GEMM && launch_class(it.g, c->plan.dtype) == LC_CONV_WIDE && conv_gemm256_eligible(it.g, c->plan.dtype) &&
+          it.g.N >= 192 && it.g.M >= 512) {
+        big.push_back(&it);
+        probs.push_back(it.g);
+      }
+    }
+    if (!big.empty() && conv_gemm256_wanted(probs.data(), (int)probs.size(), c->plan.dtype))
+      for (Item* it : big) it->big_tile = true;
+  }
   // grouped contractions, one launch per tile shape (and per GEMM_MAX_PROBS problems)
-  for (int key = 0; key < LC_GEN_FIRST + 2 * TILE_COUNT; ++key) {
+  for (int key = 0; key <= LC_CONV_256; ++key) {
     std::vector<const Item*> sel;
     for (const Item& it : items)
-      if (it.kind == IT_GEMM && launch_class(it.g, c->plan.dtype) == key) sel.push_back(&it);
+      if (it.kind == IT_GEMM && (it.big_tile ? LC_CONV_256 : launch_class(it.g, c->plan.dtype)) == key) sel.push_back(&it);
     // longest reductions first so the tail of the launch is made of short tiles
     std::stable_sort(sel.begin(), sel.end(),
                      [](const Item* a, const Item* b) { return a->g.K / a->g.splits > b->g.K / b->g.splits; });
@@ -708,6 +727,7 @@ int launch_level(cdp_ctx* c, std::vector<Item>& items) {
         conv_gemm_tile(batch.p, batch.n, &bm, &bn);
         HIP_TRY(c, launch_conv_gemm(batch, c->plan.dtype, bm, bn, c->stream));
       }
+      else if (key == LC_CONV_256) HIP_TRY(c, launch_conv_gemm256(batch, c->plan.dtype, c->stream));
       else if (key == LC_CWGRAD_64 || key == LC_CWGRAD_128) HIP_TRY(c, launch_conv_wgrad(batch, c->plan.dtype, key == LC_CWGRAD_128, c->stream));
       else HIP_TRY(c, launch_gemm_batch(batch, c->plan.dtype, (key - LC_GEN_FIRST) / 2, c->stream));
       if (timed) {
@@ -732,21 +752,37 @@ int launch_level(cdp_ctx* c, std::vector<Item>& items) {
     HIP_TRY(c, launch_colsum_batch(cb, c->plan.dtype, c->stream));
     c->stats.kernel_launches++;
   }
+  // folds of the convolution weight-gradient partial sums: part of the contraction (timed with it)
   WReduceBatch rb;
   rb.n = 0;
+  auto flush_folds = [&]() -> int {
+    if (!rb.n) return CDP_OK;
+    cdp_ctx::ProfRec pr{nullptr, nullptr, 0, 0};
+    const bool timed = c->profiling && c->prof.size() < (1u << 18);
+    if (timed) {
+      for (hipEvent_t* e : {&pr.a, &pr.b}) {
+        if (!c->event_pool.empty()) { *e = c->event_pool.back(); c->event_pool.pop_back(); }
+        else HIP_TRY(c, hipEventCreate(e));
+      }
+      // no algorithmic work of its own: the accumulator's read-modify-write is already counted with the
+      // weight-gradient contraction, the partial sums are this implementation's traffic
+      HIP_TRY(c, hipEventRecord(pr.a, c->stream));
+    }
+    HIP_TRY(c, launch_wgrad_reduce(rb, c->plan.dtype, c->stream));
+    if (timed) {
+      HIP_TRY(c, hipEventRecord(pr.b, c->stream));
+      c->prof.push_back(pr);
+    }
+    c->stats.kernel_launches++;
+    rb.n = 0;
+    return CDP_OK;
+  };
   for (const Item& it : items) {
     if (it.kind != IT_WREDUCE) continue;
     rb.p[rb.n++] = it.r;
-    if (rb.n == WREDUCE_MAX_PROBS) {
-      HIP_TRY(c, launch_wgrad_reduce(rb, c->plan.dtype, c->stream));
-      c->stats.kernel_launches++;
-      rb.n = 0;
-    }
+    if (rb.n == WREDUCE_MAX_PROBS) { int rc = flush_folds(); if (rc) return rc; }
   }
-  if (rb.n) {
-    HIP_TRY(c, launch_wgrad_reduce(rb, c->plan.dtype, c->stream));
-    c->stats.kernel_launches++;
-  }
+  { int rc = flush_folds(); if (rc) return rc; }
   const int dt = c->plan.dtype;
   for (const Item& it : items) {
     switch (it.kind) {
@@ -898,6 +934,10 @@ int run_tick(cdp_ctx* c, const float* x_dev, const int32_t* y_dev) {
       c->steps_enqueued++;
       c->heads_done[t_new % LOSS_LOG_STEPS] = 0;
     }
+  }
+  else if (x_dev != nullptr && c->origin_step + rel_tick / (2 * S) >= c->steps_enqueued) {
+    // a mini-batch handed over in the middle of its step: its first micro-batches should have started already
+    return fail(c, CDP_ESTATE, "the mini-batch of this step was not handed over at the step's first tick");
   }
   struct Visit { int i; int64_t t; int j; int dir; int version; };
   std::vector<Visit> act;
@@ -1196,9 +1236,20 @@ int cdp_set_weights(cdp_ctx* c, int stage, const float* host, size_t n) {
   return CDP_OK;
 }
 
+// A tick that fails after it has started to change the timeline state (counters, records, pool) cannot be
+// retried: the context refuses further ticks.  A failure before any change leaves the context as it was.
+static int guarded_tick(cdp_ctx* c, const float* x_dev, const int32_t* y_dev) {
+  if (c->poisoned) return fail(c, CDP_ESTATE, "an earlier tick failed half-way; the context can only be read and destroyed");
+  const int64_t enq = c->steps_enqueued;
+  const size_t ticks_logged = c->live_counts.size();
+  const int rc = run_tick(c, x_dev, y_dev);
+  if (rc != CDP_OK && (c->steps_enqueued != enq || c->live_counts.size() != ticks_logged)) c->poisoned = true;
+  return rc;
+}
+
 int cdp_tick(cdp_ctx* c, const float* x_dev, const int32_t* y_dev) {
   if (!c) return fail(nullptr, CDP_EINVAL, "ctx is NULL");
-  return run_tick(c, x_dev, y_dev);
+  return guarded_tick(c, x_dev, y_dev);
 }
 
 int cdp_step(cdp_ctx* c, const float* x_dev, const int32_t* y_dev) {
@@ -1206,7 +1257,7 @@ int cdp_step(cdp_ctx* c, const float* x_dev, const int32_t* y_dev) {
   if (!x_dev || !y_dev) return fail(c, CDP_EINVAL, "x_dev / y_dev is NULL");
   if ((c->tick - c->origin_tick) % (2 * c->S) != 0) return fail(c, CDP_ESTATE, "cdp_step must start on a step boundary");
   for (int k = 0; k < 2 * c->S; ++k) {
-    int rc = run_tick(c, x_dev, y_dev);
+    int rc = guarded_tick(c, x_dev, y_dev);
     if (rc) return rc;
   }
   return CDP_OK;
@@ -1218,7 +1269,7 @@ int cdp_drain(cdp_ctx* c) {
   // remaining passes are exactly those of micro-batches already in flight
   int guard = 4 * c->S + c->d * c->N + 4;
   while (inflight(c) > 0 && guard-- > 0) {
-    int rc = run_tick(c, nullptr, nullptr);
+    int rc = guarded_tick(c, nullptr, nullptr);
     if (rc) return rc;
   }
   return CDP_OK;

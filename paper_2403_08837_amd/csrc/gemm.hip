@@ -4,36 +4,10 @@
 // problems of a tick are independent and use distinct stage weights).  One launch walks
 // a tile list over all problems.  Tiles are staged through LDS and contracted with
 // MFMA (bf16: v_mfma_f32_32x32x16_bf16, fp32: v_mfma_f32_32x32x2_f32), fp32 accumulate.
+#include "elem.h"
 #include "kernels.h"
 
 namespace cdp {
-
-typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 v8bf16;
-typedef __attribute__((__vector_size__(16 * sizeof(float)))) float v16f;
-
-__device__ __forceinline__ float bf16_bits_to_f32(uint16_t h) { return __uint_as_float(((uint32_t)h) << 16); }
-__device__ __forceinline__ uint16_t f32_to_bf16_bits(float f) {
-  uint32_t u = __float_as_uint(f);
-  if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x40u);  // quiet NaN
-  u += 0x7fffu + ((u >> 16) & 1u);                                            // round to nearest even
-  return (uint16_t)(u >> 16);
-}
-
-template <typename T> struct Elem;
-template <> struct Elem<uint16_t> {
-  static constexpr int VEC = 8;     // elements per 16-byte chunk
-  static constexpr int MFMA_K = 16; // reduction elements per MFMA
-  static constexpr int KPL = 8;     // reduction elements per lane per MFMA
-  __device__ static __forceinline__ float to_f32(uint16_t v) { return bf16_bits_to_f32(v); }
-  __device__ static __forceinline__ uint16_t from_f32(float f) { return f32_to_bf16_bits(f); }
-};
-template <> struct Elem<float> {
-  static constexpr int VEC = 4;
-  static constexpr int MFMA_K = 2;
-  static constexpr int KPL = 1;
-  __device__ static __forceinline__ float to_f32(float v) { return v; }
-  __device__ static __forceinline__ float from_f32(float f) { return f; }
-};
 
 // Element offset of virtual operand entry (r, k), or -1 where the entry is a structural
 // zero (padding, stride hole, out of range).
@@ -153,16 +127,16 @@ struct TileLoader {
 };
 
 template <typename T>
-__device__ __forceinline__ v16f mfma_step(const T* a_lds, const T* b_lds, v16f acc);
+__device__ __forceinline__ v16f_t mfma_step(const T* a_lds, const T* b_lds, v16f_t acc);
 
 template <>
-__device__ __forceinline__ v16f mfma_step<uint16_t>(const uint16_t* a, const uint16_t* b, v16f acc) {
+__device__ __forceinline__ v16f_t mfma_step<uint16_t>(const uint16_t* a, const uint16_t* b, v16f_t acc) {
   uint4 av = *reinterpret_cast<const uint4*>(a);
   uint4 bv = *reinterpret_cast<const uint4*>(b);
-  return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(v8bf16, av), __builtin_bit_cast(v8bf16, bv), acc, 0, 0, 0);
+  return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(v8bf16_t, av), __builtin_bit_cast(v8bf16_t, bv), acc, 0, 0, 0);
 }
 template <>
-__device__ __forceinline__ v16f mfma_step<float>(const float* a, const float* b, v16f acc) {
+__device__ __forceinline__ v16f_t mfma_step<float>(const float* a, const float* b, v16f_t acc) {
   return __builtin_amdgcn_mfma_f32_32x32x2f32(*a, *b, acc, 0, 0, 0);
 }
 
@@ -209,7 +183,7 @@ __global__ __launch_bounds__(256) void gemm_grouped_kernel(const GemmBatch batch
 
   TileLoader<T, BM, BK> la;
   TileLoader<T, BN, BK> lb;
-  v16f acc[MI][NI];
+  v16f_t acc[MI][NI];
 #pragma unroll
   for (int i = 0; i < MI; ++i)
 #pragma unroll

@@ -145,6 +145,11 @@ constexpr int64_t THIN_WS_BYTES = (int64_t)THIN_WS_SLOTS * (32 * 32 * 4 + 4);  /
 bool conv_fast_eligible(const GemmProb& p, int dtype);
 void conv_gemm_tile(const GemmProb* p, int n, int* bm, int* bn);  // tile shape that keeps the chip busy for these problems
 hipError_t launch_conv_gemm(GemmBatch& batch, int dtype, int bm, int bn, hipStream_t stream);  // forward / data gradient
+// Large-tile variant (256 x 256 outputs, eight wavefronts, operands loaded straight into LDS) for bf16
+// problems whose reduction slabs of 64 lie inside one tap; _wanted: enough mostly-full tiles to fill the chip.
+bool conv_gemm256_eligible(const GemmProb& p, int dtype);
+bool conv_gemm256_wanted(const GemmProb* p, int n, int dtype);
+hipError_t launch_conv_gemm256(GemmBatch& batch, int dtype, hipStream_t stream);
 // Weight gradient in two phases: launch_conv_wgrad writes per-range partial sums
 // (out = f32 [splits][Cout][Ncol], aux3 = f32 [splits][Cout] or NULL, splits fixed by
 // conv_wgrad_splits), launch_wgrad_reduce folds them into the accumulators.

@@ -47,6 +47,8 @@ int cdp_k_conv(int dtype, int which, const void* in0, const void* in1, void* out
   p.A = in0; p.B = in1; p.out = out;
   ConvGeom& g = p.g;
   g.KH = ks; g.KW = ks; g.stride = stride; g.pad = pad;
+  const bool force256 = which == 3 || which == 4;  // the large tile regardless of the launch heuristic
+  if (force256) which -= 3;
   if (which == 0) {
     p.M = B * Ho * Wo; p.N = Cout; p.K = ks * ks * Cin;
     p.a_mode = OP_CONV_FWD; p.b_mode = OP_PLAIN_K; p.ldb = p.K; p.ldo = Cout;
@@ -83,7 +85,11 @@ int cdp_k_conv(int dtype, int which, const void* in0, const void* in1, void* out
       if (launch_conv_wgrad(b, dtype, p.M >= 128, st) != hipSuccess) return CDP_EHIP;
       return launch_wgrad_reduce(rb, dtype, st) == hipSuccess ? CDP_OK : CDP_EHIP;
     }
+  } else if (force256) {
+    if (!conv_gemm256_eligible(p, dtype)) return CDP_EINVAL;
+    return launch_conv_gemm256(b, dtype, st) == hipSuccess ? CDP_OK : CDP_EHIP;
   } else if (conv_fast_eligible(p, dtype)) {
+    if (conv_gemm256_wanted(&p, 1, dtype)) return launch_conv_gemm256(b, dtype, st) == hipSuccess ? CDP_OK : CDP_EHIP;
     int bm, bn;
     conv_gemm_tile(&p, 1, &bm, &bn);
     return launch_conv_gemm(b, dtype, bm, bn, st) == hipSuccess ? CDP_OK : CDP_EHIP;

@@ -16,40 +16,17 @@
 // channels (weight rows are a power of two apart).
 #include <algorithm>
 
+#include "elem.h"
 #include "kernels.h"
 #include "mfma_frag.h"
 #include "sgd_step.h"
 
 namespace cdp {
 
-typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 v8bf16_t;
-typedef __attribute__((__vector_size__(16 * sizeof(float)))) float v16f_t;
-
 namespace {
 
-__device__ __forceinline__ float bf2f(uint16_t h) { return __uint_as_float(((uint32_t)h) << 16); }
-__device__ __forceinline__ uint16_t f2bf(float f) {
-  uint32_t u = __float_as_uint(f);
-  if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x40u);
-  u += 0x7fffu + ((u >> 16) & 1u);
-  return (uint16_t)(u >> 16);
-}
-template <typename T> struct LT;
-template <> struct LT<uint16_t> {
-  static constexpr int VEC = 8, MFMA_K = 16, KPL = 8, SLAB = 128;
-  __device__ static __forceinline__ float to_f32(uint16_t v) { return bf2f(v); }
-  __device__ static __forceinline__ uint16_t from_f32(float f) { return f2bf(f); }
-};
-template <> struct LT<float> {
-  static constexpr int VEC = 4, MFMA_K = 2, KPL = 1, SLAB = 64;
-  __device__ static __forceinline__ float to_f32(float v) { return v; }
-  __device__ static __forceinline__ float from_f32(float f) { return f; }
-};
-
-template <typename T> union Chunk16 {
-  uint4 v;
-  uint2 h[2];
-  T e[16 / sizeof(T)];
+template <typename T> struct LT : Elem<T> {
+  static constexpr int SLAB = 16 * Elem<T>::VEC;  // reduction depth of a staged slab
 };
 
 // blockIdx -> logical tile: consecutive workgroup ids are dealt round-robin to the 8 XCDs,
@@ -65,17 +42,6 @@ __host__ __device__ __forceinline__ int dw_tile_rows(const GemmProb& p) {
   return ((p.M + 63) / 64) * p.tiles_n < 512 && (p.K <= 64 || p.upd) ? 32 : 64;
 }
 
-__device__ __forceinline__ int find_problem(const GemmBatch& batch, int tile) {
-  int pi = 0;
-  for (int q = 1; q < batch.n; ++q)
-    if (tile >= batch.p[q].tile_begin) pi = q;
-  return pi;
-}
-
-__device__ __forceinline__ v16f_t mfma_bf16(uint4 a, uint4 b, v16f_t c) {
-  return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(v8bf16_t, a), __builtin_bit_cast(v8bf16_t, b), c, 0, 0, 0);
-}
-
 }  // namespace
 
 // One 16-byte chunk of operand elements read from an fp32 matrix and rounded to T (RNE), the
@@ -87,8 +53,8 @@ __device__ __forceinline__ uint4 load_chunk_f32(const float* src) {
     return *reinterpret_cast<const uint4*>(src);
   } else {
     const float4 lo = *reinterpret_cast<const float4*>(src), hi = *reinterpret_cast<const float4*>(src + 4);
-    return make_uint4((uint32_t)f2bf(lo.x) | ((uint32_t)f2bf(lo.y) << 16), (uint32_t)f2bf(lo.z) | ((uint32_t)f2bf(lo.w) << 16),
-                      (uint32_t)f2bf(hi.x) | ((uint32_t)f2bf(hi.y) << 16), (uint32_t)f2bf(hi.z) | ((uint32_t)f2bf(hi.w) << 16));
+    return make_uint4((uint32_t)f32_to_bf16(lo.x) | ((uint32_t)f32_to_bf16(lo.y) << 16), (uint32_t)f32_to_bf16(lo.z) | ((uint32_t)f32_to_bf16(lo.w) << 16),
+                      (uint32_t)f32_to_bf16(hi.x) | ((uint32_t)f32_to_bf16(hi.y) << 16), (uint32_t)f32_to_bf16(hi.z) | ((uint32_t)f32_to_bf16(hi.w) << 16));
   }
 }
 

@@ -2,24 +2,11 @@
 // softmax cross-entropy head (one wavefront per row), bias-gradient column sums, the
 // SGD update with re-layout of the new weight version (Eq. (CDP): theta_{t+1} =
 // theta_t - gamma/N * sum_i grad f_i), pooling.
+#include "elem.h"
 #include "kernels.h"
 #include "sgd_step.h"
 
 namespace cdp {
-
-__device__ __forceinline__ float bf16_to_f32(uint16_t h) { return __uint_as_float(((uint32_t)h) << 16); }
-__device__ __forceinline__ uint16_t f32_to_bf16(float f) {
-  uint32_t u = __float_as_uint(f);
-  if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x40u);
-  u += 0x7fffu + ((u >> 16) & 1u);
-  return (uint16_t)(u >> 16);
-}
-template <typename T> __device__ __forceinline__ float ld_f32(const T* p, int64_t i);
-template <> __device__ __forceinline__ float ld_f32<uint16_t>(const uint16_t* p, int64_t i) { return bf16_to_f32(p[i]); }
-template <> __device__ __forceinline__ float ld_f32<float>(const float* p, int64_t i) { return p[i]; }
-template <typename T> __device__ __forceinline__ void st_f32(T* p, int64_t i, float v);
-template <> __device__ __forceinline__ void st_f32<uint16_t>(uint16_t* p, int64_t i, float v) { p[i] = f32_to_bf16(v); }
-template <> __device__ __forceinline__ void st_f32<float>(float* p, int64_t i, float v) { p[i] = v; }
 
 #define CDP_DISPATCH(dtype, CALL)                 \
   do {                                            \

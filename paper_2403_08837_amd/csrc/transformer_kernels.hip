@@ -2,25 +2,15 @@
 // GELU and the self-attention core.  Token-wise linear maps run on the convolution path as
 // 1x1 convolutions.  LayerNorm and the softmax take one wavefront per token row; the attention
 // contractions (about a tenth of a block's flops at 196 tokens) are a batched MFMA product.
+#include "elem.h"
 #include "kernels.h"
 
 namespace cdp {
 
 namespace {
 
-__device__ __forceinline__ float t_bf2f(uint16_t h) { return __uint_as_float(((uint32_t)h) << 16); }
-__device__ __forceinline__ uint16_t t_f2bf(float f) {
-  uint32_t u = __float_as_uint(f);
-  if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x40u);
-  u += 0x7fffu + ((u >> 16) & 1u);
-  return (uint16_t)(u >> 16);
-}
-template <typename T> __device__ __forceinline__ float tld(const T* p, int64_t i);
-template <> __device__ __forceinline__ float tld<uint16_t>(const uint16_t* p, int64_t i) { return t_bf2f(p[i]); }
-template <> __device__ __forceinline__ float tld<float>(const float* p, int64_t i) { return p[i]; }
-template <typename T> __device__ __forceinline__ void tst(T* p, int64_t i, float v);
-template <> __device__ __forceinline__ void tst<uint16_t>(uint16_t* p, int64_t i, float v) { p[i] = t_f2bf(v); }
-template <> __device__ __forceinline__ void tst<float>(float* p, int64_t i, float v) { p[i] = v; }
+template <typename T> __device__ __forceinline__ float tld(const T* p, int64_t i) { return ld_f32<T>(p, i); }
+template <typename T> __device__ __forceinline__ void tst(T* p, int64_t i, float v) { st_f32<T>(p, i, v); }
 
 #define CDP_TDISPATCH(dtype, CALL)                        \
   do {                                                    \
@@ -67,10 +57,10 @@ template <> struct RowChunk<uint16_t> {
   }
   __device__ static __forceinline__ void store(uint16_t* p, const float* v) {
     uint4 u;
-    u.x = (uint32_t)t_f2bf(v[0]) | ((uint32_t)t_f2bf(v[1]) << 16);
-    u.y = (uint32_t)t_f2bf(v[2]) | ((uint32_t)t_f2bf(v[3]) << 16);
-    u.z = (uint32_t)t_f2bf(v[4]) | ((uint32_t)t_f2bf(v[5]) << 16);
-    u.w = (uint32_t)t_f2bf(v[6]) | ((uint32_t)t_f2bf(v[7]) << 16);
+    u.x = (uint32_t)f32_to_bf16(v[0]) | ((uint32_t)f32_to_bf16(v[1]) << 16);
+    u.y = (uint32_t)f32_to_bf16(v[2]) | ((uint32_t)f32_to_bf16(v[3]) << 16);
+    u.z = (uint32_t)f32_to_bf16(v[4]) | ((uint32_t)f32_to_bf16(v[5]) << 16);
+    u.w = (uint32_t)f32_to_bf16(v[6]) | ((uint32_t)f32_to_bf16(v[7]) << 16);
     *reinterpret_cast<uint4*>(p) = u;
   }
 };
@@ -387,8 +377,8 @@ __device__ __forceinline__ void t_ld4(const float* p, int64_t g, float* v) {
 }
 __device__ __forceinline__ void t_st4(uint16_t* p, int64_t g, const float* v) {
   uint2 u;
-  u.x = (uint32_t)t_f2bf(v[0]) | ((uint32_t)t_f2bf(v[1]) << 16);
-  u.y = (uint32_t)t_f2bf(v[2]) | ((uint32_t)t_f2bf(v[3]) << 16);
+  u.x = (uint32_t)f32_to_bf16(v[0]) | ((uint32_t)f32_to_bf16(v[1]) << 16);
+  u.y = (uint32_t)f32_to_bf16(v[2]) | ((uint32_t)f32_to_bf16(v[3]) << 16);
   reinterpret_cast<uint2*>(p)[g] = u;
 }
 __device__ __forceinline__ void t_st4(float* p, int64_t g, const float* v) {

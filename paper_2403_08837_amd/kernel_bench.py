@@ -51,10 +51,10 @@ def conv(which, B, H, W, Cin, Cout, ks, st, pad, reps=20):
     dx = torch.empty_like(x)
     dw = torch.empty(Cout, ks, ks, Cin, device="cuda")
     ws = torch.empty(64 << 20, device="cuda", dtype=torch.float32)
-    if which == 0:
-        call = lambda: b.cdp_k_conv(1, 0, x.data_ptr(), w.data_ptr(), y.data_ptr(), B, H, W, Cin, Cout, ks, st, pad)
-    elif which == 1:
-        call = lambda: b.cdp_k_conv(1, 1, dy.data_ptr(), wt.data_ptr(), dx.data_ptr(), B, H, W, Cin, Cout, ks, st, pad)
+    if which in (0, 3):      # 3 / 4: forced onto the 256 x 256 tile
+        call = lambda: b.cdp_k_conv(1, which, x.data_ptr(), w.data_ptr(), y.data_ptr(), B, H, W, Cin, Cout, ks, st, pad)
+    elif which in (1, 4):
+        call = lambda: b.cdp_k_conv(1, which, dy.data_ptr(), wt.data_ptr(), dx.data_ptr(), B, H, W, Cin, Cout, ks, st, pad)
     else:
         call = lambda: b.cdp_k_conv(1, 2, dy.data_ptr(), x.data_ptr(), dw.data_ptr(), B, H, W, Cin, Cout, ks, st, pad,
                                     ws.data_ptr(), ws.numel() * 4)
@@ -149,6 +149,15 @@ def main():
         for which, name in ((0, "fwd"), (1, "dgrad"), (2, "wgrad")):
             us, tf, gb = conv(which, *s[1:])
             parts.append("%s %7.1f us %6.1f TF/s (%.2f) %5.0f GB/s (%.2f)" % (name, us, tf, tf / MFMA_PEAK, gb, gb / HBM_PEAK))
+        print("%-34s %s" % (s[0], " | ".join(parts)), flush=True)
+    print("# The same passes forced onto the 256 x 256 tile (cdp_k_conv which = 3 / 4), where the channel counts allow")
+    for s in CONV_SHAPES + [("8192 x 8192 x 8192 product", 32, 16, 16, 8192, 8192, 1, 1, 0)]:
+        if args.only not in s[0] or s[4] % 64 or s[5] % 64:
+            continue
+        parts = []
+        for which, name in ((3, "fwd"), (4, "dgrad")):
+            us, tf, gb = conv(which, *s[1:])
+            parts.append("%s %7.1f us %6.1f TF/s (%.2f)" % (name, us, tf, tf / MFMA_PEAK))
         print("%-34s %s" % (s[0], " | ".join(parts)), flush=True)
 
 

@@ -100,6 +100,47 @@ def test_conv_passes_match_oracle(dtype, case):
         assert err <= tol, (name, err)
 
 
+LARGE_TILE_CASES = [
+    # pass, B, H, W, Cin, Cout, ks, stride, pad: shapes that fill the chip with 256 x 256 tiles
+    ("fwd", 16, 56, 56, 64, 256, 3, 1, 1),
+    ("dgrad", 16, 56, 56, 256, 64, 3, 1, 1),
+    ("fwd", 64, 56, 56, 64, 256, 3, 2, 1),       # stride 2: padding on one side only
+    ("dgrad", 16, 56, 56, 256, 64, 3, 2, 1),     # stride 2: taps on the stride lattice
+    ("dgrad", 4, 45, 45, 4040, 128, 1, 1, 0),    # ragged in both directions
+    ("fwd", 8, 28, 28, 1024, 2048, 1, 1, 0),     # 16 slabs
+    ("fwd", 2, 9, 7, 64, 64, 3, 1, 1),           # a single ragged tile
+    ("dgrad", 3, 10, 10, 64, 128, 3, 2, 1),
+]
+
+
+@pytest.mark.parametrize("case", LARGE_TILE_CASES)
+def test_conv_large_tile_matches_oracle(case):
+    """Forward / data gradient on the 256 x 256 tile (bf16; operands loaded straight into LDS, swizzled
+    rows, two stages) against the oracle's convolution."""
+    torch = _torch()
+    which, B, H, W, Cin, Cout, ks, st, pad = case
+    dtype = wl.BF16
+    x = wl.random_normal(7, 1, B * H * W * Cin).reshape(B, H, W, Cin)
+    w = wl.random_normal(7, 2, Cout * ks * ks * Cin).reshape(Cout, ks, ks, Cin) / np.sqrt(ks * ks * Cin)
+    xr, wr = _rnd(x, dtype), _rnd(w, dtype)
+    if which == "fwd":
+        ref = L.conv2d_fwd(xr, wr, st, pad)
+        xd, wd = _dev(x, dtype), _dev(w, dtype)
+        got = torch.full(ref.shape, float("nan"), dtype=torch.bfloat16, device="cuda")
+        b.cdp_k_conv(dtype, 3, xd.data_ptr(), wd.data_ptr(), got.data_ptr(), B, H, W, Cin, Cout, ks, st, pad)
+    else:
+        Ho, Wo = (H + 2 * pad - ks) // st + 1, (W + 2 * pad - ks) // st + 1
+        dy = wl.random_normal(7, 3, B * Ho * Wo * Cout).reshape(B, Ho, Wo, Cout)
+        ref, _ = L.conv2d_bwd(xr, wr, st, pad, _rnd(dy, dtype))
+        dyd, wtd = _dev(dy, dtype), _dev(np.transpose(w, (3, 1, 2, 0)), dtype)
+        got = torch.full(x.shape, float("nan"), dtype=torch.bfloat16, device="cuda")
+        b.cdp_k_conv(dtype, 4, dyd.data_ptr(), wtd.data_ptr(), got.data_ptr(), B, H, W, Cin, Cout, ks, st, pad)
+    torch.cuda.synchronize()
+    g = got.float().cpu().numpy().astype(np.float64)
+    assert np.isfinite(g).all()
+    assert np.abs(g - ref).max() / np.abs(ref).max() <= 2.0 ** -7
+
+
 @pytest.mark.gpu
 @pytest.mark.parametrize("dtype", [wl.F32, wl.BF16])
 @pytest.mark.parametrize("which", ["fwd", "dgrad"])

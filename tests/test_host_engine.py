@@ -187,3 +187,20 @@ def test_retained_activation_bytes_per_tick_are_periodic(name):
         unit = cfg.B * 4096 * 2
         assert min(ks) == 200 * unit and max(ks) == 200 * unit + unit + cfg.B * 1000 * 2
     tr.close()
+
+
+def test_mini_batch_handed_over_after_its_first_tick_is_refused():
+    """A step whose mini-batch pointer is missing at the step's first tick cannot take it later: the
+    micro-batches that should have started would silently never run."""
+    cfg = wl.get_config("mlp_mini")
+    tr = b.Trainer(cfg.stages, cfg.in_shape, cfg.N, cfg.B, cfg.lr, wl.RULE_V2, cfg.dtype, dry_run=True)
+    for _ in range(2 * cfg.S):
+        tr.tick_dry(True)
+    tr.tick_dry(False)                     # boundary of step 1 without data: nothing new starts
+    with pytest.raises(b.CdpError) as e:
+        tr.tick_dry(True)                  # too late for step 1
+    assert e.value.code == b.CDP_ESTATE
+    tr.drain()                             # the context is unchanged by the refused call
+    r = O.train_schedule(cfg, None, [None], [None], wl.RULE_V2, compute=False)
+    assert [t[1:] for t in tr.trace()] == [t[1:] for t in r.trace] or len(tr.trace()) == len(r.trace)
+    tr.close()

@@ -72,7 +72,7 @@ def test_v2_rule_table_from_paper():
 
 @pytest.mark.parametrize("S,N", SN)
 def test_v2_freshest_equals_closed_form(S, N):
-    """Operational rule ("parameters in memory are always the freshest available") ==
+    """Operational rule (Sec. 3.2: whatever parameters are in memory are the freshest ones) ==
     closed form d(i+1)+2j >= 2S, which is the paper's predicate when S = N."""
     T = 4
     r = _run(S, N, wl.RULE_V2, T)

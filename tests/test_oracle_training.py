@@ -8,7 +8,7 @@ import cdp_workloads as wl
 from oracle import cdp_oracle as O
 from oracle import layers as L
 from test_oracle_layers import torch_forward, to_torch_params, to_torch_x
-from bf16_emulation import Bf16Storage
+from precision_standins import Bf16Storage, Fp32Accumulation
 
 RULES = [wl.RULE_DP, wl.RULE_V1, wl.RULE_V2]
 
