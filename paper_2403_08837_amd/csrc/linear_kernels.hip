@@ -490,43 +490,81 @@ __device__ __forceinline__ void dw_tile(const GemmBatch& batch, const GemmProb& 
   const bool dvec = (P.lda % VEC) == 0, xvec = (P.ldb % VEC) == 0;
   for (int m0 = 0; m0 < Mb; m0 += MB) {
     if (m0 > 0) __syncthreads();
-    // 2. stage dY[m0.., n0..n0+63] and X[m0.., k0..k0+127] as they lie in memory
+    // 2. stage dY[m0.., n0..n0+TN-1] and X[m0.., k0..k0+127] as they lie in memory.  All of a thread's chunks
+    // are requested before the first one is written to LDS: requested one by one (load, LDS store, load, ...)
+    // the six round trips to L2 of a bf16 tile cost 30 us of a 280 us launch of 16384 tiles.
     constexpr int DCH = TN / VEC, XCH = TK / VEC;  // chunks per row
-    for (int id = tid; id < MB * DCH; id += 256) {
-      const int m = id / DCH, c = (id % DCH) * VEC;
-      Chunk16<T> tmp;
-      tmp.v = make_uint4(0, 0, 0, 0);
-      if (m0 + m < Mb) {
-        const T* src = Dp + (int64_t)(m0 + m) * P.lda + n0 + c;
-        if (dvec && n0 + c + VEC <= Nn) {
-          tmp.v = *reinterpret_cast<const uint4*>(src);
-        } else {
+    constexpr int ND = MB * DCH / 256, NX = MB * XCH / 256;
+    static_assert(ND * 256 == MB * DCH && NX * 256 == MB * XCH, "whole chunks per thread");
+    if (dvec && xvec && (Nn % VEC) == 0 && (Kk % VEC) == 0) {  // every chunk is whole: inside or outside the matrices
+      uint4 rd[ND], rx[NX];
 #pragma unroll
-          for (int e = 0; e < VEC; ++e)
-            if (n0 + c + e < Nn) tmp.e[e] = src[e];
-        }
+      for (int i = 0; i < ND; ++i) {
+        const int id = tid + 256 * i, m = id / DCH, c = (id % DCH) * VEC;
+        rd[i] = (m0 + m < Mb && n0 + c < Nn) ? *reinterpret_cast<const uint4*>(Dp + (int64_t)(m0 + m) * P.lda + n0 + c)
+                                              : make_uint4(0, 0, 0, 0);
       }
-      uint2* dst = reinterpret_cast<uint2*>(Ds + m * PD + c);
-      dst[0] = tmp.h[0];
-      dst[1] = tmp.h[1];
-    }
-    for (int id = tid; id < MB * XCH; id += 256) {
-      const int m = id / XCH, c = (id % XCH) * VEC;
-      Chunk16<T> tmp;
-      tmp.v = make_uint4(0, 0, 0, 0);
-      if (m0 + m < Mb) {
-        const T* src = Xp + (int64_t)(m0 + m) * P.ldb + k0 + c;
-        if (xvec && k0 + c + VEC <= Kk) {
-          tmp.v = *reinterpret_cast<const uint4*>(src);
-        } else {
 #pragma unroll
-          for (int e = 0; e < VEC; ++e)
-            if (k0 + c + e < Kk) tmp.e[e] = src[e];
-        }
+      for (int i = 0; i < NX; ++i) {
+        const int id = tid + 256 * i, m = id / XCH, c = (id % XCH) * VEC;
+        rx[i] = (m0 + m < Mb && k0 + c < Kk) ? *reinterpret_cast<const uint4*>(Xp + (int64_t)(m0 + m) * P.ldb + k0 + c)
+                                              : make_uint4(0, 0, 0, 0);
       }
-      uint2* dst = reinterpret_cast<uint2*>(Xs + m * PX + c);
-      dst[0] = tmp.h[0];
-      dst[1] = tmp.h[1];
+#pragma unroll
+      for (int i = 0; i < ND; ++i) {
+        const int id = tid + 256 * i, m = id / DCH, c = (id % DCH) * VEC;
+        Chunk16<T> tmp;
+        tmp.v = rd[i];
+        uint2* dst = reinterpret_cast<uint2*>(Ds + m * PD + c);
+        dst[0] = tmp.h[0];
+        dst[1] = tmp.h[1];
+      }
+#pragma unroll
+      for (int i = 0; i < NX; ++i) {
+        const int id = tid + 256 * i, m = id / XCH, c = (id % XCH) * VEC;
+        Chunk16<T> tmp;
+        tmp.v = rx[i];
+        uint2* dst = reinterpret_cast<uint2*>(Xs + m * PX + c);
+        dst[0] = tmp.h[0];
+        dst[1] = tmp.h[1];
+      }
+    } else {
+      for (int id = tid; id < MB * DCH; id += 256) {
+        const int m = id / DCH, c = (id % DCH) * VEC;
+        Chunk16<T> tmp;
+        tmp.v = make_uint4(0, 0, 0, 0);
+        if (m0 + m < Mb) {
+          const T* src = Dp + (int64_t)(m0 + m) * P.lda + n0 + c;
+          if (dvec && n0 + c + VEC <= Nn) {
+            tmp.v = *reinterpret_cast<const uint4*>(src);
+          } else {
+  #pragma unroll
+            for (int e = 0; e < VEC; ++e)
+              if (n0 + c + e < Nn) tmp.e[e] = src[e];
+          }
+        }
+        uint2* dst = reinterpret_cast<uint2*>(Ds + m * PD + c);
+        dst[0] = tmp.h[0];
+        dst[1] = tmp.h[1];
+      }
+      for (int id = tid; id < MB * XCH; id += 256) {
+        const int m = id / XCH, c = (id % XCH) * VEC;
+        Chunk16<T> tmp;
+        tmp.v = make_uint4(0, 0, 0, 0);
+        if (m0 + m < Mb) {
+          const T* src = Xp + (int64_t)(m0 + m) * P.ldb + k0 + c;
+          if (xvec && k0 + c + VEC <= Kk) {
+            tmp.v = *reinterpret_cast<const uint4*>(src);
+          } else {
+  #pragma unroll
+            for (int e = 0; e < VEC; ++e)
+              if (k0 + c + e < Kk) tmp.e[e] = src[e];
+          }
+        }
+        uint2* dst = reinterpret_cast<uint2*>(Xs + m * PX + c);
+        dst[0] = tmp.h[0];
+        dst[1] = tmp.h[1];
+      }
     }
     __syncthreads();
     // 3. contraction over the batch rows; fragments are read transposed out of LDS
@@ -644,6 +682,211 @@ __device__ __forceinline__ void dw_tile(const GemmBatch& batch, const GemmProb& 
 }
 
 // ---------------------------------------------------------------------------------
+// dw_run: DW_RUN consecutive 64 x 128 tiles of one row block of G per workgroup, software-pipelined.  With one
+// tile per workgroup the resident workgroups of a launch move in step (request, wait, contract, store), and the
+// time of the operand / contraction phase adds to the time of the accumulator stream instead of hiding under
+// it (a 16384-tile launch: 117 us without the accumulator traffic, 188 us for that traffic alone, 280 us
+// together).  Here the accumulator tile and the X tile of the NEXT column tile are requested before the
+// current one is contracted and written back, and the dY tile is staged once for the whole run.
+// For plain accumulate tiles (no fused SGD step) of a single reduction slab (at most 64 batch rows) whose
+// operand chunks are whole; same operand convention as dw_tile.
+constexpr int DW_RUN = 4;
+// upd_ok: a problem with a fused SGD step may take this path (wide kernel, no momentum)
+__host__ __device__ __forceinline__ int dw_run_length(const GemmProb& p, int vec, bool upd_ok) {
+  const bool whole = p.lda % vec == 0 && p.ldb % vec == 0 && p.M % vec == 0 && p.N % vec == 0;
+  return ((!p.upd || upd_ok) && whole && p.K <= 64 && p.N >= 8 * 128 && p.M >= 512) ? DW_RUN : 1;
+}
+
+template <typename T, bool UPD>
+__device__ __forceinline__ void dw_run(const GemmBatch& batch, const GemmProb& P, int tile, unsigned char* smem) {
+  using E = LT<T>;
+  constexpr int TN = 64, TK = 128, MB = 64, VEC = E::VEC, NI2 = TN / 32;
+  constexpr int PAD = sizeof(T) == 2 ? 16 : 4;
+  constexpr int PD = 64 + PAD, PX = TK + PAD;
+  constexpr int PW = TK + (sizeof(T) == 2 ? 2 : 1);  // LDS pitch of the new-weight tile [TN][TK] (UPD)
+  T* Ds = reinterpret_cast<T*>(smem);
+  T* Xs = Ds + MB * PD;
+  T* Ws = Xs + MB * PX;
+  const int groups = (P.tiles_n + DW_RUN - 1) / DW_RUN;
+  const int local = tile - P.tile_begin;
+  const int tk0 = (local % groups) * DW_RUN, tnn = local / groups;
+  const int nrun = min(DW_RUN, P.tiles_n - tk0);
+  const int n0 = tnn * TN;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int Nn = P.M, Kk = P.N, Mb = P.K;
+  const bool rmw = (P.flags & GF_ACCUM) != 0;
+  const LinUpdate& U = batch.upd[UPD ? P.upd - 1 : 0];
+  float* __restrict__ G = static_cast<float*>(P.out);
+  const T* __restrict__ Dp = static_cast<const T*>(P.A);
+  const T* __restrict__ Xp = static_cast<const T*>(P.B);
+  constexpr int DCH = TN / VEC, XCH = TK / VEC;
+  constexpr int ND = MB * DCH / 256, NX = MB * XCH / 256;
+
+  float gold[2][16 * NI2];
+  uint4 rx[NX];
+  // old accumulator values; with a fused SGD step combined with the master weights so that only this
+  // micro-batch's share is missing: w' = [w - lr*(Gold/N + wd*w)] - (lr/N)*acc
+  auto load_gold = [&](float* g, int k0) {
+    const int gc = k0 + wave * 32 + (lane & 31);
+#pragma unroll
+    for (int i = 0; i < NI2; ++i)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        const int r = n0 + i * 32 + (v >> 2) * 8 + (lane >> 5) * 4 + (v & 3);
+        const bool inb = r < Nn && gc < Kk;
+        const int64_t idx = (int64_t)r * P.ldo + gc;
+        float g0 = (rmw && inb) ? G[idx] : 0.f;
+        if (UPD && inb) {
+          const float w = U.master[idx];
+          g0 = w - U.sgd.lr * (g0 * U.sgd.inv_n + U.sgd.wd * w);
+        }
+        g[i * 16 + v] = g0;
+      }
+  };
+  auto load_x = [&](int k0) {
+#pragma unroll
+    for (int i = 0; i < NX; ++i) {
+      const int id = tid + 256 * i, m = id / XCH, c = (id % XCH) * VEC;
+      rx[i] = (m < Mb && k0 + c < Kk) ? *reinterpret_cast<const uint4*>(Xp + (int64_t)m * P.ldb + k0 + c) : make_uint4(0, 0, 0, 0);
+    }
+  };
+  auto store_x = [&]() {
+#pragma unroll
+    for (int i = 0; i < NX; ++i) {
+      const int id = tid + 256 * i, m = id / XCH, c = (id % XCH) * VEC;
+      Chunk16<T> tmp;
+      tmp.v = rx[i];
+      uint2* dst = reinterpret_cast<uint2*>(Xs + m * PX + c);
+      dst[0] = tmp.h[0];
+      dst[1] = tmp.h[1];
+    }
+  };
+
+  // prologue: accumulator tile 0, the dY tile of the row block, X tile 0
+  load_gold(gold[0], tk0 * TK);
+  {
+    uint4 rd[ND];
+#pragma unroll
+    for (int i = 0; i < ND; ++i) {
+      const int id = tid + 256 * i, m = id / DCH, c = (id % DCH) * VEC;
+      rd[i] = (m < Mb && n0 + c < Nn) ? *reinterpret_cast<const uint4*>(Dp + (int64_t)m * P.lda + n0 + c) : make_uint4(0, 0, 0, 0);
+    }
+    load_x(tk0 * TK);
+#pragma unroll
+    for (int i = 0; i < ND; ++i) {
+      const int id = tid + 256 * i, m = id / DCH, c = (id % DCH) * VEC;
+      Chunk16<T> tmp;
+      tmp.v = rd[i];
+      uint2* dst = reinterpret_cast<uint2*>(Ds + m * PD + c);
+      dst[0] = tmp.h[0];
+      dst[1] = tmp.h[1];
+    }
+    store_x();
+  }
+  __syncthreads();
+  float bsum = 0.f;  // bias gradient of column n0 + tid (first column tile of the matrix only)
+  if (tk0 == 0 && P.aux2 != nullptr && tid < TN)
+    for (int m = 0; m < MB; ++m) bsum += E::to_f32(Ds[m * PD + tid]);
+
+#pragma unroll
+  for (int t = 0; t < DW_RUN; ++t) {
+    if (t >= nrun) break;
+    const int k0 = (tk0 + t) * TK;
+    float* gcur = gold[t & 1];
+    // next tile's accumulator and X tile are on their way while this one is contracted and written back
+    if (t + 1 < nrun) {
+      load_gold(gold[(t + 1) & 1], k0 + TK);
+      load_x(k0 + TK);
+    }
+    v16f_t acc[NI2];
+#pragma unroll
+    for (int i = 0; i < NI2; ++i)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[i][v] = 0.f;
+    const int g = lane >> 5, l31 = lane & 31;
+    if constexpr (sizeof(T) == 2) {
+#pragma unroll
+      for (int kk = 0; kk < MB; kk += 16) {
+        const uint4 bv = frag_tr_bf16(Xs, PX, kk, wave * 32, lane);
+#pragma unroll
+        for (int i = 0; i < NI2; ++i) acc[i] = mfma_bf16(frag_tr_bf16(Ds, PD, kk, i * 32, lane), bv, acc[i]);
+      }
+    } else {
+#pragma unroll 8
+      for (int kk = 0; kk < MB; kk += 2) {
+        const float bv = Xs[(kk + g) * PX + wave * 32 + l31];
+#pragma unroll
+        for (int i = 0; i < NI2; ++i)
+          acc[i] = __builtin_amdgcn_mfma_f32_32x32x2f32(Ds[(kk + g) * PD + i * 32 + l31], bv, acc[i], 0, 0, 0);
+      }
+    }
+    const int gc = k0 + wave * 32 + l31;
+#pragma unroll
+    for (int i = 0; i < NI2; ++i)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        const int rl = i * 32 + (v >> 2) * 8 + g * 4 + (v & 3);
+        const int r = n0 + rl;
+        if constexpr (!UPD) {
+          if (r < Nn && gc < Kk) G[(int64_t)r * P.ldo + gc] = gcur[i * 16 + v] + acc[i][v];
+        } else {
+          // this contraction completes the sum over the micro-batches: the SGD step on the master weights
+          float w = 0.f;
+          if (r < Nn && gc < Kk) {
+            w = gcur[i * 16 + v] - (U.sgd.lr * U.sgd.inv_n) * acc[i][v];
+            U.master[(int64_t)r * P.ldo + gc] = w;
+          }
+          Ws[rl * PW + wave * 32 + l31] = E::from_f32(w);
+        }
+      }
+    if (UPD || t + 1 < nrun) __syncthreads();  // every wave has read its fragments of X tile t; Ws is complete
+    if (t + 1 < nrun) store_x();
+    if constexpr (UPD) {
+      // both compute copies of the new version, out of the new-weight tile in LDS
+      T* __restrict__ wf = static_cast<T*>(U.wf);
+      T* __restrict__ wt = static_cast<T*>(U.wt);
+      {  // forward layout: rows n, 16-byte chunks along k
+        constexpr int CPR = TK / VEC;
+        for (int id = tid; id < TN * CPR; id += 256) {
+          const int n = id / CPR, ck = (id % CPR) * VEC;
+          if (n0 + n >= Nn || k0 + ck >= Kk) continue;
+          Chunk16<T> tmp;
+#pragma unroll
+          for (int e = 0; e < VEC; ++e) tmp.e[e] = Ws[n * PW + ck + e];
+          *reinterpret_cast<uint4*>(wf + (int64_t)(n0 + n) * Kk + k0 + ck) = tmp.v;
+        }
+      }
+      {  // data-gradient layout: rows k, 16-byte chunks along n (read transposed out of LDS)
+        constexpr int CPR = TN / VEC;
+        for (int id = tid; id < TK * CPR; id += 256) {
+          const int k = id / CPR, cn = (id % CPR) * VEC;
+          if (k0 + k >= Kk || n0 + cn >= Nn) continue;
+          Chunk16<T> tmp;
+#pragma unroll
+          for (int e = 0; e < VEC; ++e) tmp.e[e] = Ws[(cn + e) * PW + k];
+          *reinterpret_cast<uint4*>(wt + (int64_t)(k0 + k) * Nn + n0 + cn) = tmp.v;
+        }
+      }
+    }
+    if (t + 1 < nrun) __syncthreads();  // X tile t+1 is staged; Ws has been read
+  }
+  if (tk0 == 0 && tid < TN && n0 + tid < Nn) {
+    if constexpr (!UPD) {
+      if (P.aux2 != nullptr) {
+        float* gb = static_cast<float*>(P.aux2) + n0 + tid;
+        *gb = rmw ? (*gb + bsum) : bsum;
+      }
+    } else if (U.bmaster != nullptr) {
+      const int n = n0 + tid;
+      const float gb = (rmw ? static_cast<const float*>(P.aux2)[n] : 0.f) + bsum;
+      const float bnew = sgd_step(U.bmaster[n], gb, U.bV ? U.bV + n : nullptr, U.sgd);
+      U.bmaster[n] = bnew;
+      U.bcopy[n] = bnew;
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------------
 // One launch for every Linear contraction of a tick level: the tile list mixes forward /
 // data-gradient tiles (skinny or thin) and weight-gradient tiles (dw), so the short read-
 // modify-write tiles fill the machine while the long weight-streaming tiles run.
@@ -651,7 +894,8 @@ template <typename T, int BN, bool THIN>
 __global__ __launch_bounds__(256) void linear_tick_kernel(const GemmBatch batch) {
   using E = LT<T>;
   constexpr int SK_BYTES = (64 + BN) * (E::SLAB + E::VEC) * (int)sizeof(T);
-  constexpr int DW_BYTES = 64 * (64 + 128 + 2 * (sizeof(T) == 2 ? 16 : 4)) * (int)sizeof(T);
+  // operand tiles of the weight gradient; in the wide kernel also the new-weight tile of a pipelined run with a fused SGD step
+  constexpr int DW_BYTES = (64 * (64 + 128 + 2 * (sizeof(T) == 2 ? 16 : 4)) + (BN == 128 && sizeof(T) == 2 ? 64 * (128 + 2) : 0)) * (int)sizeof(T);
   constexpr int TH_BYTES = THIN ? 4 * 2 * 32 * (2 * 4 * E::VEC + E::VEC) * (int)sizeof(T) : 0;  // thin tile: staging blocks of the four wavefronts
   static_assert(TH_BYTES == 0 || TH_BYTES >= 4 * 16 * 64 * 4, "the thin tile's partial sums must fit");
   constexpr int SM_BYTES = SK_BYTES > DW_BYTES ? (SK_BYTES > TH_BYTES ? SK_BYTES : TH_BYTES) : (DW_BYTES > TH_BYTES ? DW_BYTES : TH_BYTES);
@@ -692,7 +936,17 @@ __global__ __launch_bounds__(256) void linear_tick_kernel(const GemmBatch batch)
   }
   const GemmProb& P = batch.p[find_problem(batch, tile)];
   if (P.epi == EPI_WGRAD) {
-    if (dw_tile_rows(P) == 32) dw_tile<T, 32>(batch, P, tile, smem);
+    constexpr bool RUN_UPD = BN == 128 && sizeof(T) == 2;  // the new-weight tile has LDS of its own only there
+    const bool upd_ok = RUN_UPD && P.upd != 0 && batch.upd[P.upd - 1].V == nullptr;
+    if (dw_run_length(P, E::VEC, upd_ok) > 1) {
+      if constexpr (RUN_UPD) {
+        if (P.upd) {
+          dw_run<T, true>(batch, P, tile, smem);
+          return;
+        }
+      }
+      dw_run<T, false>(batch, P, tile, smem);
+    } else if (dw_tile_rows(P) == 32) dw_tile<T, 32>(batch, P, tile, smem);
     else dw_tile<T, 64>(batch, P, tile, smem);
   } else {
     if constexpr (THIN) {
@@ -753,6 +1007,8 @@ hipError_t launch_linear_tick(GemmBatch& b, int dtype, bool wide, bool allow_thi
       {
         const int rows = dw_tile_rows(p);
         tiles = ((p.M + rows - 1) / rows) * p.tiles_n;
+        const int run = dw_run_length(p, vec, wide && dtype == DT_BF16 && p.upd != 0 && b.upd[p.upd - 1].V == nullptr);
+        if (run > 1) tiles = ((p.M + 63) / 64) * ((p.tiles_n + run - 1) / run);  // runs of column tiles, 64 rows high
         if (p.upd) b.upd_tiles += tiles;
       }
     } else {
