@@ -577,31 +577,65 @@ __global__ __launch_bounds__(256) void wgrad_reduce_kernel(const WReduceBatch ba
   }
   red[grp][cl] = sum;
   __syncthreads();
-  if (!row_ok || q0 != 0) return;
-  float tot[4] = {0.f, 0.f, 0.f, 0.f};
-  for (int k = 0; k < rg; ++k) {
-    const float4 v = red[grp + k][cl];
-    tot[0] += v.x; tot[1] += v.y; tot[2] += v.z; tot[3] += v.w;
-  }
-  const float gam = P.gamma ? P.gamma[o] : 1.f;
+  const bool owner = row_ok && q0 == 0;  // this group of 32 lanes finishes row o
   float dg = 0.f;
-#pragma unroll
-  for (int e = 0; e < 4; ++e)
-    if (c + e < P.Ncol) {
-      P.G[row + c + e] += gam * tot[e];
-      if (P.wplain) dg += tot[e] * E::to_f32(static_cast<const T*>(P.wplain)[row + c + e]);
+  if (owner) {
+    float tot[4] = {0.f, 0.f, 0.f, 0.f};
+    for (int k = 0; k < rg; ++k) {
+      const float4 v = red[grp + k][cl];
+      tot[0] += v.x; tot[1] += v.y; tot[2] += v.z; tot[3] += v.w;
     }
-  if (P.Ggamma) {  // the 32 lanes of this group (shuffles stay inside a half wavefront)
+    const float gam = P.gamma ? P.gamma[o] : 1.f;
 #pragma unroll
-    for (int off = 16; off >= 1; off >>= 1) dg += __shfl_xor(dg, off, 64);
-    if (cl == 0) atomicAdd(P.Ggamma + o, dg);
+    for (int e = 0; e < 4; ++e)
+      if (c + e < P.Ncol) {
+        P.G[row + c + e] += gam * tot[e];
+        if (P.wplain) dg += tot[e] * E::to_f32(static_cast<const T*>(P.wplain)[row + c + e]);
+      }
+    if (c0 == 0 && P.Gbeta) {
+      float sb = 0.f;
+      for (int q = cl; q < P.splits; q += 32) sb += P.part_beta[(int64_t)q * P.Cout + o];
+#pragma unroll
+      for (int off = 16; off >= 1; off >>= 1) sb += __shfl_xor(sb, off, 64);
+      if (cl == 0) P.Gbeta[o] += sb;
+    }
   }
-  if (c0 == 0 && P.Gbeta) {
-    float sb = 0.f;
-    for (int q = cl; q < P.splits; q += 32) sb += P.part_beta[(int64_t)q * P.Cout + o];
+  if (!P.Ggamma) return;  // uniform over the workgroup
+  // the 32 lanes of a group (shuffles stay inside a half wavefront; lanes of other groups carry zeros)
 #pragma unroll
-    for (int off = 16; off >= 1; off >>= 1) sb += __shfl_xor(sb, off, 64);
-    if (cl == 0) P.Gbeta[o] += sb;
+  for (int off = 16; off >= 1; off >>= 1) dg += __shfl_xor(dg, off, 64);
+  const int chunk = c0 >> 7;
+  if (chunks == 1) {
+    if (owner && cl == 0) P.Ggamma[o] += dg;
+    return;
+  }
+  if (!P.gpart || !P.cnt) {
+    if (owner && cl == 0) atomicAdd(P.Ggamma + o, dg);
+    return;
+  }
+  // share of this chunk -> workspace; the last workgroup of the row block to get here adds the shares of
+  // every row of the block in chunk order.  Shares and counter are device-scope atomics ordered by waiting
+  // for the stores' acknowledgement before the barrier (as in the split contraction tiles).
+  if (owner && cl == 0) __hip_atomic_store(P.gpart + (int64_t)o * chunks + chunk, dg, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+  __syncthreads();
+  __shared__ int last;
+  if (threadIdx.x == 0) {
+    const unsigned int arrived = atomicAdd(P.cnt + ob, 1u);
+    last = arrived == (unsigned)(chunks - 1);
+    if (last) atomicExch(P.cnt + ob, 0u);  // ready for the next launch
+  }
+  __syncthreads();
+  if (!last) return;
+  if ((int)threadIdx.x < rows_per_wg) {
+    const int orow = ob * rows_per_wg + (int)threadIdx.x;
+    if (orow < P.Cout) {
+      float total = 0.f;
+      for (int k = 0; k < chunks; ++k)
+        total += __hip_atomic_load(P.gpart + (int64_t)orow * chunks + k, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      P.Ggamma[orow] += total;
+    }
   }
 }
 
@@ -612,6 +646,7 @@ hipError_t launch_wgrad_reduce(WReduceBatch& b, int dtype, hipStream_t stream) {
   for (int i = 0; i < b.n; ++i) {
     WReduceProb& p = b.p[i];
     if (p.Cout <= 0 || p.Ncol <= 0 || p.splits <= 0) return hipErrorInvalidValue;
+    if ((p.gpart == nullptr) != (p.cnt == nullptr)) return hipErrorInvalidValue;
     p.rg = p.splits <= 8 ? 1 : p.splits <= 16 ? 2 : p.splits <= 32 ? 4 : 8;
     const int rows_per_wg = 8 / p.rg;
     p.tile_begin = (int)total;

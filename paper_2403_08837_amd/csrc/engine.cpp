@@ -115,7 +115,7 @@ struct cdp_ctx {
   char* arena = nullptr;
   int64_t arena_bytes = 0;
   std::vector<StageState> st;
-  int64_t labels_off = 0, loss_off = 0, thin_ws_off = 0, conv_ws_off = -1;
+  int64_t labels_off = 0, loss_off = 0, thin_ws_off = 0, conv_ws_off = -1, fold_cnt_off = -1;
   Pool pool;
   int64_t scratch_base = 0, scratch_cap = -1, scratch_bump = 0;  // per-tick workspace (im2col buffers, partial sums)
   std::vector<std::vector<VisitRecord>> rec;  // [mb][stage]
@@ -189,7 +189,7 @@ bool scratch_alloc(cdp_ctx* c, int64_t bytes, Block* b) {
 // --------------------------------------------------------------------------- layouts
 struct StaticLayout {
   std::vector<StageState> st;
-  int64_t labels_off, loss_off, thin_ws_off, conv_ws_off, pool_base, weight_bytes;
+  int64_t labels_off, loss_off, thin_ws_off, conv_ws_off, fold_cnt_off, pool_base, weight_bytes;
 };
 
 StaticLayout static_layout(const ModelPlan& plan, int N, int B, int groups, bool velocity) {
@@ -213,7 +213,11 @@ StaticLayout static_layout(const ModelPlan& plan, int N, int B, int groups, bool
   for (const StagePlan& sp : plan.stages)
     for (const Op& o : sp.ops)
       if (o.kind == OPK_GEMM && o.is_conv) L.conv_ws_off = 0;
-  if (L.conv_ws_off == 0) { L.conv_ws_off = off; off = align_up(off + CONV_SPLIT_WS_BYTES + CONV_SPLIT_SLOTS * 4, 256); }
+  L.fold_cnt_off = -1;
+  if (L.conv_ws_off == 0) {
+    L.conv_ws_off = off; off = align_up(off + CONV_SPLIT_WS_BYTES + CONV_SPLIT_SLOTS * 4, 256);
+    L.fold_cnt_off = off; off = align_up(off + (int64_t)FOLD_COUNTERS * 4, 256);  // zeroed at init, left zero by every fold launch
+  }
   L.pool_base = off;
   return L;
 }
@@ -566,6 +570,13 @@ int build_backward(cdp_ctx* c, int i, int j, int version, Program* prog, bool fi
         rd.r.G = G + o.w_off; rd.r.Ggamma = o.has_gamma ? G + o.g_off : nullptr; rd.r.Gbeta = o.b_off >= 0 ? G + o.b_off : nullptr;
         rd.r.gamma = static_cast<const float*>(w.g.aux0); rd.r.wplain = w.g.aux1;
         rd.r.Cout = o.Cout; rd.r.Ncol = (int)o.K(); rd.r.splits = w.g.splits;
+        rd.r.gpart = nullptr; rd.r.cnt = nullptr;
+        const int chunks = ((int)o.K() + 127) / 128;
+        if (o.has_gamma && chunks > 1) {  // shares of d gamma per 128-column chunk, added in chunk order by the fold
+          Block gp;
+          if (!scratch_alloc(c, (int64_t)o.Cout * chunks * 4, &gp)) return fail(c, CDP_ENOMEM, "tick workspace exhausted");
+          rd.r.gpart = c->fptr(gp.off);
+        }
         w.g.out = part; w.g.aux0 = nullptr; w.g.aux1 = nullptr; w.g.aux2 = nullptr;
         w.g.aux3 = o.b_off >= 0 ? part + wn : nullptr;
         at(wl + 1).push_back(rd);
@@ -767,6 +778,19 @@ int launch_level(cdp_ctx* c, std::vector<Item>& items) {
       // no algorithmic work of its own: the accumulator's read-modify-write is already counted with the
       // weight-gradient contraction, the partial sums are this implementation's traffic
       HIP_TRY(c, hipEventRecord(pr.a, c->stream));
+    }
+    {
+      // one counter per block of rows of every problem that orders its d gamma shares
+      int64_t used = 0;
+      unsigned int* base = c->fold_cnt_off >= 0 ? reinterpret_cast<unsigned int*>(c->ptr(c->fold_cnt_off)) : nullptr;
+      for (int q = 0; q < rb.n; ++q) {
+        WReduceProb& r = rb.p[q];
+        if (!r.gpart) continue;
+        const int rg = r.splits <= 8 ? 1 : r.splits <= 16 ? 2 : r.splits <= 32 ? 4 : 8;  // as launch_wgrad_reduce
+        const int blocks = (r.Cout + 8 / rg - 1) / (8 / rg);
+        if (base && used + blocks <= FOLD_COUNTERS) { r.cnt = base + used; used += blocks; }
+        else r.gpart = nullptr;  // no counters left: the shares meet in atomic adds
+      }
     }
     HIP_TRY(c, launch_wgrad_reduce(rb, c->plan.dtype, c->stream));
     if (timed) {
@@ -1124,7 +1148,7 @@ int make_ctx(cdp_ctx** out, const cdp_stage_desc* stages, int n_stages, int N, i
   c->momentum = opts->momentum; c->weight_decay = opts->weight_decay;
   StaticLayout L = static_layout(c->plan, N, B, c->groups, c->momentum != 0.f);
   c->st = L.st;
-  c->labels_off = L.labels_off; c->loss_off = L.loss_off; c->thin_ws_off = L.thin_ws_off; c->conv_ws_off = L.conv_ws_off;
+  c->labels_off = L.labels_off; c->loss_off = L.loss_off; c->thin_ws_off = L.thin_ws_off; c->conv_ws_off = L.conv_ws_off; c->fold_cnt_off = L.fold_cnt_off;
   c->pool.base = L.pool_base;
   c->pool.cap = c->dry ? -1 : c->arena_bytes - L.pool_base;
   c->rec.assign(N, std::vector<VisitRecord>(n_stages));
@@ -1319,7 +1343,9 @@ int cdp_get_losses(cdp_ctx* c, int64_t step, float* host, size_t cap) {
   if (c->heads_done[step % LOSS_LOG_STEPS] < c->N) return fail(c, CDP_ESTATE, "not every micro-batch of that step has reached the head yet");
   if (c->dry) return fail(c, CDP_ESTATE, "no losses in a dry run");
   HIP_TRY(c, hipStreamSynchronize(c->stream));
-  HIP_TRY(c, hipMemcpy(host, c->fptr(c->loss_off) + (step % LOSS_LOG_STEPS) * n_loss, n_loss * 4, hipMemcpyDeviceToHost));
+  std::vector<int32_t> fixed(n_loss);  // the slots hold fixed-point sums (LOSS_SCALE)
+  HIP_TRY(c, hipMemcpy(fixed.data(), c->fptr(c->loss_off) + (step % LOSS_LOG_STEPS) * n_loss, n_loss * 4, hipMemcpyDeviceToHost));
+  for (size_t k = 0; k < n_loss; ++k) host[k] = (float)((double)fixed[k] / (double)LOSS_SCALE);
   return CDP_OK;
 }
 

@@ -162,7 +162,14 @@ struct WReduceProb {
   int Cout, Ncol, splits;
   int tile_begin;  // first workgroup of this problem in the launch (set by launch_wgrad_reduce)
   int rg;          // groups of 32 lanes that share one weight row (set by launch_wgrad_reduce)
+  // d gamma of a row is a sum over the row's 128-column chunks, which different workgroups hold.  With gpart
+  // (f32 [Cout][chunks]) and cnt (one zeroed counter per block of rows, left zero by the launch) the chunks'
+  // shares are written there and the last workgroup of a row block adds them in chunk order (one writer per
+  // row, fixed order); without them (or with one chunk) the shares meet in a float atomic add / a plain add.
+  float* gpart;
+  unsigned int* cnt;
 };
+constexpr int FOLD_COUNTERS = 1 << 16;  // counters the engine keeps for the fold launches
 constexpr int WREDUCE_MAX_PROBS = 32;
 struct WReduceBatch { int n; WReduceProb p[WREDUCE_MAX_PROBS]; };
 hipError_t launch_wgrad_reduce(WReduceBatch& b, int dtype, hipStream_t stream);
@@ -175,9 +182,14 @@ hipError_t launch_wgrad_reduce(WReduceBatch& b, int dtype, hipStream_t stream);
 hipError_t launch_stage_input(const float* x, const int32_t* y, void* x_out, int32_t* y_out, float* loss_slot, int n_slots,
                               int rows, int64_t per_row, int dtype, hipStream_t stream);
 
+// Loss slots hold the micro-batch objective as a 32-bit fixed-point number (units of 1 / LOSS_SCALE): every
+// row adds round(loss_row / rows_per_slot * LOSS_SCALE) with an integer atomic, so the sum does not depend
+// on the order in which the rows arrive (a float atomic add would).  Range +-512, resolution 2.4e-7.
+constexpr float LOSS_SCALE = 4194304.0f;  // 2^22
+
 // Softmax cross-entropy of one batch: logits f32 [B][C] -> dlogits = (softmax - onehot)/B as
 // T [B][C]; the mean loss of every group of rows_per_slot consecutive rows (a divisor of B) is
-// added to loss_out[group] (zeroed by the staging kernel).
+// added to loss_out[group] (zeroed by the staging kernel) in the fixed-point form above.
 hipError_t launch_ce_head(const float* logits, const int32_t* labels, void* dlogits, float* loss_out,
                           int B, int C, int rows_per_slot, int dtype, hipStream_t stream);
 

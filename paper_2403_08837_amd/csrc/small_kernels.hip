@@ -77,7 +77,8 @@ __global__ __launch_bounds__(256) void ce_head_kernel(const float* __restrict__ 
     float p = expf(z[c] - m) * inv;
     st_f32<T>(dlogits, (int64_t)row * C + c, (p - (c == y ? 1.f : 0.f)) * invB);
   }
-  if (lane == 0) atomicAdd(loss_out + row / rows_per_slot, ((m + logf(s)) - z[y]) / (float)rows_per_slot);
+  if (lane == 0)
+    atomicAdd(reinterpret_cast<int*>(loss_out) + row / rows_per_slot, __float2int_rn(((m + logf(s)) - z[y]) / (float)rows_per_slot * LOSS_SCALE));
 }
 
 hipError_t launch_ce_head(const float* logits, const int32_t* labels, void* dlogits, float* loss_out, int B, int C,
