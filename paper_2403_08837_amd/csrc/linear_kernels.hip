@@ -172,9 +172,19 @@ __device__ __forceinline__ void skinny_tile(const GemmBatch& batch, const GemmPr
   const int sb = split * per, nslab = max(0, min(nslab_all, sb + per) - sb);
   const int s0 = nslab > 0 ? (int)(((unsigned)tile * 2654435761u) >> 8) % nslab : 0;  // per-workgroup starting slab
   auto slab_k = [&](int i) { const int q = s0 + i; return (sb + (q >= nslab ? q - nslab : q)) * BK; };
+  // An interior tile of whole chunks (every row of both operand blocks exists, K is whole slabs) loads without
+  // a branch per chunk: guarded loads sit in basic blocks of their own and the compiler then waits for each.
+  const bool clean = vec && !a_f32 && row0 + BM <= P.M && col0 + BN <= P.N && (P.K % BK) == 0;
+  auto fetch_clean = [&](uint4* qa, uint4* qb, int k0) {
+#pragma unroll
+    for (int i = 0; i < NA; ++i) qa[i] = *reinterpret_cast<const uint4*>(Ap + offA[i] + k0);
+#pragma unroll
+    for (int i = 0; i < NB; ++i) qb[i] = *reinterpret_cast<const uint4*>(Bp + offB[i] + k0);
+  };
+  auto k_loop = [&](auto&& fetch_fn) {
 #pragma unroll
   for (int d = 0; d < DEPTH; ++d)
-    if (d < nslab) fetch(ra[d], rb[d], slab_k(d));
+    if (d < nslab) fetch_fn(ra[d], rb[d], slab_k(d));
   for (int it0 = 0; it0 < nslab; it0 += DEPTH)
 #pragma unroll
   for (int d = 0; d < DEPTH; ++d) {
@@ -186,7 +196,7 @@ __device__ __forceinline__ void skinny_tile(const GemmBatch& batch, const GemmPr
 #pragma unroll
     for (int i = 0; i < NB; ++i) *reinterpret_cast<uint4*>(Bs + (crow + 16 * i) * LDP + ck) = rb[d][i];
     __syncthreads();
-    if (it + DEPTH < nslab) fetch(ra[d], rb[d], slab_k(it + DEPTH));
+    if (it + DEPTH < nslab) fetch_fn(ra[d], rb[d], slab_k(it + DEPTH));
     const int kg = (lane >> 5) * E::KPL;
     const T* ap = As + (wm * 32 + (lane & 31)) * LDP + kg;
     const T* bp = Bs + (wn * (BN / 2) + (lane & 31)) * LDP + kg;
@@ -203,6 +213,10 @@ __device__ __forceinline__ void skinny_tile(const GemmBatch& batch, const GemmPr
       }
     }
   }
+
+  };
+  if (clean) k_loop(fetch_clean);
+  else k_loop(fetch);
 
   if constexpr (SPLIT) {
     if (ks > 1) {
