@@ -55,13 +55,13 @@ def measured_traffic(workload):
     return None
 
 
-def gpu_run(cfg, rule, steps, warmup, n_batches=4, dp_batched=False, reps=1):
+def gpu_run(cfg, rule, steps, warmup, n_batches=4, dp_batched=False, reps=1, dw_group=1):
     import torch
     from paper_2403_08837_amd import binding as b
 
     if not torch.cuda.is_available():
         raise SystemExit("bench.py needs a GPU; libcdp has no CPU path")
-    tr = b.Trainer(cfg.stages, cfg.in_shape, cfg.N, cfg.B, cfg.lr, rule, cfg.dtype, dp_batched=dp_batched)
+    tr = b.Trainer(cfg.stages, cfg.in_shape, cfg.N, cfg.B, cfg.lr, rule, cfg.dtype, dp_batched=dp_batched, dw_group=dw_group)
     tr.set_weights(wl.init_params(cfg, 0))
     data = []
     for t in range(n_batches):
@@ -145,9 +145,9 @@ def cpu_baseline(cfg, rule, budget_s=15.0, threads=None):
                       % (steps, cfg.name, total)}
 
 
-def run_workload(name, rule, steps, warmup, n_batches=4, dp_batched=False, reps=1):
+def run_workload(name, rule, steps, warmup, n_batches=4, dp_batched=False, reps=1, dw_group=1):
     cfg = wl.get_config(name)
-    r = gpu_run(cfg, rule, steps, warmup, n_batches, dp_batched, reps)
+    r = gpu_run(cfg, rule, steps, warmup, n_batches, dp_batched, reps, dw_group)
     samples = cfg.N * cfg.B * steps
     prof = r["prof"]
     # event-to-event times minus what an empty event pair reads: the kernels' own durations
@@ -190,7 +190,8 @@ def run_workload(name, rule, steps, warmup, n_batches=4, dp_batched=False, reps=
         "data": "synthetic",
         "config": {"workload": "%s: %s" % (name, WORKLOAD_TEXT[name]),
                    "rule": wl.RULE_NAMES[rule] + ("_batched" if dp_batched else ""),
-                   "S": cfg.S, "N": cfg.N, "B": cfg.B, "delay_ticks": cfg.delay if rule != wl.RULE_DP else 0},
+                   "S": cfg.S, "N": cfg.N, "B": cfg.B, "delay_ticks": cfg.delay if rule != wl.RULE_DP else 0,
+                   "dw_group": dw_group},
         "gpu_ms_per_step": r["gpu_ms"] / steps,
         "repetitions": {"n": reps, "ms_per_step": [w * 1e3 / steps for w in r["walls"]], "reported": "median"},
         "activation_bytes_per_tick": r["act"],
@@ -213,6 +214,15 @@ def lockstep_summary(name, steps):
             "peak_activation_bytes": w["peak_activation_bytes"], "peak_live_stage_inputs": w["peak_live_stage_inputs"]}
 
 
+def grouped_summary(name, rule, steps, g):
+    """The same workload with the weight gradients of g consecutive micro-batches of a stage taken in one
+    pass over the accumulator (cdp_opts.dw_group): a g-th of the accumulator traffic, paid in activation memory."""
+    w = run_workload(name, rule, steps, 3, n_batches=2, reps=3, dw_group=g)
+    return {"value": w["value"], "unit": w["unit"], "ms_per_step": w["ms_per_step"], "steps": steps,
+            "peak_activation_bytes": w["peak_activation_bytes"], "activation_bytes_per_tick": w["activation_bytes_per_tick"],
+            "roofline_frac": w["roofline"]["frac"], "algorithmic_bytes_per_launch": w["roofline"]["algorithmic_bytes_per_launch"]}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -229,6 +239,10 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--also", default="cfg4,cfg2",
                     help="comma-separated further workloads summarised under \"workloads\" (short runs); empty for none")
+    ap.add_argument("--dw-group", type=int, default=1,
+                    help="weight gradients of this many consecutive micro-batches of a stage in one accumulator pass (Linear layers)")
+    ap.add_argument("--no-dw-group-rows", action="store_true",
+                    help="skip the short dw_group = 2 / 4 runs of the headline workload reported under \"dw_group_rows\"")
     ap.add_argument("--calib-copy", action="store_true",
                     help="also run one plain 1 GiB device copy (reference for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE)")
     args = ap.parse_args()
@@ -248,7 +262,7 @@ def main():
         dst.copy_(src)
         torch.cuda.synchronize()
         del src, dst
-    out = run_workload(args.workload, rule, steps, warmup, dp_batched=batched, reps=max(1, args.reps))
+    out = run_workload(args.workload, rule, steps, warmup, dp_batched=batched, reps=max(1, args.reps), dw_group=args.dw_group)
     if args.also:
         out["workloads"] = {}
         for name in args.also.split(","):
@@ -263,6 +277,8 @@ def main():
                     out["workloads"][name]["lockstep_dp"] = lockstep_summary(name, short)
     if not args.no_dp_baseline and not batched:
         out["lockstep_dp"] = lockstep_summary(args.workload, max(2, steps // 4))
+    if not args.no_dw_group_rows and not batched and rule != wl.RULE_DP and args.dw_group == 1 and args.workload in ("cfg1", "cfg2", "cfg5"):
+        out["dw_group_rows"] = {str(g): grouped_summary(args.workload, rule, max(2, steps // 2), g) for g in (2, 4) if cfg.N % g == 0}
     # The stated target of the build: the grouped contraction of a tick at >= 50 % of the bf16 MFMA peak.  The
     # Linear workloads sit far below the MFMA / HBM ridge (arithmetic intensity ~ micro-batch rows), so for
     # them the HBM fraction is the bound; the convolution workload is where the MFMA fraction is meaningful.

@@ -114,6 +114,12 @@ typedef struct {
                           alludes to: no second copy of the parameters needed).  The applied gradient is
                           then not the gradient of f_i at one point.  The trace records the version the
                           backward read.  Not combined with dp_batched.                              */
+  int32_t dw_group;    /* 0 or 1: every backward pass adds its weight gradient to the stage accumulator (Eq. (CDP),
+                          sum over i).  g = 2..4 (a divisor of N, cyclic rules): the Linear layers keep (dY, X) of g
+                          consecutive micro-batches of a stage and take ONE pass over the accumulator per group -
+                          the same sum in the same order i = 0..N-1, a g-th of the accumulator traffic, paid with
+                          the activations of up to g-1 finished backward passes per stage staying in the pool (they
+                          show in peak_activation_bytes and cdp_get_live_bytes).  Convolution layers are not grouped. */
 } cdp_opts;
 
 /* One executed (micro-batch, stage) pass. */

@@ -37,7 +37,7 @@ class cdp_opts(C.Structure):
     _fields_ = [("dtype", C.c_int32), ("dry_run", C.c_int32), ("in_rank", C.c_int32), ("in_dims", C.c_int32 * 3),
                 ("hip_stream", C.c_void_p), ("arena", C.c_void_p), ("arena_bytes", C.c_size_t),
                 ("momentum", C.c_float), ("weight_decay", C.c_float), ("dp_batched", C.c_int32),
-                ("fresh_mask", C.c_void_p), ("bwd_fresh", C.c_int32)]
+                ("fresh_mask", C.c_void_p), ("bwd_fresh", C.c_int32), ("dw_group", C.c_int32)]
 
 
 class cdp_trace_rec(C.Structure):
@@ -128,7 +128,7 @@ def marshal_stages(stages: Sequence[Sequence[object]]):
 
 def make_opts(dtype: int, in_shape: Sequence[int], dry_run: bool = False, stream: int = 0, arena: int = 0,
               arena_bytes: int = 0, momentum: float = 0.0, weight_decay: float = 0.0,
-              dp_batched: bool = False, fresh_mask=None, bwd_fresh: bool = False) -> cdp_opts:
+              dp_batched: bool = False, fresh_mask=None, bwd_fresh: bool = False, dw_group: int = 1) -> cdp_opts:
     o = cdp_opts()
     o.dtype, o.dry_run, o.in_rank = int(dtype), int(bool(dry_run)), len(in_shape)
     for k, v in enumerate(in_shape):
@@ -137,6 +137,7 @@ def make_opts(dtype: int, in_shape: Sequence[int], dry_run: bool = False, stream
     o.momentum, o.weight_decay = float(momentum), float(weight_decay)
     o.dp_batched = int(bool(dp_batched))
     o.bwd_fresh = int(bool(bwd_fresh))
+    o.dw_group = int(dw_group)
     if fresh_mask is not None:
         m = np.ascontiguousarray(np.asarray(fresh_mask) != 0, dtype=np.uint8)
         o._mask_keepalive = m           # the library copies it during cdp_init
@@ -290,14 +291,14 @@ class Trainer:
 
     def __init__(self, stages, in_shape, N: int, B: int, lr: float, rule: int, dtype: int, dry_run: bool = False,
                  device: str = "cuda:0", momentum: float = 0.0, weight_decay: float = 0.0, dp_batched: bool = False,
-                 fresh_mask=None, bwd_fresh: bool = False):
+                 fresh_mask=None, bwd_fresh: bool = False, dw_group: int = 1):
         self.N, self.B, self.S = N, B, len(stages)
         self.ctx = None
         self._arena = None
         if fresh_mask is not None and np.asarray(fresh_mask).shape != (N, len(stages)):
             raise ValueError("fresh_mask must have shape (N, S)")
         opts = make_opts(dtype, in_shape, dry_run=dry_run, momentum=momentum, weight_decay=weight_decay,
-                         dp_batched=dp_batched, fresh_mask=fresh_mask, bwd_fresh=bwd_fresh)
+                         dp_batched=dp_batched, fresh_mask=fresh_mask, bwd_fresh=bwd_fresh, dw_group=dw_group)
         if not dry_run:
             import torch
             if not torch.cuda.is_available():
@@ -308,7 +309,7 @@ class Trainer:
             stream = torch.cuda.current_stream(self._arena.device).cuda_stream
             opts = make_opts(dtype, in_shape, stream=stream, arena=base, arena_bytes=need, momentum=momentum,
                              weight_decay=weight_decay, dp_batched=dp_batched, fresh_mask=fresh_mask,
-                             bwd_fresh=bwd_fresh)
+                             bwd_fresh=bwd_fresh, dw_group=dw_group)
             self.arena_bytes = need
         self.ctx = cdp_init(stages, N, B, lr, rule, opts)
 

@@ -107,6 +107,11 @@ struct cdp_ctx {
   int S = 0, N = 0, B = 0, d = 0, rule = 0;
   std::vector<uint8_t> fresh_mask;  // CDP_RULE_MASK: [micro-batch][stage]
   bool bwd_fresh = false;           // backward reads the freshest version
+  int dw_group = 1;                 // micro-batches per pass over a Linear accumulator (cdp_opts.dw_group)
+  // weight gradients deferred until their group is complete: per stage, the (dY, X) pointers of every Linear
+  // layer of the passes waiting, and the blocks those passes would have released
+  struct PendingPass { std::vector<std::pair<const void*, const void*>> ops; std::vector<Block> held; };
+  std::vector<std::vector<PendingPass>> pending;  // [stage][waiting passes]
   double empty_pair_ms = 0.0;       // event-to-event time of an empty bracket (cdp_profile_gemm)
   int groups = 1;  // lock-step batched DP: the caller's micro-batches run as one batch of groups * (caller's B) rows (then N = 1)
   float lr = 0.f, momentum = 0.f, weight_decay = 0.f;
@@ -341,7 +346,8 @@ enum LaunchClass {
 int launch_class(const GemmProb& p, int dtype) {
   (void)dtype;
   if (p.epi != EPI_WGRAD && p.a_mode == OP_PLAIN_K && p.b_mode == OP_PLAIN_K && p.M <= 128) return LC_LINEAR;
-  if (p.epi == EPI_WGRAD && p.a_mode == OP_PLAIN_R && p.b_mode == OP_PLAIN_R && !(p.flags & GF_ATOMIC) && !p.aux0 && !p.aux1)
+  if (p.epi == EPI_WGRAD && p.a_mode == OP_PLAIN_R && p.b_mode == OP_PLAIN_R && !(p.flags & GF_ATOMIC) &&
+      ((p.flags & GF_GROUP) || (!p.aux0 && !p.aux1)))
     return LC_LINEAR;
   if (conv_fast_eligible(p, dtype)) {
     if (p.epi == EPI_WGRAD) return p.M >= 128 ? LC_CWGRAD_128 : LC_CWGRAD_64;
@@ -491,6 +497,14 @@ int build_backward(cdp_ctx* c, int i, int j, int version, Program* prog, bool fi
     if (!incoming.valid()) return fail(c, CDP_ESTATE, "missing upstream gradient");
     g[last] = c->ptr(incoming.off);
   }
+  // Deferred weight gradients (dw_group > 1): the Linear layers of this pass only note their (dY, X) until the
+  // group is complete (or the step's last gradient arrives); the completing pass contracts all members in one
+  // pass over the accumulator, members in arrival order.
+  const int waiting = (int)c->pending[j].size();
+  const bool grouping = c->dw_group > 1;
+  const bool flush = !grouping || waiting + 1 == c->dw_group || ss.cnt == c->N - 1;
+  cdp_ctx::PendingPass mine;
+  size_t lin_idx = 0;
   size_t level = 0;
   auto at = [&](size_t l) -> std::vector<Item>& { if (prog->size() <= l) prog->resize(l + 1); return (*prog)[l]; };
   for (int oi = (int)sp.ops.size() - 1; oi >= 0; --oi) {
@@ -539,8 +553,27 @@ int build_backward(cdp_ctx* c, int i, int j, int version, Program* prog, bool fi
         w_src = c->ptr(col.off);
         wl = level + 1;
       }
-      w.g = wgrad_prob(c, o, dz, w_src, slot, slot_f, G, first_grad);
-      op_work(c, o, 2, o.is_conv || !first_grad, false, &w);
+      const bool groupable = grouping && linear_update_fusable(o);
+      if (groupable && !flush) {  // noted; contracted by the pass that completes the group
+        mine.ops.push_back({dz, w_src});
+        ++lin_idx;
+        ++level;
+        continue;
+      }
+      const bool first_of_step = groupable ? (ss.cnt - waiting == 0) : first_grad;
+      w.g = wgrad_prob(c, o, dz, w_src, slot, slot_f, G, first_of_step);
+      op_work(c, o, 2, o.is_conv || !first_of_step, false, &w);
+      if (groupable && waiting > 0) {
+        const int rows = c->B;
+        for (int m = 0; m < waiting; ++m) dw_set_member(w.g, m, c->pending[j][m].ops[lin_idx].first, c->pending[j][m].ops[lin_idx].second);
+        dw_set_member(w.g, waiting, dz, w_src);
+        w.g.flags |= GF_GROUP;
+        w.g.g.pad = rows;
+        w.g.K = (waiting + 1) * rows;
+        w.flops *= (waiting + 1);
+        w.bytes += (double)waiting * rows * (o.Cin + o.Cout) * c->plan.elem_bytes;
+      }
+      if (groupable) ++lin_idx;
       if (fuse_update && linear_update_fusable(o)) {
         // this gradient is the N-th of the step: its contraction also takes the SGD step and
         // writes the new version into the other ring slot (which no pass of this tick reads)
@@ -643,14 +676,22 @@ int build_backward(cdp_ctx* c, int i, int j, int version, Program* prog, bool fi
     ++level;
   }
   // release everything the pass held; the gradient of the stage input travels on
+  // (a pass whose weight gradients wait for their group keeps what it would release: dY and X are in there)
+  std::vector<Block>& sink = flush ? c->deferred : mine.held;
   for (int k = 0; k < nt; ++k) {
-    if (r.t[k].valid()) c->deferred.push_back(r.t[k]);
+    if (r.t[k].valid()) sink.push_back(r.t[k]);
     if (owned[k].valid()) {
       if (k == 0 && j > 0) c->carry[i] = owned[k];
-      else c->deferred.push_back(owned[k]);
+      else sink.push_back(owned[k]);
     }
   }
-  if (incoming.valid()) c->deferred.push_back(incoming);
+  if (incoming.valid()) sink.push_back(incoming);
+  if (!flush) {
+    c->pending[j].push_back(std::move(mine));
+  } else if (waiting > 0) {
+    for (auto& pp : c->pending[j]) c->deferred.insert(c->deferred.end(), pp.held.begin(), pp.held.end());
+    c->pending[j].clear();
+  }
   r.live = false;
   r.t.clear();
   return CDP_OK;
@@ -991,6 +1032,9 @@ int run_tick(cdp_ctx* c, const float* x_dev, const int32_t* y_dev) {
     for (int j = 0; j < S; ++j)
       if (c->rec[i][j].live)
         for (const Block& b : c->rec[i][j].t) retained += b.valid() ? b.bytes : 0;
+  for (int j = 0; j < S; ++j)  // passes whose weight gradients wait for their group (dw_group > 1)
+    for (const auto& pp : c->pending[j])
+      for (const Block& b : pp.held) retained += b.bytes;
   c->weights_locked = c->weights_locked || !act.empty();
 
   // weight version of every pass: forward by the update rule, backward as its own forward
@@ -1118,6 +1162,8 @@ int check_args(const cdp_stage_desc* stages, int n_stages, int N, int B, int rul
     return fail(nullptr, CDP_EINVAL, "momentum must be in [0, 1) and weight_decay >= 0");
   if (opts->dp_batched && rule != CDP_RULE_DP) return fail(nullptr, CDP_EINVAL, "dp_batched needs CDP_RULE_DP");
   if (opts->dp_batched && N > 256) return fail(nullptr, CDP_EINVAL, "dp_batched supports at most 256 micro-batches");
+  if (opts->dw_group < 0 || opts->dw_group > DW_GROUP_MAX || (opts->dw_group > 1 && (rule == CDP_RULE_DP || N % opts->dw_group != 0)))
+    return fail(nullptr, CDP_EINVAL, "dw_group must be 0 or 1 (off) or a divisor of N up to 4, with a cyclic rule");
   if ((int64_t)B * (opts->dp_batched ? N : 1) > 1024 && plan->stages.back().has_head)
     return fail(nullptr, CDP_EINVAL, "a head pass over more than 1024 rows is not supported");
   return CDP_OK;
@@ -1137,6 +1183,7 @@ int make_ctx(cdp_ctx** out, const cdp_stage_desc* stages, int n_stages, int N, i
   }
   if (rule == CDP_RULE_MASK) c->fresh_mask.assign(opts->fresh_mask, opts->fresh_mask + (size_t)N * n_stages);
   c->bwd_fresh = opts->bwd_fresh != 0;
+  c->dw_group = opts->dw_group > 1 ? opts->dw_group : 1;
   c->S = n_stages; c->N = N; c->B = B; c->rule = rule; c->lr = lr;
   c->d = rule == CDP_RULE_DP ? 0 : 2 * n_stages / N;
   c->dry = force_dry || opts->dry_run != 0;
@@ -1153,6 +1200,7 @@ int make_ctx(cdp_ctx** out, const cdp_stage_desc* stages, int n_stages, int N, i
   c->pool.cap = c->dry ? -1 : c->arena_bytes - L.pool_base;
   c->rec.assign(N, std::vector<VisitRecord>(n_stages));
   c->carry.assign(N, Block());
+  c->pending.assign(n_stages, {});
   c->heads_done.assign(LOSS_LOG_STEPS, 0);
   memset(&c->stats, 0, sizeof(c->stats));
   c->stats.weight_bytes = L.weight_bytes;

@@ -4,6 +4,7 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <cstddef>
 #include <string>
 
 namespace cdp {
@@ -59,11 +60,32 @@ struct GemmProb {
   int upd;           // linear_tick_kernel, WGRAD: 1 + index into GemmBatch::upd of a fused SGD step, 0 = none
   ConvGeom g;        // geometry of the (single) gathered operand, if any
 };
+static_assert(sizeof(ConvGeom) >= 36, "group pointers of a deferred weight gradient are kept in the geometry block");
+
+// Weight gradient of a Linear layer over a GROUP of micro-batches (GF_GROUP): G (+)= sum_m dY_m^T X_m in one
+// pass over the accumulator, members m = 0 .. nmem-1 (nmem <= DW_GROUP_MAX) of `rows` rows each.  Member 0 is
+// (A, B); the further members' (dY, X) pointers travel in fields a Linear weight gradient does not use:
+// (aux0, aux1), then four pointers laid over the geometry block; g.pad holds `rows`.  P.K = nmem * rows.
+constexpr int DW_GROUP_MAX = 4;
+struct DwGroupView { const void* p[4]; int rows; };
+static_assert(sizeof(DwGroupView) <= sizeof(ConvGeom) + 4 && offsetof(DwGroupView, rows) == offsetof(ConvGeom, pad), "layout of the overlay");
+__host__ __device__ inline const void* dw_member(const GemmProb& P, int m, int which /*0: dY, 1: X*/) {
+  if (m == 0) return which ? P.B : P.A;
+  if (m == 1) return which ? P.aux1 : P.aux0;
+  const void* const* q = reinterpret_cast<const void* const*>(&P.g);
+  return q[(m - 2) * 2 + which];
+}
+__host__ inline void dw_set_member(GemmProb& P, int m, const void* dy, const void* x) {
+  if (m == 0) { P.A = dy; P.B = x; }
+  else if (m == 1) { P.aux0 = dy; P.aux1 = x; }
+  else { const void** q = reinterpret_cast<const void**>(&P.g); q[(m - 2) * 2] = dy; q[(m - 2) * 2 + 1] = x; }
+}
 
 enum : int {
   GF_RELU = 1, GF_OUT_F32 = 2, GF_ACCUM = 4, GF_ATOMIC = 8,
   GF_THIN = 16,  // set by launch_linear_tick
   GF_A_F32 = 32, // linear_tick_kernel, forward: A holds fp32 values, rounded to the compute type on load
+  GF_GROUP = 128, // linear_tick_kernel, WGRAD: operands of several micro-batches (DwGroupView)
   GF_CE = 64     // linear_tick_kernel, thin forward tile with N <= 32 classes: softmax cross-entropy in the epilogue
                  // (out = dlogits T[M][N], aux2 = int32 labels, aux3 = loss slots, g.H = rows per loss slot)
 };

@@ -499,11 +499,16 @@ __device__ __forceinline__ void dw_tile(const GemmBatch& batch, const GemmProb& 
     for (int v = 0; v < 16; ++v) acc[i][v] = 0.f;
   float bsum = 0.f;  // bias gradient of column n0 + tid (threads 0..63 of the first column tile)
 
-  const T* __restrict__ Dp = static_cast<const T*>(P.A);
-  const T* __restrict__ Xp = static_cast<const T*>(P.B);
   const bool dvec = (P.lda % VEC) == 0, xvec = (P.ldb % VEC) == 0;
-  for (int m0 = 0; m0 < Mb; m0 += MB) {
-    if (m0 > 0) __syncthreads();
+  // the reduction runs over the rows of one micro-batch, or (GF_GROUP) of several micro-batches whose dY / X
+  // lie in buffers of their own
+  const bool grouped = (flags & GF_GROUP) != 0;
+  const int rows = grouped ? P.g.pad : Mb, nmem = grouped ? Mb / P.g.pad : 1;
+  for (int mem = 0; mem < nmem; ++mem) {
+  const T* __restrict__ Dp = static_cast<const T*>(dw_member(P, mem, 0));
+  const T* __restrict__ Xp = static_cast<const T*>(dw_member(P, mem, 1));
+  for (int m0 = 0; m0 < rows; m0 += MB) {
+    if (mem > 0 || m0 > 0) __syncthreads();
     // 2. stage dY[m0.., n0..n0+TN-1] and X[m0.., k0..k0+127] as they lie in memory.  All of a thread's chunks
     // are requested before the first one is written to LDS: requested one by one (load, LDS store, load, ...)
     // the six round trips to L2 of a bf16 tile cost 30 us of a 280 us launch of 16384 tiles.
@@ -515,13 +520,13 @@ __device__ __forceinline__ void dw_tile(const GemmBatch& batch, const GemmProb& 
 #pragma unroll
       for (int i = 0; i < ND; ++i) {
         const int id = tid + 256 * i, m = id / DCH, c = (id % DCH) * VEC;
-        rd[i] = (m0 + m < Mb && n0 + c < Nn) ? *reinterpret_cast<const uint4*>(Dp + (int64_t)(m0 + m) * P.lda + n0 + c)
+        rd[i] = (m0 + m < rows && n0 + c < Nn) ? *reinterpret_cast<const uint4*>(Dp + (int64_t)(m0 + m) * P.lda + n0 + c)
                                               : make_uint4(0, 0, 0, 0);
       }
 #pragma unroll
       for (int i = 0; i < NX; ++i) {
         const int id = tid + 256 * i, m = id / XCH, c = (id % XCH) * VEC;
-        rx[i] = (m0 + m < Mb && k0 + c < Kk) ? *reinterpret_cast<const uint4*>(Xp + (int64_t)(m0 + m) * P.ldb + k0 + c)
+        rx[i] = (m0 + m < rows && k0 + c < Kk) ? *reinterpret_cast<const uint4*>(Xp + (int64_t)(m0 + m) * P.ldb + k0 + c)
                                               : make_uint4(0, 0, 0, 0);
       }
 #pragma unroll
@@ -547,7 +552,7 @@ __device__ __forceinline__ void dw_tile(const GemmBatch& batch, const GemmProb& 
         const int m = id / DCH, c = (id % DCH) * VEC;
         Chunk16<T> tmp;
         tmp.v = make_uint4(0, 0, 0, 0);
-        if (m0 + m < Mb) {
+        if (m0 + m < rows) {
           const T* src = Dp + (int64_t)(m0 + m) * P.lda + n0 + c;
           if (dvec && n0 + c + VEC <= Nn) {
             tmp.v = *reinterpret_cast<const uint4*>(src);
@@ -565,7 +570,7 @@ __device__ __forceinline__ void dw_tile(const GemmBatch& batch, const GemmProb& 
         const int m = id / XCH, c = (id % XCH) * VEC;
         Chunk16<T> tmp;
         tmp.v = make_uint4(0, 0, 0, 0);
-        if (m0 + m < Mb) {
+        if (m0 + m < rows) {
           const T* src = Xp + (int64_t)(m0 + m) * P.ldb + k0 + c;
           if (xvec && k0 + c + VEC <= Kk) {
             tmp.v = *reinterpret_cast<const uint4*>(src);
@@ -602,6 +607,7 @@ __device__ __forceinline__ void dw_tile(const GemmBatch& batch, const GemmProb& 
     if (tk == 0 && P.aux2 != nullptr && tid < TN) {
       for (int m = 0; m < MB; ++m) bsum += E::to_f32(Ds[m * PD + tid]);
     }
+  }
   }
 
   if (!upd) {
@@ -708,7 +714,7 @@ constexpr int DW_RUN = 2;  // 2, 4 and 8 measured within 2 % of each other on 40
 // upd_ok: a problem with a fused SGD step may take this path (wide kernel, no momentum)
 __host__ __device__ __forceinline__ int dw_run_length(const GemmProb& p, int vec, bool upd_ok) {
   const bool whole = p.lda % vec == 0 && p.ldb % vec == 0 && p.M % vec == 0 && p.N % vec == 0;
-  return ((!p.upd || upd_ok) && whole && p.K <= 64 && p.N >= 8 * 128 && p.M >= 512) ? DW_RUN : 1;
+  return ((!p.upd || upd_ok) && whole && !(p.flags & GF_GROUP) && p.K <= 64 && p.N >= 8 * 128 && p.M >= 512) ? DW_RUN : 1;
 }
 
 template <typename T, bool UPD>
@@ -1009,7 +1015,9 @@ hipError_t launch_linear_tick(GemmBatch& b, int dtype, bool wide, bool allow_thi
     p.flags &= ~GF_THIN;
     int tiles;
     if (p.epi == EPI_WGRAD) {
-      if (p.a_mode != OP_PLAIN_R || p.b_mode != OP_PLAIN_R || (p.flags & GF_ATOMIC) || p.aux0 || p.aux1) return hipErrorInvalidValue;
+      const bool grouped = (p.flags & GF_GROUP) != 0;
+      if (p.a_mode != OP_PLAIN_R || p.b_mode != OP_PLAIN_R || (p.flags & GF_ATOMIC) || (!grouped && (p.aux0 || p.aux1))) return hipErrorInvalidValue;
+      if (grouped && (p.g.pad <= 0 || p.K % p.g.pad != 0 || p.K / p.g.pad > DW_GROUP_MAX)) return hipErrorInvalidValue;
       if (p.upd < 0 || p.upd > b.n_upd || b.n_upd > LIN_UPD_MAX) return hipErrorInvalidValue;
       if (p.upd) {
         const LinUpdate& u = b.upd[p.upd - 1];

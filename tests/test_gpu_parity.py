@@ -29,11 +29,12 @@ RULES = [wl.RULE_DP, wl.RULE_V1, wl.RULE_V2]
 
 
 def run_gpu(cfg, rule, T, p0, xs, ys, lr=None, momentum=0.0, weight_decay=0.0, dp_batched=False, mask=None, bwd_fresh=False,
-            dtype=None):
+            dtype=None, dw_group=1):
     import torch
     assert torch.cuda.is_available(), "GPU tests need a GPU"
     tr = b.Trainer(cfg.stages, cfg.in_shape, cfg.N, cfg.B, cfg.lr if lr is None else lr, rule, cfg.dtype if dtype is None else dtype,
-                   momentum=momentum, weight_decay=weight_decay, dp_batched=dp_batched, fresh_mask=mask, bwd_fresh=bwd_fresh)
+                   momentum=momentum, weight_decay=weight_decay, dp_batched=dp_batched, fresh_mask=mask, bwd_fresh=bwd_fresh,
+                   dw_group=dw_group)
     tr.set_weights(p0)
     keep = []
     for t in range(T):
@@ -65,7 +66,7 @@ def say(capfd, line):
 
 
 def check(cfg, rule, T, seed=0, lr=None, emulate=True, also_f32=False, capfd=None, momentum=0.0, weight_decay=0.0,
-          dp_batched=False, mask=None, bwd_fresh=False, full_size=False):
+          dp_batched=False, mask=None, bwd_fresh=False, full_size=False, dw_group=1):
     """One oracle run (fp64) against the library in the configuration's arithmetic; for bf16
     configurations the bf16-storage stand-in as yardstick (`emulate`) and optionally the library again
     in fp32 (`also_f32`).  full_size: benchmark-sized runs - the oracle legs run side by side in child
@@ -89,7 +90,7 @@ def check(cfg, rule, T, seed=0, lr=None, emulate=True, also_f32=False, capfd=Non
         if "bf16" in legs:
             emu["bf16"] = O.train_schedule(cfg, p0, xs, ys, rule, keep_versions=False, stage_impl=Bf16Storage, **kw).params
     t_ref = time.time() - t0
-    got = run_gpu(cfg, rule, T, p0, xs, ys, dp_batched=dp_batched, **kw)
+    got = run_gpu(cfg, rule, T, p0, xs, ys, dp_batched=dp_batched, dw_group=dw_group, **kw)
     assert got["trace"] == ref.trace
     assert got["live"] == ref.live_inputs
     assert np.isfinite(got["losses"]).all()
@@ -118,7 +119,7 @@ def check(cfg, rule, T, seed=0, lr=None, emulate=True, also_f32=False, capfd=Non
 
     judge(got, "fp32" if f32 else "bf16", not f32)
     if also_f32 and not f32:
-        g32 = run_gpu(cfg, rule, T, p0, xs, ys, dp_batched=dp_batched, dtype=wl.F32, **kw)
+        g32 = run_gpu(cfg, rule, T, p0, xs, ys, dp_batched=dp_batched, dtype=wl.F32, dw_group=dw_group, **kw)
         assert g32["trace"] == ref.trace and g32["live"] == ref.live_inputs
         judge(g32, "same shapes in fp32", False)
     assert not failures, failures
@@ -451,3 +452,28 @@ def test_two_runs_give_identical_bits(name):
     for wa, wb in zip(a["weights"], b2["weights"]):
         for x, y in zip(wa, wb):
             assert np.array_equal(x, y)
+
+
+@pytest.mark.parametrize("name,rule,g", [("cfg1", wl.RULE_V2, 2), ("cfg1", wl.RULE_V2, 4), ("cfg1", wl.RULE_V1, 2), ("mlp_odd", wl.RULE_V2, 2),
+                                         ("mlp_odd", wl.RULE_V2, 4), ("mlp_longk_b40", wl.RULE_V2, 4), ("cfg2_mini", wl.RULE_V2, 2),
+                                         ("cfg5_mini", wl.RULE_V2, 4), ("resnet18_mini_f32", wl.RULE_V2, 2)])
+def test_weight_gradients_of_a_group_of_micro_batches_in_one_pass(name, rule, g):
+    """dw_group = g: the Linear layers keep (dY, X) of g consecutive micro-batches of a stage and take one pass
+    over the accumulator per group.  The sum of Eq. (CDP) is the same, in the same order of micro-batches:
+    same trace, same live counts, weights and losses within the usual criteria; what changes is the memory:
+    finished backward passes keep their activations until the group is complete."""
+    cfg = wl.get_config(name)
+    got, _ = check(cfg, rule, cfg.steps, dw_group=g)
+    xs, ys = wl.make_data(cfg, cfg.steps)
+    base = run_gpu(cfg, rule, cfg.steps, wl.init_params(cfg), xs, ys)
+    linear_only = all(l.kind != wl.CONV2D for st in cfg.stages for l in st)
+    if linear_only:
+        assert got["stats"]["peak_activation_bytes"] > base["stats"]["peak_activation_bytes"]
+        assert max(got["live_bytes"]) > max(base["live_bytes"])
+
+
+def test_cfg5_grouped_weight_gradients_full_size(capfd):
+    """cfg5 with dw_group = 4: a quarter of the accumulator passes, at full size, 3 steps."""
+    cfg = wl.get_config("cfg5")
+    got, _ = check(cfg, wl.RULE_V2, 3, full_size=True, dw_group=4, capfd=capfd)
+    assert got["stats"]["peak_live_stage_inputs"] == 200

@@ -34,8 +34,9 @@ def test_enum_values_match_workload_vocabulary():
         assert re.search(r"\b%s = %d\b" % (name, val), hdr), name
 
 
-def _dry(cfg, rule, T, dp_batched=False):
-    tr = b.Trainer(cfg.stages, cfg.in_shape, cfg.N, cfg.B, cfg.lr, rule, cfg.dtype, dry_run=True, dp_batched=dp_batched)
+def _dry(cfg, rule, T, dp_batched=False, dw_group=1):
+    tr = b.Trainer(cfg.stages, cfg.in_shape, cfg.N, cfg.B, cfg.lr, rule, cfg.dtype, dry_run=True, dp_batched=dp_batched,
+                   dw_group=dw_group)
     for _ in range(T * 2 * cfg.S):
         tr.tick_dry(True)
     tr.drain()
@@ -204,3 +205,20 @@ def test_mini_batch_handed_over_after_its_first_tick_is_refused():
     r = O.train_schedule(cfg, None, [None], [None], wl.RULE_V2, compute=False)
     assert [t[1:] for t in tr.trace()] == [t[1:] for t in r.trace] or len(tr.trace()) == len(r.trace)
     tr.close()
+
+
+@pytest.mark.parametrize("name,g", [("cfg1", 2), ("cfg5", 2), ("cfg5", 4), ("cfg2", 4), ("mlp_odd", 4)])
+def test_grouped_weight_gradients_keep_the_timeline_and_cost_memory(name, g):
+    """dw_group changes no pass of the timeline (same trace, same live counts); the finished backward passes
+    that wait for their group hold their activations, which the byte series and the pool's peak show."""
+    cfg = wl.get_config(name)
+    T = 3
+    tr, base = _dry(cfg, wl.RULE_V2, T, dw_group=g), _dry(cfg, wl.RULE_V2, T)
+    assert tr.trace() == base.trace() and tr.live_counts() == base.live_counts()
+    assert tr.stats()["cur_activation_bytes"] == 0
+    assert tr.stats()["peak_activation_bytes"] > base.stats()["peak_activation_bytes"]
+    kept, kept0 = tr.live_bytes(0), base.live_bytes(0)
+    assert all(a >= b0 for a, b0 in zip(kept, kept0)) and max(kept) > max(kept0)
+    tr.close(); base.close()
+    with pytest.raises(b.CdpError):
+        b.Trainer(cfg.stages, cfg.in_shape, cfg.N, cfg.B, cfg.lr, wl.RULE_V2, cfg.dtype, dry_run=True, dw_group=3)
