@@ -1055,11 +1055,13 @@ hipError_t launch_linear_tick(GemmBatch& b, int dtype, bool wide, bool allow_thi
       } else {
         p.tiles_n = (p.N + bn - 1) / bn;
         tiles = ((p.M + 63) / 64) * p.tiles_n;
-        // few (at most 32) 64-column tiles with a long reduction (a classifier on its own in a launch):
-        // ranges of at least 4 slabs of 128, at most 8 per tile
+        // few (at most 64) 64-column tiles with a long reduction (a classifier, or the one layer of a stage that
+        // is alone at its level of the tick): ranges of at least 4 slabs of 128, at most 8 per tile, about 256
+        // workgroups in all (the partial tiles of a launch share a workspace of 256 slots)
         const int nslab = (p.K + 16 * vec - 1) / (16 * vec);
-        if (split_ok && !wide && tiles <= 32 && nslab >= 8) {
-          p.splits = std::min(8, nslab / 4);
+        const int want = std::min(std::min(8, nslab / 4), std::max(1, 256 / std::max(1, tiles)));
+        if (split_ok && !wide && tiles <= 64 && want >= 2) {
+          p.splits = want;
           tiles *= p.splits;
           skinny_split = true;
         }
