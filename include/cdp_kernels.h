@@ -31,9 +31,9 @@ int cdp_k_gemm(int dtype, int tile_shape, int a_kmajor, int b_kmajor, const void
  *   which 0: forward        y[B][Ho][Wo][Cout] (elem type) = conv(x, w),  w[Cout][k][k][Cin]
  *         1: data gradient  dx[B][H][W][Cin]   (elem type) from dy and wt[Cin][k][k][Cout]
  *         2: weight gradient dw[Cout][k][k][Cin] (fp32, overwritten) from dy and x
- *         3, 4: as 0, 1 on the 256 x 256 tile whatever the size (the engine and which = 0, 1 choose it only
- *               for launches that fill the chip); CDP_EINVAL unless bf16 with channel counts that are
- *               multiples of 64
+ *         3, 4: as 0, 1 on the direct-to-LDS kernel's 256 x 256 tile whatever the size (the engine and which =
+ *               0, 1 choose by launch size); 5, 6: the same kernel's 128 x 128 tile; CDP_EINVAL unless bf16 with
+ *               channel counts that are multiples of 64
  * in0/in1: (x, w) | (dy, wt) | (dy, x).  `out` must not alias the inputs.
  * workspace (device, may be NULL): scratch for the split weight-gradient kernel; with at
  * least 4 * Cout*k*k*Cin * (B*Ho*Wo / 512 + 4) bytes the two-phase path is used when the

@@ -24,13 +24,7 @@ namespace cdp {
 
 namespace {
 
-constexpr int BM = 256, BN = 256, BK = 64;
-constexpr int NWAVE = 8, WAVES_M = 2, WAVES_N = NWAVE / WAVES_M;
-constexpr int WTM = BM / WAVES_M, WTN = BN / WAVES_N;  // 128 x 64
-constexpr int MI = WTM / 32, NI = WTN / 32;            // 4 x 2 MFMA tiles per wave
-constexpr int STAGE_BYTES = (BM + BN) * BK * 2;        // 64 KB
-constexpr int BLOCKS = BM / 8;                         // 1 KB blocks (8 rows) per operand and stage
-constexpr int LPW = BLOCKS / NWAVE;                    // load instructions per wave, operand and slab (4)
+constexpr int BK = 64;
 
 __device__ uint4 g_zero_chunk[4];  // zero-initialised; source of structural zeros
 
@@ -38,7 +32,17 @@ typedef __attribute__((address_space(3))) void* lds_ptr;
 
 }  // namespace
 
-__global__ __launch_bounds__(512) void conv_gemm256_kernel(const GemmBatch batch) {
+// BM x BN outputs per workgroup, WAVES_M x WAVES_N wavefronts: 256 x 256 with 2 x 4 (wave tile 128 x 64, one
+// workgroup per CU), 128 x 128 with 2 x 2 (wave tile 64 x 64, two workgroups per CU).
+template <int BM, int BN, int WAVES_M, int WAVES_N>
+__global__ __launch_bounds__(WAVES_M * WAVES_N * 64) void conv_gemm_dl_kernel(const GemmBatch batch) {
+  constexpr int NWAVE = WAVES_M * WAVES_N;
+  constexpr int WTM = BM / WAVES_M, WTN = BN / WAVES_N;  // wave tile
+  constexpr int MI = WTM / 32, NI = WTN / 32;            // MFMA tiles per wave
+  constexpr int STAGE_BYTES = (BM + BN) * BK * 2;        // one LDS stage
+  constexpr int LPA = BM / 8 / NWAVE, LPB = BN / 8 / NWAVE;  // 1 KB blocks (8 rows) a wave loads per operand and slab
+  static_assert(LPA * 8 * NWAVE == BM && LPB * 8 * NWAVE == BN && BM == BN, "tile rows are dealt to the waves in blocks of 8");
+  constexpr int LPW = LPA;
   __shared__ __attribute__((aligned(1024))) unsigned char smem0[STAGE_BYTES];
   __shared__ __attribute__((aligned(1024))) unsigned char smem1[STAGE_BYTES];
   using E = Elem<uint16_t>;
@@ -172,13 +176,14 @@ __global__ __launch_bounds__(512) void conv_gemm256_kernel(const GemmBatch batch
   // ---- epilogue: 32 rows of the wave tile at a time through a staging area of the wave's own (fp32),
   // then 16-byte rows.  No load is outstanding and every wave has passed the last barrier: both stages are free.
   constexpr int SP = WTN + 4;
-  static_assert(4 * 32 * SP * 4 <= STAGE_BYTES, "four waves' staging areas per LDS stage");
-  float* stage = reinterpret_cast<float*>(wave < 4 ? smem0 : smem1) + (wave & 3) * (32 * SP);
+  constexpr int HALF = NWAVE / 2;
+  static_assert(HALF * 32 * SP * 4 <= STAGE_BYTES, "half of the waves' staging areas per LDS stage");
+  float* stage = reinterpret_cast<float*>(wave < HALF ? smem0 : smem1) + (wave % HALF) * (32 * SP);
   const int flags = P.flags;
   const bool fwd = P.epi == EPI_FWD;
   uint16_t* outp = static_cast<uint16_t*>(P.out);
-  constexpr int CPS = WTN / VEC;      // chunks per staged row (8)
-  constexpr int NCH = 32 * CPS / 64;  // chunks per lane (4)
+  constexpr int CPS = WTN / VEC;      // chunks per staged row
+  constexpr int NCH = 32 * CPS / 64;  // chunks per lane
 #pragma unroll
   for (int i = 0; i < MI; ++i) {
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
@@ -253,11 +258,12 @@ bool conv_gemm256_eligible(const GemmProb& p, int dtype) {
   return a_elems < (1ll << 31) && (int64_t)p.N * p.ldb < (1ll << 31);
 }
 
-// Worth it (measured against the 128 x 128 tile: 880 vs 720 TFLOP/s on a 3x3 convolution over 512 channels
-// with 25088 rows, 1050 TFLOP/s on an 8192^3 product, but 705 vs 745 on 25088 x 2048 x 2048, where the 784
-// tiles make 3.06 rounds of one workgroup per CU): long reductions (the tile's prologue and epilogue are
-// paid once per 256 x 256 outputs), mostly full tiles, and a tile count that rounds well to the 256 CUs.
+// Worth it (measured against the 128 x 128 tile of conv_gemm_kernel: 880 vs 720 TFLOP/s on a 3x3 convolution
+// over 512 channels with 25088 rows, 1050 TFLOP/s on an 8192^3 product, but 705 vs 745 on 25088 x 2048 x 2048,
+// where the 784 tiles make 3.06 rounds of one workgroup per CU): long reductions (the tile's prologue and
+// epilogue are paid once per 256 x 256 outputs), mostly full tiles, and a tile count that rounds well to the CUs.
 bool conv_gemm256_wanted(const GemmProb* p, int n, int dtype) {
+  constexpr int BM = 256, BN = 256;
   int64_t tiles = 0;
   double useful = 0;
   for (int i = 0; i < n; ++i) {
@@ -270,20 +276,21 @@ bool conv_gemm256_wanted(const GemmProb* p, int n, int dtype) {
   return useful / ((double)rounds * 256 * BM * BN) >= 0.75;
 }
 
-hipError_t launch_conv_gemm256(GemmBatch& b, int dtype, hipStream_t stream) {
+hipError_t launch_conv_gemm256(GemmBatch& b, int dtype, hipStream_t stream, int tile) {
   if (b.n <= 0) return hipSuccess;
-  if (b.n > GEMM_MAX_PROBS) return hipErrorInvalidValue;
+  if (b.n > GEMM_MAX_PROBS || (tile != 256 && tile != 128)) return hipErrorInvalidValue;
   int total = 0;
   for (int i = 0; i < b.n; ++i) {
     GemmProb& p = b.p[i];
     if (p.M <= 0 || p.N <= 0 || p.K <= 0 || !conv_gemm256_eligible(p, dtype)) return hipErrorInvalidValue;
     p.splits = 1;
-    p.tiles_n = (p.N + BN - 1) / BN;
+    p.tiles_n = (p.N + tile - 1) / tile;
     p.tile_begin = total;
-    total += ((p.M + BM - 1) / BM) * p.tiles_n;
+    total += ((p.M + tile - 1) / tile) * p.tiles_n;
   }
   b.total_tiles = total;
-  hipLaunchKernelGGL(conv_gemm256_kernel, dim3(total), dim3(512), 0, stream, b);
+  if (tile == 256) hipLaunchKernelGGL((conv_gemm_dl_kernel<256, 256, 2, 4>), dim3(total), dim3(512), 0, stream, b);
+  else hipLaunchKernelGGL((conv_gemm_dl_kernel<128, 128, 2, 2>), dim3(total), dim3(256), 0, stream, b);
   return hipGetLastError();
 }
 

@@ -171,7 +171,7 @@ hipError_t launch_conv_gemm(GemmBatch& batch, int dtype, int bm, int bn, hipStre
 // problems whose reduction slabs of 64 lie inside one tap; _wanted: enough mostly-full tiles to fill the chip.
 bool conv_gemm256_eligible(const GemmProb& p, int dtype);
 bool conv_gemm256_wanted(const GemmProb* p, int n, int dtype);
-hipError_t launch_conv_gemm256(GemmBatch& batch, int dtype, hipStream_t stream);
+hipError_t launch_conv_gemm256(GemmBatch& batch, int dtype, hipStream_t stream, int tile = 256);  // tile: 256 or 128 (same kernel, four wavefronts)
 // Weight gradient in two phases: launch_conv_wgrad writes per-range partial sums
 // (out = f32 [splits][Cout][Ncol], aux3 = f32 [splits][Cout] or NULL, splits fixed by
 // conv_wgrad_splits), launch_wgrad_reduce folds them into the accumulators.

@@ -47,8 +47,9 @@ int cdp_k_conv(int dtype, int which, const void* in0, const void* in1, void* out
   p.A = in0; p.B = in1; p.out = out;
   ConvGeom& g = p.g;
   g.KH = ks; g.KW = ks; g.stride = stride; g.pad = pad;
-  const bool force256 = which == 3 || which == 4;  // the large tile regardless of the launch heuristic
-  if (force256) which -= 3;
+  const bool force256 = which >= 3 && which <= 6;  // the direct-to-LDS tile regardless of the launch heuristic
+  const int forced_tile = which >= 5 ? 128 : 256;
+  if (force256) which -= which >= 5 ? 5 : 3;
   if (which == 0) {
     p.M = B * Ho * Wo; p.N = Cout; p.K = ks * ks * Cin;
     p.a_mode = OP_CONV_FWD; p.b_mode = OP_PLAIN_K; p.ldb = p.K; p.ldo = Cout;
@@ -87,7 +88,7 @@ int cdp_k_conv(int dtype, int which, const void* in0, const void* in1, void* out
     }
   } else if (force256) {
     if (!conv_gemm256_eligible(p, dtype)) return CDP_EINVAL;
-    return launch_conv_gemm256(b, dtype, st) == hipSuccess ? CDP_OK : CDP_EHIP;
+    return launch_conv_gemm256(b, dtype, st, forced_tile) == hipSuccess ? CDP_OK : CDP_EHIP;
   } else if (conv_fast_eligible(p, dtype)) {
     if (conv_gemm256_wanted(&p, 1, dtype)) return launch_conv_gemm256(b, dtype, st) == hipSuccess ? CDP_OK : CDP_EHIP;
     int bm, bn;

@@ -51,9 +51,9 @@ def conv(which, B, H, W, Cin, Cout, ks, st, pad, reps=20):
     dx = torch.empty_like(x)
     dw = torch.empty(Cout, ks, ks, Cin, device="cuda")
     ws = torch.empty(64 << 20, device="cuda", dtype=torch.float32)
-    if which in (0, 3):      # 3 / 4: forced onto the 256 x 256 tile
+    if which in (0, 3, 5):      # 3 / 4: forced onto the 256 x 256 direct-to-LDS tile, 5 / 6: onto its 128 x 128 form
         call = lambda: b.cdp_k_conv(1, which, x.data_ptr(), w.data_ptr(), y.data_ptr(), B, H, W, Cin, Cout, ks, st, pad)
-    elif which in (1, 4):
+    elif which in (1, 4, 6):
         call = lambda: b.cdp_k_conv(1, which, dy.data_ptr(), wt.data_ptr(), dx.data_ptr(), B, H, W, Cin, Cout, ks, st, pad)
     else:
         call = lambda: b.cdp_k_conv(1, 2, dy.data_ptr(), x.data_ptr(), dw.data_ptr(), B, H, W, Cin, Cout, ks, st, pad,
@@ -150,12 +150,12 @@ def main():
             us, tf, gb = conv(which, *s[1:])
             parts.append("%s %7.1f us %6.1f TF/s (%.2f) %5.0f GB/s (%.2f)" % (name, us, tf, tf / MFMA_PEAK, gb, gb / HBM_PEAK))
         print("%-34s %s" % (s[0], " | ".join(parts)), flush=True)
-    print("# The same passes forced onto the 256 x 256 tile (cdp_k_conv which = 3 / 4), where the channel counts allow")
+    print("# The same passes forced onto the direct-to-LDS kernel (cdp_k_conv which = 3 / 4: 256 x 256 tile, 5 / 6: 128 x 128), where the channel counts allow")
     for s in CONV_SHAPES + [("8192 x 8192 x 8192 product", 32, 16, 16, 8192, 8192, 1, 1, 0)]:
         if args.only not in s[0] or s[4] % 64 or s[5] % 64:
             continue
         parts = []
-        for which, name in ((3, "fwd"), (4, "dgrad")):
+        for which, name in ((3, "fwd 256"), (4, "dgrad 256"), (5, "fwd 128"), (6, "dgrad 128")):
             us, tf, gb = conv(which, *s[1:])
             parts.append("%s %7.1f us %6.1f TF/s (%.2f)" % (name, us, tf, tf / MFMA_PEAK))
         print("%-34s %s" % (s[0], " | ".join(parts)), flush=True)

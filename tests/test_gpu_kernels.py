@@ -113,10 +113,11 @@ LARGE_TILE_CASES = [
 ]
 
 
+@pytest.mark.parametrize("tile", [256, 128])
 @pytest.mark.parametrize("case", LARGE_TILE_CASES)
-def test_conv_large_tile_matches_oracle(case):
-    """Forward / data gradient on the 256 x 256 tile (bf16; operands loaded straight into LDS, swizzled
-    rows, two stages) against the oracle's convolution."""
+def test_conv_large_tile_matches_oracle(case, tile):
+    """Forward / data gradient on the direct-to-LDS kernel (bf16; swizzled rows, two stages), 256 x 256 and
+    128 x 128 tiles, against the oracle's convolution."""
     torch = _torch()
     which, B, H, W, Cin, Cout, ks, st, pad = case
     dtype = wl.BF16
@@ -127,14 +128,14 @@ def test_conv_large_tile_matches_oracle(case):
         ref = L.conv2d_fwd(xr, wr, st, pad)
         xd, wd = _dev(x, dtype), _dev(w, dtype)
         got = torch.full(ref.shape, float("nan"), dtype=torch.bfloat16, device="cuda")
-        b.cdp_k_conv(dtype, 3, xd.data_ptr(), wd.data_ptr(), got.data_ptr(), B, H, W, Cin, Cout, ks, st, pad)
+        b.cdp_k_conv(dtype, 3 if tile == 256 else 5, xd.data_ptr(), wd.data_ptr(), got.data_ptr(), B, H, W, Cin, Cout, ks, st, pad)
     else:
         Ho, Wo = (H + 2 * pad - ks) // st + 1, (W + 2 * pad - ks) // st + 1
         dy = wl.random_normal(7, 3, B * Ho * Wo * Cout).reshape(B, Ho, Wo, Cout)
         ref, _ = L.conv2d_bwd(xr, wr, st, pad, _rnd(dy, dtype))
         dyd, wtd = _dev(dy, dtype), _dev(np.transpose(w, (3, 1, 2, 0)), dtype)
         got = torch.full(x.shape, float("nan"), dtype=torch.bfloat16, device="cuda")
-        b.cdp_k_conv(dtype, 4, dyd.data_ptr(), wtd.data_ptr(), got.data_ptr(), B, H, W, Cin, Cout, ks, st, pad)
+        b.cdp_k_conv(dtype, 4 if tile == 256 else 6, dyd.data_ptr(), wtd.data_ptr(), got.data_ptr(), B, H, W, Cin, Cout, ks, st, pad)
     torch.cuda.synchronize()
     g = got.float().cpu().numpy().astype(np.float64)
     assert np.isfinite(g).all()

@@ -437,13 +437,15 @@ def test_long_reduction_shared_by_several_workgroups(name, rule):
 
 
 
-@pytest.mark.parametrize("name", ["resnet18_mini", "resnet50_mini_f32", "cfg2_mini"])
-def test_two_runs_give_identical_bits(name):
+@pytest.mark.parametrize("name,T", [("resnet18_mini", 3), ("resnet50_mini_f32", 3), ("cfg2_mini", 3), ("mlp_longk", 60),
+                                    ("mlp_longk_b40", 60), ("resnet18_mini_f32", 40)])
+def test_two_runs_give_identical_bits(name, T):
     """Nothing in a step depends on the order in which workgroups happen to finish: partial sums meet in
     fixed orders, row losses in integer adds.  Two runs of the same steps agree bit for bit in every
-    weight and every logged loss."""
+    weight and every logged loss.  The long runs are a soak of the reductions shared by several workgroups
+    (partial tiles in a workspace, the last arrival adds them): some thousand such launches per run, and a
+    partial tile read before it was complete would change the bits."""
     cfg = wl.get_config(name)
-    T = 3
     xs, ys = wl.make_data(cfg, T)
     p0 = wl.init_params(cfg)
     a = run_gpu(cfg, wl.RULE_V2, T, p0, xs, ys)
