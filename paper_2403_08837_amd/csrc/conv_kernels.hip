@@ -659,6 +659,8 @@ hipError_t launch_wgrad_reduce(WReduceBatch& b, int dtype, hipStream_t stream) {
   return hipGetLastError();
 }
 
+int conv_wgrad_slab(int dtype) { return wg_slab(dtype); }
+
 int conv_wgrad_splits(const GemmProb& p, int dtype, int wanted) {
   // Short ranges (one per WG_MAX_SLABS slabs) measured faster than few long ones as long as the
   // launch is short of workgroups, even though they write more partial sums; a layer with
@@ -792,7 +794,7 @@ hipError_t launch_conv_wgrad(GemmBatch& b, int dtype, bool wide, hipStream_t str
   for (int i = 0; i < b.n; ++i) {
     GemmProb& p = b.p[i];
     if (p.M <= 0 || p.N <= 0 || p.K <= 0 || p.epi != EPI_WGRAD || !conv_fast_eligible(p, dtype)) return hipErrorInvalidValue;
-    if (p.splits != conv_wgrad_splits(p, dtype, p.splits)) return hipErrorInvalidValue;  // caller sized the partial buffer
+    if (p.splits < 1 || p.splits > (p.K + wg_slab(dtype) - 1) / wg_slab(dtype)) return hipErrorInvalidValue;  // the caller sized the partial buffer
     p.tiles_n = (p.N + 127) / 128;
     p.tile_begin = total;
     total += ((p.M + to - 1) / to) * p.tiles_n * p.splits;

@@ -1094,11 +1094,51 @@ int run_tick(cdp_ctx* c, const float* x_dev, const int32_t* y_dev) {
     }
     if (!folds.empty()) p.push_back(std::move(folds));
   };
+  // Neither do the convolution weight gradients: nothing in the tick reads their partial sums but the folds, and
+  // their operands (saved inputs, output gradients) stay untouched until the tick's blocks are released.  They
+  // leave their levels too and run as one launch per tile height in front of the folds, with the reduction
+  // ranges chosen for the launch as a whole: several layers together fill the chip with fewer, longer ranges
+  // than each layer would need on its own, and every range less is one partial tile less to write and fold.
+  auto defer_wgrads = [c](Program& p) {
+    constexpr int TARGET_WGS = 2048;  // workgroups the launch aims at (8 per CU: measured best of 1024 / 2048 / 4096)
+    constexpr int MIN_CHUNK = 8;      // slabs per reduction range at least
+    std::vector<Item> wg;
+    auto is_cw = [c](const Item& it) {
+      if (it.kind != IT_GEMM || it.g.epi != EPI_WGRAD) return false;
+      const int lc = launch_class(it.g, c->plan.dtype);
+      return lc == LC_CWGRAD_64 || lc == LC_CWGRAD_128;
+    };
+    for (auto& level : p) {
+      auto keep = std::stable_partition(level.begin(), level.end(), [&](const Item& it) { return !is_cw(it); });
+      wg.insert(wg.end(), keep, level.end());
+      level.erase(keep, level.end());
+    }
+    if (wg.empty()) return;
+    const int slab = conv_wgrad_slab(c->plan.dtype);
+    int64_t work = 0;  // slabs of all tiles
+    for (const Item& it : wg) {
+      const int to = it.g.M >= 128 ? 128 : 64;
+      work += (int64_t)((it.g.M + to - 1) / to) * ((it.g.N + 127) / 128) * ((it.g.K + slab - 1) / slab);
+    }
+    const int64_t chunk = std::max<int64_t>(MIN_CHUNK, (work + TARGET_WGS - 1) / TARGET_WGS);
+    for (Item& it : wg) {
+      // never more ranges than the pass asked for: its partial-sum buffer is sized for those
+      const int nslab = (it.g.K + slab - 1) / slab;
+      const int splits = (int)std::max<int64_t>(1, std::min<int64_t>(it.g.splits, (nslab + chunk - 1) / chunk));
+      if (splits == it.g.splits) continue;
+      for (auto& level : p)  // the fold of the same partial sums
+        for (Item& f : level)
+          if (f.kind == IT_WREDUCE && f.r.part == static_cast<const float*>(it.g.out)) f.r.splits = splits;
+      it.g.splits = splits;
+    }
+    p.push_back(std::move(wg));
+  };
   if (!c->dry) {
     if (c->rule == CDP_RULE_DP) {
       // lock-step: all micro-batches hit the same stage, so passes run one after another
       // (their weight gradients share one accumulator)
       for (auto& p : progs) {
+        defer_wgrads(p);
         defer_folds(p);
         int rc = launch_program(c, p);
         if (rc) return rc;
@@ -1111,6 +1151,7 @@ int run_tick(cdp_ctx* c, const float* x_dev, const int32_t* y_dev) {
         if (merged.size() < p.size()) merged.resize(p.size());
         for (size_t l = 0; l < p.size(); ++l) merged[l].insert(merged[l].end(), p[l].begin(), p[l].end());
       }
+      defer_wgrads(merged);
       defer_folds(merged);
       int rc = launch_program(c, merged);
       if (rc) return rc;

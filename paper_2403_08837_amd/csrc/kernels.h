@@ -173,9 +173,11 @@ bool conv_gemm256_eligible(const GemmProb& p, int dtype);
 bool conv_gemm256_wanted(const GemmProb* p, int n, int dtype);
 hipError_t launch_conv_gemm256(GemmBatch& batch, int dtype, hipStream_t stream, int tile = 256);  // tile: 256 or 128 (same kernel, four wavefronts)
 // Weight gradient in two phases: launch_conv_wgrad writes per-range partial sums
-// (out = f32 [splits][Cout][Ncol], aux3 = f32 [splits][Cout] or NULL, splits fixed by
-// conv_wgrad_splits), launch_wgrad_reduce folds them into the accumulators.
+// (out = f32 [splits][Cout][Ncol], aux3 = f32 [splits][Cout] or NULL; splits: any number of ranges from 1 to
+// ceil(K / conv_wgrad_slab), conv_wgrad_splits gives what a problem launched on its own wants),
+// launch_wgrad_reduce folds them into the accumulators.
 int conv_wgrad_splits(const GemmProb& p, int dtype, int wanted);
+int conv_wgrad_slab(int dtype);  // output positions per reduction slab; a problem takes 1 .. ceil(K / slab) ranges
 hipError_t launch_conv_wgrad(GemmBatch& batch, int dtype, bool wide, hipStream_t stream);
 struct WReduceProb {
   const float* part; const float* part_beta;  // partial sums [splits][Cout][Ncol], [splits][Cout]
