@@ -208,6 +208,25 @@ __global__ __launch_bounds__(256) void conv_gemm_kernel(const GemmBatch batch) {
     }
   }
 
+  // The epilogue's own operand (forward: the residual, data gradient: the ReLU mask) for all of the tile's
+  // staging passes is requested here in one go, into the registers the operand prefetch no longer needs: its
+  // round trip to memory overlaps the staging of the first pass instead of being paid once per pass (what
+  // counts for the short reductions of the 1x1 layers, whose tiles are a chain of memory latencies).
+  constexpr int CPS = WTN / VEC;             // chunks per staged row of the epilogue
+  constexpr int NCH = 32 * CPS / 64;         // chunks per lane and pass
+  uint4 pa[MI][NCH];
+  if (P.aux1) {
+#pragma unroll
+    for (int i = 0; i < MI; ++i)
+#pragma unroll
+      for (int t = 0; t < NCH; ++t) {
+        const int q = lane + 64 * t;
+        const int r = row0 + wm * WTM + i * 32 + q / CPS, c = col0 + wn * WTN + (q % CPS) * VEC;
+        pa[i][t] = (r < P.M && c < P.N) ? *reinterpret_cast<const uint4*>(static_cast<const T*>(P.aux1) + (int64_t)r * P.ldo + c)
+                                        : make_uint4(0, 0, 0, 0);
+      }
+  }
+
   if (SPLIT && ks > 1) {
     // Partial tile -> this workgroup's slot of the workspace, in register order (lane-contiguous).
     // Partials and counter are device-scope atomics (they bypass the per-XCD L2) ordered by
@@ -260,8 +279,6 @@ __global__ __launch_bounds__(256) void conv_gemm_kernel(const GemmBatch batch) {
   const bool fwd = P.epi == EPI_FWD;
   float* stage = reinterpret_cast<float*>(smem) + wave * (32 * SP);
   T* outp = static_cast<T*>(P.out);
-  constexpr int CPS = WTN / VEC;             // chunks per staged row
-  constexpr int NCH = 32 * CPS / 64;         // chunks per lane
 #pragma unroll
   for (int i = 0; i < MI; ++i) {
     __syncthreads();  // operand tiles (first pass) or the previous staging pass are consumed
@@ -287,7 +304,7 @@ __global__ __launch_bounds__(256) void conv_gemm_kernel(const GemmBatch batch) {
           for (int e = 0; e < VEC; ++e) val[e] += static_cast<const float*>(P.aux0)[c + e];
         }
         if (P.aux1) {
-          x1.v = *reinterpret_cast<const uint4*>(static_cast<const T*>(P.aux1) + o);
+          x1.v = pa[i][t];
 #pragma unroll
           for (int e = 0; e < VEC; ++e) val[e] += E::to_f32(x1.e[e]);
         }
@@ -307,7 +324,7 @@ __global__ __launch_bounds__(256) void conv_gemm_kernel(const GemmBatch batch) {
           for (int e = 0; e < VEC; ++e) val[e] += E::to_f32(x2.e[e]);
         }
         if (P.aux1) {
-          x1.v = *reinterpret_cast<const uint4*>(static_cast<const T*>(P.aux1) + o);
+          x1.v = pa[i][t];
 #pragma unroll
           for (int e = 0; e < VEC; ++e)
             if (!(E::to_f32(x1.e[e]) > 0.f)) val[e] = 0.f;
