@@ -215,6 +215,13 @@ __global__ __launch_bounds__(256) void conv_gemm_kernel(const GemmBatch batch) {
   constexpr int CPS = WTN / VEC;             // chunks per staged row of the epilogue
   constexpr int NCH = 32 * CPS / 64;         // chunks per lane and pass
   uint4 pa[MI][NCH];
+  float bias[VEC];  // forward: the bias of this lane's columns (the same columns in every pass and chunk: CPS divides 64)
+  static_assert(64 % CPS == 0, "a lane keeps its columns from chunk to chunk");
+  if (P.epi == EPI_FWD && P.aux0) {
+    const int c = col0 + wn * WTN + (lane % CPS) * VEC;
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) bias[e] = c < P.N ? static_cast<const float*>(P.aux0)[c + e] : 0.f;
+  }
   if (P.aux1) {
 #pragma unroll
     for (int i = 0; i < MI; ++i)
@@ -301,7 +308,7 @@ __global__ __launch_bounds__(256) void conv_gemm_kernel(const GemmBatch batch) {
       if (fwd) {
         if (P.aux0) {
 #pragma unroll
-          for (int e = 0; e < VEC; ++e) val[e] += static_cast<const float*>(P.aux0)[c + e];
+          for (int e = 0; e < VEC; ++e) val[e] += bias[e];
         }
         if (P.aux1) {
           x1.v = pa[i][t];
