@@ -21,6 +21,11 @@
 
 namespace cdp {
 
+// Consecutive logical tiles that one XCD takes in a row (xcd_block_cyclic); measured on the ResNet-50 and ViT-B/16
+// shaped workloads: 4, 8 and 16 within 0.5 % of each other in time, L2 misses of the forward / data-gradient
+// kernel 26 % below the round-robin order.
+constexpr int XCD_RUN = 8;
+
 // ---------------------------------------------------------------------------------
 // forward / data gradient: 128 x BN tile, waves 2 x 2, reduction slab BK (a divisor of the
 // channel count).  The epilogue goes through LDS so that results, residuals and masks move
@@ -41,7 +46,8 @@ __global__ __launch_bounds__(256) void conv_gemm_kernel(const GemmBatch batch) {
   constexpr int BUF = (BM + BN) * LDP;  // elements per operand buffer
   T* const As0 = reinterpret_cast<T*>(smem);
 
-  const int tile = (int)blockIdx.x;
+  // runs of XCD_RUN neighbouring tiles (same rows, next columns; then the next rows, whose 3x3 halo they share) on one XCD
+  const int tile = xcd_block_cyclic((int)blockIdx.x, batch.total_tiles, XCD_RUN);
   const GemmProb& P = batch.p[find_problem(batch, tile)];
   // a long reduction of a small launch is shared by P.splits workgroups (neighbours in the
   // tile list); the last of them to finish adds the partial tiles and runs the epilogue

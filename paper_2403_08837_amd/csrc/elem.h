@@ -50,6 +50,17 @@ __device__ __forceinline__ int find_problem(const GemmBatch& batch, int tile) {
   return pi;
 }
 
+// blockIdx -> logical tile so that runs of G consecutive logical tiles (neighbours in a problem's tile grid, which
+// read the same operand rows) execute on one XCD and find each other's rows in its L2: consecutive workgroup ids
+// are dealt round-robin to the 8 XCDs, so inside every block of 8 * G ids the k-th id that lands on XCD x takes
+// logical tile x * G + k.  The ids past the last whole block keep their number.
+__device__ __forceinline__ int xcd_block_cyclic(int bid, int total, int G) {
+  const int block = 8 * G, whole = total - total % block;
+  if (bid >= whole) return bid;
+  const int s = bid / block, r = bid - s * block;
+  return s * block + (r & 7) * G + (r >> 3);
+}
+
 __device__ __forceinline__ v16f_t mfma_bf16(uint4 a, uint4 b, v16f_t c) {
   return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(v8bf16_t, a), __builtin_bit_cast(v8bf16_t, b), c, 0, 0, 0);
 }
