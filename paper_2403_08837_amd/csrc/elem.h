@@ -12,12 +12,8 @@ typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 v8bf16_t;
 typedef __attribute__((__vector_size__(16 * sizeof(float)))) float v16f_t;
 
 __device__ __forceinline__ float bf16_to_f32(uint16_t h) { return __uint_as_float(((uint32_t)h) << 16); }
-__device__ __forceinline__ uint16_t f32_to_bf16(float f) {
-  uint32_t u = __float_as_uint(f);
-  if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x40u);  // quiet NaN
-  u += 0x7fffu + ((u >> 16) & 1u);                                            // round to nearest even
-  return (uint16_t)(u >> 16);
-}
+// round to nearest even, in hardware (v_cvt_pk_bf16_f32)
+__device__ __forceinline__ uint16_t f32_to_bf16(float f) { return __builtin_bit_cast(uint16_t, static_cast<__bf16>(f)); }
 
 template <typename T> struct Elem;
 template <> struct Elem<uint16_t> {

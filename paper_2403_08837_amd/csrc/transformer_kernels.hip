@@ -691,6 +691,209 @@ __global__ __launch_bounds__(256) void softmax_bwd_vec_kernel(const T* __restric
     }
 }
 
+// ---------------------------------------------------------------------------------
+// Score rows without the fp32 round trip through memory (bf16, at most 256 tokens, head width a multiple of 16 up
+// to 80).  A workgroup owns 64 query rows of one (sample, head) and all keys: wavefront w contracts the 64 x 64
+// block of keys 64 w .. 64 w + 63 (2 x 2 MFMA accumulators, reduction over the head width); the fp32 block then
+// goes to LDS (over the operand tiles), and each wavefront finishes 16 whole rows, a lane holding four
+// neighbouring keys of the row: the row maximum / sums are wavefront reductions and rows move as 8-byte vectors.
+//   forward : A = q, B = k:     P = softmax(scale * A B^T)                           -> out (bf16)
+//   backward: A = d out, B = v: dP = A B^T, dS = P * (dP - rowsum(dP * P)) * scale   -> out (bf16)
+struct AttnScoreArgs {
+  const uint16_t* A; int64_t a_sample, a_head, a_row;  // rows = queries (reduction index contiguous)
+  const uint16_t* B; int64_t b_sample, b_head, b_row;  // rows = keys
+  const uint16_t* P;                                   // backward: probabilities [z][NT][NT]
+  uint16_t* out;                                       // [z][NT][NT]
+  int NT, dh, heads;
+  float scale;
+  int vec;  // rows of P / out are whole 8-byte groups (NT % 4 == 0, bases 8-byte aligned)
+};
+__device__ __forceinline__ float row16_sum(float v) {  // over the 16 lanes of a VALU row, result in each of them
+  v += dpp_rot<0x121>(v);
+  v += dpp_rot<0x122>(v);
+  v += dpp_rot<0x124>(v);
+  return v + dpp_rot<0x128>(v);
+}
+__device__ __forceinline__ float row16_max(float v) {
+  v = fmaxf(v, dpp_rot<0x121>(v));
+  v = fmaxf(v, dpp_rot<0x122>(v));
+  v = fmaxf(v, dpp_rot<0x124>(v));
+  return fmaxf(v, dpp_rot<0x128>(v));
+}
+constexpr int ATTN_SP = 264;  // pitch (floats) of the score block in LDS: rows 4 apart sit 32 banks apart
+
+template <bool BWD>
+__global__ __launch_bounds__(256) void attn_scores_kernel(const AttnScoreArgs a) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char attn_smem[];
+  const int pitch = a.dh + 8;  // elements; rows stay 16-byte aligned and 16 fragment rows cover all banks
+  uint16_t* As = reinterpret_cast<uint16_t*>(attn_smem);  // [64][pitch]
+  uint16_t* Bs = As + 64 * pitch;                         // [256][pitch]
+  float* S = reinterpret_cast<float*>(attn_smem);         // [32][ATTN_SP], after the contraction
+  const int z = blockIdx.y, sample = z / a.heads, head = z % a.heads;
+  const int q0 = blockIdx.x * 64, NT = a.NT;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, l31 = lane & 31, hi = lane >> 5;
+  const uint16_t* Ap = a.A + sample * a.a_sample + head * a.a_head;
+  const uint16_t* Bp = a.B + sample * a.b_sample + head * a.b_head;
+  const int cpr = a.dh >> 3;  // 16-byte chunks per row
+  for (int e = tid; e < 64 * cpr; e += 256) {
+    const int r = e / cpr, c = (e - r * cpr) * 8;
+    const uint4 v = q0 + r < NT ? *reinterpret_cast<const uint4*>(Ap + (int64_t)(q0 + r) * a.a_row + c) : make_uint4(0, 0, 0, 0);
+    *reinterpret_cast<uint4*>(As + r * pitch + c) = v;
+  }
+  const int key_rows = min(256, (NT + 63) & ~63);  // key blocks some wavefront contracts
+  for (int e = tid; e < key_rows * cpr; e += 256) {
+    const int r = e / cpr, c = (e - r * cpr) * 8;
+    const uint4 v = r < NT ? *reinterpret_cast<const uint4*>(Bp + (int64_t)r * a.b_row + c) : make_uint4(0, 0, 0, 0);
+    *reinterpret_cast<uint4*>(Bs + r * pitch + c) = v;
+  }
+  // the score block passes through LDS in two halves of 32 rows; of each half this wavefront finishes rows
+  // 8 wave .. 8 wave + 7, four at a time: 16 lanes per row, a lane holding keys
+  // 64 k + 4 l15 .. + 3 for k = 0 .. 3, so that row reductions stay inside the 16-lane rows of the VALU (DPP).
+  // Backward: the rows' probabilities are requested now.
+  const int sub = lane >> 4, l15 = lane & 15;
+  auto tile_row = [&](int ps) { return (ps >> 1) * 32 + wave * 8 + (ps & 1) * 4 + sub; };  // pass ps = 0 .. 3 of this lane
+  const int64_t rbase = ((int64_t)z * NT + q0) * NT + 4 * l15;  // + row * NT + 64 k
+  uint2 pr[4][4];
+  if constexpr (BWD) {
+#pragma unroll
+    for (int ps = 0; ps < 4; ++ps)
+#pragma unroll
+      for (int k = 0; k < 4; ++k) {
+        pr[ps][k] = make_uint2(0, 0);
+        const int c = 64 * k + 4 * l15;
+        if (q0 + tile_row(ps) < NT && c < NT) {
+          const uint16_t* src = a.P + rbase + (int64_t)tile_row(ps) * NT + 64 * k;
+          if (a.vec) pr[ps][k] = *reinterpret_cast<const uint2*>(src);
+          else {
+            uint32_t e[4];
+#pragma unroll
+            for (int q = 0; q < 4; ++q) e[q] = c + q < NT ? src[q] : 0u;
+            pr[ps][k] = make_uint2(e[0] | (e[1] << 16), e[2] | (e[3] << 16));
+          }
+        }
+      }
+  }
+  __syncthreads();
+  // element (i, j, v) of this lane: row = 32 i + 8 (v / 4) + 4 hi + v % 4, key = 64 wave + 32 j + l31
+  const bool live = wave * 64 < NT;          // wavefront-uniform
+  const bool second = wave * 64 + 32 < NT;   // so is the presence of the wavefront's second block of 32 keys
+  bmm_v16f acc[2][2];
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+  if (live) {
+    const uint16_t* ar = As + l31 * pitch + 8 * hi;
+    const uint16_t* br = Bs + (wave * 64 + l31) * pitch + 8 * hi;
+    for (int kk = 0; kk < a.dh; kk += 16) {
+      uint4 av[2], bv[2];
+#pragma unroll
+      for (int i = 0; i < 2; ++i) av[i] = *reinterpret_cast<const uint4*>(ar + i * 32 * pitch + kk);
+#pragma unroll
+      for (int j = 0; j < 2; ++j) bv[j] = *reinterpret_cast<const uint4*>(br + j * 32 * pitch + kk);
+#pragma unroll
+      for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+          if (j == 0 || second)
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bmm_v8bf, av[i]), __builtin_bit_cast(bmm_v8bf, bv[j]), acc[i][j], 0, 0, 0);
+    }
+  }
+#pragma unroll
+  for (int ps = 0; ps < 4; ++ps) {
+    if ((ps & 1) == 0) {
+      __syncthreads();  // the operand tiles / the first half of the score block are consumed
+      if (live) {
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+          for (int v = 0; v < 16; ++v)
+            S[((v >> 2) * 8 + hi * 4 + (v & 3)) * ATTN_SP + wave * 64 + j * 32 + l31] = acc[ps >> 1][j][v];
+      }
+      __syncthreads();
+    }
+    const int row = tile_row(ps), srow = wave * 8 + (ps & 1) * 4 + sub;  // row of the tile, row of the half in LDS
+    // (no early exit: every wavefront reaches the barriers; rows past the end compute on zeros and store nothing)
+    const bool row_ok = q0 + row < NT;
+    float x[4][4], y[4][4];
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      const float4 s4 = *reinterpret_cast<const float4*>(S + srow * ATTN_SP + 64 * k + 4 * l15);
+      x[k][0] = s4.x; x[k][1] = s4.y; x[k][2] = s4.z; x[k][3] = s4.w;
+    }
+    if constexpr (!BWD) {
+      float m = -INFINITY;
+#pragma unroll
+      for (int k = 0; k < 4; ++k)
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          x[k][q] = 64 * k + 4 * l15 + q < NT ? x[k][q] * a.scale : -INFINITY;  // (columns of wavefronts that are not live hold no scores)
+          m = fmaxf(m, x[k][q]);
+        }
+      m = row16_max(m);  // key 0 is always there: finite
+      float sum = 0.f;
+#pragma unroll
+      for (int k = 0; k < 4; ++k)
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          y[k][q] = 64 * k + 4 * l15 + q < NT ? __expf(x[k][q] - m) : 0.f;
+          sum += y[k][q];
+        }
+      const float inv = __builtin_amdgcn_rcpf(row16_sum(sum));
+#pragma unroll
+      for (int k = 0; k < 4; ++k)
+#pragma unroll
+        for (int q = 0; q < 4; ++q) y[k][q] *= inv;
+    } else {
+      float dot = 0.f;
+#pragma unroll
+      for (int k = 0; k < 4; ++k) {
+        y[k][0] = __uint_as_float(pr[ps][k].x << 16); y[k][1] = __uint_as_float(pr[ps][k].x & 0xffff0000u);
+        y[k][2] = __uint_as_float(pr[ps][k].y << 16); y[k][3] = __uint_as_float(pr[ps][k].y & 0xffff0000u);
+#pragma unroll
+        for (int q = 0; q < 4; ++q) dot += 64 * k + 4 * l15 + q < NT ? y[k][q] * x[k][q] : 0.f;
+      }
+      dot = row16_sum(dot);
+#pragma unroll
+      for (int k = 0; k < 4; ++k)
+#pragma unroll
+        for (int q = 0; q < 4; ++q) y[k][q] = y[k][q] * (x[k][q] - dot) * a.scale;
+    }
+    if (!row_ok) continue;
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      const int c = 64 * k + 4 * l15;
+      if (c >= NT) continue;
+      uint16_t* dst = a.out + rbase + (int64_t)row * NT + 64 * k;
+      if (a.vec) {
+        *reinterpret_cast<uint2*>(dst) = make_uint2((uint32_t)f32_to_bf16(y[k][0]) | ((uint32_t)f32_to_bf16(y[k][1]) << 16),
+                                                    (uint32_t)f32_to_bf16(y[k][2]) | ((uint32_t)f32_to_bf16(y[k][3]) << 16));
+      } else {
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+          if (c + q < NT) dst[q] = f32_to_bf16(y[k][q]);
+      }
+    }
+  }
+}
+
+static bool attn_scores_fused_ok(const void* a, int64_t a_row, const void* b, int64_t b_row, int NT, int dh, int dtype) {
+  return dtype == DT_BF16 && NT <= 256 && dh % 16 == 0 && dh <= 80 && a_row % 8 == 0 && b_row % 8 == 0 &&
+         reinterpret_cast<uintptr_t>(a) % 16 == 0 && reinterpret_cast<uintptr_t>(b) % 16 == 0;
+}
+template <bool BWD>
+static hipError_t launch_attn_scores(const AttnScoreArgs& a, int batch, hipStream_t stream) {
+  if (batch <= 0 || batch > 65535) return hipErrorInvalidValue;
+  const size_t lds = std::max<size_t>((size_t)(64 + 256) * (a.dh + 8) * 2, (size_t)32 * ATTN_SP * 4);
+  AttnScoreArgs b = a;
+  b.vec = a.NT % 4 == 0 && reinterpret_cast<uintptr_t>(a.out) % 8 == 0 && (!BWD || reinterpret_cast<uintptr_t>(a.P) % 8 == 0);
+  hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_scores_kernel<BWD>), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+  hipLaunchKernelGGL((attn_scores_kernel<BWD>), dim3((a.NT + 63) / 64, batch), dim3(256), lds, stream, b);
+  return hipGetLastError();
+}
+
 // Self-attention core on qkv[B][T][3*D] (q | k | v per token, head h in columns h*dh..):
 // forward  S = q k^T / sqrt(dh) (fp32 workspace), P = softmax(S) (kept for the backward), out = P v;
 // backward dv = P^T do, dP = do v^T (fp32 workspace), ds = P * (dP - rowsum(dP * P)) / sqrt(dh),
@@ -703,6 +906,15 @@ hipError_t launch_attention_fwd(const void* qkv, void* P, void* out, float* ws, 
   const float scale = 1.0f / sqrtf((float)dh);
   const char* base = static_cast<const char*>(qkv);
   const int eb = dtype == DT_BF16 ? 2 : 4;
+  const int64_t rows = (int64_t)B * heads * NT;
+  if (attn_scores_fused_ok(base, tok, base + (int64_t)D * eb, tok, NT, dh, dtype) && (dh * eb) % 16 == 0) {
+    AttnScoreArgs f;
+    f.A = reinterpret_cast<const uint16_t*>(base); f.a_sample = NT * tok; f.a_head = dh; f.a_row = tok;
+    f.B = reinterpret_cast<const uint16_t*>(base + (int64_t)D * eb); f.b_sample = NT * tok; f.b_head = dh; f.b_row = tok;
+    f.P = nullptr; f.out = static_cast<uint16_t*>(P); f.NT = NT; f.dh = dh; f.heads = heads; f.scale = scale;
+    hipError_t e = launch_attn_scores<false>(f, B * heads, stream);
+    if (e != hipSuccess) return e;
+  } else {
   BmmArgs s;  // S[z][q][key] = scale * sum_j q[q][j] k[key][j]
   s.A = BmmOperand{base, NT * tok, dh, tok, 1};
   s.B = BmmOperand{base + (int64_t)D * eb, NT * tok, dh, tok, 1};
@@ -710,7 +922,6 @@ hipError_t launch_attention_fwd(const void* qkv, void* P, void* out, float* ws, 
   s.M = NT; s.N = NT; s.K = dh; s.heads = heads; s.alpha = scale; s.c_f32 = 1;
   hipError_t e = launch_bmm(s, B * heads, dtype, stream);
   if (e != hipSuccess) return e;
-  const int64_t rows = (int64_t)B * heads * NT;
   if (NT % 4 == 0 && aligned16(ws) && aligned16(P))
     CDP_TDISPATCH(dtype, hipLaunchKernelGGL((softmax_fwd_vec_kernel<T>), dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, stream, ws,
                                             static_cast<T*>(P), rows, NT));
@@ -718,6 +929,7 @@ hipError_t launch_attention_fwd(const void* qkv, void* P, void* out, float* ws, 
     CDP_TDISPATCH(dtype, hipLaunchKernelGGL((softmax_fwd_kernel<T>), dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, stream, ws,
                                             static_cast<T*>(P), rows, NT));
   if ((e = hipGetLastError()) != hipSuccess) return e;
+  }
   BmmArgs o;  // out[z][q][j] = sum_key P[q][key] v[key][j]
   o.A = BmmOperand{P, heads * TT, TT, NT, 1};
   o.B = BmmOperand{base + 2ll * D * eb, NT * tok, dh, 1, tok};
@@ -745,6 +957,14 @@ hipError_t launch_attention_bwd(const void* qkv, const void* P, const void* dout
   a.A = Pkq; a.B = dOjq; a.C = dbase + 2ll * D * eb; a.c_sample = NT * tok; a.c_head = dh; a.c_row = tok; a.c_col = 1;
   a.M = NT; a.N = dh; a.K = NT; a.heads = heads; a.alpha = 1.f; a.c_f32 = 0;
   if ((e = launch_bmm(a, B * heads, dtype, stream)) != hipSuccess) return e;
+  if (attn_scores_fused_ok(dout, D, base + 2ll * D * eb, tok, NT, dh, dtype) && (dh * eb) % 16 == 0) {
+    // dS straight from d out, v and P
+    AttnScoreArgs f;
+    f.A = static_cast<const uint16_t*>(dout); f.a_sample = (int64_t)NT * D; f.a_head = dh; f.a_row = D;
+    f.B = reinterpret_cast<const uint16_t*>(base + 2ll * D * eb); f.b_sample = NT * tok; f.b_head = dh; f.b_row = tok;
+    f.P = static_cast<const uint16_t*>(P); f.out = static_cast<uint16_t*>(ws_ds); f.NT = NT; f.dh = dh; f.heads = heads; f.scale = scale;
+    if ((e = launch_attn_scores<true>(f, B * heads, stream)) != hipSuccess) return e;
+  } else {
   // dP[q][key] = sum_j do[q][j] v[key][j]
   a.A = dOqj; a.B = BmmOperand{base + 2ll * D * eb, NT * tok, dh, tok, 1}; a.C = ws_dp;
   a.c_sample = heads * TT; a.c_head = TT; a.c_row = NT; a.c_col = 1; a.M = NT; a.N = NT; a.K = dh; a.c_f32 = 1;
@@ -757,6 +977,7 @@ hipError_t launch_attention_bwd(const void* qkv, const void* P, const void* dout
     CDP_TDISPATCH(dtype, hipLaunchKernelGGL((softmax_bwd_kernel<T>), dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, stream,
                                             static_cast<const T*>(P), ws_dp, static_cast<T*>(ws_ds), rows, NT, scale));
   if ((e = hipGetLastError()) != hipSuccess) return e;
+  }
   const BmmOperand dSqk{ws_ds, heads * TT, TT, NT, 1}, dSkq{ws_ds, heads * TT, TT, 1, NT};
   // dq[q][j] = sum_key ds[q][key] k[key][j]
   a.A = dSqk; a.B = BmmOperand{base + (int64_t)D * eb, NT * tok, dh, 1, tok}; a.C = dbase;
