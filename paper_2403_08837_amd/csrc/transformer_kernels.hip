@@ -294,25 +294,30 @@ __global__ __launch_bounds__(256) void layernorm_bwd_cols_kernel(const T* __rest
   }
 }
 
-// Column sums of the n_part partial rows (2C wide): 64 columns x 4 row groups per workgroup.
+// Column sums of the n_part partial rows (2C wide): 16 columns x 16 row groups per workgroup (a short chain of
+// loads per lane: the kernel is a handful of memory round trips long), the groups' sums added in group order.
 __global__ __launch_bounds__(256) void layernorm_fold_kernel(const float* __restrict__ part, int n_part, float* __restrict__ Ggamma,
                                                              float* __restrict__ Gbeta, int C) {
-  __shared__ float red[4][64];
-  const int col = threadIdx.x & 63, grp = threadIdx.x >> 6;
-  const int c = blockIdx.x * 64 + col;
-  float s0 = 0.f, s1 = 0.f;
+  __shared__ float red[16][17];
+  const int col = threadIdx.x & 15, grp = threadIdx.x >> 4;
+  const int c = blockIdx.x * 16 + col;
+  float s0 = 0.f, s1 = 0.f, s2 = 0.f, s3 = 0.f;
   if (c < 2 * C) {
     int k = grp;
-    for (; k + 4 < n_part; k += 8) {
+    for (; k + 48 < n_part; k += 64) {
       s0 += part[(int64_t)k * 2 * C + c];
-      s1 += part[(int64_t)(k + 4) * 2 * C + c];
+      s1 += part[(int64_t)(k + 16) * 2 * C + c];
+      s2 += part[(int64_t)(k + 32) * 2 * C + c];
+      s3 += part[(int64_t)(k + 48) * 2 * C + c];
     }
-    if (k < n_part) s0 += part[(int64_t)k * 2 * C + c];
+    for (; k < n_part; k += 16) s0 += part[(int64_t)k * 2 * C + c];
   }
-  red[grp][col] = s0 + s1;
+  red[grp][col] = (s0 + s1) + (s2 + s3);
   __syncthreads();
   if (grp == 0 && c < 2 * C) {
-    const float s = (red[0][col] + red[1][col]) + (red[2][col] + red[3][col]);
+    float s = 0.f;
+#pragma unroll
+    for (int g = 0; g < 16; ++g) s += red[g][col];
     if (c < C) Ggamma[c] += s;
     else Gbeta[c - C] += s;
   }
@@ -359,7 +364,7 @@ hipError_t launch_layernorm_bwd(const void* x, const void* dy, const void* add, 
   CDP_TDISPATCH(dtype, hipLaunchKernelGGL((layernorm_bwd_cols_kernel<T>), dim3(wgs), dim3(256), 0, stream, static_cast<const T*>(x),
                                           static_cast<const T*>(dy), stats, part, rows, C));
   if ((e = hipGetLastError()) != hipSuccess) return e;
-  hipLaunchKernelGGL(layernorm_fold_kernel, dim3((2 * C + 63) / 64), dim3(256), 0, stream, part, wgs, Ggamma, Gbeta, C);
+  hipLaunchKernelGGL(layernorm_fold_kernel, dim3((2 * C + 15) / 16), dim3(256), 0, stream, part, wgs, Ggamma, Gbeta, C);
   return hipGetLastError();
 }
 
