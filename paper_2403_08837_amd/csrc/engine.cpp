@@ -892,12 +892,12 @@ int launch_level(cdp_ctx* c, std::vector<Item>& items) {
       case IT_ATTN_F:
         HIP_TRY(c, launch_attention_fwd(it.p0, it.p3, it.p2, static_cast<float*>(it.p4), it.i[0], it.i[1], it.i[2], it.i[3], dt,
                                         c->stream));
-        c->stats.kernel_launches += 2;  // three kernels
+        c->stats.kernel_launches += attention_launches(false, it.i[1], it.i[2], it.i[3], dt) - 1;
         break;
       case IT_ATTN_B:
         HIP_TRY(c, launch_attention_bwd(it.p0, it.p5, it.p1, it.p2, static_cast<float*>(it.p3), it.p4, it.i[0], it.i[1], it.i[2],
                                         it.i[3], dt, c->stream));
-        c->stats.kernel_launches += 5;  // six kernels
+        c->stats.kernel_launches += attention_launches(true, it.i[1], it.i[2], it.i[3], dt) - 1;
         break;
       case IT_GAP_B:
         HIP_TRY(c, launch_gap_bwd(it.p0, it.p1, it.p2, it.i[0], it.i[1], it.i[2], it.i[3], dt, c->stream));

@@ -285,6 +285,8 @@ hipError_t launch_attention_fwd(const void* qkv, void* P, void* out, float* ws, 
                                 hipStream_t stream);
 hipError_t launch_attention_bwd(const void* qkv, const void* P, const void* dout, void* dqkv, float* ws_dp, void* ws_ds, int B,
                                 int T, int D, int heads, int dtype, hipStream_t stream);
+// Kernels one call of the above launches (the score rows take one kernel where attn_scores_kernel applies, else two).
+int attention_launches(bool backward, int NT, int D, int heads, int dtype);
 
 // T -> f32 copy (cdp_get_weights of a ring copy).
 hipError_t launch_to_f32(const void* src, float* dst, int64_t n, int dtype, hipStream_t stream);

@@ -943,6 +943,13 @@ hipError_t launch_attention_fwd(const void* qkv, void* P, void* out, float* ws, 
   return launch_bmm(o, B * heads, dtype, stream);
 }
 
+int attention_launches(bool backward, int NT, int D, int heads, int dtype) {
+  const int dh = heads > 0 ? D / heads : 0;
+  // (operands the engine passes are 256-byte aligned)
+  const bool fused = dtype == DT_BF16 && NT <= 256 && dh > 0 && dh % 16 == 0 && dh <= 80 && D % 8 == 0;
+  return backward ? (fused ? 4 : 5) : (fused ? 2 : 3);
+}
+
 hipError_t launch_attention_bwd(const void* qkv, const void* P, const void* dout, void* dqkv, float* ws_dp, void* ws_ds, int B,
                                 int NT, int D, int heads, int dtype, hipStream_t stream) {
   if (B <= 0 || NT <= 0 || NT > 64 * LN_MAX_PER_LANE || heads <= 0 || D % heads) return hipErrorInvalidValue;

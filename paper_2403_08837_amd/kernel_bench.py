@@ -98,10 +98,10 @@ def vit_kernels(reps=50):
     wsa = torch.empty(2 * tt + 128, device="cuda")
     us = _time(lambda: b.cdp_k_attention(1, 0, qkv.data_ptr(), P.data_ptr(), 0, o.data_ptr(), wsa.data_ptr(), wsa.numel() * 4,
                                          Bn, T, D, H), reps)
-    res.append(("attention fwd 32x12 heads, 196 tokens (3 kernels)", us, 2.0 * (qkv.numel() + tt + o.numel()) / us / 1e3))
+    res.append(("attention fwd 32x12 heads, 196 tokens (2 kernels)", us, 2.0 * (qkv.numel() + tt + o.numel()) / us / 1e3))
     us = _time(lambda: b.cdp_k_attention(1, 1, qkv.data_ptr(), P.data_ptr(), do.data_ptr(), dq.data_ptr(), wsa.data_ptr(),
                                          wsa.numel() * 4, Bn, T, D, H), reps)
-    res.append(("attention bwd 32x12 heads, 196 tokens (5 kernels)", us, 2.0 * (2 * qkv.numel() + tt + do.numel()) / us / 1e3))
+    res.append(("attention bwd 32x12 heads, 196 tokens (4 kernels)", us, 2.0 * (2 * qkv.numel() + tt + do.numel()) / us / 1e3))
     return res
 
 
