@@ -273,17 +273,26 @@ __global__ __launch_bounds__(256) void conv_gemm_kernel(const GemmBatch batch) {
       for (int j = 0; j < NI; ++j)
 #pragma unroll
         for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
-    for (int sp = 0; sp < ks; ++sp) {  // one round trip per slot: all of a slot's loads are issued together
-      const float* src = first + (int64_t)sp * (BM * BN) + tid;
-      float part[MI * NI * 16];
+    // one round trip per group of four slots: all their loads are issued together, then added in slot order
+    constexpr int GS = 4, PE = MI * NI * 16;
+    for (int sp = 0; sp < ks; sp += GS) {
+      float part[GS][PE];
 #pragma unroll
-      for (int e = 0; e < MI * NI * 16; ++e) part[e] = __hip_atomic_load(src + e * 256, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      for (int u = 0; u < GS; ++u) {
+        const float* src = first + (int64_t)min(sp + u, ks - 1) * (BM * BN) + tid;  // (past the last slot: a harmless re-read)
 #pragma unroll
-      for (int i = 0; i < MI; ++i)
+        for (int e = 0; e < PE; ++e) part[u][e] = __hip_atomic_load(src + e * 256, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      }
 #pragma unroll
-        for (int j = 0; j < NI; ++j)
+      for (int u = 0; u < GS; ++u)
+        if (sp + u < ks) {
 #pragma unroll
-          for (int v = 0; v < 16; ++v) acc[i][j][v] += part[(i * NI + j) * 16 + v];
+          for (int i = 0; i < MI; ++i)
+#pragma unroll
+            for (int j = 0; j < NI; ++j)
+#pragma unroll
+              for (int v = 0; v < 16; ++v) acc[i][j][v] += part[u][(i * NI + j) * 16 + v];
+        }
     }
   }
 
