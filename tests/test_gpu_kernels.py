@@ -238,11 +238,14 @@ def test_gelu_kernels_match_oracle(dtype):
 
 @pytest.mark.parametrize("dtype", [wl.F32, wl.BF16])
 @pytest.mark.parametrize("B,T,D,heads", [(2, 196, 768, 12), (3, 9, 20, 4), (1, 324, 16, 2), (2, 16, 32, 4), (2, 50, 64, 2),
-                                         (1, 256, 128, 2), (1, 33, 64, 1)])
+                                         (1, 256, 128, 2), (1, 33, 64, 1), (1, 70, 160, 2), (2, 129, 48, 3), (1, 200, 96, 1),
+                                         (1, 260, 64, 2)])
 def test_attention_kernels_match_oracle(dtype, B, T, D, heads):
     """Probabilities, output and the gradient with respect to q | k | v: the ViT-B/16 shape,
     a shape where nothing is a multiple of four (element-wise staging, ragged tiles), 324
-    tokens, the reduced test shape, and heads of width 32 / 64 with 50, 256 and 33 tokens."""
+    tokens, the reduced test shape, heads of width 32 / 64 with 50, 256 and 33 tokens, and the limits of the
+    one-kernel score rows of the bf16 path (head widths 80, 16 and 96: the last one too wide for it; 129 and 260
+    tokens: a third key block of one key, and one token too many)."""
     torch = _torch()
     tdt = torch.bfloat16 if dtype == wl.BF16 else torch.float32
     eb = 2 if dtype == wl.BF16 else 4
