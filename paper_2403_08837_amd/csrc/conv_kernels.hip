@@ -625,11 +625,21 @@ __global__ __launch_bounds__(256) void wgrad_reduce_kernel(const WReduceBatch ba
       tot[0] += v.x; tot[1] += v.y; tot[2] += v.z; tot[3] += v.w;
     }
     const float gam = P.gamma ? P.gamma[o] : 1.f;
+    // loads before stores (which may alias them for all the compiler knows: one round trip instead of four)
+    float gold[4], wpl[4];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      gold[e] = wpl[e] = 0.f;
+      if (c + e < P.Ncol) {
+        gold[e] = P.G[row + c + e];
+        if (P.wplain) wpl[e] = E::to_f32(static_cast<const T*>(P.wplain)[row + c + e]);
+      }
+    }
 #pragma unroll
     for (int e = 0; e < 4; ++e)
       if (c + e < P.Ncol) {
-        P.G[row + c + e] += gam * tot[e];
-        if (P.wplain) dg += tot[e] * E::to_f32(static_cast<const T*>(P.wplain)[row + c + e]);
+        P.G[row + c + e] = gold[e] + gam * tot[e];
+        dg += tot[e] * wpl[e];
       }
     if (c0 == 0 && P.Gbeta) {
       float sb = 0.f;

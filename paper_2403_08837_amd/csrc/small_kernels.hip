@@ -167,20 +167,39 @@ __global__ __launch_bounds__(256) void repack_kernel(const RepackBatch batch) {
   T* wf = static_cast<T*>(a.wf);
   T* wt = static_cast<T*>(a.wt);
   T* wp = static_cast<T*>(a.wp);
-#pragma unroll 4
+  // all loads of the tile first (the stores below may alias them for all the compiler knows: interleaved, the 16
+  // rows of a thread would be 16 memory round trips one after the other)
+  float wv[16], gv[16], vv[16], gam[16];
+#pragma unroll
+  for (int i = 0; i < 16; ++i) {
+    const int o = o0 + ty + i * 4, c = c0 + tx;
+    wv[i] = gv[i] = vv[i] = 0.f;
+    gam[i] = 1.f;
+    if (o < a.O && c < a.C) {
+      const int64_t idx = ((int64_t)o * a.T + t) * a.C + c;
+      wv[i] = a.master[idx];
+      if (a.sgd.apply) {
+        gv[i] = a.G[idx];
+        if (a.V) vv[i] = a.V[idx];
+      }
+      if (a.gamma) gam[i] = a.gamma[o];
+    }
+  }
+#pragma unroll
   for (int i = 0; i < 16; ++i) {
     const int o = o0 + ty + i * 4, c = c0 + tx;
     float v = 0.f;
     if (o < a.O && c < a.C) {
       const int64_t idx = ((int64_t)o * a.T + t) * a.C + c;
-      float w = a.master[idx];
+      float w = wv[i];
       if (a.sgd.apply) {
-        w = sgd_step(w, a.G[idx], a.V ? a.V + idx : nullptr, a.sgd);
+        w = sgd_step(w, gv[i], a.V ? &vv[i] : nullptr, a.sgd);
         a.master[idx] = w;
+        if (a.V) a.V[idx] = vv[i];
       }
       if (a.zero_g) a.G[idx] = 0.f;
       if (wp) st_f32<T>(wp, idx, w);
-      v = a.gamma ? a.gamma[o] * w : w;
+      v = a.gamma ? gam[i] * w : w;
       st_f32<T>(wf, (int64_t)o * a.ldf + (int64_t)t * a.C + c, v);
     }
     tile[ty + i * 4][tx] = v;
