@@ -58,22 +58,45 @@ __device__ __forceinline__ uint4 load_chunk_f32(const float* src) {
   }
 }
 
-// Epilogue of one output element of a forward (bias, residual, ReLU) or data-gradient
-// (addend, accumulate, ReLU mask) contraction.
+// Epilogue of one output element of a forward (bias, residual, ReLU) or data-gradient (addend, accumulate,
+// ReLU mask) contraction, in two steps: what it reads from memory, then the arithmetic and the store.  A tile
+// requests the operands of ALL its elements before the first store: a store may alias the later loads for all
+// the compiler knows, so element by element every load would wait for the store before it and the epilogue
+// would be one memory round trip per element.
+struct EpiOperand {
+  float a;     // forward: residual; data gradient: addend (+ the old output value when accumulating)
+  float mask;  // data gradient: the ReLU argument (1 when there is no mask)
+};
 template <typename T>
-__device__ __forceinline__ void store_result(const GemmProb& P, int r, int c, float val, float bias) {
+__device__ __forceinline__ EpiOperand load_epilogue_operand(const GemmProb& P, int r, int c, bool inb) {
+  using E = LT<T>;
+  EpiOperand e{0.f, 1.f};
+  if (!inb) return e;
+  const int64_t o = (int64_t)r * P.ldo + c;
+  if (P.epi == EPI_FWD) {
+    if (P.aux1) e.a = E::to_f32(static_cast<const T*>(P.aux1)[o]);
+  } else {
+    // (val + addend) + old in the single-step form; here addend + old first: both are T values, their fp32 sum is
+    // exact unless they differ by more than 2^16 in magnitude, and the tolerance of the result is that of a T value
+    if (P.aux0) e.a = E::to_f32(static_cast<const T*>(P.aux0)[o]);
+    if (P.flags & GF_ACCUM) e.a += E::to_f32(static_cast<const T*>(P.out)[o]);
+    if (P.aux1) e.mask = E::to_f32(static_cast<const T*>(P.aux1)[o]);
+  }
+  return e;
+}
+template <typename T>
+__device__ __forceinline__ void store_result(const GemmProb& P, int r, int c, float val, float bias, const EpiOperand& e) {
   using E = LT<T>;
   const int64_t o = (int64_t)r * P.ldo + c;
   if (P.epi == EPI_FWD) {
     val += bias;
-    if (P.aux1) val += E::to_f32(static_cast<const T*>(P.aux1)[o]);
+    val += e.a;
     if (P.flags & GF_RELU) val = fmaxf(val, 0.f);
     if (P.flags & GF_OUT_F32) static_cast<float*>(P.out)[o] = val;
     else static_cast<T*>(P.out)[o] = E::from_f32(val);
   } else {
-    if (P.aux0) val += E::to_f32(static_cast<const T*>(P.aux0)[o]);
-    if (P.flags & GF_ACCUM) val += E::to_f32(static_cast<T*>(P.out)[o]);
-    if (P.aux1 && !(E::to_f32(static_cast<const T*>(P.aux1)[o]) > 0.f)) val = 0.f;
+    val += e.a;
+    if (!(e.mask > 0.f)) val = 0.f;
     static_cast<T*>(P.out)[o] = E::from_f32(val);
   }
 }
@@ -249,15 +272,26 @@ __device__ __forceinline__ void skinny_tile(const GemmBatch& batch, const GemmPr
       }
     }
   }
+  EpiOperand eo[NI][16];
+  float bias[NI];
 #pragma unroll
   for (int j = 0; j < NI; ++j) {
     const int c = col0 + wn * (BN / 2) + j * 32 + (lane & 31);
-    const float bias = (P.epi == EPI_FWD && P.aux0 != nullptr && c < P.N) ? static_cast<const float*>(P.aux0)[c] : 0.f;
+    bias[j] = (P.epi == EPI_FWD && P.aux0 != nullptr && c < P.N) ? static_cast<const float*>(P.aux0)[c] : 0.f;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+      const int r = row0 + wm * 32 + (v >> 2) * 8 + (lane >> 5) * 4 + (v & 3);
+      eo[j][v] = load_epilogue_operand<T>(P, r, c, r < P.M && c < P.N);
+    }
+  }
+#pragma unroll
+  for (int j = 0; j < NI; ++j) {
+    const int c = col0 + wn * (BN / 2) + j * 32 + (lane & 31);
 #pragma unroll
     for (int v = 0; v < 16; ++v) {
       const int r = row0 + wm * 32 + (v >> 2) * 8 + (lane >> 5) * 4 + (v & 3);
       if (r >= P.M || c >= P.N) continue;
-      store_result<T>(P, r, c, acc[j][v], bias);
+      store_result<T>(P, r, c, acc[j][v], bias[j], eo[j][v]);
     }
   }
 }
@@ -408,12 +442,18 @@ __device__ __forceinline__ void thin_tile(const GemmBatch& batch, const GemmProb
       for (int q = 0; q < 4; ++q) vals[q] += part[q];
     }
   }
+  EpiOperand eo[4];
+#pragma unroll
+  for (int q = 0; q < 4; ++q) {
+    const int r = wave * 8 + g * 4 + q;
+    eo[q] = load_epilogue_operand<T>(P, r, c, !ce && r < P.M && c < P.N);
+  }
 #pragma unroll
   for (int q = 0; q < 4; ++q) {
     const float val = vals[q];
     const int r = wave * 8 + g * 4 + q;
     if (!ce) {
-      if (r < P.M && c < P.N) store_result<T>(P, r, c, val, bias);
+      if (r < P.M && c < P.N) store_result<T>(P, r, c, val, bias, eo[q]);
       continue;
     }
     // Loss head on the logits row this half wavefront holds (one class per lane, N <= 32):
@@ -911,7 +951,7 @@ __device__ __forceinline__ void dw_run(const GemmBatch& batch, const GemmProb& P
 // data-gradient tiles (skinny or thin) and weight-gradient tiles (dw), so the short read-
 // modify-write tiles fill the machine while the long weight-streaming tiles run.
 template <typename T, int BN, bool THIN>
-__global__ __launch_bounds__(256) void linear_tick_kernel(const GemmBatch batch) {
+__device__ __forceinline__ void linear_tick_body(const GemmBatch& batch) {
   using E = LT<T>;
   constexpr int SK_BYTES = (64 + BN) * (E::SLAB + E::VEC) * (int)sizeof(T);
   // operand tiles of the weight gradient; in the wide kernel also the new-weight tile of a pipelined run with a fused SGD step
@@ -979,16 +1019,32 @@ __global__ __launch_bounds__(256) void linear_tick_kernel(const GemmBatch batch)
   }
 }
 
+// The bf16 kernel is held to three wavefronts per SIMD (168 registers): left alone the allocator takes 176, one
+// workgroup per CU less, which costs the weight-streaming launches 6 % (cfg5 19.5 -> 18.2 ms per step).  The fp32
+// kernel needs more registers and keeps two.
+template <typename T, int BN, bool THIN>
+__global__ __launch_bounds__(256) void linear_tick_kernel(const GemmBatch batch) {
+  linear_tick_body<T, BN, THIN>(batch);
+}
+template <int BN, bool THIN>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 3))) void linear_tick_kernel_bf16(const GemmBatch batch) {
+  linear_tick_body<uint16_t, BN, THIN>(batch);
+}
+template <typename T, int BN, bool THIN>
+static void launch_tick_kernel(const GemmBatch& b, dim3 grid, hipStream_t stream) {
+  if constexpr (sizeof(T) == 2) hipLaunchKernelGGL((linear_tick_kernel_bf16<BN, THIN>), grid, dim3(256), 0, stream, b);
+  else hipLaunchKernelGGL((linear_tick_kernel<T, BN, THIN>), grid, dim3(256), 0, stream, b);
+}
+
 namespace {
 template <typename T>
 void launch_variant(const GemmBatch& b, bool wide, bool thin, dim3 grid, hipStream_t stream) {
-  const dim3 block(256);
   if (thin) {
-    if (wide) hipLaunchKernelGGL((linear_tick_kernel<T, 128, true>), grid, block, 0, stream, b);
-    else hipLaunchKernelGGL((linear_tick_kernel<T, 64, true>), grid, block, 0, stream, b);
+    if (wide) launch_tick_kernel<T, 128, true>(b, grid, stream);
+    else launch_tick_kernel<T, 64, true>(b, grid, stream);
   } else {
-    if (wide) hipLaunchKernelGGL((linear_tick_kernel<T, 128, false>), grid, block, 0, stream, b);
-    else hipLaunchKernelGGL((linear_tick_kernel<T, 64, false>), grid, block, 0, stream, b);
+    if (wide) launch_tick_kernel<T, 128, false>(b, grid, stream);
+    else launch_tick_kernel<T, 64, false>(b, grid, stream);
   }
 }
 }  // namespace
