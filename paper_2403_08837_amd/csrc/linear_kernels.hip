@@ -523,14 +523,42 @@ __device__ __forceinline__ void dw_tile(const GemmBatch& batch, const GemmProb& 
       const int r = n0 + i * 32 + (v >> 2) * 8 + (lane >> 5) * 4 + (v & 3);
       const bool inb = r < Nn && gc < Kk;
       const int64_t idx = (int64_t)r * P.ldo + gc;
-      float g0 = (rmw && inb) ? G[idx] : 0.f;
-      if (upd && inb) {
-        const float w = U.master[idx];
-        const float gw = g0 * U.sgd.inv_n + U.sgd.wd * w;
-        g0 = mom ? U.sgd.momentum * U.V[idx] + gw : w - U.sgd.lr * gw;
-      }
-      gold[i * 16 + v] = g0;
+      gold[i * 16 + v] = (rmw && inb) ? G[idx] : 0.f;
     }
+  if (upd) {
+    // All master weights (and velocities) of the tile are requested before the first one is used: read inside
+    // a per-element branch, each was waited for before the next was issued, 32 memory round trips in a row.
+    // Outside the matrix everything reads 0 and combines to 0.
+    float wm[16 * NI2];
+#pragma unroll
+    for (int i = 0; i < NI2; ++i)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        const int r = n0 + i * 32 + (v >> 2) * 8 + (lane >> 5) * 4 + (v & 3);
+        wm[i * 16 + v] = (r < Nn && gc < Kk) ? U.master[(int64_t)r * P.ldo + gc] : 0.f;
+      }
+    if (mom) {
+      float vm[16 * NI2];
+#pragma unroll
+      for (int i = 0; i < NI2; ++i)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          const int r = n0 + i * 32 + (v >> 2) * 8 + (lane >> 5) * 4 + (v & 3);
+          vm[i * 16 + v] = (r < Nn && gc < Kk) ? U.V[(int64_t)r * P.ldo + gc] : 0.f;
+        }
+#pragma unroll
+      for (int e = 0; e < 16 * NI2; ++e) {
+        const float gw = gold[e] * U.sgd.inv_n + U.sgd.wd * wm[e];
+        gold[e] = U.sgd.momentum * vm[e] + gw;
+      }
+    } else {
+#pragma unroll
+      for (int e = 0; e < 16 * NI2; ++e) {
+        const float gw = gold[e] * U.sgd.inv_n + U.sgd.wd * wm[e];
+        gold[e] = wm[e] - U.sgd.lr * gw;
+      }
+    }
+  }
 
   v16f_t acc[NI2];
 #pragma unroll
@@ -671,6 +699,20 @@ __device__ __forceinline__ void dw_tile(const GemmBatch& batch, const GemmProb& 
   constexpr int PW = TK + (sizeof(T) == 2 ? 2 : 1);  // LDS pitch of the new-weight tile [TN][TK]
   T* Ws = reinterpret_cast<T*>(smem);
   __syncthreads();  // the operand tiles in LDS are no longer read
+  // (parameters and pointers in locals: read through the descriptor they are fetched again after every store)
+  const float lr = U.sgd.lr, inv_n = U.sgd.inv_n, step = U.sgd.lr * U.sgd.inv_n;
+  float* const master = U.master;
+  float* const Vel = U.V;
+  float wm[16 * NI2];
+  if (mom) {  // the master weights again, all requested before the first store
+#pragma unroll
+    for (int i = 0; i < NI2; ++i)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        const int r = n0 + i * 32 + (v >> 2) * 8 + (lane >> 5) * 4 + (v & 3);
+        wm[i * 16 + v] = (r < Nn && gc < Kk) ? master[(int64_t)r * P.ldo + gc] : 0.f;
+      }
+  }
 #pragma unroll
   for (int i = 0; i < NI2; ++i)
 #pragma unroll
@@ -681,13 +723,13 @@ __device__ __forceinline__ void dw_tile(const GemmBatch& batch, const GemmProb& 
       if (r < Nn && gc < Kk) {
         const int64_t idx = (int64_t)r * P.ldo + gc;
         if (mom) {
-          const float vel = gold[i * 16 + v] + acc[i][v] * U.sgd.inv_n;
-          U.V[idx] = vel;
-          w = U.master[idx] - U.sgd.lr * vel;
+          const float vel = gold[i * 16 + v] + acc[i][v] * inv_n;
+          Vel[idx] = vel;
+          w = wm[i * 16 + v] - lr * vel;
         } else {
-          w = gold[i * 16 + v] - (U.sgd.lr * U.sgd.inv_n) * acc[i][v];
+          w = gold[i * 16 + v] - step * acc[i][v];
         }
-        U.master[idx] = w;
+        master[idx] = w;
       }
       Ws[rl * PW + wave * 32 + (lane & 31)] = E::from_f32(w);
     }
@@ -754,7 +796,8 @@ constexpr int DW_RUN = 2;  // 2, 4 and 8 measured within 2 % of each other on 40
 // upd_ok: a problem with a fused SGD step may take this path (wide kernel, no momentum)
 __host__ __device__ __forceinline__ int dw_run_length(const GemmProb& p, int vec, bool upd_ok) {
   const bool whole = p.lda % vec == 0 && p.ldb % vec == 0 && p.M % vec == 0 && p.N % vec == 0;
-  return ((!p.upd || upd_ok) && whole && !(p.flags & GF_GROUP) && p.K <= 64 && p.N >= 8 * 128 && p.M >= 512) ? DW_RUN : 1;
+  const bool off32 = (int64_t)p.M * p.ldo < (1ll << 30);  // accumulator elements are addressed by 32-bit byte offsets
+  return ((!p.upd || upd_ok) && whole && off32 && !(p.flags & GF_GROUP) && p.K <= 64 && p.N >= 8 * 128 && p.M >= 512) ? DW_RUN : 1;
 }
 
 template <typename T, bool UPD>
@@ -782,10 +825,25 @@ __device__ __forceinline__ void dw_run(const GemmBatch& batch, const GemmProb& P
   constexpr int DCH = TN / VEC, XCH = TK / VEC;
   constexpr int ND = MB * DCH / 256, NX = MB * XCH / 256;
 
+  // (parameters and pointers of the SGD step in locals: read through the descriptor they are fetched again after every store)
+  const float upd_lr = UPD ? U.sgd.lr : 0.f, upd_inv_n = UPD ? U.sgd.inv_n : 0.f, upd_wd = UPD ? U.sgd.wd : 0.f;
+  const float upd_step = upd_lr * upd_inv_n;
+  float* const upd_master = UPD ? U.master : nullptr;
   float gold[2][16 * NI2];
   uint4 rx[NX];
   // old accumulator values; with a fused SGD step combined with the master weights so that only this
   // micro-batch's share is missing: w' = [w - lr*(Gold/N + wd*w)] - (lr/N)*acc
+  // Element (r, c) of an accumulator-shaped array at a 32-bit byte offset from its (uniform) base: the row
+  // offsets of a tile then cost one register each where 64-bit indices cost two, which is what decides
+  // whether the update tiles fit the kernel's register budget.  dw_run_length admits only matrices below 4 GiB.
+  const uint32_t ldo4 = (uint32_t)P.ldo * 4u;
+  auto at32 = [&](float* base, int r, int c) -> float* {
+    return reinterpret_cast<float*>(reinterpret_cast<char*>(base) + ((uint32_t)r * ldo4 + (uint32_t)c * 4u));
+  };
+  // Accumulator tile; with a fused SGD step finish_gold then combines it with the master weights.  Every element
+  // of an array is requested before the first value is used: with the master weight read inside a per-element
+  // branch the compiler waited for each one before it issued the next, 32 memory round trips in a row per tile.
+  // (Outside the matrix both reads give 0 and so does the combination.)
   auto load_gold = [&](float* g, int k0) {
     const int gc = k0 + wave * 32 + (lane & 31);
 #pragma unroll
@@ -793,15 +851,26 @@ __device__ __forceinline__ void dw_run(const GemmBatch& batch, const GemmProb& P
 #pragma unroll
       for (int v = 0; v < 16; ++v) {
         const int r = n0 + i * 32 + (v >> 2) * 8 + (lane >> 5) * 4 + (v & 3);
-        const bool inb = r < Nn && gc < Kk;
-        const int64_t idx = (int64_t)r * P.ldo + gc;
-        float g0 = (rmw && inb) ? G[idx] : 0.f;
-        if (UPD && inb) {
-          const float w = U.master[idx];
-          g0 = w - U.sgd.lr * (g0 * U.sgd.inv_n + U.sgd.wd * w);
-        }
-        g[i * 16 + v] = g0;
+        g[i * 16 + v] = (rmw && r < Nn && gc < Kk) ? *at32(G, r, gc) : 0.f;
       }
+  };
+  auto finish_gold = [&](float* g, int k0) {
+    if constexpr (UPD) {
+      const int gc = k0 + wave * 32 + (lane & 31);
+      float wm[16 * NI2];
+#pragma unroll
+      for (int i = 0; i < NI2; ++i)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          const int r = n0 + i * 32 + (v >> 2) * 8 + (lane >> 5) * 4 + (v & 3);
+          wm[i * 16 + v] = (r < Nn && gc < Kk) ? *at32(upd_master, r, gc) : 0.f;
+        }
+#pragma unroll
+      for (int e = 0; e < 16 * NI2; ++e) {
+        const float w = wm[e];
+        g[e] = w - upd_lr * (g[e] * upd_inv_n + upd_wd * w);
+      }
+    }
   };
   auto load_x = [&](int k0) {
 #pragma unroll
@@ -843,6 +912,7 @@ __device__ __forceinline__ void dw_run(const GemmBatch& batch, const GemmProb& P
     }
     store_x();
   }
+  finish_gold(gold[0], tk0 * TK);  // after the staging: both together need more registers than the kernel has
   __syncthreads();
   float bsum = 0.f;  // bias gradient of column n0 + tid (first column tile of the matrix only)
   if (tk0 == 0 && P.aux2 != nullptr && tid < TN)
@@ -856,6 +926,7 @@ __device__ __forceinline__ void dw_run(const GemmBatch& batch, const GemmProb& P
     // next tile's accumulator and X tile are on their way while this one is contracted and written back
     if (t + 1 < nrun) {
       load_gold(gold[(t + 1) & 1], k0 + TK);
+      finish_gold(gold[(t + 1) & 1], k0 + TK);
       load_x(k0 + TK);
     }
     v16f_t acc[NI2];
@@ -888,13 +959,13 @@ __device__ __forceinline__ void dw_run(const GemmBatch& batch, const GemmProb& P
         const int rl = i * 32 + (v >> 2) * 8 + g * 4 + (v & 3);
         const int r = n0 + rl;
         if constexpr (!UPD) {
-          if (r < Nn && gc < Kk) G[(int64_t)r * P.ldo + gc] = gcur[i * 16 + v] + acc[i][v];
+          if (r < Nn && gc < Kk) *at32(G, r, gc) = gcur[i * 16 + v] + acc[i][v];
         } else {
           // this contraction completes the sum over the micro-batches: the SGD step on the master weights
           float w = 0.f;
           if (r < Nn && gc < Kk) {
-            w = gcur[i * 16 + v] - (U.sgd.lr * U.sgd.inv_n) * acc[i][v];
-            U.master[(int64_t)r * P.ldo + gc] = w;
+            w = gcur[i * 16 + v] - upd_step * acc[i][v];
+            *at32(upd_master, r, gc) = w;
           }
           Ws[rl * PW + wave * 32 + l31] = E::from_f32(w);
         }
