@@ -475,39 +475,62 @@ __device__ __forceinline__ void bmm_put4(float* dst, int stride, float4 v) {
   dst[0] = v.x; dst[stride] = v.y; dst[2 * stride] = v.z; dst[3 * stride] = v.w;
 }
 
-// tile[r][k] = op[row0 + r][k0 + k] for r < 64, k < 32, zero outside rows x K.
+// tile[r][k] = op[row0 + r][k0 + k] for r < 64, k < 32, zero outside rows x K, in two steps: bmm_fetch requests a
+// thread's two 4-element pieces (vector modes 1 and 2), bmm_store writes them to LDS (mode 0, element by element
+// with arbitrary strides, does all its work in bmm_store).  Split so that the pieces of both operands, and of the
+// next slab, are in flight together: fetched and stored piece by piece, a slab was four memory round trips in a row.
 template <typename T>
-__device__ __forceinline__ void bmm_stage(T* tile, const T* base, int64_t s_row, int64_t s_k, int mode, int row0, int rows,
-                                          int k0, int K) {
-  constexpr int PITCH = BmmTile<T>::PITCH;
+__device__ __forceinline__ void bmm_fetch(typename BmmTile<T>::vec4 (&v)[2], const T* base, int64_t s_row, int64_t s_k, int mode,
+                                          int row0, int rows, int k0, int K) {
   typedef typename BmmTile<T>::vec4 vec4;
   if (mode == 1) {
-    for (int e = threadIdx.x; e < 512; e += 256) {
-      const int r = e >> 3, k = (e & 7) * 4;
-      vec4 v = {};
-      if (row0 + r < rows && k0 + k < K) v = *reinterpret_cast<const vec4*>(base + (int64_t)(row0 + r) * s_row + (k0 + k));
-      bmm_put4(tile + r * PITCH + k, 1, v);
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+      const int e = threadIdx.x + 256 * i, r = e >> 3, k = (e & 7) * 4;
+      v[i] = vec4{};
+      if (row0 + r < rows && k0 + k < K) v[i] = *reinterpret_cast<const vec4*>(base + (int64_t)(row0 + r) * s_row + (k0 + k));
     }
   } else if (mode == 2) {
-    for (int e = threadIdx.x; e < 512; e += 256) {
-      const int k = e >> 4, r = (e & 15) * 4;
-      vec4 v = {};
-      if (row0 + r < rows && k0 + k < K) v = *reinterpret_cast<const vec4*>(base + (row0 + r) + (int64_t)(k0 + k) * s_k);
-      bmm_put4(tile + r * PITCH + k, PITCH, v);
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+      const int e = threadIdx.x + 256 * i, k = e >> 4, r = (e & 15) * 4;
+      v[i] = vec4{};
+      if (row0 + r < rows && k0 + k < K) v[i] = *reinterpret_cast<const vec4*>(base + (row0 + r) + (int64_t)(k0 + k) * s_k);
+    }
+  }
+}
+template <typename T>
+__device__ __forceinline__ void bmm_store(T* tile, const typename BmmTile<T>::vec4 (&v)[2], const T* base, int64_t s_row, int64_t s_k,
+                                          int mode, int row0, int rows, int k0, int K) {
+  constexpr int PITCH = BmmTile<T>::PITCH;
+  if (mode == 1) {
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+      const int e = threadIdx.x + 256 * i, r = e >> 3, k = (e & 7) * 4;
+      bmm_put4(tile + r * PITCH + k, 1, v[i]);
+    }
+  } else if (mode == 2) {
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+      const int e = threadIdx.x + 256 * i, k = e >> 4, r = (e & 15) * 4;
+      bmm_put4(tile + r * PITCH + k, PITCH, v[i]);
     }
   } else {
     for (int e = threadIdx.x; e < 2048; e += 256) {
       const int r = e >> 5, k = e & 31;
-      T v = T(0);
-      if (row0 + r < rows && k0 + k < K) v = base[(int64_t)(row0 + r) * s_row + (int64_t)(k0 + k) * s_k];
-      tile[r * PITCH + k] = v;
+      T x = T(0);
+      if (row0 + r < rows && k0 + k < K) x = base[(int64_t)(row0 + r) * s_row + (int64_t)(k0 + k) * s_k];
+      tile[r * PITCH + k] = x;
     }
   }
 }
 
-template <typename T>
+// MODES: 4 * mode_a + mode_b for the four pairs of vector modes (straight-line staging code, which lets the
+// next slab's requests stay in flight across the contraction), or -1: the modes are read from the arguments.
+template <typename T, int MODES>
 __global__ __launch_bounds__(256) void bmm_kernel(const BmmArgs a) {
   constexpr int PITCH = BmmTile<T>::PITCH;
+  const int mode_a = MODES >= 0 ? MODES / 4 : a.mode_a, mode_b = MODES >= 0 ? MODES % 4 : a.mode_b;
   __shared__ __attribute__((aligned(16))) T As[64 * PITCH];
   __shared__ __attribute__((aligned(16))) T Bs[64 * PITCH];
   const int z = blockIdx.z, sample = z / a.heads, head = z % a.heads;
@@ -521,10 +544,17 @@ __global__ __launch_bounds__(256) void bmm_kernel(const BmmArgs a) {
   bmm_v16f acc;
 #pragma unroll
   for (int v = 0; v < 16; ++v) acc[v] = 0.f;
+  typename BmmTile<T>::vec4 ra[2], rb[2];
+  bmm_fetch<T>(ra, Ap, a.A.s_row, a.A.s_k, mode_a, i0, a.M, 0, a.K);
+  bmm_fetch<T>(rb, Bp, a.B.s_row, a.B.s_k, mode_b, j0, a.N, 0, a.K);
   for (int k0 = 0; k0 < a.K; k0 += 32) {
-    bmm_stage<T>(As, Ap, a.A.s_row, a.A.s_k, a.mode_a, i0, a.M, k0, a.K);
-    bmm_stage<T>(Bs, Bp, a.B.s_row, a.B.s_k, a.mode_b, j0, a.N, k0, a.K);
+    bmm_store<T>(As, ra, Ap, a.A.s_row, a.A.s_k, mode_a, i0, a.M, k0, a.K);
+    bmm_store<T>(Bs, rb, Bp, a.B.s_row, a.B.s_k, mode_b, j0, a.N, k0, a.K);
     __syncthreads();
+    if (k0 + 32 < a.K) {  // the next slab's pieces are on their way while this one is contracted
+      bmm_fetch<T>(ra, Ap, a.A.s_row, a.A.s_k, mode_a, i0, a.M, k0 + 32, a.K);
+      bmm_fetch<T>(rb, Bp, a.B.s_row, a.B.s_k, mode_b, j0, a.N, k0 + 32, a.K);
+    }
     if (live) {
       const T* ar = As + (wm * 32 + l31) * PITCH;
       const T* br = Bs + (wn * 32 + l31) * PITCH;
@@ -570,7 +600,14 @@ static hipError_t launch_bmm(BmmArgs a, int batch, int dtype, hipStream_t stream
   a.mode_a = bmm_mode(a.A, a.M, a.K, eb);
   a.mode_b = bmm_mode(a.B, a.N, a.K, eb);
   dim3 grid((a.N + 63) / 64, (a.M + 63) / 64, batch);
-  CDP_TDISPATCH(dtype, hipLaunchKernelGGL((bmm_kernel<T>), grid, dim3(256), 0, stream, a));
+  const int modes = (a.mode_a >= 1 && a.mode_b >= 1) ? 4 * a.mode_a + a.mode_b : -1;
+  switch (modes) {
+    case 5: CDP_TDISPATCH(dtype, hipLaunchKernelGGL((bmm_kernel<T, 5>), grid, dim3(256), 0, stream, a)); break;
+    case 6: CDP_TDISPATCH(dtype, hipLaunchKernelGGL((bmm_kernel<T, 6>), grid, dim3(256), 0, stream, a)); break;
+    case 9: CDP_TDISPATCH(dtype, hipLaunchKernelGGL((bmm_kernel<T, 9>), grid, dim3(256), 0, stream, a)); break;
+    case 10: CDP_TDISPATCH(dtype, hipLaunchKernelGGL((bmm_kernel<T, 10>), grid, dim3(256), 0, stream, a)); break;
+    default: CDP_TDISPATCH(dtype, hipLaunchKernelGGL((bmm_kernel<T, -1>), grid, dim3(256), 0, stream, a)); break;
+  }
   return hipGetLastError();
 }
 
