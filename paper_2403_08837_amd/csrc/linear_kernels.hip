@@ -572,19 +572,45 @@ __device__ __forceinline__ void dw_tile(const GemmBatch& batch, const GemmProb& 
   // lie in buffers of their own
   const bool grouped = (flags & GF_GROUP) != 0;
   const int rows = grouped ? P.g.pad : Mb, nmem = grouped ? Mb / P.g.pad : 1;
-  for (int mem = 0; mem < nmem; ++mem) {
-  const T* __restrict__ Dp = static_cast<const T*>(dw_member(P, mem, 0));
-  const T* __restrict__ Xp = static_cast<const T*>(dw_member(P, mem, 1));
-  for (int m0 = 0; m0 < rows; m0 += MB) {
-    if (mem > 0 || m0 > 0) __syncthreads();
-    // 2. stage dY[m0.., n0..n0+TN-1] and X[m0.., k0..k0+127] as they lie in memory.  All of a thread's chunks
-    // are requested before the first one is written to LDS: requested one by one (load, LDS store, load, ...)
-    // the six round trips to L2 of a bf16 tile cost 30 us of a 280 us launch of 16384 tiles.
-    constexpr int DCH = TN / VEC, XCH = TK / VEC;  // chunks per row
-    constexpr int ND = MB * DCH / 256, NX = MB * XCH / 256;
-    static_assert(ND * 256 == MB * DCH && NX * 256 == MB * XCH, "whole chunks per thread");
-    if (dvec && xvec && (Nn % VEC) == 0 && (Kk % VEC) == 0) {  // every chunk is whole: inside or outside the matrices
-      uint4 rd[ND], rx[NX];
+  constexpr int DCH = TN / VEC, XCH = TK / VEC;  // chunks per row
+  constexpr int ND = MB * DCH / 256, NX = MB * XCH / 256;
+  static_assert(ND * 256 == MB * DCH && NX * 256 == MB * XCH, "whole chunks per thread");
+  // 3. contraction over the batch rows of the staged slab; fragments are read transposed out of LDS
+  auto contract = [&]() {
+    const int g = lane >> 5, l31 = lane & 31;
+    if constexpr (sizeof(T) == 2) {
+#pragma unroll
+      for (int kk = 0; kk < MB; kk += 16) {
+        const uint4 bv = frag_tr_bf16(Xs, PX, kk, wave * 32, lane);
+#pragma unroll
+        for (int i = 0; i < NI2; ++i) acc[i] = mfma_bf16(frag_tr_bf16(Ds, PD, kk, i * 32, lane), bv, acc[i]);
+      }
+    } else {
+#pragma unroll 8
+      for (int kk = 0; kk < MB; kk += 2) {
+        const float bv = Xs[(kk + g) * PX + wave * 32 + l31];
+#pragma unroll
+        for (int i = 0; i < NI2; ++i)
+          acc[i] = __builtin_amdgcn_mfma_f32_32x32x2f32(Ds[(kk + g) * PD + i * 32 + l31], bv, acc[i], 0, 0, 0);
+      }
+    }
+    if (tk == 0 && P.aux2 != nullptr && tid < TN) {
+      for (int m = 0; m < MB; ++m) bsum += E::to_f32(Ds[m * PD + tid]);
+    }
+  };
+  if (dvec && xvec && (Nn % VEC) == 0 && (Kk % VEC) == 0) {
+    // 2. every chunk is whole (inside or outside the matrices): slabs of 64 batch rows of dY[.., n0..n0+TN-1] and
+    // X[.., k0..k0+127] are staged as they lie in memory, one slab ahead: the next slab (of this member or of the
+    // next one of the group) is requested before the current one is contracted, so a reduction over several
+    // slabs is not one memory round trip per slab.  All of a thread's chunks are requested before the first one
+    // is written to LDS (requested one by one, the six round trips of a bf16 tile cost 30 us of a 280 us launch
+    // of 16384 tiles).
+    const int per = (rows + MB - 1) / MB, nit = nmem * per;
+    uint4 rd[ND], rx[NX];
+    auto fetch = [&](int it) {
+      const int mem = it / per, m0 = (it - mem * per) * MB;
+      const T* __restrict__ Dp = static_cast<const T*>(dw_member(P, mem, 0));
+      const T* __restrict__ Xp = static_cast<const T*>(dw_member(P, mem, 1));
 #pragma unroll
       for (int i = 0; i < ND; ++i) {
         const int id = tid + 256 * i, m = id / DCH, c = (id % DCH) * VEC;
@@ -597,6 +623,10 @@ __device__ __forceinline__ void dw_tile(const GemmBatch& batch, const GemmProb& 
         rx[i] = (m0 + m < rows && k0 + c < Kk) ? *reinterpret_cast<const uint4*>(Xp + (int64_t)(m0 + m) * P.ldb + k0 + c)
                                               : make_uint4(0, 0, 0, 0);
       }
+    };
+    fetch(0);
+    for (int it = 0; it < nit; ++it) {
+      if (it > 0) __syncthreads();
 #pragma unroll
       for (int i = 0; i < ND; ++i) {
         const int id = tid + 256 * i, m = id / DCH, c = (id % DCH) * VEC;
@@ -615,7 +645,17 @@ __device__ __forceinline__ void dw_tile(const GemmBatch& batch, const GemmProb& 
         dst[0] = tmp.h[0];
         dst[1] = tmp.h[1];
       }
-    } else {
+      __syncthreads();
+      if (it + 1 < nit) fetch(it + 1);
+      contract();
+    }
+  } else {
+  for (int mem = 0; mem < nmem; ++mem) {
+  const T* __restrict__ Dp = static_cast<const T*>(dw_member(P, mem, 0));
+  const T* __restrict__ Xp = static_cast<const T*>(dw_member(P, mem, 1));
+  for (int m0 = 0; m0 < rows; m0 += MB) {
+    if (mem > 0 || m0 > 0) __syncthreads();
+    {
       for (int id = tid; id < MB * DCH; id += 256) {
         const int m = id / DCH, c = (id % DCH) * VEC;
         Chunk16<T> tmp;
@@ -654,27 +694,8 @@ __device__ __forceinline__ void dw_tile(const GemmBatch& batch, const GemmProb& 
       }
     }
     __syncthreads();
-    // 3. contraction over the batch rows; fragments are read transposed out of LDS
-    const int g = lane >> 5, l31 = lane & 31;
-    if constexpr (sizeof(T) == 2) {
-#pragma unroll
-      for (int kk = 0; kk < MB; kk += 16) {
-        const uint4 bv = frag_tr_bf16(Xs, PX, kk, wave * 32, lane);
-#pragma unroll
-        for (int i = 0; i < NI2; ++i) acc[i] = mfma_bf16(frag_tr_bf16(Ds, PD, kk, i * 32, lane), bv, acc[i]);
-      }
-    } else {
-#pragma unroll 8
-      for (int kk = 0; kk < MB; kk += 2) {
-        const float bv = Xs[(kk + g) * PX + wave * 32 + l31];
-#pragma unroll
-        for (int i = 0; i < NI2; ++i)
-          acc[i] = __builtin_amdgcn_mfma_f32_32x32x2f32(Ds[(kk + g) * PD + i * 32 + l31], bv, acc[i], 0, 0, 0);
-      }
-    }
-    if (tk == 0 && P.aux2 != nullptr && tid < TN) {
-      for (int m = 0; m < MB; ++m) bsum += E::to_f32(Ds[m * PD + tid]);
-    }
+    contract();
+  }
   }
   }
 
