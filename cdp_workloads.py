@@ -348,6 +348,14 @@ def get_config(name: str) -> Config:
         c = get_config("resnet18_mini")
         c.name, c.dtype = "resnet18_mini_f32", F32
         return c
+    if name == "resnet18_odd_f32":  # 9x9 images: image rows of 27 elements are not whole 16-byte pieces, maps of 9, 5, 3, 2
+        c = get_config("resnet18_mini")
+        c.name, c.dtype, c.in_shape, c.B = "resnet18_odd_f32", F32, (9, 9, 3), 3
+        return c
+    if name == "resnet18_odd":
+        c = get_config("resnet18_odd_f32")
+        c.name, c.dtype = "resnet18_odd", BF16
+        return c
     if name == "resnet50_mini":  # 16 bottleneck stages at 1/8 width, 32x32 images
         return Config("resnet50_mini", _resnet50(20, widths=(8, 16, 32, 64)), (32, 32, 3), 20,
                       N=8, B=2, dtype=BF16, lr=0.05, steps=4, init_gain_last_affine=0.25)

@@ -189,14 +189,14 @@ def test_single_microbatch_and_zero_lr():
             assert np.array_equal(a, w)
 
 
-@pytest.mark.parametrize("name", ["resnet18_mini_f32", "resnet50_mini_f32"])
+@pytest.mark.parametrize("name", ["resnet18_mini_f32", "resnet50_mini_f32", "resnet18_odd_f32"])
 @pytest.mark.parametrize("rule", [wl.RULE_DP, wl.RULE_V2])
 def test_resnet_mini_fp32(name, rule):
     cfg = wl.get_config(name)
     check(cfg, rule, cfg.steps)
 
 
-@pytest.mark.parametrize("name", ["resnet18_mini", "resnet50_mini"])
+@pytest.mark.parametrize("name", ["resnet18_mini", "resnet50_mini", "resnet18_odd"])
 def test_resnet_mini_bf16(name):
     cfg = wl.get_config(name)
     check(cfg, wl.RULE_V2, cfg.steps)

@@ -43,7 +43,7 @@ def _dry(cfg, rule, T, dp_batched=False, dw_group=1):
     return tr
 
 
-@pytest.mark.parametrize("name", ["mlp_mini", "mlp_odd", "cfg1", "cfg2", "cfg3", "cfg4", "cfg5", "resnet50_mini", "vit_mini", "vit_odd", "mlp_longk",
+@pytest.mark.parametrize("name", ["mlp_mini", "mlp_odd", "cfg1", "cfg2", "cfg3", "cfg4", "cfg5", "resnet50_mini", "resnet18_odd", "vit_mini", "vit_odd", "mlp_longk",
                                   "vit_b16"])
 @pytest.mark.parametrize("rule", RULES)
 def test_trace_and_live_counts_equal_oracle(name, rule):
