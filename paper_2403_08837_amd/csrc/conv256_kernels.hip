@@ -184,22 +184,8 @@ __global__ __launch_bounds__(WAVES_M * WAVES_N * 64) void conv_gemm_dl_kernel(co
   uint16_t* outp = static_cast<uint16_t*>(P.out);
   constexpr int CPS = WTN / VEC;      // chunks per staged row
   constexpr int NCH = 32 * CPS / 64;  // chunks per lane
-  static_assert(64 % CPS == 0, "a lane keeps its columns from chunk to chunk");
 #pragma unroll
   for (int i = 0; i < MI; ++i) {
-    // The pass's own operand (forward: the residual, data gradient: the ReLU mask) of all of the lane's chunks is
-    // requested before the pass is staged: read chunk by chunk behind the previous chunk's store (which may alias
-    // it for all the compiler knows), it was one memory round trip per chunk, sixteen per tile.
-    uint4 pa[NCH];
-    if (P.aux1) {
-#pragma unroll
-      for (int t = 0; t < NCH; ++t) {
-        const int q = lane + 64 * t;
-        const int r = row0 + wm * WTM + i * 32 + q / CPS, c = col0 + wn * WTN + (q % CPS) * VEC;
-        pa[t] = (r < P.M && c < P.N) ? *reinterpret_cast<const uint4*>(static_cast<const uint16_t*>(P.aux1) + (int64_t)r * P.ldo + c)
-                                     : make_uint4(0, 0, 0, 0);
-      }
-    }
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
     __builtin_amdgcn_wave_barrier();  // the previous pass's reads are done
 #pragma unroll
@@ -226,7 +212,7 @@ __global__ __launch_bounds__(WAVES_M * WAVES_N * 64) void conv_gemm_dl_kernel(co
           for (int e = 0; e < VEC; ++e) val[e] += static_cast<const float*>(P.aux0)[c + e];
         }
         if (P.aux1) {
-          x1.v = pa[t];
+          x1.v = *reinterpret_cast<const uint4*>(static_cast<const uint16_t*>(P.aux1) + o);
 #pragma unroll
           for (int e = 0; e < VEC; ++e) val[e] += E::to_f32(x1.e[e]);
         }
@@ -246,7 +232,7 @@ __global__ __launch_bounds__(WAVES_M * WAVES_N * 64) void conv_gemm_dl_kernel(co
           for (int e = 0; e < VEC; ++e) val[e] += E::to_f32(x2.e[e]);
         }
         if (P.aux1) {
-          x1.v = pa[t];
+          x1.v = *reinterpret_cast<const uint4*>(static_cast<const uint16_t*>(P.aux1) + o);
 #pragma unroll
           for (int e = 0; e < VEC; ++e)
             if (!(E::to_f32(x1.e[e]) > 0.f)) val[e] = 0.f;
