@@ -849,7 +849,41 @@ int launch_level(cdp_ctx* c, std::vector<Item>& items) {
   }
   { int rc = flush_folds(); if (rc) return rc; }
   const int dt = c->plan.dtype;
+  // LayerNorm passes of one shape (the same layer of several stages / micro-batches) share their launches
+  for (size_t a = 0; a < items.size(); ++a) {
+    Item& first = items[a];
+    if (first.done || (first.kind != IT_LN_F && first.kind != IT_LN_B)) continue;
+    auto batchable = [&](const Item& it) {
+      return it.kind == IT_LN_F ? layernorm_batchable(it.p0, it.p2, nullptr, nullptr, it.i[1], dt)
+                                : layernorm_batchable(it.p0, it.p1, it.p5, it.p2, it.i[1], dt);
+    };
+    if (!batchable(first)) continue;
+    std::vector<Item*> grp;
+    for (size_t b = a; b < items.size() && grp.size() < (size_t)LN_BATCH_MAX; ++b) {
+      Item& it = items[b];
+      if (!it.done && it.kind == first.kind && it.i[0] == first.i[0] && it.i[1] == first.i[1] && batchable(it)) grp.push_back(&it);
+    }
+    if (grp.size() < 2) continue;
+    if (first.kind == IT_LN_F) {
+      LnFwdBatch fb;
+      fb.n = (int)grp.size();
+      for (int q = 0; q < fb.n; ++q)
+        fb.p[q] = LnFwdProb{grp[q]->p0, static_cast<const float*>(grp[q]->p1), static_cast<const float*>(grp[q]->p5), grp[q]->p2};
+      HIP_TRY(c, launch_layernorm_fwd_batch(fb, first.i[0], first.i[1], dt, c->stream));
+      c->stats.kernel_launches += 1;
+    } else {
+      LnBwdBatch bb;
+      bb.n = (int)grp.size();
+      for (int q = 0; q < bb.n; ++q)
+        bb.p[q] = LnBwdProb{grp[q]->p0, grp[q]->p1, grp[q]->p5, static_cast<const float*>(grp[q]->p3), grp[q]->p2,
+                            static_cast<float*>(grp[q]->p4), static_cast<float*>(grp[q]->p6), static_cast<float*>(grp[q]->p7)};
+      HIP_TRY(c, launch_layernorm_bwd_batch(bb, first.i[0], first.i[1], dt, c->stream));
+      c->stats.kernel_launches += 3;
+    }
+    for (Item* it : grp) it->done = true;
+  }
   for (const Item& it : items) {
+    if (it.done && (it.kind == IT_LN_F || it.kind == IT_LN_B)) continue;
     switch (it.kind) {
       case IT_STAGE_IN:
         if (it.done) continue;

@@ -273,6 +273,17 @@ hipError_t launch_gap_bwd(const void* x, const void* dy, void* dx, int B, int HW
 hipError_t launch_layernorm_fwd(const void* x, const float* gamma, const float* beta, void* y, int rows, int C, int dtype,
                                 hipStream_t stream);
 int64_t layernorm_bwd_workspace_bytes(int rows, int C);
+// The same passes for up to LN_BATCH_MAX problems of one shape in one launch each (rows that are whole 16-byte
+// chunks only: layernorm_batchable on every tensor of a problem; workspace as for launch_layernorm_bwd).
+constexpr int LN_BATCH_MAX = 8;
+struct LnFwdProb { const void* x; const float* gamma; const float* beta; void* y; };
+struct LnFwdBatch { LnFwdProb p[LN_BATCH_MAX]; int n; };
+struct LnBwdProb { const void* x; const void* dy; const void* add; const float* gamma; void* dx; float* Ggamma; float* Gbeta; float* workspace; };
+struct LnBwdBatch { LnBwdProb p[LN_BATCH_MAX]; int n; };
+bool layernorm_batchable(const void* a, const void* b, const void* c, const void* d, int C, int dtype);
+hipError_t launch_layernorm_fwd_batch(const LnFwdBatch& b, int rows, int C, int dtype, hipStream_t stream);
+hipError_t launch_layernorm_bwd_batch(const LnBwdBatch& b, int rows, int C, int dtype, hipStream_t stream);
+
 hipError_t launch_layernorm_bwd(const void* x, const void* dy, const void* add, const float* gamma, void* dx, float* Ggamma,
                                 float* Gbeta, float* workspace, int rows, int C, int dtype, hipStream_t stream);
 // Exact GELU and its derivative, elementwise.

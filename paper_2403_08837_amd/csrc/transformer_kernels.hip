@@ -113,7 +113,7 @@ __global__ __launch_bounds__(256) void layernorm_fwd_kernel(const T* __restrict_
 // The same with 16-byte accesses, for rows that are whole 16-byte chunks: lane l owns chunks
 // l, l + 64, ... of its row.
 template <typename T>
-__global__ __launch_bounds__(256) void layernorm_fwd_vec_kernel(const T* __restrict__ x, const float* __restrict__ gamma,
+__device__ __forceinline__ void layernorm_fwd_vec_body(const T* __restrict__ x, const float* __restrict__ gamma,
                                                                 const float* __restrict__ beta, T* __restrict__ y, int rows, int C) {
   constexpr int N = RowChunk<T>::N, Q = LN_MAX_PER_LANE / N;
   const int lane = threadIdx.x & 63, row = blockIdx.x * 4 + (threadIdx.x >> 6);
@@ -152,7 +152,7 @@ __global__ __launch_bounds__(256) void layernorm_fwd_vec_kernel(const T* __restr
 }
 
 template <typename T>
-__global__ __launch_bounds__(256) void layernorm_bwd_rows_vec_kernel(const T* __restrict__ x, const T* __restrict__ dy,
+__device__ __forceinline__ void layernorm_bwd_rows_vec_body(const T* __restrict__ x, const T* __restrict__ dy,
                                                                      const T* __restrict__ add, const float* __restrict__ gamma,
                                                                      T* __restrict__ dx, float* __restrict__ stats, int rows, int C) {
   constexpr int N = RowChunk<T>::N, Q = LN_MAX_PER_LANE / N;
@@ -270,7 +270,7 @@ __global__ __launch_bounds__(256) void layernorm_bwd_rows_kernel(const T* __rest
 }
 
 template <typename T>
-__global__ __launch_bounds__(256) void layernorm_bwd_cols_kernel(const T* __restrict__ x, const T* __restrict__ dy,
+__device__ __forceinline__ void layernorm_bwd_cols_body(const T* __restrict__ x, const T* __restrict__ dy,
                                                                  const float* __restrict__ stats, float* __restrict__ part,
                                                                  int rows, int C) {
   __shared__ float st[2 * LN_ROWS_PER_WG];
@@ -296,7 +296,7 @@ __global__ __launch_bounds__(256) void layernorm_bwd_cols_kernel(const T* __rest
 
 // Column sums of the n_part partial rows (2C wide): 16 columns x 16 row groups per workgroup (a short chain of
 // loads per lane: the kernel is a handful of memory round trips long), the groups' sums added in group order.
-__global__ __launch_bounds__(256) void layernorm_fold_kernel(const float* __restrict__ part, int n_part, float* __restrict__ Ggamma,
+__device__ __forceinline__ void layernorm_fold_body(const float* __restrict__ part, int n_part, float* __restrict__ Ggamma,
                                                              float* __restrict__ Gbeta, int C) {
   __shared__ float red[16][17];
   const int col = threadIdx.x & 15, grp = threadIdx.x >> 4;
@@ -321,6 +321,46 @@ __global__ __launch_bounds__(256) void layernorm_fold_kernel(const float* __rest
     if (c < C) Ggamma[c] += s;
     else Gbeta[c - C] += s;
   }
+}
+
+// The kernels proper: one problem per launch, or (batch kernels) the same pass of up to LN_BATCH_MAX problems of one
+// shape, problem = blockIdx.y.  The passes of a tick that sit at the same level are the same layer of different
+// stages and micro-batches; each alone is a launch of a few microseconds, most of it the launch's own latency.
+template <typename T>
+__global__ __launch_bounds__(256) void layernorm_fwd_vec_kernel(const T* x, const float* gamma, const float* beta, T* y, int rows, int C) {
+  layernorm_fwd_vec_body<T>(x, gamma, beta, y, rows, C);
+}
+template <typename T>
+__global__ __launch_bounds__(256) void layernorm_bwd_rows_vec_kernel(const T* x, const T* dy, const T* add, const float* gamma, T* dx,
+                                                                     float* stats, int rows, int C) {
+  layernorm_bwd_rows_vec_body<T>(x, dy, add, gamma, dx, stats, rows, C);
+}
+template <typename T>
+__global__ __launch_bounds__(256) void layernorm_bwd_cols_kernel(const T* x, const T* dy, const float* stats, float* part, int rows, int C) {
+  layernorm_bwd_cols_body<T>(x, dy, stats, part, rows, C);
+}
+__global__ __launch_bounds__(256) void layernorm_fold_kernel(const float* part, int n_part, float* Ggamma, float* Gbeta, int C) {
+  layernorm_fold_body(part, n_part, Ggamma, Gbeta, C);
+}
+template <typename T>
+__global__ __launch_bounds__(256) void layernorm_fwd_vec_batch_kernel(const LnFwdBatch b, int rows, int C) {
+  const LnFwdProb& p = b.p[blockIdx.y];
+  layernorm_fwd_vec_body<T>(static_cast<const T*>(p.x), p.gamma, p.beta, static_cast<T*>(p.y), rows, C);
+}
+template <typename T>
+__global__ __launch_bounds__(256) void layernorm_bwd_rows_vec_batch_kernel(const LnBwdBatch b, int rows, int C) {
+  const LnBwdProb& p = b.p[blockIdx.y];
+  layernorm_bwd_rows_vec_body<T>(static_cast<const T*>(p.x), static_cast<const T*>(p.dy), static_cast<const T*>(p.add), p.gamma,
+                                 static_cast<T*>(p.dx), p.workspace, rows, C);
+}
+template <typename T>
+__global__ __launch_bounds__(256) void layernorm_bwd_cols_batch_kernel(const LnBwdBatch b, int rows, int C, int stats_floats) {
+  const LnBwdProb& p = b.p[blockIdx.y];
+  layernorm_bwd_cols_body<T>(static_cast<const T*>(p.x), static_cast<const T*>(p.dy), p.workspace, p.workspace + stats_floats, rows, C);
+}
+__global__ __launch_bounds__(256) void layernorm_fold_batch_kernel(const LnBwdBatch b, int n_part, int C, int stats_floats) {
+  const LnBwdProb& p = b.p[blockIdx.y];
+  layernorm_fold_body(p.workspace + stats_floats, n_part, p.Ggamma, p.Gbeta, C);
 }
 
 // rows of C elements at p are whole, 16-byte aligned chunks
@@ -365,6 +405,36 @@ hipError_t launch_layernorm_bwd(const void* x, const void* dy, const void* add, 
                                           static_cast<const T*>(dy), stats, part, rows, C));
   if ((e = hipGetLastError()) != hipSuccess) return e;
   hipLaunchKernelGGL(layernorm_fold_kernel, dim3((2 * C + 15) / 16), dim3(256), 0, stream, part, wgs, Ggamma, Gbeta, C);
+  return hipGetLastError();
+}
+
+bool layernorm_batchable(const void* a, const void* b, const void* c, const void* d, int C, int dtype) {
+  const int eb = dtype == DT_BF16 ? 2 : 4;
+  return C > 0 && C <= 64 * LN_MAX_PER_LANE && ln_vec_ok(a, C, eb) && ln_vec_ok(b, C, eb) && ln_vec_ok(c, C, eb) && ln_vec_ok(d, C, eb);
+}
+hipError_t launch_layernorm_fwd_batch(const LnFwdBatch& b, int rows, int C, int dtype, hipStream_t stream) {
+  if (b.n <= 0) return hipSuccess;
+  if (b.n > LN_BATCH_MAX || rows <= 0) return hipErrorInvalidValue;
+  for (int i = 0; i < b.n; ++i)
+    if (!b.p[i].x || !b.p[i].y || !layernorm_batchable(b.p[i].x, b.p[i].y, nullptr, nullptr, C, dtype)) return hipErrorInvalidValue;
+  CDP_TDISPATCH(dtype, hipLaunchKernelGGL((layernorm_fwd_vec_batch_kernel<T>), dim3((rows + 3) / 4, b.n), dim3(256), 0, stream, b, rows, C));
+  return hipGetLastError();
+}
+hipError_t launch_layernorm_bwd_batch(const LnBwdBatch& b, int rows, int C, int dtype, hipStream_t stream) {
+  if (b.n <= 0) return hipSuccess;
+  if (b.n > LN_BATCH_MAX || rows <= 0) return hipErrorInvalidValue;
+  for (int i = 0; i < b.n; ++i)
+    if (!b.p[i].workspace || !b.p[i].x || !b.p[i].dy || !b.p[i].dx || !b.p[i].Ggamma || !b.p[i].Gbeta ||
+        !layernorm_batchable(b.p[i].x, b.p[i].dy, b.p[i].add, b.p[i].dx, C, dtype))
+      return hipErrorInvalidValue;
+  const int wgs = (rows + LN_ROWS_PER_WG - 1) / LN_ROWS_PER_WG;
+  const int stats_floats = (int)(ln_stats_bytes(rows) / 4);
+  CDP_TDISPATCH(dtype, hipLaunchKernelGGL((layernorm_bwd_rows_vec_batch_kernel<T>), dim3((rows + 3) / 4, b.n), dim3(256), 0, stream, b, rows, C));
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  CDP_TDISPATCH(dtype, hipLaunchKernelGGL((layernorm_bwd_cols_batch_kernel<T>), dim3(wgs, b.n), dim3(256), 0, stream, b, rows, C, stats_floats));
+  if ((e = hipGetLastError()) != hipSuccess) return e;
+  hipLaunchKernelGGL(layernorm_fold_batch_kernel, dim3((2 * C + 15) / 16, b.n), dim3(256), 0, stream, b, wgs, C, stats_floats);
   return hipGetLastError();
 }
 
