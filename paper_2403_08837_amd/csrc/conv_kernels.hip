@@ -371,8 +371,11 @@ constexpr int WG_MAX_SLABS = 16;  // slabs per chunk of a workgroup's range (siz
 template <typename T> struct WgSlab { static constexpr int MB = sizeof(T) == 2 ? 64 : 32; };  // positions per slab
 static inline int wg_slab(int dtype) { return dtype == DT_BF16 ? 64 : 32; }
 
+// One tile (TO rows of the weight matrix x 128 columns, one reduction range) of problem P; Ds [MB][TO + PAD],
+// Xs [MB][128 + PAD] and the two position tables [WG_MAX_SLABS * MB] are the workgroup's LDS.
 template <typename T, int TO>
-__global__ __launch_bounds__(256) void conv_wgrad_kernel(const GemmBatch batch) {
+__device__ __forceinline__ void conv_wgrad_body(const GemmProb& P, int tile, T* __restrict__ Ds, T* __restrict__ Xs,
+                                                int* __restrict__ pos_base, int* __restrict__ pos_hw) {
   using E = Elem<T>;
   constexpr int TC = 128, VEC = E::VEC, MB = WgSlab<T>::MB;
   constexpr int PAD = (sizeof(T) == 2) ? 16 : 4;  // bf16: pitch of 32 bytes modulo 128 for the transposing LDS read
@@ -381,13 +384,6 @@ __global__ __launch_bounds__(256) void conv_wgrad_kernel(const GemmBatch batch) 
   constexpr int WAVES_C = 4 / WAVES_O;         // 4 or 2
   constexpr int WTC = TC / WAVES_C;            // 32 or 64 columns per wave
   constexpr int NI = WTC / 32;                 // 1 or 2
-  __shared__ __attribute__((aligned(16))) T Ds[MB * PD];
-  __shared__ __attribute__((aligned(16))) T Xs[MB * PX];
-  __shared__ int pos_base[WG_MAX_SLABS * MB];
-  __shared__ int pos_hw[WG_MAX_SLABS * MB];
-
-  const int tile = (int)blockIdx.x;
-  const GemmProb& P = batch.p[find_problem(batch, tile)];
   int local = tile - P.tile_begin;
   const int split = local % P.splits;
   local /= P.splits;
@@ -553,6 +549,33 @@ __global__ __launch_bounds__(256) void conv_wgrad_kernel(const GemmBatch batch) 
       }
     }
   if (do_beta && o0 + tid < Cout) static_cast<float*>(P.aux3)[(int64_t)split * Cout + o0 + tid] = bsum;
+}
+
+template <typename T, int TO>
+__global__ __launch_bounds__(256) void conv_wgrad_kernel(const GemmBatch batch) {
+  constexpr int MB = WgSlab<T>::MB, PAD = (sizeof(T) == 2) ? 16 : 4;
+  __shared__ __attribute__((aligned(16))) T Ds[MB * (TO + PAD)];
+  __shared__ __attribute__((aligned(16))) T Xs[MB * (128 + PAD)];
+  __shared__ int pos_base[WG_MAX_SLABS * MB];
+  __shared__ int pos_hw[WG_MAX_SLABS * MB];
+  const int tile = (int)blockIdx.x;
+  conv_wgrad_body<T, TO>(batch.p[find_problem(batch, tile)], tile, Ds, Xs, pos_base, pos_hw);
+}
+// Tiles of both heights in one launch (the height is the problem's: 128 rows for matrices of 128 rows and more, 64
+// below): the weight gradients of a tick are one launch instead of one per height, each of which alone is short
+// of workgroups on the small ResNet configurations.
+__host__ __device__ inline int conv_wgrad_rows(const GemmProb& p) { return p.M >= 128 ? 128 : 64; }
+template <typename T>
+__global__ __launch_bounds__(256) void conv_wgrad_mixed_kernel(const GemmBatch batch) {
+  constexpr int MB = WgSlab<T>::MB, PAD = (sizeof(T) == 2) ? 16 : 4;
+  __shared__ __attribute__((aligned(16))) T Ds[MB * (128 + PAD)];
+  __shared__ __attribute__((aligned(16))) T Xs[MB * (128 + PAD)];
+  __shared__ int pos_base[WG_MAX_SLABS * MB];
+  __shared__ int pos_hw[WG_MAX_SLABS * MB];
+  const int tile = (int)blockIdx.x;
+  const GemmProb& P = batch.p[find_problem(batch, tile)];
+  if (conv_wgrad_rows(P) == 128) conv_wgrad_body<T, 128>(P, tile, Ds, Xs, pos_base, pos_hw);
+  else conv_wgrad_body<T, 64>(P, tile, Ds, Xs, pos_base, pos_hw);
 }
 
 // Fold of the partial sums.  A workgroup is 8 groups of 32 lanes; a lane owns 4 of the 128
@@ -833,6 +856,25 @@ hipError_t launch_conv_gemm(GemmBatch& b, int dtype, int bm, int bn, hipStream_t
                                     : launch_conv_gemm_typed<uint16_t, 32>(b, bm, bn, grid, stream);
   return deep ? launch_conv_gemm_typed<float, 32>(b, bm, bn, grid, stream)
               : launch_conv_gemm_typed<float, 16>(b, bm, bn, grid, stream);
+}
+
+hipError_t launch_conv_wgrad_mixed(GemmBatch& b, int dtype, hipStream_t stream) {
+  if (b.n <= 0) return hipSuccess;
+  if (b.n > GEMM_MAX_PROBS) return hipErrorInvalidValue;
+  int total = 0;
+  for (int i = 0; i < b.n; ++i) {
+    GemmProb& p = b.p[i];
+    if (p.M <= 0 || p.N <= 0 || p.K <= 0 || p.epi != EPI_WGRAD || !conv_fast_eligible(p, dtype)) return hipErrorInvalidValue;
+    if (p.splits < 1 || p.splits > (p.K + wg_slab(dtype) - 1) / wg_slab(dtype)) return hipErrorInvalidValue;  // the caller sized the partial buffer
+    const int to = conv_wgrad_rows(p);
+    p.tiles_n = (p.N + 127) / 128;
+    p.tile_begin = total;
+    total += ((p.M + to - 1) / to) * p.tiles_n * p.splits;
+  }
+  b.total_tiles = total;
+  if (dtype == DT_BF16) hipLaunchKernelGGL((conv_wgrad_mixed_kernel<uint16_t>), dim3(total), dim3(256), 0, stream, b);
+  else hipLaunchKernelGGL((conv_wgrad_mixed_kernel<float>), dim3(total), dim3(256), 0, stream, b);
+  return hipGetLastError();
 }
 
 hipError_t launch_conv_wgrad(GemmBatch& b, int dtype, bool wide, hipStream_t stream) {

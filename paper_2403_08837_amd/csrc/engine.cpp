@@ -716,10 +716,17 @@ int launch_level(cdp_ctx* c, std::vector<Item>& items) {
       for (Item* it : big) it->big_tile = true;
   }
   // grouped contractions, one launch per tile shape (and per GEMM_MAX_PROBS problems)
+  // convolution weight gradients of both tile heights share one launch (each height alone is short of workgroups
+  // on the small configurations): they are all listed under the taller class
+  auto item_class = [&](const Item& it) {
+    if (it.big_tile) return (int)LC_CONV_256;
+    const int lc = launch_class(it.g, c->plan.dtype);
+    return lc == LC_CWGRAD_64 ? (int)LC_CWGRAD_128 : lc;
+  };
   for (int key = 0; key <= LC_CONV_256; ++key) {
     std::vector<const Item*> sel;
     for (const Item& it : items)
-      if (it.kind == IT_GEMM && (it.big_tile ? LC_CONV_256 : launch_class(it.g, c->plan.dtype)) == key) sel.push_back(&it);
+      if (it.kind == IT_GEMM && item_class(it) == key) sel.push_back(&it);
     // longest reductions first so the tail of the launch is made of short tiles
     std::stable_sort(sel.begin(), sel.end(),
                      [](const Item* a, const Item* b) { return a->g.K / a->g.splits > b->g.K / b->g.splits; });
@@ -780,7 +787,7 @@ int launch_level(cdp_ctx* c, std::vector<Item>& items) {
         HIP_TRY(c, launch_conv_gemm(batch, c->plan.dtype, bm, bn, c->stream));
       }
       else if (key == LC_CONV_256) HIP_TRY(c, launch_conv_gemm256(batch, c->plan.dtype, c->stream));
-      else if (key == LC_CWGRAD_64 || key == LC_CWGRAD_128) HIP_TRY(c, launch_conv_wgrad(batch, c->plan.dtype, key == LC_CWGRAD_128, c->stream));
+      else if (key == LC_CWGRAD_128) HIP_TRY(c, launch_conv_wgrad_mixed(batch, c->plan.dtype, c->stream));
       else HIP_TRY(c, launch_gemm_batch(batch, c->plan.dtype, (key - LC_GEN_FIRST) / 2, c->stream));
       if (timed) {
         HIP_TRY(c, hipEventRecord(pr.b, c->stream));
@@ -1130,7 +1137,7 @@ int run_tick(cdp_ctx* c, const float* x_dev, const int32_t* y_dev) {
   };
   // Neither do the convolution weight gradients: nothing in the tick reads their partial sums but the folds, and
   // their operands (saved inputs, output gradients) stay untouched until the tick's blocks are released.  They
-  // leave their levels too and run as one launch per tile height in front of the folds, with the reduction
+  // leave their levels too and run as one launch (tiles of both heights) in front of the folds, with the reduction
   // ranges chosen for the launch as a whole: several layers together fill the chip with fewer, longer ranges
   // than each layer would need on its own, and every range less is one partial tile less to write and fold.
   auto defer_wgrads = [c](Program& p) {

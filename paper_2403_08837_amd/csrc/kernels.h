@@ -179,6 +179,8 @@ hipError_t launch_conv_gemm256(GemmBatch& batch, int dtype, hipStream_t stream, 
 int conv_wgrad_splits(const GemmProb& p, int dtype, int wanted);
 int conv_wgrad_slab(int dtype);  // output positions per reduction slab; a problem takes 1 .. ceil(K / slab) ranges
 hipError_t launch_conv_wgrad(GemmBatch& batch, int dtype, bool wide, hipStream_t stream);
+// the same with the tile height chosen per problem (128 rows for matrices of 128 rows and more, 64 below)
+hipError_t launch_conv_wgrad_mixed(GemmBatch& batch, int dtype, hipStream_t stream);
 struct WReduceProb {
   const float* part; const float* part_beta;  // partial sums [splits][Cout][Ncol], [splits][Cout]
   float* G; float* Ggamma; float* Gbeta;      // accumulators (Ggamma / Gbeta may be NULL)
