@@ -718,9 +718,26 @@ int launch_level(cdp_ctx* c, std::vector<Item>& items) {
   // grouped contractions, one launch per tile shape (and per GEMM_MAX_PROBS problems)
   // convolution weight gradients of both tile heights share one launch (each height alone is short of workgroups
   // on the small configurations): they are all listed under the taller class
+  // Forward / data-gradient problems with at most 64 output columns have a launch of their own (128 x 64 tiles).
+  // Where the level's wide problems fill a launch of 128 x 128 tiles by themselves, the narrow ones join it
+  // instead, half of each of their tiles empty: they are bound by their operand traffic, not by the matrix
+  // cores, and one launch fewer per level is worth more than the idle half (cfg4 22.8 -> 22.0 ms per step; on
+  // the small launches of cfg3, which run on 64 x 64 tiles with shared reductions, the same costs 19 %).
+  bool narrow_joins_wide = false;
+  {
+    std::vector<GemmProb> wide;
+    for (const Item& it : items)
+      if (it.kind == IT_GEMM && !it.big_tile && launch_class(it.g, c->plan.dtype) == LC_CONV_WIDE) wide.push_back(it.g);
+    if (!wide.empty() && wide.size() < (size_t)GEMM_MAX_PROBS) {
+      int bm = 0, bn = 0;
+      conv_gemm_tile(wide.data(), (int)wide.size(), &bm, &bn);
+      narrow_joins_wide = bm == 128 && bn == 128;
+    }
+  }
   auto item_class = [&](const Item& it) {
     if (it.big_tile) return (int)LC_CONV_256;
     const int lc = launch_class(it.g, c->plan.dtype);
+    if (lc == LC_CONV_NARROW && narrow_joins_wide) return (int)LC_CONV_WIDE;
     return lc == LC_CWGRAD_64 ? (int)LC_CWGRAD_128 : lc;
   };
   for (int key = 0; key <= LC_CONV_256; ++key) {
