@@ -711,9 +711,102 @@ __global__ __launch_bounds__(256) void wgrad_reduce_kernel(const WReduceBatch ba
   }
 }
 
+// The same fold for layers with at most 8 ranges and rows of whole 16-byte groups, by rows: a group of 32 lanes
+// walks all 128-column chunks of one weight row (eight rows per workgroup), so a row's d gamma is complete inside
+// its group - no shares in a workspace, no counters, no barriers - and a workgroup moves 8 whole rows instead of
+// 4 KB of the accumulator.  Every sum is associated as wgrad_reduce_kernel associates it (ranges: groups of four
+// into four running sums, the rest into the first; a chunk's d gamma share: the lane's four products in order,
+// then the 32-lane exchange tree; shares in chunk order), so the two kernels give the same bits.
+template <typename T>
+__global__ __launch_bounds__(256) void wgrad_fold_rows_kernel(const WReduceBatch batch) {
+  using E = Elem<T>;
+  int pi = 0;
+  for (int q = 1; q < batch.n; ++q)
+    if ((int)blockIdx.x >= batch.p[q].tile_begin) pi = q;
+  const WReduceProb& P = batch.p[pi];
+  const int cl = threadIdx.x & 31, grp = threadIdx.x >> 5;
+  const int o = ((int)blockIdx.x - P.tile_begin) * 8 + grp;
+  if (o >= P.Cout) return;  // whole 32-lane groups leave: the exchanges below stay inside a group
+  const int splits = P.splits, chunks = (P.Ncol + 127) >> 7;
+  const int64_t row = (int64_t)o * P.Ncol, stride = (int64_t)P.Cout * P.Ncol;
+  const float gam = P.gamma ? P.gamma[o] : 1.f;
+  const T* __restrict__ wplain = static_cast<const T*>(P.wplain);
+  float dgsum = 0.f;
+  for (int chunk = 0; chunk < chunks; ++chunk) {
+    const int c = chunk * 128 + cl * 4;
+    float dg = 0.f;
+    if (c < P.Ncol) {
+      const float* src = P.part + row + c;
+      float4 v[8];
+#pragma unroll
+      for (int q = 0; q < 8; ++q) v[q] = q < splits ? *reinterpret_cast<const float4*>(src + q * stride) : make_float4(0.f, 0.f, 0.f, 0.f);
+      const float4 gold = *reinterpret_cast<const float4*>(P.G + row + c);
+      float wpl[4] = {0.f, 0.f, 0.f, 0.f};
+      if (wplain) {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) wpl[e] = E::to_f32(wplain[row + c + e]);
+      }
+      float4 sum = make_float4(0.f, 0.f, 0.f, 0.f), s1 = sum, s2 = sum, s3 = sum;
+      const int full = splits & ~3;
+#pragma unroll
+      for (int q = 0; q < 8; q += 4)
+        if (q + 3 < splits) {
+          sum.x += v[q].x; sum.y += v[q].y; sum.z += v[q].z; sum.w += v[q].w;
+          s1.x += v[q + 1].x; s1.y += v[q + 1].y; s1.z += v[q + 1].z; s1.w += v[q + 1].w;
+          s2.x += v[q + 2].x; s2.y += v[q + 2].y; s2.z += v[q + 2].z; s2.w += v[q + 2].w;
+          s3.x += v[q + 3].x; s3.y += v[q + 3].y; s3.z += v[q + 3].z; s3.w += v[q + 3].w;
+        }
+#pragma unroll
+      for (int q = 0; q < 8; ++q)
+        if (q >= full && q < splits) { sum.x += v[q].x; sum.y += v[q].y; sum.z += v[q].z; sum.w += v[q].w; }
+      sum.x += (s1.x + s2.x) + s3.x; sum.y += (s1.y + s2.y) + s3.y;
+      sum.z += (s1.z + s2.z) + s3.z; sum.w += (s1.w + s2.w) + s3.w;
+      const float tot[4] = {0.f + sum.x, 0.f + sum.y, 0.f + sum.z, 0.f + sum.w};
+      *reinterpret_cast<float4*>(P.G + row + c) =
+          make_float4(gold.x + gam * tot[0], gold.y + gam * tot[1], gold.z + gam * tot[2], gold.w + gam * tot[3]);
+#pragma unroll
+      for (int e = 0; e < 4; ++e) dg += tot[e] * wpl[e];
+    }
+    if (chunk == 0 && P.Gbeta) {
+      float sb = 0.f;
+      for (int q = cl; q < splits; q += 32) sb += P.part_beta[(int64_t)q * P.Cout + o];
+#pragma unroll
+      for (int off = 16; off >= 1; off >>= 1) sb += __shfl_xor(sb, off, 64);
+      if (cl == 0) P.Gbeta[o] += sb;
+    }
+    if (P.Ggamma) {
+#pragma unroll
+      for (int off = 16; off >= 1; off >>= 1) dg += __shfl_xor(dg, off, 64);
+      dgsum += dg;
+    }
+  }
+  if (P.Ggamma && cl == 0) P.Ggamma[o] += dgsum;
+}
+
 hipError_t launch_wgrad_reduce(WReduceBatch& b, int dtype, hipStream_t stream) {
   if (b.n <= 0) return hipSuccess;
   if (b.n > WREDUCE_MAX_PROBS) return hipErrorInvalidValue;
+  {
+    // by rows where every problem allows it and the launch still has a few workgroups per compute unit
+    bool rows_ok = true;
+    int64_t wgs = 0;
+    for (int i = 0; i < b.n && rows_ok; ++i) {
+      const WReduceProb& p = b.p[i];
+      rows_ok = p.splits >= 1 && p.splits <= 8 && p.Cout > 0 && p.Ncol > 0 && p.Ncol % 4 == 0 &&
+                reinterpret_cast<uintptr_t>(p.part) % 16 == 0 && reinterpret_cast<uintptr_t>(p.G) % 16 == 0 && (!p.Gbeta || p.part_beta);
+      wgs += (p.Cout + 7) / 8;
+    }
+    if (rows_ok && wgs >= 512 && wgs < (1ll << 31)) {
+      int total = 0;
+      for (int i = 0; i < b.n; ++i) {
+        b.p[i].tile_begin = total;
+        total += (b.p[i].Cout + 7) / 8;
+      }
+      if (dtype == DT_BF16) hipLaunchKernelGGL((wgrad_fold_rows_kernel<uint16_t>), dim3((unsigned)total), dim3(256), 0, stream, b);
+      else hipLaunchKernelGGL((wgrad_fold_rows_kernel<float>), dim3((unsigned)total), dim3(256), 0, stream, b);
+      return hipGetLastError();
+    }
+  }
   int64_t total = 0;
   for (int i = 0; i < b.n; ++i) {
     WReduceProb& p = b.p[i];
