@@ -39,7 +39,7 @@ WORKLOAD_TEXT = {
 KERNELS = {"cfg1": "linear_tick_kernel<float>", "cfg2": "linear_tick_kernel_bf16<64>", "cfg5": "linear_tick_kernel_bf16<128>",
            "cfg3": "conv_gemm_kernel + conv_wgrad_mixed_kernel + wgrad_reduce_kernel (+ linear_tick_kernel for the classifier)",
            "cfg4": "conv_gemm_kernel + conv_wgrad_mixed_kernel + wgrad_reduce_kernel (+ linear_tick_kernel for the classifier)",
-           "vit_b16": "conv_gemm_kernel + conv_wgrad_mixed_kernel + wgrad_reduce_kernel on the token-wise linear maps (attention and LayerNorm kernels are not in this figure)"}
+           "vit_b16": "conv_gemm_kernel + conv_wgrad_mixed_kernel + wgrad_fold_rows_kernel on the token-wise linear maps (attention and LayerNorm kernels are not in this figure)"}
 
 
 def measured_traffic(workload):
