@@ -56,6 +56,7 @@ __device__ __forceinline__ float wave_sum(float v) {
   return v;
 }
 
+constexpr int CE_ROW_REGS = 16;  // rows of up to 1024 classes are held in registers
 template <typename T>
 __global__ __launch_bounds__(256) void ce_head_kernel(const float* __restrict__ logits, const int32_t* __restrict__ labels,
                                                       T* __restrict__ dlogits, float* __restrict__ loss_out, int B, int C,
@@ -65,13 +66,44 @@ __global__ __launch_bounds__(256) void ce_head_kernel(const float* __restrict__ 
   if (row >= B) return;
   const float invB = 1.0f / (float)B;
   const float* z = logits + (int64_t)row * C;
+  const int y = labels[row];
+  if (C <= 64 * CE_ROW_REGS) {
+    // The row lives in registers: all of a lane's reads are in flight together and every exponential is taken
+    // once.  Same operations in the same order as the loops below, so the results are the same bits.
+    float zc[CE_ROW_REGS];
+#pragma unroll
+    for (int k = 0; k < CE_ROW_REGS; ++k) {
+      const int c = lane + 64 * k;
+      zc[k] = c < C ? z[c] : -INFINITY;
+    }
+    const float zy = lane == 0 ? z[y] : 0.f;
+    float m = -INFINITY;
+#pragma unroll
+    for (int k = 0; k < CE_ROW_REGS; ++k) m = fmaxf(m, zc[k]);
+    m = wave_max(m);
+    float s = 0.f;
+#pragma unroll
+    for (int k = 0; k < CE_ROW_REGS; ++k) {
+      zc[k] = expf(zc[k] - m);
+      if (lane + 64 * k < C) s += zc[k];
+    }
+    s = wave_sum(s);
+    const float inv = 1.0f / s;
+#pragma unroll
+    for (int k = 0; k < CE_ROW_REGS; ++k) {
+      const int c = lane + 64 * k;
+      if (c < C) st_f32<T>(dlogits, (int64_t)row * C + c, (zc[k] * inv - (c == y ? 1.f : 0.f)) * invB);
+    }
+    if (lane == 0)
+      atomicAdd(reinterpret_cast<int*>(loss_out) + row / rows_per_slot, __float2int_rn(((m + logf(s)) - zy) / (float)rows_per_slot * LOSS_SCALE));
+    return;
+  }
   float m = -INFINITY;
   for (int c = lane; c < C; c += 64) m = fmaxf(m, z[c]);
   m = wave_max(m);
   float s = 0.f;
   for (int c = lane; c < C; c += 64) s += expf(z[c] - m);
   s = wave_sum(s);
-  const int y = labels[row];
   const float inv = 1.0f / s;
   for (int c = lane; c < C; c += 64) {
     float p = expf(z[c] - m) * inv;
